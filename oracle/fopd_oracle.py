@@ -1,0 +1,319 @@
+"""Float64 CPU oracle for the f-OPD loss pass.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, plain statement of what the loss pass computes, written from the
+paper's definitions (Sec. 4.1 Eq. "kl-diagnostics", Eq. "freshness"; Sec. 4.2 Eq.
+"sample-aggregated-loss", the freshness-weighting expectation, the anchored objective;
+Appendix Algorithm 1).  It shares no code with the HIP library and must never be imported by
+the product package: only the tests, the smoke check and the benchmark's CPU-baseline leg
+may call it.
+
+Everything is numpy float64 (integers are numpy int64/int32).  Rows are handled one at a
+time by ordinary Python loops; there is no blocking, fusion or re-ordering beyond what the
+definitions state.
+
+Readings of the paper that this oracle fixes (the paper leaves them open):
+
+* The token loss ``l`` (Eq. "sample-aggregated-loss") is the sampled-token reverse-KL term
+  ``log pi_theta(y) - log pi_teacher(y)``; it is optimised as a score-function (policy
+  gradient) term whose advantage ``A = log pi_teacher(y) - log pi_theta(y)`` is held
+  constant.
+* ``D_i^roll`` (Eq. "kl-diagnostics", first line) is estimated on the sampled token, which
+  was drawn from the rollout policy, by ``k(delta) = rho*delta - rho + 1`` with
+  ``delta = log pi^t(y) - log pi^{r(i)}(y)`` and ``rho = exp(delta)``; its expectation under
+  the rollout policy is KL(pi^t || pi^{r(i)}) and it is never negative.
+* ``D_i^sup`` (Eq. "kl-diagnostics", second line) uses the same ``k`` on the teacher's
+  current-context minus stale-context log-probability, or is 0 when no stale-context array
+  is given (Remark "When the supervision gap is negligible").
+* One 0/1 mask stands for both aligned sets U_i^roll and U_i^sup.
+* The expectation over the buffer divides by the number of samples B, whether or not a
+  sample is gated or invalid (Algorithm 1, anchored minibatch loss).
+* Freshness weights are constants in the gradient (Algorithm 1 scores the buffer before the
+  minibatch loop).
+
+Hyper-parameter values are not given by the paper: parity on them is unpinned by the paper
+and rests on both sides receiving the same numbers.
+"""
+
+import math
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------------------
+# integer bookkeeping (Sec. 4.1: token length H_i, aligned sets U_i; Algorithm 1 ratios)
+# ----------------------------------------------------------------------------------------
+
+def segment_offsets(seq_lens):
+    """cu[0] = 0, cu[i+1] = cu[i] + H_i  (H_i: token length of sample i, Sec. 4.1)."""
+    seq_lens = np.asarray(seq_lens)
+    cu = np.zeros(seq_lens.shape[0] + 1, dtype=np.int64)
+    for i in range(seq_lens.shape[0]):
+        if int(seq_lens[i]) < 0:
+            raise ValueError("negative sequence length")
+        cu[i + 1] = cu[i] + int(seq_lens[i])
+    return cu
+
+
+def trainable_counts(mask, cu):
+    """n_i = |U_i| = number of mask==1 rows inside segment i (Sec. 4.1, aligned sets)."""
+    mask = np.asarray(mask)
+    B = cu.shape[0] - 1
+    n = np.zeros(B, dtype=np.int32)
+    for i in range(B):
+        cnt = 0
+        for t in range(int(cu[i]), int(cu[i + 1])):
+            if mask[t] != 0:
+                cnt += 1
+        n[i] = cnt
+    return n
+
+
+def gather_index(token_ids, ld):
+    """Flat element offset of the sampled token y_t inside a [T, ld] row-major matrix."""
+    token_ids = np.asarray(token_ids)
+    out = np.zeros(token_ids.shape[0], dtype=np.int64)
+    for t in range(token_ids.shape[0]):
+        out[t] = int(t) * int(ld) + int(token_ids[t])
+    return out
+
+
+# ----------------------------------------------------------------------------------------
+# student log-probability of the sampled token (pi_theta^t(. | x_{i,h}) in Eq.
+# "kl-diagnostics" and Eq. "sample-aggregated-loss")
+# ----------------------------------------------------------------------------------------
+
+def row_logsumexp(z):
+    """log sum_v exp(z_v) of one row, shifted by the row maximum."""
+    z = np.asarray(z, dtype=np.float64)
+    mx = np.max(z)
+    return float(mx + np.log(np.sum(np.exp(z - mx))))
+
+
+def token_logprobs(logits, token_ids, mask=None):
+    """Per row t with mask 1: lse_t and lp_t = z_{t,y_t} - lse_t.  Masked rows give 0, 0.
+
+    logits: [T, V] array whose columns are exactly the vocabulary (a caller holding a padded
+    [T, ld] matrix slices the first V columns off before calling).
+    """
+    logits = np.asarray(logits)
+    T, V = logits.shape
+    lse = np.zeros(T, dtype=np.float64)
+    lp = np.zeros(T, dtype=np.float64)
+    for t in range(T):
+        if mask is not None and mask[t] == 0:
+            continue
+        y = int(token_ids[t])
+        if y < 0 or y >= V:
+            raise ValueError("token id out of range at row %d" % t)
+        z = logits[t].astype(np.float64)
+        lse[t] = row_logsumexp(z)
+        lp[t] = z[y] - lse[t]
+    return lse, lp
+
+
+# ----------------------------------------------------------------------------------------
+# per-token drift and advantage terms
+# ----------------------------------------------------------------------------------------
+
+def kl_estimator(d):
+    """k(d) = e^d * d - e^d + 1, the sampled-token estimator of KL(current || stale) when the
+    token was drawn from the stale distribution and d = log current - log stale."""
+    d = np.asarray(d, dtype=np.float64)
+    r = np.exp(d)
+    return r * d - r + 1.0
+
+
+def token_terms(logp, behav_logp, teacher_logp, teacher_logp_stale=None):
+    """delta_t, rho_t, A_t, k^roll_t, k^sup_t for every row (mask is applied later)."""
+    lp = np.asarray(logp, dtype=np.float64)
+    lb = np.asarray(behav_logp, dtype=np.float64)
+    lq = np.asarray(teacher_logp, dtype=np.float64)
+    delta = lp - lb                      # log-ratio current student / rollout policy
+    rho = np.exp(delta)                  # importance ratio, not clipped
+    adv = lq - lp                        # OPD advantage against the teacher
+    k_roll = rho * delta - rho + 1.0
+    if teacher_logp_stale is None:
+        k_sup = np.zeros_like(lp)
+    else:
+        eps = lq - np.asarray(teacher_logp_stale, dtype=np.float64)
+        k_sup = kl_estimator(eps)
+    return delta, rho, adv, k_roll, k_sup
+
+
+# ----------------------------------------------------------------------------------------
+# per-sample statistics (Eq. "kl-diagnostics", Eq. "sample-aggregated-loss", Algorithm 1
+# alignment ratios)
+# ----------------------------------------------------------------------------------------
+
+def sample_statistics(logp, teacher_logp, k_roll, k_sup, mask, cu):
+    """D_i^roll, D_i^sup, l_i (token means over the mask) and cover_i = n_i / H_i.
+
+    Samples with n_i = 0 get zeros everywhere (Algorithm 1, invalid-sample branch)."""
+    lp = np.asarray(logp, dtype=np.float64)
+    lq = np.asarray(teacher_logp, dtype=np.float64)
+    B = cu.shape[0] - 1
+    D_roll = np.zeros(B)
+    D_sup = np.zeros(B)
+    ell = np.zeros(B)
+    cover = np.zeros(B)
+    n = trainable_counts(mask, cu)
+    for i in range(B):
+        a, b = int(cu[i]), int(cu[i + 1])
+        H = b - a
+        if n[i] == 0:
+            continue
+        rows = [t for t in range(a, b) if mask[t] != 0]
+        D_roll[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])
+        D_sup[i] = math.fsum(float(k_sup[t]) for t in rows) / int(n[i])
+        ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / int(n[i])
+        cover[i] = int(n[i]) / H
+    return D_roll, D_sup, ell, cover, n
+
+
+# ----------------------------------------------------------------------------------------
+# freshness score, aggregates, weights, loss (Eq. "freshness"; Sec. 4.2; Algorithm 1)
+# ----------------------------------------------------------------------------------------
+
+def freshness_score(D_roll, D_sup, lag, n_train, alpha, beta):
+    """f_i = exp(-(alpha*sqrt(D_i^roll) + beta*sqrt(D_i^sup))) / (tau_i + 1); 0 if n_i = 0."""
+    if alpha < 0 or beta < 0:
+        raise ValueError("alpha, beta must be non-negative (Eq. freshness)")
+    B = len(D_roll)
+    f = np.zeros(B)
+    for i in range(B):
+        if int(lag[i]) < 0:
+            raise ValueError("negative lag")
+        if int(n_train[i]) == 0:
+            f[i] = 0.0
+            continue
+        surrogate = alpha * math.sqrt(D_roll[i]) + beta * math.sqrt(D_sup[i])
+        f[i] = math.exp(-surrogate) / (int(lag[i]) + 1)
+    return f
+
+
+def buffer_aggregates(f, cover):
+    """(mean freshness, mean roll coverage, mean sup coverage) over all B samples.
+    One mask serves both aligned sets, so the two coverage means coincide."""
+    B = len(f)
+    fbar = math.fsum(float(x) for x in f) / B
+    mbar = math.fsum(float(x) for x in cover) / B
+    return np.array([fbar, mbar, mbar])
+
+
+def freshness_weights(f, xi, n_train):
+    """w_i = ReLU(f_i - xi); invalid samples (n_i = 0) are excluded whatever xi is."""
+    w = np.zeros(len(f))
+    for i in range(len(f)):
+        if int(n_train[i]) == 0:
+            continue
+        w[i] = max(float(f[i]) - xi, 0.0)
+    return w
+
+
+def anchored_loss(w, ell, D_roll, lam):
+    """L = B^-1 * sum_i w_i * (l_i + lambda * D_i^roll)   (Algorithm 1, anchored loss)."""
+    B = len(w)
+    return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / B
+
+
+# ----------------------------------------------------------------------------------------
+# gradient with respect to the logits
+# ----------------------------------------------------------------------------------------
+
+def grad_coefficients(delta, rho, adv, mask, cu, n_train, w, lam, grad_scale=1.0):
+    """c_t = g * m_t * w_i / (B * n_i) * (A_t - lambda * rho_t * delta_t).
+
+    d(-A*lp)/dz = A*(p - onehot) with A constant; d(lambda*k(delta))/dlp = lambda*rho*delta,
+    and dlp/dz = onehot - p, hence the minus sign on the anchor part."""
+    T = len(delta)
+    B = cu.shape[0] - 1
+    c = np.zeros(T)
+    for i in range(B):
+        if int(n_train[i]) == 0 or w[i] == 0.0:
+            continue
+        for t in range(int(cu[i]), int(cu[i + 1])):
+            if mask[t] == 0:
+                continue
+            c[t] = grad_scale * w[i] / (B * int(n_train[i])) * (adv[t] - lam * rho[t] * delta[t])
+    return c
+
+
+def dlogits_row(z, y, lse_t, c_t):
+    """One row of dLoss/dlogits: c_t * (softmax(z) - onehot(y)) in float64."""
+    z = np.asarray(z, dtype=np.float64)
+    if c_t == 0.0:
+        return np.zeros_like(z)
+    g = np.exp(z - lse_t)
+    g[y] -= 1.0
+    return c_t * g
+
+
+# ----------------------------------------------------------------------------------------
+# rounding to the storage types
+# ----------------------------------------------------------------------------------------
+
+def round_to_bf16(x):
+    """Round float64 values to the nearest bfloat16 (8-bit significand, fp32 exponent range),
+    ties to even, straight from float64; returns float64 holding the bf16 value."""
+    x = np.asarray(x, dtype=np.float64)
+    out = np.array(x, copy=True)
+    fin = np.isfinite(x) & (x != 0.0)
+    _, e = np.frexp(x[fin])                 # |x| = m * 2^e with m in [0.5, 1)
+    e = np.maximum(e - 1, -126)             # exponent of the leading bit, clamped at subnormals
+    quantum = np.ldexp(1.0, e - 7)          # spacing of bf16 numbers in that binade
+    r = np.rint(x[fin] / quantum) * quantum
+    r = np.where(np.abs(r) >= np.ldexp(1.0, 128), np.copysign(np.inf, r), r)
+    out[fin] = r
+    return out
+
+
+def bf16_ulp(x):
+    """Spacing of bfloat16 numbers at |x| (float64 in, float64 out)."""
+    x = np.abs(np.asarray(x, dtype=np.float64))
+    _, e = np.frexp(np.where(x == 0.0, 1.0, x))
+    e = np.where(x == 0.0, -126, np.maximum(e - 1, -126))
+    return np.ldexp(1.0, e - 7)
+
+
+def round_to_f32(x):
+    return np.asarray(x, dtype=np.float64).astype(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------------------
+# the whole pass, in Algorithm 1's order
+# ----------------------------------------------------------------------------------------
+
+def fopd_loss_fwd_bwd(logits, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
+                      seq_lens, lag, alpha, beta, xi, lam, grad_scale=1.0,
+                      out_dtype="f32", want_dlogits=True, ld=None):
+    """Runs every step on whole arrays and returns a dict of all intermediate and final values.
+
+    logits: [T, V] float array (bf16 inputs must be widened exactly by the caller).
+    out_dtype: "f32" or "bf16" - the storage type dlogits is rounded to.
+    """
+    logits = np.asarray(logits)
+    T, V = logits.shape
+    if mask is None:
+        mask = np.ones(T, dtype=np.uint8)
+    cu = segment_offsets(seq_lens)
+    if int(cu[-1]) != T:
+        raise ValueError("sequence lengths do not add up to T")
+    gidx = gather_index(token_ids, V if ld is None else ld)
+    lse, lp = token_logprobs(logits, token_ids, mask)
+    delta, rho, adv, k_roll, k_sup = token_terms(lp, behav_logp, teacher_logp, teacher_logp_stale)
+    D_roll, D_sup, ell, cover, n = sample_statistics(lp, teacher_logp, k_roll, k_sup, mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
+    agg = buffer_aggregates(f, cover)
+    w = freshness_weights(f, xi, n)
+    loss = anchored_loss(w, ell, D_roll, lam)
+    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale)
+    res = dict(cu_seqlens=cu, n_train=n, gather_idx=gidx, lse=lse, logp=lp, delta=delta,
+               rho=rho, adv=adv, k_roll=k_roll, k_sup=k_sup, D_roll=D_roll, D_sup=D_sup,
+               ell=ell, cover=cover, freshness=f, agg=agg, weights=w, loss=loss, coef=coef)
+    if want_dlogits:
+        g = np.zeros((T, V), dtype=np.float64)
+        for t in range(T):
+            g[t] = dlogits_row(logits[t], int(token_ids[t]), lse[t], coef[t])
+        res["dlogits_exact"] = g
+        res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
+    return res

@@ -1,0 +1,415 @@
+"""Pins for the float64 oracle: closed forms, library routines, brute-force enumeration and
+finite differences.  None of these tests touches the GPU or the HIP library.
+
+Each test is chosen so that a plausible slip in the oracle (dropped term, wrong sign or
+index, transposed operand, wrong normaliser) makes it fail.
+"""
+
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import fopd_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------------------------------
+# integers
+# ---------------------------------------------------------------------------------------
+
+def test_segment_offsets_and_counts_against_python_ints():
+    rng = _rng(1)
+    seq = rng.integers(0, 9, size=11)
+    seq[3] = 0                                   # an empty sample
+    cu = orc.segment_offsets(seq)
+    assert cu.dtype == np.int64 and cu[0] == 0
+    assert list(cu) == [sum(int(s) for s in seq[:i]) for i in range(12)]
+    T = int(cu[-1])
+    mask = rng.integers(0, 2, size=T).astype(np.uint8)
+    n = orc.trainable_counts(mask, cu)
+    assert n.dtype == np.int32
+    for i in range(11):
+        assert int(n[i]) == int(mask[cu[i]:cu[i + 1]].sum())
+    assert int(n[3]) == 0
+
+
+def test_gather_index_is_64_bit_row_major():
+    ids = np.array([5, 0, 151935], dtype=np.int32)
+    out = orc.gather_index(ids, 151936)
+    assert out.dtype == np.int64
+    assert list(out) == [5, 151936, 2 * 151936 + 151935]
+    # beyond 2^32: row 40000 of a 151936-wide matrix
+    big = orc.gather_index(np.arange(40001, dtype=np.int32) % 7, 151936)
+    assert int(big[40000]) == 40000 * 151936 + 40000 % 7 > 2 ** 32
+
+
+# ---------------------------------------------------------------------------------------
+# log-softmax
+# ---------------------------------------------------------------------------------------
+
+def test_logprobs_match_library_log_softmax():
+    rng = _rng(2)
+    T, V = 9, 257
+    z = rng.normal(0, 3, size=(T, V))
+    z[4] *= 200.0                                # large magnitudes: must not overflow
+    y = rng.integers(0, V, size=T)
+    lse, lp = orc.token_logprobs(z, y, None)
+    ref = scipy.special.log_softmax(z, axis=1)
+    np.testing.assert_allclose(lp, ref[np.arange(T), y], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(lse, scipy.special.logsumexp(z, axis=1), rtol=1e-14)
+    tref = torch.log_softmax(torch.from_numpy(z), dim=1).numpy()
+    np.testing.assert_allclose(lp, tref[np.arange(T), y], rtol=0, atol=1e-12)
+
+
+def test_logprobs_closed_forms():
+    # constant row: lp = -log V whatever the constant
+    V = 1000
+    z = np.full((2, V), 7.25)
+    z[1] = -3e4
+    _, lp = orc.token_logprobs(z, np.array([3, 999]), None)
+    # lse = const + log V is rounded at the magnitude of the constant (ulp(3e4) = 3.6e-12)
+    np.testing.assert_allclose(lp, [-math.log(V)] * 2, rtol=0, atol=1e-11)
+    # z = log(1,2,3,4): probabilities 0.1 .. 0.4
+    z = np.log(np.array([[1.0, 2.0, 3.0, 4.0]] * 4))
+    _, lp = orc.token_logprobs(z, np.array([0, 1, 2, 3]), None)
+    np.testing.assert_allclose(np.exp(lp), [0.1, 0.2, 0.3, 0.4], rtol=1e-14)
+    # two classes, z = (0, log 3): p = (1/4, 3/4)
+    z = np.array([[0.0, math.log(3.0)]] * 2)
+    lse, lp = orc.token_logprobs(z, np.array([0, 1]), None)
+    np.testing.assert_allclose(lp, [math.log(0.25), math.log(0.75)], rtol=1e-14)
+    np.testing.assert_allclose(lse, [math.log(4.0)] * 2, rtol=1e-14)
+
+
+def test_softmax_rows_sum_to_one_and_masked_rows_are_zero():
+    rng = _rng(3)
+    z = rng.normal(0, 2, size=(6, 300))
+    y = rng.integers(0, 300, size=6)
+    mask = np.array([1, 0, 1, 1, 0, 1], dtype=np.uint8)
+    lse, lp = orc.token_logprobs(z, y, mask)
+    for t in range(6):
+        if mask[t]:
+            assert abs(np.exp(z[t] - lse[t]).sum() - 1.0) < 1e-13
+        else:
+            assert lse[t] == 0.0 and lp[t] == 0.0
+
+
+def test_token_out_of_range_raises():
+    z = np.zeros((1, 4))
+    with pytest.raises(ValueError):
+        orc.token_logprobs(z, np.array([4]), None)
+    with pytest.raises(ValueError):
+        orc.token_logprobs(z, np.array([-1]), None)
+
+
+# ---------------------------------------------------------------------------------------
+# estimator k, ratio, advantage
+# ---------------------------------------------------------------------------------------
+
+def test_kl_estimator_expectation_equals_enumerated_kl():
+    """sum_y pi_r(y) k(log pi_t(y) - log pi_r(y)) = KL(pi_t || pi_r) by enumeration."""
+    rng = _rng(4)
+    for V in (2, 5, 16):
+        zt, zr = rng.normal(0, 1.5, size=V), rng.normal(0, 1.5, size=V)
+        pt = np.exp(zt - scipy.special.logsumexp(zt))
+        pr = np.exp(zr - scipy.special.logsumexp(zr))
+        kl = sum(pt[v] * math.log(pt[v] / pr[v]) for v in range(V))
+        kl_rev = sum(pr[v] * math.log(pr[v] / pt[v]) for v in range(V))
+        est = 0.0
+        for y in range(V):
+            d, rho, _, k_roll, _ = orc.token_terms(np.array([math.log(pt[y])]),
+                                                   np.array([math.log(pr[y])]),
+                                                   np.array([0.0]))
+            assert abs(rho[0] - pt[y] / pr[y]) < 1e-12
+            assert k_roll[0] >= 0.0
+            est += pr[y] * k_roll[0]
+        assert abs(est - kl) < 1e-12
+        assert abs(est - kl_rev) > 1e-3          # the direction matters: it is not KL(pi_r||pi_t)
+
+
+def test_k_is_zero_iff_fresh_and_derivative_is_rho_delta():
+    lp = np.array([-1.3, -0.2, -7.0])
+    d, rho, adv, k_roll, k_sup = orc.token_terms(lp, lp.copy(), lp - 0.5, None)
+    assert np.all(d == 0) and np.all(rho == 1.0) and np.all(k_roll == 0.0) and np.all(k_sup == 0.0)
+    np.testing.assert_allclose(adv, [-0.5] * 3)
+    # dk/d(delta) = rho * delta by central differences
+    for delta in (-0.7, -0.01, 0.3, 1.1):
+        h = 1e-6
+        fd = (orc.kl_estimator(delta + h) - orc.kl_estimator(delta - h)) / (2 * h)
+        assert abs(fd - math.exp(delta) * delta) < 1e-8
+    # k_sup uses current minus stale teacher log-prob
+    lq, lqs = np.array([-0.4]), np.array([-0.9])
+    *_, ks = orc.token_terms(np.array([-1.0]), np.array([-1.0]), lq, lqs)
+    e = 0.5
+    assert abs(ks[0] - (math.exp(e) * e - math.exp(e) + 1)) < 1e-15
+
+
+def test_on_policy_expected_gradient_is_gradient_of_reverse_kl():
+    """sum_y p_y * A_y * (p - e_y) = grad_z KL(softmax(z) || q) = p * (log p - log q - KL)."""
+    rng = _rng(5)
+    V = 7
+    z = rng.normal(0, 1.2, size=V)
+    zq = rng.normal(0, 1.2, size=V)
+    logp = z - scipy.special.logsumexp(z)
+    logq = zq - scipy.special.logsumexp(zq)
+    p = np.exp(logp)
+    kl = float(np.sum(p * (logp - logq)))
+    want = p * (logp - logq - kl)
+    got = np.zeros(V)
+    lse = scipy.special.logsumexp(z)
+    for y in range(V):
+        _, _, adv, _, _ = orc.token_terms(np.array([logp[y]]), np.array([logp[y]]), np.array([logq[y]]))
+        got += p[y] * orc.dlogits_row(z, y, lse, adv[0])
+    np.testing.assert_allclose(got, want, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------
+# freshness score, weights, loss
+# ---------------------------------------------------------------------------------------
+
+def test_freshness_closed_form_fixture():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "freshness_closed_form.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 6
+    for tau, dr, ds, a, b, want in rows:
+        f = orc.freshness_score([float(dr)], [float(ds)], [int(tau)], [5], float(a), float(b))
+        assert abs(f[0] - float(want)) <= 1e-15 * max(1.0, float(want)) + 2e-16
+
+
+def test_freshness_lag_only_monotone_and_invalid():
+    lag = np.arange(0, 12)
+    f = orc.freshness_score(np.full(12, 0.3), np.full(12, 0.7), lag, np.full(12, 4), 0.0, 0.0)
+    np.testing.assert_allclose(f, 1.0 / (lag + 1.0), rtol=1e-15)       # lag-only special case
+    f = orc.freshness_score(np.full(12, 0.3), np.full(12, 0.1), lag, np.full(12, 4), 1.0, 2.0)
+    assert np.all(np.diff(f) < 0) and np.all(f > 0) and np.all(f <= 1)
+    D = np.linspace(0, 2, 9)
+    f_r = orc.freshness_score(D, np.zeros(9), np.zeros(9, int), np.ones(9, int), 1.5, 0.5)
+    f_s = orc.freshness_score(np.zeros(9), D, np.zeros(9, int), np.ones(9, int), 1.5, 0.5)
+    assert np.all(np.diff(f_r) < 0) and np.all(np.diff(f_s) < 0)
+    assert f_r[0] == 1.0 and f_s[0] == 1.0
+    np.testing.assert_allclose(f_r, np.exp(-1.5 * np.sqrt(D)), rtol=1e-15)
+    np.testing.assert_allclose(f_s, np.exp(-0.5 * np.sqrt(D)), rtol=1e-15)   # alpha/beta not swapped
+    f = orc.freshness_score([0.0, 0.0], [0.0, 0.0], [0, 0], [0, 3], 1.0, 1.0)
+    assert f[0] == 0.0 and f[1] == 1.0                                  # n_i = 0 -> f_i = 0
+    with pytest.raises(ValueError):
+        orc.freshness_score([0.0], [0.0], [0], [1], -1.0, 0.0)
+    with pytest.raises(ValueError):
+        orc.freshness_score([0.0], [0.0], [-1], [1], 1.0, 0.0)
+
+
+def test_weights_are_relu_of_f_minus_xi():
+    f = np.array([0.9, 0.05, 0.049, 0.0, 0.5])
+    n = np.array([3, 3, 3, 0, 0])
+    w = orc.freshness_weights(f, 0.05, n)
+    np.testing.assert_allclose(w, [0.85, 0.0, 0.0, 0.0, 0.0], atol=1e-16)
+    w = orc.freshness_weights(f, -0.1, n)       # a negative threshold must not revive invalid samples
+    assert w[3] == 0.0 and w[4] == 0.0 and abs(w[1] - 0.15) < 1e-15
+
+
+def test_loss_normaliser_linearity_and_permutation():
+    rng = _rng(6)
+    B = 9
+    w = rng.uniform(0, 1, B); w[2] = 0.0
+    ell = rng.normal(0.2, 0.1, B)
+    D = rng.uniform(0, 0.1, B)
+    L0 = orc.anchored_loss(w, ell, D, 0.0)
+    L1 = orc.anchored_loss(w, ell, D, 1.0)
+    L3 = orc.anchored_loss(w, ell, D, 3.0)
+    assert abs(L0 - float(np.sum(w * ell)) / B) < 1e-15       # divides by all B, gated included
+    assert abs((L3 - L0) - 3.0 * (L1 - L0)) < 1e-15           # linear in lambda
+    assert abs((L1 - L0) - float(np.sum(w * D)) / B) < 1e-15
+    perm = rng.permutation(B)
+    assert orc.anchored_loss(w[perm], ell[perm], D[perm], 0.7) == orc.anchored_loss(w, ell, D, 0.7)
+
+
+# ---------------------------------------------------------------------------------------
+# whole pass: tiny brute-force cases
+# ---------------------------------------------------------------------------------------
+
+def _tiny_case(seed, V=11, seq=(3, 0, 5, 4), stale=True, lag=(0, 2, 1, 3)):
+    rng = _rng(seed)
+    seq = np.array(seq, dtype=np.int32)
+    T = int(seq.sum())
+    z = rng.normal(0, 2, size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    mask = (rng.uniform(size=T) < 0.75).astype(np.uint8)
+    lp_true = scipy.special.log_softmax(z, axis=1)[np.arange(T), y]
+    lb = np.minimum(lp_true + rng.normal(0, 0.2, T), 0.0)
+    lq = np.minimum(lp_true + rng.normal(-0.3, 0.5, T), 0.0)
+    lqs = np.minimum(lq + rng.normal(0, 0.2, T), 0.0) if stale else None
+    return dict(z=z, y=y, mask=mask, lb=lb, lq=lq, lqs=lqs, seq=seq,
+                lag=np.array(lag, dtype=np.int32))
+
+
+def _scalar_reimplementation(c, alpha, beta, xi, lam, g):
+    """The same pass with nothing but Python floats and loops (no numpy arithmetic)."""
+    z, y, mask = c["z"], c["y"], c["mask"]
+    T, V = z.shape
+    B = len(c["seq"])
+    out_f, out_w, out_D, out_ell = [], [], [], []
+    grads = [[0.0] * V for _ in range(T)]
+    loss = 0.0
+    start = 0
+    for i in range(B):
+        H = int(c["seq"][i])
+        rows = [t for t in range(start, start + H) if mask[t]]
+        start += H
+        if not rows:
+            out_f.append(0.0); out_w.append(0.0); out_D.append(0.0); out_ell.append(0.0)
+            continue
+        lps = {}
+        for t in rows:
+            mx = max(float(v) for v in z[t])
+            lse = mx + math.log(sum(math.exp(float(v) - mx) for v in z[t]))
+            lps[t] = (float(z[t][y[t]]) - lse, lse)
+        n = len(rows)
+        Dr = sum(math.exp(lps[t][0] - c["lb"][t]) * (lps[t][0] - c["lb"][t])
+                 - math.exp(lps[t][0] - c["lb"][t]) + 1.0 for t in rows) / n
+        Ds = 0.0
+        if c["lqs"] is not None:
+            Ds = sum(math.exp(c["lq"][t] - c["lqs"][t]) * (c["lq"][t] - c["lqs"][t])
+                     - math.exp(c["lq"][t] - c["lqs"][t]) + 1.0 for t in rows) / n
+        el = sum(lps[t][0] - c["lq"][t] for t in rows) / n
+        f = math.exp(-alpha * math.sqrt(Dr) - beta * math.sqrt(Ds)) / (int(c["lag"][i]) + 1)
+        w = max(f - xi, 0.0)
+        loss += w * (el + lam * Dr) / B
+        for t in rows:
+            lp, lse = lps[t]
+            d = lp - c["lb"][t]
+            ct = g * w / (B * n) * ((c["lq"][t] - lp) - lam * math.exp(d) * d)
+            for v in range(V):
+                grads[t][v] = ct * (math.exp(float(z[t][v]) - lse) - (1.0 if v == y[t] else 0.0))
+        out_f.append(f); out_w.append(w); out_D.append(Dr); out_ell.append(el)
+    return dict(f=out_f, w=out_w, D=out_D, ell=out_ell, loss=loss, grads=np.array(grads))
+
+
+@pytest.mark.parametrize("seed,stale", [(10, True), (11, False), (12, True)])
+def test_whole_pass_matches_scalar_reimplementation(seed, stale):
+    c = _tiny_case(seed, stale=stale)
+    hp = dict(alpha=1.3, beta=0.6, xi=0.2, lam=0.4)
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"],
+                                c["lag"], grad_scale=1.7, **hp)
+    ref = _scalar_reimplementation(c, hp["alpha"], hp["beta"], hp["xi"], hp["lam"], 1.7)
+    np.testing.assert_allclose(res["freshness"], ref["f"], rtol=1e-13, atol=0)
+    np.testing.assert_allclose(res["weights"], ref["w"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["D_roll"], ref["D"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["ell"], ref["ell"], rtol=1e-12, atol=1e-16)
+    assert abs(res["loss"] - ref["loss"]) < 1e-14
+    np.testing.assert_allclose(res["dlogits_exact"], ref["grads"], rtol=1e-11, atol=1e-16)
+    assert res["freshness"][1] == 0.0 and res["cover"][1] == 0.0          # the empty sample
+    assert np.any(res["weights"] == 0.0) and np.any(res["weights"] > 0.0)  # both branches taken
+    np.testing.assert_allclose(res["agg"][0], np.mean(res["freshness"]), rtol=1e-15)
+    np.testing.assert_allclose(res["agg"][1], np.mean(res["cover"]), rtol=1e-15)
+
+
+def test_fresh_buffer_gives_unit_ratio_and_unit_score():
+    c = _tiny_case(20, stale=False, lag=(0, 0, 0, 0))
+    _, lp = orc.token_logprobs(c["z"], c["y"], c["mask"])
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], lp, c["lq"], None, c["seq"], c["lag"],
+                                alpha=2.0, beta=3.0, xi=0.0, lam=0.5)
+    assert np.all(res["rho"][c["mask"] == 1] == 1.0)
+    assert np.all(res["D_roll"] == 0.0) and np.all(res["D_sup"] == 0.0)
+    valid = res["n_train"] > 0
+    assert np.all(res["freshness"][valid] == 1.0) and np.all(res["freshness"][~valid] == 0.0)
+    # with zero drift the anchor contributes nothing: loss is the weighted mean of l_i
+    assert abs(res["loss"] - float(np.sum(res["weights"] * res["ell"])) / 4) < 1e-15
+
+
+def test_gradient_rows_sum_to_zero_gated_rows_exactly_zero():
+    c = _tiny_case(21, lag=(0, 1, 40, 2))
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"],
+                                c["lag"], alpha=1.0, beta=1.0, xi=0.05, lam=0.1)
+    g = res["dlogits_exact"]
+    assert np.max(np.abs(g.sum(axis=1))) < 1e-15
+    cu = res["cu_seqlens"]
+    assert res["weights"][2] == 0.0 and res["freshness"][2] > 0.0         # lag 40 -> gated
+    assert np.all(g[cu[2]:cu[3]] == 0.0) and np.all(res["dlogits"][cu[2]:cu[3]] == 0.0)
+    assert np.all(g[c["mask"] == 0] == 0.0)
+    live = (c["mask"] == 1) & (np.repeat(res["weights"], c["seq"]) > 0)
+    assert np.all(np.abs(g[live]).sum(axis=1) > 0)
+    # gating removes the sample from the loss but not from the 1/B normaliser
+    keep = [0, 3]
+    L = sum(res["weights"][i] * (res["ell"][i] + 0.1 * res["D_roll"][i]) for i in keep) / 4
+    assert abs(res["loss"] - L) < 1e-15
+
+
+def test_gradient_by_finite_differences_of_surrogate():
+    """F(z) = sum_t m_t w_i/(B n_i) [ (lp_t - lq_t)^2 / 2 + lambda k(lp_t - lb_t) ] with w frozen
+    has dF/dlp = (lp - lq) + lambda rho delta = -(A - lambda rho delta): the oracle's gradient
+    must equal grad F.  log-softmax here comes from scipy, not from the oracle."""
+    c = _tiny_case(22, V=6, seq=(2, 3), lag=(1, 0))
+    c["mask"][:] = 1
+    c["mask"][3] = 0
+    hp = dict(alpha=0.8, beta=0.3, xi=0.1, lam=0.7)
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"],
+                                c["lag"], grad_scale=2.5, **hp)
+    w, n, cu = res["weights"], res["n_train"], res["cu_seqlens"]
+    T, V = c["z"].shape
+    B = 2
+    sample_of = np.repeat(np.arange(B), c["seq"])
+
+    def F(zz):
+        lp = scipy.special.log_softmax(zz, axis=1)[np.arange(T), c["y"]]
+        tot = 0.0
+        for t in range(T):
+            if not c["mask"][t]:
+                continue
+            i = sample_of[t]
+            d = lp[t] - c["lb"][t]
+            tot += 2.5 * w[i] / (B * n[i]) * (0.5 * (lp[t] - c["lq"][t]) ** 2
+                                             + hp["lam"] * (math.exp(d) * d - math.exp(d) + 1))
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = c["z"].copy(), c["z"].copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (F(zp) - F(zm)) / (2 * h)
+    scale = np.max(np.abs(num))
+    assert scale > 1e-3
+    assert np.max(np.abs(num - res["dlogits_exact"])) < 1e-6 * scale * 10
+    assert np.all(res["dlogits_exact"][3] == 0.0)
+
+
+def test_sequence_lengths_must_cover_all_rows():
+    c = _tiny_case(23)
+    with pytest.raises(ValueError):
+        orc.fopd_loss_fwd_bwd(c["z"][:-1], c["y"][:-1], c["mask"][:-1], c["lb"][:-1], c["lq"][:-1],
+                              None, c["seq"], c["lag"], 1.0, 1.0, 0.0, 0.0)
+
+
+# ---------------------------------------------------------------------------------------
+# rounding to the storage types
+# ---------------------------------------------------------------------------------------
+
+def test_bf16_rounding_matches_library_on_float32_inputs():
+    rng = _rng(7)
+    x32 = np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 1e-6, 5000),
+                          rng.normal(0, 1e30, 5000), [0.0, -0.0, 1.0, -1.0, 3.3895313892515355e38],
+                          rng.normal(0, 1e-39, 2000)]).astype(np.float32)
+    want = torch.from_numpy(x32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = orc.round_to_bf16(x32.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_bf16_rounding_ties_and_no_double_rounding():
+    e = 2.0 ** -7                                  # bf16 spacing in [1, 2)
+    assert orc.round_to_bf16(1.0 + e / 2) == 1.0            # tie -> even (mantissa 0)
+    assert orc.round_to_bf16(1.0 + 3 * e / 2) == 1.0 + 2 * e  # tie -> even (mantissa 2)
+    x = 1.0 + e / 2 + 2.0 ** -40                   # just above the tie; float32 would lose the 2^-40
+    assert np.float64(np.float32(x)) == 1.0 + e / 2
+    assert orc.round_to_bf16(x) == 1.0 + e
+    assert orc.round_to_bf16(-x) == -(1.0 + e)
+    np.testing.assert_array_equal(orc.bf16_ulp([1.0, 1.99, 2.0, 0.75, 0.0]),
+                                  [e, e, 2 * e, e / 2, 2.0 ** -133])
