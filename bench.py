@@ -1,0 +1,143 @@
+"""Benchmark of the fused f-OPD loss pass on one MI355X.
+
+A step is one call of fopd_loss_fwd_bwd that does everything (token log-probs, drift diagnostics,
+freshness scores, weights, loss, gradient) over the "reasoning" workload: B=64 ragged sequences,
+V=151,936, bf16 logits, already resident in HBM.  Prints one JSON line.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def cpu_baseline(w, hp, budget_rows=1536):
+    """The float64 oracle, as it stands, on whole samples of the same workload (host cores)."""
+    import numpy as np
+    from oracle import fopd_oracle as orc
+
+    seq = w["seq_lens_host"]
+    cu = orc.segment_offsets(seq)
+    order = np.argsort(seq, kind="stable")
+    chosen, rows = [], 0
+    for i in order:
+        chosen.append(int(i))
+        rows += int(seq[i])
+        if rows >= budget_rows:
+            break
+    a, b, xi, lam = hp
+    host = []
+    for i in chosen:                                   # copies are not timed
+        s, e = int(cu[i]), int(cu[i + 1])
+        host.append(dict(z=w["logits"][s:e].float().cpu().double().numpy(),
+                         y=w["token_ids"][s:e].cpu().numpy(), m=w["mask_host"][s:e],
+                         lb=w["behav_logp"][s:e].cpu().double().numpy(),
+                         lq=w["teacher_logp"][s:e].cpu().double().numpy(),
+                         seq=seq[i:i + 1], lag=w["lag_host"][i:i + 1]))
+    t0 = time.perf_counter()
+    trainable = 0
+    for h in host:
+        res = orc.fopd_loss_fwd_bwd(h["z"], h["y"], h["m"], h["lb"], h["lq"], None, h["seq"], h["lag"],
+                                    a, b, xi, lam, out_dtype="bf16", want_dlogits=True)
+        trainable += int(res["n_train"].sum())
+    dt = time.perf_counter() - t0
+    return dict(value=trainable / dt, unit="tokens/s", cores=1, kind="oracle",
+                sample="%d whole samples (%d rows, V=%d) of the same workload, full pass incl. bf16 gradient, "
+                       "%.1f s single-threaded numpy float64" % (len(chosen), rows, w["V"], dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="reasoning")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the loss pass shards by sample with no "
+                 "exchange on the hot path); run it with --gpus 1")
+
+    import torch
+    from paper_2605_17862_amd import binding as fb
+    from paper_2605_17862_amd import workloads as wl
+    from paper_2605_17862_amd.loss_pass import DEFAULT_HPARAMS, LossPass
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    fb.load_library()
+    hp = DEFAULT_HPARAMS
+    w = wl.generate(args.workload, "cuda:0", seed=0)
+    T, V, B = w["T"], w["V"], w["B"]
+    lp = LossPass(T, V, B, w["dtype"], ld=w["ld"], device="cuda:0")
+
+    for _ in range(args.warmup):
+        lp.loss_fwd_bwd(w, hp)
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        lp.loss_fwd_bwd(w, hp)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fb.fopd_profile_enable(False)
+    st, flags = lp.status()
+    if st != 0:
+        sys.exit("device flags set: %d" % flags)
+
+    k1_ms, k1_n = fb.fopd_profile_read(0)
+    k4_ms, k4_n = fb.fopd_profile_read(1)
+    ms_per_step = elapsed / args.steps * 1e3
+    n_train = w["n_trainable"]
+
+    # algorithmic HBM bytes of one launch (element size e): a live row of an un-gated sample is read
+    # once and written once by the gradient kernel; a masked or gated row is only written
+    import numpy as np
+    e = 2 if w["dtype"] == "bf16" else 4
+    wts = lp.weights.cpu().numpy()
+    per_row_w = np.repeat(wts, w["seq_lens_host"])
+    live = (w["mask_host"] != 0) & (per_row_w > 0)
+    rows_live = int(live.sum())
+    side = 4 * 4                                        # coef, lse, logp, token id per row
+    k4_bytes = rows_live * 2 * V * e + (T - rows_live) * V * e + T * side
+    k1_rows = int((w["mask_host"] != 0).sum())
+    k1_bytes = k1_rows * V * e + T * (4 + 1 + 8)
+    k4_avg_s = k4_ms / max(k4_n, 1) * 1e-3
+    k1_avg_s = k1_ms / max(k1_n, 1) * 1e-3
+    achieved = k4_bytes / k4_avg_s / 1e9
+
+    out = {
+        "metric": "tokens/s and % HBM peak, fused OPD loss fwd+bwd, V=151,936 bf16",
+        "value": n_train * args.steps / elapsed,
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "T_rows": T, "trainable_tokens": n_train, "V": V,
+                   "storage": w["dtype"], "hparams": {"alpha": hp[0], "beta": hp[1], "xi": hp[2], "lambda": hp[3]},
+                   "gated_samples": int((wts == 0).sum()), "call": "fopd_loss_fwd_bwd (all steps fused)"},
+        "roofline": {"bound": "hbm", "kernel": "fopd_k4_grad", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": k4_bytes, "avg_ms": k4_avg_s * 1e3},
+        "kernels": {"fopd_k1_lse": {"avg_ms": k1_avg_s * 1e3, "GB/s": k1_bytes / k1_avg_s / 1e9,
+                                    "frac": k1_bytes / k1_avg_s / 1e9 / HBM_PEAK_GBS},
+                    "fopd_k4_grad": {"avg_ms": k4_avg_s * 1e3, "GB/s": achieved},
+                    "whole_step_GB/s": (k1_bytes + k4_bytes) / (ms_per_step * 1e-3) / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, hp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,185 @@
+/*
+ * fopd.h - C ABI of the f-OPD loss pass for AMD MI355X (gfx950).
+ *
+ * The library evaluates, for one batch of buffered rollouts, the freshness-weighted,
+ * rollout-anchored on-policy-distillation objective of the f-OPD paper and its gradient
+ * with respect to the student logits:
+ *
+ *   per token   lp_t   = log softmax(z_t)[y_t]                       (student term of Eq. "kl-diagnostics"
+ *                                                                     and Eq. "sample-aggregated-loss")
+ *               delta_t = lp_t - lb_t,  rho_t = exp(delta_t)          (log-ratio to the rollout policy)
+ *               A_t    = lq_t - lp_t                                  (advantage against the teacher)
+ *               k(d)   = e^d d - e^d + 1                              (sampled-token KL estimator)
+ *   per sample  D_i^roll = mean_{t in U_i} k(delta_t)                 (Eq. "kl-diagnostics", line 1)
+ *               D_i^sup  = mean_{t in U_i} k(lq_t - lq_t^stale)       (Eq. "kl-diagnostics", line 2; 0 if absent)
+ *               l_i      = mean_{t in U_i} (lp_t - lq_t)              (Eq. "sample-aggregated-loss")
+ *               f_i      = exp(-alpha sqrt(D_i^roll) - beta sqrt(D_i^sup)) / (tau_i + 1)   (Eq. "freshness")
+ *               w_i      = max(f_i - xi, 0)                           (freshness weighting, Sec. 4.2)
+ *   buffer      L = B^-1 sum_i w_i (l_i + lambda D_i^roll)            (anchored objective, Algorithm 1)
+ *   gradient    dL/dz_{t,v} = c_t (softmax(z_t)_v - [v = y_t]),
+ *               c_t = g m_t w_i / (B n_i) (A_t - lambda rho_t delta_t),   w_i and A_t held constant.
+ *
+ * Here U_i is the set of rows of sample i whose mask is 1, n_i = |U_i|, H_i = seq_lens[i],
+ * tau_i = lag[i], and a sample with n_i = 0 has f_i = w_i = 0 (Algorithm 1, invalid-sample branch).
+ *
+ * Conventions common to every entry point
+ *   - Every pointer argument is a DEVICE pointer (HIP device memory) unless it is named
+ *     "*_host".  The caller owns all buffers; the library allocates no device memory.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  No entry point synchronises, except those documented as host-synchronous.
+ *   - Matrices are row-major [T, ld] with ld >= V; columns V..ld-1 are never read or written.
+ *     The base address must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
+ *   - The return value reports what the host can check before launching (arguments, sizes,
+ *     alignment, workspace size) and launch failures.  Conditions only visible on the device
+ *     (token id outside [0, V), negative lag or length, lengths not adding up to T) set sticky
+ *     bits in the first int32 of the workspace; fopd_workspace_status() reads them.  A row
+ *     with an out-of-range token id is treated as masked.
+ *   - Non-finite inputs propagate to non-finite outputs; nothing traps.
+ *   - Identical inputs give bit-identical outputs (all reductions have a fixed order).
+ *   - Masked rows (mask 0) produce lp = lse = 0 and an all-zero gradient row and are not read.
+ */
+#ifndef FOPD_H
+#define FOPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FOPD_OK = 0,
+  FOPD_EINVAL = 1,       /* NULL required pointer, negative alpha/beta, inconsistent optional arguments */
+  FOPD_ESHAPE = 2,       /* T, V, B <= 0 (T = 0 is allowed and does nothing), ld < V, V > 2^31-16 */
+  FOPD_EALIGN = 3,       /* base pointer or row pitch not 16-byte aligned */
+  FOPD_EDTYPE = 4,       /* dtype is neither FOPD_F32 nor FOPD_BF16 */
+  FOPD_EWORKSPACE = 5,   /* workspace NULL, misaligned (256 B) or smaller than fopd_workspace_bytes */
+  FOPD_ETOKEN_RANGE = 6, /* device flag: some token id outside [0, V) */
+  FOPD_ESEGMENTS = 7,    /* device flag: seq_lens negative or not covering the rows of the call */
+  FOPD_ELAG = 8,         /* device flag: some lag < 0 */
+  FOPD_EHIP = 9          /* a HIP runtime call or kernel launch failed */
+} fopd_status;
+
+typedef enum { FOPD_F32 = 0, FOPD_BF16 = 1 } fopd_dtype;
+
+/* Hyper-parameters of Algorithm 1: score coefficients alpha, beta >= 0 (Eq. "freshness"),
+ * gate threshold xi (freshness weighting) and anchor strength lambda (full objective). */
+typedef struct {
+  float alpha;
+  float beta;
+  float xi;
+  float lambda;
+} fopd_hparams;
+
+/* Static, NUL-terminated description of a status code. Never NULL. */
+const char* fopd_status_string(int status);
+
+/* Bytes of device workspace that any entry point needs for a call with at most T rows and B
+ * samples (a multiple of 256).  The workspace must be 256-byte aligned. */
+size_t fopd_workspace_bytes(int64_t T, int32_t B);
+
+/* Clears the sticky device flags at the head of a workspace (asynchronous, on `stream`).
+ * Must be called once before the first use of a workspace; may be called again at any time. */
+fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
+
+/* HOST-SYNCHRONOUS.  Waits for `stream`, reads the sticky device flags and returns FOPD_OK or the
+ * first of FOPD_ETOKEN_RANGE, FOPD_ESEGMENTS, FOPD_ELAG that is set.  If flags_host is not NULL
+ * it receives the raw bit mask (bit 0 token range, bit 1 segments, bit 2 lag). */
+fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host);
+
+/*
+ * Student log-probability of the sampled tokens: the streaming pass over the logits.
+ * (pi_theta^t(y_{i,h} | x_{i,h}) of Eq. "kl-diagnostics" / Eq. "sample-aggregated-loss".)
+ *
+ *   logits      [T, ld] of `dt`, read once (masked rows are skipped)
+ *   token_ids   [T] int32, sampled token y_t of each row
+ *   mask        [T] uint8 0/1, NULL = all ones
+ *   logp        [T] f32 out: lp_t = z_{t,y_t} - lse_t   (0 for masked rows)
+ *   lse         [T] f32 out: log sum_v exp(z_{t,v})      (0 for masked rows)
+ *   gather_idx  [T] int64 out, NULL to skip: t * ld + y_t for every row, masked or not
+ *
+ * lp_t is formed from the sum over v != y_t, so it keeps full relative accuracy as
+ * softmax(z_t)[y_t] approaches 1.
+ */
+fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                const int32_t* token_ids, const uint8_t* mask,
+                                float* logp, float* lse, int64_t* gather_idx,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-sample drift diagnostics and freshness scores (first loop of Algorithm 1; Eq.
+ * "kl-diagnostics", Eq. "freshness", buffer aggregates of Sec. 4.2).  Touches only the
+ * per-token and per-sample arrays, never the logits.
+ *
+ *   logp, behav_logp, teacher_logp  [T] f32: current student, rollout-time student and
+ *                                   current-context teacher log-probability of y_t
+ *   teacher_logp_stale              [T] f32 or NULL: teacher log-probability under the context
+ *                                   used at grading time; NULL gives D^sup = 0
+ *   mask [T] uint8 or NULL; seq_lens [B] int32 (sum must be T); lag [B] int32 >= 0
+ *   outputs: cu_seqlens [B+1] int64 (exclusive scan of seq_lens), n_train [B] int32,
+ *            D_roll, D_sup, ell, cover (= n_i / H_i), freshness: [B] f32 each,
+ *            agg [3] f32 = mean_i f_i, mean_i cover_i (roll), mean_i cover_i (sup).
+ *   Any of the output pointers except freshness may be NULL.
+ */
+fopd_status fopd_freshness_score(const float* logp, const float* behav_logp,
+                                 const float* teacher_logp, const float* teacher_logp_stale,
+                                 const uint8_t* mask, const int32_t* seq_lens, const int32_t* lag,
+                                 int64_t T, int32_t B, fopd_hparams hp,
+                                 int64_t* cu_seqlens, int32_t* n_train,
+                                 float* D_roll, float* D_sup, float* ell, float* cover,
+                                 float* freshness, float* agg,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Loss and gradient (second loop of Algorithm 1), fused with the two steps above when their
+ * results are not supplied.
+ *
+ * The call covers rows [row_begin, row_begin + T) of the concatenation of the B samples.
+ *
+ *   freshness_in == NULL : everything is computed here; requires lse_in == logp_in ==
+ *                          n_train_in == NULL, row_begin == 0 and sum(seq_lens) == T.
+ *   freshness_in != NULL : [B] scores computed earlier (Algorithm 1 scores the buffer before
+ *                          the minibatch loop); they define the weights.  n_train_in is the
+ *                          [B] count array of fopd_freshness_score, or NULL when the call
+ *                          covers whole samples (row_begin == 0, sum(seq_lens) == T) and the
+ *                          counts are to be taken from `mask`.
+ *   lse_in / logp_in     : both or neither.  When given ([T] f32, the outputs of
+ *                          fopd_token_logprobs for these rows) the logits are read only by the
+ *                          gradient pass.  Requires freshness_in.
+ *
+ *   grad_scale  upstream scale g of the loss (1 for the plain objective)
+ *   loss        [1] f32 out: sum over the rows of the call of
+ *               m_t w_i / (B n_i) (lp_t - lq_t + lambda k(delta_t)); equals L when the call
+ *               covers all rows, and the chunk's additive share of L otherwise
+ *   freshness   [B] f32 out or NULL (a copy of freshness_in when that is given)
+ *   weights     [B] f32 out or NULL
+ *   logp        [T] f32 out or NULL
+ *   dlogits     [T, ld] of `dt` out, rounded to nearest-even; MAY alias `logits` (in place)
+ */
+fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                              const int32_t* token_ids, const uint8_t* mask,
+                              const float* behav_logp, const float* teacher_logp,
+                              const float* teacher_logp_stale,
+                              const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                              const float* freshness_in, const int32_t* n_train_in, int64_t row_begin,
+                              const float* lse_in, const float* logp_in,
+                              float grad_scale,
+                              float* loss, float* freshness, float* weights, float* logp,
+                              void* dlogits,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
+ * is bracketed by HIP events on the launch stream.  Not thread-safe; meant for a single
+ * benchmarking thread.  fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
+ *   which: 0 = log-sum-exp pass, 1 = gradient pass.
+ */
+fopd_status fopd_profile_enable(int on);
+fopd_status fopd_profile_reset(void);
+fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FOPD_H */

@@ -220,15 +220,18 @@ def anchored_loss(w, ell, D_roll, lam):
 # gradient with respect to the logits
 # ----------------------------------------------------------------------------------------
 
-def grad_coefficients(delta, rho, adv, mask, cu, n_train, w, lam, grad_scale=1.0):
+def grad_coefficients(delta, rho, adv, mask, cu, n_train, w, lam, grad_scale=1.0, n_samples=None):
     """c_t = g * m_t * w_i / (B * n_i) * (A_t - lambda * rho_t * delta_t).
+
+    B is the number of samples of the whole buffer: len(cu) - 1, or `n_samples` when the arrays
+    passed in hold only some of the buffer's samples.
 
     d(-A*lp)/dz = A*(p - onehot) with A constant; d(lambda*k(delta))/dlp = lambda*rho*delta,
     and dlp/dz = onehot - p, hence the minus sign on the anchor part."""
     T = len(delta)
-    B = cu.shape[0] - 1
+    B = cu.shape[0] - 1 if n_samples is None else int(n_samples)
     c = np.zeros(T)
-    for i in range(B):
+    for i in range(cu.shape[0] - 1):
         if int(n_train[i]) == 0 or w[i] == 0.0:
             continue
         for t in range(int(cu[i]), int(cu[i + 1])):

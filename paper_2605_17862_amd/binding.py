@@ -1,0 +1,203 @@
+"""ctypes binding of include/fopd.h.
+
+Argument marshalling only: every function here has the name and argument order of the C entry
+point it calls, takes torch tensors (or raw device addresses as ints) for the pointer
+arguments, and launches on torch's current stream unless told otherwise.  All arithmetic runs
+in the HIP kernels; if the shared library is missing or cannot be loaded this module raises.
+"""
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "lib", "libfopd.so")
+
+FOPD_F32 = 0
+FOPD_BF16 = 1
+
+SYMBOLS = (
+    "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
+    "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
+    "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read",
+)
+
+
+class Hparams(ctypes.Structure):
+    """fopd_hparams: alpha, beta (score coefficients), xi (gate), lambda (anchor strength)."""
+    _fields_ = [("alpha", ctypes.c_float), ("beta", ctypes.c_float),
+                ("xi", ctypes.c_float), ("lambda_", ctypes.c_float)]
+
+
+class FopdError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s: status %d (%s)" % (where, self.status, fopd_status_string(self.status)))
+
+
+_lib = None
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads lib/libfopd.so (built by paper_2605_17862_amd/build.py).  Fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("HIP library not built: %s is missing (run `python -m paper_2605_17862_amd.build`)"
+                          % _LIB_PATH)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32, f32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+    lib.fopd_status_string.restype = ctypes.c_char_p
+    lib.fopd_status_string.argtypes = [ctypes.c_int]
+    lib.fopd_workspace_bytes.restype = sz
+    lib.fopd_workspace_bytes.argtypes = [i64, i32]
+    lib.fopd_workspace_init.restype = ctypes.c_int
+    lib.fopd_workspace_init.argtypes = [vp, sz, vp]
+    lib.fopd_workspace_status.restype = ctypes.c_int
+    lib.fopd_workspace_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.fopd_token_logprobs.restype = ctypes.c_int
+    lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_freshness_score.restype = ctypes.c_int
+    lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
+                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
+    lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
+                                      vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_profile_enable.restype = ctypes.c_int
+    lib.fopd_profile_enable.argtypes = [ctypes.c_int]
+    lib.fopd_profile_reset.restype = ctypes.c_int
+    lib.fopd_profile_reset.argtypes = []
+    lib.fopd_profile_read.restype = ctypes.c_int
+    lib.fopd_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    _lib = lib
+    return lib
+
+
+def _ptr(x, dtype=None, name="argument"):
+    """Device address of a tensor (checked: contiguous, on a GPU, expected dtype), an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if not x.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if not x.is_cuda:
+        raise ValueError("%s must live in device memory" % name)
+    if dtype is not None and x.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise ValueError("%s has dtype %s, expected %s" % (name, x.dtype, dtype))
+    return ctypes.c_void_p(x.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def _check(status, where):
+    if status != 0:
+        raise FopdError(status, where)
+
+
+def _hp(hp):
+    if isinstance(hp, Hparams):
+        return hp
+    alpha, beta, xi, lam = hp
+    return Hparams(float(alpha), float(beta), float(xi), float(lam))
+
+
+def _ws(workspace):
+    if isinstance(workspace, tuple):
+        return ctypes.c_void_p(int(workspace[0])), int(workspace[1])
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def fopd_status_string(status):
+    return load_library().fopd_status_string(int(status)).decode()
+
+
+def fopd_workspace_bytes(T, B):
+    return int(load_library().fopd_workspace_bytes(int(T), int(B)))
+
+
+def fopd_workspace_init(workspace, stream=None):
+    p, n = _ws(workspace)
+    _check(load_library().fopd_workspace_init(p, n, _stream(stream)), "fopd_workspace_init")
+
+
+def fopd_workspace_status(workspace, stream=None):
+    """Host-synchronous.  Returns (status, flag bits)."""
+    p, _ = _ws(workspace)
+    flags = ctypes.c_int32(0)
+    st = load_library().fopd_workspace_status(p, _stream(stream), ctypes.byref(flags))
+    return int(st), int(flags.value)
+
+
+def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, workspace,
+                        stream=None):
+    import torch
+    p, n = _ws(workspace)
+    st = load_library().fopd_token_logprobs(
+        _ptr(logits, (torch.float32, torch.bfloat16), "logits"), int(dt), int(T), int(V), int(ld),
+        _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(logp, torch.float32, "logp"), _ptr(lse, torch.float32, "lse"),
+        _ptr(gather_idx, torch.int64, "gather_idx"), p, n, _stream(stream))
+    _check(st, "fopd_token_logprobs")
+
+
+def fopd_freshness_score(logp, behav_logp, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B, hp,
+                         cu_seqlens, n_train, D_roll, D_sup, ell, cover, freshness, agg, workspace,
+                         stream=None):
+    import torch
+    f32 = torch.float32
+    p, n = _ws(workspace)
+    st = load_library().fopd_freshness_score(
+        _ptr(logp, f32, "logp"), _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(T), int(B), _hp(hp),
+        _ptr(cu_seqlens, torch.int64, "cu_seqlens"), _ptr(n_train, torch.int32, "n_train"),
+        _ptr(D_roll, f32, "D_roll"), _ptr(D_sup, f32, "D_sup"), _ptr(ell, f32, "ell"),
+        _ptr(cover, f32, "cover"), _ptr(freshness, f32, "freshness"), _ptr(agg, f32, "agg"),
+        p, n, _stream(stream))
+    _check(st, "fopd_freshness_score")
+
+
+def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
+                      seq_lens, lag, B, hp, freshness_in, n_train_in, row_begin, lse_in, logp_in, grad_scale,
+                      loss, freshness, weights, logp, dlogits, workspace, stream=None):
+    import torch
+    f32 = torch.float32
+    mat = (torch.float32, torch.bfloat16)
+    p, n = _ws(workspace)
+    st = load_library().fopd_loss_fwd_bwd(
+        _ptr(logits, mat, "logits"), int(dt), int(T), int(V), int(ld),
+        _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
+        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"), int(row_begin),
+        _ptr(lse_in, f32, "lse_in"), _ptr(logp_in, f32, "logp_in"), float(grad_scale),
+        _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
+        _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
+    _check(st, "fopd_loss_fwd_bwd")
+
+
+def fopd_profile_enable(on):
+    _check(load_library().fopd_profile_enable(int(bool(on))), "fopd_profile_enable")
+
+
+def fopd_profile_reset():
+    _check(load_library().fopd_profile_reset(), "fopd_profile_reset")
+
+
+def fopd_profile_read(which):
+    """Host-synchronous.  Returns (total milliseconds, number of launches) of kernel `which`."""
+    ms = ctypes.c_double(0.0)
+    n = ctypes.c_int64(0)
+    _check(load_library().fopd_profile_read(int(which), ctypes.byref(ms), ctypes.byref(n)), "fopd_profile_read")
+    return float(ms.value), int(n.value)

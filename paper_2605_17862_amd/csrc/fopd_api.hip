@@ -1,0 +1,317 @@
+// Host side of the C ABI declared in include/fopd.h: argument checks, workspace carving and
+// kernel launches.  Nothing here allocates device memory or synchronises, apart from the
+// two documented host-synchronous helpers.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "fopd.h"
+#include "fopd_kernels.hip"
+
+namespace {
+
+using namespace fopd;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Carving of the caller's workspace.  Every region starts on a 256-byte boundary.
+struct Workspace {
+  size_t flags, cu, n_train, fresh64, coef, lse, logp, partials, total;
+  Workspace(int64_t T, int32_t B) {
+    const size_t t = static_cast<size_t>(T < 0 ? 0 : T), b = static_cast<size_t>(B < 0 ? 0 : B);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+      const size_t at = off;
+      off = align_up(off + bytes, 256);
+      return at;
+    };
+    flags = take(4 * sizeof(int32_t));
+    cu = take((b + 1) * sizeof(int64_t));
+    n_train = take(b * sizeof(int32_t));
+    fresh64 = take(b * sizeof(double));
+    coef = take(t * sizeof(float));
+    lse = take(t * sizeof(float));
+    logp = take(t * sizeof(float));
+    partials = take(((t + kStreamThreads - 1) / kStreamThreads + 1) * sizeof(double));
+    total = off;
+  }
+};
+
+template <typename P>
+inline P* at(void* ws, size_t off) {
+  return reinterpret_cast<P*>(static_cast<char*>(ws) + off);
+}
+
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+fopd_status check_matrix(const void* m, fopd_dtype dt, int64_t T, int64_t V, int64_t ld) {
+  if (dt != FOPD_F32 && dt != FOPD_BF16) return FOPD_EDTYPE;
+  if (T < 0 || V <= 0 || ld < V || V > 2147483647LL - 16) return FOPD_ESHAPE;
+  if (m == nullptr) return FOPD_EINVAL;
+  const size_t es = (dt == FOPD_F32) ? 4 : 2;
+  if (misaligned(m, 16) || (static_cast<size_t>(ld) * es) % 16 != 0) return FOPD_EALIGN;
+  return FOPD_OK;
+}
+
+fopd_status check_workspace(const void* ws, size_t bytes, int64_t T, int32_t B) {
+  if (ws == nullptr || misaligned(ws, 256)) return FOPD_EWORKSPACE;
+  if (bytes < Workspace(T, B).total) return FOPD_EWORKSPACE;
+  return FOPD_OK;
+}
+
+inline fopd_status launched() { return hipGetLastError() == hipSuccess ? FOPD_OK : FOPD_EHIP; }
+
+// ---- optional per-kernel timing ---------------------------------------------------------
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> start[2], stop[2];
+  size_t used[2] = {0, 0};
+} g_prof;
+
+struct ScopedTimer {
+  int which;
+  hipStream_t s;
+  size_t slot = 0;
+  bool active = false;
+  ScopedTimer(int w, hipStream_t st) : which(w), s(st) {
+    if (!g_prof.on) return;
+    if (g_prof.used[w] == g_prof.start[w].size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+      g_prof.start[w].push_back(a);
+      g_prof.stop[w].push_back(b);
+    }
+    slot = g_prof.used[w]++;
+    active = true;
+    (void)hipEventRecord(g_prof.start[w][slot], s);
+  }
+  ~ScopedTimer() {
+    if (active) (void)hipEventRecord(g_prof.stop[which][slot], s);
+  }
+};
+
+// ---- launch helpers ---------------------------------------------------------------------
+
+fopd_status launch_k1(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                      const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
+                      int64_t* gather_idx, int32_t* flags, hipStream_t s) {
+  if (T == 0) return FOPD_OK;
+  ScopedTimer timer(0, s);
+  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  if (dt == FOPD_BF16)
+    fopd_k1_lse<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids,
+                                                           mask, logp, lse, gather_idx, flags);
+  else
+    fopd_k1_lse<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids,
+                                                          mask, logp, lse, gather_idx, flags);
+  return launched();
+}
+
+fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                      const int32_t* token_ids, const float* lse, const float* logp, const float* coef,
+                      hipStream_t s) {
+  if (T == 0) return FOPD_OK;
+  ScopedTimer timer(1, s);
+  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  if (dt == FOPD_BF16)
+    fopd_k4_grad<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+                                                            token_ids, lse, logp, coef);
+  else
+    fopd_k4_grad<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+                                                           token_ids, lse, logp, coef);
+  return launched();
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fopd_status_string(int status) {
+  switch (status) {
+    case FOPD_OK: return "ok";
+    case FOPD_EINVAL: return "invalid argument (NULL pointer, negative coefficient or inconsistent optional inputs)";
+    case FOPD_ESHAPE: return "invalid shape (T, V, B, ld)";
+    case FOPD_EALIGN: return "matrix base or row pitch is not 16-byte aligned";
+    case FOPD_EDTYPE: return "unsupported element type";
+    case FOPD_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case FOPD_ETOKEN_RANGE: return "token id outside [0, V) (row treated as masked)";
+    case FOPD_ESEGMENTS: return "sequence lengths negative or not covering the rows of the call";
+    case FOPD_ELAG: return "negative lag";
+    case FOPD_EHIP: return "HIP runtime or launch failure";
+    default: return "unknown status";
+  }
+}
+
+size_t fopd_workspace_bytes(int64_t T, int32_t B) { return Workspace(T, B).total; }
+
+fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < 256) return FOPD_EWORKSPACE;
+  fopd_clear_flags<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t*>(workspace));
+  return launched();
+}
+
+fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host) {
+  if (workspace == nullptr) return FOPD_EWORKSPACE;
+  int32_t f = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&f, workspace, sizeof(f), hipMemcpyDeviceToHost, s) != hipSuccess) return FOPD_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return FOPD_EHIP;
+  if (flags_host != nullptr) *flags_host = f;
+  if (f & kFlagToken) return FOPD_ETOKEN_RANGE;
+  if (f & kFlagSegments) return FOPD_ESEGMENTS;
+  if (f & kFlagLag) return FOPD_ELAG;
+  return FOPD_OK;
+}
+
+fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
+                                int64_t* gather_idx, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if (token_ids == nullptr || logp == nullptr || lse == nullptr) return FOPD_EINVAL;
+  st = check_workspace(workspace, workspace_bytes, T, 0);
+  if (st != FOPD_OK) return st;
+  Workspace w(T, 0);
+  return launch_k1(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx,
+                   at<int32_t>(workspace, w.flags), static_cast<hipStream_t>(stream));
+}
+
+fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* teacher_logp,
+                                 const float* teacher_logp_stale, const uint8_t* mask,
+                                 const int32_t* seq_lens, const int32_t* lag, int64_t T, int32_t B,
+                                 fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, float* D_roll,
+                                 float* D_sup, float* ell, float* cover, float* freshness, float* agg,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0 || B <= 0) return FOPD_ESHAPE;
+  if (logp == nullptr || behav_logp == nullptr || teacher_logp == nullptr || seq_lens == nullptr ||
+      lag == nullptr || freshness == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  fopd_status st = check_workspace(workspace, workspace_bytes, T, B);
+  if (st != FOPD_OK) return st;
+  Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = (cu_seqlens != nullptr) ? cu_seqlens : at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  double* f64 = at<double>(workspace, w.fresh64);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, teacher_logp, teacher_logp_stale, mask,
+                                               cu, lag, T, hp, n_train, D_roll, D_sup, ell, cover,
+                                               freshness, f64, nws);
+  if ((st = launched()) != FOPD_OK) return st;
+  if (agg != nullptr) {
+    fopd_aggregate<<<1, kSegThreads, 0, s>>>(f64, nws, cu, B, agg);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  return FOPD_OK;
+}
+
+fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                              const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                              const float* teacher_logp, const float* teacher_logp_stale,
+                              const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                              const float* freshness_in, const int32_t* n_train_in, int64_t row_begin,
+                              const float* lse_in, const float* logp_in, float grad_scale, float* loss,
+                              float* freshness, float* weights, float* logp, void* dlogits,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0 || row_begin < 0) return FOPD_ESHAPE;
+  if (token_ids == nullptr || behav_logp == nullptr || teacher_logp == nullptr || seq_lens == nullptr ||
+      lag == nullptr || loss == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  const bool scored = (freshness_in != nullptr);
+  const bool have_lse = (lse_in != nullptr);
+  if (have_lse != (logp_in != nullptr)) return FOPD_EINVAL;
+  if (!scored && (have_lse || n_train_in != nullptr || row_begin != 0)) return FOPD_EINVAL;
+  if (scored && n_train_in == nullptr && row_begin != 0) return FOPD_EINVAL;
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+
+  Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  double* f64 = at<double>(workspace, w.fresh64);
+  float* coef = at<float>(workspace, w.coef);
+  float* lse_ws = at<float>(workspace, w.lse);
+  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+  double* partials = at<double>(workspace, w.partials);
+
+  // segment offsets; whole-sample calls must cover exactly T rows, chunks at least their range
+  const bool whole = (n_train_in == nullptr);
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, whole ? T : -1, row_begin + T, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+
+  // token log-probabilities: computed here, or taken from an earlier fopd_token_logprobs
+  const float* lse_use = lse_in;
+  const float* logp_use = logp_in;
+  if (!have_lse) {
+    st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, flags, s);
+    if (st != FOPD_OK) return st;
+    lse_use = lse_ws;
+    logp_use = logp_ws;
+  } else if (logp != nullptr && T > 0) {
+    if (hipMemcpyAsync(logp, logp_in, static_cast<size_t>(T) * sizeof(float), hipMemcpyDeviceToDevice, s) !=
+        hipSuccess)
+      return FOPD_EHIP;
+  }
+
+  // per-sample counts and scores
+  const int32_t* n_use = n_train_in;
+  if (whole) {
+    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, teacher_logp, teacher_logp_stale,
+                                                 mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
+                                                 nullptr, nullptr, f64, nws);
+    if ((st = launched()) != FOPD_OK) return st;
+    n_use = nws;
+  }
+  const double* f64_use = scored ? nullptr : f64;
+
+  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
+  if (T > 0) {
+    fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp_use, behav_logp, teacher_logp, mask, cu, n_use, f64_use, freshness_in, T, B, row_begin, hp,
+        grad_scale, coef, partials);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, f64_use, freshness_in, B, hp.xi, loss,
+                                            weights, freshness);
+  if ((st = launched()) != FOPD_OK) return st;
+
+  return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
+}
+
+fopd_status fopd_profile_enable(int on) {
+  g_prof.on = (on != 0);
+  return FOPD_OK;
+}
+
+fopd_status fopd_profile_reset(void) {
+  g_prof.used[0] = g_prof.used[1] = 0;
+  return FOPD_OK;
+}
+
+fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host) {
+  if (which < 0 || which > 1 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
+  double tot = 0.0;
+  for (size_t i = 0; i < g_prof.used[which]; ++i) {
+    if (hipEventSynchronize(g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.start[which][i], g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;
+    tot += ms;
+  }
+  *total_ms_host = tot;
+  *launches_host = static_cast<int64_t>(g_prof.used[which]);
+  return FOPD_OK;
+}
+
+}  // extern "C"

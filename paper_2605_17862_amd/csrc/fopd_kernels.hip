@@ -1,0 +1,561 @@
+// HIP kernels of the f-OPD loss pass for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Two kernels stream the [T, V] logits and are bound by HBM bandwidth:
+//   fopd_k1_lse   one read of the logits  -> lse_t, lp_t            (Eq. "kl-diagnostics" /
+//                                                                     Eq. "sample-aggregated-loss": pi_theta^t(y|x))
+//   fopd_k4_grad  one read + one write    -> c_t (softmax - onehot)  (gradient of Algorithm 1's anchored loss)
+// The remaining kernels touch only O(T) + O(B) data:
+//   fopd_scan_seqlens   segment offsets, argument checks
+//   fopd_segment_stats  per-sample D^roll, D^sup, l_i, coverage, freshness (Eq. "freshness")
+//   fopd_aggregate      buffer means of Sec. 4.2
+//   fopd_coef_loss      per-token gradient coefficient and loss partial sums
+//   fopd_loss_final     loss scalar and weights
+//
+// There is no matrix contraction anywhere on this path, so no MFMA is used.  All reductions
+// run in a fixed order (wavefront shuffles, then LDS), so results are bit-reproducible.
+
+#ifndef FOPD_KERNELS_HIP_
+#define FOPD_KERNELS_HIP_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fopd.h"
+
+namespace fopd {
+
+constexpr int kStreamThreads = 256;   // 4 wavefronts per row in the streaming kernels
+constexpr int kUnroll = 4;            // 16-byte loads in flight per lane and loop trip
+constexpr int kScanThreads = 1024;
+constexpr int kSegThreads = 512;
+enum : int32_t { kFlagToken = 1, kFlagSegments = 2, kFlagLag = 4 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;   // nearest float to log2(e)
+constexpr double kLn2 = 0.6931471805599453094;
+constexpr float kNegInit = -1.0e38f;            // "nothing seen yet" reference (finite on purpose)
+
+template <int DT> struct Elem;
+template <> struct Elem<FOPD_F32> {
+  static constexpr int kPerVec = 4;
+  static constexpr int kBytes = 4;
+};
+template <> struct Elem<FOPD_BF16> {
+  static constexpr int kPerVec = 8;
+  static constexpr int kBytes = 2;
+};
+
+// ---- element access -------------------------------------------------------------------
+
+template <int DT>
+__device__ __forceinline__ void unpack(const u32x4& q, float* x);
+
+template <>
+__device__ __forceinline__ void unpack<FOPD_F32>(const u32x4& q, float* x) {
+  x[0] = __uint_as_float(q.x);
+  x[1] = __uint_as_float(q.y);
+  x[2] = __uint_as_float(q.z);
+  x[3] = __uint_as_float(q.w);
+}
+
+// A bf16 is the upper half of a float: element 2k sits in the low half of word k.
+template <>
+__device__ __forceinline__ void unpack<FOPD_BF16>(const u32x4& q, float* x) {
+  x[0] = __uint_as_float(q.x << 16);
+  x[1] = __uint_as_float(q.x & 0xffff0000u);
+  x[2] = __uint_as_float(q.y << 16);
+  x[3] = __uint_as_float(q.y & 0xffff0000u);
+  x[4] = __uint_as_float(q.z << 16);
+  x[5] = __uint_as_float(q.z & 0xffff0000u);
+  x[6] = __uint_as_float(q.w << 16);
+  x[7] = __uint_as_float(q.w & 0xffff0000u);
+}
+
+template <int DT>
+__device__ __forceinline__ float load_elem(const void* row, int idx);
+template <>
+__device__ __forceinline__ float load_elem<FOPD_F32>(const void* row, int idx) {
+  return static_cast<const float*>(row)[idx];
+}
+template <>
+__device__ __forceinline__ float load_elem<FOPD_BF16>(const void* row, int idx) {
+  return __uint_as_float(static_cast<uint32_t>(static_cast<const uint16_t*>(row)[idx]) << 16);
+}
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// Two floats -> two bf16 in one word, round to nearest even (gfx950 has a packed convert).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, b);
+}
+
+template <int DT>
+__device__ __forceinline__ u32x4 pack(const float* g);
+template <>
+__device__ __forceinline__ u32x4 pack<FOPD_F32>(const float* g) {
+  return u32x4{__float_as_uint(g[0]), __float_as_uint(g[1]), __float_as_uint(g[2]),
+                    __float_as_uint(g[3])};
+}
+template <>
+__device__ __forceinline__ u32x4 pack<FOPD_BF16>(const float* g) {
+  return u32x4{pack_bf16x2(g[0], g[1]), pack_bf16x2(g[2], g[3]), pack_bf16x2(g[4], g[5]),
+                    pack_bf16x2(g[6], g[7])};
+}
+
+template <int DT>
+__device__ __forceinline__ void store_elem(void* row, int idx, float g);
+template <>
+__device__ __forceinline__ void store_elem<FOPD_F32>(void* row, int idx, float g) {
+  static_cast<float*>(row)[idx] = g;
+}
+template <>
+__device__ __forceinline__ void store_elem<FOPD_BF16>(void* row, int idx, float g) {
+  static_cast<uint16_t*>(row)[idx] = static_cast<uint16_t>(pack_bf16x2(g, 0.0f) & 0xffffu);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// ---- wavefront / block reductions (fixed order) ----------------------------------------
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Sum over a block of NT threads; the result is valid in thread 0.  `sh` holds NT/64 doubles.
+template <int NT>
+__device__ __forceinline__ double block_sum(double v, double* sh) {
+  v = wave_sum(v);
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  __syncthreads();
+  if (lane == 0) sh[w] = v;
+  __syncthreads();
+  double tot = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) tot += sh[i];
+  }
+  return tot;
+}
+
+// ---- online log-sum-exp state of one lane ----------------------------------------------
+// The lane holds rL (its running maximum times log2 e, as rounded) and s = sum 2^(x log2e - rL)
+// over the elements it has seen, the sampled token excluded.
+
+template <int N>
+__device__ __forceinline__ void accumulate(const float* x, float& r, float& rL, float& s) {
+  float bm = x[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i) bm = fmaxf(bm, x[i]);
+  if (bm > r) {                       // rare after the first few vectors
+    const float nrL = bm * kLog2e;
+    s *= fast_exp2(rL - nrL);
+    r = bm;
+    rL = nrL;
+  }
+  float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+  for (int i = 0; i < N; i += 2) {
+    a0 += fast_exp2(fmaf(x[i], kLog2e, -rL));
+    if (i + 1 < N) a1 += fast_exp2(fmaf(x[i + 1], kLog2e, -rL));
+  }
+  s += a0 + a1;
+}
+
+}  // namespace
+
+// =========================================================================================
+// K1: streaming log-sum-exp and sampled-token log-probability.  One workgroup per row.
+// =========================================================================================
+
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
+            const uint8_t* mask, float* logp, float* lse, int64_t* gather_idx, int32_t* flags) {
+  constexpr int E = Elem<DT>::kPerVec;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int y = token_ids[t];
+  if (tid == 0 && gather_idx != nullptr) gather_idx[t] = t * ld + static_cast<int64_t>(y);
+  bool live = (mask == nullptr) || (mask[t] != 0);
+  if (live && (y < 0 || y >= V)) {
+    if (tid == 0) atomicOr(flags, kFlagToken);
+    live = false;
+  }
+  if (!live) {
+    if (tid == 0) {
+      logp[t] = 0.f;
+      lse[t] = 0.f;
+    }
+    return;
+  }
+
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  const int nvec = V / E;
+  const int jy = y / E, ey = y % E;
+  const float kNegInf = -__builtin_inff();
+
+  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
+  __shared__ float sh_zy;
+  __shared__ float sh_R[kStreamThreads / 64];
+  __shared__ float sh_S[kStreamThreads / 64];
+
+  int j = tid;
+  for (; j + (U - 1) * kStreamThreads < nvec; j += U * kStreamThreads) {
+    u32x4 q[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(rv + j + u * kStreamThreads);
+    float x[U * E];
+#pragma unroll
+    for (int u = 0; u < U; ++u) unpack<DT>(q[u], x + u * E);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (j + u * kStreamThreads == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          if (e == ey) {
+            sh_zy = x[u * E + e];
+            x[u * E + e] = kNegInf;
+          }
+        }
+      }
+    }
+    accumulate<U * E>(x, r, rL, s);
+  }
+  for (; j < nvec; j += kStreamThreads) {
+    const u32x4 q = __builtin_nontemporal_load(rv + j);
+    float x[E];
+    unpack<DT>(q, x);
+    if (j == jy) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if (e == ey) {
+          sh_zy = x[e];
+          x[e] = kNegInf;
+        }
+      }
+    }
+    accumulate<E>(x, r, rL, s);
+  }
+  {
+    const int idx = nvec * E + tid;   // ragged tail: fewer than E elements
+    if (idx < V) {
+      float x1 = load_elem<DT>(row, idx);
+      if (idx == y) {
+        sh_zy = x1;
+        x1 = kNegInf;
+      }
+      accumulate<1>(&x1, r, rL, s);
+    }
+  }
+
+  // combine the lanes: common reference first, then one rescale per lane
+  const float Rw = wave_max(rL);
+  const float Sw = wave_sum(s * fast_exp2(rL - Rw));
+  const int lane = tid & 63, w = tid >> 6;
+  if (lane == 0) {
+    sh_R[w] = Rw;
+    sh_S[w] = Sw;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float RR = sh_R[0];
+#pragma unroll
+    for (int i = 1; i < kStreamThreads / 64; ++i) RR = fmaxf(RR, sh_R[i]);
+    float SS = 0.f;
+#pragma unroll
+    for (int i = 0; i < kStreamThreads / 64; ++i) SS += sh_S[i] * fast_exp2(sh_R[i] - RR);
+    // Everything below is in log2 units of the scaled logits x * kLog2e.
+    //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
+    //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
+    const float zy = sh_zy;
+    const double zyL = static_cast<double>(zy) * static_cast<double>(kLog2e);
+    const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
+    const double sp = (a2 > 0.0 ? a2 : 0.0) + log1p(exp2(-fabs(a2))) * (1.0 / kLn2);
+    logp[t] = static_cast<float>(-sp * kLn2);
+    lse[t] = static_cast<float>((zyL + sp) * kLn2);
+  }
+}
+
+// =========================================================================================
+// K4: gradient stream.  dlogits[t, v] = c_t * (exp(z - lse_t) - [v == y_t]).  One workgroup
+// per row; rows with c_t == 0 are zero-filled without reading the logits.  `dlogits` may be
+// the same buffer as `logits`: every 16-byte vector is read and written by the same lane.
+// =========================================================================================
+
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k4_grad(const void* logits, void* dlogits, int64_t T, int V, int64_t ld,
+             const int32_t* token_ids, const float* lse, const float* logp, const float* coef) {
+  constexpr int E = Elem<DT>::kPerVec;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float c = coef[t];
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int nvec = V / E;
+
+  if (c == 0.f) {
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    for (int j = tid; j < nvec; j += kStreamThreads) __builtin_nontemporal_store(zero, ov + j);
+    const int idx = nvec * E + tid;
+    if (idx < V) store_elem<DT>(orow, idx, 0.f);
+    return;
+  }
+
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  const int y = token_ids[t];
+  const int jy = y / E, ey = y % E;
+  const float lseL = lse[t] * kLog2e;
+  // c * (p_y - 1) from lp_y, which stays accurate when p_y is close to 1
+  const float gy = c * expm1f(logp[t]);
+
+  int j = tid;
+  for (; j + (U - 1) * kStreamThreads < nvec; j += U * kStreamThreads) {
+    u32x4 q[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(rv + j + u * kStreamThreads);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float x[E];
+      unpack<DT>(q[u], x);
+#pragma unroll
+      for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+      if (j + u * kStreamThreads == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          if (e == ey) x[e] = gy;
+      }
+      __builtin_nontemporal_store(pack<DT>(x), ov + j + u * kStreamThreads);
+    }
+  }
+  for (; j < nvec; j += kStreamThreads) {
+    const u32x4 q = __builtin_nontemporal_load(rv + j);
+    float x[E];
+    unpack<DT>(q, x);
+#pragma unroll
+    for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+    if (j == jy) {
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (e == ey) x[e] = gy;
+    }
+    __builtin_nontemporal_store(pack<DT>(x), ov + j);
+  }
+  {
+    const int idx = nvec * E + tid;
+    if (idx < V) {
+      float g = c * fast_exp2(fmaf(load_elem<DT>(row, idx), kLog2e, -lseL));
+      if (idx == y) g = gy;
+      store_elem<DT>(orow, idx, g);
+    }
+  }
+}
+
+// =========================================================================================
+// Small kernels
+// =========================================================================================
+
+__global__ void fopd_clear_flags(int32_t* flags) {
+  if (threadIdx.x < 4) flags[threadIdx.x] = 0;
+}
+
+// Exclusive scan of seq_lens into cu[0..B] (int64) with one workgroup; checks signs and the
+// total.  need_exact >= 0: the total must equal it; otherwise the total must be >= need_min.
+__global__ void __launch_bounds__(kScanThreads)
+fopd_scan_seqlens(const int32_t* seq_lens, const int32_t* lag, int32_t B, int64_t need_exact,
+                  int64_t need_min, int64_t* cu, int32_t* flags) {
+  __shared__ int64_t sh[kScanThreads];
+  const int tid = threadIdx.x;
+  const int per = (B + kScanThreads - 1) / kScanThreads;
+  const int lo = tid * per;
+  const int hi = min(lo + per, B);
+  int64_t local = 0;
+  bool bad_len = false, bad_lag = false;
+  for (int i = lo; i < hi; ++i) {
+    const int32_t h = seq_lens[i];
+    bad_len |= (h < 0);
+    local += (h < 0 ? 0 : h);
+    if (lag != nullptr) bad_lag |= (lag[i] < 0);
+  }
+  sh[tid] = local;
+  __syncthreads();
+  for (int off = 1; off < kScanThreads; off <<= 1) {   // inclusive scan of the per-thread sums
+    int64_t add = (tid >= off) ? sh[tid - off] : 0;
+    __syncthreads();
+    sh[tid] += add;
+    __syncthreads();
+  }
+  int64_t run = sh[tid] - local;                        // exclusive prefix of this thread
+  for (int i = lo; i < hi; ++i) {
+    cu[i] = run;
+    const int32_t h = seq_lens[i];
+    run += (h < 0 ? 0 : h);
+  }
+  if (tid == kScanThreads - 1) {
+    const int64_t total = sh[tid];
+    cu[B] = total;
+    if (need_exact >= 0 ? (total != need_exact) : (total < need_min)) atomicOr(flags, kFlagSegments);
+  }
+  if (bad_len) atomicOr(flags, kFlagSegments);
+  if (bad_lag) atomicOr(flags, kFlagLag);
+}
+
+// e^d * d - e^d + 1 without cancellation for small d
+__device__ __forceinline__ double kl_term(double d, double* rho_out) {
+  const double e1 = expm1(d);
+  if (rho_out != nullptr) *rho_out = e1 + 1.0;
+  return d * e1 + (d - e1);
+}
+
+// One workgroup per sample: token means over the mask, then the freshness score.
+__global__ void __launch_bounds__(kSegThreads)
+fopd_segment_stats(const float* logp, const float* behav_logp, const float* teacher_logp,
+                   const float* teacher_logp_stale, const uint8_t* mask, const int64_t* cu,
+                   const int32_t* lag, int64_t T, fopd_hparams hp, int32_t* n_train, float* D_roll,
+                   float* D_sup, float* ell, float* cover, float* freshness, double* fresh64,
+                   int32_t* n_train_ws) {
+  __shared__ double sh[kSegThreads / 64];
+  const int i = blockIdx.x;
+  const int64_t a = cu[i];
+  int64_t b = cu[i + 1];
+  if (b > T) b = T;                      // lengths that overrun T are flagged by the scan
+  double sr = 0.0, ss = 0.0, sl = 0.0, cnt = 0.0;
+  for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads) {
+    if (mask != nullptr && mask[t] == 0) continue;
+    const double lp = logp[t], lq = teacher_logp[t];
+    sr += kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
+    if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
+    sl += lp - lq;
+    cnt += 1.0;
+  }
+  const double tr = block_sum<kSegThreads>(sr, sh);
+  const double ts = block_sum<kSegThreads>(ss, sh);
+  const double tl = block_sum<kSegThreads>(sl, sh);
+  const double tn = block_sum<kSegThreads>(cnt, sh);
+  if (threadIdx.x == 0) {
+    const int32_t n = static_cast<int32_t>(tn);
+    const int64_t H = cu[i + 1] - a;
+    double dr = 0.0, ds = 0.0, el = 0.0, cv = 0.0, f = 0.0;
+    if (n > 0) {
+      dr = tr / tn;
+      ds = ts / tn;
+      el = tl / tn;
+      cv = tn / static_cast<double>(H);
+      // k >= 0 mathematically; clamp the rounding noise of an all-fresh sample
+      const double surrogate = static_cast<double>(hp.alpha) * sqrt(dr > 0.0 ? dr : 0.0) +
+                               static_cast<double>(hp.beta) * sqrt(ds > 0.0 ? ds : 0.0);
+      f = exp(-surrogate) / (static_cast<double>(lag[i]) + 1.0);
+    }
+    if (n_train != nullptr) n_train[i] = n;
+    if (n_train_ws != nullptr) n_train_ws[i] = n;
+    if (D_roll != nullptr) D_roll[i] = static_cast<float>(dr);
+    if (D_sup != nullptr) D_sup[i] = static_cast<float>(ds);
+    if (ell != nullptr) ell[i] = static_cast<float>(el);
+    if (cover != nullptr) cover[i] = static_cast<float>(cv);
+    if (freshness != nullptr) freshness[i] = static_cast<float>(f);
+    if (fresh64 != nullptr) fresh64[i] = f;
+  }
+}
+
+// mean_i f_i and mean_i cover_i over all B samples (one workgroup).
+__global__ void __launch_bounds__(kSegThreads)
+fopd_aggregate(const double* fresh64, const int32_t* n_train, const int64_t* cu, int32_t B, float* agg) {
+  __shared__ double sh[kSegThreads / 64];
+  double sf = 0.0, sc = 0.0;
+  for (int i = threadIdx.x; i < B; i += kSegThreads) {
+    sf += fresh64[i];
+    const int64_t H = cu[i + 1] - cu[i];
+    if (n_train[i] > 0) sc += static_cast<double>(n_train[i]) / static_cast<double>(H);
+  }
+  const double tf = block_sum<kSegThreads>(sf, sh);
+  const double tc = block_sum<kSegThreads>(sc, sh);
+  if (threadIdx.x == 0) {
+    agg[0] = static_cast<float>(tf / B);
+    agg[1] = static_cast<float>(tc / B);
+    agg[2] = static_cast<float>(tc / B);
+  }
+}
+
+__device__ __forceinline__ double weight_of(double f, int32_t n, float xi) {
+  if (n <= 0) return 0.0;
+  const double w = f - static_cast<double>(xi);
+  return w > 0.0 ? w : 0.0;
+}
+
+// Per-token gradient coefficient c_t and the block's share of the loss.
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_logp,
+               const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const double* fresh64,
+               const float* fresh32, int64_t T, int32_t B, int64_t row_begin, fopd_hparams hp,
+               float grad_scale, float* coef, double* partials) {
+  __shared__ double sh[kStreamThreads / 64];
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
+  double lt = 0.0;
+  if (t < T) {
+    float c = 0.f;
+    const int64_t gt = row_begin + t;
+    if ((mask == nullptr || mask[t] != 0) && gt < cu[B]) {
+      int lo = 0, hi = B;                      // largest i with cu[i] <= gt  (cu[B] > gt)
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= gt) lo = mid; else hi = mid;
+      }
+      const int32_t n = n_train[lo];
+      const double f = (fresh64 != nullptr) ? fresh64[lo] : static_cast<double>(fresh32[lo]);
+      const double w = weight_of(f, n, hp.xi);
+      if (w > 0.0) {
+        const double lp = logp[t], lq = teacher_logp[t];
+        const double d = lp - static_cast<double>(behav_logp[t]);
+        double rho;
+        const double k = kl_term(d, &rho);
+        const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
+        const double lam = hp.lambda;
+        c = static_cast<float>(static_cast<double>(grad_scale) * pref * ((lq - lp) - lam * rho * d));
+        lt = pref * ((lp - lq) + lam * k);
+      }
+    }
+    coef[t] = c;
+  }
+  const double tot = block_sum<kStreamThreads>(lt, sh);
+  if (threadIdx.x == 0) partials[blockIdx.x] = tot;
+}
+
+// Sums the loss partials in a fixed order; writes the weights and the freshness copy.
+__global__ void __launch_bounds__(kSegThreads)
+fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, const double* fresh64,
+                const float* fresh32, int32_t B, float xi, float* loss, float* weights, float* freshness) {
+  __shared__ double sh[kSegThreads / 64];
+  double s = 0.0;
+  for (int64_t i = threadIdx.x; i < nparts; i += kSegThreads) s += partials[i];
+  const double tot = block_sum<kSegThreads>(s, sh);
+  if (threadIdx.x == 0) loss[0] = static_cast<float>(tot);
+  for (int i = threadIdx.x; i < B; i += kSegThreads) {
+    const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
+    if (weights != nullptr) weights[i] = static_cast<float>(weight_of(f, n_train[i], xi));
+    if (freshness != nullptr) freshness[i] = static_cast<float>(f);
+  }
+}
+
+}  // namespace fopd
+
+#endif  // FOPD_KERNELS_HIP_

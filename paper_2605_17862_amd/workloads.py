@@ -1,0 +1,151 @@
+"""Seeded synthetic inputs for the loss pass (test and benchmark harness, not part of the path).
+
+The five workloads mirror the shapes of buffered rollouts in short-horizon reasoning, multi-turn
+tool use and long-horizon coding-agent training at Qwen-scale vocabulary; they stand in for the
+paper's rollout data, which is not available.  This module does none of the method's
+arithmetic on behalf of the library or of the oracle: both receive the arrays made here.  The
+only model-like step is drawing the sampled token and its reference log-probability with the
+tensor library's own ``log_softmax`` so that the stored log-probabilities are realistic.
+
+Everything is a function of (name, seed, overrides) and of the device's random generator, so
+the same call gives the same arrays on the same device type.
+"""
+
+import numpy as np
+import torch
+
+CONFIGS = {
+    # B samples of fixed length, all trainable
+    "tiny": dict(V=4096, dtype="f32", B=4, len_lo=128, len_hi=128, structure="plain",
+                 logit="normal", sigma=2.0, boost=0, lags=[0, 1, 2, 3], behav_sigma=0.05,
+                 teacher_mu=-0.3, teacher_sigma=0.5, stale_sigma=0.0),
+    "reasoning": dict(V=151936, dtype="bf16", B=64, len_lo=512, len_hi=4096, structure="plain",
+                      logit="normal", sigma=3.0, boost=32, lag_lo=0, lag_hi=4, behav_sigma=0.05,
+                      teacher_mu=-0.2, teacher_sigma=0.4, stale_sigma=0.0),
+    # 8 turns: masked observation span then trainable response span
+    "tooluse": dict(V=151936, dtype="bf16", B=32, structure="turns", turns=8, resp_lo=256, resp_hi=1024,
+                    obs_lo=128, obs_hi=512, logit="normal", sigma=3.0, boost=32, lag_lo=0, lag_hi=8,
+                    behav_sigma=0.05, teacher_mu=-0.2, teacher_sigma=0.4, stale_sigma=0.0),
+    # fixed total length, alternating trainable / masked spans, stale teacher context present
+    "coding": dict(V=151936, dtype="bf16", B=8, structure="spans", total_len=32768, resp_lo=512, resp_hi=2048,
+                   obs_lo=256, obs_hi=1536, logit="normal", sigma=3.0, boost=32, lag_lo=0, lag_hi=16,
+                   behav_sigma=0.05, teacher_mu=-0.2, teacher_sigma=0.4, stale_sigma=0.1, chunk=16384),
+    "largevocab": dict(V=262144, dtype="bf16", B=16, len_lo=16384, len_hi=16384, structure="plain",
+                       logit="student_t3", sigma=2.0, boost=0, lag_split=(8, 32), behav_sigma=0.05,
+                       teacher_mu=-0.2, teacher_sigma=0.4, stale_sigma=0.0),
+}
+
+
+def _structure(cfg, rs):
+    """seq_lens [B], mask [T] (numpy) for the workload's turn structure."""
+    B = cfg["B"]
+    lens, masks = [], []
+    for _ in range(B):
+        if cfg["structure"] == "plain":
+            n = int(rs.randint(cfg["len_lo"], cfg["len_hi"] + 1))
+            m = np.ones(n, dtype=np.uint8)
+        elif cfg["structure"] == "turns":
+            parts = []
+            for _ in range(cfg["turns"]):
+                parts.append(np.zeros(int(rs.randint(cfg["obs_lo"], cfg["obs_hi"] + 1)), dtype=np.uint8))
+                parts.append(np.ones(int(rs.randint(cfg["resp_lo"], cfg["resp_hi"] + 1)), dtype=np.uint8))
+            m = np.concatenate(parts)
+        elif cfg["structure"] == "spans":
+            total = cfg["total_len"]
+            parts, have, train = [], 0, True
+            while have < total:
+                lo, hi = (cfg["resp_lo"], cfg["resp_hi"]) if train else (cfg["obs_lo"], cfg["obs_hi"])
+                n = min(int(rs.randint(lo, hi + 1)), total - have)
+                parts.append(np.full(n, 1 if train else 0, dtype=np.uint8))
+                have += n
+                train = not train
+            m = np.concatenate(parts)
+        else:
+            raise ValueError(cfg["structure"])
+        lens.append(len(m))
+        masks.append(m)
+    return np.array(lens, dtype=np.int32), np.concatenate(masks)
+
+
+def _lags(cfg, rs):
+    B = cfg["B"]
+    if "lags" in cfg:
+        return np.array([cfg["lags"][i % len(cfg["lags"])] for i in range(B)], dtype=np.int32)
+    if "lag_split" in cfg:                       # first half fresh, second half very stale
+        lo, hi = cfg["lag_split"]
+        lag = np.zeros(B, dtype=np.int32)
+        lag[B // 2:] = rs.randint(lo, hi + 1, size=B - B // 2)
+        return lag
+    return rs.randint(cfg["lag_lo"], cfg["lag_hi"] + 1, size=B).astype(np.int32)
+
+
+def _logit_rows(cfg, rows, V, gen, device):
+    """[rows, V] float32 raw logits before rounding to the storage type."""
+    if cfg["logit"] == "normal":
+        z = torch.randn(rows, V, generator=gen, device=device) * cfg["sigma"]
+    elif cfg["logit"] == "student_t3":           # heavy tails: t with 3 degrees of freedom
+        z = torch.randn(rows, V, generator=gen, device=device)
+        chi = torch.zeros(rows, V, device=device)
+        for _ in range(3):
+            chi += torch.randn(rows, V, generator=gen, device=device) ** 2
+        z = z * torch.rsqrt(chi / 3.0) * cfg["sigma"]
+        del chi
+    else:
+        raise ValueError(cfg["logit"])
+    if cfg["boost"] > 0:                         # a few strongly preferred tokens per row
+        idx = torch.randint(0, V, (rows, cfg["boost"]), generator=gen, device=device)
+        z.scatter_(1, idx, z.gather(1, idx) + 8.0)
+    return z
+
+
+def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
+    """Builds one workload.  Returns a dict of tensors on `device` plus plain metadata.
+
+    overrides replace entries of CONFIGS[name] (e.g. B=8, V=4096, len_hi=600) to make the
+    reduced-size replicas the tests use.
+    """
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    V = int(cfg["V"])
+    ld = V if ld is None else int(ld)
+    dtype = torch.float32 if cfg["dtype"] == "f32" else torch.bfloat16
+    rs = np.random.RandomState(seed)
+    seq_lens, mask = _structure(cfg, rs)
+    lag = _lags(cfg, rs)
+    T = int(seq_lens.sum())
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed * 1000003 + 17)
+
+    logits = torch.empty(T, ld, dtype=dtype, device=dev)
+    if ld > V:
+        logits[:, V:] = 0
+    token_ids = torch.empty(T, dtype=torch.int32, device=dev)
+    ref_logp = torch.empty(T, dtype=torch.float32, device=dev)
+    for a in range(0, T, row_block):
+        b = min(a + row_block, T)
+        z = _logit_rows(cfg, b - a, V, gen, dev).to(dtype)
+        logits[a:b, :V] = z
+        zf = z.float()
+        u = torch.rand(b - a, V, generator=gen, device=dev).clamp_(1e-20, 1.0)
+        y = torch.argmax(zf - torch.log(-torch.log(u)), dim=1)      # Gumbel-max draw from softmax(z)
+        token_ids[a:b] = y.to(torch.int32)
+        ref_logp[a:b] = torch.log_softmax(zf, dim=1).gather(1, y[:, None])[:, 0]
+        del z, zf, u, y
+
+    per_tok_lag = torch.from_numpy(np.repeat(lag, seq_lens).astype(np.float32)).to(dev)
+    n1 = torch.randn(T, generator=gen, device=dev)
+    n2 = torch.randn(T, generator=gen, device=dev)
+    n3 = torch.randn(T, generator=gen, device=dev)
+    behav = torch.clamp(ref_logp + cfg["behav_sigma"] * per_tok_lag * n1, max=0.0)
+    teacher = torch.clamp(ref_logp + cfg["teacher_mu"] + cfg["teacher_sigma"] * n2, max=0.0)
+    stale = None
+    if cfg["stale_sigma"] > 0:
+        stale = torch.clamp(teacher + cfg["stale_sigma"] * per_tok_lag * n3, max=0.0)
+
+    return dict(name=name, cfg=cfg, T=T, V=V, ld=ld, B=int(cfg["B"]), dtype=cfg["dtype"],
+                logits=logits, token_ids=token_ids, mask=torch.from_numpy(mask).to(dev),
+                behav_logp=behav, teacher_logp=teacher, teacher_logp_stale=stale,
+                seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
+                seq_lens_host=seq_lens, lag_host=lag, mask_host=mask,
+                n_trainable=int(mask.sum()))

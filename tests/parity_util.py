@@ -1,0 +1,96 @@
+"""Shared pieces of the GPU parity tests: tensor -> float64 adapters for the oracle and the
+tolerances, written out where they are applied.
+
+Tolerances (the arithmetic behind them is in DESIGN.md, section "Tolerances"):
+  integers (cu_seqlens, n_train, gather_idx)      bit-exact
+  logp, lse                                       1e-4 absolute
+  freshness, loss                                 1e-5 relative
+  weights                                         1e-5 * f_i absolute (w = f - xi cancels near the gate)
+  D_roll, D_sup, ell                              2e-5 relative + 1e-9 absolute
+  dlogits                                         2 ulp of the storage type (bf16), 2e-5 relative (f32),
+                                                  plus the floor |p_v - [v=y]| * eps_c(t), where eps_c is
+                                                  the absolute uncertainty of the row coefficient c_t that
+                                                  the tolerances on lp (fp32) and f_i already allow
+"""
+
+import numpy as np
+import torch
+
+from oracle import fopd_oracle as orc
+
+EPS_A = 4e-6        # absolute error allowed on (A_t - lambda rho_t delta_t), from fp32 log-probs
+EPS_F = 1e-5        # relative error allowed on f_i
+
+
+def np64(t):
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        t = t.float()
+    return t.detach().cpu().double().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
+
+
+def oracle_full(w, hp, grad_scale=1.0, want_dlogits=True):
+    """The oracle on a whole (small) workload."""
+    alpha, beta, xi, lam = hp
+    V = w["V"]
+    return orc.fopd_loss_fwd_bwd(np64(w["logits"])[:, :V], np64(w["token_ids"]), np64(w["mask"]),
+                                 np64(w["behav_logp"]), np64(w["teacher_logp"]), np64(w["teacher_logp_stale"]),
+                                 np64(w["seq_lens"]), np64(w["lag"]), alpha, beta, xi, lam, grad_scale,
+                                 out_dtype=w["dtype"], want_dlogits=want_dlogits, ld=w["ld"])
+
+
+def assert_close(name, got, want, rtol=0.0, atol=0.0):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    err = np.abs(got - want)
+    lim = rtol * np.abs(want) + atol
+    bad = err > lim
+    assert not np.any(bad), "%s: %d of %d outside tolerance, worst err %.3e (limit %.3e) at %s" % (
+        name, int(bad.sum()), bad.size, float(err[bad].max()), float(lim[bad][np.argmax(err[bad])]),
+        np.argwhere(bad)[0])
+
+
+def coef_uncertainty(ref, hp, grad_scale, n_samples, mask):
+    """eps_c(t): how far the row coefficient may move given the allowed errors of lp and f."""
+    _, _, xi, lam = hp
+    T = len(ref["coef"])
+    cu, n, f, w = ref["cu_seqlens"], ref["n_train"], ref["freshness"], ref["weights"]
+    out = np.zeros(T)
+    for i in range(len(n)):
+        if n[i] == 0:
+            continue
+        a, b = int(cu[i]), int(cu[i + 1])
+        aeff = np.abs(ref["adv"][a:b] - lam * ref["rho"][a:b] * ref["delta"][a:b])
+        out[a:b] = abs(grad_scale) / (n_samples * int(n[i])) * (w[i] * EPS_A + EPS_F * f[i] * aeff)
+    return out * (np.asarray(mask) != 0)
+
+
+def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label=""):
+    """got_rows: [R, V] float64 values read back from the GPU; the rest are oracle arrays for the
+    same R rows.  Rows whose oracle coefficient is exactly 0 (masked or gated) must be all-zero
+    unless eps_c allows a weight that is barely positive."""
+    R, V = got_rows.shape
+    for r in range(R):
+        exact = orc.dlogits_row(z_rows[r], int(y[r]), lse[r], coef[r])
+        if coef[r] == 0.0 and eps_c[r] == 0.0:
+            assert not np.any(got_rows[r]), "row %s%d must be exactly zero" % (rows_label, r)
+            continue
+        pm = np.exp(z_rows[r] - lse[r])
+        pm[int(y[r])] -= 1.0
+        floor = np.abs(pm) * eps_c[r] + 2.0 ** -126
+        # the float64 oracle forms p_y - 1 by subtraction: its own rounding (lse carries an error of
+        # one float64 ulp of |lse|) is visible when p_y is within 1e-13 of 1
+        u = 4.0 * np.spacing(max(abs(lse[r]), 1.0))
+        floor[int(y[r])] += (abs(coef[r]) + eps_c[r]) * u
+        if store == "bf16":
+            want = orc.round_to_bf16(exact)
+            lim = 2.0 * orc.bf16_ulp(want) + floor
+        else:
+            want = orc.round_to_f32(exact)
+            lim = 2e-5 * np.abs(want) + floor
+        err = np.abs(got_rows[r] - want)
+        bad = err > lim
+        assert not np.any(bad), "dlogits row %s%d: %d elements off, worst %.3e vs limit %.3e at v=%d (c=%.3e)" % (
+            rows_label, r, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]),
+            int(np.argmax(err * bad)), coef[r])

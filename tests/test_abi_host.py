@@ -1,0 +1,128 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares, and turns
+every host-checkable mistake into a status code before anything is launched."""
+
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2605_17862_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+P = ctypes.c_void_p
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "fopd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fopd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = fb.load_library()
+    names = _declared_functions()
+    assert set(names) == set(fb.SYMBOLS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings():
+    seen = set()
+    for code in range(0, 10):
+        s = fb.fopd_status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 10
+    assert fb.fopd_status_string(99) == "unknown status"
+
+
+def test_workspace_bytes():
+    a = fb.fopd_workspace_bytes(512, 4)
+    b = fb.fopd_workspace_bytes(147456, 64)
+    assert a % 256 == 0 and b % 256 == 0 and 0 < a < b
+    assert b >= 147456 * 12                      # three per-row float arrays live there
+    assert fb.fopd_workspace_bytes(0, 1) >= 256
+
+
+def _tok(lib, logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, logp=4096, lse=4096, ws=4096, wsb=1 << 20):
+    return lib.fopd_token_logprobs(P(logits), dt, T, V, ld, P(ids), None, P(logp), P(lse), None,
+                                   P(ws), wsb, None)
+
+
+def test_token_logprobs_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _tok(lib, logits=None) == 1           # EINVAL
+    assert _tok(lib, ids=None) == 1
+    assert _tok(lib, logp=None) == 1
+    assert _tok(lib, dt=2) == 4                  # EDTYPE
+    assert _tok(lib, V=0) == 2                   # ESHAPE
+    assert _tok(lib, T=-1) == 2
+    assert _tok(lib, ld=56) == 2
+    assert _tok(lib, logits=4096 + 8) == 3       # EALIGN
+    assert _tok(lib, V=60, ld=60) == 3           # bf16 pitch 120 B
+    assert _tok(lib, dt=0, V=62, ld=62) == 3     # f32 pitch 248 B
+    assert _tok(lib, ws=None) == 5               # EWORKSPACE
+    assert _tok(lib, ws=4096 + 64) == 5
+    assert _tok(lib, wsb=128) == 5
+
+
+def _loss(lib, **kw):
+    a = dict(logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, mask=None, lb=4096, lq=4096, lqs=None,
+             seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), fin=None, nin=None, row=0,
+             lse=None, lpin=None, g=1.0, loss=4096, f=None, w=None, lp=None, dl=8192, ws=4096, wsb=1 << 20)
+    a.update(kw)
+    return lib.fopd_loss_fwd_bwd(P(a["logits"]), a["dt"], a["T"], a["V"], a["ld"], P(a["ids"]), P(a["mask"]),
+                                 P(a["lb"]), P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"],
+                                 a["hp"], P(a["fin"]), P(a["nin"]), a["row"], P(a["lse"]), P(a["lpin"]),
+                                 a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]), P(a["dl"]),
+                                 P(a["ws"]), a["wsb"], None)
+
+
+def test_loss_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _loss(lib, dl=None) == 1
+    assert _loss(lib, loss=None) == 1
+    assert _loss(lib, lb=None) == 1
+    assert _loss(lib, seq=None) == 1
+    assert _loss(lib, B=0) == 2
+    assert _loss(lib, row=-1) == 2
+    assert _loss(lib, hp=fb.Hparams(-1, 1, 0, 0)) == 1       # alpha, beta >= 0 (Eq. freshness)
+    assert _loss(lib, hp=fb.Hparams(1, float("nan"), 0, 0)) == 1
+    assert _loss(lib, lse=4096) == 1                          # lse_in without logp_in
+    assert _loss(lib, lse=4096, lpin=4096) == 1               # ... and without freshness_in
+    assert _loss(lib, row=16) == 1                            # a chunk needs scores and counts
+    assert _loss(lib, fin=4096, row=16) == 1                  # ... counts still missing
+    assert _loss(lib, dl=8192 + 4) == 3
+    assert _loss(lib, wsb=256) == 5
+
+
+def test_freshness_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+
+    def call(logp=4096, seq=4096, lag=4096, f=4096, T=8, B=2, hp=fb.Hparams(1, 1, 0, 0), ws=4096, wsb=1 << 20):
+        return lib.fopd_freshness_score(P(logp), P(4096), P(4096), None, None, P(seq), P(lag), T, B, hp,
+                                        None, None, None, None, None, None, P(f), None, P(ws), wsb, None)
+
+    assert call(logp=None) == 1
+    assert call(f=None) == 1
+    assert call(lag=None) == 1
+    assert call(B=0) == 2
+    assert call(T=-3) == 2
+    assert call(hp=fb.Hparams(1, -0.5, 0, 0)) == 1
+    assert call(ws=None) == 5
+
+
+def test_profile_read_argument_checks():
+    lib = fb.load_library()
+    ms, n = ctypes.c_double(), ctypes.c_int64()
+    assert lib.fopd_profile_read(2, ctypes.byref(ms), ctypes.byref(n)) == 1
+    assert lib.fopd_profile_read(0, None, ctypes.byref(n)) == 1
+    assert lib.fopd_profile_reset() == 0
+    assert lib.fopd_profile_read(0, ctypes.byref(ms), ctypes.byref(n)) == 0 and n.value == 0
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    with pytest.raises(ValueError):
+        fb._ptr(torch.zeros(4), torch.float32, "x")
