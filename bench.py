@@ -16,9 +16,22 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PMC_SUMMARY = os.path.join(ROOT, "profiles", "fopd_loss_fwd_bwd_reasoning_pmc_hbm_traffic.txt")
 
 
-def cpu_baseline(w, hp, budget_rows=1536):
+def measured_traffic(workload, T, V, key):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE runs,
+    scaled by the copy-kernel calibration), if that summary is for exactly this workload; else None."""
+    try:
+        kv = dict(l.strip().split(": ", 1) for l in open(PMC_SUMMARY) if ": " in l and not l.startswith(" "))
+        if kv.get("workload") == workload and int(kv["T_rows"]) == T and int(kv["V"]) == V:
+            return float(kv[key])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
+def cpu_baseline(w, hp, budget_rows=6000):
     """The float64 oracle, as it stands, on whole samples of the same workload (host cores)."""
     import numpy as np
     from oracle import fopd_oracle as orc
@@ -127,7 +140,8 @@ def main():
                    "storage": w["dtype"], "hparams": {"alpha": hp[0], "beta": hp[1], "xi": hp[2], "lambda": hp[3]},
                    "gated_samples": int((wts == 0).sum()), "call": "fopd_loss_fwd_bwd (all steps fused)"},
         "roofline": {"bound": "hbm", "kernel": "fopd_k4_grad", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(args.workload, T, V, "fopd_k4_grad_traffic_bytes_per_launch"),
                      "bytes_per_launch": k4_bytes, "avg_ms": k4_avg_s * 1e3},
         "kernels": {"fopd_k1_lse": {"avg_ms": k1_avg_s * 1e3, "GB/s": k1_bytes / k1_avg_s / 1e9,
                                     "frac": k1_bytes / k1_avg_s / 1e9 / HBM_PEAK_GBS},

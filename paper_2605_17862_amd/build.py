@@ -7,6 +7,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "lib", "libfopd.so")
+PROBE = os.path.join(PKG, "lib", "hbm_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -15,20 +16,27 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose=False):
-    os.makedirs(os.path.dirname(LIB), exist_ok=True)
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [
-        "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-        "-o", LIB, os.path.join(PKG, "csrc", "fopd_api.hip"),
-    ]
+def _run(cmd, what, verbose):
     res = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "is not a recognized feature for this target"
+    noise = "is not a recognized feature for this target"   # the host pass does not know the flag
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
     if verbose or res.returncode != 0:
         sys.stderr.write(" ".join(cmd) + "\n" + err + "\n")
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed building libfopd.so")
+        raise RuntimeError("hipcc failed building " + what)
+
+
+def build_library(verbose=False):
+    """Compiles the C-ABI library and the bandwidth probe.  Returns the library's path."""
+    os.makedirs(os.path.dirname(LIB), exist_ok=True)
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    _run([hipcc] + HIPCC_FLAGS + [
+        "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
+        "-o", LIB, os.path.join(PKG, "csrc", "fopd_api.hip"),
+    ], "libfopd.so", verbose)
+    probe_flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    _run([hipcc] + probe_flags + ["-o", PROBE, os.path.join(PKG, "csrc", "hbm_probe.hip")],
+         "hbm_probe", verbose)
     return LIB
 
 
