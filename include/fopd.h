@@ -97,7 +97,8 @@ fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* 
  *   mask        [T] uint8 0/1, NULL = all ones
  *   logp        [T] f32 out: lp_t = z_{t,y_t} - lse_t   (0 for masked rows)
  *   lse         [T] f32 out: log sum_v exp(z_{t,v})      (0 for masked rows)
- *   gather_idx  [T] int64 out, NULL to skip: t * ld + y_t for every row, masked or not
+ *   gather_idx  [T] int64 out, NULL to skip: t * ld + y_t for every row, masked or not (an element
+ *               offset from the `logits` pointer of this call)
  *
  * lp_t is formed from the sum over v != y_t, so it keeps full relative accuracy as
  * softmax(z_t)[y_t] approaches 1.

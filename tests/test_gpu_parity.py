@@ -62,7 +62,8 @@ def _compare_everything(w, hp, grad_scale=1.0, staged=True):
         assert np.array_equal(np64(st.cu_seqlens), ref["cu_seqlens"]) and st.cu_seqlens.dtype == torch.int64
         assert np.array_equal(np64(st.n_train), ref["n_train"]) and st.n_train.dtype == torch.int32
         assert torch.equal(st.logp, lp.logp)                         # same kernel, same bits
-        assert_close("lse", np64(st.lse), ref["lse"], atol=1e-4)
+        assert_close("lse", np64(st.lse), ref["lse"],
+                     atol=1e-4 + np.spacing(np.abs(ref["lse"]).astype(np.float32)).astype(np.float64))
         assert_close("D_roll", np64(st.D_roll), ref["D_roll"], rtol=2e-5, atol=1e-9)
         assert_close("D_sup", np64(st.D_sup), ref["D_sup"], rtol=2e-5, atol=1e-9)
         assert_close("ell", np64(st.ell), ref["ell"], rtol=2e-5, atol=1e-9)
@@ -353,6 +354,108 @@ def test_upstream_scale_and_lambda():
 # the benchmark's workload at full size, in the benchmark's launch configuration
 # ---------------------------------------------------------------------------------------
 
+def _oracle_sample(w, i, cu, hp, B, logits=None, block=2048):
+    """Oracle values of one whole sample of a full-size workload, rows pulled to the host in blocks.
+    `logits` replaces w["logits"] (a saved copy) when the call under test ran in place."""
+    V = w["V"]
+    a, b = int(cu[i]), int(cu[i + 1])
+    src = w["logits"] if logits is None else logits
+    off = 0 if logits is None else a
+    mask = w["mask_host"][a:b]
+    y = np64(w["token_ids"][a:b])
+    lse, lpo = np.zeros(b - a), np.zeros(b - a)
+    for s0 in range(a, b, block):
+        e0 = min(s0 + block, b)
+        l, p = orc.token_logprobs(np64(src[s0 - off:e0 - off, :V]), y[s0 - a:e0 - a], mask[s0 - a:e0 - a])
+        lse[s0 - a:e0 - a], lpo[s0 - a:e0 - a] = l, p
+    lb, lq = np64(w["behav_logp"][a:b]), np64(w["teacher_logp"][a:b])
+    lqs = None if w["teacher_logp_stale"] is None else np64(w["teacher_logp_stale"][a:b])
+    delta, rho, adv, k_roll, k_sup = orc.token_terms(lpo, lb, lq, lqs)
+    cu1 = np.array([0, b - a], dtype=np.int64)
+    D_roll, D_sup, ell, cover, n = orc.sample_statistics(lpo, lq, k_roll, k_sup, mask, cu1)
+    f = orc.freshness_score(D_roll, D_sup, w["lag_host"][i:i + 1], n, hp[0], hp[1])
+    wt = orc.freshness_weights(f, hp[2], n)
+    coef = orc.grad_coefficients(delta, rho, adv, mask, cu1, n, wt, hp[3], 1.0, n_samples=B)
+    ref = dict(coef=coef, cu_seqlens=cu1, n_train=n, freshness=f, weights=wt, adv=adv, rho=rho, delta=delta)
+    eps_c = coef_uncertainty(ref, hp, 1.0, B, mask)
+    return dict(a=a, b=b, y=y, mask=mask, lse=lse, logp=lpo, D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover,
+                n=n, f=f, w=wt, coef=coef, eps_c=eps_c)
+
+
+def _check_sample(o, i, logp, lse, freshness, weights, st):
+    live = o["mask"] != 0
+    assert_close("logp sample %d" % i, np64(logp[o["a"]:o["b"]]), o["logp"], atol=1e-4)
+    # lse is stored in fp32: one fp32 spacing at its magnitude on top of the 1e-4
+    assert_close("lse sample %d" % i, np64(lse[o["a"]:o["b"]]), o["lse"],
+                 atol=1e-4 + np.spacing(np.abs(o["lse"]).astype(np.float32)).astype(np.float64))
+    assert not np.any(np64(logp[o["a"]:o["b"]])[~live])
+    f = o["f"][0]
+    assert abs(float(freshness[i]) - f) <= 1e-5 * f, (i, float(freshness[i]), f)
+    assert abs(float(weights[i]) - o["w"][0]) <= 1e-5 * f
+    if st is not None:
+        assert_close("D_roll %d" % i, np64(st.D_roll[i:i + 1]), o["D_roll"], rtol=2e-5, atol=1e-9)
+        assert_close("D_sup %d" % i, np64(st.D_sup[i:i + 1]), o["D_sup"], rtol=2e-5, atol=1e-9)
+        assert_close("ell %d" % i, np64(st.ell[i:i + 1]), o["ell"], rtol=2e-5, atol=1e-9)
+        assert_close("cover %d" % i, np64(st.cover[i:i + 1]), o["cover"], rtol=1e-6)
+        assert int(st.n_train[i]) == int(o["n"][0])
+
+
+def _check_sample_grad_rows(o, i, w, get_rows, picks, logits=None):
+    """picks: row numbers inside the sample; get_rows(global_rows) returns the GPU gradient rows."""
+    V = w["V"]
+    src = w["logits"] if logits is None else logits
+    off = 0 if logits is None else o["a"]
+    idx = torch.from_numpy(np.asarray(picks) + o["a"] - off).to(DEV)
+    z = np64(src[idx][:, :V])
+    got = np64(get_rows(np.asarray(picks) + o["a"]))[:, :V]
+    check_grad_rows(got, z, o["y"][picks], o["lse"][picks], o["coef"][picks], o["eps_c"][picks], w["dtype"],
+                    rows_label="s%d:" % i)
+
+
+def _integers_everywhere(w, st, chunk=None):
+    """cu_seqlens, n_train and gather_idx of every sample and row, bit for bit.  gather_idx is an offset
+    from the matrix pointer of the call that wrote it, so with chunked calls it restarts per chunk."""
+    cu = orc.segment_offsets(w["seq_lens_host"])
+    assert np.array_equal(np64(st.cu_seqlens), cu)
+    assert np.array_equal(np64(st.n_train), orc.trainable_counts(w["mask_host"], cu))
+    ids = np64(w["token_ids"])
+    if chunk is None:
+        want = orc.gather_index(ids, w["ld"])
+    else:
+        want = np.concatenate([orc.gather_index(ids[a:a + chunk], w["ld"]) for a in range(0, w["T"], chunk)])
+    assert np.array_equal(np64(st.gather_idx), want)
+    return cu
+
+
+def _row_properties(w, cu, dlogits_row, weights, n_rows=48, seed=1, expect_nonzero=True):
+    """Properties that hold at any size: rows of gated or masked tokens are exactly zero, the others
+    sum to ~0 (softmax minus one-hot) and are non-zero at the sampled token."""
+    g = torch.Generator().manual_seed(seed)
+    w_host = np64(weights)
+    for t in torch.randint(0, w["T"], (n_rows,), generator=g).tolist():
+        row = dlogits_row(t).double()
+        i = int(np.searchsorted(cu, t, side="right") - 1)
+        if w_host[i] == 0.0 or w["mask_host"][t] == 0:
+            assert not bool(row.any()), "row %d must be zero" % t
+        else:
+            assert abs(float(row.sum())) <= 2.0 ** -7 * float(row.abs().sum()) + 1e-30
+            if expect_nonzero:         # not with heavy tails: c (p_y - 1) underflows when p_y -> 1
+                assert float(row[int(w["token_ids"][t])]) != 0.0
+
+
+def _pick_samples(seq, min_samples, min_rows, prefer=None):
+    order = list(np.argsort(seq, kind="stable"))
+    if prefer:
+        order = list(prefer) + [i for i in order if i not in prefer]
+    chosen, rows = [], 0
+    for i in order:
+        chosen.append(int(i))
+        rows += int(seq[i])
+        if len(chosen) >= min_samples and rows >= min_rows:
+            break
+    return chosen, rows
+
+
 def test_reasoning_full_size_sampled_parity():
     _say("reasoning at full size (B=64, V=151936): generating ...")
     w = wl.generate("reasoning", DEV, seed=0)
@@ -365,60 +468,134 @@ def test_reasoning_full_size_sampled_parity():
     st.token_logprobs(w)
     st.freshness_score(w, HP)
     _sync_ok(st)
-    seq, lag, mask = w["seq_lens_host"], w["lag_host"], w["mask_host"]
-    cu = orc.segment_offsets(seq)
-    # integers, all samples and rows
-    assert np.array_equal(np64(st.cu_seqlens), cu)
-    assert np.array_equal(np64(st.n_train), orc.trainable_counts(mask, cu))
-    assert np.array_equal(np64(st.gather_idx), orc.gather_index(np64(w["token_ids"]), w["ld"]))
+    cu = _integers_everywhere(w, st)
     assert torch.equal(st.logp, lp.logp) and torch.equal(st.freshness, lp.freshness)
     # whole samples for the oracle: shortest first until at least 4 samples and 8k rows
-    order = np.argsort(seq, kind="stable")
-    chosen, rows = [], 0
-    for i in order:
-        chosen.append(int(i))
-        rows += int(seq[i])
-        if len(chosen) >= 4 and rows >= 8192:
-            break
+    chosen, rows = _pick_samples(w["seq_lens_host"], 4, 8192)
     _say("oracle on samples %s (%d rows)" % (chosen, rows))
-    f_gpu = np64(lp.freshness)
-    w_gpu = np64(lp.weights)
     for i in chosen:
-        a, b = int(cu[i]), int(cu[i + 1])
-        z = np64(w["logits"][a:b])
-        y = np64(w["token_ids"][a:b])
-        lse, lpo = orc.token_logprobs(z, y, mask[a:b])
-        assert_close("logp sample %d" % i, np64(lp.logp[a:b]), lpo, atol=1e-4)
-        assert_close("lse sample %d" % i, np64(st.lse[a:b]), lse, atol=1e-4)
-        lb, lq = np64(w["behav_logp"][a:b]), np64(w["teacher_logp"][a:b])
-        delta, rho, adv, k_roll, k_sup = orc.token_terms(lpo, lb, lq, None)
-        cu1 = np.array([0, b - a], dtype=np.int64)
-        D_roll, D_sup, ell, cover, n = orc.sample_statistics(lpo, lq, k_roll, k_sup, mask[a:b], cu1)
-        f = orc.freshness_score(D_roll, D_sup, lag[i:i + 1], n, HP[0], HP[1])
-        wt = orc.freshness_weights(f, HP[2], n)
-        assert abs(f_gpu[i] - f[0]) <= 1e-5 * f[0], (i, f_gpu[i], f[0])
-        assert abs(w_gpu[i] - wt[0]) <= 1e-5 * f[0]
-        assert_close("D_roll %d" % i, np64(st.D_roll[i:i + 1]), D_roll, rtol=2e-5, atol=1e-9)
-        assert_close("ell %d" % i, np64(st.ell[i:i + 1]), ell, rtol=2e-5, atol=1e-9)
-        coef = orc.grad_coefficients(delta, rho, adv, mask[a:b], cu1, n, wt, HP[3], 1.0, n_samples=B)
-        ref = dict(coef=coef, cu_seqlens=cu1, n_train=n, freshness=f, weights=wt, adv=adv, rho=rho, delta=delta)
-        eps_c = coef_uncertainty(ref, HP, 1.0, B, mask[a:b])
-        pick = np.unique(np.linspace(0, b - a - 1, 6).astype(int))
-        check_grad_rows(np64(lp.dlogits[a:b][torch.from_numpy(pick).to(DEV)]), z[pick], y[pick], lse[pick], coef[pick], eps_c[pick],
-                        "bf16", rows_label="s%d:" % i)
-        _say("sample %d ok (f=%.6f, w=%.6f)" % (i, f[0], wt[0]))
-    # properties that hold at any size
-    # (1) the loss is the weighted mean of the per-sample terms the library itself reports
+        o = _oracle_sample(w, i, cu, HP, B)
+        _check_sample(o, i, lp.logp, st.lse, lp.freshness, lp.weights, st)
+        picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 6).astype(int))
+        _check_sample_grad_rows(o, i, w, lambda rows_: lp.dlogits[torch.from_numpy(rows_).to(DEV)], picks)
+        _say("sample %d ok (f=%.6f, w=%.6f)" % (i, o["f"][0], o["w"][0]))
+    # the loss is the weighted mean of the per-sample terms the library itself reports
+    w_gpu = np64(lp.weights)
     Ls = float(np.sum(w_gpu * (np64(st.ell) + HP[3] * np64(st.D_roll))) / B)
     assert abs(float(lp.loss) - Ls) <= 2e-6 * abs(Ls)
-    # (2) gradient rows sum to ~0 and are exactly zero for gated samples (sampled rows)
-    g = torch.Generator().manual_seed(1)
-    for t in torch.randint(0, T, (48,), generator=g).tolist():
-        row = lp.dlogits[t].double()
-        i = int(np.searchsorted(cu, t, side="right") - 1)
-        if w_gpu[i] == 0.0:
-            assert not bool(row.any())
-        else:
-            assert abs(float(row.sum())) <= 2.0 ** -7 * float(row.abs().sum()) + 1e-30
-            assert float(row[int(w["token_ids"][t])]) * float(row.abs().max()) != 0.0
-    assert_close("agg f", float(st.agg[0]), float(np.mean(f_gpu)), rtol=1e-6)
+    _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights)
+    assert_close("agg f", float(st.agg[0]), float(np.mean(np64(lp.freshness))), rtol=1e-6)
+
+
+def test_tooluse_full_size_sampled_parity():
+    _say("tooluse at full size (B=32 x 8 turns, V=151936, masked observation spans): generating ...")
+    w = wl.generate("tooluse", DEV, seed=0)
+    T, V, B = w["T"], w["V"], w["B"]
+    _say("T=%d rows (%d trainable), logits %.1f GB; fused call, gradient in place" % (T, w["n_trainable"], T * V * 2 / 1e9))
+    chosen, rows = _pick_samples(w["seq_lens_host"], 2, 8192)
+    cu0 = orc.segment_offsets(w["seq_lens_host"])
+    saved = {i: w["logits"][int(cu0[i]):int(cu0[i + 1])].clone() for i in chosen}
+    st = _pass_for(w, alloc_dlogits=False)
+    st.token_logprobs(w)
+    st.freshness_score(w, HP)
+    _sync_ok(st)
+    cu = _integers_everywhere(w, st)
+    lp = _pass_for(w, alloc_dlogits=False)
+    lp.loss_fwd_bwd(w, HP, dlogits=w["logits"])                  # in place: 75 GB instead of 150 GB
+    _sync_ok(lp)
+    assert torch.equal(st.logp, lp.logp) and torch.equal(st.freshness, lp.freshness)
+    _say("oracle on samples %s (%d rows)" % (chosen, rows))
+    for i in chosen:
+        o = _oracle_sample(w, i, cu, HP, B, logits=saved[i])
+        _check_sample(o, i, lp.logp, st.lse, lp.freshness, lp.weights, st)
+        live = np.flatnonzero(o["mask"])
+        dead = np.flatnonzero(o["mask"] == 0)
+        picks = np.concatenate([live[np.linspace(0, len(live) - 1, 4).astype(int)], dead[:2]])
+        _check_sample_grad_rows(o, i, w, lambda rows_: w["logits"][torch.from_numpy(rows_).to(DEV)], picks,
+                                logits=saved[i])
+        _say("sample %d ok (f=%.6f, w=%.6f, n=%d of %d)" % (i, o["f"][0], o["w"][0], o["n"][0], o["b"] - o["a"]))
+    w_gpu = np64(lp.weights)
+    Ls = float(np.sum(w_gpu * (np64(st.ell) + HP[3] * np64(st.D_roll))) / B)
+    assert abs(float(lp.loss) - Ls) <= 2e-6 * abs(Ls)
+    _row_properties(w, cu, lambda t: w["logits"][t], lp.weights)
+    assert_close("agg cover", float(st.agg[1]), float(np.mean(np64(st.cover))), rtol=1e-6)
+
+
+def test_coding_full_size_chunked_flow():
+    _say("coding at full size (B=8 x 32768, V=151936), processed in chunks of 16384 rows: generating ...")
+    w = wl.generate("coding", DEV, seed=0)
+    T, V, B = w["T"], w["V"], w["B"]
+    chunk = w["cfg"]["chunk"]
+    assert T == 262144 and chunk == 16384
+    full = _pass_for(w, alloc_dlogits=False)
+    for a in range(0, T, chunk):                                  # phase 1: log-probs per chunk
+        full.token_logprobs(w, rows=(a, a + chunk))
+    full.freshness_score(w, HP)                                   # phase 2: scores over the O(T) arrays
+    _sync_ok(full)
+    cu = _integers_everywhere(w, full, chunk=chunk)
+    lagh = w["lag_host"]                                          # smallest non-zero lag: D_sup > 0, not gated
+    i = int(np.argmin(np.where(lagh > 0, lagh, 1 << 30)))
+    _say("oracle on sample %d (%d rows, lag %d)" % (i, w["seq_lens_host"][i], w["lag_host"][i]))
+    o = _oracle_sample(w, i, cu, HP, B)
+    wts = torch.empty(B, device=DEV)
+    _check_sample(o, i, full.logp, full.lse, full.freshness,
+                  torch.clamp(full.freshness - HP[2], min=0.0), full)
+    assert o["D_sup"][0] > 0
+    live = np.flatnonzero(o["mask"])
+    picks = np.concatenate([live[np.linspace(0, len(live) - 1, 6).astype(int)], np.flatnonzero(o["mask"] == 0)[:2]])
+    picks_global = set((picks + o["a"]).tolist())
+    grads = {}
+    dl = torch.empty(chunk, w["ld"], dtype=torch.bfloat16, device=DEV)
+    total = 0.0
+    part = torch.zeros(1, device=DEV)
+    for a in range(0, T, chunk):                                  # phase 3: gradient per chunk
+        b = a + chunk
+        fb.fopd_loss_fwd_bwd(w["logits"][a:b], full.dt, chunk, V, w["ld"], w["token_ids"][a:b], w["mask"][a:b],
+                             w["behav_logp"][a:b], w["teacher_logp"][a:b], w["teacher_logp_stale"][a:b],
+                             w["seq_lens"], w["lag"], B, HP, full.freshness, full.n_train, a, full.lse[a:b],
+                             full.logp[a:b], 1.0, part, None, wts, None, dl, full.workspace)
+        total += float(part)
+        for t in picks_global:
+            if a <= t < b:
+                grads[t] = dl[t - a].clone()
+        if a == 0:
+            _row_properties(dict(w, T=chunk), cu, lambda t: dl[t], wts, n_rows=16)
+    _sync_ok(full)
+    _check_sample_grad_rows(o, i, w, lambda rows_: torch.stack([grads[int(t)] for t in rows_]), picks)
+    w_gpu = np64(wts)
+    assert np.any(w_gpu == 0.0) and np.any(w_gpu > 0.0)           # lags up to 16: some samples gated
+    Ls = float(np.sum(w_gpu * (np64(full.ell) + HP[3] * np64(full.D_roll))) / B)
+    assert abs(total - Ls) <= 1e-5 * abs(Ls), (total, Ls)        # chunk losses add up to L
+
+
+def test_largevocab_full_size_in_place():
+    _say("largevocab at full size (B=16 x 16384, V=262144, heavy-tailed logits): generating ...")
+    w = wl.generate("largevocab", DEV, seed=0)
+    T, V, B = w["T"], w["V"], w["B"]
+    _say("logits %.1f GB; gradient written in place" % (T * V * 2 / 1e9))
+    chosen = [0, B - 1]                                           # one fresh sample, one very stale one
+    cu0 = orc.segment_offsets(w["seq_lens_host"])
+    saved = {i: w["logits"][int(cu0[i]):int(cu0[i + 1])].clone() for i in chosen}
+    st = _pass_for(w, alloc_dlogits=False)
+    st.token_logprobs(w)
+    st.freshness_score(w, HP)
+    _sync_ok(st)
+    cu = _integers_everywhere(w, st)
+    lp = _pass_for(w, alloc_dlogits=False)
+    lp.loss_fwd_bwd(w, HP, dlogits=w["logits"])
+    _sync_ok(lp)
+    assert torch.equal(st.logp, lp.logp) and torch.equal(st.freshness, lp.freshness)
+    for i in chosen:
+        o = _oracle_sample(w, i, cu, HP, B, logits=saved[i], block=1024)
+        # heavy tails: most sampled tokens have p_y within 1e-13 of 1, where z_y - lse cancels in float64;
+        # compare log-probs with an absolute tolerance only (the relative check is in test_extreme_rows)
+        _check_sample(o, i, lp.logp, st.lse, lp.freshness, lp.weights, st)
+        picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 5).astype(int))
+        _check_sample_grad_rows(o, i, w, lambda rows_: w["logits"][torch.from_numpy(rows_).to(DEV)], picks,
+                                logits=saved[i])
+        _say("sample %d ok (lag %d, f=%.6f, w=%.6f)" % (i, w["lag_host"][i], o["f"][0], o["w"][0]))
+    assert float(lp.weights[0]) > 0.0 and float(lp.weights[B - 1]) == 0.0
+    _row_properties(w, cu, lambda t: w["logits"][t], lp.weights, n_rows=32, expect_nonzero=False)
+    w_gpu = np64(lp.weights)
+    Ls = float(np.sum(w_gpu * (np64(st.ell) + HP[3] * np64(st.D_roll))) / B)
+    assert abs(float(lp.loss) - Ls) <= 2e-6 * abs(Ls)
