@@ -145,6 +145,8 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp,
  *                          [B] count array of fopd_freshness_score, or NULL when the call
  *                          covers whole samples (row_begin == 0, sum(seq_lens) == T) and the
  *                          counts are to be taken from `mask`.
+ *                          Without lse_in the logits are still read from HBM only once: one kernel
+ *                          makes both passes over each row while it is cache-resident.
  *   lse_in / logp_in     : both or neither.  When given ([T] f32, the outputs of
  *                          fopd_token_logprobs for these rows) the logits are read only by the
  *                          gradient pass.  Requires freshness_in.
@@ -171,10 +173,20 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Launch-shape options (process-wide, not thread-safe; set before the calls they affect):
+ *   "k14_threads"      256, 512 or 1024 lanes per row in the kernel that makes both passes over a row
+ *                      (used when freshness_in is given without lse_in); default 256
+ *   "k14_rows_per_cu"  1..8 rows in flight per compute unit in that kernel; default 6 (the second
+ *                      pass over a row is served from cache only while few rows are in flight).
+ * Returns FOPD_EINVAL for an unknown name or a value outside the stated set.
+ */
+fopd_status fopd_set_option(const char* name, int value);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
  * is bracketed by HIP events on the launch stream.  Not thread-safe; meant for a single
  * benchmarking thread.  fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
- *   which: 0 = log-sum-exp pass, 1 = gradient pass.
+ *   which: 0 = log-sum-exp pass, 1 = gradient pass, 2 = both passes in one kernel (scores supplied).
  */
 fopd_status fopd_profile_enable(int on);
 fopd_status fopd_profile_reset(void);

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     fopd_profile_enable,
     fopd_profile_read,
     fopd_profile_reset,
+    fopd_set_option,
     fopd_status_string,
     fopd_token_logprobs,
     fopd_workspace_bytes,

@@ -18,7 +18,7 @@ FOPD_BF16 = 1
 SYMBOLS = (
     "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
-    "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read",
+    "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
 )
 
 
@@ -67,6 +67,8 @@ def load_library():
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                       vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_set_option.restype = ctypes.c_int
+    lib.fopd_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.fopd_profile_enable.restype = ctypes.c_int
     lib.fopd_profile_enable.argtypes = [ctypes.c_int]
     lib.fopd_profile_reset.restype = ctypes.c_int
@@ -185,6 +187,10 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
     _check(st, "fopd_loss_fwd_bwd")
+
+
+def fopd_set_option(name, value):
+    _check(load_library().fopd_set_option(name.encode(), int(value)), "fopd_set_option")
 
 
 def fopd_profile_enable(on):

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <string>
 #include <vector>
 
 #include "fopd.h"
@@ -34,7 +35,7 @@ struct Workspace {
     coef = take(t * sizeof(float));
     lse = take(t * sizeof(float));
     logp = take(t * sizeof(float));
-    partials = take(((t + kStreamThreads - 1) / kStreamThreads + 1) * sizeof(double));
+    partials = take((t + 1) * sizeof(double));     // per-block or per-row loss terms
     total = off;
   }
 };
@@ -66,8 +67,8 @@ inline fopd_status launched() { return hipGetLastError() == hipSuccess ? FOPD_OK
 // ---- optional per-kernel timing ---------------------------------------------------------
 struct Profiler {
   bool on = false;
-  std::vector<hipEvent_t> start[2], stop[2];
-  size_t used[2] = {0, 0};
+  std::vector<hipEvent_t> start[3], stop[3];
+  size_t used[3] = {0, 0, 0};
 } g_prof;
 
 struct ScopedTimer {
@@ -91,6 +92,14 @@ struct ScopedTimer {
     if (active) (void)hipEventRecord(g_prof.stop[which][slot], s);
   }
 };
+
+// ---- options ------------------------------------------------------------------------------
+struct Options {
+  int k14_threads = 256;          // lanes per row in the two-pass-per-row kernel
+  int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
+} g_opt;
+
+constexpr size_t kLdsPerCu = 160 * 1024;
 
 // ---- launch helpers ---------------------------------------------------------------------
 
@@ -122,6 +131,45 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
     fopd_k4_grad<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
                                                            token_ids, lse, logp, coef);
   return launched();
+}
+
+template <int DT, int NT>
+fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V, int64_t ld,
+                         const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
+                         const int64_t* cu, const int32_t* n_train, const float* fresh32, int32_t B,
+                         int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss,
+                         int32_t* flags, hipStream_t s) {
+  auto kern = fopd_k14_fused<DT, NT, kUnroll>;
+  // dynamic LDS is requested only to cap the workgroups resident per compute unit
+  size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          static_cast<int>(pad)) != hipSuccess)
+    return FOPD_EHIP;
+  kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+                                                            token_ids, mask, lb, lq, cu, n_train, fresh32, B,
+                                                            row_begin, hp, grad_scale, logp, row_loss, flags);
+  return launched();
+}
+
+fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                       const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
+                       const int64_t* cu, const int32_t* n_train, const float* fresh32, int32_t B,
+                       int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss,
+                       int32_t* flags, hipStream_t s) {
+  if (T == 0) return FOPD_OK;
+  ScopedTimer timer(2, s);
+#define FOPD_K14_CASE(DTV, NTV)                                                                             \
+  return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, token_ids, mask, lb, lq, cu, n_train, fresh32, B, \
+                                row_begin, hp, grad_scale, logp, row_loss, flags, s)
+  if (dt == FOPD_BF16) {
+    if (g_opt.k14_threads == 512) FOPD_K14_CASE(FOPD_BF16, 512);
+    if (g_opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_BF16, 1024);
+    FOPD_K14_CASE(FOPD_BF16, 256);
+  }
+  if (g_opt.k14_threads == 512) FOPD_K14_CASE(FOPD_F32, 512);
+  if (g_opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_F32, 1024);
+  FOPD_K14_CASE(FOPD_F32, 256);
+#undef FOPD_K14_CASE
 }
 
 }  // namespace
@@ -251,6 +299,23 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, whole ? T : -1, row_begin + T, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
 
+  // Scores supplied, log-probs not: both passes over each row run in one kernel, and the second
+  // read of the row comes out of the Infinity Cache.
+  if (scored && !have_lse) {
+    const int32_t* n_use = n_train_in;
+    if (whole) {
+      fopd_count_train<<<B, kSegThreads, 0, s>>>(mask, cu, T, nws);
+      if ((st = launched()) != FOPD_OK) return st;
+      n_use = nws;
+    }
+    st = launch_k14(logits, dlogits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, cu, n_use,
+                    freshness_in, B, row_begin, hp, grad_scale, logp, partials, flags, s);
+    if (st != FOPD_OK) return st;
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, T, n_use, nullptr, freshness_in, B, hp.xi, loss, weights,
+                                              freshness);
+    return launched();
+  }
+
   // token log-probabilities: computed here, or taken from an earlier fopd_token_logprobs
   const float* lse_use = lse_in;
   const float* logp_use = logp_in;
@@ -290,18 +355,34 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
 }
 
+fopd_status fopd_set_option(const char* name, int value) {
+  if (name == nullptr) return FOPD_EINVAL;
+  const std::string key(name);
+  if (key == "k14_threads") {
+    if (value != 256 && value != 512 && value != 1024) return FOPD_EINVAL;
+    g_opt.k14_threads = value;
+    return FOPD_OK;
+  }
+  if (key == "k14_rows_per_cu") {
+    if (value < 1 || value > 8) return FOPD_EINVAL;
+    g_opt.k14_rows_per_cu = value;
+    return FOPD_OK;
+  }
+  return FOPD_EINVAL;
+}
+
 fopd_status fopd_profile_enable(int on) {
   g_prof.on = (on != 0);
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_reset(void) {
-  g_prof.used[0] = g_prof.used[1] = 0;
+  g_prof.used[0] = g_prof.used[1] = g_prof.used[2] = 0;
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host) {
-  if (which < 0 || which > 1 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
+  if (which < 0 || which > 2 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
   double tot = 0.0;
   for (size_t i = 0; i < g_prof.used[which]; ++i) {
     if (hipEventSynchronize(g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;

@@ -10,6 +10,8 @@
 //   fopd_aggregate      buffer means of Sec. 4.2
 //   fopd_coef_loss      per-token gradient coefficient and loss partial sums
 //   fopd_loss_final     loss scalar and weights
+// A third streaming kernel, fopd_k14_fused, does both passes over a row in one workgroup when the
+// freshness scores are supplied by the caller (second loop of Algorithm 1 on its own).
 //
 // There is no matrix contraction anywhere on this path, so no MFMA is used.  All reductions
 // run in a fixed order (wavefront shuffles, then LDS), so results are bit-reproducible.
@@ -179,60 +181,44 @@ __device__ __forceinline__ void accumulate(const float* x, float& r, float& rL, 
   s += a0 + a1;
 }
 
-}  // namespace
+// ---- row routines shared by the streaming kernels ----------------------------------------
+// NT lanes walk one row of V elements in 16-byte vectors, U vectors in flight per lane and trip;
+// vector j of a trip belongs to lane j % NT, so a wavefront instruction touches 1 KB contiguous.
+// CACHED selects ordinary loads (lines stay in L2 / Infinity Cache for a second pass over the
+// same row) instead of non-temporal ones.
 
-// =========================================================================================
-// K1: streaming log-sum-exp and sampled-token log-probability.  One workgroup per row.
-// =========================================================================================
+template <bool CACHED>
+__device__ __forceinline__ u32x4 load_vec(const u32x4* p) {
+  if (CACHED) return *p;
+  return __builtin_nontemporal_load(p);
+}
 
-template <int DT, int U>
-__global__ void __launch_bounds__(kStreamThreads)
-fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
-            const uint8_t* mask, float* logp, float* lse, int64_t* gather_idx, int32_t* flags) {
+// Pass over a row for the log-sum-exp: updates the lane's (r, rL, s); the lane that meets the
+// sampled token y stores its value to *zy_out (LDS) and leaves it out of the sum.
+template <int DT, int NT, int U, bool CACHED>
+__device__ __forceinline__ void row_lse(const char* row, int V, int y, float& r, float& rL, float& s,
+                                        float* zy_out) {
   constexpr int E = Elem<DT>::kPerVec;
-  const int64_t t = blockIdx.x;
-  const int tid = threadIdx.x;
-  const int y = token_ids[t];
-  if (tid == 0 && gather_idx != nullptr) gather_idx[t] = t * ld + static_cast<int64_t>(y);
-  bool live = (mask == nullptr) || (mask[t] != 0);
-  if (live && (y < 0 || y >= V)) {
-    if (tid == 0) atomicOr(flags, kFlagToken);
-    live = false;
-  }
-  if (!live) {
-    if (tid == 0) {
-      logp[t] = 0.f;
-      lse[t] = 0.f;
-    }
-    return;
-  }
-
-  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
   const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  const int tid = threadIdx.x;
   const int nvec = V / E;
   const int jy = y / E, ey = y % E;
   const float kNegInf = -__builtin_inff();
-
-  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
-  __shared__ float sh_zy;
-  __shared__ float sh_R[kStreamThreads / 64];
-  __shared__ float sh_S[kStreamThreads / 64];
-
   int j = tid;
-  for (; j + (U - 1) * kStreamThreads < nvec; j += U * kStreamThreads) {
+  for (; j + (U - 1) * NT < nvec; j += U * NT) {
     u32x4 q[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(rv + j + u * kStreamThreads);
+    for (int u = 0; u < U; ++u) q[u] = load_vec<CACHED>(rv + j + u * NT);
     float x[U * E];
 #pragma unroll
     for (int u = 0; u < U; ++u) unpack<DT>(q[u], x + u * E);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if (j + u * kStreamThreads == jy) {
+      if (j + u * NT == jy) {
 #pragma unroll
         for (int e = 0; e < E; ++e) {
           if (e == ey) {
-            sh_zy = x[u * E + e];
+            *zy_out = x[u * E + e];
             x[u * E + e] = kNegInf;
           }
         }
@@ -240,15 +226,15 @@ fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* tok
     }
     accumulate<U * E>(x, r, rL, s);
   }
-  for (; j < nvec; j += kStreamThreads) {
-    const u32x4 q = __builtin_nontemporal_load(rv + j);
+  for (; j < nvec; j += NT) {
+    const u32x4 q = load_vec<CACHED>(rv + j);
     float x[E];
     unpack<DT>(q, x);
     if (j == jy) {
 #pragma unroll
       for (int e = 0; e < E; ++e) {
         if (e == ey) {
-          sh_zy = x[e];
+          *zy_out = x[e];
           x[e] = kNegInf;
         }
       }
@@ -260,96 +246,80 @@ fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* tok
     if (idx < V) {
       float x1 = load_elem<DT>(row, idx);
       if (idx == y) {
-        sh_zy = x1;
+        *zy_out = x1;
         x1 = kNegInf;
       }
       accumulate<1>(&x1, r, rL, s);
     }
   }
+}
 
-  // combine the lanes: common reference first, then one rescale per lane
+// Merges the lanes' (rL, s) pairs; thread 0 returns lp and lse in fp64 (others return garbage).
+// Contains one __syncthreads.  sh_R / sh_S hold NT/64 floats each.
+template <int NT>
+__device__ __forceinline__ void block_lse_finish(float rL, float s, const float* zy_in, float* sh_R,
+                                                 float* sh_S, double& lp_out, double& lse_out) {
+  // common reference first, then one rescale per lane
   const float Rw = wave_max(rL);
   const float Sw = wave_sum(s * fast_exp2(rL - Rw));
-  const int lane = tid & 63, w = tid >> 6;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (lane == 0) {
     sh_R[w] = Rw;
     sh_S[w] = Sw;
   }
   __syncthreads();
-  if (tid == 0) {
+  lp_out = 0.0;
+  lse_out = 0.0;
+  if (threadIdx.x == 0) {
     float RR = sh_R[0];
 #pragma unroll
-    for (int i = 1; i < kStreamThreads / 64; ++i) RR = fmaxf(RR, sh_R[i]);
+    for (int i = 1; i < NT / 64; ++i) RR = fmaxf(RR, sh_R[i]);
     float SS = 0.f;
 #pragma unroll
-    for (int i = 0; i < kStreamThreads / 64; ++i) SS += sh_S[i] * fast_exp2(sh_R[i] - RR);
+    for (int i = 0; i < NT / 64; ++i) SS += sh_S[i] * fast_exp2(sh_R[i] - RR);
     // Everything below is in log2 units of the scaled logits x * kLog2e.
     //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
     //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
-    const float zy = sh_zy;
-    const double zyL = static_cast<double>(zy) * static_cast<double>(kLog2e);
+    const double zyL = static_cast<double>(*zy_in) * static_cast<double>(kLog2e);
     const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
     const double sp = (a2 > 0.0 ? a2 : 0.0) + log1p(exp2(-fabs(a2))) * (1.0 / kLn2);
-    logp[t] = static_cast<float>(-sp * kLn2);
-    lse[t] = static_cast<float>((zyL + sp) * kLn2);
+    lp_out = -sp * kLn2;
+    lse_out = (zyL + sp) * kLn2;
   }
 }
 
-// =========================================================================================
-// K4: gradient stream.  dlogits[t, v] = c_t * (exp(z - lse_t) - [v == y_t]).  One workgroup
-// per row; rows with c_t == 0 are zero-filled without reading the logits.  `dlogits` may be
-// the same buffer as `logits`: every 16-byte vector is read and written by the same lane.
-// =========================================================================================
-
-template <int DT, int U>
-__global__ void __launch_bounds__(kStreamThreads)
-fopd_k4_grad(const void* logits, void* dlogits, int64_t T, int V, int64_t ld,
-             const int32_t* token_ids, const float* lse, const float* logp, const float* coef) {
+// Gradient row: g_v = c * 2^(x_v log2e - lseL), the sampled token's entry replaced by gy.
+// Input and output rows may be the same memory: each vector is read and written by one lane.
+template <int DT, int NT, int U, bool CACHED>
+__device__ __forceinline__ void row_grad(const char* row, char* orow, int V, int y, float c, float lseL,
+                                         float gy) {
   constexpr int E = Elem<DT>::kPerVec;
-  const int64_t t = blockIdx.x;
-  const int tid = threadIdx.x;
-  const float c = coef[t];
-  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
-  u32x4* ov = reinterpret_cast<u32x4*>(orow);
-  const int nvec = V / E;
-
-  if (c == 0.f) {
-    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
-    for (int j = tid; j < nvec; j += kStreamThreads) __builtin_nontemporal_store(zero, ov + j);
-    const int idx = nvec * E + tid;
-    if (idx < V) store_elem<DT>(orow, idx, 0.f);
-    return;
-  }
-
-  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
   const u32x4* rv = reinterpret_cast<const u32x4*>(row);
-  const int y = token_ids[t];
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int tid = threadIdx.x;
+  const int nvec = V / E;
   const int jy = y / E, ey = y % E;
-  const float lseL = lse[t] * kLog2e;
-  // c * (p_y - 1) from lp_y, which stays accurate when p_y is close to 1
-  const float gy = c * expm1f(logp[t]);
-
   int j = tid;
-  for (; j + (U - 1) * kStreamThreads < nvec; j += U * kStreamThreads) {
+  for (; j + (U - 1) * NT < nvec; j += U * NT) {
     u32x4 q[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) q[u] = __builtin_nontemporal_load(rv + j + u * kStreamThreads);
+    for (int u = 0; u < U; ++u) q[u] = load_vec<CACHED>(rv + j + u * NT);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float x[E];
       unpack<DT>(q[u], x);
 #pragma unroll
       for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
-      if (j + u * kStreamThreads == jy) {
+      if (j + u * NT == jy) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
           if (e == ey) x[e] = gy;
       }
-      __builtin_nontemporal_store(pack<DT>(x), ov + j + u * kStreamThreads);
+      __builtin_nontemporal_store(pack<DT>(x), ov + j + u * NT);
     }
   }
-  for (; j < nvec; j += kStreamThreads) {
-    const u32x4 q = __builtin_nontemporal_load(rv + j);
+  for (; j < nvec; j += NT) {
+    const u32x4 q = load_vec<CACHED>(rv + j);
     float x[E];
     unpack<DT>(q, x);
 #pragma unroll
@@ -369,6 +339,187 @@ fopd_k4_grad(const void* logits, void* dlogits, int64_t T, int V, int64_t ld,
       store_elem<DT>(orow, idx, g);
     }
   }
+}
+
+template <int DT, int NT>
+__device__ __forceinline__ void row_zero(char* orow, int V) {
+  constexpr int E = Elem<DT>::kPerVec;
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int nvec = V / E;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  for (int j = threadIdx.x; j < nvec; j += NT) __builtin_nontemporal_store(zero, ov + j);
+  const int idx = nvec * E + threadIdx.x;
+  if (idx < V) store_elem<DT>(orow, idx, 0.f);
+}
+
+// e^d * d - e^d + 1 without cancellation for small d
+__device__ __forceinline__ double kl_term(double d, double* rho_out) {
+  const double e1 = expm1(d);
+  if (rho_out != nullptr) *rho_out = e1 + 1.0;
+  return d * e1 + (d - e1);
+}
+
+__device__ __forceinline__ double weight_of(double f, int32_t n, float xi) {
+  if (n <= 0) return 0.0;
+  const double w = f - static_cast<double>(xi);
+  return w > 0.0 ? w : 0.0;
+}
+
+// Row coefficient c_t and the row's share of the loss, from the fp32-rounded log-prob.
+__device__ __forceinline__ float coef_and_loss(double lp, double lb, double lq, double w, int32_t n, int32_t B,
+                                               fopd_hparams hp, float grad_scale, double* loss_term) {
+  double rho;
+  const double d = lp - lb;
+  const double k = kl_term(d, &rho);
+  const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
+  const double lam = hp.lambda;
+  *loss_term = pref * ((lp - lq) + lam * k);
+  return static_cast<float>(static_cast<double>(grad_scale) * pref * ((lq - lp) - lam * rho * d));
+}
+
+// Largest i with cu[i] <= gt, given cu[0] <= gt < cu[B].
+__device__ __forceinline__ int sample_of_row(const int64_t* cu, int32_t B, int64_t gt) {
+  int lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= gt) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+}  // namespace
+
+// =========================================================================================
+// K1: streaming log-sum-exp and sampled-token log-probability.  One workgroup per row.
+// =========================================================================================
+
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
+            const uint8_t* mask, float* logp, float* lse, int64_t* gather_idx, int32_t* flags) {
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int y = token_ids[t];
+  if (tid == 0 && gather_idx != nullptr) gather_idx[t] = t * ld + static_cast<int64_t>(y);
+  bool live = (mask == nullptr) || (mask[t] != 0);
+  if (live && (y < 0 || y >= V)) {
+    if (tid == 0) atomicOr(flags, kFlagToken);
+    live = false;
+  }
+  if (!live) {
+    if (tid == 0) {
+      logp[t] = 0.f;
+      lse[t] = 0.f;
+    }
+    return;
+  }
+  __shared__ float sh_zy;
+  __shared__ float sh_R[kStreamThreads / 64];
+  __shared__ float sh_S[kStreamThreads / 64];
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
+  row_lse<DT, kStreamThreads, U, false>(row, V, y, r, rL, s, &sh_zy);
+  double lp, ls;
+  block_lse_finish<kStreamThreads>(rL, s, &sh_zy, sh_R, sh_S, lp, ls);
+  if (tid == 0) {
+    logp[t] = static_cast<float>(lp);
+    lse[t] = static_cast<float>(ls);
+  }
+}
+
+// =========================================================================================
+// K4: gradient stream.  dlogits[t, v] = c_t * (exp(z - lse_t) - [v == y_t]).  One workgroup
+// per row; rows with c_t == 0 are zero-filled without reading the logits.  `dlogits` may be
+// the same buffer as `logits`: every 16-byte vector is read and written by the same lane.
+// =========================================================================================
+
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k4_grad(const void* logits, void* dlogits, int64_t T, int V, int64_t ld,
+             const int32_t* token_ids, const float* lse, const float* logp, const float* coef) {
+  const int64_t t = blockIdx.x;
+  const float c = coef[t];
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  if (c == 0.f) {
+    row_zero<DT, kStreamThreads>(orow, V);
+    return;
+  }
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  // the sampled token's entry c * (p_y - 1) comes from lp_y, which stays accurate as p_y -> 1
+  row_grad<DT, kStreamThreads, U, false>(row, orow, V, token_ids[t], c, lse[t] * kLog2e, c * expm1f(logp[t]));
+}
+
+// =========================================================================================
+// K14: both passes over one row in one workgroup, for calls whose freshness scores are given.
+// The first pass uses ordinary loads so that the row stays in the Infinity Cache; the second
+// pass re-reads it from there and writes the gradient: HBM sees one read and one write per
+// row.  NT lanes per row; the caller caps the rows in flight per compute unit through the
+// dynamic LDS size (launch shapes measured on MI355X: 256 lanes x 6 rows is the fastest).
+// With NT = kStreamThreads it produces the same bits as K1 + fopd_coef_loss + K4 (same partition of
+// the row over lanes); other NT sum the row in another order and may differ in the last place.
+// =========================================================================================
+
+template <int DT, int NT, int U>
+__global__ void __launch_bounds__(NT)
+fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
+               const uint8_t* mask, const float* behav_logp, const float* teacher_logp, const int64_t* cu,
+               const int32_t* n_train, const float* fresh32, int32_t B, int64_t row_begin, fopd_hparams hp,
+               float grad_scale, float* logp, double* row_loss, int32_t* flags) {
+  extern __shared__ char occupancy_pad[];      // sized by the host only to cap workgroups per CU
+  __shared__ float sh_zy;
+  __shared__ float sh_R[NT / 64];
+  __shared__ float sh_S[NT / 64];
+  __shared__ float sh_c, sh_lseL, sh_gy;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int y = token_ids[t];
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  bool live = (mask == nullptr) || (mask[t] != 0);
+  if (live && (y < 0 || y >= V)) {
+    if (tid == 0) atomicOr(flags, kFlagToken);
+    live = false;
+  }
+  const int64_t gt = row_begin + t;
+  double w = 0.0;
+  int32_t n = 0;
+  if (live && gt < cu[B]) {
+    const int i = sample_of_row(cu, B, gt);
+    n = n_train[i];
+    w = weight_of(static_cast<double>(fresh32[i]), n, hp.xi);
+  }
+  if (!live || (w == 0.0 && logp == nullptr)) {   // nothing to learn from this row: no read at all
+    if (tid == 0) {
+      if (logp != nullptr) logp[t] = 0.f;
+      row_loss[t] = 0.0;
+    }
+    row_zero<DT, NT>(orow, V);
+    return;
+  }
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
+  row_lse<DT, NT, U, true>(row, V, y, r, rL, s, &sh_zy);
+  double lp, ls;
+  block_lse_finish<NT>(rL, s, &sh_zy, sh_R, sh_S, lp, ls);
+  if (tid == 0) {
+    const float lp32 = static_cast<float>(lp);
+    const float lse32 = static_cast<float>(ls);
+    if (logp != nullptr) logp[t] = lp32;
+    float c = 0.f;
+    double lt = 0.0;
+    if (w > 0.0)
+      c = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], w, n, B, hp, grad_scale, &lt);
+    row_loss[t] = lt;
+    sh_c = c;
+    sh_lseL = lse32 * kLog2e;
+    sh_gy = c * expm1f(lp32);
+  }
+  __syncthreads();
+  const float c = sh_c;
+  if (c == 0.f) {
+    row_zero<DT, NT>(orow, V);
+    return;
+  }
+  row_grad<DT, NT, U, false>(row, orow, V, y, c, sh_lseL, sh_gy);   // non-temporal re-read measured faster
 }
 
 // =========================================================================================
@@ -420,11 +571,19 @@ fopd_scan_seqlens(const int32_t* seq_lens, const int32_t* lag, int32_t B, int64_
   if (bad_lag) atomicOr(flags, kFlagLag);
 }
 
-// e^d * d - e^d + 1 without cancellation for small d
-__device__ __forceinline__ double kl_term(double d, double* rho_out) {
-  const double e1 = expm1(d);
-  if (rho_out != nullptr) *rho_out = e1 + 1.0;
-  return d * e1 + (d - e1);
+// n_i = number of mask == 1 rows of sample i (one workgroup per sample).
+__global__ void __launch_bounds__(kSegThreads)
+fopd_count_train(const uint8_t* mask, const int64_t* cu, int64_t T, int32_t* n_train) {
+  __shared__ double sh[kSegThreads / 64];
+  const int i = blockIdx.x;
+  const int64_t a = cu[i];
+  int64_t b = cu[i + 1];
+  if (b > T) b = T;
+  double cnt = 0.0;
+  for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads)
+    if (mask == nullptr || mask[t] != 0) cnt += 1.0;
+  const double tn = block_sum<kSegThreads>(cnt, sh);
+  if (threadIdx.x == 0) n_train[i] = static_cast<int32_t>(tn);
 }
 
 // One workgroup per sample: token means over the mask, then the freshness score.
@@ -496,12 +655,6 @@ fopd_aggregate(const double* fresh64, const int32_t* n_train, const int64_t* cu,
   }
 }
 
-__device__ __forceinline__ double weight_of(double f, int32_t n, float xi) {
-  if (n <= 0) return 0.0;
-  const double w = f - static_cast<double>(xi);
-  return w > 0.0 ? w : 0.0;
-}
-
 // Per-token gradient coefficient c_t and the block's share of the loss.
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_logp,
@@ -515,24 +668,12 @@ fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_
     float c = 0.f;
     const int64_t gt = row_begin + t;
     if ((mask == nullptr || mask[t] != 0) && gt < cu[B]) {
-      int lo = 0, hi = B;                      // largest i with cu[i] <= gt  (cu[B] > gt)
-      while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (cu[mid] <= gt) lo = mid; else hi = mid;
-      }
-      const int32_t n = n_train[lo];
-      const double f = (fresh64 != nullptr) ? fresh64[lo] : static_cast<double>(fresh32[lo]);
+      const int i = sample_of_row(cu, B, gt);
+      const int32_t n = n_train[i];
+      const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
       const double w = weight_of(f, n, hp.xi);
-      if (w > 0.0) {
-        const double lp = logp[t], lq = teacher_logp[t];
-        const double d = lp - static_cast<double>(behav_logp[t]);
-        double rho;
-        const double k = kl_term(d, &rho);
-        const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
-        const double lam = hp.lambda;
-        c = static_cast<float>(static_cast<double>(grad_scale) * pref * ((lq - lp) - lam * rho * d));
-        lt = pref * ((lp - lq) + lam * k);
-      }
+      if (w > 0.0)
+        c = coef_and_loss(logp[t], behav_logp[t], teacher_logp[t], w, n, B, hp, grad_scale, &lt);
     }
     coef[t] = c;
   }

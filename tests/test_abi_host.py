@@ -116,7 +116,7 @@ def test_freshness_rejects_bad_arguments_before_launch():
 def test_profile_read_argument_checks():
     lib = fb.load_library()
     ms, n = ctypes.c_double(), ctypes.c_int64()
-    assert lib.fopd_profile_read(2, ctypes.byref(ms), ctypes.byref(n)) == 1
+    assert lib.fopd_profile_read(3, ctypes.byref(ms), ctypes.byref(n)) == 1
     assert lib.fopd_profile_read(0, None, ctypes.byref(n)) == 1
     assert lib.fopd_profile_reset() == 0
     assert lib.fopd_profile_read(0, ctypes.byref(ms), ctypes.byref(n)) == 0 and n.value == 0
@@ -126,3 +126,13 @@ def test_binding_refuses_host_tensors():
     import torch
     with pytest.raises(ValueError):
         fb._ptr(torch.zeros(4), torch.float32, "x")
+
+
+def test_set_option_checks_names_and_values():
+    lib = fb.load_library()
+    assert lib.fopd_set_option(b"k14_threads", 512) == 0
+    assert lib.fopd_set_option(b"k14_threads", 300) == 1
+    assert lib.fopd_set_option(b"k14_rows_per_cu", 2) == 0
+    assert lib.fopd_set_option(b"k14_rows_per_cu", 0) == 1
+    assert lib.fopd_set_option(b"no_such_option", 1) == 1
+    assert lib.fopd_set_option(None, 1) == 1

@@ -312,6 +312,73 @@ def test_scores_supplied_and_chunked_flow():
     assert torch.equal(ck.weights, sc.weights)
 
 
+@pytest.mark.parametrize("threads,rows_per_cu,dtype,V,ld", [(256, 6, "bf16", 5003, 5008), (512, 2, "bf16", 40000, 40000),
+                                                          (1024, 1, "bf16", 151936, 151936), (256, 8, "f32", 4097, 4100),
+                                                          (1024, 2, "f32", 3, 4), (512, 4, "bf16", 1, 8)])
+def test_two_passes_per_row_kernel_matches_separate_kernels(threads, rows_per_cu, dtype, V, ld):
+    """With scores supplied and no stored log-probs, one kernel makes both passes over each row.  With
+    256 lanes per row (the default, and the partition the log-prob kernel uses) it must give the bits
+    of the separate log-prob, coefficient and gradient kernels; other lane counts sum the row in a
+    different order, so they may differ by one unit in the last place.  Covered: masks, gated samples,
+    padding, a row offset and an aliased output."""
+    _say("two-pass-per-row kernel: %d lanes, %d rows/CU, %s V=%d" % (threads, rows_per_cu, dtype, V))
+    w = wl.generate("tooluse", DEV, seed=13, B=5, turns=2, obs_lo=2, obs_hi=5, resp_lo=3, resp_hi=9, V=V, ld=ld,
+                    dtype=dtype, boost=min(4, V), lag_lo=0, lag_hi=30, row_block=32)
+    T, B = w["T"], w["B"]
+    hp = (1.0, 1.0, 0.05, 0.3)
+    st = _pass_for(w)
+    st.token_logprobs(w)
+    st.freshness_score(w, hp)
+    _sync_ok(st)
+    f_gpu, n_gpu = st.freshness.clone(), st.n_train.clone()
+    assert bool((f_gpu < 0.05).any()) and bool((f_gpu > 0.05).any())        # gated and live samples
+
+    def call(lp, a, b, lse, logp_in, logp_out, out, n_in):
+        fb.fopd_loss_fwd_bwd(w["logits"][a:b], lp.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b],
+                             w["behav_logp"][a:b], w["teacher_logp"][a:b], None, w["seq_lens"], w["lag"], B, hp,
+                             f_gpu, n_in, a, lse, logp_in, 0.5, lp.loss, None, lp.weights, logp_out, out,
+                             lp.workspace)
+
+    ref = _pass_for(w)                    # separate kernels: stored lse / logp, gradient kernel only
+    ref.dlogits.fill_(3.0)
+    call(ref, 0, T, st.lse, st.logp, None, ref.dlogits, n_gpu)
+    _sync_ok(ref)
+    try:
+        fb.fopd_set_option("k14_threads", threads)
+        fb.fopd_set_option("k14_rows_per_cu", rows_per_cu)
+        one = _pass_for(w)
+        one.dlogits.fill_(5.0)
+        call(one, 0, T, None, None, one.logp, one.dlogits, None)            # counts taken from the mask
+        _sync_ok(one)
+        def same(x, y_):
+            if threads == 256:
+                return torch.equal(x, y_)
+            xd, yd = np64(x), np64(y_)
+            lim = orc.bf16_ulp(yd) if dtype == "bf16" else 1e-5 * np.abs(yd) + 1e-30
+            return bool(np.all(np.abs(xd - yd) <= lim)) and float(np.mean(xd == yd)) > 0.9
+
+        assert same(one.dlogits[:, :V], ref.dlogits[:, :V])
+        if ld > V:
+            assert bool((one.dlogits[:, V:] == 5.0).all())
+        assert torch.equal(one.weights, ref.weights)
+        assert torch.equal(one.logp, st.logp) or (threads != 256 and
+                                                  torch.allclose(one.logp, st.logp, rtol=2e-6, atol=2e-6))
+        assert abs(float(one.loss) - float(ref.loss)) <= 2e-6 * abs(float(ref.loss)) + 1e-12
+        # a row range that starts inside a sample, output aliased onto the input, no log-prob output
+        a, b = 3, T - 2
+        z = w["logits"].clone()
+        two = _pass_for(w, alloc_dlogits=False)
+        fb.fopd_loss_fwd_bwd(z[a:b], two.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b],
+                             w["behav_logp"][a:b], w["teacher_logp"][a:b], None, w["seq_lens"], w["lag"], B, hp,
+                             f_gpu, n_gpu, a, None, None, 0.5, two.loss, None, None, None, z[a:b], two.workspace)
+        _sync_ok(two)
+        assert same(z[a:b, :V], ref.dlogits[a:b, :V])
+        assert torch.equal(z[:a], w["logits"][:a]) and torch.equal(z[b:], w["logits"][b:])
+    finally:
+        fb.fopd_set_option("k14_threads", 256)
+        fb.fopd_set_option("k14_rows_per_cu", 6)
+
+
 def test_device_side_error_flags():
     _say("device flags: token range, segments, lag")
     w = wl.generate("reasoning", DEV, seed=12, B=3, len_lo=4, len_hi=6, V=512)
