@@ -99,13 +99,16 @@ fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* 
  *   lse         [T] f32 out: log sum_v exp(z_{t,v})      (0 for masked rows)
  *   gather_idx  [T] int64 out, NULL to skip: t * ld + y_t for every row, masked or not (an element
  *               offset from the `logits` pointer of this call)
+ *   entropy     [T] f32 out, NULL to skip: H_t = -sum_v p_v log p_v of softmax(z_t), the token-level
+ *               response entropy logged as a monitoring proxy (App. B); 0 for masked rows.  Costs
+ *               one more multiply-add per logit in the same pass, no extra memory traffic.
  *
  * lp_t is formed from the sum over v != y_t, so it keeps full relative accuracy as
  * softmax(z_t)[y_t] approaches 1.
  */
 fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                                 const int32_t* token_ids, const uint8_t* mask,
-                                float* logp, float* lse, int64_t* gather_idx,
+                                float* logp, float* lse, int64_t* gather_idx, float* entropy,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*

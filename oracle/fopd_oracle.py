@@ -111,6 +111,22 @@ def token_logprobs(logits, token_ids, mask=None):
     return lse, lp
 
 
+def token_entropy(logits, mask=None):
+    """H_t = -sum_v p_v log p_v of softmax(z_t) (the token-level response entropy that App. B logs as a
+    monitoring proxy).  Masked rows give 0; entries with p_v = 0 (logit -inf) contribute 0."""
+    logits = np.asarray(logits)
+    T = logits.shape[0]
+    H = np.zeros(T, dtype=np.float64)
+    for t in range(T):
+        if mask is not None and mask[t] == 0:
+            continue
+        z = logits[t].astype(np.float64)
+        logp = z - row_logsumexp(z)
+        p = np.exp(logp)
+        H[t] = -float(np.sum(np.where(p > 0.0, p * np.where(p > 0.0, logp, 0.0), 0.0)))
+    return H
+
+
 # ----------------------------------------------------------------------------------------
 # per-token drift and advantage terms
 # ----------------------------------------------------------------------------------------

@@ -60,7 +60,7 @@ def load_library():
     lib.fopd_workspace_status.restype = ctypes.c_int
     lib.fopd_workspace_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.fopd_token_logprobs.restype = ctypes.c_int
-    lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -140,7 +140,7 @@ def fopd_workspace_status(workspace, stream=None):
     return int(st), int(flags.value)
 
 
-def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, workspace,
+def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, entropy, workspace,
                         stream=None):
     import torch
     p, n = _ws(workspace)
@@ -148,7 +148,8 @@ def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather
         _ptr(logits, (torch.float32, torch.bfloat16), "logits"), int(dt), int(T), int(V), int(ld),
         _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(logp, torch.float32, "logp"), _ptr(lse, torch.float32, "lse"),
-        _ptr(gather_idx, torch.int64, "gather_idx"), p, n, _stream(stream))
+        _ptr(gather_idx, torch.int64, "gather_idx"), _ptr(entropy, torch.float32, "entropy"),
+        p, n, _stream(stream))
     _check(st, "fopd_token_logprobs")
 
 

@@ -105,16 +105,20 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 
 fopd_status launch_k1(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                       const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
-                      int64_t* gather_idx, int32_t* flags, hipStream_t s) {
+                      int64_t* gather_idx, float* entropy, int32_t* flags, hipStream_t s) {
   if (T == 0) return FOPD_OK;
   ScopedTimer timer(0, s);
   const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
-  if (dt == FOPD_BF16)
-    fopd_k1_lse<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids,
-                                                           mask, logp, lse, gather_idx, flags);
-  else
-    fopd_k1_lse<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids,
-                                                          mask, logp, lse, gather_idx, flags);
+  const int v = static_cast<int>(V);
+#define FOPD_K1_ARGS logits, T, v, ld, token_ids, mask, logp, lse, gather_idx, entropy, flags
+  if (dt == FOPD_BF16) {
+    if (entropy != nullptr) fopd_k1_lse<FOPD_BF16, kUnroll, true><<<grid, block, 0, s>>>(FOPD_K1_ARGS);
+    else fopd_k1_lse<FOPD_BF16, kUnroll, false><<<grid, block, 0, s>>>(FOPD_K1_ARGS);
+  } else {
+    if (entropy != nullptr) fopd_k1_lse<FOPD_F32, kUnroll, true><<<grid, block, 0, s>>>(FOPD_K1_ARGS);
+    else fopd_k1_lse<FOPD_F32, kUnroll, false><<<grid, block, 0, s>>>(FOPD_K1_ARGS);
+  }
+#undef FOPD_K1_ARGS
   return launched();
 }
 
@@ -215,7 +219,7 @@ fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* 
 
 fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                                 const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
-                                int64_t* gather_idx, void* workspace, size_t workspace_bytes,
+                                int64_t* gather_idx, float* entropy, void* workspace, size_t workspace_bytes,
                                 void* stream) {
   fopd_status st = check_matrix(logits, dt, T, V, ld);
   if (st != FOPD_OK) return st;
@@ -223,7 +227,7 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
   st = check_workspace(workspace, workspace_bytes, T, 0);
   if (st != FOPD_OK) return st;
   Workspace w(T, 0);
-  return launch_k1(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx,
+  return launch_k1(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, entropy,
                    at<int32_t>(workspace, w.flags), static_cast<hipStream_t>(stream));
 }
 
@@ -320,7 +324,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   const float* lse_use = lse_in;
   const float* logp_use = logp_in;
   if (!have_lse) {
-    st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, flags, s);
+    st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s);
     if (st != FOPD_OK) return st;
     lse_use = lse_ws;
     logp_use = logp_ws;

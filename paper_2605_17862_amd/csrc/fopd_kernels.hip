@@ -38,7 +38,6 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;   // nearest float to log2(e)
 constexpr double kLn2 = 0.6931471805599453094;
-constexpr float kNegInit = -1.0e38f;            // "nothing seen yet" reference (finite on purpose)
 
 template <int DT> struct Elem;
 template <> struct Elem<FOPD_F32> {
@@ -158,27 +157,52 @@ __device__ __forceinline__ double block_sum(double v, double* sh) {
 }
 
 // ---- online log-sum-exp state of one lane ----------------------------------------------
-// The lane holds rL (its running maximum times log2 e, as rounded) and s = sum 2^(x log2e - rL)
-// over the elements it has seen, the sampled token excluded.
+// The lane holds rL (its running maximum times log2 e, as rounded) and s = sum 2^t over the
+// elements it has seen, t = x log2e - rL, the sampled token excluded; with ENT also w = sum t 2^t,
+// from which the row's entropy follows without cancellation at the scale of the logits
+// (monitoring proxy, App. B "response entropy").
 
-template <int N>
-__device__ __forceinline__ void accumulate(const float* x, float& r, float& rL, float& s) {
+struct LaneState {
+  float r = -1.0e38f;                       // "nothing seen yet" (finite on purpose)
+  float rL = -1.0e38f * 1.4426950408889634f;
+  float s = 0.f;
+  float w = 0.f;
+};
+
+// Moves a (s, w) pair from reference `from` to reference `to` (both in log2 units).
+__device__ __forceinline__ void rebase(float from, float to, float& s, float& w, bool ent) {
+  const float scale = fast_exp2(from - to);
+  if (ent) w = fmaf(from - to, s, w) * scale;
+  s *= scale;
+}
+
+template <int N, bool ENT>
+__device__ __forceinline__ void accumulate(const float* x, LaneState& st) {
   float bm = x[0];
 #pragma unroll
   for (int i = 1; i < N; ++i) bm = fmaxf(bm, x[i]);
-  if (bm > r) {                       // rare after the first few vectors
+  if (bm > st.r) {                    // rare after the first few vectors
     const float nrL = bm * kLog2e;
-    s *= fast_exp2(rL - nrL);
-    r = bm;
-    rL = nrL;
+    rebase(st.rL, nrL, st.s, st.w, ENT);
+    st.r = bm;
+    st.rL = nrL;
   }
-  float a0 = 0.f, a1 = 0.f;
+  float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f;
 #pragma unroll
   for (int i = 0; i < N; i += 2) {
-    a0 += fast_exp2(fmaf(x[i], kLog2e, -rL));
-    if (i + 1 < N) a1 += fast_exp2(fmaf(x[i + 1], kLog2e, -rL));
+    const float t0 = fmaf(x[i], kLog2e, -st.rL);
+    const float e0 = fast_exp2(t0);
+    a0 += e0;
+    if (ENT) w0 = fmaf(e0, fmaxf(t0, -1.0e30f), w0);       // t = -inf has e = 0: keep 0 * t finite
+    if (i + 1 < N) {
+      const float t1 = fmaf(x[i + 1], kLog2e, -st.rL);
+      const float e1 = fast_exp2(t1);
+      a1 += e1;
+      if (ENT) w1 = fmaf(e1, fmaxf(t1, -1.0e30f), w1);
+    }
   }
-  s += a0 + a1;
+  st.s += a0 + a1;
+  if (ENT) st.w += w0 + w1;
 }
 
 // ---- row routines shared by the streaming kernels ----------------------------------------
@@ -193,11 +217,10 @@ __device__ __forceinline__ u32x4 load_vec(const u32x4* p) {
   return __builtin_nontemporal_load(p);
 }
 
-// Pass over a row for the log-sum-exp: updates the lane's (r, rL, s); the lane that meets the
+// Pass over a row for the log-sum-exp: updates the lane's state; the lane that meets the
 // sampled token y stores its value to *zy_out (LDS) and leaves it out of the sum.
-template <int DT, int NT, int U, bool CACHED>
-__device__ __forceinline__ void row_lse(const char* row, int V, int y, float& r, float& rL, float& s,
-                                        float* zy_out) {
+template <int DT, int NT, int U, bool CACHED, bool ENT>
+__device__ __forceinline__ void row_lse(const char* row, int V, int y, LaneState& st, float* zy_out) {
   constexpr int E = Elem<DT>::kPerVec;
   const u32x4* rv = reinterpret_cast<const u32x4*>(row);
   const int tid = threadIdx.x;
@@ -224,7 +247,7 @@ __device__ __forceinline__ void row_lse(const char* row, int V, int y, float& r,
         }
       }
     }
-    accumulate<U * E>(x, r, rL, s);
+    accumulate<U * E, ENT>(x, st);
   }
   for (; j < nvec; j += NT) {
     const u32x4 q = load_vec<CACHED>(rv + j);
@@ -239,7 +262,7 @@ __device__ __forceinline__ void row_lse(const char* row, int V, int y, float& r,
         }
       }
     }
-    accumulate<E>(x, r, rL, s);
+    accumulate<E, ENT>(x, st);
   }
   {
     const int idx = nvec * E + tid;   // ragged tail: fewer than E elements
@@ -249,42 +272,67 @@ __device__ __forceinline__ void row_lse(const char* row, int V, int y, float& r,
         *zy_out = x1;
         x1 = kNegInf;
       }
-      accumulate<1>(&x1, r, rL, s);
+      accumulate<1, ENT>(&x1, st);
     }
   }
 }
 
-// Merges the lanes' (rL, s) pairs; thread 0 returns lp and lse in fp64 (others return garbage).
-// Contains one __syncthreads.  sh_R / sh_S hold NT/64 floats each.
-template <int NT>
-__device__ __forceinline__ void block_lse_finish(float rL, float s, const float* zy_in, float* sh_R,
-                                                 float* sh_S, double& lp_out, double& lse_out) {
-  // common reference first, then one rescale per lane
-  const float Rw = wave_max(rL);
-  const float Sw = wave_sum(s * fast_exp2(rL - Rw));
+// Merges the lanes' states; thread 0 returns lp, lse (and with ENT the row entropy) in fp64, the
+// other lanes return zeros.  Contains one __syncthreads.  sh_R / sh_S / sh_W hold NT/64 floats each.
+template <int NT, bool ENT>
+__device__ __forceinline__ void block_lse_finish(const LaneState& st, const float* zy_in, float* sh_R,
+                                                 float* sh_S, float* sh_W, double& lp_out, double& lse_out,
+                                                 double& ent_out) {
+  // common reference first, then one rebase per lane
+  const float Rw = wave_max(st.rL);
+  float ls = st.s, lw = st.w;
+  rebase(st.rL, Rw, ls, lw, ENT);
+  const float Sw = wave_sum(ls);
+  float Ww = 0.f;
+  if (ENT) Ww = wave_sum(lw);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   if (lane == 0) {
     sh_R[w] = Rw;
     sh_S[w] = Sw;
+    if (ENT) sh_W[w] = Ww;
   }
   __syncthreads();
   lp_out = 0.0;
   lse_out = 0.0;
+  ent_out = 0.0;
   if (threadIdx.x == 0) {
     float RR = sh_R[0];
 #pragma unroll
     for (int i = 1; i < NT / 64; ++i) RR = fmaxf(RR, sh_R[i]);
-    float SS = 0.f;
+    float SS = 0.f, WW = 0.f;
 #pragma unroll
-    for (int i = 0; i < NT / 64; ++i) SS += sh_S[i] * fast_exp2(sh_R[i] - RR);
+    for (int i = 0; i < NT / 64; ++i) {
+      float si = sh_S[i], wi = ENT ? sh_W[i] : 0.f;
+      rebase(sh_R[i], RR, si, wi, ENT);
+      SS += si;
+      WW += wi;
+    }
     // Everything below is in log2 units of the scaled logits x * kLog2e.
     //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
     //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
     const double zyL = static_cast<double>(*zy_in) * static_cast<double>(kLog2e);
     const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
-    const double sp = (a2 > 0.0 ? a2 : 0.0) + log1p(exp2(-fabs(a2))) * (1.0 / kLn2);
+    const double q = exp2(-fabs(a2));                  // 2^-|a2|, in (0, 1]
+    const double l1q = log1p(q) * (1.0 / kLn2);        // log2(1 + 2^-|a2|)
+    const double sp = (a2 > 0.0 ? a2 : 0.0) + l1q;
     lp_out = -sp * kLn2;
     lse_out = (zyL + sp) * kLn2;
+    if (ENT) {
+      // H = h(p_y) + (1 - p_y) * H(softmax over the other tokens): the binary entropy of
+      // {y, not y} plus the conditional entropy, each a sum of non-negative terms.
+      const double a = fabs(a2);
+      const double h2 = (a < 1.0e300) ? l1q + a * q / (1.0 + q) : 0.0;
+      const double p_not = (a2 > 0.0) ? 1.0 / (1.0 + q) : q / (1.0 + q);
+      double h_ex = 0.0;
+      if (SS > 0.f) h_ex = log2(static_cast<double>(SS)) - static_cast<double>(WW) / static_cast<double>(SS);
+      if (h_ex < 0.0) h_ex = 0.0;
+      ent_out = (h2 + p_not * h_ex) * kLn2;
+    }
   }
 }
 
@@ -393,10 +441,11 @@ __device__ __forceinline__ int sample_of_row(const int64_t* cu, int32_t B, int64
 // K1: streaming log-sum-exp and sampled-token log-probability.  One workgroup per row.
 // =========================================================================================
 
-template <int DT, int U>
+template <int DT, int U, bool ENT>
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
-            const uint8_t* mask, float* logp, float* lse, int64_t* gather_idx, int32_t* flags) {
+            const uint8_t* mask, float* logp, float* lse, int64_t* gather_idx, float* entropy,
+            int32_t* flags) {
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x;
   const int y = token_ids[t];
@@ -410,20 +459,23 @@ fopd_k1_lse(const void* logits, int64_t T, int V, int64_t ld, const int32_t* tok
     if (tid == 0) {
       logp[t] = 0.f;
       lse[t] = 0.f;
+      if (ENT) entropy[t] = 0.f;
     }
     return;
   }
   __shared__ float sh_zy;
   __shared__ float sh_R[kStreamThreads / 64];
   __shared__ float sh_S[kStreamThreads / 64];
+  __shared__ float sh_W[kStreamThreads / 64];
   const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
-  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
-  row_lse<DT, kStreamThreads, U, false>(row, V, y, r, rL, s, &sh_zy);
-  double lp, ls;
-  block_lse_finish<kStreamThreads>(rL, s, &sh_zy, sh_R, sh_S, lp, ls);
+  LaneState st;
+  row_lse<DT, kStreamThreads, U, false, ENT>(row, V, y, st, &sh_zy);
+  double lp, ls, ent;
+  block_lse_finish<kStreamThreads, ENT>(st, &sh_zy, sh_R, sh_S, sh_W, lp, ls, ent);
   if (tid == 0) {
     logp[t] = static_cast<float>(lp);
     lse[t] = static_cast<float>(ls);
+    if (ENT) entropy[t] = static_cast<float>(ent);
   }
 }
 
@@ -496,10 +548,10 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
     return;
   }
   const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
-  float r = kNegInit, rL = kNegInit * kLog2e, s = 0.f;
-  row_lse<DT, NT, U, true>(row, V, y, r, rL, s, &sh_zy);
-  double lp, ls;
-  block_lse_finish<NT>(rL, s, &sh_zy, sh_R, sh_S, lp, ls);
+  LaneState st;
+  row_lse<DT, NT, U, true, false>(row, V, y, st, &sh_zy);
+  double lp, ls, ent;
+  block_lse_finish<NT, false>(st, &sh_zy, sh_R, sh_S, nullptr, lp, ls, ent);
   if (tid == 0) {
     const float lp32 = static_cast<float>(lp);
     const float lse32 = static_cast<float>(ls);

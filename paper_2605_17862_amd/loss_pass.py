@@ -21,6 +21,7 @@ class LossPass:
         self.logp = torch.empty(self.T, **f32)
         self.lse = torch.empty(self.T, **f32)
         self.gather_idx = torch.empty(self.T, dtype=torch.int64, device=dev)
+        self.entropy = None
         self.cu_seqlens = torch.empty(self.B + 1, dtype=torch.int64, device=dev)
         self.n_train = torch.empty(self.B, dtype=torch.int32, device=dev)
         self.D_roll = torch.empty(self.B, **f32)
@@ -39,11 +40,14 @@ class LossPass:
         self.workspace = self.workspace[off:off + nbytes]
         fb.fopd_workspace_init(self.workspace)
 
-    def token_logprobs(self, w, rows=None, want_gather=True):
+    def token_logprobs(self, w, rows=None, want_gather=True, want_entropy=False):
         a, b = (0, self.T) if rows is None else rows
+        if want_entropy and self.entropy is None:
+            self.entropy = torch.empty(self.T, dtype=torch.float32, device=self.logp.device)
         fb.fopd_token_logprobs(w["logits"][a:b], self.dt, b - a, self.V, self.ld, w["token_ids"][a:b],
                                w["mask"][a:b], self.logp[a:b], self.lse[a:b],
-                               self.gather_idx[a:b] if want_gather else None, self.workspace)
+                               self.gather_idx[a:b] if want_gather else None,
+                               self.entropy[a:b] if want_entropy else None, self.workspace)
 
     def freshness_score(self, w, hp=DEFAULT_HPARAMS):
         stale = w["teacher_logp_stale"]

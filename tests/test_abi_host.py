@@ -46,7 +46,7 @@ def test_workspace_bytes():
 
 
 def _tok(lib, logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, logp=4096, lse=4096, ws=4096, wsb=1 << 20):
-    return lib.fopd_token_logprobs(P(logits), dt, T, V, ld, P(ids), None, P(logp), P(lse), None,
+    return lib.fopd_token_logprobs(P(logits), dt, T, V, ld, P(ids), None, P(logp), P(lse), None, None,
                                    P(ws), wsb, None)
 
 

@@ -55,9 +55,12 @@ def _compare_everything(w, hp, grad_scale=1.0, staged=True):
             assert float(lp.weights[i]) == 0.0
     if staged:
         st = _pass_for(w, alloc_dlogits=False)
-        st.token_logprobs(w)
+        st.token_logprobs(w, want_entropy=True)
         st.freshness_score(w, hp)
         _sync_ok(st)
+        # token entropy comes out of the same pass and must not disturb the log-probs
+        H = orc.token_entropy(np64(w["logits"])[:, :w["V"]], np64(w["mask"]))
+        assert_close("entropy", np64(st.entropy), H, rtol=2e-5, atol=2e-5)
         assert np.array_equal(np64(st.gather_idx), ref["gather_idx"]) and st.gather_idx.dtype == torch.int64
         assert np.array_equal(np64(st.cu_seqlens), ref["cu_seqlens"]) and st.cu_seqlens.dtype == torch.int64
         assert np.array_equal(np64(st.n_train), ref["n_train"]) and st.n_train.dtype == torch.int32
@@ -226,6 +229,13 @@ def test_extreme_rows():
     assert_close("logp extreme", got, lp_ref, rtol=1e-5, atol=1e-40)
     assert_close("lse extreme", np64(lp.lse), lse_ref, rtol=1e-6, atol=1e-5)
     assert abs(got[5] + np.log(V)) < 1e-6
+    lp.token_logprobs(w, want_entropy=True)
+    _sync_ok(lp)
+    assert np.array_equal(np64(lp.logp), got)                       # same log-probs with the entropy variant
+    H = orc.token_entropy(np64(zb), None)
+    # the oracle's log p_y = z_y - lse cancels in float64 when p_y -> 1 (row 0 loses its p_y log p_y term)
+    assert_close("entropy extreme", np64(lp.entropy), H, rtol=2e-5, atol=8 * np.spacing(np.abs(lse_ref)))
+    assert abs(float(lp.entropy[5]) - np.log(V)) < 1e-5 and float(lp.entropy[0]) < 1e-18
     # gradient of the same rows: the sampled-token entry is c * (p_y - 1), accurate as p_y -> 1
     ref = oracle_full(w, (1.0, 1.0, 0.0, 0.1))
     lp.loss_fwd_bwd(w, (1.0, 1.0, 0.0, 0.1))

@@ -103,6 +103,27 @@ def test_softmax_rows_sum_to_one_and_masked_rows_are_zero():
             assert lse[t] == 0.0 and lp[t] == 0.0
 
 
+def test_entropy_closed_forms_and_library():
+    import scipy.stats
+    V = 512
+    z = np.zeros((4, V))
+    z[1] = 3.7                                   # uniform rows: H = log V
+    z[2, 5] = 800.0                              # one-hot: H = 0
+    z[3, :2] = [math.log(3.0), 0.0]
+    z[3, 2:] = -np.inf                           # two live classes (3/4, 1/4), the rest excluded
+    H = orc.token_entropy(z, np.array([1, 1, 1, 1]))
+    np.testing.assert_allclose(H[:2], [math.log(V)] * 2, rtol=1e-13)
+    assert abs(H[2]) < 1e-300 + 1e-12
+    np.testing.assert_allclose(H[3], -(0.75 * math.log(0.75) + 0.25 * math.log(0.25)), rtol=1e-13)
+    rng = _rng(30)
+    z = rng.normal(0, 3, size=(5, 300))
+    mask = np.array([1, 1, 0, 1, 1], dtype=np.uint8)
+    H = orc.token_entropy(z, mask)
+    ref = scipy.stats.entropy(scipy.special.softmax(z, axis=1), axis=1)
+    np.testing.assert_allclose(H[mask == 1], ref[mask == 1], rtol=1e-12)
+    assert H[2] == 0.0 and np.all(H[mask == 1] > 0) and np.all(H <= math.log(300))
+
+
 def test_token_out_of_range_raises():
     z = np.zeros((1, 4))
     with pytest.raises(ValueError):
