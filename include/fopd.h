@@ -176,6 +176,33 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Adaptive refresh test (Sec. 4.2, refresh condition; Algorithm 1, step after the aggregates; App. B:
+ * the rule may fire at most once every `min_interval` optimizer steps, 200 in the paper).  HOST ONLY: all
+ * pointers are host pointers and nothing touches the GPU.  `agg_host` is a host copy of the `agg` output
+ * of fopd_freshness_score: mean freshness, mean roll coverage, mean sup coverage.
+ *
+ * The buffer is to be refreshed when   agg[0] <= kappa_f  or  agg[1] < kappa_roll  or  agg[2] < kappa_sup
+ * and no refresh happened in the last `min_interval - 1` steps (last_refresh_step < 0 means never).
+ * Returns 1 (refresh: the state records `step` and counts it) or 0; `reason_host`, if not NULL, receives
+ * the bits of the conditions that hold (1 freshness, 2 roll coverage, 4 sup coverage) whether or not
+ * the rate limit lets the refresh through.  Returns -1 on a NULL argument or min_interval < 1.
+ */
+typedef struct {
+  float kappa_f;
+  float kappa_roll;
+  float kappa_sup;
+  int64_t min_interval;
+} fopd_refresh_config;
+
+typedef struct {
+  int64_t last_refresh_step; /* initialise to -1 */
+  int64_t refreshes;         /* initialise to 0 */
+} fopd_refresh_state;
+
+int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,
+                        int64_t step, int32_t* reason_host);
+
+/*
  * Launch-shape options (process-wide, not thread-safe; set before the calls they affect):
  *   "k14_threads"      256, 512 or 1024 lanes per row in the kernel that makes both passes over a row
  *                      (used when freshness_in is given without lse_in); default 256

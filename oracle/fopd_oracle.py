@@ -232,6 +232,22 @@ def anchored_loss(w, ell, D_roll, lam):
     return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / B
 
 
+def refresh_decision(agg, kappa_f, kappa_roll, kappa_sup, step, last_refresh_step, min_interval):
+    """Adaptive refresh test (Sec. 4.2 refresh condition; App. B rate limit).  Returns (refresh, reasons):
+    reasons lists which of "f", "roll", "sup" hold; refresh is True when any holds and at least
+    min_interval steps have passed since the last refresh (last_refresh_step None = never)."""
+    fbar, mroll, msup = float(agg[0]), float(agg[1]), float(agg[2])
+    reasons = []
+    if fbar <= kappa_f:
+        reasons.append("f")
+    if mroll < kappa_roll:
+        reasons.append("roll")
+    if msup < kappa_sup:
+        reasons.append("sup")
+    rested = last_refresh_step is None or step - last_refresh_step >= min_interval
+    return (len(reasons) > 0 and rested), reasons
+
+
 # ----------------------------------------------------------------------------------------
 # gradient with respect to the logits
 # ----------------------------------------------------------------------------------------

@@ -5,11 +5,14 @@ from .binding import (  # noqa: F401
     FOPD_F32,
     FopdError,
     Hparams,
+    RefreshConfig,
+    RefreshState,
     fopd_freshness_score,
     fopd_loss_fwd_bwd,
     fopd_profile_enable,
     fopd_profile_read,
     fopd_profile_reset,
+    fopd_refresh_decide,
     fopd_set_option,
     fopd_status_string,
     fopd_token_logprobs,

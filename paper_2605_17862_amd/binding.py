@@ -19,6 +19,7 @@ SYMBOLS = (
     "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
+    "fopd_refresh_decide",
 )
 
 
@@ -26,6 +27,19 @@ class Hparams(ctypes.Structure):
     """fopd_hparams: alpha, beta (score coefficients), xi (gate), lambda (anchor strength)."""
     _fields_ = [("alpha", ctypes.c_float), ("beta", ctypes.c_float),
                 ("xi", ctypes.c_float), ("lambda_", ctypes.c_float)]
+
+
+class RefreshConfig(ctypes.Structure):
+    """fopd_refresh_config: thresholds kappa_f, kappa_roll, kappa_sup and the rate limit in steps."""
+    _fields_ = [("kappa_f", ctypes.c_float), ("kappa_roll", ctypes.c_float), ("kappa_sup", ctypes.c_float),
+                ("min_interval", ctypes.c_int64)]
+
+
+class RefreshState(ctypes.Structure):
+    _fields_ = [("last_refresh_step", ctypes.c_int64), ("refreshes", ctypes.c_int64)]
+
+    def __init__(self):
+        super().__init__(-1, 0)
 
 
 class FopdError(RuntimeError):
@@ -67,6 +81,9 @@ def load_library():
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                       vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_refresh_decide.restype = ctypes.c_int
+    lib.fopd_refresh_decide.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(RefreshConfig),
+                                        ctypes.POINTER(RefreshState), i64, ctypes.POINTER(i32)]
     lib.fopd_set_option.restype = ctypes.c_int
     lib.fopd_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int]
     lib.fopd_profile_enable.restype = ctypes.c_int
@@ -188,6 +205,17 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
     _check(st, "fopd_loss_fwd_bwd")
+
+
+def fopd_refresh_decide(agg_host, cfg, state, step):
+    """Host only.  agg_host: three floats (a host copy of `agg`).  Returns (refresh?, reason bits)."""
+    arr = (ctypes.c_float * 3)(*[float(x) for x in agg_host])
+    reason = ctypes.c_int32(0)
+    r = load_library().fopd_refresh_decide(arr, ctypes.byref(cfg), ctypes.byref(state), int(step),
+                                           ctypes.byref(reason))
+    if r < 0:
+        raise FopdError(1, "fopd_refresh_decide")
+    return bool(r), int(reason.value)
 
 
 def fopd_set_option(name, value):

@@ -359,6 +359,23 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
 }
 
+int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,
+                        int64_t step, int32_t* reason_host) {
+  if (agg_host == nullptr || cfg_host == nullptr || state_host == nullptr || cfg_host->min_interval < 1) return -1;
+  int32_t reason = 0;
+  if (agg_host[0] <= cfg_host->kappa_f) reason |= 1;
+  if (agg_host[1] < cfg_host->kappa_roll) reason |= 2;
+  if (agg_host[2] < cfg_host->kappa_sup) reason |= 4;
+  if (reason_host != nullptr) *reason_host = reason;
+  if (reason == 0) return 0;
+  const bool rested = state_host->last_refresh_step < 0 ||
+                      step - state_host->last_refresh_step >= cfg_host->min_interval;
+  if (!rested) return 0;
+  state_host->last_refresh_step = step;
+  state_host->refreshes += 1;
+  return 1;
+}
+
 fopd_status fopd_set_option(const char* name, int value) {
   if (name == nullptr) return FOPD_EINVAL;
   const std::string key(name);
