@@ -118,6 +118,9 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *
  *   logp, behav_logp, teacher_logp  [T] f32: current student, rollout-time student and
  *                                   current-context teacher log-probability of y_t
+ *   roll_kl                         [T] f32 or NULL: per-row full-vocabulary KL(pi^t || pi^r) from
+ *                                   fopd_rollout_kl; when given it is the token drift that D^roll
+ *                                   averages and behav_logp is not read (it may then be NULL)
  *   teacher_logp_stale              [T] f32 or NULL: teacher log-probability under the context
  *                                   used at grading time; NULL gives D^sup = 0
  *   mask [T] uint8 or NULL; seq_lens [B] int32 (sum must be T); lag [B] int32 >= 0
@@ -126,7 +129,7 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *            agg [3] f32 = mean_i f_i, mean_i cover_i (roll), mean_i cover_i (sup).
  *   Any of the output pointers except freshness may be NULL.
  */
-fopd_status fopd_freshness_score(const float* logp, const float* behav_logp,
+fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
                                  const float* teacher_logp, const float* teacher_logp_stale,
                                  const uint8_t* mask, const int32_t* seq_lens, const int32_t* lag,
                                  int64_t T, int32_t B, fopd_hparams hp,
@@ -174,6 +177,37 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               float* loss, float* freshness, float* weights, float* logp,
                               void* dlogits,
                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Full-vocabulary rollout drift, Eq. "kl-diagnostics" first line as printed: per row
+ *   roll_kl_t = KL( softmax(z_t) || softmax(z'_t) ),   z' = logits of the stale checkpoint pi^{r(i)}
+ * replayed on the same prefixes.  One pass over both tensors (masked rows are not read).
+ *   logits, logits_stale  [T, ld] / [T, ld_stale] of `dt`
+ *   roll_kl, logp, lse    [T] f32 out as in fopd_token_logprobs (0 for masked rows)
+ *   dlse                  [T] f32 out: lse_t - lse'_t
+ * Feed roll_kl to fopd_freshness_score to score the buffer with the paper's own diagnostic.
+ */
+fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
+                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
+                            float* roll_kl, float* logp, float* lse, float* dlse,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The whole pass with D_i^roll = token mean of that full-vocabulary KL, everything computed in the call
+ * (segment offsets, log-probs, drift, scores, weights, loss, gradient).  The anchor term lambda D_i^roll is
+ * differentiated through the full KL:
+ *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (log p_u - log p'_u - roll_kl_t),
+ *   c1_t = g m_t w_i / (B n_i) A_t,   c2_t = g m_t w_i / (B n_i) lambda.
+ * Arguments as in fopd_loss_fwd_bwd; behav_logp is not needed.  logp, roll_kl, freshness, weights may be
+ * NULL.  dlogits may alias logits but not logits_stale.  Whole samples only: sum(seq_lens) must be T.
+ */
+fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T,
+                                      int64_t V, int64_t ld, int64_t ld_stale, const int32_t* token_ids,
+                                      const uint8_t* mask, const float* teacher_logp,
+                                      const float* teacher_logp_stale, const int32_t* seq_lens, const int32_t* lag,
+                                      int32_t B, fopd_hparams hp, float grad_scale,
+                                      float* loss, float* freshness, float* weights, float* logp, float* roll_kl,
+                                      void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Adaptive refresh test (Sec. 4.2, refresh condition; Algorithm 1, step after the aggregates; App. B:

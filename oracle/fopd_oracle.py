@@ -232,6 +232,99 @@ def anchored_loss(w, ell, D_roll, lam):
     return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / B
 
 
+# ----------------------------------------------------------------------------------------
+# full-vocabulary rollout drift: Eq. "kl-diagnostics", first line, as printed (needs the stale
+# checkpoint's logits on the same prefixes)
+# ----------------------------------------------------------------------------------------
+
+def rollout_kl_full(logits, logits_stale, mask=None):
+    """KL(pi^t(.|x_t) || pi^r(.|x_t)) per row from the two logits tensors; also lse of both.
+    Masked rows give 0.  Entries whose current probability is 0 contribute 0."""
+    logits = np.asarray(logits)
+    logits_stale = np.asarray(logits_stale)
+    T = logits.shape[0]
+    kl = np.zeros(T)
+    lse = np.zeros(T)
+    lse_stale = np.zeros(T)
+    for t in range(T):
+        if mask is not None and mask[t] == 0:
+            continue
+        z = logits[t].astype(np.float64)
+        zs = logits_stale[t].astype(np.float64)
+        lse[t] = row_logsumexp(z)
+        lse_stale[t] = row_logsumexp(zs)
+        logp = z - lse[t]
+        logq = zs - lse_stale[t]
+        p = np.exp(logp)
+        kl[t] = float(np.sum(np.where(p > 0.0, p * (np.where(p > 0.0, logp, 0.0) - logq), 0.0)))
+    return kl, lse, lse_stale
+
+
+def dlogits_row_full_kl(z, zs, y, lse_t, lse_stale_t, kl_t, c1_t, c2_t):
+    """One gradient row when the anchor is the full-vocabulary KL:
+    c1 (p - onehot) + c2 p (log p - log p' - KL_t);  d KL(p||p')/dz_u = p_u (log p_u - log p'_u - KL)."""
+    z = np.asarray(z, dtype=np.float64)
+    zs = np.asarray(zs, dtype=np.float64)
+    if c1_t == 0.0 and c2_t == 0.0:
+        return np.zeros_like(z)
+    logp = z - lse_t
+    p = np.exp(logp)
+    g = p * (c1_t + c2_t * ((logp - (zs - lse_stale_t)) - kl_t))
+    g[y] -= c1_t
+    return g
+
+
+def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, token_ids, mask, teacher_logp, teacher_logp_stale,
+                              seq_lens, lag, alpha, beta, xi, lam, grad_scale=1.0, out_dtype="f32",
+                              want_dlogits=True):
+    """The whole pass with D_i^roll taken as the token mean of the full-vocabulary KL (Eq.
+    "kl-diagnostics" as printed) instead of the sampled-token estimator, in Algorithm 1's order.  The
+    anchor term lambda D_i^roll is then differentiated through the full KL."""
+    logits = np.asarray(logits)
+    T, V = logits.shape
+    if mask is None:
+        mask = np.ones(T, dtype=np.uint8)
+    cu = segment_offsets(seq_lens)
+    if int(cu[-1]) != T:
+        raise ValueError("sequence lengths do not add up to T")
+    lse, lp = token_logprobs(logits, token_ids, mask)
+    kl, lse2, lse_stale = rollout_kl_full(logits, logits_stale, mask)
+    lq = np.asarray(teacher_logp, dtype=np.float64)
+    adv = lq - lp
+    if teacher_logp_stale is None:
+        k_sup = np.zeros(T)
+    else:
+        k_sup = kl_estimator(lq - np.asarray(teacher_logp_stale, dtype=np.float64))
+    D_roll, D_sup, ell, cover, n = sample_statistics(lp, lq, kl, k_sup, mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
+    agg = buffer_aggregates(f, cover)
+    w = freshness_weights(f, xi, n)
+    loss = anchored_loss(w, ell, D_roll, lam)
+    B = len(n)
+    c1 = np.zeros(T)
+    c2 = np.zeros(T)
+    for i in range(B):
+        if int(n[i]) == 0 or w[i] == 0.0:
+            continue
+        for t in range(int(cu[i]), int(cu[i + 1])):
+            if mask[t] == 0:
+                continue
+            pref = grad_scale * w[i] / (B * int(n[i]))
+            c1[t] = pref * adv[t]
+            c2[t] = pref * lam
+    res = dict(cu_seqlens=cu, n_train=n, lse=lse, lse_stale=lse_stale, logp=lp, adv=adv, roll_kl=kl,
+               D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover, freshness=f, agg=agg, weights=w, loss=loss,
+               c1=c1, c2=c2)
+    if want_dlogits:
+        g = np.zeros((T, V))
+        for t in range(T):
+            g[t] = dlogits_row_full_kl(logits[t], np.asarray(logits_stale)[t], int(token_ids[t]), lse[t],
+                                       lse_stale[t], kl[t], c1[t], c2[t])
+        res["dlogits_exact"] = g
+        res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
+    return res
+
+
 def refresh_decision(agg, kappa_f, kappa_roll, kappa_sup, step, last_refresh_step, min_interval):
     """Adaptive refresh test (Sec. 4.2 refresh condition; App. B rate limit).  Returns (refresh, reasons):
     reasons lists which of "f", "roll", "sup" hold; refresh is True when any holds and at least

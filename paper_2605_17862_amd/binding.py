@@ -19,7 +19,7 @@ SYMBOLS = (
     "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
-    "fopd_refresh_decide",
+    "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl",
 )
 
 
@@ -76,8 +76,13 @@ def load_library():
     lib.fopd_token_logprobs.restype = ctypes.c_int
     lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
-    lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
+    lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_rollout_kl.restype = ctypes.c_int
+    lib.fopd_rollout_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_loss_fwd_bwd_full_kl.restype = ctypes.c_int
+    lib.fopd_loss_fwd_bwd_full_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32,
+                                              Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                       vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -170,14 +175,15 @@ def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather
     _check(st, "fopd_token_logprobs")
 
 
-def fopd_freshness_score(logp, behav_logp, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B, hp,
-                         cu_seqlens, n_train, D_roll, D_sup, ell, cover, freshness, agg, workspace,
+def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B,
+                         hp, cu_seqlens, n_train, D_roll, D_sup, ell, cover, freshness, agg, workspace,
                          stream=None):
     import torch
     f32 = torch.float32
     p, n = _ws(workspace)
     st = load_library().fopd_freshness_score(
-        _ptr(logp, f32, "logp"), _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(logp, f32, "logp"), _ptr(behav_logp, f32, "behav_logp"), _ptr(roll_kl, f32, "roll_kl"),
+        _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(mask, torch.uint8, "mask"),
         _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(T), int(B), _hp(hp),
         _ptr(cu_seqlens, torch.int64, "cu_seqlens"), _ptr(n_train, torch.int32, "n_train"),
@@ -205,6 +211,38 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
     _check(st, "fopd_loss_fwd_bwd")
+
+
+def fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, roll_kl, logp, lse, dlse,
+                    workspace, stream=None):
+    import torch
+    f32 = torch.float32
+    mat = (torch.float32, torch.bfloat16)
+    p, n = _ws(workspace)
+    st = load_library().fopd_rollout_kl(
+        _ptr(logits, mat, "logits"), _ptr(logits_stale, mat, "logits_stale"), int(dt), int(T), int(V), int(ld),
+        int(ld_stale), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(roll_kl, f32, "roll_kl"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"), _ptr(dlse, f32, "dlse"),
+        p, n, _stream(stream))
+    _check(st, "fopd_rollout_kl")
+
+
+def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, teacher_logp,
+                              teacher_logp_stale, seq_lens, lag, B, hp, grad_scale, loss, freshness, weights, logp,
+                              roll_kl, dlogits, workspace, stream=None):
+    import torch
+    f32 = torch.float32
+    mat = (torch.float32, torch.bfloat16)
+    p, n = _ws(workspace)
+    st = load_library().fopd_loss_fwd_bwd_full_kl(
+        _ptr(logits, mat, "logits"), _ptr(logits_stale, mat, "logits_stale"), int(dt), int(T), int(V), int(ld),
+        int(ld_stale), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(teacher_logp, f32, "teacher_logp"), _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), float(grad_scale),
+        _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
+        _ptr(logp, f32, "logp"), _ptr(roll_kl, f32, "roll_kl"), _ptr(dlogits, mat, "dlogits"), p, n,
+        _stream(stream))
+    _check(st, "fopd_loss_fwd_bwd_full_kl")
 
 
 def fopd_refresh_decide(agg_host, cfg, state, step):

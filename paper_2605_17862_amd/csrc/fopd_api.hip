@@ -19,7 +19,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Carving of the caller's workspace.  Every region starts on a 256-byte boundary.
 struct Workspace {
-  size_t flags, cu, n_train, fresh64, coef, lse, logp, partials, total;
+  size_t flags, cu, n_train, fresh64, coef, lse, logp, coef2, dlse, kl, partials, total;
   Workspace(int64_t T, int32_t B) {
     const size_t t = static_cast<size_t>(T < 0 ? 0 : T), b = static_cast<size_t>(B < 0 ? 0 : B);
     size_t off = 0;
@@ -35,6 +35,9 @@ struct Workspace {
     coef = take(t * sizeof(float));
     lse = take(t * sizeof(float));
     logp = take(t * sizeof(float));
+    coef2 = take(t * sizeof(float));
+    dlse = take(t * sizeof(float));
+    kl = take(t * sizeof(float));
     partials = take((t + 1) * sizeof(double));     // per-block or per-row loss terms
     total = off;
   }
@@ -231,15 +234,15 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
                    at<int32_t>(workspace, w.flags), static_cast<hipStream_t>(stream));
 }
 
-fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* teacher_logp,
-                                 const float* teacher_logp_stale, const uint8_t* mask,
+fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
+                                 const float* teacher_logp, const float* teacher_logp_stale, const uint8_t* mask,
                                  const int32_t* seq_lens, const int32_t* lag, int64_t T, int32_t B,
                                  fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, float* D_roll,
                                  float* D_sup, float* ell, float* cover, float* freshness, float* agg,
                                  void* workspace, size_t workspace_bytes, void* stream) {
   if (T < 0 || B <= 0) return FOPD_ESHAPE;
-  if (logp == nullptr || behav_logp == nullptr || teacher_logp == nullptr || seq_lens == nullptr ||
-      lag == nullptr || freshness == nullptr)
+  if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || teacher_logp == nullptr ||
+      seq_lens == nullptr || lag == nullptr || freshness == nullptr)
     return FOPD_EINVAL;
   if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
   fopd_status st = check_workspace(workspace, workspace_bytes, T, B);
@@ -253,7 +256,7 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, teacher_logp, teacher_logp_stale, mask,
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask,
                                                cu, lag, T, hp, n_train, D_roll, D_sup, ell, cover,
                                                freshness, f64, nws);
   if ((st = launched()) != FOPD_OK) return st;
@@ -337,7 +340,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   // per-sample counts and scores
   const int32_t* n_use = n_train_in;
   if (whole) {
-    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, teacher_logp, teacher_logp_stale,
+    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, nullptr, teacher_logp, teacher_logp_stale,
                                                  mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
                                                  nullptr, nullptr, f64, nws);
     if ((st = launched()) != FOPD_OK) return st;
@@ -357,6 +360,95 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   if ((st = launched()) != FOPD_OK) return st;
 
   return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
+}
+
+fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
+                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
+                            float* roll_kl, float* logp, float* lse, float* dlse, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(logits_stale, dt, T, V, ld_stale)) != FOPD_OK) return st;
+  if (token_ids == nullptr || roll_kl == nullptr || logp == nullptr || lse == nullptr || dlse == nullptr)
+    return FOPD_EINVAL;
+  if ((st = check_workspace(workspace, workspace_bytes, T, 0)) != FOPD_OK) return st;
+  if (T == 0) return FOPD_OK;
+  Workspace w(T, 0);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  ScopedTimer timer(0, s);
+  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  if (dt == FOPD_BF16)
+    fopd_k5_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, T, static_cast<int>(V), ld, ld_stale,
+                                                          token_ids, mask, roll_kl, logp, lse, dlse,
+                                                          at<int32_t>(workspace, w.flags));
+  else
+    fopd_k5_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, T, static_cast<int>(V), ld, ld_stale,
+                                                         token_ids, mask, roll_kl, logp, lse, dlse,
+                                                         at<int32_t>(workspace, w.flags));
+  return launched();
+}
+
+fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T,
+                                      int64_t V, int64_t ld, int64_t ld_stale, const int32_t* token_ids,
+                                      const uint8_t* mask, const float* teacher_logp,
+                                      const float* teacher_logp_stale, const int32_t* seq_lens, const int32_t* lag,
+                                      int32_t B, fopd_hparams hp, float grad_scale, float* loss, float* freshness,
+                                      float* weights, float* logp, float* roll_kl, void* dlogits, void* workspace,
+                                      size_t workspace_bytes, void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(logits_stale, dt, T, V, ld_stale)) != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0) return FOPD_ESHAPE;
+  if (token_ids == nullptr || teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  if (dlogits == logits_stale) return FOPD_EINVAL;      // the stale logits are read by both passes
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+
+  Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  double* f64 = at<double>(workspace, w.fresh64);
+  float* c1 = at<float>(workspace, w.coef);
+  float* c2 = at<float>(workspace, w.coef2);
+  float* lse_ws = at<float>(workspace, w.lse);
+  float* dlse_ws = at<float>(workspace, w.dlse);
+  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+  float* kl_ws = (roll_kl != nullptr) ? roll_kl : at<float>(workspace, w.kl);
+  double* partials = at<double>(workspace, w.partials);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  st = fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, kl_ws, logp_ws, lse_ws,
+                       dlse_ws, workspace, workspace_bytes, stream);
+  if (st != FOPD_OK) return st;
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, nullptr, kl_ws, teacher_logp, teacher_logp_stale, mask, cu,
+                                               lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                               f64, nws);
+  if ((st = launched()) != FOPD_OK) return st;
+  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
+  if (T > 0) {
+    fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp_ws, kl_ws, teacher_logp, mask, cu, nws, f64, T, B, hp, grad_scale, c1, c2, partials);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, f64, nullptr, B, hp.xi, loss, weights, freshness);
+  if ((st = launched()) != FOPD_OK) return st;
+  if (T == 0) return FOPD_OK;
+  ScopedTimer timer(1, s);
+  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  if (dt == FOPD_BF16)
+    fopd_k6_grad_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, dlogits, T, static_cast<int>(V),
+                                                               ld, ld_stale, token_ids, lse_ws, dlse_ws, kl_ws,
+                                                               logp_ws, c1, c2);
+  else
+    fopd_k6_grad_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, dlogits, T, static_cast<int>(V),
+                                                              ld, ld_stale, token_ids, lse_ws, dlse_ws, kl_ws,
+                                                              logp_ws, c1, c2);
+  return launched();
 }
 
 int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,

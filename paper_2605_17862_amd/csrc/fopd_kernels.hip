@@ -575,6 +575,314 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 }
 
 // =========================================================================================
+// K5 / K6: the same two passes when the rollout drift is the full-vocabulary KL of Eq.
+// "kl-diagnostics" as printed, KL(pi^t || pi^r) per row, from a second logits tensor z' (the
+// stale checkpoint replayed on the same prefixes).  With d_v = z_v - z'_v and p = softmax(z):
+//     lse' - lse = log E_p[e^-d],      KL = E_p[d] + log E_p[e^-d].
+// K5 accumulates, on z's running reference, S = sum e_v, W = sum e_v d_v and U = sum (e'_v - e_v)
+// with e'_v = 2^(z'_v log2e - ref): the small quantity E_p[e^-d - 1] = U / S is summed directly,
+// so KL does not come out as the difference of two independently rounded log-sum-exps.
+// =========================================================================================
+
+struct LaneStateKl {
+  float r = -1.0e38f;
+  float rL = -1.0e38f * 1.4426950408889634f;
+  float s = 0.f, w = 0.f, u = 0.f;
+};
+
+template <int N>
+__device__ __forceinline__ void accumulate_kl(const float* x, const float* xs, LaneStateKl& st) {
+  float bm = x[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i) bm = fmaxf(bm, x[i]);
+  if (bm > st.r) {
+    const float nrL = bm * kLog2e;
+    const float scale = fast_exp2(st.rL - nrL);
+    st.s *= scale;
+    st.w *= scale;
+    st.u *= scale;
+    st.r = bm;
+    st.rL = nrL;
+  }
+  float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const float e = fast_exp2(fmaf(x[i], kLog2e, -st.rL));
+    const float es = fast_exp2(fmaf(xs[i], kLog2e, -st.rL));
+    // both -inf (an excluded vocabulary entry) must give d = 0, not NaN
+    const float d = fmaxf(x[i], -1.0e30f) - fmaxf(xs[i], -1.0e30f);
+    if (i & 1) {
+      a1 += e;
+      w1 = fmaf(e, d, w1);
+      u1 += es - e;
+    } else {
+      a0 += e;
+      w0 = fmaf(e, d, w0);
+      u0 += es - e;
+    }
+  }
+  st.s += a0 + a1;
+  st.w += w0 + w1;
+  st.u += u0 + u1;
+}
+
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64_t ld, int64_t ld_stale,
+           const int32_t* token_ids, const uint8_t* mask, float* roll_kl, float* logp, float* lse, float* dlse,
+           int32_t* flags) {
+  constexpr int E = Elem<DT>::kPerVec;
+  constexpr int NT = kStreamThreads;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int y = token_ids[t];
+  bool live = (mask == nullptr) || (mask[t] != 0);
+  if (live && (y < 0 || y >= V)) {
+    if (tid == 0) atomicOr(flags, kFlagToken);
+    live = false;
+  }
+  if (!live) {
+    if (tid == 0) {
+      roll_kl[t] = 0.f;
+      logp[t] = 0.f;
+      lse[t] = 0.f;
+      dlse[t] = 0.f;
+    }
+    return;
+  }
+  __shared__ float sh_zy, sh_zsy;
+  __shared__ float sh_R[NT / 64], sh_S[NT / 64], sh_W[NT / 64], sh_U[NT / 64];
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const char* rows = static_cast<const char*>(logits_stale) + t * ld_stale * Elem<DT>::kBytes;
+  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  const u32x4* rsv = reinterpret_cast<const u32x4*>(rows);
+  const int nvec = V / E;
+  const int jy = y / E, ey = y % E;
+  const float kNegInf = -__builtin_inff();
+  LaneStateKl st;
+  constexpr int U2 = (U > 1) ? U / 2 : 1;      // two tensors: half the vectors of each per trip
+  int j = tid;
+  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT) {
+    u32x4 q[U2], qs[U2];
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+      q[u] = __builtin_nontemporal_load(rv + j + u * NT);
+      qs[u] = __builtin_nontemporal_load(rsv + j + u * NT);
+    }
+    float x[U2 * E], xs[U2 * E];
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+      unpack<DT>(q[u], x + u * E);
+      unpack<DT>(qs[u], xs + u * E);
+    }
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+      if (j + u * NT == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          if (e == ey) {
+            sh_zy = x[u * E + e];
+            sh_zsy = xs[u * E + e];
+            x[u * E + e] = kNegInf;         // the sampled token is left out of the lane sums
+            xs[u * E + e] = kNegInf;
+          }
+        }
+      }
+    }
+    accumulate_kl<U2 * E>(x, xs, st);
+  }
+  for (; j < nvec; j += NT) {
+    float x[E], xs[E];
+    unpack<DT>(__builtin_nontemporal_load(rv + j), x);
+    unpack<DT>(__builtin_nontemporal_load(rsv + j), xs);
+    if (j == jy) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        if (e == ey) {
+          sh_zy = x[e];
+          sh_zsy = xs[e];
+          x[e] = kNegInf;
+          xs[e] = kNegInf;
+        }
+      }
+    }
+    accumulate_kl<E>(x, xs, st);
+  }
+  {
+    const int idx = nvec * E + tid;
+    if (idx < V) {
+      float x1 = load_elem<DT>(row, idx), xs1 = load_elem<DT>(rows, idx);
+      if (idx == y) {
+        sh_zy = x1;
+        sh_zsy = xs1;
+        x1 = kNegInf;
+        xs1 = kNegInf;
+      }
+      accumulate_kl<1>(&x1, &xs1, st);
+    }
+  }
+  const float Rw = wave_max(st.rL);
+  const float scale = fast_exp2(st.rL - Rw);
+  const float Sw = wave_sum(st.s * scale), Ww = wave_sum(st.w * scale), Uw = wave_sum(st.u * scale);
+  const int lane = tid & 63, wv = tid >> 6;
+  if (lane == 0) {
+    sh_R[wv] = Rw;
+    sh_S[wv] = Sw;
+    sh_W[wv] = Ww;
+    sh_U[wv] = Uw;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float RR = sh_R[0];
+#pragma unroll
+    for (int i = 1; i < NT / 64; ++i) RR = fmaxf(RR, sh_R[i]);
+    float SS = 0.f, WW = 0.f, UU = 0.f;
+#pragma unroll
+    for (int i = 0; i < NT / 64; ++i) {
+      const float sc = fast_exp2(sh_R[i] - RR);
+      SS += sh_S[i] * sc;
+      WW += sh_W[i] * sc;
+      UU += sh_U[i] * sc;
+    }
+    const double zy = sh_zy, zsy = sh_zsy;
+    const double zyL = zy * static_cast<double>(kLog2e);
+    const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
+    const double q = exp2(-fabs(a2));
+    const double sp = (a2 > 0.0 ? a2 : 0.0) + log1p(q) * (1.0 / kLn2);
+    const double lp = -sp * kLn2;
+    const double p_not = (a2 > 0.0) ? 1.0 / (1.0 + q) : q / (1.0 + q);
+    const double p_y = (a2 > 0.0) ? q / (1.0 + q) : 1.0 / (1.0 + q);
+    // E_p[d] and E_p[e^-d - 1]: the other tokens through the lane sums, the sampled token directly
+    double ed = 0.0, eu = 0.0;
+    if (SS > 0.f) {
+      ed = p_not * (static_cast<double>(WW) / static_cast<double>(SS));
+      eu = p_not * (static_cast<double>(UU) / static_cast<double>(SS));
+    }
+    const double dy = zy - zsy;
+    ed += p_y * dy;
+    eu += p_y * expm1(-dy);
+    const double dl = -log1p(eu);                 // lse - lse'
+    double kl = ed - dl;
+    if (kl < 0.0) kl = 0.0;                       // rounding noise of identical rows
+    roll_kl[t] = static_cast<float>(kl);
+    logp[t] = static_cast<float>(lp);
+    lse[t] = static_cast<float>((zyL + sp) * kLn2);
+    dlse[t] = static_cast<float>(dl);
+  }
+}
+
+// Coefficients for the full-KL gradient: c1 = g pref A_t, c2 = g pref lambda; loss share of the row.
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_coef_loss_kl(const float* logp, const float* roll_kl, const float* teacher_logp, const uint8_t* mask,
+                  const int64_t* cu, const int32_t* n_train, const double* fresh64, int64_t T, int32_t B,
+                  fopd_hparams hp, float grad_scale, float* c1, float* c2, double* partials) {
+  __shared__ double sh[kStreamThreads / 64];
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
+  double lt = 0.0;
+  if (t < T) {
+    float a = 0.f, b = 0.f;
+    if ((mask == nullptr || mask[t] != 0) && t < cu[B]) {
+      const int i = sample_of_row(cu, B, t);
+      const int32_t n = n_train[i];
+      const double w = weight_of(fresh64[i], n, hp.xi);
+      if (w > 0.0) {
+        const double lp = logp[t], lq = teacher_logp[t], lam = hp.lambda;
+        const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
+        a = static_cast<float>(static_cast<double>(grad_scale) * pref * (lq - lp));
+        b = static_cast<float>(static_cast<double>(grad_scale) * pref * lam);
+        lt = pref * ((lp - lq) + lam * static_cast<double>(roll_kl[t]));
+      }
+    }
+    c1[t] = a;
+    c2[t] = b;
+  }
+  const double tot = block_sum<kStreamThreads>(lt, sh);
+  if (threadIdx.x == 0) partials[blockIdx.x] = tot;
+}
+
+// K6: dlogits[t,u] = p_u (c1 + c2 (d_u - (lse - lse') - KL_t)) - c1 [u == y], since
+// d KL(p||p') / dz_u = p_u (log p_u - log p'_u - KL) and log p_u - log p'_u = d_u - (lse - lse').
+template <int DT, int U>
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_k6_grad_kl(const void* logits, const void* logits_stale, void* dlogits, int64_t T, int V, int64_t ld,
+                int64_t ld_stale, const int32_t* token_ids, const float* lse, const float* dlse,
+                const float* roll_kl, const float* logp, const float* c1, const float* c2) {
+  constexpr int E = Elem<DT>::kPerVec;
+  constexpr int NT = kStreamThreads;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float a = c1[t], b = c2[t];
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  if (a == 0.f && b == 0.f) {
+    row_zero<DT, NT>(orow, V);
+    return;
+  }
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const char* rows = static_cast<const char*>(logits_stale) + t * ld_stale * Elem<DT>::kBytes;
+  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  const u32x4* rsv = reinterpret_cast<const u32x4*>(rows);
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int nvec = V / E;
+  const int y = token_ids[t];
+  const int jy = y / E, ey = y % E;
+  const float lseL = lse[t] * kLog2e;
+  const float k0 = a - b * (dlse[t] + roll_kl[t]);     // factor = k0 + c2 d_u
+  const float lp = logp[t];
+  auto grad_of = [&](float x, float xs) {
+    const float d = fmaxf(x, -1.0e30f) - fmaxf(xs, -1.0e30f);
+    return fast_exp2(fmaf(x, kLog2e, -lseL)) * fmaf(b, d, k0);
+  };
+  auto grad_y = [&](float x, float xs) {               // c1 (p_y - 1) + c2 p_y (...), accurate as p_y -> 1
+    const float d = x - xs;
+    return a * expm1f(lp) + b * __expf(lp) * (d - dlse[t] - roll_kl[t]);
+  };
+  constexpr int U2 = (U > 1) ? U / 2 : 1;
+  int j = tid;
+  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT) {
+    u32x4 q[U2], qs[U2];
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+      q[u] = __builtin_nontemporal_load(rv + j + u * NT);
+      qs[u] = __builtin_nontemporal_load(rsv + j + u * NT);
+    }
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+      float x[E], xs[E], g[E];
+      unpack<DT>(q[u], x);
+      unpack<DT>(qs[u], xs);
+#pragma unroll
+      for (int e = 0; e < E; ++e) g[e] = grad_of(x[e], xs[e]);
+      if (j + u * NT == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          if (e == ey) g[e] = grad_y(x[e], xs[e]);
+      }
+      __builtin_nontemporal_store(pack<DT>(g), ov + j + u * NT);
+    }
+  }
+  for (; j < nvec; j += NT) {
+    float x[E], xs[E], g[E];
+    unpack<DT>(__builtin_nontemporal_load(rv + j), x);
+    unpack<DT>(__builtin_nontemporal_load(rsv + j), xs);
+#pragma unroll
+    for (int e = 0; e < E; ++e) g[e] = grad_of(x[e], xs[e]);
+    if (j == jy) {
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (e == ey) g[e] = grad_y(x[e], xs[e]);
+    }
+    __builtin_nontemporal_store(pack<DT>(g), ov + j);
+  }
+  {
+    const int idx = nvec * E + tid;
+    if (idx < V) {
+      const float x1 = load_elem<DT>(row, idx), xs1 = load_elem<DT>(rows, idx);
+      store_elem<DT>(orow, idx, idx == y ? grad_y(x1, xs1) : grad_of(x1, xs1));
+    }
+  }
+}
+
+// =========================================================================================
 // Small kernels
 // =========================================================================================
 
@@ -640,7 +948,7 @@ fopd_count_train(const uint8_t* mask, const int64_t* cu, int64_t T, int32_t* n_t
 
 // One workgroup per sample: token means over the mask, then the freshness score.
 __global__ void __launch_bounds__(kSegThreads)
-fopd_segment_stats(const float* logp, const float* behav_logp, const float* teacher_logp,
+fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll_kl, const float* teacher_logp,
                    const float* teacher_logp_stale, const uint8_t* mask, const int64_t* cu,
                    const int32_t* lag, int64_t T, fopd_hparams hp, int32_t* n_train, float* D_roll,
                    float* D_sup, float* ell, float* cover, float* freshness, double* fresh64,
@@ -654,7 +962,9 @@ fopd_segment_stats(const float* logp, const float* behav_logp, const float* teac
   for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads) {
     if (mask != nullptr && mask[t] == 0) continue;
     const double lp = logp[t], lq = teacher_logp[t];
-    sr += kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
+    // rollout drift of the token: full-vocabulary KL if the caller has it, else the sampled estimator
+    sr += (roll_kl != nullptr) ? static_cast<double>(roll_kl[t])
+                               : kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
     if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
     sl += lp - lq;
     cnt += 1.0;

@@ -102,7 +102,9 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     """Builds one workload.  Returns a dict of tensors on `device` plus plain metadata.
 
     overrides replace entries of CONFIGS[name] (e.g. B=8, V=4096, len_hi=600) to make the
-    reduced-size replicas the tests use.
+    reduced-size replicas the tests use.  stale_logit_sigma=s (> 0) also returns `logits_stale`:
+    the logits a stale checkpoint would give on the same prefixes, logits + s * lag_i * N(0, 1)
+    per entry (identical to the current ones for lag 0), for the full-vocabulary drift diagnostic.
     """
     cfg = dict(CONFIGS[name])
     cfg.update(overrides)
@@ -120,12 +122,21 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     logits = torch.empty(T, ld, dtype=dtype, device=dev)
     if ld > V:
         logits[:, V:] = 0
+    stale_sigma = float(cfg.get("stale_logit_sigma", 0.0))
+    logits_stale = torch.zeros(T, ld, dtype=dtype, device=dev) if stale_sigma > 0 else None
+    lag_rows = torch.from_numpy(np.repeat(lag, seq_lens).astype(np.float32)).to(dev)
     token_ids = torch.empty(T, dtype=torch.int32, device=dev)
     ref_logp = torch.empty(T, dtype=torch.float32, device=dev)
     for a in range(0, T, row_block):
         b = min(a + row_block, T)
-        z = _logit_rows(cfg, b - a, V, gen, dev).to(dtype)
+        zraw = _logit_rows(cfg, b - a, V, gen, dev)
+        z = zraw.to(dtype)
         logits[a:b, :V] = z
+        if logits_stale is not None:
+            drift = torch.randn(b - a, V, generator=gen, device=dev) * (stale_sigma * lag_rows[a:b, None])
+            logits_stale[a:b, :V] = torch.where(lag_rows[a:b, None] > 0, (zraw + drift).to(dtype), z)
+            del drift
+        del zraw
         zf = z.float()
         u = torch.rand(b - a, V, generator=gen, device=dev).clamp_(1e-20, 1.0)
         y = torch.argmax(zf - torch.log(-torch.log(u)), dim=1)      # Gumbel-max draw from softmax(z)
@@ -144,7 +155,7 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
         stale = torch.clamp(teacher + cfg["stale_sigma"] * per_tok_lag * n3, max=0.0)
 
     return dict(name=name, cfg=cfg, T=T, V=V, ld=ld, B=int(cfg["B"]), dtype=cfg["dtype"],
-                logits=logits, token_ids=token_ids, mask=torch.from_numpy(mask).to(dev),
+                logits=logits, logits_stale=logits_stale, token_ids=token_ids, mask=torch.from_numpy(mask).to(dev),
                 behav_logp=behav, teacher_logp=teacher, teacher_logp_stale=stale,
                 seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
                 seq_lens_host=seq_lens, lag_host=lag, mask_host=mask,

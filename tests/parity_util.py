@@ -94,3 +94,39 @@ def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label="")
         assert not np.any(bad), "dlogits row %s%d: %d elements off, worst %.3e vs limit %.3e at v=%d (c=%.3e)" % (
             rows_label, r, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]),
             int(np.argmax(err * bad)), coef[r])
+
+
+def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_scale, n_samples, sample_of_row, store):
+    """Gradient rows of the full-vocabulary-KL variant against the oracle.  Tolerance: 2 ulp of the
+    storage type plus what the allowed errors of lp (fp32), f_i (1e-5 relative) and of the per-row
+    KL / lse difference (4e-6 absolute, fp32 sums) can move the row by."""
+    lam = hp[3]
+    for k, t in enumerate(rows):
+        c1, c2 = ref["c1"][t], ref["c2"][t]
+        exact = orc.dlogits_row_full_kl(z_rows[k], zs_rows[k], int(y[k]), ref["lse"][t], ref["lse_stale"][t],
+                                        ref["roll_kl"][t], c1, c2)
+        i = sample_of_row[t]
+        n, f, w = int(ref["n_train"][i]), ref["freshness"][i], ref["weights"][i]
+        if c1 == 0.0 and c2 == 0.0 and (n == 0 or f < hp[2] * (1 - 1e-4) or ref["lse"][t] == 0.0):
+            assert not np.any(got_rows[k]), "row %d must be exactly zero" % t
+            continue
+        pref = abs(grad_scale) / (n_samples * max(n, 1))
+        p = np.exp(z_rows[k] - ref["lse"][t])
+        pm = p.copy()
+        pm[int(y[k])] -= 1.0
+        ld = (z_rows[k] - ref["lse"][t]) - (zs_rows[k] - ref["lse_stale"][t]) - ref["roll_kl"][t]
+        eps_c1 = pref * (w * EPS_A + EPS_F * f * abs(ref["adv"][t]))
+        eps_c2 = pref * lam * EPS_F * f
+        floor = np.abs(pm) * eps_c1 + p * (np.abs(ld) * eps_c2 + abs(c2) * 8e-6) + 2.0 ** -126
+        u = 4.0 * np.spacing(max(abs(ref["lse"][t]), 1.0))
+        floor[int(y[k])] += (abs(c1) + eps_c1) * u
+        if store == "bf16":
+            want = orc.round_to_bf16(exact)
+            lim = 2.0 * orc.bf16_ulp(want) + floor
+        else:
+            want = orc.round_to_f32(exact)
+            lim = 2e-5 * np.abs(want) + floor
+        err = np.abs(got_rows[k] - want)
+        bad = err > lim
+        assert not np.any(bad), "full-KL dlogits row %d: %d elements off, worst %.3e vs limit %.3e at v=%d" % (
+            t, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]), int(np.argmax(err * bad)))

@@ -9,7 +9,8 @@ from oracle import fopd_oracle as orc
 from paper_2605_17862_amd import binding as fb
 from paper_2605_17862_amd import workloads as wl
 from paper_2605_17862_amd.loss_pass import DEFAULT_HPARAMS, LossPass
-from parity_util import assert_close, check_grad_rows, coef_uncertainty, np64, oracle_full
+from parity_util import (assert_close, check_grad_rows, check_grad_rows_full_kl, coef_uncertainty, np64,
+                         oracle_full)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -387,6 +388,74 @@ def test_two_passes_per_row_kernel_matches_separate_kernels(threads, rows_per_cu
     finally:
         fb.fopd_set_option("k14_threads", 256)
         fb.fopd_set_option("k14_rows_per_cu", 6)
+
+
+# ---------------------------------------------------------------------------------------
+# full-vocabulary rollout drift (the diagnostic as printed in the paper)
+# ---------------------------------------------------------------------------------------
+
+FULL_KL_CASES = {
+    "reasoning": dict(B=6, len_lo=12, len_hi=30, V=151936, stale_logit_sigma=0.03),
+    "tooluse": dict(B=4, turns=2, obs_lo=2, obs_hi=6, resp_lo=4, resp_hi=10, V=5003, ld=5008, stale_logit_sigma=0.05,
+                    lag_hi=24),
+    "coding": dict(B=2, total_len=48, resp_lo=6, resp_hi=14, obs_lo=3, obs_hi=8, V=40000, stale_logit_sigma=0.02),
+    "tiny": dict(B=4, len_lo=9, len_hi=9, V=4097, ld=4100, stale_logit_sigma=0.04),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FULL_KL_CASES))
+def test_full_vocabulary_drift_variant(name):
+    _say("full-vocabulary KL variant on a %s replica" % name)
+    w = wl.generate(name, DEV, seed=21, row_block=32, **FULL_KL_CASES[name])
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    hp, g = (1.0, 1.0, 0.05, 0.5), 2.0
+    z, zs = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+    ref = orc.fopd_loss_fwd_bwd_full_kl(z, zs, np64(w["token_ids"]), np64(w["mask"]), np64(w["teacher_logp"]),
+                                        np64(w["teacher_logp_stale"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                        hp[0], hp[1], hp[2], hp[3], g, out_dtype=w["dtype"])
+    lp = _pass_for(w)
+    kl = torch.empty(T, device=DEV)
+    dlse = torch.empty(T, device=DEV)
+    lp.dlogits.fill_(4.0)
+    fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                 w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, g,
+                                 lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    live = np64(w["mask"]) != 0
+    assert_close("logp", np64(lp.logp), ref["logp"], atol=1e-4)
+    # fp32 sums over the vocabulary: 2e-5 relative plus 3e-8 absolute on the per-row KL
+    assert_close("roll_kl", np64(kl), ref["roll_kl"], rtol=2e-5, atol=3e-8)
+    assert not np.any(np64(kl)[~live]) and np.all(np64(kl) >= 0)
+    assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(lp.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]))
+    check_grad_rows_full_kl(np64(lp.dlogits)[:, :V], z, zs, np64(w["token_ids"]), ref, range(T), hp, g, B, sample_of,
+                            w["dtype"])
+    if ld > V:
+        assert bool((lp.dlogits[:, V:] == 4.0).all())
+    # staged: drift pass on its own, then the scores with roll_kl in place of the sampled estimator
+    st = _pass_for(w, alloc_dlogits=False)
+    fb.fopd_rollout_kl(w["logits"], w["logits_stale"], st.dt, T, V, ld, ld, w["token_ids"], w["mask"], kl, st.logp,
+                       st.lse, dlse, st.workspace)
+    fb.fopd_freshness_score(st.logp, None, kl, w["teacher_logp"], w["teacher_logp_stale"], w["mask"], w["seq_lens"],
+                            w["lag"], T, B, hp, st.cu_seqlens, st.n_train, st.D_roll, st.D_sup, st.ell, st.cover,
+                            st.freshness, st.agg, st.workspace)
+    _sync_ok(st)
+    assert torch.equal(st.logp, lp.logp) and torch.equal(st.freshness, lp.freshness)
+    assert_close("D_roll", np64(st.D_roll), ref["D_roll"], rtol=2e-5, atol=3e-8)
+    assert_close("lse", np64(st.lse), ref["lse"], atol=1e-4)
+    assert_close("dlse", np64(dlse), (ref["lse"] - ref["lse_stale"]) * live, atol=2e-6, rtol=1e-5)
+    # a lag-0 sample has identical stale logits: exactly zero drift, fresh score
+    for i in np.flatnonzero((np64(w["lag"]) == 0) & (ref["n_train"] > 0)):
+        assert float(st.D_roll[i]) == 0.0
+    # in place over the current logits
+    zc = w["logits"].clone()
+    fb.fopd_loss_fwd_bwd_full_kl(zc, w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                 w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, g,
+                                 lp.loss, None, None, None, None, zc, lp.workspace)
+    _sync_ok(lp)
+    assert torch.equal(zc[:, :V], lp.dlogits[:, :V])
 
 
 def test_device_side_error_flags():

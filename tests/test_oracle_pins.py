@@ -434,3 +434,83 @@ def test_bf16_rounding_ties_and_no_double_rounding():
     assert orc.round_to_bf16(-x) == -(1.0 + e)
     np.testing.assert_array_equal(orc.bf16_ulp([1.0, 1.99, 2.0, 0.75, 0.0]),
                                   [e, e, 2 * e, e / 2, 2.0 ** -133])
+
+
+# ---------------------------------------------------------------------------------------
+# full-vocabulary rollout drift (Eq. kl-diagnostics as printed)
+# ---------------------------------------------------------------------------------------
+
+def test_full_kl_matches_library_pinsker_and_sampled_estimator():
+    import scipy.stats
+    rng = _rng(40)
+    T, V = 7, 60
+    z = rng.normal(0, 2, size=(T, V))
+    zs = z + rng.normal(0, 0.4, size=(T, V))
+    zs[3] = z[3] + 1.75                         # a constant shift is the same distribution
+    mask = np.array([1, 1, 1, 1, 0, 1, 1], dtype=np.uint8)
+    kl, lse, lse_s = orc.rollout_kl_full(z, zs, mask)
+    p = scipy.special.softmax(z, axis=1)
+    q = scipy.special.softmax(zs, axis=1)
+    ref = scipy.stats.entropy(p, q, axis=1)     # library KL(p || q)
+    live = mask == 1
+    np.testing.assert_allclose(kl[live], ref[live], rtol=1e-11, atol=1e-15)
+    rev = scipy.stats.entropy(q, p, axis=1)
+    assert np.max(np.abs(kl[live] - rev[live])[[0, 1, 2]]) > 1e-4       # direction: current || stale
+    assert kl[4] == 0.0 and abs(kl[3]) < 1e-14 and np.all(kl[live] >= -1e-15)
+    tv = 0.5 * np.abs(p - q).sum(axis=1)
+    assert np.all(tv[live] <= np.sqrt(kl[live] / 2) + 1e-12)           # Pinsker
+    np.testing.assert_allclose(lse[live], scipy.special.logsumexp(z, axis=1)[live], rtol=1e-14)
+    np.testing.assert_allclose(lse_s[live], scipy.special.logsumexp(zs, axis=1)[live], rtol=1e-14)
+    # the sampled-token estimator used by the default path has this KL as its mean under the stale policy
+    logp, logq = np.log(p), np.log(q)
+    for t in (0, 5):
+        est = sum(q[t, y] * orc.kl_estimator(logp[t, y] - logq[t, y]) for y in range(V))
+        assert abs(est - kl[t]) < 1e-12
+
+
+def test_full_kl_gradient_by_finite_differences():
+    """F(z) = sum_t m_t w_i/(B n_i) [ (lp_t - lq_t)^2 / 2 + lambda KL(softmax(z_t) || softmax(z'_t)) ], w frozen."""
+    rng = _rng(41)
+    seq = np.array([3, 2], dtype=np.int32)
+    T, V, B = 5, 6, 2
+    z = rng.normal(0, 1.5, size=(T, V))
+    zs = z + rng.normal(0, 0.5, size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    mask = np.array([1, 1, 0, 1, 1], dtype=np.uint8)
+    lq = scipy.special.log_softmax(z, axis=1)[np.arange(T), y] + rng.normal(-0.3, 0.4, T)
+    lag = np.array([1, 0], dtype=np.int32)
+    hp = dict(alpha=0.9, beta=0.0, xi=0.05, lam=0.8)
+    res = orc.fopd_loss_fwd_bwd_full_kl(z, zs, y, mask, lq, None, seq, lag, grad_scale=1.5, **hp)
+    w, n = res["weights"], res["n_train"]
+    sample_of = np.repeat(np.arange(B), seq)
+    assert np.all(w > 0)
+    np.testing.assert_allclose(res["D_roll"][0], np.mean(res["roll_kl"][[0, 1]]), rtol=1e-14)   # masked row 2 left out
+
+    def F(zz):
+        logp_all = scipy.special.log_softmax(zz, axis=1)
+        logq_all = scipy.special.log_softmax(zs, axis=1)
+        tot = 0.0
+        for t in range(T):
+            if not mask[t]:
+                continue
+            i = sample_of[t]
+            kl_t = float(np.sum(np.exp(logp_all[t]) * (logp_all[t] - logq_all[t])))
+            tot += 1.5 * w[i] / (B * n[i]) * (0.5 * (logp_all[t, y[t]] - lq[t]) ** 2 + hp["lam"] * kl_t)
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = z.copy(), z.copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (F(zp) - F(zm)) / (2 * h)
+    scale = np.max(np.abs(num))
+    assert np.max(np.abs(num - res["dlogits_exact"])) < 1e-5 * scale
+    assert np.all(res["dlogits_exact"][2] == 0.0) and np.max(np.abs(res["dlogits_exact"].sum(axis=1))) < 1e-15
+    # lambda = 0 reduces to the default path's gradient with no anchor
+    r0 = orc.fopd_loss_fwd_bwd_full_kl(z, zs, y, mask, lq, None, seq, lag, 0.0, 0.0, 0.05, 0.0)
+    lb = scipy.special.log_softmax(z, axis=1)[np.arange(T), y]
+    r1 = orc.fopd_loss_fwd_bwd(z, y, mask, lb, lq, None, seq, lag, 0.0, 0.0, 0.05, 0.0)
+    np.testing.assert_allclose(r0["dlogits_exact"], r1["dlogits_exact"], rtol=1e-13, atol=1e-18)
+    assert abs(r0["loss"] - r1["loss"]) < 1e-15
