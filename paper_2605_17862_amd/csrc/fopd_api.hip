@@ -147,11 +147,16 @@ fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V
                          int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss,
                          int32_t* flags, hipStream_t s) {
   auto kern = fopd_k14_fused<DT, NT, kUnroll>;
-  // dynamic LDS is requested only to cap the workgroups resident per compute unit
-  size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          static_cast<int>(pad)) != hipSuccess)
-    return FOPD_EHIP;
+  // dynamic LDS is requested only to cap the workgroups resident per compute unit; the kernel is told
+  // once (per instantiation) that it may be given up to a whole CU's worth
+  static bool allowed = false;
+  if (!allowed) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(kLdsPerCu - 1024)) != hipSuccess)
+      return FOPD_EHIP;
+    allowed = true;
+  }
+  const size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
   kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
                                                             token_ids, mask, lb, lq, cu, n_train, fresh32, B,
                                                             row_begin, hp, grad_scale, logp, row_loss, flags);

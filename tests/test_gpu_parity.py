@@ -458,6 +458,47 @@ def test_full_vocabulary_drift_variant(name):
     assert torch.equal(zc[:, :V], lp.dlogits[:, :V])
 
 
+def test_replay_from_a_hip_graph():
+    """The calls enqueue kernels and device copies only, so a caller may capture them in a HIP graph (worth
+    it for small problems, where the six launches of a step cost more than the kernels).  Replays,
+    with eager work and synchronisations in between, must reproduce the eager bits."""
+    _say("HIP graph capture and replay of the fused step and of the scores-supplied step")
+    w = wl.generate("tiny", DEV, seed=4)
+    eager = _pass_for(w)
+    eager.loss_fwd_bwd(w, HP)
+    torch.cuda.synchronize()
+    f_in = eager.freshness.clone()
+    sc = _pass_for(w)
+    fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                         w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, 0, None, None,
+                         1.0, sc.loss, None, sc.weights, sc.logp, sc.dlogits, sc.workspace)   # also warms the kernel up
+    torch.cuda.synchronize()
+    g1, g2 = _pass_for(w), _pass_for(w)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        g1.loss_fwd_bwd(w, HP)
+        fb.fopd_loss_fwd_bwd(w["logits"], g2.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                             w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, 0, None, None,
+                             1.0, g2.loss, None, g2.weights, g2.logp, g2.dlogits, g2.workspace)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        g1.dlogits.fill_(float(rep))                 # eager work between the replays
+        g2.dlogits.fill_(float(rep))
+        g1.loss.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g1.dlogits, eager.dlogits) and torch.equal(g1.loss, eager.loss)
+        assert torch.equal(g1.freshness, eager.freshness) and torch.equal(g1.logp, eager.logp)
+        assert torch.equal(g2.dlogits, sc.dlogits) and torch.equal(g2.loss, sc.loss)
+    _sync_ok(g1)
+    _sync_ok(g2)
+
+
 def test_device_side_error_flags():
     _say("device flags: token range, segments, lag")
     w = wl.generate("reasoning", DEV, seed=12, B=3, len_lo=4, len_hi=6, V=512)
