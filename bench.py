@@ -66,6 +66,50 @@ def cpu_baseline(w, hp, budget_rows=6000):
                        "%.1f s single-threaded numpy float64" % (len(chosen), rows, w["V"], dt))
 
 
+def bench_full_kl(args, torch, fb, wl, LossPass, hp):
+    """One JSON line for fopd_loss_fwd_bwd_full_kl on the same workload plus stale-checkpoint logits."""
+    w = wl.generate(args.workload, "cuda:0", seed=0, stale_logit_sigma=0.03)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    lp = LossPass(T, V, B, w["dtype"], ld=ld, device="cuda:0")
+    kl = torch.empty(T, device="cuda:0")
+
+    def step():
+        fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                     w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, 1.0,
+                                     lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fb.fopd_profile_enable(False)
+    k5_ms, n5 = fb.fopd_profile_read(0)
+    k6_ms, n6 = fb.fopd_profile_read(1)
+    e = 2 if w["dtype"] == "bf16" else 4
+    live = int((w["mask_host"] != 0).sum())
+    k5_bytes = live * 2 * V * e
+    k6_bytes = live * 3 * V * e + (T - live) * V * e
+    k5_s, k6_s = k5_ms / max(n5, 1) * 1e-3, k6_ms / max(n6, 1) * 1e-3
+    print(json.dumps({
+        "metric": "tokens/s, OPD loss fwd+bwd with full-vocabulary rollout KL, V=%d %s" % (V, w["dtype"]),
+        "value": w["n_trainable"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload + "+stale_logits", "B": B, "T_rows": T, "V": V, "storage": w["dtype"],
+                   "call": "fopd_loss_fwd_bwd_full_kl"},
+        "roofline": {"bound": "hbm", "kernel": "fopd_k6_grad_kl", "achieved": k6_bytes / k6_s / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k6_bytes / k6_s / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": k6_bytes, "avg_ms": k6_s * 1e3},
+        "kernels": {"fopd_k5_kl": {"avg_ms": k5_s * 1e3, "GB/s": k5_bytes / k5_s / 1e9,
+                                   "frac": k5_bytes / k5_s / 1e9 / HBM_PEAK_GBS}}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +117,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="reasoning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variant", choices=("default", "full_kl"), default="default",
+                    help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
+                         "(stale-checkpoint) logits tensor; reported as its own line, not the headline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the loss pass shards by sample with no "
@@ -87,6 +134,8 @@ def main():
         sys.exit("bench.py needs a GPU")
     fb.load_library()
     hp = DEFAULT_HPARAMS
+    if args.variant == "full_kl":
+        return bench_full_kl(args, torch, fb, wl, LossPass, hp)
     w = wl.generate(args.workload, "cuda:0", seed=0)
     T, V, B = w["T"], w["V"], w["B"]
     lp = LossPass(T, V, B, w["dtype"], ld=w["ld"], device="cuda:0")

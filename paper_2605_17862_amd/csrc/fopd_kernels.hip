@@ -1048,8 +1048,16 @@ __global__ void __launch_bounds__(kSegThreads)
 fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, const double* fresh64,
                 const float* fresh32, int32_t B, float xi, float* loss, float* weights, float* freshness) {
   __shared__ double sh[kSegThreads / 64];
-  double s = 0.0;
-  for (int64_t i = threadIdx.x; i < nparts; i += kSegThreads) s += partials[i];
+  // eight independent partial sums per lane keep eight loads in flight (nparts is T in the
+  // two-passes-per-row path); the order of additions is still fixed
+  double acc[8] = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+  int64_t i = threadIdx.x;
+  for (; i + 7 * kSegThreads < nparts; i += 8 * kSegThreads) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc[k] += partials[i + k * kSegThreads];
+  }
+  for (int k = 0; i < nparts; i += kSegThreads, ++k) acc[k & 7] += partials[i];
+  const double s = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
   const double tot = block_sum<kSegThreads>(s, sh);
   if (threadIdx.x == 0) loss[0] = static_cast<float>(tot);
   for (int i = threadIdx.x; i < B; i += kSegThreads) {
