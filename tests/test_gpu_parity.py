@@ -786,3 +786,40 @@ def test_largevocab_full_size_in_place():
     w_gpu = np64(lp.weights)
     Ls = float(np.sum(w_gpu * (np64(st.ell) + HP[3] * np64(st.D_roll))) / B)
     assert abs(float(lp.loss) - Ls) <= 2e-6 * abs(Ls)
+
+
+def test_full_vocabulary_drift_variant_at_full_size():
+    _say("full-vocabulary KL variant at full size (reasoning + stale logits, 3 x 49.8 GB): generating ...")
+    w = wl.generate("reasoning", DEV, seed=0, stale_logit_sigma=0.03)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    hp = HP
+    lp = _pass_for(w)
+    kl = torch.empty(T, device=DEV)
+    fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                 w["teacher_logp"], None, w["seq_lens"], w["lag"], B, hp, 1.0, lp.loss, lp.freshness,
+                                 lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    seq, lag = w["seq_lens_host"], w["lag_host"]
+    cu = orc.segment_offsets(seq)
+    stale_ones = [i for i in np.argsort(seq, kind="stable") if lag[i] > 0][:2]
+    fresh_one = [i for i in np.argsort(seq, kind="stable") if lag[i] == 0][:1]
+    f_gpu, w_gpu = np64(lp.freshness), np64(lp.weights)
+    for i in [int(x) for x in stale_ones + fresh_one]:
+        a, b = int(cu[i]), int(cu[i + 1])
+        z, zs = np64(w["logits"][a:b]), np64(w["logits_stale"][a:b])
+        y = np64(w["token_ids"][a:b])
+        ref = orc.fopd_loss_fwd_bwd_full_kl(z, zs, y, None, np64(w["teacher_logp"][a:b]), None, seq[i:i + 1],
+                                            lag[i:i + 1], hp[0], hp[1], hp[2], hp[3], 1.0 / B, want_dlogits=False)
+        # (one sample passed alone: its 1/B normaliser is restored through grad_scale = 1/B above)
+        assert_close("roll_kl s%d" % i, np64(kl[a:b]), ref["roll_kl"], rtol=2e-5, atol=3e-8)
+        assert_close("logp s%d" % i, np64(lp.logp[a:b]), ref["logp"], atol=1e-4)
+        f = ref["freshness"][0]
+        assert abs(f_gpu[i] - f) <= 1e-5 * f and abs(w_gpu[i] - ref["weights"][0]) <= 1e-5 * f
+        if lag[i] == 0:
+            assert not bool(kl[a:b].any()) and abs(f_gpu[i] - 1.0) < 1e-12
+        picks = np.unique(np.linspace(0, b - a - 1, 4).astype(int))
+        got = np64(lp.dlogits[a:b][torch.from_numpy(picks).to(DEV)])
+        check_grad_rows_full_kl(got, z[picks], zs[picks], y[picks], ref, picks, hp, 1.0, B,
+                                np.zeros(b - a, dtype=int), "bf16")
+        _say("sample %d ok (lag %d, D_roll=%.3e, f=%.6f)" % (i, lag[i], ref["D_roll"][0], f))
+    _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights, n_rows=24)
