@@ -51,7 +51,7 @@ extern "C" {
 typedef enum {
   FOPD_OK = 0,
   FOPD_EINVAL = 1,       /* NULL required pointer, negative alpha/beta, inconsistent optional arguments */
-  FOPD_ESHAPE = 2,       /* T, V, B <= 0 (T = 0 is allowed and does nothing), ld < V, V > 2^31-16 */
+  FOPD_ESHAPE = 2,       /* T < 0 or T >= 2^31, V or B <= 0 (T = 0 is allowed and does nothing), ld < V, V > 2^31-16 */
   FOPD_EALIGN = 3,       /* base pointer or row pitch not 16-byte aligned */
   FOPD_EDTYPE = 4,       /* dtype is neither FOPD_F32 nor FOPD_BF16 */
   FOPD_EWORKSPACE = 5,   /* workspace NULL, misaligned (256 B) or smaller than fopd_workspace_bytes */

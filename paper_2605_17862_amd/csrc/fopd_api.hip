@@ -52,7 +52,7 @@ inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 
 fopd_status check_matrix(const void* m, fopd_dtype dt, int64_t T, int64_t V, int64_t ld) {
   if (dt != FOPD_F32 && dt != FOPD_BF16) return FOPD_EDTYPE;
-  if (T < 0 || V <= 0 || ld < V || V > 2147483647LL - 16) return FOPD_ESHAPE;
+  if (T < 0 || T > 2147483647LL || V <= 0 || ld < V || V > 2147483647LL - 16) return FOPD_ESHAPE;
   if (m == nullptr) return FOPD_EINVAL;
   const size_t es = (dt == FOPD_F32) ? 4 : 2;
   if (misaligned(m, 16) || (static_cast<size_t>(ld) * es) % 16 != 0) return FOPD_EALIGN;

@@ -12,6 +12,8 @@
 //   fopd_loss_final     loss scalar and weights
 // A third streaming kernel, fopd_k14_fused, does both passes over a row in one workgroup when the
 // freshness scores are supplied by the caller (second loop of Algorithm 1 on its own).
+// fopd_k5_kl / fopd_coef_loss_kl / fopd_k6_grad_kl are the same two passes when the rollout drift is
+// the full-vocabulary KL against a second (stale-checkpoint) logits tensor.
 //
 // There is no matrix contraction anywhere on this path, so no MFMA is used.  All reductions
 // run in a fixed order (wavefront shuffles, then LDS), so results are bit-reproducible.

@@ -58,6 +58,7 @@ def test_token_logprobs_rejects_bad_arguments_before_launch():
     assert _tok(lib, dt=2) == 4                  # EDTYPE
     assert _tok(lib, V=0) == 2                   # ESHAPE
     assert _tok(lib, T=-1) == 2
+    assert _tok(lib, T=1 << 31) == 2             # one workgroup per row: the grid holds 2^31 - 1
     assert _tok(lib, ld=56) == 2
     assert _tok(lib, logits=4096 + 8) == 3       # EALIGN
     assert _tok(lib, V=60, ld=60) == 3           # bf16 pitch 120 B

@@ -135,6 +135,29 @@ def test_ragged_vocabulary_and_padding(dtype, V, ld):
         assert bool((lp.dlogits[:, V:] == -7.0).all())
 
 
+def test_random_shapes_sweep():
+    """Forty seeded random problems: vocabulary size, padding, storage type, sample count and lengths,
+    masks, empty samples, lags (some gated), hyper-parameters and upstream scale all vary."""
+    rs = np.random.RandomState(77)
+    for case in range(40):
+        dtype = "bf16" if rs.rand() < 0.7 else "f32"
+        per = 8 if dtype == "bf16" else 4
+        V = int(rs.choice([1, 2, 5, 8, 9, 31, 64, 255, 1000, 2049, 4096, 10007, 32768, 65537]))
+        ld = ((V + per - 1) // per) * per + per * int(rs.randint(0, 3))
+        B = int(rs.randint(1, 7))
+        hp = (float(rs.choice([0.0, 0.5, 1.0, 2.0])), float(rs.choice([0.0, 1.0])),
+              float(rs.choice([0.0, 0.05, 0.2])), float(rs.choice([0.0, 0.1, 1.0])))
+        g = float(rs.choice([1.0, 0.125, -2.0]))
+        _say("random case %d: %s V=%d ld=%d B=%d hp=%s g=%g" % (case, dtype, V, ld, B, hp, g))
+        w = wl.generate("tooluse", DEV, seed=1000 + case, B=B, turns=int(rs.randint(1, 4)), obs_lo=0,
+                        obs_hi=int(rs.randint(0, 5)), resp_lo=0, resp_hi=int(rs.randint(1, 9)), V=V, ld=ld,
+                        dtype=dtype, boost=min(3, V), lag_lo=0, lag_hi=int(rs.choice([0, 3, 25])),
+                        stale_sigma=float(rs.choice([0.0, 0.1])), row_block=64)
+        if w["T"] == 0:
+            continue
+        _compare_everything(w, hp, grad_scale=g, staged=True)
+
+
 def test_empty_masked_and_gated_samples():
     _say("empty / fully masked / gated samples")
     w = wl.generate("reasoning", DEV, seed=6, B=6, len_lo=5, len_hi=12, V=2048)
@@ -161,6 +184,25 @@ def test_empty_masked_and_gated_samples():
     lp.loss_fwd_bwd(w, (1.0, 1.0, -0.5, 0.1))
     torch.cuda.synchronize()
     assert float(lp.weights[1]) == 0.0 and float(lp.weights[3]) == 0.0 and float(lp.weights[5]) > 0.5
+
+
+def test_zero_rows_is_a_valid_call():
+    """T = 0 (an empty chunk): nothing is read or written except loss = 0 and the per-sample outputs."""
+    B = 3
+    dummy = torch.zeros(64, dtype=torch.bfloat16, device=DEV)
+    f32 = torch.zeros(8, device=DEV)
+    i32 = torch.zeros(8, dtype=torch.int32, device=DEV)
+    lp = LossPass(1, 64, B, "bf16", device=DEV)
+    lp.loss.fill_(7.0)
+    fb.fopd_loss_fwd_bwd(dummy, lp.dt, 0, 64, 64, i32, None, f32, f32, None, i32[:B], i32[:B], B, HP, None, None, 0,
+                         None, None, 1.0, lp.loss, lp.freshness, lp.weights, None, dummy, lp.workspace)
+    _sync_ok(lp)
+    assert float(lp.loss) == 0.0 and not bool(lp.freshness.any()) and not bool(lp.weights.any())
+    fb.fopd_token_logprobs(dummy, lp.dt, 0, 64, 64, i32, None, f32, f32, None, None, lp.workspace)
+    fb.fopd_freshness_score(f32, f32, None, f32, None, None, i32[:B], i32[:B], 0, B, HP, lp.cu_seqlens, lp.n_train,
+                            None, None, None, lp.cover, lp.freshness, lp.agg, lp.workspace)
+    _sync_ok(lp)
+    assert not bool(lp.cu_seqlens.any()) and not bool(lp.n_train.any()) and not bool(lp.agg.any())
 
 
 def test_all_rows_masked_gives_zero_everything():
