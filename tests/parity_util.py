@@ -1,7 +1,9 @@
 """Shared pieces of the GPU parity tests: tensor -> float64 adapters for the oracle and the
 tolerances, written out where they are applied.
 
-Tolerances (the arithmetic behind them is in DESIGN.md, section "Tolerances"):
+Tolerances.  The kernels sum the vocabulary in fp32 and keep lp, lse in fp32: lp carries up to 1e-6 of
+rounding (|lse| < 32) plus a 2e-7 bias from log2(e) held as a float; everything per token and per sample
+after that is fp64.  Hence:
   integers (cu_seqlens, n_train, gather_idx)      bit-exact
   logp, lse                                       1e-4 absolute
   freshness, loss                                 1e-5 relative
