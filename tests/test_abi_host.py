@@ -137,3 +137,26 @@ def test_set_option_checks_names_and_values():
     assert lib.fopd_set_option(b"k14_rows_per_cu", 0) == 1
     assert lib.fopd_set_option(b"no_such_option", 1) == 1
     assert lib.fopd_set_option(None, 1) == 1
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fopd.h must compile as C99 (no C++ in the boundary) and declare what the library exports."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not available")
+    src = tmp_path / "use_fopd.c"
+    src.write_text('#include "fopd.h"\n'
+                   "int main(void) {\n"
+                   "  fopd_hparams hp = {1.0f, 1.0f, 0.05f, 0.1f};\n"
+                   "  fopd_refresh_config rc = {0.3f, 0.5f, 0.5f, 200};\n"
+                   "  fopd_refresh_state rs = {-1, 0};\n"
+                   "  float agg[3] = {0.1f, 1.0f, 1.0f};\n"
+                   "  (void)hp; (void)fopd_status_string(FOPD_OK);\n"
+                   "  (void)fopd_workspace_bytes(16, 2);\n"
+                   "  return fopd_refresh_decide(agg, &rc, &rs, 0, 0) == 1 ? 0 : 1;\n"
+                   "}\n")
+    obj = tmp_path / "use_fopd.o"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        "-c", str(src), "-o", str(obj)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr

@@ -514,3 +514,47 @@ def test_full_kl_gradient_by_finite_differences():
     r1 = orc.fopd_loss_fwd_bwd(z, y, mask, lb, lq, None, seq, lag, 0.0, 0.0, 0.05, 0.0)
     np.testing.assert_allclose(r0["dlogits_exact"], r1["dlogits_exact"], rtol=1e-13, atol=1e-18)
     assert abs(r0["loss"] - r1["loss"]) < 1e-15
+
+
+# ---------------------------------------------------------------------------------------
+# invariances of the whole pass
+# ---------------------------------------------------------------------------------------
+
+def test_invariances_shift_vocabulary_permutation_sample_permutation_scale():
+    c = _tiny_case(50, V=13, seq=(4, 3, 5), lag=(0, 2, 1))
+    hp = dict(alpha=1.1, beta=0.4, xi=0.1, lam=0.3)
+
+    def run(z, y, seq=None, order=None, g=1.0):
+        cc = dict(c)
+        if order is not None:                    # reorder whole samples
+            starts = np.concatenate([[0], np.cumsum(c["seq"])])
+            rows = np.concatenate([np.arange(starts[i], starts[i + 1]) for i in order])
+            cc = {k: (v[rows] if isinstance(v, np.ndarray) and v.shape[:1] == (len(c["y"]),) else v) for k, v in c.items()}
+            z, y = z[rows], y[rows]
+            cc["seq"], cc["lag"] = c["seq"][list(order)], c["lag"][list(order)]
+        return orc.fopd_loss_fwd_bwd(z, y, cc["mask"], cc["lb"], cc["lq"], cc["lqs"], cc["seq"], cc["lag"],
+                                     grad_scale=g, **hp)
+
+    base = run(c["z"], c["y"])
+    assert np.all(base["freshness"] > 0) and np.all(base["freshness"] <= 1)
+    # (1) adding a constant to a row's logits changes nothing but lse
+    shift = _rng(51).normal(0, 30, size=(len(c["y"]), 1))
+    sh = run(c["z"] + shift, c["y"])
+    np.testing.assert_allclose(sh["logp"], base["logp"], atol=1e-12)
+    np.testing.assert_allclose(sh["dlogits_exact"], base["dlogits_exact"], atol=1e-14)
+    assert abs(sh["loss"] - base["loss"]) < 1e-13
+    # (2) relabelling the vocabulary permutes the gradient columns
+    perm = _rng(52).permutation(13)
+    inv = np.argsort(perm)
+    pv = run(c["z"][:, perm], inv[c["y"]].astype(np.int32))
+    np.testing.assert_allclose(pv["dlogits_exact"], base["dlogits_exact"][:, perm], atol=1e-15)
+    np.testing.assert_allclose(pv["freshness"], base["freshness"], rtol=1e-13)
+    # (3) reordering the samples reorders the per-sample outputs and leaves the loss alone
+    order = (2, 0, 1)
+    ro = run(c["z"], c["y"], order=order)
+    np.testing.assert_allclose(ro["freshness"], base["freshness"][list(order)], rtol=1e-14)
+    assert abs(ro["loss"] - base["loss"]) < 1e-15
+    # (4) the upstream scale multiplies the gradient and nothing else
+    sc = run(c["z"], c["y"], g=-3.5)
+    np.testing.assert_allclose(sc["dlogits_exact"], -3.5 * base["dlogits_exact"], rtol=1e-14, atol=1e-300)
+    assert sc["loss"] == base["loss"]
