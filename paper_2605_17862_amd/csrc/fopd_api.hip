@@ -336,7 +336,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
     if (st != FOPD_OK) return st;
     lse_use = lse_ws;
     logp_use = logp_ws;
-  } else if (logp != nullptr && T > 0) {
+  } else if (logp != nullptr && logp != logp_in && T > 0) {
     if (hipMemcpyAsync(logp, logp_in, static_cast<size_t>(T) * sizeof(float), hipMemcpyDeviceToDevice, s) !=
         hipSuccess)
       return FOPD_EHIP;
