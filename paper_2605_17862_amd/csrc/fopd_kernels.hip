@@ -229,22 +229,28 @@ __device__ __forceinline__ void row_lse(const char* row, int V, int y, LaneState
   const int nvec = V / E;
   const int jy = y / E, ey = y % E;
   const float kNegInf = -__builtin_inff();
+  // the sampled token sits in exactly one trip of the loop: a wavefront-uniform test keeps the
+  // per-vector comparisons out of all the others
+  const int ytrip = jy / (U * NT);
+  int trip = 0;
   int j = tid;
-  for (; j + (U - 1) * NT < nvec; j += U * NT) {
+  for (; j + (U - 1) * NT < nvec; j += U * NT, ++trip) {
     u32x4 q[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) q[u] = load_vec<CACHED>(rv + j + u * NT);
     float x[U * E];
 #pragma unroll
     for (int u = 0; u < U; ++u) unpack<DT>(q[u], x + u * E);
+    if (trip == ytrip) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (j + u * NT == jy) {
+      for (int u = 0; u < U; ++u) {
+        if (j + u * NT == jy) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-          if (e == ey) {
-            *zy_out = x[u * E + e];
-            x[u * E + e] = kNegInf;
+          for (int e = 0; e < E; ++e) {
+            if (e == ey) {
+              *zy_out = x[u * E + e];
+              x[u * E + e] = kNegInf;
+            }
           }
         }
       }
@@ -349,8 +355,12 @@ __device__ __forceinline__ void row_grad(const char* row, char* orow, int V, int
   const int tid = threadIdx.x;
   const int nvec = V / E;
   const int jy = y / E, ey = y % E;
+  // the sampled token sits in exactly one trip of the loop: a wavefront-uniform test keeps the
+  // per-vector comparisons out of all the others
+  const int ytrip = jy / (U * NT);
+  int trip = 0;
   int j = tid;
-  for (; j + (U - 1) * NT < nvec; j += U * NT) {
+  for (; j + (U - 1) * NT < nvec; j += U * NT, ++trip) {
     u32x4 q[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) q[u] = load_vec<CACHED>(rv + j + u * NT);
@@ -360,7 +370,7 @@ __device__ __forceinline__ void row_grad(const char* row, char* orow, int V, int
       unpack<DT>(q[u], x);
 #pragma unroll
       for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
-      if (j + u * NT == jy) {
+      if (trip == ytrip && j + u * NT == jy) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
           if (e == ey) x[e] = gy;
@@ -663,8 +673,10 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
   const float kNegInf = -__builtin_inff();
   LaneStateKl st;
   constexpr int U2 = (U > 1) ? U / 2 : 1;      // two tensors: half the vectors of each per trip
+  const int ytrip = jy / (U2 * NT);
+  int trip = 0;
   int j = tid;
-  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT) {
+  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT, ++trip) {
     u32x4 q[U2], qs[U2];
 #pragma unroll
     for (int u = 0; u < U2; ++u) {
@@ -677,16 +689,18 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
       unpack<DT>(q[u], x + u * E);
       unpack<DT>(qs[u], xs + u * E);
     }
+    if (trip == ytrip) {
 #pragma unroll
-    for (int u = 0; u < U2; ++u) {
-      if (j + u * NT == jy) {
+      for (int u = 0; u < U2; ++u) {
+        if (j + u * NT == jy) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) {
-          if (e == ey) {
-            sh_zy = x[u * E + e];
-            sh_zsy = xs[u * E + e];
-            x[u * E + e] = kNegInf;         // the sampled token is left out of the lane sums
-            xs[u * E + e] = kNegInf;
+          for (int e = 0; e < E; ++e) {
+            if (e == ey) {
+              sh_zy = x[u * E + e];
+              sh_zsy = xs[u * E + e];
+              x[u * E + e] = kNegInf;         // the sampled token is left out of the lane sums
+              xs[u * E + e] = kNegInf;
+            }
           }
         }
       }
@@ -839,8 +853,10 @@ fopd_k6_grad_kl(const void* logits, const void* logits_stale, void* dlogits, int
     return a * expm1f(lp) + b * __expf(lp) * (d - dlse[t] - roll_kl[t]);
   };
   constexpr int U2 = (U > 1) ? U / 2 : 1;
+  const int ytrip = jy / (U2 * NT);
+  int trip = 0;
   int j = tid;
-  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT) {
+  for (; j + (U2 - 1) * NT < nvec; j += U2 * NT, ++trip) {
     u32x4 q[U2], qs[U2];
 #pragma unroll
     for (int u = 0; u < U2; ++u) {
@@ -854,7 +870,7 @@ fopd_k6_grad_kl(const void* logits, const void* logits_stale, void* dlogits, int
       unpack<DT>(qs[u], xs);
 #pragma unroll
       for (int e = 0; e < E; ++e) g[e] = grad_of(x[e], xs[e]);
-      if (j + u * NT == jy) {
+      if (trip == ytrip && j + u * NT == jy) {
 #pragma unroll
         for (int e = 0; e < E; ++e)
           if (e == ey) g[e] = grad_y(x[e], xs[e]);
