@@ -210,6 +210,26 @@ fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_sta
                                       void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The whole pass with a distribution-level token loss (Eq. "sample-aggregated-loss" with l taken as the
+ * reverse KL between the two distributions): l_t = KL( softmax(z_t) || softmax(q_t) ), q = the teacher's
+ * full logits under the current context.  The rollout drift keeps the sampled-token estimator on
+ * behav_logp; the teacher's log-probability of y_t, needed for D^sup when teacher_logp_stale is given,
+ * is taken from teacher_logits.
+ *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (log p_u - log q_u - l_t),
+ *   c1_t = -g m_t w_i / (B n_i) lambda rho_t delta_t,   c2_t = g m_t w_i / (B n_i).
+ * Averaged over y ~ softmax(z) the default path's sampled-token gradient equals this one's KL part.
+ *   token_kl  [T] f32 out or NULL: l_t.  Other arguments as in fopd_loss_fwd_bwd_full_kl.
+ * dlogits may alias logits but not teacher_logits.  Whole samples only.
+ */
+fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teacher_logits, fopd_dtype dt, int64_t T,
+                                           int64_t V, int64_t ld, int64_t ld_teacher, const int32_t* token_ids,
+                                           const uint8_t* mask, const float* behav_logp,
+                                           const float* teacher_logp_stale, const int32_t* seq_lens,
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
+                                           float* loss, float* freshness, float* weights, float* logp, float* token_kl,
+                                           void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Adaptive refresh test (Sec. 4.2, refresh condition; Algorithm 1, step after the aggregates; App. B:
  * the rule may fire at most once every `min_interval` optimizer steps, 200 in the paper).  HOST ONLY: all
  * pointers are host pointers and nothing touches the GPU.  `agg_host` is a host copy of the `agg` output

@@ -325,6 +325,64 @@ def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, token_ids, mask, teacher_log
     return res
 
 
+def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, token_ids, mask, behav_logp, teacher_logp_stale,
+                                   seq_lens, lag, alpha, beta, xi, lam, grad_scale=1.0, out_dtype="f32",
+                                   want_dlogits=True):
+    """The whole pass with a distribution-level token loss: l_t = KL(pi_theta(.|x_t) || pi_teacher(.|c_t))
+    from the teacher's full logits (Eq. "sample-aggregated-loss" with l taken as the reverse KL between the
+    two distributions instead of its sampled-token form).  The rollout drift keeps the sampled-token
+    estimator.  Gradient: d l_t/dz_u = p_u (log p_u - log q_u - l_t); the anchor contributes
+    -lambda rho delta (p - onehot) as in the default path."""
+    logits = np.asarray(logits)
+    teacher_logits = np.asarray(teacher_logits)
+    T, V = logits.shape
+    if mask is None:
+        mask = np.ones(T, dtype=np.uint8)
+    cu = segment_offsets(seq_lens)
+    if int(cu[-1]) != T:
+        raise ValueError("sequence lengths do not add up to T")
+    lse, lp = token_logprobs(logits, token_ids, mask)
+    lse_q, lq = token_logprobs(teacher_logits, token_ids, mask)      # teacher log-prob of the sampled token
+    tok_kl, _, _ = rollout_kl_full(logits, teacher_logits, mask)     # KL(student || teacher) per row
+    delta, rho, _, k_roll, k_sup = token_terms(lp, behav_logp, lq, teacher_logp_stale)
+    B = cu.shape[0] - 1
+    n = trainable_counts(mask, cu)
+    D_roll, D_sup, ell, cover = np.zeros(B), np.zeros(B), np.zeros(B), np.zeros(B)
+    for i in range(B):
+        if n[i] == 0:
+            continue
+        rows = [t for t in range(int(cu[i]), int(cu[i + 1])) if mask[t] != 0]
+        D_roll[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])
+        D_sup[i] = math.fsum(float(k_sup[t]) for t in rows) / int(n[i])
+        ell[i] = math.fsum(float(tok_kl[t]) for t in rows) / int(n[i])
+        cover[i] = int(n[i]) / (int(cu[i + 1]) - int(cu[i]))
+    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
+    agg = buffer_aggregates(f, cover)
+    w = freshness_weights(f, xi, n)
+    loss = anchored_loss(w, ell, D_roll, lam)
+    c1, c2 = np.zeros(T), np.zeros(T)
+    for i in range(B):
+        if int(n[i]) == 0 or w[i] == 0.0:
+            continue
+        for t in range(int(cu[i]), int(cu[i + 1])):
+            if mask[t] == 0:
+                continue
+            pref = grad_scale * w[i] / (B * int(n[i]))
+            c1[t] = -pref * lam * rho[t] * delta[t]
+            c2[t] = pref
+    res = dict(cu_seqlens=cu, n_train=n, lse=lse, lse_stale=lse_q, logp=lp, teacher_logp=lq, roll_kl=tok_kl,
+               token_kl=tok_kl, delta=delta, rho=rho, adv=-lam * rho * delta, D_roll=D_roll, D_sup=D_sup, ell=ell,
+               cover=cover, freshness=f, agg=agg, weights=w, loss=loss, c1=c1, c2=c2)
+    if want_dlogits:
+        g = np.zeros((T, V))
+        for t in range(T):
+            g[t] = dlogits_row_full_kl(logits[t], teacher_logits[t], int(token_ids[t]), lse[t], lse_q[t], tok_kl[t],
+                                       c1[t], c2[t])
+        res["dlogits_exact"] = g
+        res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
+    return res
+
+
 def refresh_decision(agg, kappa_f, kappa_roll, kappa_sup, step, last_refresh_step, min_interval):
     """Adaptive refresh test (Sec. 4.2 refresh condition; App. B rate limit).  Returns (refresh, reasons):
     reasons lists which of "f", "roll", "sup" hold; refresh is True when any holds and at least

@@ -19,7 +19,7 @@ SYMBOLS = (
     "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
-    "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl",
+    "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
 )
 
 
@@ -80,6 +80,9 @@ def load_library():
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_rollout_kl.restype = ctypes.c_int
     lib.fopd_rollout_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_loss_fwd_bwd_full_teacher.restype = ctypes.c_int
+    lib.fopd_loss_fwd_bwd_full_teacher.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp,
+                                                   i32, Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd_full_kl.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_full_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32,
                                               Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -243,6 +246,24 @@ def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, dt, T, V, ld, ld_stale, toke
         _ptr(logp, f32, "logp"), _ptr(roll_kl, f32, "roll_kl"), _ptr(dlogits, mat, "dlogits"), p, n,
         _stream(stream))
     _check(st, "fopd_loss_fwd_bwd_full_kl")
+
+
+def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, dt, T, V, ld, ld_teacher, token_ids, mask, behav_logp,
+                                   teacher_logp_stale, seq_lens, lag, B, hp, grad_scale, loss, freshness, weights,
+                                   logp, token_kl, dlogits, workspace, stream=None):
+    import torch
+    f32 = torch.float32
+    mat = (torch.float32, torch.bfloat16)
+    p, n = _ws(workspace)
+    st = load_library().fopd_loss_fwd_bwd_full_teacher(
+        _ptr(logits, mat, "logits"), _ptr(teacher_logits, mat, "teacher_logits"), int(dt), int(T), int(V), int(ld),
+        int(ld_teacher), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), float(grad_scale),
+        _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
+        _ptr(logp, f32, "logp"), _ptr(token_kl, f32, "token_kl"), _ptr(dlogits, mat, "dlogits"), p, n,
+        _stream(stream))
+    _check(st, "fopd_loss_fwd_bwd_full_teacher")
 
 
 def fopd_refresh_decide(agg_host, cfg, state, step):

@@ -19,7 +19,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Carving of the caller's workspace.  Every region starts on a 256-byte boundary.
 struct Workspace {
-  size_t flags, cu, n_train, fresh64, coef, lse, logp, coef2, dlse, kl, partials, total;
+  size_t flags, cu, n_train, fresh64, coef, lse, logp, coef2, dlse, kl, logq, partials, total;
   Workspace(int64_t T, int32_t B) {
     const size_t t = static_cast<size_t>(T < 0 ? 0 : T), b = static_cast<size_t>(B < 0 ? 0 : B);
     size_t off = 0;
@@ -38,6 +38,7 @@ struct Workspace {
     coef2 = take(t * sizeof(float));
     dlse = take(t * sizeof(float));
     kl = take(t * sizeof(float));
+    logq = take(t * sizeof(float));
     partials = take((t + 1) * sizeof(double));     // per-block or per-row loss terms
     total = off;
   }
@@ -261,7 +262,7 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask,
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, nullptr, teacher_logp, teacher_logp_stale, mask,
                                                cu, lag, T, hp, n_train, D_roll, D_sup, ell, cover,
                                                freshness, f64, nws);
   if ((st = launched()) != FOPD_OK) return st;
@@ -345,7 +346,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   // per-sample counts and scores
   const int32_t* n_use = n_train_in;
   if (whole) {
-    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, nullptr, teacher_logp, teacher_logp_stale,
+    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, nullptr, nullptr, teacher_logp, teacher_logp_stale,
                                                  mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
                                                  nullptr, nullptr, f64, nws);
     if ((st = launched()) != FOPD_OK) return st;
@@ -367,10 +368,10 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
 }
 
-fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
-                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
-                            float* roll_kl, float* logp, float* lse, float* dlse, void* workspace,
-                            size_t workspace_bytes, void* stream) {
+static fopd_status rollout_kl_impl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
+                                   int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
+                                   float* roll_kl, float* logp, float* lse, float* dlse, float* logq,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
   fopd_status st = check_matrix(logits, dt, T, V, ld);
   if (st != FOPD_OK) return st;
   if ((st = check_matrix(logits_stale, dt, T, V, ld_stale)) != FOPD_OK) return st;
@@ -384,12 +385,62 @@ fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_d
   const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
   if (dt == FOPD_BF16)
     fopd_k5_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, T, static_cast<int>(V), ld, ld_stale,
-                                                          token_ids, mask, roll_kl, logp, lse, dlse,
+                                                          token_ids, mask, roll_kl, logp, lse, dlse, logq,
                                                           at<int32_t>(workspace, w.flags));
   else
     fopd_k5_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, T, static_cast<int>(V), ld, ld_stale,
-                                                         token_ids, mask, roll_kl, logp, lse, dlse,
+                                                         token_ids, mask, roll_kl, logp, lse, dlse, logq,
                                                          at<int32_t>(workspace, w.flags));
+  return launched();
+}
+
+fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
+                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
+                            float* roll_kl, float* logp, float* lse, float* dlse, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  return rollout_kl_impl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, roll_kl, logp, lse, dlse,
+                         nullptr, workspace, workspace_bytes, stream);
+}
+
+// Shared tail of the two-tensor variants: scores from the per-row values, coefficients, loss, gradient.
+static fopd_status two_tensor_tail(const void* logits, const void* second, void* dlogits, fopd_dtype dt, int64_t T,
+                                   int64_t V, int64_t ld, int64_t ld_second, const int32_t* token_ids,
+                                   const uint8_t* mask, const float* behav_logp, const float* roll_term,
+                                   const float* ell_term, const float* lq, const float* lq_stale,
+                                   const float* token_kl, const float* logp_ws, const float* lse_ws,
+                                   const float* dlse_ws, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                   float grad_scale, bool anchor_is_kl, float* loss, float* freshness, float* weights,
+                                   void* workspace, hipStream_t s) {
+  Workspace w(T, B);
+  fopd_status st;
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  double* f64 = at<double>(workspace, w.fresh64);
+  float* c1 = at<float>(workspace, w.coef);
+  float* c2 = at<float>(workspace, w.coef2);
+  double* partials = at<double>(workspace, w.partials);
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, roll_term, ell_term, lq, lq_stale, mask, cu, lag, T,
+                                               hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, f64, nws);
+  if ((st = launched()) != FOPD_OK) return st;
+  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
+  if (T > 0) {
+    fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp_ws, token_kl, lq, behav_logp, mask, cu, nws, f64, T, B, hp, grad_scale, anchor_is_kl, c1, c2, partials);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, f64, nullptr, B, hp.xi, loss, weights, freshness);
+  if ((st = launched()) != FOPD_OK) return st;
+  if (T == 0) return FOPD_OK;
+  ScopedTimer timer(1, s);
+  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  if (dt == FOPD_BF16)
+    fopd_k6_grad_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, second, dlogits, T, static_cast<int>(V), ld,
+                                                               ld_second, token_ids, lse_ws, dlse_ws, token_kl, logp_ws,
+                                                               c1, c2);
+  else
+    fopd_k6_grad_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, second, dlogits, T, static_cast<int>(V), ld,
+                                                              ld_second, token_ids, lse_ws, dlse_ws, token_kl, logp_ws,
+                                                              c1, c2);
   return launched();
 }
 
@@ -415,45 +466,59 @@ fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_sta
   hipStream_t s = static_cast<hipStream_t>(stream);
   int32_t* flags = at<int32_t>(workspace, w.flags);
   int64_t* cu = at<int64_t>(workspace, w.cu);
-  int32_t* nws = at<int32_t>(workspace, w.n_train);
-  double* f64 = at<double>(workspace, w.fresh64);
-  float* c1 = at<float>(workspace, w.coef);
-  float* c2 = at<float>(workspace, w.coef2);
   float* lse_ws = at<float>(workspace, w.lse);
   float* dlse_ws = at<float>(workspace, w.dlse);
   float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
   float* kl_ws = (roll_kl != nullptr) ? roll_kl : at<float>(workspace, w.kl);
-  double* partials = at<double>(workspace, w.partials);
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
-  st = fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, kl_ws, logp_ws, lse_ws,
-                       dlse_ws, workspace, workspace_bytes, stream);
+  st = rollout_kl_impl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, kl_ws, logp_ws, lse_ws, dlse_ws,
+                       nullptr, workspace, workspace_bytes, stream);
   if (st != FOPD_OK) return st;
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, nullptr, kl_ws, teacher_logp, teacher_logp_stale, mask, cu,
-                                               lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                               f64, nws);
+  return two_tensor_tail(logits, logits_stale, dlogits, dt, T, V, ld, ld_stale, token_ids, mask, nullptr, kl_ws, nullptr,
+                         teacher_logp, teacher_logp_stale, kl_ws, logp_ws, lse_ws, dlse_ws, lag, B, hp, grad_scale,
+                         true, loss, freshness, weights, workspace, s);
+}
+
+fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teacher_logits, fopd_dtype dt, int64_t T,
+                                           int64_t V, int64_t ld, int64_t ld_teacher, const int32_t* token_ids,
+                                           const uint8_t* mask, const float* behav_logp,
+                                           const float* teacher_logp_stale, const int32_t* seq_lens,
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
+                                           float* loss, float* freshness, float* weights, float* logp, float* token_kl,
+                                           void* dlogits, void* workspace, size_t workspace_bytes, void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(teacher_logits, dt, T, V, ld_teacher)) != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0) return FOPD_ESHAPE;
+  if (token_ids == nullptr || behav_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  if (dlogits == teacher_logits) return FOPD_EINVAL;     // the teacher logits are read by both passes
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+
+  Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  float* lse_ws = at<float>(workspace, w.lse);
+  float* dlse_ws = at<float>(workspace, w.dlse);
+  float* logq_ws = at<float>(workspace, w.logq);
+  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+  float* kl_ws = (token_kl != nullptr) ? token_kl : at<float>(workspace, w.kl);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
-  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
-  if (T > 0) {
-    fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_ws, kl_ws, teacher_logp, mask, cu, nws, f64, T, B, hp, grad_scale, c1, c2, partials);
-    if ((st = launched()) != FOPD_OK) return st;
-  }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, f64, nullptr, B, hp.xi, loss, weights, freshness);
-  if ((st = launched()) != FOPD_OK) return st;
-  if (T == 0) return FOPD_OK;
-  ScopedTimer timer(1, s);
-  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
-  if (dt == FOPD_BF16)
-    fopd_k6_grad_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, dlogits, T, static_cast<int>(V),
-                                                               ld, ld_stale, token_ids, lse_ws, dlse_ws, kl_ws,
-                                                               logp_ws, c1, c2);
-  else
-    fopd_k6_grad_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, logits_stale, dlogits, T, static_cast<int>(V),
-                                                              ld, ld_stale, token_ids, lse_ws, dlse_ws, kl_ws,
-                                                              logp_ws, c1, c2);
-  return launched();
+  st = rollout_kl_impl(logits, teacher_logits, dt, T, V, ld, ld_teacher, token_ids, mask, kl_ws, logp_ws, lse_ws, dlse_ws,
+                       logq_ws, workspace, workspace_bytes, stream);
+  if (st != FOPD_OK) return st;
+  // drift from the sampled estimator (behav_logp), token loss from the full KL, teacher log-prob of the
+  // sampled token (for D^sup) from the teacher logits themselves
+  return two_tensor_tail(logits, teacher_logits, dlogits, dt, T, V, ld, ld_teacher, token_ids, mask, behav_logp, nullptr,
+                         kl_ws, logq_ws, teacher_logp_stale, kl_ws, logp_ws, lse_ws, dlse_ws, lag, B, hp, grad_scale,
+                         false, loss, freshness, weights, workspace, s);
 }
 
 int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,

@@ -12,8 +12,9 @@
 //   fopd_loss_final     loss scalar and weights
 // A third streaming kernel, fopd_k14_fused, does both passes over a row in one workgroup when the
 // freshness scores are supplied by the caller (second loop of Algorithm 1 on its own).
-// fopd_k5_kl / fopd_coef_loss_kl / fopd_k6_grad_kl are the same two passes when the rollout drift is
-// the full-vocabulary KL against a second (stale-checkpoint) logits tensor.
+// fopd_k5_kl / fopd_coef_loss_kl / fopd_k6_grad_kl are the same two passes over two logits tensors: the
+// second is either the stale checkpoint's (full-vocabulary rollout drift) or the teacher's
+// (distribution-level token loss).
 //
 // There is no matrix contraction anywhere on this path, so no MFMA is used.  All reductions
 // run in a fixed order (wavefront shuffles, then LDS), so results are bit-reproducible.
@@ -642,7 +643,7 @@ template <int DT, int U>
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64_t ld, int64_t ld_stale,
            const int32_t* token_ids, const uint8_t* mask, float* roll_kl, float* logp, float* lse, float* dlse,
-           int32_t* flags) {
+           float* logq, int32_t* flags) {
   constexpr int E = Elem<DT>::kPerVec;
   constexpr int NT = kStreamThreads;
   const int64_t t = blockIdx.x;
@@ -659,6 +660,7 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
       logp[t] = 0.f;
       lse[t] = 0.f;
       dlse[t] = 0.f;
+      if (logq != nullptr) logq[t] = 0.f;
     }
     return;
   }
@@ -782,16 +784,23 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
     if (kl < 0.0) kl = 0.0;                       // rounding noise of identical rows
     roll_kl[t] = static_cast<float>(kl);
     logp[t] = static_cast<float>(lp);
-    lse[t] = static_cast<float>((zyL + sp) * kLn2);
+    const double ls = (zyL + sp) * kLn2;
+    lse[t] = static_cast<float>(ls);
     dlse[t] = static_cast<float>(dl);
+    if (logq != nullptr) logq[t] = static_cast<float>(zsy - (ls - dl));   // log softmax(z')[y]
   }
 }
 
-// Coefficients for the full-KL gradient: c1 = g pref A_t, c2 = g pref lambda; loss share of the row.
+// Coefficients of the two-tensor gradient kernel and the row's share of the loss.
+//   anchor_is_kl = true   token_kl is the full-vocabulary rollout drift (second tensor = stale logits):
+//                         c1 = g pref A_t, c2 = g pref lambda, loss share pref ((lp - lq) + lambda kl)
+//   anchor_is_kl = false  token_kl is the distribution-level token loss (second tensor = teacher logits):
+//                         c1 = -g pref lambda rho delta, c2 = g pref, loss share pref (kl + lambda k(delta))
 __global__ void __launch_bounds__(kStreamThreads)
-fopd_coef_loss_kl(const float* logp, const float* roll_kl, const float* teacher_logp, const uint8_t* mask,
-                  const int64_t* cu, const int32_t* n_train, const double* fresh64, int64_t T, int32_t B,
-                  fopd_hparams hp, float grad_scale, float* c1, float* c2, double* partials) {
+fopd_coef_loss_kl(const float* logp, const float* token_kl, const float* teacher_logp, const float* behav_logp,
+                  const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const double* fresh64, int64_t T,
+                  int32_t B, fopd_hparams hp, float grad_scale, bool anchor_is_kl, float* c1, float* c2,
+                  double* partials) {
   __shared__ double sh[kStreamThreads / 64];
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
   double lt = 0.0;
@@ -802,11 +811,22 @@ fopd_coef_loss_kl(const float* logp, const float* roll_kl, const float* teacher_
       const int32_t n = n_train[i];
       const double w = weight_of(fresh64[i], n, hp.xi);
       if (w > 0.0) {
-        const double lp = logp[t], lq = teacher_logp[t], lam = hp.lambda;
+        const double lp = logp[t], lam = hp.lambda, kl = token_kl[t];
         const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
-        a = static_cast<float>(static_cast<double>(grad_scale) * pref * (lq - lp));
-        b = static_cast<float>(static_cast<double>(grad_scale) * pref * lam);
-        lt = pref * ((lp - lq) + lam * static_cast<double>(roll_kl[t]));
+        const double gp = static_cast<double>(grad_scale) * pref;
+        if (anchor_is_kl) {
+          const double lq = teacher_logp[t];
+          a = static_cast<float>(gp * (lq - lp));
+          b = static_cast<float>(gp * lam);
+          lt = pref * ((lp - lq) + lam * kl);
+        } else {
+          double rho;
+          const double d = lp - static_cast<double>(behav_logp[t]);
+          const double k = kl_term(d, &rho);
+          a = static_cast<float>(-gp * lam * rho * d);
+          b = static_cast<float>(gp);
+          lt = pref * (kl + lam * k);
+        }
       }
     }
     c1[t] = a;
@@ -966,8 +986,9 @@ fopd_count_train(const uint8_t* mask, const int64_t* cu, int64_t T, int32_t* n_t
 
 // One workgroup per sample: token means over the mask, then the freshness score.
 __global__ void __launch_bounds__(kSegThreads)
-fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll_kl, const float* teacher_logp,
-                   const float* teacher_logp_stale, const uint8_t* mask, const int64_t* cu,
+fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll_kl, const float* ell_term,
+                   const float* teacher_logp, const float* teacher_logp_stale, const uint8_t* mask,
+                   const int64_t* cu,
                    const int32_t* lag, int64_t T, fopd_hparams hp, int32_t* n_train, float* D_roll,
                    float* D_sup, float* ell, float* cover, float* freshness, double* fresh64,
                    int32_t* n_train_ws) {
@@ -984,7 +1005,8 @@ fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll
     sr += (roll_kl != nullptr) ? static_cast<double>(roll_kl[t])
                                : kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
     if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
-    sl += lp - lq;
+    // token loss: a distribution-level value if the caller has one, else the sampled-token form
+    sl += (ell_term != nullptr) ? static_cast<double>(ell_term[t]) : lp - lq;
     cnt += 1.0;
   }
   const double tr = block_sum<kSegThreads>(sr, sh);

@@ -98,7 +98,8 @@ def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label="")
             int(np.argmax(err * bad)), coef[r])
 
 
-def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_scale, n_samples, sample_of_row, store):
+def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_scale, n_samples, sample_of_row, store,
+                            c2_scales_with_weight=False):
     """Gradient rows of the full-vocabulary-KL variant against the oracle.  Tolerance: 2 ulp of the
     storage type plus what the allowed errors of lp (fp32), f_i (1e-5 relative) and of the per-row
     KL / lse difference (4e-6 absolute, fp32 sums) can move the row by."""
@@ -118,7 +119,7 @@ def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_sc
         pm[int(y[k])] -= 1.0
         ld = (z_rows[k] - ref["lse"][t]) - (zs_rows[k] - ref["lse_stale"][t]) - ref["roll_kl"][t]
         eps_c1 = pref * (w * EPS_A + EPS_F * f * abs(ref["adv"][t]))
-        eps_c2 = pref * lam * EPS_F * f
+        eps_c2 = pref * (1.0 if c2_scales_with_weight else lam) * EPS_F * f
         floor = np.abs(pm) * eps_c1 + p * (np.abs(ld) * eps_c2 + abs(c2) * 8e-6) + 2.0 ** -126
         u = 4.0 * np.spacing(max(abs(ref["lse"][t]), 1.0))
         floor[int(y[k])] += (abs(c1) + eps_c1) * u

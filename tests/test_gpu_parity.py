@@ -541,6 +541,42 @@ def test_replay_from_a_hip_graph():
     _sync_ok(g2)
 
 
+@pytest.mark.parametrize("name", ["reasoning", "coding", "tiny"])
+def test_full_teacher_distribution_variant(name):
+    """Token loss = KL(student || teacher) from the teacher's full logits (here: the generator's second
+    logits tensor plays the teacher), rollout drift from the sampled-token estimator."""
+    _say("distribution-level teacher loss on a %s replica" % name)
+    over = dict(FULL_KL_CASES[name], stale_logit_sigma=0.3)
+    if name == "tiny":
+        over["lags"] = [1, 2, 3, 30]                     # the last sample is gated
+    w = wl.generate(name, DEV, seed=31, row_block=32, **over)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    hp, g = (1.0, 1.0, 0.05, 0.5), 1.5
+    z, zq = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+    # the generator's stored per-token teacher log-prob is used here as the stale-context one
+    ref = orc.fopd_loss_fwd_bwd_full_teacher(z, zq, np64(w["token_ids"]), np64(w["mask"]), np64(w["behav_logp"]),
+                                             np64(w["teacher_logp"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                             hp[0], hp[1], hp[2], hp[3], g, out_dtype=w["dtype"])
+    lp = _pass_for(w)
+    kl = torch.empty(T, device=DEV)
+    lp.dlogits.fill_(4.0)
+    fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                      w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, g, lp.loss,
+                                      lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    assert_close("logp", np64(lp.logp), ref["logp"], atol=1e-4)
+    assert_close("token_kl", np64(kl), ref["token_kl"], rtol=2e-5, atol=3e-8)
+    assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(lp.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    assert np.any(ref["D_sup"] > 0)                      # the teacher log-prob came out of the teacher logits
+    sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]))
+    check_grad_rows_full_kl(np64(lp.dlogits)[:, :V], z, zq, np64(w["token_ids"]), ref, range(T), hp, g, B, sample_of,
+                            w["dtype"], c2_scales_with_weight=True)
+    if ld > V:
+        assert bool((lp.dlogits[:, V:] == 4.0).all())
+
+
 def test_device_side_error_flags():
     _say("device flags: token range, segments, lag")
     w = wl.generate("reasoning", DEV, seed=12, B=3, len_lo=4, len_hi=6, V=512)

@@ -558,3 +558,56 @@ def test_invariances_shift_vocabulary_permutation_sample_permutation_scale():
     sc = run(c["z"], c["y"], g=-3.5)
     np.testing.assert_allclose(sc["dlogits_exact"], -3.5 * base["dlogits_exact"], rtol=1e-14, atol=1e-300)
     assert sc["loss"] == base["loss"]
+
+
+def test_full_teacher_variant_gradient_and_link_to_sampled_form():
+    """Distribution-level token loss KL(pi_theta || teacher): finite differences of
+    F(z) = sum_t m_t w_i/(B n_i) [ KL(softmax(z_t) || q_t) + lambda k(lp_t - lb_t) ] (w frozen), and the
+    on-policy identity: averaging the default path's sampled-token gradient over y ~ softmax(z) gives
+    this variant's KL gradient."""
+    rng = _rng(60)
+    seq = np.array([2, 3], dtype=np.int32)
+    T, V, B = 5, 7, 2
+    z = rng.normal(0, 1.3, size=(T, V))
+    zq = rng.normal(0, 1.3, size=(T, V))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    mask = np.array([1, 1, 1, 0, 1], dtype=np.uint8)
+    lb = scipy.special.log_softmax(z, axis=1)[np.arange(T), y] + rng.normal(0, 0.3, T)
+    lag = np.array([0, 1], dtype=np.int32)
+    hp = dict(alpha=0.7, beta=0.0, xi=0.02, lam=0.6)
+    res = orc.fopd_loss_fwd_bwd_full_teacher(z, zq, y, mask, lb, None, seq, lag, grad_scale=0.8, **hp)
+    w, n = res["weights"], res["n_train"]
+    sample_of = np.repeat(np.arange(B), seq)
+    logq_all = scipy.special.log_softmax(zq, axis=1)
+    np.testing.assert_allclose(res["teacher_logp"][mask == 1], logq_all[np.arange(T), y][mask == 1], atol=1e-13)
+    np.testing.assert_allclose(res["ell"][0], np.mean(res["token_kl"][:2]), rtol=1e-14)
+
+    def F(zz):
+        logp_all = scipy.special.log_softmax(zz, axis=1)
+        tot = 0.0
+        for t in range(T):
+            if not mask[t]:
+                continue
+            i = sample_of[t]
+            d = logp_all[t, y[t]] - lb[t]
+            kl_t = float(np.sum(np.exp(logp_all[t]) * (logp_all[t] - logq_all[t])))
+            tot += 0.8 * w[i] / (B * n[i]) * (kl_t + hp["lam"] * (math.exp(d) * d - math.exp(d) + 1))
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = z.copy(), z.copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (F(zp) - F(zm)) / (2 * h)
+    assert np.max(np.abs(num - res["dlogits_exact"])) < 1e-5 * np.max(np.abs(num))
+    assert np.all(res["dlogits_exact"][3] == 0.0)
+    # on-policy link, one row, no anchor: E_{y ~ p}[ A_y (p - e_y) ] with A_y = log q_y - log p_y
+    t = 0
+    lse_t = scipy.special.logsumexp(z[t])
+    p = np.exp(z[t] - lse_t)
+    mean_sampled = sum(p[v] * orc.dlogits_row(z[t], v, lse_t, logq_all[t, v] - (z[t, v] - lse_t)) for v in range(V))
+    kl_t = float(np.sum(p * ((z[t] - lse_t) - logq_all[t])))
+    full = orc.dlogits_row_full_kl(z[t], zq[t], 0, lse_t, scipy.special.logsumexp(zq[t]), kl_t, 0.0, 1.0)
+    np.testing.assert_allclose(mean_sampled, full, atol=1e-14)
