@@ -201,7 +201,7 @@ def main():
     achieved = k4_bytes / k4_avg_s / 1e9
 
     out = {
-        "metric": "tokens/s and % HBM peak, fused OPD loss fwd+bwd, V=151,936 bf16",
+        "metric": "tokens/s and %% HBM peak, fused OPD loss fwd+bwd, V=%s %s" % (format(V, ","), w["dtype"]),
         "value": n_train * args.steps / elapsed,
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
