@@ -43,6 +43,19 @@ def test_segment_offsets_and_counts_against_python_ints():
     assert int(n[3]) == 0
 
 
+def test_coverage_is_aligned_positions_over_length():
+    """m_i = |U_i| / H_i (Algorithm 1, alignment ratios): 3 of 4 rows, 1 of 2 rows, an empty sample."""
+    seq = np.array([4, 2, 0], dtype=np.int32)
+    mask = np.array([1, 0, 1, 1, 0, 1], dtype=np.uint8)
+    z = np.zeros((6, 3))
+    y = np.zeros(6, dtype=np.int32)
+    lp = np.full(6, -math.log(3.0))
+    res = orc.fopd_loss_fwd_bwd(z, y, mask, lp, lp - 0.1, None, seq, np.zeros(3, dtype=np.int32), 1.0, 1.0, 0.0, 0.0)
+    np.testing.assert_allclose(res["cover"], [0.75, 0.5, 0.0], rtol=1e-15)
+    np.testing.assert_allclose(res["agg"], [2.0 / 3.0, 1.25 / 3.0, 1.25 / 3.0], rtol=1e-15)   # means over all 3 samples
+    assert list(res["n_train"]) == [3, 1, 0]
+
+
 def test_gather_index_is_64_bit_row_major():
     ids = np.array([5, 0, 151935], dtype=np.int32)
     out = orc.gather_index(ids, 151936)

@@ -1,0 +1,125 @@
+"""The pins must fail when the oracle is wrong.  Each case plants one plausible mistake (a dropped term, a
+wrong sign, a swapped operand, a wrong normaliser) in a copy of the oracle's source, loads that copy as a
+module and runs the pin tests with it in place of the real oracle; at least one pin has to fail.  CPU
+only: the mistakes live in the oracle, never in the GPU path."""
+
+import os
+import types
+
+import pytest
+
+import test_oracle_pins as pins
+import test_refresh_rule as refresh_pins
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ORACLE_SRC = open(os.path.join(ROOT, "oracle", "fopd_oracle.py")).read()
+
+MISTAKES = {
+    "advantage sign": ("adv = lq - lp                        # OPD advantage against the teacher",
+                       "adv = lp - lq"),
+    "drift estimator loses its -rho + 1": ("k_roll = rho * delta - rho + 1.0", "k_roll = rho * delta"),
+    "estimator of the opposite KL direction": ("return r * d - r + 1.0", "return r - 1.0 - d"),
+    "lag enters as tau instead of tau + 1": ("f[i] = math.exp(-surrogate) / (int(lag[i]) + 1)",
+                                             "f[i] = math.exp(-surrogate) / max(int(lag[i]), 1)"),
+    "alpha and beta swapped": ("surrogate = alpha * math.sqrt(D_roll[i]) + beta * math.sqrt(D_sup[i])",
+                               "surrogate = beta * math.sqrt(D_roll[i]) + alpha * math.sqrt(D_sup[i])"),
+    "square roots dropped": ("surrogate = alpha * math.sqrt(D_roll[i]) + beta * math.sqrt(D_sup[i])",
+                             "surrogate = alpha * D_roll[i] + beta * D_sup[i]"),
+    "gate keeps f instead of f - xi": ("w[i] = max(float(f[i]) - xi, 0.0)",
+                                       "w[i] = float(f[i]) if float(f[i]) > xi else 0.0"),
+    "loss normalised by surviving samples": (
+        "return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / B",
+        "return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / "
+        "max(1, sum(1 for i in range(B) if w[i] > 0))"),
+    "anchor gradient sign": ("* (adv[t] - lam * rho[t] * delta[t])", "* (adv[t] + lam * rho[t] * delta[t])"),
+    "anchor gradient loses rho": ("* (adv[t] - lam * rho[t] * delta[t])", "* (adv[t] - lam * delta[t])"),
+    "coefficient normalised by H instead of n": (
+        "c[t] = grad_scale * w[i] / (B * int(n_train[i]))", "c[t] = grad_scale * w[i] / (B * int(cu[i + 1] - cu[i]))"),
+    "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
+    "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
+                                      "return float(np.log(np.sum(np.exp(z - mx))))"),
+    "token means over all rows": ("ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / int(n[i])",
+                                  "ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / H"),
+    "coverage inverted": ("cover[i] = int(n[i]) / H", "cover[i] = H / max(int(n[i]), 1)"),
+    "bf16 rounding truncates": ("r = np.rint(x[fin] / quantum) * quantum", "r = np.trunc(x[fin] / quantum) * quantum"),
+    "mask ignored in the counts": ("            if mask[t] != 0:\n                cnt += 1", "            cnt += 1"),
+    "offsets start at the first length": ("cu[i + 1] = cu[i] + int(seq_lens[i])",
+                                          "cu[i + 1] = cu[i] + int(seq_lens[min(i + 1, seq_lens.shape[0] - 1)])"),
+    "gather index with the wrong pitch": ("out[t] = int(t) * int(ld) + int(token_ids[t])",
+                                          "out[t] = int(t) * (int(ld) - 1) + int(token_ids[t])"),
+    "full KL weighted by the stale distribution": (
+        "kl[t] = float(np.sum(np.where(p > 0.0, p * (np.where(p > 0.0, logp, 0.0) - logq), 0.0)))",
+        "kl[t] = float(np.sum(np.exp(logq) * (logp - logq)))"),
+    "full-KL gradient forgets the -KL centring": ("g = p * (c1_t + c2_t * ((logp - (zs - lse_stale_t)) - kl_t))",
+                                                  "g = p * (c1_t + c2_t * (logp - (zs - lse_stale_t)))"),
+    "entropy sign": ("H[t] = -float(np.sum(", "H[t] = float(np.sum("),
+    "refresh uses < for mean freshness": ("if fbar <= kappa_f:", "if fbar < kappa_f:"),
+    "refresh rate limit off by one": ("step - last_refresh_step >= min_interval", "step - last_refresh_step > min_interval"),
+    "invalid samples keep a weight": ("        if int(n_train[i]) == 0:\n            continue\n        w[i] = max(",
+                                      "        w[i] = max("),
+    "ratio linearised": ("rho = np.exp(delta)                  # importance ratio, not clipped", "rho = 1.0 + delta"),
+    "supervision drift averages the rollout terms": (
+        "D_sup[i] = math.fsum(float(k_sup[t]) for t in rows) / int(n[i])",
+        "D_sup[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])"),
+    "buffer means over valid samples only": ("fbar = math.fsum(float(x) for x in f) / B",
+                                             "fbar = math.fsum(float(x) for x in f) / max(1, sum(1 for x in f if x > 0))"),
+    "upstream scale dropped": ("c[t] = grad_scale * w[i] / (B * int(n_train[i]))", "c[t] = w[i] / (B * int(n_train[i]))"),
+    "bf16 spacing one bit too fine": ("quantum = np.ldexp(1.0, e - 7)          # spacing of bf16 numbers in that binade",
+                                      "quantum = np.ldexp(1.0, e - 8)"),
+    "full-teacher anchor sign": ("c1[t] = -pref * lam * rho[t] * delta[t]", "c1[t] = pref * lam * rho[t] * delta[t]"),
+    "full-KL variant drops the advantage": ("            c1[t] = pref * adv[t]\n            c2[t] = pref * lam",
+                                            "            c1[t] = 0.0\n            c2[t] = pref * lam"),
+    "stale teacher difference reversed": ("eps = lq - np.asarray(teacher_logp_stale, dtype=np.float64)",
+                                          "eps = np.asarray(teacher_logp_stale, dtype=np.float64) - lq"),
+}
+
+
+def _load(source):
+    mod = types.ModuleType("fopd_oracle_under_test")
+    exec(compile(source, "fopd_oracle_under_test.py", "exec"), mod.__dict__)
+    return mod
+
+
+def _pin_calls():
+    """Every pin test as a (name, zero-argument callable), parametrised ones expanded."""
+    calls = []
+    for module in (pins, refresh_pins):
+        for name, fn in sorted(vars(module).items()):
+            if not name.startswith("test_") or not callable(fn):
+                continue
+            marks = [m for m in getattr(fn, "pytestmark", []) if m.name == "parametrize"]
+            if not marks:
+                calls.append((name, fn))
+                continue
+            argnames = [a.strip() for a in marks[0].args[0].split(",")]
+            for values in marks[0].args[1]:
+                values = values if isinstance(values, (tuple, list)) else (values,)
+                calls.append(("%s%s" % (name, list(values)), (lambda f=fn, kw=dict(zip(argnames, values)): f(**kw))))
+    return calls
+
+
+def _first_failing_pin(oracle_module):
+    saved = pins.orc, refresh_pins.orc
+    pins.orc = refresh_pins.orc = oracle_module
+    try:
+        for name, call in _pin_calls():
+            try:
+                call()
+            except Exception:          # an assertion, or the broken oracle raising on its own
+                return name
+        return None
+    finally:
+        pins.orc, refresh_pins.orc = saved
+
+
+def test_control_an_unchanged_copy_passes():
+    assert len(_pin_calls()) >= 30
+    assert _first_failing_pin(_load(ORACLE_SRC)) is None
+
+
+@pytest.mark.parametrize("name", sorted(MISTAKES))
+def test_planted_mistake_is_caught(name):
+    old, new = MISTAKES[name]
+    assert ORACLE_SRC.count(old) >= 1, "the oracle no longer contains: " + old
+    caught_by = _first_failing_pin(_load(ORACLE_SRC.replace(old, new)))
+    assert caught_by is not None, "no pin noticed: " + name
