@@ -577,6 +577,29 @@ def test_full_teacher_distribution_variant(name):
         assert bool((lp.dlogits[:, V:] == 4.0).all())
 
 
+def test_profile_hooks_count_and_time_the_streaming_kernels():
+    w = wl.generate("tiny", DEV, seed=5)
+    lp = _pass_for(w)
+    lp.loss_fwd_bwd(w, HP)
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    try:
+        for _ in range(3):
+            lp.loss_fwd_bwd(w, HP)
+        lp.token_logprobs(w)
+    finally:
+        fb.fopd_profile_enable(False)
+    lp.loss_fwd_bwd(w, HP)                              # not recorded any more
+    ms0, n0 = fb.fopd_profile_read(0)
+    ms1, n1 = fb.fopd_profile_read(1)
+    ms2, n2 = fb.fopd_profile_read(2)
+    assert (n0, n1, n2) == (4, 3, 0) and ms0 > 0.0 and ms1 > 0.0 and ms2 == 0.0
+    assert ms0 < 1000.0 and ms1 < 1000.0
+    fb.fopd_profile_reset()
+    assert fb.fopd_profile_read(0) == (0.0, 0)
+
+
 def test_device_side_error_flags():
     _say("device flags: token range, segments, lag")
     w = wl.generate("reasoning", DEV, seed=12, B=3, len_lo=4, len_hi=6, V=512)
