@@ -131,12 +131,12 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
                       hipStream_t s) {
   if (T == 0) return FOPD_OK;
   ScopedTimer timer(1, s);
-  const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
+  const dim3 grid(static_cast<unsigned>(T)), block(kGradThreads);
   if (dt == FOPD_BF16)
-    fopd_k4_grad<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+    fopd_k4_grad<FOPD_BF16, kGradUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
                                                             token_ids, lse, logp, coef);
   else
-    fopd_k4_grad<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+    fopd_k4_grad<FOPD_F32, kGradUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
                                                            token_ids, lse, logp, coef);
   return launched();
 }
