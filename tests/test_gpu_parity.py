@@ -638,6 +638,32 @@ def test_upstream_scale_and_lambda():
     _compare_everything(w, (0.0, 2.0, 0.0, 2.0), grad_scale=-1.0, staged=False)
 
 
+def test_ablation_arms_are_parameter_settings():
+    """The ablation arms of App. B as plain settings of the same calls: lag-only scoring
+    (alpha = beta = 0), weighting without the anchor (lambda = 0), and the anchor without weighting
+    (scores supplied as 1 with xi = 0, so that every valid sample has weight 1)."""
+    _say("ablation arms")
+    w = wl.generate("coding", DEV, seed=21, B=4, total_len=48, resp_lo=5, resp_hi=12, obs_lo=2, obs_hi=7, V=9001, ld=9008)
+    _compare_everything(w, (0.0, 0.0, 0.05, 0.1), grad_scale=1.0, staged=False)       # lag-only
+    _compare_everything(w, (1.0, 1.0, 0.05, 0.0), grad_scale=1.0, staged=True)        # weighting-only
+    T, V, B = w["T"], w["V"], w["B"]
+    hp = (1.0, 1.0, 0.0, 0.4)
+    ones = torch.ones(B, dtype=torch.float32, device=DEV)
+    sc = _pass_for(w)
+    fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                         w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
+                         ones, None, 0, None, None, 1.0, sc.loss, sc.freshness, sc.weights, sc.logp,
+                         sc.dlogits, sc.workspace)
+    _sync_ok(sc)
+    n_used = orc.trainable_counts(np64(w["mask"]), orc.segment_offsets(np64(w["seq_lens"])))
+    ref, z, y = _scored_reference(w, hp, np.ones(B), n_used, 1.0)
+    assert np.array_equal(np64(sc.weights), (n_used > 0).astype(np.float64))
+    eps_c = coef_uncertainty(ref, hp, 1.0, B, np64(w["mask"]))
+    check_grad_rows(np64(sc.dlogits)[:, :V], z, y, ref["lse"], ref["coef"], eps_c, w["dtype"])
+    L = float(np.sum(ref["loss_terms"]))
+    assert abs(float(sc.loss) - L) <= 1e-5 * abs(L)
+
+
 # ---------------------------------------------------------------------------------------
 # the benchmark's workload at full size, in the benchmark's launch configuration
 # ---------------------------------------------------------------------------------------
