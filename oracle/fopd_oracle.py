@@ -111,6 +111,23 @@ def token_logprobs(logits, token_ids, mask=None):
     return lse, lp
 
 
+def lm_head_logits(hidden, weight):
+    """z_{t,v} = sum_k h_{t,k} * W_{v,k}: the output projection that makes the student's logits from the
+    last hidden state (pi_theta^t(. | x) of Eq. "kl-diagnostics" is softmax of this row).  hidden [T, d],
+    weight [V, d] (one row per vocabulary entry); both are widened to float64 exactly and the logits are
+    not rounded to any storage type."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    if hidden.ndim != 2 or weight.ndim != 2 or hidden.shape[1] != weight.shape[1]:
+        raise ValueError("hidden [T, d] and weight [V, d] must share d")
+    return np.matmul(hidden, weight.T)
+
+
+def lm_head_token_logprobs(hidden, weight, token_ids, mask=None):
+    """lse_t and lp_t as in token_logprobs, on logits formed from the hidden states and never stored."""
+    return token_logprobs(lm_head_logits(hidden, weight), token_ids, mask)
+
+
 def token_entropy(logits, mask=None):
     """H_t = -sum_v p_v log p_v of softmax(z_t) (the token-level response entropy that App. B logs as a
     monitoring proxy).  Masked rows give 0; entries with p_v = 0 (logit -inf) contribute 0."""

@@ -624,3 +624,44 @@ def test_full_teacher_variant_gradient_and_link_to_sampled_form():
     kl_t = float(np.sum(p * ((z[t] - lse_t) - logq_all[t])))
     full = orc.dlogits_row_full_kl(z[t], zq[t], 0, lse_t, scipy.special.logsumexp(zq[t]), kl_t, 0.0, 1.0)
     np.testing.assert_allclose(mean_sampled, full, atol=1e-14)
+
+
+# ---------------------------------------------------------------------------------------
+# logits made from hidden states (the projection in front of the pass)
+# ---------------------------------------------------------------------------------------
+
+def test_projection_by_integer_brute_force_and_special_cases():
+    rs = _rng(41)
+    T, d, V = 3, 4, 5                                   # all different: a transposed operand cannot pass
+    hidden = rs.integers(-3, 4, size=(T, d))
+    weight = rs.integers(-3, 4, size=(V, d))
+    z = orc.lm_head_logits(hidden, weight)
+    assert z.shape == (T, V)
+    for t in range(T):
+        for v in range(V):
+            exact = sum(int(hidden[t, k]) * int(weight[v, k]) for k in range(d))    # Python ints
+            assert z[t, v] == float(exact)
+    y = np.array([4, 0, 2])
+    lse, lp = orc.lm_head_token_logprobs(hidden, weight, y, np.array([1, 0, 1]))
+    for t in (0, 2):
+        zs = [sum(int(hidden[t, k]) * int(weight[v, k]) for k in range(d)) for v in range(V)]
+        ref = math.log(math.fsum(math.exp(a - max(zs)) for a in zs)) + max(zs)
+        assert abs(lse[t] - ref) < 1e-13 and abs(lp[t] - (zs[y[t]] - ref)) < 1e-13
+    assert lse[1] == 0.0 and lp[1] == 0.0
+    # identity projection: the logits are the hidden states themselves
+    h = rs.normal(size=(6, 7))
+    yy = rs.integers(0, 7, size=6)
+    a = orc.lm_head_token_logprobs(h, np.eye(7), yy)
+    b = orc.token_logprobs(h, yy)
+    np.testing.assert_array_equal(a[0], b[0])
+    np.testing.assert_array_equal(a[1], b[1])
+    # one more vector added to every vocabulary row shifts row t's logits by h_t . c: lp unchanged
+    w = rs.normal(size=(9, 7))
+    c = rs.normal(size=7)
+    y9 = rs.integers(0, 9, size=6)
+    l0, p0 = orc.lm_head_token_logprobs(h, w, y9)
+    l1, p1 = orc.lm_head_token_logprobs(h, w + c[None, :], y9)
+    np.testing.assert_allclose(p1, p0, atol=1e-13)
+    np.testing.assert_allclose(l1 - l0, h @ c, atol=1e-13)
+    with pytest.raises(ValueError):
+        orc.lm_head_logits(np.zeros((2, 3)), np.zeros((3, 2)))

@@ -69,6 +69,10 @@ MISTAKES = {
     "full-teacher anchor sign": ("c1[t] = -pref * lam * rho[t] * delta[t]", "c1[t] = pref * lam * rho[t] * delta[t]"),
     "full-KL variant drops the advantage": ("            c1[t] = pref * adv[t]\n            c2[t] = pref * lam",
                                             "            c1[t] = 0.0\n            c2[t] = pref * lam"),
+    "projection contracts the wrong axis": ("return np.matmul(hidden, weight.T)",
+                                            "return np.matmul(hidden, weight[:, ::-1].T)"),
+    "projection returns vocabulary-major logits": ("return np.matmul(hidden, weight.T)",
+                                                   "return np.matmul(weight, hidden.T)"),
     "stale teacher difference reversed": ("eps = lq - np.asarray(teacher_logp_stale, dtype=np.float64)",
                                           "eps = np.asarray(teacher_logp_stale, dtype=np.float64) - lq"),
 }
