@@ -267,10 +267,33 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
 fopd_status fopd_set_option(const char* name, int value);
 
 /*
+ * The same two outputs as fopd_token_logprobs, from the last hidden states and the output projection
+ * instead of stored logits: z_{t,v} = sum_k hidden[t,k] * weight[v,k] is formed tile by tile on the
+ * matrix cores (bf16 inputs, fp32 accumulation) and reduced on the fly, so the [T, V] logits are never
+ * written.  (pi_theta^t(y | x) of Eq. "kl-diagnostics" is the softmax of this projection; the paper's
+ * students are Qwen models, App. B, whose projection is [V, d] = [151,936, 4096].)
+ *
+ *   hidden      [T, ldh] bf16, ldh >= d           weight      [V, ldw] bf16, ldw >= d
+ *   d           hidden size, a multiple of 64; T * ldh and V * ldw must each be below 2^31
+ *   token_ids, mask, logp, lse: as in fopd_token_logprobs (masked rows give 0, 0)
+ *   workspace   fopd_lm_head_workspace_bytes(T) bytes, 256-byte aligned, initialised once with
+ *               fopd_workspace_init; token ids outside [0, V) raise the same sticky flag
+ *
+ * The logits are not rounded to bf16 on the way, so lse differs from the stored-logits call by that
+ * rounding.  lp_t uses a separate fp32 dot product for z_{t,y_t} and is clamped at 0.
+ */
+size_t fopd_lm_head_workspace_bytes(int64_t T);
+fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const void* weight, int64_t ldw,
+                                        int64_t T, int64_t V, int64_t d, const int32_t* token_ids,
+                                        const uint8_t* mask, float* logp, float* lse,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
  * is bracketed by HIP events on the launch stream.  Not thread-safe; meant for a single
  * benchmarking thread.  fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
- *   which: 0 = log-sum-exp pass, 1 = gradient pass, 2 = both passes in one kernel (scores supplied).
+ *   which: 0 = log-sum-exp pass, 1 = gradient pass, 2 = both passes in one kernel (scores supplied),
+ *          3 = projection fused with the log-sum-exp.
  */
 fopd_status fopd_profile_enable(int on);
 fopd_status fopd_profile_reset(void);

@@ -20,6 +20,7 @@ SYMBOLS = (
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
     "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
+    "fopd_lm_head_workspace_bytes", "fopd_lm_head_token_logprobs",
 )
 
 
@@ -75,6 +76,10 @@ def load_library():
     lib.fopd_workspace_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
     lib.fopd_token_logprobs.restype = ctypes.c_int
     lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_lm_head_workspace_bytes.restype = sz
+    lib.fopd_lm_head_workspace_bytes.argtypes = [i64]
+    lib.fopd_lm_head_token_logprobs.restype = ctypes.c_int
+    lib.fopd_lm_head_token_logprobs.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -176,6 +181,21 @@ def fopd_token_logprobs(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather
         _ptr(gather_idx, torch.int64, "gather_idx"), _ptr(entropy, torch.float32, "entropy"),
         p, n, _stream(stream))
     _check(st, "fopd_token_logprobs")
+
+
+def fopd_lm_head_workspace_bytes(T):
+    return int(load_library().fopd_lm_head_workspace_bytes(int(T)))
+
+
+def fopd_lm_head_token_logprobs(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, logp, lse, workspace,
+                                stream=None):
+    import torch
+    p, n = _ws(workspace)
+    st = load_library().fopd_lm_head_token_logprobs(
+        _ptr(hidden, torch.bfloat16, "hidden"), int(ldh), _ptr(weight, torch.bfloat16, "weight"), int(ldw),
+        int(T), int(V), int(d), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(logp, torch.float32, "logp"), _ptr(lse, torch.float32, "lse"), p, n, _stream(stream))
+    _check(st, "fopd_lm_head_token_logprobs")
 
 
 def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B,

@@ -10,6 +10,7 @@
 
 #include "fopd.h"
 #include "fopd_kernels.hip"
+#include "fopd_lm_head.hip"
 
 namespace {
 
@@ -44,6 +45,19 @@ struct Workspace {
   }
 };
 
+// Workspace of the projection-fused log-prob call: the same flag words, then one (reference, sum) pair per
+// strip and token, the tokens padded to whole tiles.
+struct LmWorkspace {
+  size_t flags, partial, t_pad, total;
+  explicit LmWorkspace(int64_t T) {
+    const size_t t = static_cast<size_t>(T < 0 ? 0 : T);
+    t_pad = (t + kLmTile - 1) / kLmTile * kLmTile;
+    flags = 0;
+    partial = 256;
+    total = align_up(partial + static_cast<size_t>(kLmStrips) * t_pad * sizeof(float2), 256);
+  }
+};
+
 template <typename P>
 inline P* at(void* ws, size_t off) {
   return reinterpret_cast<P*>(static_cast<char*>(ws) + off);
@@ -71,8 +85,8 @@ inline fopd_status launched() { return hipGetLastError() == hipSuccess ? FOPD_OK
 // ---- optional per-kernel timing ---------------------------------------------------------
 struct Profiler {
   bool on = false;
-  std::vector<hipEvent_t> start[3], stop[3];
-  size_t used[3] = {0, 0, 0};
+  std::vector<hipEvent_t> start[4], stop[4];
+  size_t used[4] = {0, 0, 0, 0};
 } g_prof;
 
 struct ScopedTimer {
@@ -538,6 +552,52 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
   return 1;
 }
 
+size_t fopd_lm_head_workspace_bytes(int64_t T) {
+  return LmWorkspace(T).total;
+}
+
+fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const void* weight, int64_t ldw,
+                                        int64_t T, int64_t V, int64_t d, const int32_t* token_ids,
+                                        const uint8_t* mask, float* logp, float* lse, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  if (T < 0 || V <= 0 || d <= 0 || d % kLmK != 0 || ldh < d || ldw < d) return FOPD_ESHAPE;
+  // every byte offset inside either matrix must fit 32 bits
+  if (T * ldh >= 2147483648LL || V * ldw >= 2147483648LL) return FOPD_ESHAPE;
+  if (hidden == nullptr || weight == nullptr || token_ids == nullptr || logp == nullptr || lse == nullptr)
+    return FOPD_EINVAL;
+  if (misaligned(hidden, 16) || misaligned(weight, 16) || (ldh * 2) % 16 != 0 || (ldw * 2) % 16 != 0)
+    return FOPD_EALIGN;
+  const LmWorkspace lay(T);
+  if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
+  if (T == 0) return FOPD_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  auto kern = fopd_k7_lm_head_lse<4>;
+  static bool allowed = false;
+  if (!allowed) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kLmLdsBytes) != hipSuccess)
+      return FOPD_EHIP;
+    allowed = true;
+  }
+  const int n_token_tiles = static_cast<int>(lay.t_pad / kLmTile);
+  const int n_vocab_tiles = static_cast<int>((V + kLmTile - 1) / kLmTile);
+  const unsigned grid = static_cast<unsigned>((n_token_tiles + 31) / 32) * 256u;
+  float2* partial = at<float2>(workspace, lay.partial);
+  const __bf16* Wp = static_cast<const __bf16*>(weight);
+  const __bf16* Hp = static_cast<const __bf16*>(hidden);
+  {
+    ScopedTimer timer(3, s);
+    kern<<<dim3(grid), dim3(512), kLmLdsBytes, s>>>(Wp, ldw, Hp, ldh, static_cast<int>(T), static_cast<int>(V),
+                                                    static_cast<int>(d), partial, n_token_tiles, n_vocab_tiles,
+                                                    static_cast<int64_t>(lay.t_pad));
+  }
+  if (launched() != FOPD_OK) return FOPD_EHIP;
+  fopd_k7_finish<<<dim3(static_cast<unsigned>((T + 3) / 4)), dim3(256), 0, s>>>(
+      Wp, ldw, Hp, ldh, partial, static_cast<int>(T), static_cast<int>(V), static_cast<int>(d),
+      static_cast<int64_t>(lay.t_pad), token_ids, mask, logp, lse, at<int32_t>(workspace, lay.flags));
+  return launched();
+}
+
 fopd_status fopd_set_option(const char* name, int value) {
   if (name == nullptr) return FOPD_EINVAL;
   const std::string key(name);
@@ -560,12 +620,12 @@ fopd_status fopd_profile_enable(int on) {
 }
 
 fopd_status fopd_profile_reset(void) {
-  g_prof.used[0] = g_prof.used[1] = g_prof.used[2] = 0;
+  g_prof.used[0] = g_prof.used[1] = g_prof.used[2] = g_prof.used[3] = 0;
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host) {
-  if (which < 0 || which > 2 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
+  if (which < 0 || which > 3 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
   double tot = 0.0;
   for (size_t i = 0; i < g_prof.used[which]; ++i) {
     if (hipEventSynchronize(g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;

@@ -160,3 +160,39 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
                 seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
                 seq_lens_host=seq_lens, lag_host=lag, mask_host=mask,
                 n_trainable=int(mask.sum()))
+
+
+def generate_lm_head(T, d, V, device="cpu", seed=0, logit_sigma=3.0, masked_every=0, row_block=2048, ldh=None,
+                     ldw=None):
+    """Hidden states and an output projection whose logits have the spread of the stored-logits
+    workloads: hidden ~ N(0, 1), weight ~ N(0, (logit_sigma / sqrt(d))^2), both bf16.  Token ids are drawn
+    from softmax of the projected row (Gumbel-max, in row blocks, with the tensor library's matmul: this
+    is input preparation, not part of the path).  masked_every = m > 0 masks every m-th row."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed * 1000003 + 29)
+    ldh = d if ldh is None else int(ldh)
+    ldw = d if ldw is None else int(ldw)
+    hidden = torch.zeros(T, ldh, dtype=torch.bfloat16, device=dev)
+    weight = torch.zeros(V, ldw, dtype=torch.bfloat16, device=dev)
+    for a in range(0, T, 8192):
+        b = min(a + 8192, T)
+        hidden[a:b, :d] = torch.randn(b - a, d, generator=gen, device=dev).to(torch.bfloat16)
+    for a in range(0, V, 8192):
+        b = min(a + 8192, V)
+        weight[a:b, :d] = (torch.randn(b - a, d, generator=gen, device=dev) * (logit_sigma / d ** 0.5)).to(torch.bfloat16)
+    token_ids = torch.empty(T, dtype=torch.int32, device=dev)
+    wt = weight[:, :d].float().t().contiguous() if dev.type == "cpu" else None
+    for a in range(0, T, row_block):
+        b = min(a + row_block, T)
+        if wt is not None:
+            z = hidden[a:b, :d].float() @ wt
+        else:
+            z = (hidden[a:b, :d] @ weight[:, :d].t()).float()
+        u = torch.rand(b - a, V, generator=gen, device=dev).clamp_(1e-20, 1.0)
+        token_ids[a:b] = torch.argmax(z - torch.log(-torch.log(u)), dim=1).to(torch.int32)
+        del z, u
+    mask = torch.ones(T, dtype=torch.uint8, device=dev)
+    if masked_every > 0:
+        mask[::masked_every] = 0
+    return dict(T=T, d=d, V=V, ldh=ldh, ldw=ldw, hidden=hidden, weight=weight, token_ids=token_ids, mask=mask)

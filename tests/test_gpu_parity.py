@@ -950,3 +950,88 @@ def test_full_vocabulary_drift_variant_at_full_size():
                                 np.zeros(b - a, dtype=int), "bf16")
         _say("sample %d ok (lag %d, D_roll=%.3e, f=%.6f)" % (i, lag[i], ref["D_roll"][0], f))
     _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights, n_rows=24)
+
+
+# ---------------------------------------------------------------------------------------
+# the projection in front of the pass: log-probs from hidden states, logits never stored
+# ---------------------------------------------------------------------------------------
+
+def _lm_head_call(w, mask=True):
+    T = w["T"]
+    nbytes = fb.fopd_lm_head_workspace_bytes(T)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=DEV)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + nbytes]
+    fb.fopd_workspace_init(ws)
+    logp = torch.full((T,), 7.0, dtype=torch.float32, device=DEV)
+    lse = torch.full((T,), 7.0, dtype=torch.float32, device=DEV)
+    fb.fopd_lm_head_token_logprobs(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, w["V"], w["d"],
+                                   w["token_ids"], w["mask"] if mask else None, logp, lse, ws)
+    return logp, lse, ws
+
+
+LM_HEAD_CASES = {
+    # T, d, V, ldh, ldw, masked_every: ragged token and vocabulary tiles, strips with no tile, one row
+    "ragged_tiles": (300, 128, 1000, 136, 128, 7),
+    "one_row_tiny_vocab": (1, 64, 5, 64, 72, 0),
+    "exact_tiles": (512, 192, 2048, 192, 192, 0),
+    "many_vocab_tiles": (520, 256, 151936, 256, 256, 5),
+}
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("name", sorted(LM_HEAD_CASES))
+def test_projection_fused_logprobs(name):
+    T, d, V, ldh, ldw, every = LM_HEAD_CASES[name]
+    _say("lm_head %s T=%d d=%d V=%d" % (name, T, d, V))
+    w = wl.generate_lm_head(T, d, V, DEV, seed=5, masked_every=every, ldh=ldh, ldw=ldw)
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    mask = np64(w["mask"])
+    ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(w["hidden"])[:, :d], np64(w["weight"])[:, :d],
+                                                 np64(w["token_ids"]), mask)
+    # fp32 accumulation over d products of magnitude ~ 3 / sqrt(d): a few 1e-6 on a logit
+    assert_close("lse (projection)", np64(lse), ref_lse, rtol=0, atol=1e-4)
+    assert_close("logp (projection)", np64(logp), ref_lp, rtol=0, atol=1e-4)
+    assert np.all(np64(logp) <= 0.0)
+    dead = mask == 0
+    assert np.all(np64(logp)[dead] == 0.0) and np.all(np64(lse)[dead] == 0.0)
+    # bit-reproducible
+    logp2, lse2, _ = _lm_head_call(w)
+    assert torch.equal(logp, logp2) and torch.equal(lse, lse2)
+
+
+@pytest.mark.gpu
+def test_projection_fused_token_range_flag_and_empty_call():
+    w = wl.generate_lm_head(40, 64, 300, DEV, seed=6)
+    w["token_ids"][3] = 300
+    w["token_ids"][9] = -1
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (6, 1)
+    assert float(logp[3]) == 0.0 and float(lse[9]) == 0.0 and float(lse[4]) != 0.0
+    # no rows: a valid call that touches nothing
+    fb.fopd_workspace_init(ws)
+    before = logp.clone()
+    fb.fopd_lm_head_token_logprobs(w["hidden"], w["ldh"], w["weight"], w["ldw"], 0, w["V"], w["d"],
+                                   w["token_ids"], None, logp, lse, ws)
+    assert fb.fopd_workspace_status(ws) == (0, 0) and torch.equal(logp, before)
+
+
+@pytest.mark.gpu
+def test_projection_fused_at_qwen_scale_sampled_rows():
+    """Qwen-scale projection (d = 4096, V = 151,936) on 32,768 tokens, checked on sampled rows."""
+    T, d, V = 32768, 4096, 151936
+    _say("lm_head full size T=%d d=%d V=%d" % (T, d, V))
+    w = wl.generate_lm_head(T, d, V, DEV, seed=0, masked_every=97)
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    rows = [0, 1, 255, 256, 4095, 16384, 32767 - 1, 32767]
+    W64 = w["weight"].float().cpu().numpy().astype(np.float64)
+    for t in rows:
+        ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(w["hidden"][t:t + 1]), W64, np64(w["token_ids"][t:t + 1]),
+                                                     np64(w["mask"][t:t + 1]))
+        assert abs(float(lse[t]) - ref_lse[0]) <= 1e-4, (t, float(lse[t]), ref_lse[0])
+        assert abs(float(logp[t]) - ref_lp[0]) <= 1e-4, (t, float(logp[t]), ref_lp[0])
+    m = np64(w["mask"])
+    assert np.all(np64(logp)[m == 0] == 0.0) and np.all(np64(logp)[m != 0] < 0.0)
+    assert np.all(np.isfinite(np64(lse)))
