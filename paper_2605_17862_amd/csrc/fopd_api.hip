@@ -571,7 +571,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
   if (T == 0) return FOPD_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  auto kern = fopd_k7_lm_head_lse<4>;
+  auto kern = fopd_k7_lm_head_lse;
   static bool allowed = false;
   if (!allowed) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -587,7 +587,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   const __bf16* Hp = static_cast<const __bf16*>(hidden);
   {
     ScopedTimer timer(3, s);
-    kern<<<dim3(grid), dim3(512), kLmLdsBytes, s>>>(Wp, ldw, Hp, ldh, static_cast<int>(T), static_cast<int>(V),
+    kern<<<dim3(grid), dim3(kLmThreads), kLmLdsBytes, s>>>(Wp, ldw, Hp, ldh, static_cast<int>(T), static_cast<int>(V),
                                                     static_cast<int>(d), partial, n_token_tiles, n_vocab_tiles,
                                                     static_cast<int64_t>(lay.t_pad));
   }

@@ -9,16 +9,23 @@
 // This is the step in front of the loss pass (pi_theta^t(y | x) of Eq. "kl-diagnostics" is the softmax of
 // the projected hidden state), and the only dense contraction near it.
 //
-// Tiling.  A workgroup of four wavefronts (2 x 2) owns 256 tokens and walks a strip of the vocabulary
-// in tiles of 256 rows; each wavefront holds a 128 x 128 block of the tile as 4 x 4 accumulators of
-// v_mfma_f32_32x32x16_bf16.  The vocabulary is the M side of the instruction and the tokens the N
-// side, because a lane of the 32 x 32 result holds 16 rows of ONE column: the reduction over the
-// vocabulary then runs inside a lane and needs a single cross-lane step (the two half-waves).
-// Both operands are k-contiguous in memory (hidden [T, d], weight [V, d]), so a lane's 8-element
-// fragment is one 16-byte LDS read.  LDS rows are 128 bytes (64 hidden elements); the 16-byte chunk
-// index is XOR-ed with the row's low three bits so that fragment reads and tile writes are free of
-// bank conflicts.  Two stages of (W tile, H tile) = 128 KB of the CU's 160 KB: global loads of the
-// next stage are issued before the MFMAs of the current one and land in registers.
+// Tiling.  A workgroup of eight wavefronts (2 along the vocabulary x 4 along the tokens, two per SIMD)
+// owns 256 tokens and walks a strip of the vocabulary in tiles of 256 rows; each wavefront holds a
+// 128 x 64 block of the tile as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16.  The vocabulary is the
+// M side of the instruction and the tokens the N side, because a lane of the 32 x 32 result holds 16
+// rows of ONE column: the reduction over the vocabulary then runs inside a lane and needs a single
+// cross-lane step (the two half-waves).  Both operands are k-contiguous in memory (hidden [T, d],
+// weight [V, d]), so a lane's 8-element fragment is one 16-byte LDS read.
+//
+// Memory pipeline.  A stage is 32 hidden elements of both tiles (2 x 16 KB); four stages rotate through
+// the LDS (128 KB of the CU's 160 KB).  Stages are filled by direct global -> LDS loads (16 bytes per
+// lane, lane i of a wave instruction writes LDS bytes [base + 16 i, + 16)), issued four stages ahead, so
+// a load has three stages of matrix work to arrive and no vector register ever holds a tile.
+// LDS rows are 64 bytes; the LDS serves 16 lanes x 16 bytes per clock (64 banks), so the 16 rows that a
+// quarter-wave reads at one logical 16-byte chunk must land on 16 different chunk slots modulo 16:
+// the chunk index is XOR-ed with bits 2..3 of the row (rows r .. r + 3 already differ by 4 slots).
+// Because the LDS side of a direct load is fixed by the lane number, the permutation is applied on
+// the global side: lane i fetches the chunk that belongs in slot i.
 
 #ifndef FOPD_LM_HEAD_HIP_
 #define FOPD_LM_HEAD_HIP_
@@ -33,12 +40,13 @@
 namespace fopd {
 
 constexpr int kLmTile = 256;                              // vocabulary rows and token rows of a workgroup tile
-constexpr int kLmK = 64;                                  // hidden elements per LDS stage
+constexpr int kLmK = 32;                                  // hidden elements per LDS stage
+constexpr int kLmStages = 4;                              // stages resident in the LDS
 constexpr int kLmStrips = 8;                              // vocabulary strips = partial pairs per token
-constexpr int kLmThreads = 256;
-constexpr int kLmOperandBytes = kLmTile * kLmK * 2;       // one operand tile of one stage: 32 KB
+constexpr int kLmThreads = 512;                           // 8 wavefronts: 2 (vocabulary) x 4 (tokens)
+constexpr int kLmOperandBytes = kLmTile * kLmK * 2;       // one operand tile of one stage: 16 KB
 constexpr int kLmStageBytes = 2 * kLmOperandBytes;
-constexpr int kLmLdsBytes = 2 * kLmStageBytes + 2 * kLmTile * 8;   // + the cross-wave exchange
+constexpr int kLmLdsBytes = kLmStages * kLmStageBytes + 2 * kLmTile * 8;   // + the cross-wave exchange
 constexpr float kLmNone = -__builtin_inff();              // "no value yet": the reference of an empty pair
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -56,26 +64,25 @@ __device__ __forceinline__ void lm_merge(float& m, float& s, float m2, float s2)
   m = mx;
 }
 
-// 16 bytes at (uniform base) + (per-lane byte offset)
-__device__ __forceinline__ u32x4 lm_load(const char* base, uint32_t voff) {
-  return *reinterpret_cast<const u32x4*>(base + voff);
+// 16 bytes per lane from (uniform base) + (per-lane byte offset) straight into the LDS: lane i of the
+// wavefront writes lds_base + 16 i (lds_base is the same for all lanes).
+__device__ __forceinline__ void lm_load_to_lds(const char* base, uint32_t voff, unsigned char* lds_base) {
+  typedef __attribute__((address_space(1))) const void gptr_t;
+  typedef __attribute__((address_space(3))) void lptr_t;
+  __builtin_amdgcn_global_load_lds((gptr_t*)(base + voff), (lptr_t*)lds_base, 16, 0, 0);
 }
 
 }  // namespace
 
-// WN = wavefronts along the tokens (2: four 128 x 128 wavefronts; 4: eight 128 x 64 wavefronts, two per SIMD)
-template <int WN>
-__global__ void __launch_bounds__(128 * WN)
+__global__ void __launch_bounds__(kLmThreads)
 fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restrict__ H, int64_t ldh,
                     int T, int V, int d, float2* __restrict__ partial, int n_token_tiles, int n_vocab_tiles,
                     int64_t t_pad) {
   extern __shared__ __align__(16) unsigned char lm_smem[];
-  constexpr int NT = 128 * WN;                         // threads
+  constexpr int WN = 4;                                // wavefronts along the tokens
   constexpr int NJ = 8 / WN;                           // 32-token blocks per wavefront
-  constexpr int NL = 2048 / NT;                        // 16-byte chunks per thread, operand and stage
-  constexpr int RS = NT / 8;                           // rows between a thread's chunks
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;            // vocabulary half, token part of the tile
+  const int wm = wave / WN, wn = wave % WN;            // vocabulary half, token quarter of the tile
 
   // Workgroups are handed to the eight XCDs in turn (id mod 8).  The 32 that run together on one XCD
   // are 4 token tiles x 8 strips, so that each L2 serves 4 hidden tiles and 8 weight tiles to 32 users.
@@ -89,61 +96,45 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   const int nk = d / kLmK;
   const int n_iter = (vt_end - vt_begin) * nk;
 
-  // global -> LDS copy: thread (row = tid / 8 + RS i, chunk = tid % 8), i < NL, 16 bytes each.
-  // Inside the matrices the address is (uniform: tile, i, slab) + (per lane: row-in-32, chunk); a tile
-  // that hangs over the end of its matrix takes per-lane row offsets that re-read the last row
-  // (those rows are discarded later).  All offsets fit 32 bits (checked on the host).
-  const int lrow = tid >> 3, chunk = tid & 7;
-  const int st_off = lrow * 128 + ((chunk ^ (lrow & 7)) << 4);
+  // global -> LDS copy.  An operand tile of a stage is 1024 chunks of 16 bytes = 16 wave instructions;
+  // wavefront w issues instructions 2 w and 2 w + 1 of each operand.  Instruction q fills rows
+  // 16 q .. 16 q + 15: lane i writes slot (row 16 q + i / 4, physical chunk i % 4) and therefore fetches
+  // logical chunk (i % 4) ^ ((i / 16) % 4) of that row.  Rows past the end of a matrix re-read its last
+  // row (they are discarded later): the row is clamped, which changes nothing inside the matrix, so
+  // the loop has no branch.  All offsets fit 32 bits (checked on the host).
+  const int cp_row = wave * 32 + (lane >> 2);          // row of instruction 2 w; instruction 2 w + 1: + 16
+  const int cp_chunk = (lane & 3) ^ ((lane >> 4) & 3);
+  const int cp_lds = wave * 2048;                      // LDS offset of instruction 2 w inside the operand
   const char* Wb = reinterpret_cast<const char*>(W);
-  const char* Hb = reinterpret_cast<const char*>(H);
-  const uint32_t w_lane = static_cast<uint32_t>(lrow * ldw + chunk * 8) * 2u;
-  const uint32_t h_lane = static_cast<uint32_t>(lrow * ldh + chunk * 8) * 2u;
-  const bool h_ragged = (t0 + kLmTile > T);
-  uint32_t h_row[NL];                                  // per-lane row offsets of the hidden tile (bytes)
+  const char* Hb = reinterpret_cast<const char*>(H) + static_cast<int64_t>(t0) * ldh * 2;
+  const uint32_t ldw2 = static_cast<uint32_t>(ldw) * 2u;
+  uint32_t h_off[2];
 #pragma unroll
-  for (int i = 0; i < NL; ++i)
-    h_row[i] = static_cast<uint32_t>(min(t0 + lrow + RS * i, T - 1) * ldh + chunk * 8) * 2u;
+  for (int q = 0; q < 2; ++q)
+    h_off[q] = static_cast<uint32_t>(min(cp_row + 16 * q, T - 1 - t0)) * static_cast<uint32_t>(ldh) * 2u + cp_chunk * 16;
 
-  u32x4 ra[NL], rb[NL];
-  auto load_stage = [&](int vtile, int ko) {
+  // the stage that holds vocabulary tile `vtile`, hidden elements ko .. ko + 31, into LDS stage `buf`
+  auto load_stage = [&](int vtile, int ko, int buf) {
     const int64_t kb = static_cast<int64_t>(ko) * 2;
-    if (vtile * kLmTile + kLmTile <= V) {
-      const char* base = Wb + static_cast<int64_t>(vtile) * kLmTile * ldw * 2 + kb;
+    const int last = V - 1 - vtile * kLmTile;          // last valid row of this tile (>= 255 inside)
+    const char* wsrc = Wb + static_cast<int64_t>(vtile) * kLmTile * ldw * 2 + kb;
+    unsigned char* dst = lm_smem + buf * kLmStageBytes + cp_lds;
 #pragma unroll
-      for (int i = 0; i < NL; ++i) ra[i] = lm_load(base + static_cast<int64_t>(RS * i) * ldw * 2, w_lane);
-    } else {
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int vr = min(vtile * kLmTile + lrow + RS * i, V - 1);
-        ra[i] = lm_load(Wb + kb, static_cast<uint32_t>(vr * ldw + chunk * 8) * 2u);
-      }
-    }
-    if (!h_ragged) {
-      const char* base = Hb + static_cast<int64_t>(t0) * ldh * 2 + kb;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) rb[i] = lm_load(base + static_cast<int64_t>(RS * i) * ldh * 2, h_lane);
-    } else {
-#pragma unroll
-      for (int i = 0; i < NL; ++i) rb[i] = lm_load(Hb + kb, h_row[i]);
-    }
-  };
-  auto store_stage = [&](unsigned char* stage) {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      *reinterpret_cast<u32x4*>(stage + st_off + i * RS * 128) = ra[i];
-      *reinterpret_cast<u32x4*>(stage + kLmOperandBytes + st_off + i * RS * 128) = rb[i];
+    for (int q = 0; q < 2; ++q) {
+      const uint32_t w_off = static_cast<uint32_t>(min(cp_row + 16 * q, last)) * ldw2 + cp_chunk * 16;
+      lm_load_to_lds(wsrc, w_off, dst + q * 1024);
+      lm_load_to_lds(Hb + kb, h_off[q], dst + kLmOperandBytes + q * 1024);
     }
   };
 
   // LDS -> fragment: lane reads row (lane % 32) of a 32-row block, hidden elements
-  // 16 ks + 8 (lane / 32) .. + 7, i.e. chunk 2 ks + lane / 32, swizzled by the row's low bits
-  const int frag_row = (lane & 31) * 128;
-  const int a_off = wm * 128 * 128 + frag_row;
-  const int b_off = kLmOperandBytes + wn * NJ * 32 * 128 + frag_row;
-  int xk[4];
+  // 16 ks + 8 (lane / 32) .. + 7 of the stage, i.e. logical chunk 2 ks + lane / 32
+  const int frag_row = (lane & 31) * 64;
+  const int a_off = wm * 128 * 64 + frag_row;
+  const int b_off = kLmOperandBytes + wn * NJ * 32 * 64 + frag_row;
+  int xk[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) xk[ks] = ((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4;
+  for (int ks = 0; ks < 2; ++ks) xk[ks] = ((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) << 4;
 
   f32x16 acc[4][NJ];
   float run_ref[NJ], run_sum[NJ];
@@ -153,11 +144,34 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
     run_sum[j] = 0.f;
   }
 
-  if (n_iter > 0) {
-    load_stage(vt_begin, 0);
-    store_stage(lm_smem);
-  }
-  __syncthreads();
+  // (vt_ld, kt_ld) is the next stage to request; it stops at the last stage, which the tail requests
+  // again (into a free buffer, never read) instead of branching.
+  int vt_ld = vt_begin, kt_ld = 0, s_ld = 0;
+  auto request_next = [&](int buf) {
+    load_stage(vt_ld, kt_ld * kLmK, buf);
+    if (s_ld + 1 < n_iter) {
+      ++s_ld;
+      if (++kt_ld == nk) {
+        kt_ld = 0;
+        ++vt_ld;
+      }
+    }
+  };
+
+  bf16x8 fa[2][4], fb[2][NJ];
+  auto read_frags = [&](int buf, const unsigned char* stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 2048 + xk[ks]);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 2048 + xk[ks]);
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
 
   // One finished tile.  Result register r of block (i, j) is vocabulary row
   // 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's 128, token 32 j + lane % 32.
@@ -191,7 +205,22 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
     }
   };
 
-  int it = 0;                                          // stages consumed so far: parity picks the LDS half
+  // Schedule of stage s (buffer s % 4), two 16-element slices:
+  //   read slice 1 of s            | multiply slice 0 of s (read at the end of stage s - 1)
+  //   wait for the own loads of s + 1, barrier: stage s + 1 is complete and stage s fully read
+  //   request stage s + 4 into the buffer of s, read slice 0 of s + 1 | multiply slice 1 of s
+  // so neither the barrier nor the LDS latency after it leaves the matrix cores without work.
+  // Outstanding load instructions per wavefront before the wait: stages s + 1, s + 2, s + 3, four each;
+  // loads complete in order, so "at most 8 outstanding" means stage s + 1 has landed.
+  if (n_iter > 0) {
+#pragma unroll
+    for (int b = 0; b < kLmStages; ++b) request_next(b);
+    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+  }
+  __syncthreads();
+  if (n_iter > 0) read_frags(0, lm_smem, 0);
+
+  int it = 0;
   for (int vt = vt_begin; vt < vt_end; ++vt) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -201,37 +230,18 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     for (int kt = 0; kt < nk; ++kt, ++it) {
-      const bool more = (it + 1 < n_iter);
-      if (more) {                                      // next stage: (vt, kt + 1) or (vt + 1, 0)
-        const bool wrap = (kt + 1 == nk);
-        load_stage(wrap ? vt + 1 : vt, wrap ? 0 : (kt + 1) * kLmK);
-      }
-
-      const unsigned char* stage = lm_smem + (it & 1) * kLmStageBytes;
-      bf16x8 a[2][4], b[2][NJ];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[0][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 4096 + xk[0]);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) b[0][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 4096 + xk[0]);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks < 3) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            a[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 4096 + xk[(ks + 1) & 3]);
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            b[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 4096 + xk[(ks + 1) & 3]);
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-      }
-
-      if (more) store_stage(lm_smem + ((it + 1) & 1) * kLmStageBytes);
+      const int buf = it & (kLmStages - 1);
+      const unsigned char* stage = lm_smem + buf * kLmStageBytes;
+      const unsigned char* next = lm_smem + ((it + 1) & (kLmStages - 1)) * kLmStageBytes;
+      read_frags(1, stage, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
       __syncthreads();
+      request_next(buf);
+      read_frags(0, next, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1);
     }
 
     const int vlane = vt * kLmTile + wm * 128 + ((lane >> 5) << 2);
@@ -240,7 +250,9 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   }
 
   // half-waves, then the two wavefronts that share these tokens, then one pair per token and strip
-  float2* ex = reinterpret_cast<float2*>(lm_smem + 2 * kLmStageBytes);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
+  __syncthreads();
+  float2* ex = reinterpret_cast<float2*>(lm_smem + kLmStages * kLmStageBytes);
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     float m = run_ref[j], s = run_sum[j];
