@@ -274,7 +274,7 @@ fopd_status fopd_set_option(const char* name, int value);
  * students are Qwen models, App. B, whose projection is [V, d] = [151,936, 4096].)
  *
  *   hidden      [T, ldh] bf16, ldh >= d           weight      [V, ldw] bf16, ldw >= d
- *   d           hidden size, a multiple of 32; T * ldh and V * ldw must each be below 2^31
+ *   d           hidden size, a multiple of 64; T * ldh and V * ldw must each be below 2^31
  *   token_ids, mask, logp, lse: as in fopd_token_logprobs (masked rows give 0, 0)
  *   workspace   fopd_lm_head_workspace_bytes(T) bytes, 256-byte aligned, initialised once with
  *               fopd_workspace_init; token ids outside [0, V) raise the same sticky flag

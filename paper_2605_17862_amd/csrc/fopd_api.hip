@@ -560,7 +560,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
                                         int64_t T, int64_t V, int64_t d, const int32_t* token_ids,
                                         const uint8_t* mask, float* logp, float* lse, void* workspace,
                                         size_t workspace_bytes, void* stream) {
-  if (T < 0 || V <= 0 || d <= 0 || d % kLmK != 0 || ldh < d || ldw < d) return FOPD_ESHAPE;
+  if (T < 0 || V <= 0 || d <= 0 || d % (2 * kLmK) != 0 || ldh < d || ldw < d) return FOPD_ESHAPE;
   // every byte offset inside either matrix must fit 32 bits
   if (T * ldh >= 2147483648LL || V * ldw >= 2147483648LL) return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || logp == nullptr || lse == nullptr)

@@ -17,10 +17,15 @@
 // cross-lane step (the two half-waves).  Both operands are k-contiguous in memory (hidden [T, d],
 // weight [V, d]), so a lane's 8-element fragment is one 16-byte LDS read.
 //
-// Memory pipeline.  A stage is 32 hidden elements of both tiles (2 x 16 KB); four stages rotate through
-// the LDS (128 KB of the CU's 160 KB).  Stages are filled by direct global -> LDS loads (16 bytes per
-// lane, lane i of a wave instruction writes LDS bytes [base + 16 i, + 16)), issued four stages ahead, so
-// a load has three stages of matrix work to arrive and no vector register ever holds a tile.
+// Memory pipeline.  A stage is 32 hidden elements of both tiles (2 x 16 KB); the LDS holds two pairs of
+// stages (128 KB of the CU's 160 KB), a pair being 64 hidden elements, i.e. whole 128-byte lines of
+// both matrices.  Stages are filled by direct global -> LDS loads (16 bytes per lane, lane i of a wave
+// instruction writes LDS bytes [base + 16 i, + 16)); no vector register ever holds a tile.  The two
+// halves of a line are requested back to back so that the second one hits in the L1; the next pair
+// is requested as soon as its buffers are free and has a whole pair of matrix work to arrive.
+// Measured on MI355X: with every load hitting the L1 the same loop runs 25 % faster, whatever the L2
+// hit rate and however far ahead the loads are issued: the L2 -> L1 path, 64 KB per 64 hidden elements
+// and compute unit, is what bounds this kernel.
 // LDS rows are 64 bytes; the LDS serves 16 lanes x 16 bytes per clock (64 banks), so the 16 rows that a
 // quarter-wave reads at one logical 16-byte chunk must land on 16 different chunk slots modulo 16:
 // the chunk index is XOR-ed with bits 2..3 of the row (rows r .. r + 3 already differ by 4 slots).
@@ -113,17 +118,20 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   for (int q = 0; q < 2; ++q)
     h_off[q] = static_cast<uint32_t>(min(cp_row + 16 * q, T - 1 - t0)) * static_cast<uint32_t>(ldh) * 2u + cp_chunk * 16;
 
-  // the stage that holds vocabulary tile `vtile`, hidden elements ko .. ko + 31, into LDS stage `buf`
-  auto load_stage = [&](int vtile, int ko, int buf) {
+  // the two stages that hold vocabulary tile `vtile`, hidden elements ko .. ko + 63, into LDS stages
+  // 2 pb and 2 pb + 1; the two halves of each 128-byte line are requested back to back
+  auto load_pair = [&](int vtile, int ko, int pb) {
     const int64_t kb = static_cast<int64_t>(ko) * 2;
-    const int last = V - 1 - vtile * kLmTile;          // last valid row of this tile (>= 255 inside)
+    const int last = V - 1 - vtile * kLmTile;
     const char* wsrc = Wb + static_cast<int64_t>(vtile) * kLmTile * ldw * 2 + kb;
-    unsigned char* dst = lm_smem + buf * kLmStageBytes + cp_lds;
+    unsigned char* dst = lm_smem + 2 * pb * kLmStageBytes + cp_lds;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const uint32_t w_off = static_cast<uint32_t>(min(cp_row + 16 * q, last)) * ldw2 + cp_chunk * 16;
       lm_load_to_lds(wsrc, w_off, dst + q * 1024);
+      lm_load_to_lds(wsrc + 64, w_off, dst + kLmStageBytes + q * 1024);
       lm_load_to_lds(Hb + kb, h_off[q], dst + kLmOperandBytes + q * 1024);
+      lm_load_to_lds(Hb + kb + 64, h_off[q], dst + kLmStageBytes + kLmOperandBytes + q * 1024);
     }
   };
 
@@ -144,14 +152,15 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
     run_sum[j] = 0.f;
   }
 
-  // (vt_ld, kt_ld) is the next stage to request; it stops at the last stage, which the tail requests
+  // (vt_ld, kt_ld) is the next pair to request; it stops at the last pair, which the tail requests
   // again (into a free buffer, never read) instead of branching.
   int vt_ld = vt_begin, kt_ld = 0, s_ld = 0;
-  auto request_next = [&](int buf) {
-    load_stage(vt_ld, kt_ld * kLmK, buf);
-    if (s_ld + 1 < n_iter) {
+  const int n_pairs = n_iter / 2, nkp = nk / 2;
+  auto request_next = [&](int pb) {
+    load_pair(vt_ld, kt_ld * 64, pb);
+    if (s_ld + 1 < n_pairs) {
       ++s_ld;
-      if (++kt_ld == nk) {
+      if (++kt_ld == nkp) {
         kt_ld = 0;
         ++vt_ld;
       }
@@ -205,22 +214,24 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
     }
   };
 
-  // Schedule of stage s (buffer s % 4), two 16-element slices:
-  //   read slice 1 of s            | multiply slice 0 of s (read at the end of stage s - 1)
-  //   wait for the own loads of s + 1, barrier: stage s + 1 is complete and stage s fully read
-  //   request stage s + 4 into the buffer of s, read slice 0 of s + 1 | multiply slice 1 of s
+  // Schedule of pair p (buffers 2 (p % 2) and 2 (p % 2) + 1), four 16-element slices:
+  //   read slice 1 | multiply slice 0 (read at the end of pair p - 1)
+  //   read slice 2 | multiply slice 1
+  //   read slice 3 | multiply slice 2
+  //   wait for the own loads of pair p + 1, barrier: pair p + 1 is complete and pair p fully read
+  //   request pair p + 2 into the buffers of p, read slice 0 of p + 1 | multiply slice 3
   // so neither the barrier nor the LDS latency after it leaves the matrix cores without work.
-  // Outstanding load instructions per wavefront before the wait: stages s + 1, s + 2, s + 3, four each;
-  // loads complete in order, so "at most 8 outstanding" means stage s + 1 has landed.
+  // Loads complete in order: after the prologue's two requests (8 instructions per wavefront each),
+  // "at most 8 outstanding" means pair 0 has landed; in the loop only pair p + 1 is outstanding.
   if (n_iter > 0) {
-#pragma unroll
-    for (int b = 0; b < kLmStages; ++b) request_next(b);
-    asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+    request_next(0);
+    request_next(1);
+    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
   }
   __syncthreads();
   if (n_iter > 0) read_frags(0, lm_smem, 0);
 
-  int it = 0;
+  int pit = 0;
   for (int vt = vt_begin; vt < vt_end; ++vt) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -229,16 +240,23 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    for (int kt = 0; kt < nk; ++kt, ++it) {
-      const int buf = it & (kLmStages - 1);
-      const unsigned char* stage = lm_smem + buf * kLmStageBytes;
-      const unsigned char* next = lm_smem + ((it + 1) & (kLmStages - 1)) * kLmStageBytes;
-      read_frags(1, stage, 1);
+    for (int kt = 0; kt < nkp; ++kt, ++pit) {
+      const int pb = pit & 1;
+      const unsigned char* lo = lm_smem + 2 * pb * kLmStageBytes;
+      const unsigned char* hi = lo + kLmStageBytes;
+      const unsigned char* next = lm_smem + 2 * (pb ^ 1) * kLmStageBytes;
+      read_frags(1, lo, 1);
       multiply(0);
       __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      read_frags(0, hi, 0);
+      multiply(1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(1, hi, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __syncthreads();
-      request_next(buf);
+      request_next(pb);
       read_frags(0, next, 0);
       __builtin_amdgcn_sched_barrier(0);
       multiply(1);
