@@ -110,6 +110,58 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
                                    "frac": k5_bytes / k5_s / 1e9 / HBM_PEAK_GBS}}}))
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def bench_lm_head(args, torch, fb, wl):
+    """One JSON line for fopd_lm_head_token_logprobs: log-probs straight from hidden states (d = 4096) and
+    the [V, d] output projection, on as many rows as the workload has, with its mask."""
+    seq_lens, mask = wl.structure_only(args.workload, seed=0)
+    T, d, V = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"])
+    w = wl.generate_lm_head(T, d, V, "cuda:0", seed=0)
+    w["mask"] = torch.from_numpy(mask).to("cuda:0")
+    nbytes = fb.fopd_lm_head_workspace_bytes(T)
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda:0")
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + nbytes]
+    fb.fopd_workspace_init(ws)
+    logp = torch.empty(T, dtype=torch.float32, device="cuda:0")
+    lse = torch.empty(T, dtype=torch.float32, device="cuda:0")
+
+    def step():
+        fb.fopd_lm_head_token_logprobs(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"],
+                                       logp, lse, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fb.fopd_profile_enable(False)
+    st, flags = fb.fopd_workspace_status(ws)
+    if st != 0:
+        sys.exit("device flags set: %d" % flags)
+    k7_ms, n7 = fb.fopd_profile_read(3)
+    k7_s = k7_ms / max(n7, 1) * 1e-3
+    flops = 2.0 * T * V * d                             # every row is multiplied, masked or not
+    print(json.dumps({
+        "metric": "tokens/s, token log-probs from hidden states (projection fused, logits never stored), "
+                  "V=%d d=%d bf16" % (V, d),
+        "value": int((mask != 0).sum()) * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d,
+                   "call": "fopd_lm_head_token_logprobs"},
+        "roofline": {"bound": "mfma", "kernel": "fopd_k7_lm_head_lse", "achieved": flops / k7_s / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops / k7_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,9 +169,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="reasoning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--variant", choices=("default", "full_kl"), default="default",
+    ap.add_argument("--variant", choices=("default", "full_kl", "lm_head"), default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
-                         "(stale-checkpoint) logits tensor; reported as its own line, not the headline")
+                         "(stale-checkpoint) logits tensor; lm_head: token log-probs from hidden states with "
+                         "the output projection fused in.  Each is reported as its own line, not the headline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the loss pass shards by sample with no "
@@ -136,6 +189,8 @@ def main():
     hp = DEFAULT_HPARAMS
     if args.variant == "full_kl":
         return bench_full_kl(args, torch, fb, wl, LossPass, hp)
+    if args.variant == "lm_head":
+        return bench_lm_head(args, torch, fb, wl)
     w = wl.generate(args.workload, "cuda:0", seed=0)
     T, V, B = w["T"], w["V"], w["B"]
     lp = LossPass(T, V, B, w["dtype"], ld=w["ld"], device="cuda:0")

@@ -54,7 +54,7 @@ struct LmWorkspace {
     t_pad = (t + kLmTile - 1) / kLmTile * kLmTile;
     flags = 0;
     partial = 256;
-    total = align_up(partial + static_cast<size_t>(kLmStrips) * t_pad * sizeof(float2), 256);
+    total = align_up(partial + static_cast<size_t>(kLmStripsMax) * t_pad * sizeof(float2), 256);
   }
 };
 
@@ -581,7 +581,19 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   }
   const int n_token_tiles = static_cast<int>(lay.t_pad / kLmTile);
   const int n_vocab_tiles = static_cast<int>((V + kLmTile - 1) / kLmTile);
-  const unsigned grid = static_cast<unsigned>((n_token_tiles + 31) / 32) * 256u;
+  // strips: 8, 16 or 32, whichever leaves the smallest idle tail when the work items (token tile x strip,
+  // all of one length) are dealt to the 256 compute units round by round
+  int n_strips = 8;
+  double best = 0.0;
+  for (int cand = 8; cand <= kLmStripsMax; cand *= 2) {
+    const int64_t items = static_cast<int64_t>(n_token_tiles) * cand;
+    const double fill = static_cast<double>(items) / static_cast<double>((items + 255) / 256 * 256);
+    if (fill > best + 0.005) {
+      best = fill;
+      n_strips = cand;
+    }
+  }
+  const unsigned grid = static_cast<unsigned>((n_token_tiles + 31) / 32) * static_cast<unsigned>(n_strips / 8) * 256u;
   float2* partial = at<float2>(workspace, lay.partial);
   const __bf16* Wp = static_cast<const __bf16*>(weight);
   const __bf16* Hp = static_cast<const __bf16*>(hidden);
@@ -589,11 +601,11 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
     ScopedTimer timer(3, s);
     kern<<<dim3(grid), dim3(kLmThreads), kLmLdsBytes, s>>>(Wp, ldw, Hp, ldh, static_cast<int>(T), static_cast<int>(V),
                                                     static_cast<int>(d), partial, n_token_tiles, n_vocab_tiles,
-                                                    static_cast<int64_t>(lay.t_pad));
+                                                    n_strips, static_cast<int64_t>(lay.t_pad));
   }
   if (launched() != FOPD_OK) return FOPD_EHIP;
   fopd_k7_finish<<<dim3(static_cast<unsigned>((T + 3) / 4)), dim3(256), 0, s>>>(
-      Wp, ldw, Hp, ldh, partial, static_cast<int>(T), static_cast<int>(V), static_cast<int>(d),
+      Wp, ldw, Hp, ldh, partial, n_strips, static_cast<int>(T), static_cast<int>(V), static_cast<int>(d),
       static_cast<int64_t>(lay.t_pad), token_ids, mask, logp, lse, at<int32_t>(workspace, lay.flags));
   return launched();
 }

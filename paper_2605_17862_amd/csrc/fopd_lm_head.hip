@@ -47,7 +47,7 @@ namespace fopd {
 constexpr int kLmTile = 256;                              // vocabulary rows and token rows of a workgroup tile
 constexpr int kLmK = 32;                                  // hidden elements per LDS stage
 constexpr int kLmStages = 4;                              // stages resident in the LDS
-constexpr int kLmStrips = 8;                              // vocabulary strips = partial pairs per token
+constexpr int kLmStripsMax = 32;                          // vocabulary strips (8, 16 or 32) = partial pairs per token
 constexpr int kLmThreads = 512;                           // 8 wavefronts: 2 (vocabulary) x 4 (tokens)
 constexpr int kLmOperandBytes = kLmTile * kLmK * 2;       // one operand tile of one stage: 16 KB
 constexpr int kLmStageBytes = 2 * kLmOperandBytes;
@@ -82,7 +82,7 @@ __device__ __forceinline__ void lm_load_to_lds(const char* base, uint32_t voff, 
 __global__ void __launch_bounds__(kLmThreads)
 fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restrict__ H, int64_t ldh,
                     int T, int V, int d, float2* __restrict__ partial, int n_token_tiles, int n_vocab_tiles,
-                    int64_t t_pad) {
+                    int n_strips, int64_t t_pad) {
   extern __shared__ __align__(16) unsigned char lm_smem[];
   constexpr int WN = 4;                                // wavefronts along the tokens
   constexpr int NJ = 8 / WN;                           // 32-token blocks per wavefront
@@ -91,12 +91,16 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
 
   // Workgroups are handed to the eight XCDs in turn (id mod 8).  The 32 that run together on one XCD
   // are 4 token tiles x 8 strips, so that each L2 serves 4 hidden tiles and 8 weight tiles to 32 users.
+  // With more than 8 strips (shorter work items, a shorter idle tail at the end of the launch) the groups
+  // of 8 strips of one set of token tiles follow each other.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int strip = (slot >> 2) & 7;
-  const int token_tile = ((((slot >> 5) << 3) + xcd) << 2) + (slot & 3);
+  const int strip_groups = n_strips >> 3;
+  const int chunk_id = slot >> 5;
+  const int strip = ((chunk_id % strip_groups) << 3) + ((slot >> 2) & 7);
+  const int token_tile = ((((chunk_id / strip_groups) << 3) + xcd) << 2) + (slot & 3);
   if (token_tile >= n_token_tiles) return;             // whole workgroup, before any barrier
-  const int vt_begin = static_cast<int>(static_cast<int64_t>(strip) * n_vocab_tiles / kLmStrips);
-  const int vt_end = static_cast<int>(static_cast<int64_t>(strip + 1) * n_vocab_tiles / kLmStrips);
+  const int vt_begin = static_cast<int>(static_cast<int64_t>(strip) * n_vocab_tiles / n_strips);
+  const int vt_end = static_cast<int>(static_cast<int64_t>(strip + 1) * n_vocab_tiles / n_strips);
   const int t0 = token_tile * kLmTile;
   const int nk = d / kLmK;
   const int n_iter = (vt_end - vt_begin) * nk;
@@ -201,15 +205,17 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
       // a lane that has seen no value yet (only in a tile that hangs over the vocabulary's end) keeps
       // a finite reference, so that every term below is exp2(-inf) = 0 rather than a NaN
       const float mref = (mx == kLmNone) ? 0.f : mx * kLog2e;
-      float s = run_sum[j] * fast_exp2(fmaf(run_ref[j], kLog2e, -mref));
+      const float carried = run_sum[j] * fast_exp2(fmaf(run_ref[j], kLog2e, -mref));
       __builtin_amdgcn_sched_barrier(0);
+      float part[4];                                   // four short chains, added as a tree
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        part[i] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s += fast_exp2(fmaf(value(i, r), kLog2e, -mref));
+        for (int r = 0; r < 16; ++r) part[i] += fast_exp2(fmaf(value(i, r), kLog2e, -mref));
       }
       run_ref[j] = mx;
-      run_sum[j] = s;
+      run_sum[j] = carried + ((part[0] + part[1]) + (part[2] + part[3]));
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -294,7 +300,7 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
 // this dot product and the matrix cores sum the same products in different orders.
 __global__ void __launch_bounds__(256)
 fopd_k7_finish(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restrict__ H, int64_t ldh,
-               const float2* __restrict__ partial, int T, int V, int d, int64_t t_pad,
+               const float2* __restrict__ partial, int n_strips, int T, int V, int d, int64_t t_pad,
                const int32_t* __restrict__ token_ids, const uint8_t* __restrict__ mask,
                float* __restrict__ logp, float* __restrict__ lse, int32_t* flags) {
   const int lane = threadIdx.x & 63;
@@ -329,8 +335,7 @@ fopd_k7_finish(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restri
   if (lane == 0) {
     float2 e = partial[t];
     float m = e.x, s = e.y;
-#pragma unroll
-    for (int k = 1; k < kLmStrips; ++k) {
+    for (int k = 1; k < n_strips; ++k) {
       e = partial[static_cast<int64_t>(k) * t_pad + t];
       lm_merge(m, s, e.x, e.y);
     }

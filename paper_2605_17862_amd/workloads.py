@@ -162,6 +162,13 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
                 n_trainable=int(mask.sum()))
 
 
+def structure_only(name, seed=0, **overrides):
+    """seq_lens [B] and mask [T] (numpy) that generate(name, seed=seed) would use, without any tensor."""
+    cfg = dict(CONFIGS[name])
+    cfg.update(overrides)
+    return _structure(cfg, np.random.RandomState(seed))
+
+
 def generate_lm_head(T, d, V, device="cpu", seed=0, logit_sigma=3.0, masked_every=0, row_block=2048, ldh=None,
                      ldw=None):
     """Hidden states and an output projection whose logits have the spread of the stored-logits

@@ -92,7 +92,7 @@ def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label="")
             want = orc.round_to_f32(exact)
             lim = 2e-5 * np.abs(want) + floor
         err = np.abs(got_rows[r] - want)
-        bad = ~((err <= lim) | (got == want))          # a NaN on either side fails
+        bad = ~((err <= lim) | (got_rows[r] == want))   # a NaN on either side fails
         assert not np.any(bad), "dlogits row %s%d: %d elements off, worst %.3e vs limit %.3e at v=%d (c=%.3e)" % (
             rows_label, r, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]),
             int(np.argmax(err * bad)), coef[r])
@@ -130,6 +130,6 @@ def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_sc
             want = orc.round_to_f32(exact)
             lim = 2e-5 * np.abs(want) + floor
         err = np.abs(got_rows[k] - want)
-        bad = ~((err <= lim) | (got == want))          # a NaN on either side fails
+        bad = ~((err <= lim) | (got_rows[k] == want))   # a NaN on either side fails
         assert not np.any(bad), "full-KL dlogits row %d: %d elements off, worst %.3e vs limit %.3e at v=%d" % (
             t, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]), int(np.argmax(err * bad)))

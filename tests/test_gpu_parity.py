@@ -1018,20 +1018,33 @@ def test_projection_fused_token_range_flag_and_empty_call():
 
 
 @pytest.mark.gpu
-def test_projection_fused_at_qwen_scale_sampled_rows():
-    """Qwen-scale projection (d = 4096, V = 151,936) on 32,768 tokens, checked on sampled rows."""
-    T, d, V = 32768, 4096, 151936
+def test_projection_fused_at_benchmark_size_sampled_rows():
+    """The projection benchmark's own configuration (rows and mask of the reasoning workload, d = 4096,
+    V = 151,936), checked on sampled rows that the oracle computes one by one."""
+    seq_lens, mask_host = wl.structure_only("reasoning", seed=0)
+    T, d, V = int(seq_lens.sum()), 4096, 151936
     _say("lm_head full size T=%d d=%d V=%d" % (T, d, V))
-    w = wl.generate_lm_head(T, d, V, DEV, seed=0, masked_every=97)
+    w = wl.generate_lm_head(T, d, V, DEV, seed=0)
+    mask_host = mask_host.copy()
+    mask_host[::97] = 0
+    w["mask"] = torch.from_numpy(mask_host).to(DEV)
     logp, lse, ws = _lm_head_call(w)
     assert fb.fopd_workspace_status(ws) == (0, 0)
-    rows = [0, 1, 255, 256, 4095, 16384, 32767 - 1, 32767]
+    rows = [0, 1, 255, 256, 4095, 16384, 100000, T - 257, T - 2, T - 1]
     W64 = w["weight"].float().cpu().numpy().astype(np.float64)
     for t in rows:
         ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(w["hidden"][t:t + 1]), W64, np64(w["token_ids"][t:t + 1]),
-                                                     np64(w["mask"][t:t + 1]))
+                                                     mask_host[t:t + 1])
         assert abs(float(lse[t]) - ref_lse[0]) <= 1e-4, (t, float(lse[t]), ref_lse[0])
         assert abs(float(logp[t]) - ref_lp[0]) <= 1e-4, (t, float(logp[t]), ref_lp[0])
-    m = np64(w["mask"])
-    assert np.all(np64(logp)[m == 0] == 0.0) and np.all(np64(logp)[m != 0] < 0.0)
+    got = np64(logp)
+    assert np.all(got[mask_host == 0] == 0.0) and np.all(got[mask_host != 0] < 0.0)
     assert np.all(np.isfinite(np64(lse)))
+    # the same rows through the 8-strip launch shape (a row count that fills the chip exactly)
+    T8 = 32768
+    w8 = dict(w, T=T8, hidden=w["hidden"][:T8], token_ids=w["token_ids"][:T8], mask=w["mask"][:T8])
+    logp8, lse8, ws8 = _lm_head_call(w8)
+    assert fb.fopd_workspace_status(ws8) == (0, 0)
+    # both launches sum 151,936 fp32 terms per row, in different orders
+    assert_close("lse, 8 strips vs 32", np64(lse8), np64(lse)[:T8], rtol=0, atol=1e-4)
+    assert_close("logp, 8 strips vs 32", np64(logp8), got[:T8], rtol=0, atol=1e-4)
