@@ -281,6 +281,8 @@ fopd_status fopd_set_option(const char* name, int value);
  *
  * The logits are not rounded to bf16 on the way, so lse differs from the stored-logits call by that
  * rounding.  lp_t uses a separate fp32 dot product for z_{t,y_t} and is clamped at 0.
+ * The first call in a process sets a kernel attribute (large dynamic LDS): make one call before
+ * capturing this entry point into a HIP graph.  Enqueues kernels only (no memset, no allocation).
  */
 size_t fopd_lm_head_workspace_bytes(int64_t T);
 fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const void* weight, int64_t ldw,

@@ -980,6 +980,20 @@ LM_HEAD_CASES = {
 
 
 @pytest.mark.gpu
+def test_projection_fused_wide_logits():
+    """Logits with a spread of 40 (row maxima around 150): the running reference rises by tens between
+    vocabulary tiles, so every rescale path of the on-the-fly log-sum-exp is taken."""
+    T, d, V = 300, 128, 3000
+    w = wl.generate_lm_head(T, d, V, DEV, seed=8, logit_sigma=40.0)
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(w["hidden"]), np64(w["weight"]), np64(w["token_ids"]), None)
+    # fp32 accumulation of d products: error on a logit of magnitude 150 is a few 1e-5
+    assert_close("lse (wide)", np64(lse), ref_lse, rtol=2e-6, atol=1e-4)
+    assert_close("logp (wide)", np64(logp), ref_lp, rtol=2e-6, atol=2e-4)
+
+
+@pytest.mark.gpu
 @pytest.mark.parametrize("name", sorted(LM_HEAD_CASES))
 def test_projection_fused_logprobs(name):
     T, d, V, ldh, ldw, every = LM_HEAD_CASES[name]
