@@ -113,9 +113,10 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def bench_lm_head(args, torch, fb, wl):
-    """One JSON line for fopd_lm_head_token_logprobs: log-probs straight from hidden states (d = 4096) and
+def bench_lm_head(args, torch, fb, wl, steps=None):
+    """Result record for fopd_lm_head_token_logprobs: log-probs straight from hidden states (d = 4096) and
     the [V, d] output projection, on as many rows as the workload has, with its mask."""
+    steps = args.steps if steps is None else steps
     seq_lens, mask = wl.structure_only(args.workload, seed=0)
     T, d, V = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"])
     w = wl.generate_lm_head(T, d, V, "cuda:0", seed=0)
@@ -138,7 +139,7 @@ def bench_lm_head(args, torch, fb, wl):
     fb.fopd_profile_reset()
     fb.fopd_profile_enable(True)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -149,17 +150,17 @@ def bench_lm_head(args, torch, fb, wl):
     k7_ms, n7 = fb.fopd_profile_read(3)
     k7_s = k7_ms / max(n7, 1) * 1e-3
     flops = 2.0 * T * V * d                             # every row is multiplied, masked or not
-    print(json.dumps({
+    return {
         "metric": "tokens/s, token log-probs from hidden states (projection fused, logits never stored), "
                   "V=%d d=%d bf16" % (V, d),
-        "value": int((mask != 0).sum()) * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "value": int((mask != 0).sum()) * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d,
                    "call": "fopd_lm_head_token_logprobs"},
         "roofline": {"bound": "mfma", "kernel": "fopd_k7_lm_head_lse", "achieved": flops / k7_s / 1e12,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops / k7_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}))
+                     "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}
 
 
 def main():
@@ -169,6 +170,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="reasoning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-projection", action="store_true",
+                    help="skip the projection-fused log-prob measurement reported beside the headline")
     ap.add_argument("--variant", choices=("default", "full_kl", "lm_head"), default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
                          "(stale-checkpoint) logits tensor; lm_head: token log-probs from hidden states with "
@@ -190,7 +193,8 @@ def main():
     if args.variant == "full_kl":
         return bench_full_kl(args, torch, fb, wl, LossPass, hp)
     if args.variant == "lm_head":
-        return bench_lm_head(args, torch, fb, wl)
+        print(json.dumps(bench_lm_head(args, torch, fb, wl)))
+        return
     w = wl.generate(args.workload, "cuda:0", seed=0)
     T, V, B = w["T"], w["V"], w["B"]
     lp = LossPass(T, V, B, w["dtype"], ld=w["ld"], device="cuda:0")
@@ -283,6 +287,13 @@ def main():
         "frac": k4_bytes / k14_avg_s / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, hp)
+    if not args.no_projection:
+        # beside the headline: the step in front of the path (its own line under --variant lm_head)
+        del lp
+        rec = bench_lm_head(args, torch, fb, wl, steps=min(args.steps, 5))
+        out["projection_fused"] = {"call": rec["config"]["call"], "d": rec["config"]["d"],
+                                   "ms_per_call": rec["ms_per_step"], "tokens/s": rec["value"],
+                                   "roofline": rec["roofline"]}
     print(json.dumps(out))
 
 
