@@ -160,3 +160,40 @@ def test_header_is_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
                         "-c", str(src), "-o", str(obj)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def _lmh(lib, hidden=4096, ldh=64, weight=8192, ldw=64, T=8, V=100, d=64, ids=4096, logp=4096, lse=4096, ws=4096,
+         wsb=1 << 20):
+    return lib.fopd_lm_head_token_logprobs(P(hidden), ldh, P(weight), ldw, T, V, d, P(ids), None, P(logp), P(lse),
+                                           P(ws), wsb, None)
+
+
+def test_projection_entry_point_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _lmh(lib, hidden=None) == 1           # EINVAL
+    assert _lmh(lib, weight=None) == 1
+    assert _lmh(lib, ids=None) == 1
+    assert _lmh(lib, lse=None) == 1
+    assert _lmh(lib, d=0) == 2                   # ESHAPE
+    assert _lmh(lib, d=96, ldh=96, ldw=96) == 2  # hidden size must be a multiple of 64
+    assert _lmh(lib, ldh=32) == 2                # pitch below d
+    assert _lmh(lib, ldw=56) == 2
+    assert _lmh(lib, T=-1) == 2
+    assert _lmh(lib, V=0) == 2
+    assert _lmh(lib, T=1 << 20, ldh=1 << 11) == 2           # T * ldh reaches 2^31
+    assert _lmh(lib, V=1 << 19, ldw=1 << 12) == 2           # V * ldw reaches 2^31
+    assert _lmh(lib, hidden=4104) == 3           # EALIGN: base not on 16 bytes
+    assert _lmh(lib, ldh=68) == 3                # row pitch not a multiple of 16 bytes
+    assert _lmh(lib, ws=None) == 5               # EWORKSPACE
+    assert _lmh(lib, ws=4100) == 5
+    assert _lmh(lib, wsb=1024) == 5
+    assert _lmh(lib, T=0) == 0                   # nothing to do, nothing launched
+
+
+def test_projection_workspace_bytes():
+    a = fb.fopd_lm_head_workspace_bytes(1)
+    b = fb.fopd_lm_head_workspace_bytes(256)
+    c = fb.fopd_lm_head_workspace_bytes(257)
+    assert a == b and c > b and a % 256 == 0     # rows are padded to whole 256-token tiles
+    assert fb.fopd_lm_head_workspace_bytes(163894) >= 163894 * 32 * 8
+    assert fb.fopd_lm_head_workspace_bytes(0) >= 256
