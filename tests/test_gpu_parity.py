@@ -980,6 +980,34 @@ LM_HEAD_CASES = {
 
 
 @pytest.mark.gpu
+def test_projection_fused_replay_from_a_hip_graph():
+    """After one eager call (which sets the kernel's LDS attribute) the entry point enqueues two kernels and
+    nothing else, so it can be captured; replays with eager work in between reproduce the eager bits."""
+    w = wl.generate_lm_head(600, 128, 5000, DEV, seed=9, masked_every=11)
+    logp_e, lse_e, ws = _lm_head_call(w)
+    torch.cuda.synchronize()
+    logp = torch.zeros_like(logp_e)
+    lse = torch.zeros_like(lse_e)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        fb.fopd_lm_head_token_logprobs(w["hidden"], w["ldh"], w["weight"], w["ldw"], w["T"], w["V"], w["d"],
+                                       w["token_ids"], w["mask"], logp, lse, ws)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        logp.fill_(float(rep))
+        lse.fill_(-1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(logp, logp_e) and torch.equal(lse, lse_e)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+
+
+@pytest.mark.gpu
 def test_projection_fused_wide_logits():
     """Logits with a spread of 40 (row maxima around 150): the running reference rises by tens between
     vocabulary tiles, so every rescale path of the on-the-fly log-sum-exp is taken."""
