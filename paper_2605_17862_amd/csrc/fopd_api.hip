@@ -119,6 +119,18 @@ struct Options {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 
+// A kernel that wants more dynamic LDS than the default limit has to be told so once per device.
+// `done` is the caller's per-kernel table of devices already told.
+constexpr int kMaxDevices = 64;
+inline fopd_status allow_dynamic_lds(const void* kern, int bytes, bool* done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FOPD_EHIP;
+  if (done[dev]) return FOPD_OK;
+  if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return FOPD_EHIP;
+  done[dev] = true;
+  return FOPD_OK;
+}
+
 // ---- launch helpers ---------------------------------------------------------------------
 
 fopd_status launch_k1(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
@@ -163,14 +175,10 @@ fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V
                          int32_t* flags, hipStream_t s) {
   auto kern = fopd_k14_fused<DT, NT, kUnroll>;
   // dynamic LDS is requested only to cap the workgroups resident per compute unit; the kernel is told
-  // once (per instantiation) that it may be given up to a whole CU's worth
-  static bool allowed = false;
-  if (!allowed) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(kLdsPerCu - 1024)) != hipSuccess)
-      return FOPD_EHIP;
-    allowed = true;
-  }
+  // once per instantiation and device that it may be given up to a whole CU's worth
+  static bool allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), static_cast<int>(kLdsPerCu - 1024), allowed) != FOPD_OK)
+    return FOPD_EHIP;
   const size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
   kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
                                                             token_ids, mask, lb, lq, cu, n_train, fresh32, B,
@@ -572,13 +580,8 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   if (T == 0) return FOPD_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   auto kern = fopd_k7_lm_head_lse;
-  static bool allowed = false;
-  if (!allowed) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kLmLdsBytes) != hipSuccess)
-      return FOPD_EHIP;
-    allowed = true;
-  }
+  static bool allowed[kMaxDevices] = {};
+  if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), kLmLdsBytes, allowed) != FOPD_OK) return FOPD_EHIP;
   const int n_token_tiles = static_cast<int>(lay.t_pad / kLmTile);
   const int n_vocab_tiles = static_cast<int>((V + kLmTile - 1) / kLmTile);
   // strips: 8, 16 or 32, whichever leaves the smallest idle tail when the work items (token tile x strip,
