@@ -67,16 +67,26 @@ def cpu_baseline(w, hp, budget_rows=6000):
 
 
 def bench_full_kl(args, torch, fb, wl, LossPass, hp):
-    """One JSON line for fopd_loss_fwd_bwd_full_kl on the same workload plus stale-checkpoint logits."""
+    """One JSON line for the two-tensor variants on the same workload plus a second logits tensor:
+    fopd_loss_fwd_bwd_full_kl (second tensor = stale checkpoint) or, with --variant full_teacher,
+    fopd_loss_fwd_bwd_full_teacher (second tensor = teacher; the same two kernels)."""
+    teacher = args.variant == "full_teacher"
     w = wl.generate(args.workload, "cuda:0", seed=0, stale_logit_sigma=0.03)
     T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
     lp = LossPass(T, V, B, w["dtype"], ld=ld, device="cuda:0")
     kl = torch.empty(T, device="cuda:0")
 
     def step():
-        fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
-                                     w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, 1.0,
-                                     lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+        if teacher:
+            fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
+                                              w["mask"], w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"],
+                                              B, hp, 1.0, lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits,
+                                              lp.workspace)
+        else:
+            fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
+                                         w["mask"], w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"],
+                                         w["lag"], B, hp, 1.0, lp.loss, lp.freshness, lp.weights, lp.logp, kl,
+                                         lp.dlogits, lp.workspace)
 
     for _ in range(args.warmup):
         step()
@@ -97,12 +107,15 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
     k6_bytes = live * 3 * V * e + (T - live) * V * e
     k5_s, k6_s = k5_ms / max(n5, 1) * 1e-3, k6_ms / max(n6, 1) * 1e-3
     print(json.dumps({
-        "metric": "tokens/s, OPD loss fwd+bwd with full-vocabulary rollout KL, V=%d %s" % (V, w["dtype"]),
+        "metric": ("tokens/s, OPD loss fwd+bwd with distribution-level loss against teacher logits, V=%d %s"
+                   if teacher else "tokens/s, OPD loss fwd+bwd with full-vocabulary rollout KL, V=%d %s")
+                  % (V, w["dtype"]),
         "value": w["n_trainable"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload + "+stale_logits", "B": B, "T_rows": T, "V": V, "storage": w["dtype"],
-                   "call": "fopd_loss_fwd_bwd_full_kl"},
+        "config": {"workload": args.workload + ("+teacher_logits" if teacher else "+stale_logits"), "B": B,
+                   "T_rows": T, "V": V, "storage": w["dtype"],
+                   "call": "fopd_loss_fwd_bwd_full_teacher" if teacher else "fopd_loss_fwd_bwd_full_kl"},
         "roofline": {"bound": "hbm", "kernel": "fopd_k6_grad_kl", "achieved": k6_bytes / k6_s / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k6_bytes / k6_s / 1e9 / HBM_PEAK_GBS,
                      "traffic": None, "bytes_per_launch": k6_bytes, "avg_ms": k6_s * 1e3},
@@ -172,7 +185,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-projection", action="store_true",
                     help="skip the projection-fused log-prob measurement reported beside the headline")
-    ap.add_argument("--variant", choices=("default", "full_kl", "lm_head"), default="default",
+    ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head"), default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
                          "(stale-checkpoint) logits tensor; lm_head: token log-probs from hidden states with "
                          "the output projection fused in.  Each is reported as its own line, not the headline")
@@ -190,7 +203,7 @@ def main():
         sys.exit("bench.py needs a GPU")
     fb.load_library()
     hp = DEFAULT_HPARAMS
-    if args.variant == "full_kl":
+    if args.variant in ("full_kl", "full_teacher"):
         return bench_full_kl(args, torch, fb, wl, LossPass, hp)
     if args.variant == "lm_head":
         print(json.dumps(bench_lm_head(args, torch, fb, wl)))
