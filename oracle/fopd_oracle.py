@@ -24,7 +24,10 @@ Readings of the paper that this oracle fixes (the paper leaves them open):
 * ``D_i^sup`` (Eq. "kl-diagnostics", second line) uses the same ``k`` on the teacher's
   current-context minus stale-context log-probability, or is 0 when no stale-context array
   is given (Remark "When the supervision gap is negligible").
-* One 0/1 mask stands for both aligned sets U_i^roll and U_i^sup.
+* The two aligned sets U_i^roll and U_i^sup (Sec. 4.1) come in one byte per row: 0 = in neither,
+  1 = in both (so a plain 0/1 loss mask means "both"), 2 = in U^roll only, 3 = in U^sup only; any other
+  non-zero value counts as 1.  D^roll averages over U^roll; D^sup and the token loss over U^sup; a sample
+  with either set empty is invalid (Algorithm 1).
 * The expectation over the buffer divides by the number of samples B, whether or not a
   sample is gated or invalid (Algorithm 1, anchored minibatch loss).
 * Freshness weights are constants in the gradient (Algorithm 1 scores the buffer before the
@@ -54,17 +57,37 @@ def segment_offsets(seq_lens):
     return cu
 
 
+def in_sup_set(m):
+    """Row belongs to U^sup (teacher contexts comparable: the token loss and D^sup use it)."""
+    return int(m) != 0 and int(m) != 2
+
+
+def in_roll_set(m):
+    """Row belongs to U^roll (replay under the stale policy comparable: D^roll uses it)."""
+    return int(m) != 0 and int(m) != 3
+
+
 def trainable_counts(mask, cu):
-    """n_i = |U_i| = number of mask==1 rows inside segment i (Sec. 4.1, aligned sets)."""
+    """n_i = |U_i^sup| = number of rows of segment i that carry the token loss (Sec. 4.1, aligned sets)."""
     mask = np.asarray(mask)
     B = cu.shape[0] - 1
     n = np.zeros(B, dtype=np.int32)
     for i in range(B):
         cnt = 0
         for t in range(int(cu[i]), int(cu[i + 1])):
-            if mask[t] != 0:
+            if in_sup_set(mask[t]):
                 cnt += 1
         n[i] = cnt
+    return n
+
+
+def roll_counts(mask, cu):
+    """|U_i^roll| = number of rows of segment i on which the rollout drift is measured."""
+    mask = np.asarray(mask)
+    B = cu.shape[0] - 1
+    n = np.zeros(B, dtype=np.int32)
+    for i in range(B):
+        n[i] = sum(1 for t in range(int(cu[i]), int(cu[i + 1])) if in_roll_set(mask[t]))
     return n
 
 
@@ -178,10 +201,12 @@ def token_terms(logp, behav_logp, teacher_logp, teacher_logp_stale=None):
 # alignment ratios)
 # ----------------------------------------------------------------------------------------
 
-def sample_statistics(logp, teacher_logp, k_roll, k_sup, mask, cu):
-    """D_i^roll, D_i^sup, l_i (token means over the mask) and cover_i = n_i / H_i.
+def sample_statistics(logp, teacher_logp, k_roll, k_sup, mask, cu, token_loss=None):
+    """D_i^roll (token mean over U_i^roll), D_i^sup and l_i (token means over U_i^sup),
+    cover_i = |U_i^sup| / H_i and n_i = |U_i^sup|.  token_loss: per-row loss values if not the
+    sampled-token form lp - lq.
 
-    Samples with n_i = 0 get zeros everywhere (Algorithm 1, invalid-sample branch)."""
+    Samples with either aligned set empty get zeros everywhere (Algorithm 1, invalid-sample branch)."""
     lp = np.asarray(logp, dtype=np.float64)
     lq = np.asarray(teacher_logp, dtype=np.float64)
     B = cu.shape[0] - 1
@@ -190,17 +215,36 @@ def sample_statistics(logp, teacher_logp, k_roll, k_sup, mask, cu):
     ell = np.zeros(B)
     cover = np.zeros(B)
     n = trainable_counts(mask, cu)
+    n_roll = roll_counts(mask, cu)
     for i in range(B):
         a, b = int(cu[i]), int(cu[i + 1])
         H = b - a
-        if n[i] == 0:
+        if n[i] == 0 or n_roll[i] == 0:
             continue
-        rows = [t for t in range(a, b) if mask[t] != 0]
-        D_roll[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])
+        rows = [t for t in range(a, b) if in_sup_set(mask[t])]
+        rows_roll = [t for t in range(a, b) if in_roll_set(mask[t])]
+        D_roll[i] = math.fsum(float(k_roll[t]) for t in rows_roll) / int(n_roll[i])
         D_sup[i] = math.fsum(float(k_sup[t]) for t in rows) / int(n[i])
-        ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / int(n[i])
+        if token_loss is None:
+            ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / int(n[i])
+        else:
+            ell[i] = math.fsum(float(token_loss[t]) for t in rows) / int(n[i])
         cover[i] = int(n[i]) / H
     return D_roll, D_sup, ell, cover, n
+
+
+def roll_coverage(mask, cu):
+    """m_i^roll = |U_i^roll| / H_i (0 for an invalid sample), and the validity count min(|U^sup|, |U^roll|),
+    which is 0 exactly for the samples Algorithm 1 marks invalid."""
+    n = trainable_counts(mask, cu)
+    n_roll = roll_counts(mask, cu)
+    B = cu.shape[0] - 1
+    cover_roll = np.zeros(B)
+    for i in range(B):
+        if n[i] == 0 or n_roll[i] == 0:
+            continue
+        cover_roll[i] = int(n_roll[i]) / (int(cu[i + 1]) - int(cu[i]))
+    return cover_roll, n_roll, np.minimum(n, n_roll)
 
 
 # ----------------------------------------------------------------------------------------
@@ -208,7 +252,8 @@ def sample_statistics(logp, teacher_logp, k_roll, k_sup, mask, cu):
 # ----------------------------------------------------------------------------------------
 
 def freshness_score(D_roll, D_sup, lag, n_train, alpha, beta):
-    """f_i = exp(-(alpha*sqrt(D_i^roll) + beta*sqrt(D_i^sup))) / (tau_i + 1); 0 if n_i = 0."""
+    """f_i = exp(-(alpha*sqrt(D_i^roll) + beta*sqrt(D_i^sup))) / (tau_i + 1); 0 for an invalid sample
+    (n_train[i] = 0: pass min(|U^sup|, |U^roll|) when the two sets differ)."""
     if alpha < 0 or beta < 0:
         raise ValueError("alpha, beta must be non-negative (Eq. freshness)")
     B = len(D_roll)
@@ -224,17 +269,19 @@ def freshness_score(D_roll, D_sup, lag, n_train, alpha, beta):
     return f
 
 
-def buffer_aggregates(f, cover):
-    """(mean freshness, mean roll coverage, mean sup coverage) over all B samples.
-    One mask serves both aligned sets, so the two coverage means coincide."""
+def buffer_aggregates(f, cover, cover_roll=None):
+    """(mean freshness, mean roll coverage, mean sup coverage) over all B samples (Sec. 4.2).
+    cover is m^sup; cover_roll = None means the two aligned sets coincide."""
     B = len(f)
     fbar = math.fsum(float(x) for x in f) / B
     mbar = math.fsum(float(x) for x in cover) / B
-    return np.array([fbar, mbar, mbar])
+    mroll = mbar if cover_roll is None else math.fsum(float(x) for x in cover_roll) / B
+    return np.array([fbar, mroll, mbar])
 
 
 def freshness_weights(f, xi, n_train):
-    """w_i = ReLU(f_i - xi); invalid samples (n_i = 0) are excluded whatever xi is."""
+    """w_i = ReLU(f_i - xi); invalid samples (n_train[i] = 0, see freshness_score) are excluded
+    whatever xi is."""
     w = np.zeros(len(f))
     for i in range(len(f)):
         if int(n_train[i]) == 0:
@@ -313,25 +360,25 @@ def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, token_ids, mask, teacher_log
     else:
         k_sup = kl_estimator(lq - np.asarray(teacher_logp_stale, dtype=np.float64))
     D_roll, D_sup, ell, cover, n = sample_statistics(lp, lq, kl, k_sup, mask, cu)
-    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
-    agg = buffer_aggregates(f, cover)
-    w = freshness_weights(f, xi, n)
+    cover_roll, n_roll, n_valid = roll_coverage(mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n_valid, alpha, beta)
+    agg = buffer_aggregates(f, cover, cover_roll)
+    w = freshness_weights(f, xi, n_valid)
     loss = anchored_loss(w, ell, D_roll, lam)
     B = len(n)
     c1 = np.zeros(T)
     c2 = np.zeros(T)
     for i in range(B):
-        if int(n[i]) == 0 or w[i] == 0.0:
+        if int(n_valid[i]) == 0 or w[i] == 0.0:
             continue
         for t in range(int(cu[i]), int(cu[i + 1])):
-            if mask[t] == 0:
-                continue
-            pref = grad_scale * w[i] / (B * int(n[i]))
-            c1[t] = pref * adv[t]
-            c2[t] = pref * lam
-    res = dict(cu_seqlens=cu, n_train=n, lse=lse, lse_stale=lse_stale, logp=lp, adv=adv, roll_kl=kl,
-               D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover, freshness=f, agg=agg, weights=w, loss=loss,
-               c1=c1, c2=c2)
+            if in_sup_set(mask[t]):
+                c1[t] = grad_scale * w[i] / (B * int(n[i])) * adv[t]
+            if in_roll_set(mask[t]):
+                c2[t] = grad_scale * w[i] / (B * int(n_roll[i])) * lam
+    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, lse=lse, lse_stale=lse_stale, logp=lp, adv=adv, roll_kl=kl,
+               D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover, cover_roll=cover_roll, freshness=f, agg=agg,
+               weights=w, loss=loss, c1=c1, c2=c2)
     if want_dlogits:
         g = np.zeros((T, V))
         for t in range(T):
@@ -363,33 +410,25 @@ def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, token_ids, mask, beha
     tok_kl, _, _ = rollout_kl_full(logits, teacher_logits, mask)     # KL(student || teacher) per row
     delta, rho, _, k_roll, k_sup = token_terms(lp, behav_logp, lq, teacher_logp_stale)
     B = cu.shape[0] - 1
-    n = trainable_counts(mask, cu)
-    D_roll, D_sup, ell, cover = np.zeros(B), np.zeros(B), np.zeros(B), np.zeros(B)
-    for i in range(B):
-        if n[i] == 0:
-            continue
-        rows = [t for t in range(int(cu[i]), int(cu[i + 1])) if mask[t] != 0]
-        D_roll[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])
-        D_sup[i] = math.fsum(float(k_sup[t]) for t in rows) / int(n[i])
-        ell[i] = math.fsum(float(tok_kl[t]) for t in rows) / int(n[i])
-        cover[i] = int(n[i]) / (int(cu[i + 1]) - int(cu[i]))
-    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
-    agg = buffer_aggregates(f, cover)
-    w = freshness_weights(f, xi, n)
+    D_roll, D_sup, ell, cover, n = sample_statistics(lp, lq, k_roll, k_sup, mask, cu, token_loss=tok_kl)
+    cover_roll, n_roll, n_valid = roll_coverage(mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n_valid, alpha, beta)
+    agg = buffer_aggregates(f, cover, cover_roll)
+    w = freshness_weights(f, xi, n_valid)
     loss = anchored_loss(w, ell, D_roll, lam)
     c1, c2 = np.zeros(T), np.zeros(T)
     for i in range(B):
-        if int(n[i]) == 0 or w[i] == 0.0:
+        if int(n_valid[i]) == 0 or w[i] == 0.0:
             continue
         for t in range(int(cu[i]), int(cu[i + 1])):
-            if mask[t] == 0:
-                continue
-            pref = grad_scale * w[i] / (B * int(n[i]))
-            c1[t] = -pref * lam * rho[t] * delta[t]
-            c2[t] = pref
-    res = dict(cu_seqlens=cu, n_train=n, lse=lse, lse_stale=lse_q, logp=lp, teacher_logp=lq, roll_kl=tok_kl,
-               token_kl=tok_kl, delta=delta, rho=rho, adv=-lam * rho * delta, D_roll=D_roll, D_sup=D_sup, ell=ell,
-               cover=cover, freshness=f, agg=agg, weights=w, loss=loss, c1=c1, c2=c2)
+            if in_roll_set(mask[t]):
+                c1[t] = -grad_scale * w[i] / (B * int(n_roll[i])) * lam * rho[t] * delta[t]
+            if in_sup_set(mask[t]):
+                c2[t] = grad_scale * w[i] / (B * int(n[i]))
+    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, lse=lse, lse_stale=lse_q, logp=lp, teacher_logp=lq,
+               roll_kl=tok_kl, token_kl=tok_kl, delta=delta, rho=rho, adv=-lam * rho * delta, D_roll=D_roll,
+               D_sup=D_sup, ell=ell, cover=cover, cover_roll=cover_roll, freshness=f, agg=agg, weights=w, loss=loss,
+               c1=c1, c2=c2)
     if want_dlogits:
         g = np.zeros((T, V))
         for t in range(T):
@@ -420,24 +459,30 @@ def refresh_decision(agg, kappa_f, kappa_roll, kappa_sup, step, last_refresh_ste
 # gradient with respect to the logits
 # ----------------------------------------------------------------------------------------
 
-def grad_coefficients(delta, rho, adv, mask, cu, n_train, w, lam, grad_scale=1.0, n_samples=None):
-    """c_t = g * m_t * w_i / (B * n_i) * (A_t - lambda * rho_t * delta_t).
+def grad_coefficients(delta, rho, adv, mask, cu, n_train, w, lam, grad_scale=1.0, n_samples=None, n_roll=None):
+    """c_t = g * w_i / B * ( [t in U^sup] A_t / |U_i^sup|  -  [t in U^roll] lambda * rho_t * delta_t / |U_i^roll| ),
+    which for coinciding sets is g * m_t * w_i / (B * n_i) * (A_t - lambda * rho_t * delta_t).
 
     B is the number of samples of the whole buffer: len(cu) - 1, or `n_samples` when the arrays
-    passed in hold only some of the buffer's samples.
+    passed in hold only some of the buffer's samples.  n_roll = None: |U^roll| = |U^sup| = n_train.
 
     d(-A*lp)/dz = A*(p - onehot) with A constant; d(lambda*k(delta))/dlp = lambda*rho*delta,
     and dlp/dz = onehot - p, hence the minus sign on the anchor part."""
     T = len(delta)
     B = cu.shape[0] - 1 if n_samples is None else int(n_samples)
+    if n_roll is None:
+        n_roll = n_train
     c = np.zeros(T)
     for i in range(cu.shape[0] - 1):
-        if int(n_train[i]) == 0 or w[i] == 0.0:
+        if int(n_train[i]) == 0 or int(n_roll[i]) == 0 or w[i] == 0.0:
             continue
         for t in range(int(cu[i]), int(cu[i + 1])):
-            if mask[t] == 0:
-                continue
-            c[t] = grad_scale * w[i] / (B * int(n_train[i])) * (adv[t] - lam * rho[t] * delta[t])
+            part = 0.0
+            if in_sup_set(mask[t]):
+                part += adv[t] / int(n_train[i])
+            if in_roll_set(mask[t]):
+                part -= lam * rho[t] * delta[t] / int(n_roll[i])
+            c[t] = grad_scale * w[i] / B * part
     return c
 
 
@@ -505,14 +550,15 @@ def fopd_loss_fwd_bwd(logits, token_ids, mask, behav_logp, teacher_logp, teacher
     lse, lp = token_logprobs(logits, token_ids, mask)
     delta, rho, adv, k_roll, k_sup = token_terms(lp, behav_logp, teacher_logp, teacher_logp_stale)
     D_roll, D_sup, ell, cover, n = sample_statistics(lp, teacher_logp, k_roll, k_sup, mask, cu)
-    f = freshness_score(D_roll, D_sup, lag, n, alpha, beta)
-    agg = buffer_aggregates(f, cover)
-    w = freshness_weights(f, xi, n)
+    cover_roll, n_roll, n_valid = roll_coverage(mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n_valid, alpha, beta)
+    agg = buffer_aggregates(f, cover, cover_roll)
+    w = freshness_weights(f, xi, n_valid)
     loss = anchored_loss(w, ell, D_roll, lam)
-    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale)
-    res = dict(cu_seqlens=cu, n_train=n, gather_idx=gidx, lse=lse, logp=lp, delta=delta,
+    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)
+    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, gather_idx=gidx, lse=lse, logp=lp, delta=delta,
                rho=rho, adv=adv, k_roll=k_roll, k_sup=k_sup, D_roll=D_roll, D_sup=D_sup,
-               ell=ell, cover=cover, freshness=f, agg=agg, weights=w, loss=loss, coef=coef)
+               ell=ell, cover=cover, cover_roll=cover_roll, freshness=f, agg=agg, weights=w, loss=loss, coef=coef)
     if want_dlogits:
         g = np.zeros((T, V), dtype=np.float64)
         for t in range(T):

@@ -665,3 +665,224 @@ def test_projection_by_integer_brute_force_and_special_cases():
     np.testing.assert_allclose(l1 - l0, h @ c, atol=1e-13)
     with pytest.raises(ValueError):
         orc.lm_head_logits(np.zeros((2, 3)), np.zeros((3, 2)))
+
+
+# ---------------------------------------------------------------------------------------
+# two aligned sets: U^roll carries the rollout drift, U^sup the token loss and supervision drift
+# ---------------------------------------------------------------------------------------
+
+def _two_set_case(seed):
+    c = _tiny_case(seed, V=9, seq=(6, 5, 4, 7, 3), lag=(0, 1, 2, 0, 1))
+    rng = _rng(seed + 1000)
+    c["mask"] = rng.integers(0, 4, size=len(c["mask"])).astype(np.uint8)      # 0 none, 1 both, 2 roll, 3 sup
+    c["mask"][6:11] = np.array([3, 3, 0, 3, 3], dtype=np.uint8)              # sample 1: U^roll empty -> invalid
+    c["mask"][11:15] = np.array([2, 0, 2, 2], dtype=np.uint8)               # sample 2: U^sup empty -> invalid
+    c["mask"][0:6] = np.array([1, 2, 3, 0, 2, 2], dtype=np.uint8)           # sample 0: all four kinds
+    return c
+
+
+def _scalar_two_sets(c, alpha, beta, xi, lam, g):
+    """Algorithm 1 with the two sets kept apart, in plain Python floats."""
+    z, y, mask = c["z"], c["y"], c["mask"]
+    T, V = z.shape
+    B = len(c["seq"])
+    k = lambda d: math.exp(d) * d - math.exp(d) + 1.0
+    res = dict(f=[], w=[], Dr=[], Ds=[], ell=[], m_roll=[], m_sup=[], grads=[[0.0] * V for _ in range(T)], loss=0.0)
+    start = 0
+    for i in range(B):
+        H = int(c["seq"][i])
+        idx = range(start, start + H)
+        start += H
+        U_roll = [t for t in idx if mask[t] in (1, 2)]
+        U_sup = [t for t in idx if mask[t] in (1, 3)]
+        if not U_roll or not U_sup:                       # invalid-sample branch: f = 0, both ratios 0
+            for key in ("f", "w", "Dr", "Ds", "ell", "m_roll", "m_sup"):
+                res[key].append(0.0)
+            continue
+        lp, lse = {}, {}
+        for t in set(U_roll) | set(U_sup):
+            mx = max(float(v) for v in z[t])
+            lse[t] = mx + math.log(sum(math.exp(float(v) - mx) for v in z[t]))
+            lp[t] = float(z[t][y[t]]) - lse[t]
+        Dr = sum(k(lp[t] - c["lb"][t]) for t in U_roll) / len(U_roll)
+        Ds = sum(k(c["lq"][t] - c["lqs"][t]) for t in U_sup) / len(U_sup)
+        el = sum(lp[t] - c["lq"][t] for t in U_sup) / len(U_sup)
+        f = math.exp(-alpha * math.sqrt(Dr) - beta * math.sqrt(Ds)) / (int(c["lag"][i]) + 1)
+        w = max(f - xi, 0.0)
+        res["loss"] += w * (el + lam * Dr) / B
+        for t in set(U_roll) | set(U_sup):
+            ct = 0.0
+            if t in U_sup:
+                ct += (c["lq"][t] - lp[t]) / len(U_sup)
+            if t in U_roll:
+                d = lp[t] - c["lb"][t]
+                ct -= lam * math.exp(d) * d / len(U_roll)
+            ct *= g * w / B
+            for v in range(V):
+                res["grads"][t][v] = ct * (math.exp(float(z[t][v]) - lse[t]) - (1.0 if v == y[t] else 0.0))
+        for key, val in (("f", f), ("w", w), ("Dr", Dr), ("Ds", Ds), ("ell", el),
+                         ("m_roll", len(U_roll) / H), ("m_sup", len(U_sup) / H)):
+            res[key].append(val)
+    res["grads"] = np.array(res["grads"])
+    return res
+
+
+@pytest.mark.parametrize("seed", [30, 31])
+def test_two_aligned_sets_against_scalar_reimplementation(seed):
+    c = _two_set_case(seed)
+    hp = dict(alpha=0.9, beta=1.4, xi=0.1, lam=0.6)
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                grad_scale=0.7, **hp)
+    ref = _scalar_two_sets(c, hp["alpha"], hp["beta"], hp["xi"], hp["lam"], 0.7)
+    np.testing.assert_allclose(res["freshness"], ref["f"], rtol=1e-13, atol=0)
+    np.testing.assert_allclose(res["weights"], ref["w"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["D_roll"], ref["Dr"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["D_sup"], ref["Ds"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["ell"], ref["ell"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(res["cover"], ref["m_sup"], rtol=1e-15)
+    np.testing.assert_allclose(res["cover_roll"], ref["m_roll"], rtol=1e-15)
+    assert abs(res["loss"] - ref["loss"]) < 1e-14
+    np.testing.assert_allclose(res["dlogits_exact"], ref["grads"], rtol=1e-11, atol=1e-16)
+    # either set empty: invalid, whatever the other holds (Algorithm 1)
+    assert res["freshness"][1] == 0.0 and res["freshness"][2] == 0.0
+    assert res["cover"][1] == 0.0 and res["cover_roll"][2] == 0.0
+    assert not np.any(res["dlogits_exact"][6:15])
+    # the two coverage means are different numbers now
+    np.testing.assert_allclose(res["agg"][1], np.mean(ref["m_roll"]), rtol=1e-15)
+    np.testing.assert_allclose(res["agg"][2], np.mean(ref["m_sup"]), rtol=1e-15)
+    assert res["cover_roll"][0] == 4 / 6 and res["cover"][0] == 2 / 6
+    # a row in U^roll only has a gradient from the anchor alone; with lambda = 0 it is exactly zero
+    res0 = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                 alpha=0.9, beta=1.4, xi=0.1, lam=0.0)
+    assert np.any(res["dlogits_exact"][1]) and not np.any(res0["dlogits_exact"][1])
+    assert np.any(res0["dlogits_exact"][2])                # a U^sup-only row (row 2) keeps the loss term
+    # an invalid sample has weight 0 whatever the threshold is, also a negative one
+    resn = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                 alpha=0.9, beta=1.4, xi=-0.5, lam=0.6)
+    assert resn["weights"][1] == 0.0 and resn["weights"][2] == 0.0 and resn["weights"][0] > 0.5
+    assert not np.any(resn["dlogits_exact"][6:15])
+
+
+def test_two_aligned_sets_plain_mask_means_both_and_counts():
+    c = _two_set_case(33)
+    cu = orc.segment_offsets(c["seq"])
+    n_sup, n_roll = orc.trainable_counts(c["mask"], cu), orc.roll_counts(c["mask"], cu)
+    start = 0
+    for i, H in enumerate(c["seq"]):
+        seg = [int(m) for m in c["mask"][start:start + int(H)]]
+        start += int(H)
+        assert n_sup[i] == sum(1 for m in seg if m in (1, 3)) and n_roll[i] == sum(1 for m in seg if m in (1, 2))
+    # a 0/1 mask (and any other non-zero byte) puts a row in both sets
+    both = (c["mask"] != 0).astype(np.uint8)
+    odd = both * 255
+    assert np.array_equal(orc.trainable_counts(both, cu), orc.roll_counts(both, cu))
+    assert np.array_equal(orc.trainable_counts(odd, cu), orc.trainable_counts(both, cu))
+    assert np.array_equal(orc.roll_counts(odd, cu), orc.roll_counts(both, cu))
+
+
+def test_two_aligned_sets_gradient_by_finite_differences():
+    c = _two_set_case(34)
+    T, V = c["z"].shape
+    hp = dict(alpha=0.5, beta=0.5, xi=0.02, lam=0.8)
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"], **hp)
+    w, B = res["weights"], len(c["seq"])
+    cu = orc.segment_offsets(c["seq"])
+    n_sup, n_roll = orc.trainable_counts(c["mask"], cu), orc.roll_counts(c["mask"], cu)
+    sample_of = np.repeat(np.arange(B), c["seq"])
+
+    def F(zz):
+        """Surrogate with the weights frozen: its gradient is the method's semi-gradient."""
+        lp_all = scipy.special.log_softmax(zz, axis=1)
+        tot = 0.0
+        for t in range(T):
+            i = sample_of[t]
+            if w[i] == 0.0:
+                continue
+            lp = lp_all[t, c["y"][t]]
+            if c["mask"][t] in (1, 3):
+                tot += w[i] / (B * n_sup[i]) * 0.5 * (lp - c["lq"][t]) ** 2
+            if c["mask"][t] in (1, 2):
+                d = lp - c["lb"][t]
+                tot += w[i] / (B * n_roll[i]) * hp["lam"] * (math.exp(d) * d - math.exp(d) + 1.0)
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = c["z"].copy(), c["z"].copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (F(zp) - F(zm)) / (2 * h)
+    assert np.max(np.abs(num - res["dlogits_exact"])) < 1e-6 * np.max(np.abs(num))
+
+
+def test_two_aligned_sets_in_the_two_tensor_variants():
+    """Full-vocabulary drift and distribution-level loss with the sets apart: D^roll over U^roll, the
+    token loss over U^sup, checked against the definitions evaluated with scipy."""
+    c = _two_set_case(35)
+    rng = _rng(77)
+    T, V = c["z"].shape
+    z2 = c["z"] + rng.normal(0, 0.3, size=(T, V))
+    cu = orc.segment_offsets(c["seq"])
+    lp_all = scipy.special.log_softmax(c["z"], axis=1)
+    l2_all = scipy.special.log_softmax(z2, axis=1)
+    kl_rows = np.sum(np.exp(lp_all) * (lp_all - l2_all), axis=1)
+    res = orc.fopd_loss_fwd_bwd_full_kl(c["z"], z2, c["y"], c["mask"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                        0.7, 0.7, 0.0, 0.5)
+    rest = orc.fopd_loss_fwd_bwd_full_teacher(c["z"], z2, c["y"], c["mask"], c["lb"], c["lqs"], c["seq"], c["lag"],
+                                              0.7, 0.7, 0.0, 0.5)
+    for i in (0, 3, 4):
+        rows = range(int(cu[i]), int(cu[i + 1]))
+        U_roll = [t for t in rows if c["mask"][t] in (1, 2)]
+        U_sup = [t for t in rows if c["mask"][t] in (1, 3)]
+        if not U_roll or not U_sup:
+            continue
+        np.testing.assert_allclose(res["D_roll"][i], np.mean(kl_rows[U_roll]), rtol=1e-12)
+        np.testing.assert_allclose(rest["ell"][i], np.mean(kl_rows[U_sup]), rtol=1e-12)
+    assert res["freshness"][1] == 0.0 and rest["freshness"][2] == 0.0
+    # coefficient supports: the advantage part lives on U^sup, the full-KL part on U^roll
+    assert np.all((res["c1"] != 0) <= np.isin(c["mask"], (1, 3))) and np.all((res["c2"] != 0) <= np.isin(c["mask"], (1, 2)))
+    assert np.all((rest["c2"] != 0) <= np.isin(c["mask"], (1, 3))) and np.all((rest["c1"] != 0) <= np.isin(c["mask"], (1, 2)))
+
+
+def test_two_aligned_sets_two_tensor_gradients_by_finite_differences():
+    c = _two_set_case(36)
+    rng = _rng(78)
+    T, V = c["z"].shape
+    z2 = c["z"] + rng.normal(0, 0.3, size=(T, V))
+    B = len(c["seq"])
+    cu = orc.segment_offsets(c["seq"])
+    n_sup, n_roll = orc.trainable_counts(c["mask"], cu), orc.roll_counts(c["mask"], cu)
+    sample_of = np.repeat(np.arange(B), c["seq"])
+    l2_all = scipy.special.log_softmax(z2, axis=1)
+    lam = 0.6
+    kl = orc.fopd_loss_fwd_bwd_full_kl(c["z"], z2, c["y"], c["mask"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                       0.4, 0.4, 0.01, lam, grad_scale=1.3)
+    te = orc.fopd_loss_fwd_bwd_full_teacher(c["z"], z2, c["y"], c["mask"], c["lb"], c["lqs"], c["seq"], c["lag"],
+                                            0.4, 0.4, 0.01, lam, grad_scale=1.3)
+
+    def surrogate(zz, w, teacher):
+        lp_all = scipy.special.log_softmax(zz, axis=1)
+        tot = 0.0
+        for t in range(T):
+            i = sample_of[t]
+            if w[i] == 0.0:
+                continue
+            lp = lp_all[t, c["y"][t]]
+            full = float(np.sum(np.exp(lp_all[t]) * (lp_all[t] - l2_all[t])))
+            if c["mask"][t] in (1, 3):                        # token loss on U^sup
+                tot += 1.3 * w[i] / (B * n_sup[i]) * (full if teacher else 0.5 * (lp - c["lq"][t]) ** 2)
+            if c["mask"][t] in (1, 2):                        # anchor on U^roll
+                d = lp - c["lb"][t]
+                tot += 1.3 * w[i] / (B * n_roll[i]) * lam * ((math.exp(d) * d - math.exp(d) + 1.0) if teacher else full)
+        return tot
+
+    h = 1e-6
+    for res, teacher in ((kl, False), (te, True)):
+        num = np.zeros((T, V))
+        for t, v in itertools.product(range(T), range(V)):
+            zp, zm = c["z"].copy(), c["z"].copy()
+            zp[t, v] += h
+            zm[t, v] -= h
+            num[t, v] = (surrogate(zp, res["weights"], teacher) - surrogate(zm, res["weights"], teacher)) / (2 * h)
+        assert np.max(np.abs(num - res["dlogits_exact"])) < 2e-6 * np.max(np.abs(num)), teacher

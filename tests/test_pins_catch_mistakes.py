@@ -31,10 +31,28 @@ MISTAKES = {
         "return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / B",
         "return math.fsum(float(w[i]) * (float(ell[i]) + lam * float(D_roll[i])) for i in range(B)) / "
         "max(1, sum(1 for i in range(B) if w[i] > 0))"),
-    "anchor gradient sign": ("* (adv[t] - lam * rho[t] * delta[t])", "* (adv[t] + lam * rho[t] * delta[t])"),
-    "anchor gradient loses rho": ("* (adv[t] - lam * rho[t] * delta[t])", "* (adv[t] - lam * delta[t])"),
+    "anchor gradient sign": ("part -= lam * rho[t] * delta[t] / int(n_roll[i])",
+                             "part += lam * rho[t] * delta[t] / int(n_roll[i])"),
+    "anchor gradient loses rho": ("part -= lam * rho[t] * delta[t] / int(n_roll[i])",
+                                  "part -= lam * delta[t] / int(n_roll[i])"),
     "coefficient normalised by H instead of n": (
-        "c[t] = grad_scale * w[i] / (B * int(n_train[i]))", "c[t] = grad_scale * w[i] / (B * int(cu[i + 1] - cu[i]))"),
+        "part += adv[t] / int(n_train[i])", "part += adv[t] / int(cu[i + 1] - cu[i])"),
+    "anchor normalised by the supervision count": ("part -= lam * rho[t] * delta[t] / int(n_roll[i])",
+                                                   "part -= lam * rho[t] * delta[t] / int(n_train[i])"),
+    "rollout drift averaged over the supervision set": (
+        "D_roll[i] = math.fsum(float(k_roll[t]) for t in rows_roll) / int(n_roll[i])",
+        "D_roll[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])"),
+    "token loss averaged over the rollout set": (
+        "            ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / int(n[i])",
+        "            ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows_roll) / int(n_roll[i])"),
+    "sample stays valid with one aligned set empty": (
+        "        if n[i] == 0 or n_roll[i] == 0:\n            continue\n        rows = ",
+        "        if n[i] == 0 and n_roll[i] == 0:\n            continue\n        rows = "),
+    "weights ignore an empty rollout set": ("    w = freshness_weights(f, xi, n_valid)\n    loss = anchored_loss(w, ell, D_roll, lam)\n    coef",
+                                            "    w = freshness_weights(f, xi, n)\n    loss = anchored_loss(w, ell, D_roll, lam)\n    coef"),
+    "roll coverage reported as sup coverage": (
+        "mroll = mbar if cover_roll is None else math.fsum(float(x) for x in cover_roll) / B", "mroll = mbar"),
+    "aligned sets swapped": ("    return int(m) != 0 and int(m) != 2\n", "    return int(m) != 0 and int(m) != 3\n"),
     "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
     "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
                                       "return float(np.log(np.sum(np.exp(z - mx))))"),
@@ -42,7 +60,7 @@ MISTAKES = {
                                   "ell[i] = math.fsum(float(lp[t] - lq[t]) for t in rows) / H"),
     "coverage inverted": ("cover[i] = int(n[i]) / H", "cover[i] = H / max(int(n[i]), 1)"),
     "bf16 rounding truncates": ("r = np.rint(x[fin] / quantum) * quantum", "r = np.trunc(x[fin] / quantum) * quantum"),
-    "mask ignored in the counts": ("            if mask[t] != 0:\n                cnt += 1", "            cnt += 1"),
+    "mask ignored in the counts": ("            if in_sup_set(mask[t]):\n                cnt += 1", "            cnt += 1"),
     "offsets start at the first length": ("cu[i + 1] = cu[i] + int(seq_lens[i])",
                                           "cu[i + 1] = cu[i] + int(seq_lens[min(i + 1, seq_lens.shape[0] - 1)])"),
     "gather index with the wrong pitch": ("out[t] = int(t) * int(ld) + int(token_ids[t])",
@@ -63,12 +81,14 @@ MISTAKES = {
         "D_sup[i] = math.fsum(float(k_roll[t]) for t in rows) / int(n[i])"),
     "buffer means over valid samples only": ("fbar = math.fsum(float(x) for x in f) / B",
                                              "fbar = math.fsum(float(x) for x in f) / max(1, sum(1 for x in f if x > 0))"),
-    "upstream scale dropped": ("c[t] = grad_scale * w[i] / (B * int(n_train[i]))", "c[t] = w[i] / (B * int(n_train[i]))"),
+    "upstream scale dropped": ("c[t] = grad_scale * w[i] / B * part", "c[t] = w[i] / B * part"),
     "bf16 spacing one bit too fine": ("quantum = np.ldexp(1.0, e - 7)          # spacing of bf16 numbers in that binade",
                                       "quantum = np.ldexp(1.0, e - 8)"),
-    "full-teacher anchor sign": ("c1[t] = -pref * lam * rho[t] * delta[t]", "c1[t] = pref * lam * rho[t] * delta[t]"),
-    "full-KL variant drops the advantage": ("            c1[t] = pref * adv[t]\n            c2[t] = pref * lam",
-                                            "            c1[t] = 0.0\n            c2[t] = pref * lam"),
+    "full-teacher anchor sign": ("c1[t] = -grad_scale * w[i] / (B * int(n_roll[i])) * lam * rho[t] * delta[t]",
+                                 "c1[t] = grad_scale * w[i] / (B * int(n_roll[i])) * lam * rho[t] * delta[t]"),
+    "full-KL variant drops the advantage": ("c1[t] = grad_scale * w[i] / (B * int(n[i])) * adv[t]", "c1[t] = 0.0"),
+    "full-KL anchor over the supervision set": ("c2[t] = grad_scale * w[i] / (B * int(n_roll[i])) * lam",
+                                                "c2[t] = grad_scale * w[i] / (B * int(n[i])) * lam"),
     "projection contracts the wrong axis": ("return np.matmul(hidden, weight.T)",
                                             "return np.matmul(hidden, weight[:, ::-1].T)"),
     "projection returns vocabulary-major logits": ("return np.matmul(hidden, weight.T)",
