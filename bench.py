@@ -238,7 +238,7 @@ def main():
     def scored_call():
         fb.fopd_loss_fwd_bwd(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
                              w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, f_in,
-                             None, 0, None, None, 1.0, lp.loss, None, lp.weights, lp.logp, lp.dlogits,
+                             None, None, 0, None, None, 1.0, lp.loss, None, lp.weights, lp.logp, lp.dlogits,
                              lp.workspace)
 
     for _ in range(args.warmup):

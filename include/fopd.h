@@ -10,17 +10,19 @@
  *               delta_t = lp_t - lb_t,  rho_t = exp(delta_t)          (log-ratio to the rollout policy)
  *               A_t    = lq_t - lp_t                                  (advantage against the teacher)
  *               k(d)   = e^d d - e^d + 1                              (sampled-token KL estimator)
- *   per sample  D_i^roll = mean_{t in U_i} k(delta_t)                 (Eq. "kl-diagnostics", line 1)
- *               D_i^sup  = mean_{t in U_i} k(lq_t - lq_t^stale)       (Eq. "kl-diagnostics", line 2; 0 if absent)
- *               l_i      = mean_{t in U_i} (lp_t - lq_t)              (Eq. "sample-aggregated-loss")
+ *   per sample  D_i^roll = mean_{t in U_i^roll} k(delta_t)            (Eq. "kl-diagnostics", line 1)
+ *               D_i^sup  = mean_{t in U_i^sup} k(lq_t - lq_t^stale)   (Eq. "kl-diagnostics", line 2; 0 if absent)
+ *               l_i      = mean_{t in U_i^sup} (lp_t - lq_t)          (Eq. "sample-aggregated-loss")
  *               f_i      = exp(-alpha sqrt(D_i^roll) - beta sqrt(D_i^sup)) / (tau_i + 1)   (Eq. "freshness")
  *               w_i      = max(f_i - xi, 0)                           (freshness weighting, Sec. 4.2)
  *   buffer      L = B^-1 sum_i w_i (l_i + lambda D_i^roll)            (anchored objective, Algorithm 1)
  *   gradient    dL/dz_{t,v} = c_t (softmax(z_t)_v - [v = y_t]),
- *               c_t = g m_t w_i / (B n_i) (A_t - lambda rho_t delta_t),   w_i and A_t held constant.
+ *               c_t = g w_i / B ( [t in U_i^sup] A_t / |U_i^sup| - [t in U_i^roll] lambda rho_t delta_t / |U_i^roll| ),
+ *               w_i and A_t held constant.
  *
- * Here U_i is the set of rows of sample i whose mask is 1, n_i = |U_i|, H_i = seq_lens[i],
- * tau_i = lag[i], and a sample with n_i = 0 has f_i = w_i = 0 (Algorithm 1, invalid-sample branch).
+ * U_i^roll and U_i^sup are the aligned sets of Sec. 4.1, named row by row by the `mask` argument (see
+ * FOPD_ALIGNED_*; a plain 0/1 loss mask makes them coincide), H_i = seq_lens[i], tau_i = lag[i], and a
+ * sample with either set empty has f_i = w_i = 0 (Algorithm 1, invalid-sample branch).
  *
  * Conventions common to every entry point
  *   - Every pointer argument is a DEVICE pointer (HIP device memory) unless it is named
@@ -36,7 +38,7 @@
  *     with an out-of-range token id is treated as masked.
  *   - Non-finite inputs propagate to non-finite outputs; nothing traps.
  *   - Identical inputs give bit-identical outputs (all reductions have a fixed order).
- *   - Masked rows (mask 0) produce lp = lse = 0 and an all-zero gradient row and are not read.
+ *   - Rows in neither aligned set (mask 0) produce lp = lse = 0 and an all-zero gradient row and are not read.
  */
 #ifndef FOPD_H
 #define FOPD_H
@@ -89,6 +91,21 @@ fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* s
 fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host);
 
 /*
+ * The `mask` argument of every entry point: one byte per row naming the aligned sets of Sec. 4.1 that
+ * the row belongs to.  U^roll (replay under the stale policy is comparable) carries the rollout drift
+ * D^roll; U^sup (the teacher's contexts are comparable) carries the token loss and the supervision
+ * drift D^sup.  A plain 0/1 loss mask puts every kept row in both sets.  A sample with either set
+ * empty is invalid (Algorithm 1): f_i = w_i = 0, both alignment ratios 0, zero gradient rows.
+ * Any other non-zero byte counts as FOPD_ALIGNED_BOTH; mask == NULL means all rows in both sets.
+ */
+enum {
+  FOPD_ALIGNED_NONE = 0,   /* in neither set: nothing is computed for the row, its gradient row is zero */
+  FOPD_ALIGNED_BOTH = 1,
+  FOPD_ALIGNED_ROLL = 2,   /* in U^roll only */
+  FOPD_ALIGNED_SUP = 3     /* in U^sup only */
+};
+
+/*
  * Student log-probability of the sampled tokens: the streaming pass over the logits.
  * (pi_theta^t(y_{i,h} | x_{i,h}) of Eq. "kl-diagnostics" / Eq. "sample-aggregated-loss".)
  *
@@ -124,17 +141,20 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *   teacher_logp_stale              [T] f32 or NULL: teacher log-probability under the context
  *                                   used at grading time; NULL gives D^sup = 0
  *   mask [T] uint8 or NULL; seq_lens [B] int32 (sum must be T); lag [B] int32 >= 0
- *   outputs: cu_seqlens [B+1] int64 (exclusive scan of seq_lens), n_train [B] int32,
- *            D_roll, D_sup, ell, cover (= n_i / H_i), freshness: [B] f32 each,
- *            agg [3] f32 = mean_i f_i, mean_i cover_i (roll), mean_i cover_i (sup).
+ *   outputs: cu_seqlens [B+1] int64 (exclusive scan of seq_lens),
+ *            n_train [B] int32 = |U_i^sup|, n_roll [B] int32 = |U_i^roll|,
+ *            D_roll (token mean over U^roll), D_sup and ell (token means over U^sup),
+ *            cover = |U_i^sup| / H_i, cover_roll = |U_i^roll| / H_i (both 0 for an invalid sample),
+ *            freshness: [B] f32 each,
+ *            agg [3] f32 = mean_i f_i, mean_i cover_roll_i, mean_i cover_i.
  *   Any of the output pointers except freshness may be NULL.
  */
 fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
                                  const float* teacher_logp, const float* teacher_logp_stale,
                                  const uint8_t* mask, const int32_t* seq_lens, const int32_t* lag,
                                  int64_t T, int32_t B, fopd_hparams hp,
-                                 int64_t* cu_seqlens, int32_t* n_train,
-                                 float* D_roll, float* D_sup, float* ell, float* cover,
+                                 int64_t* cu_seqlens, int32_t* n_train, int32_t* n_roll,
+                                 float* D_roll, float* D_sup, float* ell, float* cover, float* cover_roll,
                                  float* freshness, float* agg,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
@@ -150,7 +170,9 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
  *                          the minibatch loop); they define the weights.  n_train_in is the
  *                          [B] count array of fopd_freshness_score, or NULL when the call
  *                          covers whole samples (row_begin == 0, sum(seq_lens) == T) and the
- *                          counts are to be taken from `mask`.
+ *                          counts are to be taken from `mask`.  n_roll_in: the [B] n_roll array of
+ *                          fopd_freshness_score, or NULL when the two sets coincide (a 0/1 mask);
+ *                          only with n_train_in.
  *                          Without lse_in the logits are still read from HBM only once: one kernel
  *                          makes both passes over each row while it is cache-resident.
  *   lse_in / logp_in     : both or neither.  When given ([T] f32, the outputs of
@@ -159,8 +181,8 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
  *
  *   grad_scale  upstream scale g of the loss (1 for the plain objective)
  *   loss        [1] f32 out: sum over the rows of the call of
- *               m_t w_i / (B n_i) (lp_t - lq_t + lambda k(delta_t)); equals L when the call
- *               covers all rows, and the chunk's additive share of L otherwise
+ *               w_i / B ( [t in U^sup] (lp_t - lq_t) / |U_i^sup| + [t in U^roll] lambda k(delta_t) / |U_i^roll| );
+ *               equals L when the call covers all rows, and the chunk's additive share of L otherwise
  *   freshness   [B] f32 out or NULL (a copy of freshness_in when that is given)
  *   weights     [B] f32 out or NULL
  *   logp        [T] f32 out or NULL
@@ -171,8 +193,8 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               const float* behav_logp, const float* teacher_logp,
                               const float* teacher_logp_stale,
                               const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
-                              const float* freshness_in, const int32_t* n_train_in, int64_t row_begin,
-                              const float* lse_in, const float* logp_in,
+                              const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                              int64_t row_begin, const float* lse_in, const float* logp_in,
                               float grad_scale,
                               float* loss, float* freshness, float* weights, float* logp,
                               void* dlogits,
@@ -197,7 +219,7 @@ fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_d
  * (segment offsets, log-probs, drift, scores, weights, loss, gradient).  The anchor term lambda D_i^roll is
  * differentiated through the full KL:
  *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (log p_u - log p'_u - roll_kl_t),
- *   c1_t = g m_t w_i / (B n_i) A_t,   c2_t = g m_t w_i / (B n_i) lambda.
+ *   c1_t = g [t in U^sup] w_i / (B |U_i^sup|) A_t,   c2_t = g [t in U^roll] w_i / (B |U_i^roll|) lambda.
  * Arguments as in fopd_loss_fwd_bwd; behav_logp is not needed.  logp, roll_kl, freshness, weights may be
  * NULL.  dlogits may alias logits but not logits_stale.  Whole samples only: sum(seq_lens) must be T.
  */
@@ -216,7 +238,7 @@ fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_sta
  * behav_logp; the teacher's log-probability of y_t, needed for D^sup when teacher_logp_stale is given,
  * is taken from teacher_logits.
  *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (log p_u - log q_u - l_t),
- *   c1_t = -g m_t w_i / (B n_i) lambda rho_t delta_t,   c2_t = g m_t w_i / (B n_i).
+ *   c1_t = -g [t in U^roll] w_i / (B |U_i^roll|) lambda rho_t delta_t,   c2_t = g [t in U^sup] w_i / (B |U_i^sup|).
  * Averaged over y ~ softmax(z) the default path's sampled-token gradient equals this one's KL part.
  *   token_kl  [T] f32 out or NULL: l_t.  Other arguments as in fopd_loss_fwd_bwd_full_kl.
  * dlogits may alias logits but not teacher_logits.  Whole samples only.

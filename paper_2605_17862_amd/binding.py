@@ -82,7 +82,7 @@ def load_library():
     lib.fopd_lm_head_token_logprobs.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
-                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_rollout_kl.restype = ctypes.c_int
     lib.fopd_rollout_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd_full_teacher.restype = ctypes.c_int
@@ -93,7 +93,7 @@ def load_library():
                                               Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
-                                      vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+                                      vp, vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_refresh_decide.restype = ctypes.c_int
     lib.fopd_refresh_decide.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.POINTER(RefreshConfig),
                                         ctypes.POINTER(RefreshState), i64, ctypes.POINTER(i32)]
@@ -199,8 +199,8 @@ def fopd_lm_head_token_logprobs(hidden, ldh, weight, ldw, T, V, d, token_ids, ma
 
 
 def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B,
-                         hp, cu_seqlens, n_train, D_roll, D_sup, ell, cover, freshness, agg, workspace,
-                         stream=None):
+                         hp, cu_seqlens, n_train, n_roll, D_roll, D_sup, ell, cover, cover_roll, freshness, agg,
+                         workspace, stream=None):
     import torch
     f32 = torch.float32
     p, n = _ws(workspace)
@@ -210,15 +210,17 @@ def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_s
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(mask, torch.uint8, "mask"),
         _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(T), int(B), _hp(hp),
         _ptr(cu_seqlens, torch.int64, "cu_seqlens"), _ptr(n_train, torch.int32, "n_train"),
+        _ptr(n_roll, torch.int32, "n_roll"),
         _ptr(D_roll, f32, "D_roll"), _ptr(D_sup, f32, "D_sup"), _ptr(ell, f32, "ell"),
-        _ptr(cover, f32, "cover"), _ptr(freshness, f32, "freshness"), _ptr(agg, f32, "agg"),
+        _ptr(cover, f32, "cover"), _ptr(cover_roll, f32, "cover_roll"), _ptr(freshness, f32, "freshness"),
+        _ptr(agg, f32, "agg"),
         p, n, _stream(stream))
     _check(st, "fopd_freshness_score")
 
 
 def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
-                      seq_lens, lag, B, hp, freshness_in, n_train_in, row_begin, lse_in, logp_in, grad_scale,
-                      loss, freshness, weights, logp, dlogits, workspace, stream=None):
+                      seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in,
+                      grad_scale, loss, freshness, weights, logp, dlogits, workspace, stream=None):
     import torch
     f32 = torch.float32
     mat = (torch.float32, torch.bfloat16)
@@ -229,7 +231,8 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
         _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
         _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
-        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"), int(row_begin),
+        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"),
+        _ptr(n_roll_in, torch.int32, "n_roll_in"), int(row_begin),
         _ptr(lse_in, f32, "lse_in"), _ptr(logp_in, f32, "logp_in"), float(grad_scale),
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))

@@ -20,7 +20,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Carving of the caller's workspace.  Every region starts on a 256-byte boundary.
 struct Workspace {
-  size_t flags, cu, n_train, fresh64, coef, lse, logp, coef2, dlse, kl, logq, partials, total;
+  size_t flags, cu, n_train, n_roll, fresh64, coef, lse, logp, coef2, dlse, kl, logq, partials, total;
   Workspace(int64_t T, int32_t B) {
     const size_t t = static_cast<size_t>(T < 0 ? 0 : T), b = static_cast<size_t>(B < 0 ? 0 : B);
     size_t off = 0;
@@ -32,6 +32,7 @@ struct Workspace {
     flags = take(4 * sizeof(int32_t));
     cu = take((b + 1) * sizeof(int64_t));
     n_train = take(b * sizeof(int32_t));
+    n_roll = take(b * sizeof(int32_t));
     fresh64 = take(b * sizeof(double));
     coef = take(t * sizeof(float));
     lse = take(t * sizeof(float));
@@ -170,9 +171,9 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
 template <int DT, int NT>
 fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V, int64_t ld,
                          const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
-                         const int64_t* cu, const int32_t* n_train, const float* fresh32, int32_t B,
-                         int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss,
-                         int32_t* flags, hipStream_t s) {
+                         const int64_t* cu, const int32_t* n_train, const int32_t* n_roll, const float* fresh32,
+                         int32_t B, int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp,
+                         double* row_loss, int32_t* flags, hipStream_t s) {
   auto kern = fopd_k14_fused<DT, NT, kUnroll>;
   // dynamic LDS is requested only to cap the workgroups resident per compute unit; the kernel is told
   // once per instantiation and device that it may be given up to a whole CU's worth
@@ -181,20 +182,20 @@ fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V
     return FOPD_EHIP;
   const size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
   kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
-                                                            token_ids, mask, lb, lq, cu, n_train, fresh32, B,
+                                                            token_ids, mask, lb, lq, cu, n_train, n_roll, fresh32, B,
                                                             row_begin, hp, grad_scale, logp, row_loss, flags);
   return launched();
 }
 
 fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                        const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
-                       const int64_t* cu, const int32_t* n_train, const float* fresh32, int32_t B,
-                       int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss,
-                       int32_t* flags, hipStream_t s) {
+                       const int64_t* cu, const int32_t* n_train, const int32_t* n_roll, const float* fresh32,
+                       int32_t B, int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp,
+                       double* row_loss, int32_t* flags, hipStream_t s) {
   if (T == 0) return FOPD_OK;
   ScopedTimer timer(2, s);
 #define FOPD_K14_CASE(DTV, NTV)                                                                             \
-  return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, token_ids, mask, lb, lq, cu, n_train, fresh32, B, \
+  return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, token_ids, mask, lb, lq, cu, n_train, n_roll, fresh32, B, \
                                 row_begin, hp, grad_scale, logp, row_loss, flags, s)
   if (dt == FOPD_BF16) {
     if (g_opt.k14_threads == 512) FOPD_K14_CASE(FOPD_BF16, 512);
@@ -265,9 +266,10 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
 fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
                                  const float* teacher_logp, const float* teacher_logp_stale, const uint8_t* mask,
                                  const int32_t* seq_lens, const int32_t* lag, int64_t T, int32_t B,
-                                 fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, float* D_roll,
-                                 float* D_sup, float* ell, float* cover, float* freshness, float* agg,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+                                 fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, int32_t* n_roll,
+                                 float* D_roll, float* D_sup, float* ell, float* cover, float* cover_roll,
+                                 float* freshness, float* agg, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
   if (T < 0 || B <= 0) return FOPD_ESHAPE;
   if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || teacher_logp == nullptr ||
       seq_lens == nullptr || lag == nullptr || freshness == nullptr)
@@ -280,16 +282,17 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
   int32_t* flags = at<int32_t>(workspace, w.flags);
   int64_t* cu = (cu_seqlens != nullptr) ? cu_seqlens : at<int64_t>(workspace, w.cu);
   int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
   double* f64 = at<double>(workspace, w.fresh64);
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
   fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, nullptr, teacher_logp, teacher_logp_stale, mask,
-                                               cu, lag, T, hp, n_train, D_roll, D_sup, ell, cover,
-                                               freshness, f64, nws);
+                                               cu, lag, T, hp, n_train, n_roll, D_roll, D_sup, ell, cover,
+                                               cover_roll, freshness, f64, nws, nrws);
   if ((st = launched()) != FOPD_OK) return st;
   if (agg != nullptr) {
-    fopd_aggregate<<<1, kSegThreads, 0, s>>>(f64, nws, cu, B, agg);
+    fopd_aggregate<<<1, kSegThreads, 0, s>>>(f64, nws, nrws, cu, B, agg);
     if ((st = launched()) != FOPD_OK) return st;
   }
   return FOPD_OK;
@@ -299,8 +302,9 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
                               const float* teacher_logp, const float* teacher_logp_stale,
                               const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
-                              const float* freshness_in, const int32_t* n_train_in, int64_t row_begin,
-                              const float* lse_in, const float* logp_in, float grad_scale, float* loss,
+                              const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                              int64_t row_begin, const float* lse_in, const float* logp_in, float grad_scale,
+                              float* loss,
                               float* freshness, float* weights, float* logp, void* dlogits,
                               void* workspace, size_t workspace_bytes, void* stream) {
   fopd_status st = check_matrix(logits, dt, T, V, ld);
@@ -315,6 +319,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   const bool have_lse = (lse_in != nullptr);
   if (have_lse != (logp_in != nullptr)) return FOPD_EINVAL;
   if (!scored && (have_lse || n_train_in != nullptr || row_begin != 0)) return FOPD_EINVAL;
+  if (n_roll_in != nullptr && n_train_in == nullptr) return FOPD_EINVAL;
   if (scored && n_train_in == nullptr && row_begin != 0) return FOPD_EINVAL;
   if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
 
@@ -323,6 +328,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   int32_t* flags = at<int32_t>(workspace, w.flags);
   int64_t* cu = at<int64_t>(workspace, w.cu);
   int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
   double* f64 = at<double>(workspace, w.fresh64);
   float* coef = at<float>(workspace, w.coef);
   float* lse_ws = at<float>(workspace, w.lse);
@@ -338,16 +344,18 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   // read of the row comes out of the Infinity Cache.
   if (scored && !have_lse) {
     const int32_t* n_use = n_train_in;
+    const int32_t* nr_use = n_roll_in;                  // NULL: the two counts coincide
     if (whole) {
-      fopd_count_train<<<B, kSegThreads, 0, s>>>(mask, cu, T, nws);
+      fopd_count_train<<<B, kSegThreads, 0, s>>>(mask, cu, T, nws, nrws);
       if ((st = launched()) != FOPD_OK) return st;
       n_use = nws;
+      nr_use = nrws;
     }
-    st = launch_k14(logits, dlogits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, cu, n_use,
+    st = launch_k14(logits, dlogits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, cu, n_use, nr_use,
                     freshness_in, B, row_begin, hp, grad_scale, logp, partials, flags, s);
     if (st != FOPD_OK) return st;
-    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, T, n_use, nullptr, freshness_in, B, hp.xi, loss, weights,
-                                              freshness);
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, T, n_use, nr_use, nullptr, freshness_in, B, hp.xi, loss,
+                                              weights, freshness);
     return launched();
   }
 
@@ -367,23 +375,25 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
 
   // per-sample counts and scores
   const int32_t* n_use = n_train_in;
+  const int32_t* nr_use = n_roll_in;                    // NULL: the two counts coincide
   if (whole) {
     fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, nullptr, nullptr, teacher_logp, teacher_logp_stale,
-                                                 mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
-                                                 nullptr, nullptr, f64, nws);
+                                                 mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                                 nullptr, nullptr, nullptr, f64, nws, nrws);
     if ((st = launched()) != FOPD_OK) return st;
     n_use = nws;
+    nr_use = nrws;
   }
   const double* f64_use = scored ? nullptr : f64;
 
   const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
   if (T > 0) {
     fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_use, behav_logp, teacher_logp, mask, cu, n_use, f64_use, freshness_in, T, B, row_begin, hp,
+        logp_use, behav_logp, teacher_logp, mask, cu, n_use, nr_use, f64_use, freshness_in, T, B, row_begin, hp,
         grad_scale, coef, partials);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, f64_use, freshness_in, B, hp.xi, loss,
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, f64_use, freshness_in, B, hp.xi, loss,
                                             weights, freshness);
   if ((st = launched()) != FOPD_OK) return st;
 
@@ -437,20 +447,24 @@ static fopd_status two_tensor_tail(const void* logits, const void* second, void*
   fopd_status st;
   int64_t* cu = at<int64_t>(workspace, w.cu);
   int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
   double* f64 = at<double>(workspace, w.fresh64);
   float* c1 = at<float>(workspace, w.coef);
   float* c2 = at<float>(workspace, w.coef2);
   double* partials = at<double>(workspace, w.partials);
   fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, roll_term, ell_term, lq, lq_stale, mask, cu, lag, T,
-                                               hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, f64, nws);
+                                               hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                               f64, nws, nrws);
   if ((st = launched()) != FOPD_OK) return st;
   const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
   if (T > 0) {
     fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_ws, token_kl, lq, behav_logp, mask, cu, nws, f64, T, B, hp, grad_scale, anchor_is_kl, c1, c2, partials);
+        logp_ws, token_kl, lq, behav_logp, mask, cu, nws, nrws, f64, T, B, hp, grad_scale, anchor_is_kl, c1, c2,
+        partials);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, f64, nullptr, B, hp.xi, loss, weights, freshness);
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, nrws, f64, nullptr, B, hp.xi, loss, weights,
+                                            freshness);
   if ((st = launched()) != FOPD_OK) return st;
   if (T == 0) return FOPD_OK;
   ScopedTimer timer(1, s);

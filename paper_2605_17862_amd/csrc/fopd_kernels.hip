@@ -422,22 +422,47 @@ __device__ __forceinline__ double kl_term(double d, double* rho_out) {
   return d * e1 + (d - e1);
 }
 
-__device__ __forceinline__ double weight_of(double f, int32_t n, float xi) {
-  if (n <= 0) return 0.0;
+// The two aligned sets of Sec. 4.1 in one byte per row: 0 = in neither, 2 = in U^roll only,
+// 3 = in U^sup only, anything else (a plain loss mask's 1) = in both.  No mask = all rows in both.
+__device__ __forceinline__ bool in_sup_set(const uint8_t* mask, int64_t t) {
+  if (mask == nullptr) return true;
+  const uint8_t m = mask[t];
+  return m != 0 && m != 2;
+}
+__device__ __forceinline__ bool in_roll_set(const uint8_t* mask, int64_t t) {
+  if (mask == nullptr) return true;
+  const uint8_t m = mask[t];
+  return m != 0 && m != 3;
+}
+
+// ReLU(f - xi); 0 for an invalid sample (either aligned set empty), whatever xi is.
+__device__ __forceinline__ double weight_of(double f, int32_t n_sup, int32_t n_roll, float xi) {
+  if (n_sup <= 0 || n_roll <= 0) return 0.0;
   const double w = f - static_cast<double>(xi);
   return w > 0.0 ? w : 0.0;
 }
 
-// Row coefficient c_t and the row's share of the loss, from the fp32-rounded log-prob.
-__device__ __forceinline__ float coef_and_loss(double lp, double lb, double lq, double w, int32_t n, int32_t B,
-                                               fopd_hparams hp, float grad_scale, double* loss_term) {
-  double rho;
-  const double d = lp - lb;
-  const double k = kl_term(d, &rho);
-  const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
+// Row coefficient c_t and the row's share of the loss, from the fp32-rounded log-prob:
+//   c_t = g w / B ( [t in U^sup] (lq - lp) / |U^sup|  -  [t in U^roll] lambda rho d / |U^roll| ).
+__device__ __forceinline__ float coef_and_loss(double lp, double lb, double lq, double w, int32_t n_sup,
+                                               int32_t n_roll, bool sup, bool roll, int32_t B, fopd_hparams hp,
+                                               float grad_scale, double* loss_term) {
+  const double wb = w / static_cast<double>(B);
   const double lam = hp.lambda;
-  *loss_term = pref * ((lp - lq) + lam * k);
-  return static_cast<float>(static_cast<double>(grad_scale) * pref * ((lq - lp) - lam * rho * d));
+  double lt = 0.0, c = 0.0;
+  if (sup) {
+    lt += (lp - lq) / static_cast<double>(n_sup);
+    c += (lq - lp) / static_cast<double>(n_sup);
+  }
+  if (roll) {
+    double rho;
+    const double d = lp - lb;
+    const double k = kl_term(d, &rho);
+    lt += lam * k / static_cast<double>(n_roll);
+    c -= lam * rho * d / static_cast<double>(n_roll);
+  }
+  *loss_term = wb * lt;
+  return static_cast<float>(static_cast<double>(grad_scale) * wb * c);
 }
 
 // Largest i with cu[i] <= gt, given cu[0] <= gt < cu[B].
@@ -530,8 +555,8 @@ template <int DT, int NT, int U>
 __global__ void __launch_bounds__(NT)
 fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
                const uint8_t* mask, const float* behav_logp, const float* teacher_logp, const int64_t* cu,
-               const int32_t* n_train, const float* fresh32, int32_t B, int64_t row_begin, fopd_hparams hp,
-               float grad_scale, float* logp, double* row_loss, int32_t* flags) {
+               const int32_t* n_train, const int32_t* n_roll, const float* fresh32, int32_t B, int64_t row_begin,
+               fopd_hparams hp, float grad_scale, float* logp, double* row_loss, int32_t* flags) {
   extern __shared__ char occupancy_pad[];      // sized by the host only to cap workgroups per CU
   __shared__ float sh_zy;
   __shared__ float sh_R[NT / 64];
@@ -548,11 +573,12 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
   }
   const int64_t gt = row_begin + t;
   double w = 0.0;
-  int32_t n = 0;
+  int32_t n = 0, nr = 0;
   if (live && gt < cu[B]) {
     const int i = sample_of_row(cu, B, gt);
     n = n_train[i];
-    w = weight_of(static_cast<double>(fresh32[i]), n, hp.xi);
+    nr = (n_roll != nullptr) ? n_roll[i] : n;
+    w = weight_of(static_cast<double>(fresh32[i]), n, nr, hp.xi);
   }
   if (!live || (w == 0.0 && logp == nullptr)) {   // nothing to learn from this row: no read at all
     if (tid == 0) {
@@ -574,7 +600,8 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
     float c = 0.f;
     double lt = 0.0;
     if (w > 0.0)
-      c = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], w, n, B, hp, grad_scale, &lt);
+      c = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], w, n, nr, in_sup_set(mask, t),
+                        in_roll_set(mask, t), B, hp, grad_scale, &lt);
     row_loss[t] = lt;
     sh_c = c;
     sh_lseL = lse32 * kLog2e;
@@ -800,34 +827,37 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
 //                         c1 = -g pref lambda rho delta, c2 = g pref, loss share pref (kl + lambda k(delta))
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_coef_loss_kl(const float* logp, const float* token_kl, const float* teacher_logp, const float* behav_logp,
-                  const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const double* fresh64, int64_t T,
-                  int32_t B, fopd_hparams hp, float grad_scale, bool anchor_is_kl, float* c1, float* c2,
-                  double* partials) {
+                  const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const int32_t* n_roll,
+                  const double* fresh64, int64_t T, int32_t B, fopd_hparams hp, float grad_scale, bool anchor_is_kl,
+                  float* c1, float* c2, double* partials) {
   __shared__ double sh[kStreamThreads / 64];
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
   double lt = 0.0;
   if (t < T) {
     float a = 0.f, b = 0.f;
-    if ((mask == nullptr || mask[t] != 0) && t < cu[B]) {
+    const bool sup = in_sup_set(mask, t), roll = in_roll_set(mask, t);
+    if ((sup || roll) && t < cu[B]) {
       const int i = sample_of_row(cu, B, t);
-      const int32_t n = n_train[i];
-      const double w = weight_of(fresh64[i], n, hp.xi);
+      const int32_t n = n_train[i], nr = n_roll[i];
+      const double w = weight_of(fresh64[i], n, nr, hp.xi);
       if (w > 0.0) {
         const double lp = logp[t], lam = hp.lambda, kl = token_kl[t];
-        const double pref = w / (static_cast<double>(B) * static_cast<double>(n));
-        const double gp = static_cast<double>(grad_scale) * pref;
-        if (anchor_is_kl) {
+        const double wb = w / static_cast<double>(B);
+        const double ps = sup ? wb / static_cast<double>(n) : 0.0;       // share of a U^sup row
+        const double pr = roll ? wb / static_cast<double>(nr) : 0.0;     // share of a U^roll row
+        const double g = static_cast<double>(grad_scale);
+        if (anchor_is_kl) {       // token loss (sampled form) on U^sup, full-vocabulary drift on U^roll
           const double lq = teacher_logp[t];
-          a = static_cast<float>(gp * (lq - lp));
-          b = static_cast<float>(gp * lam);
-          lt = pref * ((lp - lq) + lam * kl);
-        } else {
+          a = static_cast<float>(g * ps * (lq - lp));
+          b = static_cast<float>(g * pr * lam);
+          lt = ps * (lp - lq) + pr * lam * kl;
+        } else {                  // distribution-level token loss on U^sup, sampled drift on U^roll
           double rho;
           const double d = lp - static_cast<double>(behav_logp[t]);
           const double k = kl_term(d, &rho);
-          a = static_cast<float>(-gp * lam * rho * d);
-          b = static_cast<float>(gp);
-          lt = pref * (kl + lam * k);
+          a = static_cast<float>(-g * pr * lam * rho * d);
+          b = static_cast<float>(g * ps);
+          lt = ps * kl + pr * lam * k;
         }
       }
     }
@@ -971,90 +1001,116 @@ fopd_scan_seqlens(const int32_t* seq_lens, const int32_t* lag, int32_t B, int64_
   if (bad_lag) atomicOr(flags, kFlagLag);
 }
 
-// n_i = number of mask == 1 rows of sample i (one workgroup per sample).
+// |U_i^sup| and |U_i^roll| of sample i (one workgroup per sample).
 __global__ void __launch_bounds__(kSegThreads)
-fopd_count_train(const uint8_t* mask, const int64_t* cu, int64_t T, int32_t* n_train) {
+fopd_count_train(const uint8_t* mask, const int64_t* cu, int64_t T, int32_t* n_train, int32_t* n_roll) {
   __shared__ double sh[kSegThreads / 64];
   const int i = blockIdx.x;
   const int64_t a = cu[i];
   int64_t b = cu[i + 1];
   if (b > T) b = T;
-  double cnt = 0.0;
-  for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads)
-    if (mask == nullptr || mask[t] != 0) cnt += 1.0;
-  const double tn = block_sum<kSegThreads>(cnt, sh);
-  if (threadIdx.x == 0) n_train[i] = static_cast<int32_t>(tn);
+  double cs = 0.0, cr = 0.0;
+  for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads) {
+    if (in_sup_set(mask, t)) cs += 1.0;
+    if (in_roll_set(mask, t)) cr += 1.0;
+  }
+  const double ts = block_sum<kSegThreads>(cs, sh);
+  const double tr = block_sum<kSegThreads>(cr, sh);
+  if (threadIdx.x == 0) {
+    n_train[i] = static_cast<int32_t>(ts);
+    n_roll[i] = static_cast<int32_t>(tr);
+  }
 }
 
-// One workgroup per sample: token means over the mask, then the freshness score.
+// One workgroup per sample: D^roll as the token mean over U^roll, D^sup and the token loss as token means
+// over U^sup (Eq. "kl-diagnostics", Eq. "sample-aggregated-loss"), then the freshness score; a sample
+// with either set empty is invalid and gets zeros (Algorithm 1).
 __global__ void __launch_bounds__(kSegThreads)
 fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll_kl, const float* ell_term,
                    const float* teacher_logp, const float* teacher_logp_stale, const uint8_t* mask,
                    const int64_t* cu,
-                   const int32_t* lag, int64_t T, fopd_hparams hp, int32_t* n_train, float* D_roll,
-                   float* D_sup, float* ell, float* cover, float* freshness, double* fresh64,
-                   int32_t* n_train_ws) {
+                   const int32_t* lag, int64_t T, fopd_hparams hp, int32_t* n_train, int32_t* n_roll, float* D_roll,
+                   float* D_sup, float* ell, float* cover, float* cover_roll, float* freshness, double* fresh64,
+                   int32_t* n_train_ws, int32_t* n_roll_ws) {
   __shared__ double sh[kSegThreads / 64];
   const int i = blockIdx.x;
   const int64_t a = cu[i];
   int64_t b = cu[i + 1];
   if (b > T) b = T;                      // lengths that overrun T are flagged by the scan
-  double sr = 0.0, ss = 0.0, sl = 0.0, cnt = 0.0;
+  double sr = 0.0, ss = 0.0, sl = 0.0, cs = 0.0, cr = 0.0;
   for (int64_t t = a + threadIdx.x; t < b; t += kSegThreads) {
-    if (mask != nullptr && mask[t] == 0) continue;
-    const double lp = logp[t], lq = teacher_logp[t];
-    // rollout drift of the token: full-vocabulary KL if the caller has it, else the sampled estimator
-    sr += (roll_kl != nullptr) ? static_cast<double>(roll_kl[t])
-                               : kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
-    if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
-    // token loss: a distribution-level value if the caller has one, else the sampled-token form
-    sl += (ell_term != nullptr) ? static_cast<double>(ell_term[t]) : lp - lq;
-    cnt += 1.0;
+    const bool sup = in_sup_set(mask, t), roll = in_roll_set(mask, t);
+    if (!sup && !roll) continue;
+    const double lp = logp[t];
+    if (roll) {
+      // rollout drift of the token: full-vocabulary KL if the caller has it, else the sampled estimator
+      sr += (roll_kl != nullptr) ? static_cast<double>(roll_kl[t])
+                                 : kl_term(lp - static_cast<double>(behav_logp[t]), nullptr);
+      cr += 1.0;
+    }
+    if (sup) {
+      const double lq = teacher_logp[t];
+      if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
+      // token loss: a distribution-level value if the caller has one, else the sampled-token form
+      sl += (ell_term != nullptr) ? static_cast<double>(ell_term[t]) : lp - lq;
+      cs += 1.0;
+    }
   }
   const double tr = block_sum<kSegThreads>(sr, sh);
   const double ts = block_sum<kSegThreads>(ss, sh);
   const double tl = block_sum<kSegThreads>(sl, sh);
-  const double tn = block_sum<kSegThreads>(cnt, sh);
+  const double tns = block_sum<kSegThreads>(cs, sh);
+  const double tnr = block_sum<kSegThreads>(cr, sh);
   if (threadIdx.x == 0) {
-    const int32_t n = static_cast<int32_t>(tn);
+    const int32_t ns = static_cast<int32_t>(tns), nr = static_cast<int32_t>(tnr);
     const int64_t H = cu[i + 1] - a;
-    double dr = 0.0, ds = 0.0, el = 0.0, cv = 0.0, f = 0.0;
-    if (n > 0) {
-      dr = tr / tn;
-      ds = ts / tn;
-      el = tl / tn;
-      cv = tn / static_cast<double>(H);
+    double dr = 0.0, ds = 0.0, el = 0.0, cv = 0.0, cvr = 0.0, f = 0.0;
+    if (ns > 0 && nr > 0) {
+      dr = tr / tnr;
+      ds = ts / tns;
+      el = tl / tns;
+      cv = tns / static_cast<double>(H);
+      cvr = tnr / static_cast<double>(H);
       // k >= 0 mathematically; clamp the rounding noise of an all-fresh sample
       const double surrogate = static_cast<double>(hp.alpha) * sqrt(dr > 0.0 ? dr : 0.0) +
                                static_cast<double>(hp.beta) * sqrt(ds > 0.0 ? ds : 0.0);
       f = exp(-surrogate) / (static_cast<double>(lag[i]) + 1.0);
     }
-    if (n_train != nullptr) n_train[i] = n;
-    if (n_train_ws != nullptr) n_train_ws[i] = n;
+    if (n_train != nullptr) n_train[i] = ns;
+    if (n_roll != nullptr) n_roll[i] = nr;
+    if (n_train_ws != nullptr) n_train_ws[i] = ns;
+    if (n_roll_ws != nullptr) n_roll_ws[i] = nr;
     if (D_roll != nullptr) D_roll[i] = static_cast<float>(dr);
     if (D_sup != nullptr) D_sup[i] = static_cast<float>(ds);
     if (ell != nullptr) ell[i] = static_cast<float>(el);
     if (cover != nullptr) cover[i] = static_cast<float>(cv);
+    if (cover_roll != nullptr) cover_roll[i] = static_cast<float>(cvr);
     if (freshness != nullptr) freshness[i] = static_cast<float>(f);
     if (fresh64 != nullptr) fresh64[i] = f;
   }
 }
 
-// mean_i f_i and mean_i cover_i over all B samples (one workgroup).
+// mean_i f_i, mean_i |U_i^roll| / H_i and mean_i |U_i^sup| / H_i over all B samples (one workgroup);
+// an invalid sample adds 0 to all three (Algorithm 1).
 __global__ void __launch_bounds__(kSegThreads)
-fopd_aggregate(const double* fresh64, const int32_t* n_train, const int64_t* cu, int32_t B, float* agg) {
+fopd_aggregate(const double* fresh64, const int32_t* n_train, const int32_t* n_roll, const int64_t* cu, int32_t B,
+               float* agg) {
   __shared__ double sh[kSegThreads / 64];
-  double sf = 0.0, sc = 0.0;
+  double sf = 0.0, sc = 0.0, scr = 0.0;
   for (int i = threadIdx.x; i < B; i += kSegThreads) {
     sf += fresh64[i];
     const int64_t H = cu[i + 1] - cu[i];
-    if (n_train[i] > 0) sc += static_cast<double>(n_train[i]) / static_cast<double>(H);
+    if (n_train[i] > 0 && n_roll[i] > 0) {
+      sc += static_cast<double>(n_train[i]) / static_cast<double>(H);
+      scr += static_cast<double>(n_roll[i]) / static_cast<double>(H);
+    }
   }
   const double tf = block_sum<kSegThreads>(sf, sh);
   const double tc = block_sum<kSegThreads>(sc, sh);
+  const double tcr = block_sum<kSegThreads>(scr, sh);
   if (threadIdx.x == 0) {
     agg[0] = static_cast<float>(tf / B);
-    agg[1] = static_cast<float>(tc / B);
+    agg[1] = static_cast<float>(tcr / B);
     agg[2] = static_cast<float>(tc / B);
   }
 }
@@ -1062,22 +1118,24 @@ fopd_aggregate(const double* fresh64, const int32_t* n_train, const int64_t* cu,
 // Per-token gradient coefficient c_t and the block's share of the loss.
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_logp,
-               const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const double* fresh64,
-               const float* fresh32, int64_t T, int32_t B, int64_t row_begin, fopd_hparams hp,
-               float grad_scale, float* coef, double* partials) {
+               const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const int32_t* n_roll,
+               const double* fresh64, const float* fresh32, int64_t T, int32_t B, int64_t row_begin,
+               fopd_hparams hp, float grad_scale, float* coef, double* partials) {
   __shared__ double sh[kStreamThreads / 64];
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
   double lt = 0.0;
   if (t < T) {
     float c = 0.f;
     const int64_t gt = row_begin + t;
-    if ((mask == nullptr || mask[t] != 0) && gt < cu[B]) {
+    const bool sup = in_sup_set(mask, t), roll = in_roll_set(mask, t);
+    if ((sup || roll) && gt < cu[B]) {
       const int i = sample_of_row(cu, B, gt);
       const int32_t n = n_train[i];
+      const int32_t nr = (n_roll != nullptr) ? n_roll[i] : n;
       const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
-      const double w = weight_of(f, n, hp.xi);
+      const double w = weight_of(f, n, nr, hp.xi);
       if (w > 0.0)
-        c = coef_and_loss(logp[t], behav_logp[t], teacher_logp[t], w, n, B, hp, grad_scale, &lt);
+        c = coef_and_loss(logp[t], behav_logp[t], teacher_logp[t], w, n, nr, sup, roll, B, hp, grad_scale, &lt);
     }
     coef[t] = c;
   }
@@ -1087,8 +1145,9 @@ fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_
 
 // Sums the loss partials in a fixed order; writes the weights and the freshness copy.
 __global__ void __launch_bounds__(kSegThreads)
-fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, const double* fresh64,
-                const float* fresh32, int32_t B, float xi, float* loss, float* weights, float* freshness) {
+fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, const int32_t* n_roll,
+                const double* fresh64, const float* fresh32, int32_t B, float xi, float* loss, float* weights,
+                float* freshness) {
   __shared__ double sh[kSegThreads / 64];
   // eight independent partial sums per lane keep eight loads in flight (nparts is T in the
   // two-passes-per-row path); the order of additions is still fixed
@@ -1104,7 +1163,8 @@ fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, 
   if (threadIdx.x == 0) loss[0] = static_cast<float>(tot);
   for (int i = threadIdx.x; i < B; i += kSegThreads) {
     const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
-    if (weights != nullptr) weights[i] = static_cast<float>(weight_of(f, n_train[i], xi));
+    if (weights != nullptr)
+      weights[i] = static_cast<float>(weight_of(f, n_train[i], (n_roll != nullptr) ? n_roll[i] : n_train[i], xi));
     if (freshness != nullptr) freshness[i] = static_cast<float>(f);
   }
 }

@@ -24,10 +24,12 @@ class LossPass:
         self.entropy = None
         self.cu_seqlens = torch.empty(self.B + 1, dtype=torch.int64, device=dev)
         self.n_train = torch.empty(self.B, dtype=torch.int32, device=dev)
+        self.n_roll = torch.empty(self.B, dtype=torch.int32, device=dev)
         self.D_roll = torch.empty(self.B, **f32)
         self.D_sup = torch.empty(self.B, **f32)
         self.ell = torch.empty(self.B, **f32)
         self.cover = torch.empty(self.B, **f32)
+        self.cover_roll = torch.empty(self.B, **f32)
         self.freshness = torch.empty(self.B, **f32)
         self.weights = torch.empty(self.B, **f32)
         self.agg = torch.empty(3, **f32)
@@ -53,15 +55,15 @@ class LossPass:
         stale = w["teacher_logp_stale"]
         fb.fopd_freshness_score(self.logp, w["behav_logp"], None, w["teacher_logp"], stale, w["mask"],
                                 w["seq_lens"], w["lag"], self.T, self.B, hp, self.cu_seqlens, self.n_train,
-                                self.D_roll, self.D_sup, self.ell, self.cover, self.freshness, self.agg,
-                                self.workspace)
+                                self.n_roll, self.D_roll, self.D_sup, self.ell, self.cover, self.cover_roll,
+                                self.freshness, self.agg, self.workspace)
 
     def loss_fwd_bwd(self, w, hp=DEFAULT_HPARAMS, grad_scale=1.0, dlogits=None):
         """Everything in one call: scores, weights, loss and gradient."""
         out = self.dlogits if dlogits is None else dlogits
         fb.fopd_loss_fwd_bwd(w["logits"], self.dt, self.T, self.V, self.ld, w["token_ids"], w["mask"],
                              w["behav_logp"], w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"],
-                             w["lag"], self.B, hp, None, None, 0, None, None, grad_scale, self.loss,
+                             w["lag"], self.B, hp, None, None, None, 0, None, None, grad_scale, self.loss,
                              self.freshness, self.weights, self.logp, out, self.workspace)
 
     def status(self):

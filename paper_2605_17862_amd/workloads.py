@@ -102,7 +102,9 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     """Builds one workload.  Returns a dict of tensors on `device` plus plain metadata.
 
     overrides replace entries of CONFIGS[name] (e.g. B=8, V=4096, len_hi=600) to make the
-    reduced-size replicas the tests use.  stale_logit_sigma=s (> 0) also returns `logits_stale`:
+    reduced-size replicas the tests use.  aligned_split=(a, b) turns a fraction a of the kept rows into
+    "rollout-aligned only" (mask 2) and a fraction b into "supervision-aligned only" (mask 3), so that the
+    two aligned sets of a sample differ.  stale_logit_sigma=s (> 0) also returns `logits_stale`:
     the logits a stale checkpoint would give on the same prefixes, logits + s * lag_i * N(0, 1)
     per entry (identical to the current ones for lag 0), for the full-vocabulary drift diagnostic.
     """
@@ -114,6 +116,10 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     rs = np.random.RandomState(seed)
     seq_lens, mask = _structure(cfg, rs)
     lag = _lags(cfg, rs)
+    if "aligned_split" in cfg:
+        a, b = cfg["aligned_split"]
+        u = np.random.RandomState(seed + 7919).uniform(size=mask.shape[0])
+        mask = np.where((mask != 0) & (u < a), 2, np.where((mask != 0) & (u < a + b), 3, mask)).astype(np.uint8)
     T = int(seq_lens.sum())
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
@@ -159,7 +165,7 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
                 behav_logp=behav, teacher_logp=teacher, teacher_logp_stale=stale,
                 seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
                 seq_lens_host=seq_lens, lag_host=lag, mask_host=mask,
-                n_trainable=int(mask.sum()))
+                n_trainable=int(((mask != 0) & (mask != 2)).sum()))
 
 
 def structure_only(name, seed=0, **overrides):

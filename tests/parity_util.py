@@ -54,18 +54,25 @@ def assert_close(name, got, want, rtol=0.0, atol=0.0):
 
 
 def coef_uncertainty(ref, hp, grad_scale, n_samples, mask):
-    """eps_c(t): how far the row coefficient may move given the allowed errors of lp and f."""
+    """eps_c(t): how far the row coefficient may move given the allowed errors of lp and f.  The
+    coefficient is g w / B ( [sup] A / n_sup - [roll] lambda rho delta / n_roll ); the lp error enters
+    through the larger of the two shares, the f error scales the whole coefficient."""
     _, _, xi, lam = hp
     T = len(ref["coef"])
     cu, n, f, w = ref["cu_seqlens"], ref["n_train"], ref["freshness"], ref["weights"]
+    n_roll = ref.get("n_roll", n)
+    mask = np.asarray(mask)
     out = np.zeros(T)
     for i in range(len(n)):
-        if n[i] == 0:
+        if n[i] == 0 or n_roll[i] == 0:
             continue
         a, b = int(cu[i]), int(cu[i + 1])
-        aeff = np.abs(ref["adv"][a:b] - lam * ref["rho"][a:b] * ref["delta"][a:b])
-        out[a:b] = abs(grad_scale) / (n_samples * int(n[i])) * (w[i] * EPS_A + EPS_F * f[i] * aeff)
-    return out * (np.asarray(mask) != 0)
+        sup = ((mask[a:b] != 0) & (mask[a:b] != 2)).astype(np.float64)
+        roll = ((mask[a:b] != 0) & (mask[a:b] != 3)).astype(np.float64)
+        share = np.maximum(sup / int(n[i]), roll / int(n_roll[i]))
+        aeff = np.abs(sup * ref["adv"][a:b] / int(n[i]) - roll * lam * ref["rho"][a:b] * ref["delta"][a:b] / int(n_roll[i]))
+        out[a:b] = abs(grad_scale) / n_samples * (w[i] * EPS_A * share + EPS_F * f[i] * aeff)
+    return out
 
 
 def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label=""):
@@ -109,7 +116,9 @@ def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_sc
         exact = orc.dlogits_row_full_kl(z_rows[k], zs_rows[k], int(y[k]), ref["lse"][t], ref["lse_stale"][t],
                                         ref["roll_kl"][t], c1, c2)
         i = sample_of_row[t]
-        n, f, w = int(ref["n_train"][i]), ref["freshness"][i], ref["weights"][i]
+        # the smaller of the two aligned-set counts: an upper bound on either share, 0 for an invalid sample
+        n = int(min(ref["n_train"][i], ref.get("n_roll", ref["n_train"])[i]))
+        f, w = ref["freshness"][i], ref["weights"][i]
         if c1 == 0.0 and c2 == 0.0 and (n == 0 or f < hp[2] * (1 - 1e-4) or ref["lse"][t] == 0.0):
             assert not np.any(got_rows[k]), "row %d must be exactly zero" % t
             continue

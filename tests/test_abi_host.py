@@ -70,12 +70,12 @@ def test_token_logprobs_rejects_bad_arguments_before_launch():
 
 def _loss(lib, **kw):
     a = dict(logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, mask=None, lb=4096, lq=4096, lqs=None,
-             seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), fin=None, nin=None, row=0,
+             seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), fin=None, nin=None, nroll=None, row=0,
              lse=None, lpin=None, g=1.0, loss=4096, f=None, w=None, lp=None, dl=8192, ws=4096, wsb=1 << 20)
     a.update(kw)
     return lib.fopd_loss_fwd_bwd(P(a["logits"]), a["dt"], a["T"], a["V"], a["ld"], P(a["ids"]), P(a["mask"]),
                                  P(a["lb"]), P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"],
-                                 a["hp"], P(a["fin"]), P(a["nin"]), a["row"], P(a["lse"]), P(a["lpin"]),
+                                 a["hp"], P(a["fin"]), P(a["nin"]), P(a["nroll"]), a["row"], P(a["lse"]), P(a["lpin"]),
                                  a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]), P(a["dl"]),
                                  P(a["ws"]), a["wsb"], None)
 
@@ -94,6 +94,7 @@ def test_loss_rejects_bad_arguments_before_launch():
     assert _loss(lib, lse=4096, lpin=4096) == 1               # ... and without freshness_in
     assert _loss(lib, row=16) == 1                            # a chunk needs scores and counts
     assert _loss(lib, fin=4096, row=16) == 1                  # ... counts still missing
+    assert _loss(lib, fin=4096, nroll=4096) == 1              # roll counts only together with the sup counts
     assert _loss(lib, dl=8192 + 4) == 3
     assert _loss(lib, wsb=256) == 5
 
@@ -103,7 +104,7 @@ def test_freshness_rejects_bad_arguments_before_launch():
 
     def call(logp=4096, seq=4096, lag=4096, f=4096, T=8, B=2, hp=fb.Hparams(1, 1, 0, 0), ws=4096, wsb=1 << 20):
         return lib.fopd_freshness_score(P(logp), P(4096), None, P(4096), None, None, P(seq), P(lag), T, B, hp,
-                                        None, None, None, None, None, None, P(f), None, P(ws), wsb, None)
+                                        None, None, None, None, None, None, None, None, P(f), None, P(ws), wsb, None)
 
     assert call(logp=None) == 1
     assert call(f=None) == 1

@@ -51,7 +51,7 @@ def _compare_everything(w, hp, grad_scale=1.0, staged=True):
     # samples the oracle gates by a clear margin must have bit-exact zero rows
     cu = ref["cu_seqlens"]
     for i in range(w["B"]):
-        if ref["n_train"][i] == 0 or ref["freshness"][i] < hp[2] * (1 - 1e-4):
+        if min(ref["n_train"][i], ref["n_roll"][i]) == 0 or ref["freshness"][i] < hp[2] * (1 - 1e-4):
             assert not np.any(got[cu[i]:cu[i + 1], :V]), "gated/invalid sample %d has non-zero rows" % i
             assert float(lp.weights[i]) == 0.0
     if staged:
@@ -65,13 +65,16 @@ def _compare_everything(w, hp, grad_scale=1.0, staged=True):
         assert np.array_equal(np64(st.gather_idx), ref["gather_idx"]) and st.gather_idx.dtype == torch.int64
         assert np.array_equal(np64(st.cu_seqlens), ref["cu_seqlens"]) and st.cu_seqlens.dtype == torch.int64
         assert np.array_equal(np64(st.n_train), ref["n_train"]) and st.n_train.dtype == torch.int32
+        assert np.array_equal(np64(st.n_roll), ref["n_roll"]) and st.n_roll.dtype == torch.int32
         assert torch.equal(st.logp, lp.logp)                         # same kernel, same bits
         assert_close("lse", np64(st.lse), ref["lse"],
                      atol=1e-4 + np.spacing(np.abs(ref["lse"]).astype(np.float32)).astype(np.float64))
         assert_close("D_roll", np64(st.D_roll), ref["D_roll"], rtol=2e-5, atol=1e-9)
         assert_close("D_sup", np64(st.D_sup), ref["D_sup"], rtol=2e-5, atol=1e-9)
-        assert_close("ell", np64(st.ell), ref["ell"], rtol=2e-5, atol=1e-9)
+        # a mean of fp32-rounded log-probs (each within 1e-6 of the exact one): absolute, not relative
+        assert_close("ell", np64(st.ell), ref["ell"], rtol=2e-5, atol=1e-6)
         assert_close("cover", np64(st.cover), ref["cover"], rtol=1e-6)
+        assert_close("cover_roll", np64(st.cover_roll), ref["cover_roll"], rtol=1e-6)
         assert_close("freshness (staged)", np64(st.freshness), ref["freshness"], rtol=1e-5)
         assert torch.equal(st.freshness, lp.freshness)
         assert_close("agg", np64(st.agg), ref["agg"], rtol=1e-5)
@@ -137,7 +140,8 @@ def test_ragged_vocabulary_and_padding(dtype, V, ld):
 
 def test_random_shapes_sweep():
     """Forty seeded random problems: vocabulary size, padding, storage type, sample count and lengths,
-    masks, empty samples, lags (some gated), hyper-parameters and upstream scale all vary."""
+    masks (one or two aligned sets), empty samples, lags (some gated), hyper-parameters and upstream scale
+    all vary."""
     rs = np.random.RandomState(77)
     for case in range(40):
         dtype = "bf16" if rs.rand() < 0.7 else "f32"
@@ -149,10 +153,12 @@ def test_random_shapes_sweep():
               float(rs.choice([0.0, 0.05, 0.2])), float(rs.choice([0.0, 0.1, 1.0])))
         g = float(rs.choice([1.0, 0.125, -2.0]))
         _say("random case %d: %s V=%d ld=%d B=%d hp=%s g=%g" % (case, dtype, V, ld, B, hp, g))
+        # every third problem keeps the two aligned sets apart (mask bytes 2 and 3 among the kept rows)
+        split = dict(aligned_split=(0.3, 0.3)) if case % 3 == 2 else {}
         w = wl.generate("tooluse", DEV, seed=1000 + case, B=B, turns=int(rs.randint(1, 4)), obs_lo=0,
                         obs_hi=int(rs.randint(0, 5)), resp_lo=0, resp_hi=int(rs.randint(1, 9)), V=V, ld=ld,
                         dtype=dtype, boost=min(3, V), lag_lo=0, lag_hi=int(rs.choice([0, 3, 25])),
-                        stale_sigma=float(rs.choice([0.0, 0.1])), row_block=64)
+                        stale_sigma=float(rs.choice([0.0, 0.1])), row_block=64, **split)
         if w["T"] == 0:
             continue
         _compare_everything(w, hp, grad_scale=g, staged=True)
@@ -194,13 +200,13 @@ def test_zero_rows_is_a_valid_call():
     i32 = torch.zeros(8, dtype=torch.int32, device=DEV)
     lp = LossPass(1, 64, B, "bf16", device=DEV)
     lp.loss.fill_(7.0)
-    fb.fopd_loss_fwd_bwd(dummy, lp.dt, 0, 64, 64, i32, None, f32, f32, None, i32[:B], i32[:B], B, HP, None, None, 0,
+    fb.fopd_loss_fwd_bwd(dummy, lp.dt, 0, 64, 64, i32, None, f32, f32, None, i32[:B], i32[:B], B, HP, None, None, None, 0,
                          None, None, 1.0, lp.loss, lp.freshness, lp.weights, None, dummy, lp.workspace)
     _sync_ok(lp)
     assert float(lp.loss) == 0.0 and not bool(lp.freshness.any()) and not bool(lp.weights.any())
     fb.fopd_token_logprobs(dummy, lp.dt, 0, 64, 64, i32, None, f32, f32, None, None, lp.workspace)
     fb.fopd_freshness_score(f32, f32, None, f32, None, None, i32[:B], i32[:B], 0, B, HP, lp.cu_seqlens, lp.n_train,
-                            None, None, None, lp.cover, lp.freshness, lp.agg, lp.workspace)
+                            None, None, None, None, lp.cover, None, lp.freshness, lp.agg, lp.workspace)
     _sync_ok(lp)
     assert not bool(lp.cu_seqlens.any()) and not bool(lp.n_train.any()) and not bool(lp.agg.any())
 
@@ -334,7 +340,7 @@ def test_scores_supplied_and_chunked_flow():
     sc = _pass_for(w)
     fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
                          w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
-                         f_gpu, None, 0, None, None, 2.0, sc.loss, sc.freshness, sc.weights, sc.logp,
+                         f_gpu, None, None, 0, None, None, 2.0, sc.loss, sc.freshness, sc.weights, sc.logp,
                          sc.dlogits, sc.workspace)
     _sync_ok(sc)
     assert torch.equal(sc.freshness, f_gpu)
@@ -355,7 +361,7 @@ def test_scores_supplied_and_chunked_flow():
         stale = w["teacher_logp_stale"]
         fb.fopd_loss_fwd_bwd(w["logits"][a:b], ck.dt, b - a, V, w["ld"], w["token_ids"][a:b], w["mask"][a:b],
                              w["behav_logp"][a:b], w["teacher_logp"][a:b], None if stale is None else stale[a:b],
-                             w["seq_lens"], w["lag"], B, hp, f_gpu, n_gpu, a, full.lse[a:b], full.logp[a:b],
+                             w["seq_lens"], w["lag"], B, hp, f_gpu, n_gpu, None, a, full.lse[a:b], full.logp[a:b],
                              2.0, part, None, ck.weights, None, ck.dlogits[a:b], ck.workspace)
         parts.append(part)
     _sync_ok(ck)
@@ -389,7 +395,7 @@ def test_two_passes_per_row_kernel_matches_separate_kernels(threads, rows_per_cu
     def call(lp, a, b, lse, logp_in, logp_out, out, n_in):
         fb.fopd_loss_fwd_bwd(w["logits"][a:b], lp.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b],
                              w["behav_logp"][a:b], w["teacher_logp"][a:b], None, w["seq_lens"], w["lag"], B, hp,
-                             f_gpu, n_in, a, lse, logp_in, 0.5, lp.loss, None, lp.weights, logp_out, out,
+                             f_gpu, n_in, None, a, lse, logp_in, 0.5, lp.loss, None, lp.weights, logp_out, out,
                              lp.workspace)
 
     ref = _pass_for(w)                    # separate kernels: stored lse / logp, gradient kernel only
@@ -423,7 +429,7 @@ def test_two_passes_per_row_kernel_matches_separate_kernels(threads, rows_per_cu
         two = _pass_for(w, alloc_dlogits=False)
         fb.fopd_loss_fwd_bwd(z[a:b], two.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b],
                              w["behav_logp"][a:b], w["teacher_logp"][a:b], None, w["seq_lens"], w["lag"], B, hp,
-                             f_gpu, n_gpu, a, None, None, 0.5, two.loss, None, None, None, z[a:b], two.workspace)
+                             f_gpu, n_gpu, None, a, None, None, 0.5, two.loss, None, None, None, z[a:b], two.workspace)
         _sync_ok(two)
         assert same(z[a:b, :V], ref.dlogits[a:b, :V])
         assert torch.equal(z[:a], w["logits"][:a]) and torch.equal(z[b:], w["logits"][b:])
@@ -481,8 +487,8 @@ def test_full_vocabulary_drift_variant(name):
     fb.fopd_rollout_kl(w["logits"], w["logits_stale"], st.dt, T, V, ld, ld, w["token_ids"], w["mask"], kl, st.logp,
                        st.lse, dlse, st.workspace)
     fb.fopd_freshness_score(st.logp, None, kl, w["teacher_logp"], w["teacher_logp_stale"], w["mask"], w["seq_lens"],
-                            w["lag"], T, B, hp, st.cu_seqlens, st.n_train, st.D_roll, st.D_sup, st.ell, st.cover,
-                            st.freshness, st.agg, st.workspace)
+                            w["lag"], T, B, hp, st.cu_seqlens, st.n_train, st.n_roll, st.D_roll, st.D_sup, st.ell, st.cover,
+                            st.cover_roll, st.freshness, st.agg, st.workspace)
     _sync_ok(st)
     assert torch.equal(st.logp, lp.logp) and torch.equal(st.freshness, lp.freshness)
     assert_close("D_roll", np64(st.D_roll), ref["D_roll"], rtol=2e-5, atol=3e-8)
@@ -512,8 +518,8 @@ def test_replay_from_a_hip_graph():
     f_in = eager.freshness.clone()
     sc = _pass_for(w)
     fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
-                         w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, 0, None, None,
-                         1.0, sc.loss, None, sc.weights, sc.logp, sc.dlogits, sc.workspace)   # also warms the kernel up
+                         w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, None, 0, None,
+                         None, 1.0, sc.loss, None, sc.weights, sc.logp, sc.dlogits, sc.workspace)   # also warms the kernel up
     torch.cuda.synchronize()
     g1, g2 = _pass_for(w), _pass_for(w)
     side = torch.cuda.Stream()
@@ -523,8 +529,8 @@ def test_replay_from_a_hip_graph():
         graph.capture_begin()
         g1.loss_fwd_bwd(w, HP)
         fb.fopd_loss_fwd_bwd(w["logits"], g2.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
-                             w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, 0, None, None,
-                             1.0, g2.loss, None, g2.weights, g2.logp, g2.dlogits, g2.workspace)
+                             w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], HP, f_in, None, None, 0, None,
+                             None, 1.0, g2.loss, None, g2.weights, g2.logp, g2.dlogits, g2.workspace)
         graph.capture_end()
     torch.cuda.current_stream().wait_stream(side)
     for rep in range(3):
@@ -652,7 +658,7 @@ def test_ablation_arms_are_parameter_settings():
     sc = _pass_for(w)
     fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
                          w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
-                         ones, None, 0, None, None, 1.0, sc.loss, sc.freshness, sc.weights, sc.logp,
+                         ones, None, None, 0, None, None, 1.0, sc.loss, sc.freshness, sc.weights, sc.logp,
                          sc.dlogits, sc.workspace)
     _sync_ok(sc)
     n_used = orc.trainable_counts(np64(w["mask"]), orc.segment_offsets(np64(w["seq_lens"])))
@@ -866,7 +872,7 @@ def test_coding_full_size_chunked_flow():
         b = a + chunk
         fb.fopd_loss_fwd_bwd(w["logits"][a:b], full.dt, chunk, V, w["ld"], w["token_ids"][a:b], w["mask"][a:b],
                              w["behav_logp"][a:b], w["teacher_logp"][a:b], w["teacher_logp_stale"][a:b],
-                             w["seq_lens"], w["lag"], B, HP, full.freshness, full.n_train, a, full.lse[a:b],
+                             w["seq_lens"], w["lag"], B, HP, full.freshness, full.n_train, None, a, full.lse[a:b],
                              full.logp[a:b], 1.0, part, None, wts, None, dl, full.workspace)
         total += float(part)
         for t in picks_global:
@@ -1090,3 +1096,110 @@ def test_projection_fused_at_benchmark_size_sampled_rows():
     # both launches sum 151,936 fp32 terms per row, in different orders
     assert_close("lse, 8 strips vs 32", np64(lse8), np64(lse)[:T8], rtol=0, atol=1e-4)
     assert_close("logp, 8 strips vs 32", np64(logp8), got[:T8], rtol=0, atol=1e-4)
+
+
+# ---------------------------------------------------------------------------------------
+# the two aligned sets kept apart (mask bytes 0 / 1 / 2 / 3)
+# ---------------------------------------------------------------------------------------
+
+def _two_set_workload(seed, **kw):
+    w = wl.generate("coding", DEV, seed=seed, B=6, total_len=96, resp_lo=8, resp_hi=24, obs_lo=3, obs_hi=9,
+                    aligned_split=(0.3, 0.25), **kw)
+    m = w["mask_host"].copy()
+    m[96:192][m[96:192] != 0] = 3                 # sample 1: U^roll empty -> invalid
+    m[192:288][m[192:288] != 0] = 2               # sample 2: U^sup empty  -> invalid
+    m[288] = 200                                  # any other non-zero byte counts as "both"
+    w["mask_host"] = m
+    w["mask"] = torch.from_numpy(m).to(DEV)
+    return w
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("V,ld", [(4099, 4104), (151936, 151936)])
+def test_two_aligned_sets_all_outputs(V, ld):
+    _say("two aligned sets V=%d" % V)
+    w = _two_set_workload(31, V=V, ld=ld)
+    assert set(np.unique(w["mask_host"])) >= {0, 1, 2, 3}
+    hp = (1.0, 1.0, 0.02, 0.4)
+    ref, lp = _compare_everything(w, hp, grad_scale=1.5, staged=True)
+    assert ref["freshness"][1] == 0.0 and ref["freshness"][2] == 0.0 and ref["agg"][1] != ref["agg"][2]
+    # invalid samples stay out whatever the threshold is
+    ref2, lp2 = _compare_everything(w, (1.0, 1.0, -0.5, 0.4), grad_scale=1.0, staged=False)
+    assert float(lp2.weights[1]) == 0.0 and float(lp2.weights[2]) == 0.0 and float(lp2.weights[0]) > 0.5
+
+
+@pytest.mark.gpu
+def test_two_aligned_sets_scored_and_chunked_flow():
+    """Scores supplied (both passes in one kernel) and the chunked gradient with both count arrays passed
+    in must give the bits of the all-in-one call."""
+    w = _two_set_workload(32, V=9001, ld=9008)
+    T, V, B = w["T"], w["V"], w["B"]
+    hp = (1.0, 1.0, 0.02, 0.4)
+    one = _pass_for(w)
+    one.loss_fwd_bwd(w, hp, 0.5)
+    st = _pass_for(w, alloc_dlogits=False)
+    st.token_logprobs(w)
+    st.freshness_score(w, hp)
+    _sync_ok(st)
+    sc = _pass_for(w)
+    fb.fopd_loss_fwd_bwd(w["logits"], sc.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                         w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
+                         st.freshness, None, None, 0, None, None, 0.5, sc.loss, None, sc.weights, sc.logp,
+                         sc.dlogits, sc.workspace)
+    _sync_ok(sc)
+    # the all-in-one call keeps f_i in fp64, this one reads the fp32 copy: equal to one bf16 ulp, not bitwise
+    a64, b64 = np64(sc.dlogits)[:, :V], np64(one.dlogits)[:, :V]
+    assert np.all(np.abs(a64 - b64) <= 2.0 ** -7 * np.abs(b64) + 2.0 ** -126)
+    assert_close("weights (scored vs fused)", np64(sc.weights), np64(one.weights), rtol=1e-6, atol=1e-9)
+    assert abs(float(sc.loss) - float(one.loss)) <= 2e-6 * abs(float(one.loss))
+    ck = _pass_for(w)
+    ck.dlogits.fill_(3.0)
+    tot = 0.0
+    for a in range(0, T, 80):                     # chunks cut samples (96 rows each)
+        b = min(a + 80, T)
+        part = torch.zeros(1, device=DEV)
+        fb.fopd_loss_fwd_bwd(w["logits"][a:b], ck.dt, b - a, V, w["ld"], w["token_ids"][a:b], w["mask"][a:b],
+                             w["behav_logp"][a:b], w["teacher_logp"][a:b], w["teacher_logp_stale"][a:b],
+                             w["seq_lens"], w["lag"], B, hp, st.freshness, st.n_train, st.n_roll, a, st.lse[a:b],
+                             st.logp[a:b], 0.5, part, None, ck.weights, None, ck.dlogits[a:b], ck.workspace)
+        tot += float(part)
+    _sync_ok(ck)
+    assert torch.equal(ck.dlogits[:, :V], sc.dlogits[:, :V])       # same bits; padding columns are never written
+    assert torch.equal(ck.weights, sc.weights)
+    assert abs(tot - float(one.loss)) <= 2e-6 * abs(float(one.loss))
+
+
+@pytest.mark.gpu
+def test_two_aligned_sets_in_the_two_tensor_variants():
+    w = _two_set_workload(33, V=5003, ld=5008, stale_logit_sigma=0.05)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    hp = (1.0, 1.0, 0.02, 0.4)
+    z, z2 = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+    sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]))
+    for teacher in (False, True):
+        lp = _pass_for(w)
+        kl = torch.empty(T, device=DEV)
+        if teacher:
+            ref = orc.fopd_loss_fwd_bwd_full_teacher(z, z2, np64(w["token_ids"]), np64(w["mask"]), np64(w["behav_logp"]),
+                                                     np64(w["teacher_logp"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                                     hp[0], hp[1], hp[2], hp[3], 1.2, out_dtype=w["dtype"])
+            fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
+                                              w["mask"], w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"],
+                                              B, hp, 1.2, lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits,
+                                              lp.workspace)
+        else:
+            ref = orc.fopd_loss_fwd_bwd_full_kl(z, z2, np64(w["token_ids"]), np64(w["mask"]), np64(w["teacher_logp"]),
+                                                np64(w["teacher_logp_stale"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                                hp[0], hp[1], hp[2], hp[3], 1.2, out_dtype=w["dtype"])
+            fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                         w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
+                                         1.2, lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+        _sync_ok(lp)
+        assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+        assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+        assert abs(float(lp.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+        assert ref["freshness"][1] == 0.0 and ref["freshness"][2] == 0.0
+        ref.setdefault("delta", np.zeros(T))
+        ref.setdefault("rho", np.ones(T))
+        check_grad_rows_full_kl(np64(lp.dlogits)[:, :V], z, z2, np64(w["token_ids"]), ref, range(T), hp, 1.2, B,
+                                sample_of, w["dtype"], c2_scales_with_weight=teacher)
