@@ -50,3 +50,19 @@ def test_boost_and_heavy_tails_and_padding():
     w = wl.generate("largevocab", "cpu", seed=0, B=4, len_lo=8, len_hi=8, V=8192)
     assert list(w["lag_host"][:2]) == [0, 0] and int(w["lag_host"][2:].min()) >= 8
     assert float(w["logits"].float().abs().max()) > 30.0        # Student-t tails
+
+
+def test_aligned_split_marks_rows_and_leaves_the_rest_of_the_workload_alone():
+    kw = dict(B=3, total_len=200, resp_lo=10, resp_hi=30, obs_lo=5, obs_hi=15, V=64)
+    a = wl.generate("coding", "cpu", seed=4, **kw)
+    b = wl.generate("coding", "cpu", seed=4, aligned_split=(0.3, 0.2), **kw)
+    ma, mb = a["mask_host"], b["mask_host"]
+    assert set(np.unique(ma)) <= {0, 1} and set(np.unique(mb)) == {0, 1, 2, 3}
+    assert np.array_equal(ma != 0, mb != 0)                       # only kept rows are re-labelled
+    kept = int((ma != 0).sum())
+    assert abs(int((mb == 2).sum()) / kept - 0.3) < 0.08 and abs(int((mb == 3).sum()) / kept - 0.2) < 0.08
+    assert b["n_trainable"] == int(((mb == 1) | (mb == 3)).sum())  # rows that carry the token loss
+    assert np.array_equal(a["seq_lens_host"], b["seq_lens_host"]) and np.array_equal(a["lag_host"], b["lag_host"])
+    assert bool((a["logits"] == b["logits"]).all()) and bool((a["token_ids"] == b["token_ids"]).all())
+    c = wl.generate("coding", "cpu", seed=4, aligned_split=(0.3, 0.2), **kw)
+    assert np.array_equal(mb, c["mask_host"])                      # seeded
