@@ -265,6 +265,52 @@ def test_loss_normaliser_linearity_and_permutation():
     assert orc.anchored_loss(w[perm], ell[perm], D[perm], 0.7) == orc.anchored_loss(w, ell, D, 0.7)
 
 
+def _hand_worked_two_set_inputs():
+    """The inputs of tests/golden/hand_worked_two_sets.txt: integer softmax weights per row, the two aligned
+    sets told apart by the mask byte, log-ratios that are +-ln2 / +-ln3 on the rows a set uses and decoys
+    (large, different values) on the rows it must not use."""
+    ln2, ln3 = math.log(2.0), math.log(3.0)
+    weights = [(1, 1, 1, 1), (1, 3, 2, 2), (2, 1, 1, 4), (1, 2, 4, 1), (4, 2, 1, 1), (1, 1, 1, 1), (1, 1, 2, 4),
+               (1, 1, 1, 1), (1, 1, 1, 1)]
+    z = np.log(np.array(weights, dtype=np.float64))
+    y = np.array([0, 1, 3, 2, 0, 2, 2, 1, 1], dtype=np.int32)
+    mask = np.array([1, 2, 2, 3, 3, 0, 1, 3, 3], dtype=np.uint8)
+    lp = np.array([-2 * ln2, ln3 - 3 * ln2, -ln2, -ln2, -ln2, -2 * ln2, -2 * ln2, -2 * ln2, -2 * ln2])
+    delta = np.array([ln2, -ln2, ln3, 2.5, 4.0, 0.3, -ln3, 0.0, 0.0])        # rows 3, 4, 5: decoys
+    lp_minus_lq = np.array([ln3, 0.9, -1.1, -ln2, ln2, 0.2, ln3, ln2, ln2])  # rows 1, 2, 5: decoys
+    lq_minus_lqs = np.array([ln2, 1.0, -0.25, ln3, -ln2, 2.0, ln2, 0.1, 0.2])  # rows 1, 2, 5: decoys
+    lq = lp - lp_minus_lq
+    return dict(z=z, y=y, mask=mask, lb=lp - delta, lq=lq, lqs=lq - lq_minus_lqs, lp=lp,
+                seq=np.array([4, 3, 2], dtype=np.int32), lag=np.array([1, 0, 0], dtype=np.int32),
+                hp=dict(alpha=0.5, beta=0.25, xi=-0.5, lam=0.5), g=2.0, weights=np.array(weights, dtype=np.float64))
+
+
+def test_hand_worked_case_with_two_different_aligned_sets():
+    """Literal values worked by hand from Eq. "kl-diagnostics" (both lines), Eq. "sample-aggregated-loss", Eq.
+    "freshness", the aggregates and weights of Sec. 4.2 and Algorithm 1's invalid-sample branch, on a case
+    where |U^sup|, |U^roll| and H_i all differ and one sample has U^roll empty while xi < 0.  Nothing here
+    re-evaluates a formula: the expected numbers are read from the fixture."""
+    want = {}
+    for line in open(os.path.join(GOLDEN, "hand_worked_two_sets.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, *vals = line.split()
+            want[name] = np.array([float(v) for v in vals])
+    c = _hand_worked_two_set_inputs()
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                grad_scale=c["g"], **c["hp"])
+    np.testing.assert_allclose(res["logp"][c["mask"] != 0], c["lp"][c["mask"] != 0], rtol=0, atol=1e-15)
+    assert list(res["n_train"]) == list(want["n_sup"]) and list(res["n_roll"]) == list(want["n_roll"])
+    for key in ("D_roll", "D_sup", "ell", "cover", "cover_roll", "freshness", "weights", "agg", "coef"):
+        np.testing.assert_allclose(res[key], want[key], rtol=0, atol=2e-16 + 1e-15, err_msg=key)
+    assert abs(res["loss"] - want["loss"][0]) <= 1e-15
+    assert want["agg"][1] != want["agg"][2]                       # the two coverage means differ in this case
+    assert res["weights"][2] == 0.0 and res["freshness"][2] == 0.0 and 0.0 - c["hp"]["xi"] > 0.0
+    # one gradient row spelled out: c_2 * (softmax - onehot) with softmax = weights / 8
+    np.testing.assert_allclose(res["dlogits_exact"][2], want["coef"][2] * np.array([0.25, 0.125, 0.125, -0.5]),
+                               rtol=0, atol=1e-15)
+    assert np.all(res["dlogits_exact"][[5, 7, 8]] == 0.0)
+
+
 # ---------------------------------------------------------------------------------------
 # whole pass: tiny brute-force cases
 # ---------------------------------------------------------------------------------------
