@@ -79,14 +79,15 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
     def step():
         if teacher:
             fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
-                                              w["mask"], w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"],
-                                              B, hp, 1.0, lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits,
+                                              w["mask"], w["behav_logp"], w["teacher_logp_stale"], w["seq_lens"],
+                                              w["lag"], B, hp, None, None, None, 0, None, None, None, None, 1.0,
+                                              lp.loss, lp.freshness, lp.weights, lp.logp, kl, lp.dlogits,
                                               lp.workspace)
         else:
             fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
                                          w["mask"], w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"],
-                                         w["lag"], B, hp, 1.0, lp.loss, lp.freshness, lp.weights, lp.logp, kl,
-                                         lp.dlogits, lp.workspace)
+                                         w["lag"], B, hp, None, None, None, 0, None, None, None, None, 1.0, lp.loss,
+                                         lp.freshness, lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
 
     for _ in range(args.warmup):
         step()
@@ -102,9 +103,12 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
     k5_ms, n5 = fb.fopd_profile_read(0)
     k6_ms, n6 = fb.fopd_profile_read(1)
     e = 2 if w["dtype"] == "bf16" else 4
+    import numpy as np
     live = int((w["mask_host"] != 0).sum())
+    per_row_w = np.repeat(lp.weights.cpu().numpy(), w["seq_lens_host"])
+    grad_rows = int(((w["mask_host"] != 0) & (per_row_w > 0)).sum())    # rows of gated samples are zero-filled unread
     k5_bytes = live * 2 * V * e
-    k6_bytes = live * 3 * V * e + (T - live) * V * e
+    k6_bytes = grad_rows * 3 * V * e + (T - grad_rows) * V * e
     k5_s, k6_s = k5_ms / max(n5, 1) * 1e-3, k6_ms / max(n6, 1) * 1e-3
     print(json.dumps({
         "metric": ("tokens/s, OPD loss fwd+bwd with distribution-level loss against teacher logits, V=%d %s"
@@ -196,7 +200,7 @@ def main():
 
     import torch
     from paper_2605_17862_amd import binding as fb
-    from paper_2605_17862_amd import workloads as wl
+    from harness import workloads as wl
     from paper_2605_17862_amd.loss_pass import DEFAULT_HPARAMS, LossPass
 
     if not torch.cuda.is_available():

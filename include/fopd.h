@@ -29,13 +29,20 @@
  *     "*_host".  The caller owns all buffers; the library allocates no device memory.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream).  No entry point synchronises, except those documented as host-synchronous.
+ *   - The library keeps no state between calls except what fopd_set_option and the fopd_profile_* hooks
+ *     set (process-wide, behind one mutex) and a per-device note that a kernel attribute has been set.
+ *     The entry points may be called from several threads; calls that share a workspace must be ordered
+ *     by the caller (same stream, or events).
  *   - Matrices are row-major [T, ld] with ld >= V; columns V..ld-1 are never read or written.
  *     The base address must be 16-byte aligned and ld * sizeof(element) a multiple of 16.
  *   - The return value reports what the host can check before launching (arguments, sizes,
  *     alignment, workspace size) and launch failures.  Conditions only visible on the device
- *     (token id outside [0, V), negative lag or length, lengths not adding up to T) set sticky
- *     bits in the first int32 of the workspace; fopd_workspace_status() reads them.  A row
- *     with an out-of-range token id is treated as masked.
+ *     (token id outside [0, V), negative lag or length, lengths not adding up to T, a mask that names
+ *     two different aligned sets where only one count array was passed) set sticky bits in the first
+ *     int32 of the workspace; fopd_workspace_status() reads them.  A row with an out-of-range token id
+ *     is treated as masked; a sample with a negative lag is treated as invalid (f_i = w_i = 0, both
+ *     alignment ratios 0); a row of only one set whose call has no n_roll_in gets a zero gradient row
+ *     and adds nothing to the loss.
  *   - Non-finite inputs propagate to non-finite outputs; nothing traps.
  *   - Identical inputs give bit-identical outputs (all reductions have a fixed order).
  *   - Rows in neither aligned set (mask 0) produce lp = lse = 0 and an all-zero gradient row and are not read.
@@ -60,7 +67,9 @@ typedef enum {
   FOPD_ETOKEN_RANGE = 6, /* device flag: some token id outside [0, V) */
   FOPD_ESEGMENTS = 7,    /* device flag: seq_lens negative or not covering the rows of the call */
   FOPD_ELAG = 8,         /* device flag: some lag < 0 */
-  FOPD_EHIP = 9          /* a HIP runtime call or kernel launch failed */
+  FOPD_EHIP = 9,         /* a HIP runtime call or kernel launch failed */
+  FOPD_ESETS = 10,       /* device flag: mask bytes 2 / 3 (the two aligned sets differ) in a chunk call made without n_roll_in */
+  FOPD_ELIMIT = 11       /* T or B beyond the fixed limits of an entry point that owns its scratch memory */
 } fopd_status;
 
 typedef enum { FOPD_F32 = 0, FOPD_BF16 = 1 } fopd_dtype;
@@ -75,7 +84,7 @@ typedef struct {
 } fopd_hparams;
 
 /* Static, NUL-terminated description of a status code. Never NULL. */
-const char* fopd_status_string(int status);
+const char* fopd_status_string(fopd_status status);
 
 /* Bytes of device workspace that any entry point needs for a call with at most T rows and B
  * samples (a multiple of 256).  The workspace must be 256-byte aligned. */
@@ -86,9 +95,12 @@ size_t fopd_workspace_bytes(int64_t T, int32_t B);
 fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* stream);
 
 /* HOST-SYNCHRONOUS.  Waits for `stream`, reads the sticky device flags and returns FOPD_OK or the
- * first of FOPD_ETOKEN_RANGE, FOPD_ESEGMENTS, FOPD_ELAG that is set.  If flags_host is not NULL
- * it receives the raw bit mask (bit 0 token range, bit 1 segments, bit 2 lag). */
+ * first of FOPD_ETOKEN_RANGE, FOPD_ESEGMENTS, FOPD_ELAG, FOPD_ESETS that is set.  If flags_host is not
+ * NULL it receives the raw bit mask (bit 0 token range, bit 1 segments, bit 2 lag, bit 3 aligned sets). */
 fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host);
+
+/* HOST ONLY.  The status that a raw flag word (as above) stands for. */
+fopd_status fopd_flags_status(int32_t flags);
 
 /*
  * The `mask` argument of every entry point: one byte per row naming the aligned sets of Sec. 4.1 that
@@ -138,6 +150,10 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *   roll_kl                         [T] f32 or NULL: per-row full-vocabulary KL(pi^t || pi^r) from
  *                                   fopd_rollout_kl; when given it is the token drift that D^roll
  *                                   averages and behav_logp is not read (it may then be NULL)
+ *   token_loss                      [T] f32 or NULL: a per-row token loss computed elsewhere (the
+ *                                   distribution-level KL against the teacher's logits, the `roll_kl`
+ *                                   output of fopd_rollout_kl called with the teacher's tensor); when
+ *                                   given, ell averages it instead of lp - lq
  *   teacher_logp_stale              [T] f32 or NULL: teacher log-probability under the context
  *                                   used at grading time; NULL gives D^sup = 0
  *   mask [T] uint8 or NULL; seq_lens [B] int32 (sum must be T); lag [B] int32 >= 0
@@ -150,6 +166,7 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *   Any of the output pointers except freshness may be NULL.
  */
 fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
+                                 const float* token_loss,
                                  const float* teacher_logp, const float* teacher_logp_stale,
                                  const uint8_t* mask, const int32_t* seq_lens, const int32_t* lag,
                                  int64_t T, int32_t B, fopd_hparams hp,
@@ -172,7 +189,8 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
  *                          covers whole samples (row_begin == 0, sum(seq_lens) == T) and the
  *                          counts are to be taken from `mask`.  n_roll_in: the [B] n_roll array of
  *                          fopd_freshness_score, or NULL when the two sets coincide (a 0/1 mask);
- *                          only with n_train_in.
+ *                          only with n_train_in.  (n_train_in without n_roll_in on a mask that does hold
+ *                          bytes 2 or 3 raises the FOPD_ESETS flag and drops those rows.)
  *                          Without lse_in the logits are still read from HBM only once: one kernel
  *                          makes both passes over each row while it is cache-resident.
  *   lse_in / logp_in     : both or neither.  When given ([T] f32, the outputs of
@@ -207,11 +225,17 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
  *   logits, logits_stale  [T, ld] / [T, ld_stale] of `dt`
  *   roll_kl, logp, lse    [T] f32 out as in fopd_token_logprobs (0 for masked rows)
  *   dlse                  [T] f32 out: lse_t - lse'_t
- * Feed roll_kl to fopd_freshness_score to score the buffer with the paper's own diagnostic.
+ *   logq                  [T] f32 out or NULL: log softmax(z'_t)[y_t], the second tensor's log-probability of
+ *                         the sampled token
+ * Feed roll_kl to fopd_freshness_score to score the buffer with the paper's own diagnostic.  The two rows
+ * may be arbitrarily far apart (each has its own running reference); for close rows the KL, a quantity much
+ * smaller than either log-sum-exp, is accumulated directly and keeps ~1e-5 relative accuracy.
+ * The same call on the TEACHER's logits gives the distribution-level token loss KL(student || teacher) per
+ * row and, in logq, the teacher's log-probability of y_t.
  */
 fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
                             int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
-                            float* roll_kl, float* logp, float* lse, float* dlse,
+                            float* roll_kl, float* logp, float* lse, float* dlse, float* logq,
                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
@@ -221,13 +245,26 @@ fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_d
  *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (log p_u - log p'_u - roll_kl_t),
  *   c1_t = g [t in U^sup] w_i / (B |U_i^sup|) A_t,   c2_t = g [t in U^roll] w_i / (B |U_i^roll|) lambda.
  * Arguments as in fopd_loss_fwd_bwd; behav_logp is not needed.  logp, roll_kl, freshness, weights may be
- * NULL.  dlogits may alias logits but not logits_stale.  Whole samples only: sum(seq_lens) must be T.
+ * NULL.  dlogits may alias logits but not logits_stale.
+ *
+ *   freshness_in == NULL : whole samples, everything computed here (sum(seq_lens) == T; the other *_in
+ *                          arguments NULL, row_begin 0).
+ *   freshness_in != NULL : the chunked long-horizon flow, when three [T, V] tensors do not fit.  Per chunk
+ *                          fopd_rollout_kl (-> roll_kl, logp, lse, dlse slices), once fopd_freshness_score
+ *                          with that roll_kl (-> freshness, n_train, n_roll), then per chunk this call with
+ *                          rows [row_begin, row_begin + T): freshness_in [B], n_train_in [B] (required),
+ *                          n_roll_in [B] (NULL = the two sets coincide), and the chunk's slices lse_in,
+ *                          logp_in, dlse_in, roll_kl_in [T] (all required).  Only coefficients, the chunk's
+ *                          additive share of the loss and the gradient rows are made; chunks may cut samples.
  */
 fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T,
                                       int64_t V, int64_t ld, int64_t ld_stale, const int32_t* token_ids,
                                       const uint8_t* mask, const float* teacher_logp,
                                       const float* teacher_logp_stale, const int32_t* seq_lens, const int32_t* lag,
-                                      int32_t B, fopd_hparams hp, float grad_scale,
+                                      int32_t B, fopd_hparams hp,
+                                      const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                                      int64_t row_begin, const float* lse_in, const float* logp_in,
+                                      const float* dlse_in, const float* roll_kl_in, float grad_scale,
                                       float* loss, float* freshness, float* weights, float* logp, float* roll_kl,
                                       void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -241,13 +278,21 @@ fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_sta
  *   c1_t = -g [t in U^roll] w_i / (B |U_i^roll|) lambda rho_t delta_t,   c2_t = g [t in U^sup] w_i / (B |U_i^sup|).
  * Averaged over y ~ softmax(z) the default path's sampled-token gradient equals this one's KL part.
  *   token_kl  [T] f32 out or NULL: l_t.  Other arguments as in fopd_loss_fwd_bwd_full_kl.
- * dlogits may alias logits but not teacher_logits.  Whole samples only.
+ * dlogits may alias logits but not teacher_logits.
+ * Chunked flow (freshness_in != NULL): per chunk fopd_rollout_kl on (logits, teacher_logits) with logq
+ * (-> token_kl, logp, lse, dlse, logq slices); once fopd_freshness_score(logp, behav_logp, NULL, token_kl,
+ * logq as teacher_logp, ...); then per chunk this call with freshness_in, n_train_in, n_roll_in, row_begin and
+ * the slices lse_in, logp_in, dlse_in, token_kl_in, exactly as for fopd_loss_fwd_bwd_full_kl.
  */
 fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teacher_logits, fopd_dtype dt, int64_t T,
                                            int64_t V, int64_t ld, int64_t ld_teacher, const int32_t* token_ids,
                                            const uint8_t* mask, const float* behav_logp,
                                            const float* teacher_logp_stale, const int32_t* seq_lens,
-                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
+                                           const int32_t* lag, int32_t B, fopd_hparams hp,
+                                           const float* freshness_in, const int32_t* n_train_in,
+                                           const int32_t* n_roll_in, int64_t row_begin, const float* lse_in,
+                                           const float* logp_in, const float* dlse_in, const float* token_kl_in,
+                                           float grad_scale,
                                            float* loss, float* freshness, float* weights, float* logp, float* token_kl,
                                            void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -279,7 +324,7 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
                         int64_t step, int32_t* reason_host);
 
 /*
- * Launch-shape options (process-wide, not thread-safe; set before the calls they affect):
+ * Launch-shape options (process-wide; a call reads them once, under the library's mutex, when it starts):
  *   "k14_threads"      256, 512 or 1024 lanes per row in the kernel that makes both passes over a row
  *                      (used when freshness_in is given without lse_in); default 256
  *   "k14_rows_per_cu"  1..8 rows in flight per compute unit in that kernel; default 6 (the second
@@ -314,8 +359,9 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
- * is bracketed by HIP events on the launch stream.  Not thread-safe; meant for a single
- * benchmarking thread.  fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
+ * is bracketed by HIP events on the launch stream (process-wide state behind the library's mutex; the
+ * events are created on first use, so do not enable it around code that may not allocate).
+ * fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
  *   which: 0 = log-sum-exp pass, 1 = gradient pass, 2 = both passes in one kernel (scores supplied),
  *          3 = projection fused with the log-sum-exp.
  */

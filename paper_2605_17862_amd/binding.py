@@ -16,7 +16,7 @@ FOPD_F32 = 0
 FOPD_BF16 = 1
 
 SYMBOLS = (
-    "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status",
+    "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status", "fopd_flags_status",
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
     "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
@@ -74,6 +74,8 @@ def load_library():
     lib.fopd_workspace_init.argtypes = [vp, sz, vp]
     lib.fopd_workspace_status.restype = ctypes.c_int
     lib.fopd_workspace_status.argtypes = [vp, vp, ctypes.POINTER(i32)]
+    lib.fopd_flags_status.restype = ctypes.c_int
+    lib.fopd_flags_status.argtypes = [i32]
     lib.fopd_token_logprobs.restype = ctypes.c_int
     lib.fopd_token_logprobs.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_lm_head_workspace_bytes.restype = sz
@@ -81,16 +83,18 @@ def load_library():
     lib.fopd_lm_head_token_logprobs.restype = ctypes.c_int
     lib.fopd_lm_head_token_logprobs.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
-    lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
+    lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_rollout_kl.restype = ctypes.c_int
-    lib.fopd_rollout_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_rollout_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd_full_teacher.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_full_teacher.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp,
-                                                   i32, Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                                   i32, Hparams, vp, vp, vp, i64, vp, vp, vp, vp, f32,
+                                                   vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd_full_kl.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_full_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32,
-                                              Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                              Hparams, vp, vp, vp, i64, vp, vp, vp, vp, f32,
+                                              vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                       vp, vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -198,7 +202,13 @@ def fopd_lm_head_token_logprobs(hidden, ldh, weight, ldw, T, V, d, token_ids, ma
     _check(st, "fopd_lm_head_token_logprobs")
 
 
-def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_stale, mask, seq_lens, lag, T, B,
+def fopd_flags_status(flags):
+    """Host only: the status code a raw device flag word stands for."""
+    return int(load_library().fopd_flags_status(int(flags)))
+
+
+def fopd_freshness_score(logp, behav_logp, roll_kl, token_loss, teacher_logp, teacher_logp_stale, mask, seq_lens, lag,
+                         T, B,
                          hp, cu_seqlens, n_train, n_roll, D_roll, D_sup, ell, cover, cover_roll, freshness, agg,
                          workspace, stream=None):
     import torch
@@ -206,7 +216,7 @@ def fopd_freshness_score(logp, behav_logp, roll_kl, teacher_logp, teacher_logp_s
     p, n = _ws(workspace)
     st = load_library().fopd_freshness_score(
         _ptr(logp, f32, "logp"), _ptr(behav_logp, f32, "behav_logp"), _ptr(roll_kl, f32, "roll_kl"),
-        _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(token_loss, f32, "token_loss"), _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(mask, torch.uint8, "mask"),
         _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(T), int(B), _hp(hp),
         _ptr(cu_seqlens, torch.int64, "cu_seqlens"), _ptr(n_train, torch.int32, "n_train"),
@@ -239,7 +249,7 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
     _check(st, "fopd_loss_fwd_bwd")
 
 
-def fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, roll_kl, logp, lse, dlse,
+def fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, roll_kl, logp, lse, dlse, logq,
                     workspace, stream=None):
     import torch
     f32 = torch.float32
@@ -249,12 +259,13 @@ def fopd_rollout_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mas
         _ptr(logits, mat, "logits"), _ptr(logits_stale, mat, "logits_stale"), int(dt), int(T), int(V), int(ld),
         int(ld_stale), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(roll_kl, f32, "roll_kl"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"), _ptr(dlse, f32, "dlse"),
-        p, n, _stream(stream))
+        _ptr(logq, f32, "logq"), p, n, _stream(stream))
     _check(st, "fopd_rollout_kl")
 
 
 def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, teacher_logp,
-                              teacher_logp_stale, seq_lens, lag, B, hp, grad_scale, loss, freshness, weights, logp,
+                              teacher_logp_stale, seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin,
+                              lse_in, logp_in, dlse_in, roll_kl_in, grad_scale, loss, freshness, weights, logp,
                               roll_kl, dlogits, workspace, stream=None):
     import torch
     f32 = torch.float32
@@ -264,7 +275,11 @@ def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, dt, T, V, ld, ld_stale, toke
         _ptr(logits, mat, "logits"), _ptr(logits_stale, mat, "logits_stale"), int(dt), int(T), int(V), int(ld),
         int(ld_stale), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(teacher_logp, f32, "teacher_logp"), _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
-        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), float(grad_scale),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
+        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"),
+        _ptr(n_roll_in, torch.int32, "n_roll_in"), int(row_begin), _ptr(lse_in, f32, "lse_in"),
+        _ptr(logp_in, f32, "logp_in"), _ptr(dlse_in, f32, "dlse_in"), _ptr(roll_kl_in, f32, "roll_kl_in"),
+        float(grad_scale),
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(roll_kl, f32, "roll_kl"), _ptr(dlogits, mat, "dlogits"), p, n,
         _stream(stream))
@@ -272,8 +287,9 @@ def fopd_loss_fwd_bwd_full_kl(logits, logits_stale, dt, T, V, ld, ld_stale, toke
 
 
 def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, dt, T, V, ld, ld_teacher, token_ids, mask, behav_logp,
-                                   teacher_logp_stale, seq_lens, lag, B, hp, grad_scale, loss, freshness, weights,
-                                   logp, token_kl, dlogits, workspace, stream=None):
+                                   teacher_logp_stale, seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in,
+                                   row_begin, lse_in, logp_in, dlse_in, token_kl_in, grad_scale, loss, freshness,
+                                   weights, logp, token_kl, dlogits, workspace, stream=None):
     import torch
     f32 = torch.float32
     mat = (torch.float32, torch.bfloat16)
@@ -282,7 +298,11 @@ def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, dt, T, V, ld, ld_teac
         _ptr(logits, mat, "logits"), _ptr(teacher_logits, mat, "teacher_logits"), int(dt), int(T), int(V), int(ld),
         int(ld_teacher), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
-        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), float(grad_scale),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
+        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"),
+        _ptr(n_roll_in, torch.int32, "n_roll_in"), int(row_begin), _ptr(lse_in, f32, "lse_in"),
+        _ptr(logp_in, f32, "logp_in"), _ptr(dlse_in, f32, "dlse_in"), _ptr(token_kl_in, f32, "token_kl_in"),
+        float(grad_scale),
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(token_kl, f32, "token_kl"), _ptr(dlogits, mat, "dlogits"), p, n,
         _stream(stream))

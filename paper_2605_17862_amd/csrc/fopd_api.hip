@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -20,28 +21,29 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Carving of the caller's workspace.  Every region starts on a 256-byte boundary.
 struct Workspace {
-  size_t flags, cu, n_train, n_roll, fresh64, coef, lse, logp, coef2, dlse, kl, logq, partials, total;
-  Workspace(int64_t T, int32_t B) {
+  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, fresh64 = 0, coef = 0, lse = 0, logp = 0, coef2 = 0, dlse = 0,
+         kl = 0, logq = 0, partials = 0, total = 0;
+  static constexpr size_t take(size_t& off, size_t bytes) {
+    const size_t at = off;
+    off = (off + bytes + 255) / 256 * 256;
+    return at;
+  }
+  constexpr Workspace(int64_t T, int32_t B) {
     const size_t t = static_cast<size_t>(T < 0 ? 0 : T), b = static_cast<size_t>(B < 0 ? 0 : B);
     size_t off = 0;
-    auto take = [&](size_t bytes) {
-      const size_t at = off;
-      off = align_up(off + bytes, 256);
-      return at;
-    };
-    flags = take(4 * sizeof(int32_t));
-    cu = take((b + 1) * sizeof(int64_t));
-    n_train = take(b * sizeof(int32_t));
-    n_roll = take(b * sizeof(int32_t));
-    fresh64 = take(b * sizeof(double));
-    coef = take(t * sizeof(float));
-    lse = take(t * sizeof(float));
-    logp = take(t * sizeof(float));
-    coef2 = take(t * sizeof(float));
-    dlse = take(t * sizeof(float));
-    kl = take(t * sizeof(float));
-    logq = take(t * sizeof(float));
-    partials = take((t + 1) * sizeof(double));     // per-block or per-row loss terms
+    flags = take(off, 4 * sizeof(int32_t));
+    cu = take(off, (b + 1) * sizeof(int64_t));
+    n_train = take(off, b * sizeof(int32_t));
+    n_roll = take(off, b * sizeof(int32_t));
+    fresh64 = take(off, b * sizeof(double));
+    coef = take(off, t * sizeof(float));
+    lse = take(off, t * sizeof(float));
+    logp = take(off, t * sizeof(float));
+    coef2 = take(off, t * sizeof(float));
+    dlse = take(off, t * sizeof(float));
+    kl = take(off, t * sizeof(float));
+    logq = take(off, t * sizeof(float));
+    partials = take(off, (t + 1) * sizeof(double));     // per-block or per-row loss terms
     total = off;
   }
 };
@@ -83,6 +85,11 @@ fopd_status check_workspace(const void* ws, size_t bytes, int64_t T, int32_t B) 
 
 inline fopd_status launched() { return hipGetLastError() == hipSuccess ? FOPD_OK : FOPD_EHIP; }
 
+// ---- the library's only process-wide state: launch-shape options, the optional timing events and the
+// per-device "attribute already set" tables.  All of it sits behind one mutex; the entry points hold it
+// only while they read or update this state, never across a launch.
+std::mutex g_state_mutex;
+
 // ---- optional per-kernel timing ---------------------------------------------------------
 struct Profiler {
   bool on = false;
@@ -90,25 +97,31 @@ struct Profiler {
   size_t used[4] = {0, 0, 0, 0};
 } g_prof;
 
+// Brackets the launches made during its lifetime with a pair of events when timing is switched on.
+// `allowed` = false (the entry point that may not allocate: event creation allocates) records nothing.
 struct ScopedTimer {
-  int which;
+  hipEvent_t stop = nullptr;
   hipStream_t s;
-  size_t slot = 0;
-  bool active = false;
-  ScopedTimer(int w, hipStream_t st) : which(w), s(st) {
-    if (!g_prof.on) return;
-    if (g_prof.used[w] == g_prof.start[w].size()) {
-      hipEvent_t a, b;
-      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
-      g_prof.start[w].push_back(a);
-      g_prof.stop[w].push_back(b);
+  ScopedTimer(int w, hipStream_t st, bool allowed = true) : s(st) {
+    if (!allowed) return;
+    hipEvent_t start = nullptr;
+    {
+      std::lock_guard<std::mutex> lock(g_state_mutex);
+      if (!g_prof.on) return;
+      if (g_prof.used[w] == g_prof.start[w].size()) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+        g_prof.start[w].push_back(a);
+        g_prof.stop[w].push_back(b);
+      }
+      const size_t slot = g_prof.used[w]++;
+      start = g_prof.start[w][slot];
+      stop = g_prof.stop[w][slot];
     }
-    slot = g_prof.used[w]++;
-    active = true;
-    (void)hipEventRecord(g_prof.start[w][slot], s);
+    (void)hipEventRecord(start, s);
   }
   ~ScopedTimer() {
-    if (active) (void)hipEventRecord(g_prof.stop[which][slot], s);
+    if (stop != nullptr) (void)hipEventRecord(stop, s);
   }
 };
 
@@ -118,6 +131,11 @@ struct Options {
   int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
 } g_opt;
 
+inline Options current_options() {
+  std::lock_guard<std::mutex> lock(g_state_mutex);
+  return g_opt;
+}
+
 constexpr size_t kLdsPerCu = 160 * 1024;
 
 // A kernel that wants more dynamic LDS than the default limit has to be told so once per device.
@@ -126,6 +144,7 @@ constexpr int kMaxDevices = 64;
 inline fopd_status allow_dynamic_lds(const void* kern, int bytes, bool* done) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FOPD_EHIP;
+  std::lock_guard<std::mutex> lock(g_state_mutex);
   if (done[dev]) return FOPD_OK;
   if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return FOPD_EHIP;
   done[dev] = true;
@@ -136,9 +155,9 @@ inline fopd_status allow_dynamic_lds(const void* kern, int bytes, bool* done) {
 
 fopd_status launch_k1(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                       const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
-                      int64_t* gather_idx, float* entropy, int32_t* flags, hipStream_t s) {
+                      int64_t* gather_idx, float* entropy, int32_t* flags, hipStream_t s, bool timed = true) {
   if (T == 0) return FOPD_OK;
-  ScopedTimer timer(0, s);
+  ScopedTimer timer(0, s, timed);
   const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
   const int v = static_cast<int>(V);
 #define FOPD_K1_ARGS logits, T, v, ld, token_ids, mask, logp, lse, gather_idx, entropy, flags
@@ -155,9 +174,9 @@ fopd_status launch_k1(const void* logits, fopd_dtype dt, int64_t T, int64_t V, i
 
 fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                       const int32_t* token_ids, const float* lse, const float* logp, const float* coef,
-                      hipStream_t s) {
+                      hipStream_t s, bool timed = true) {
   if (T == 0) return FOPD_OK;
-  ScopedTimer timer(1, s);
+  ScopedTimer timer(1, s, timed);
   const dim3 grid(static_cast<unsigned>(T)), block(kGradThreads);
   if (dt == FOPD_BF16)
     fopd_k4_grad<FOPD_BF16, kGradUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
@@ -168,163 +187,74 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
   return launched();
 }
 
+// Everything the two-passes-per-row kernel needs besides the matrices.
+struct RowPassArgs {
+  const int32_t* token_ids;
+  const uint8_t* mask;
+  const float* lb;
+  const float* lq;
+  const int64_t* cu;
+  const int32_t* n_train;
+  const int32_t* n_roll;
+  const int32_t* lag;
+  const float* fresh32;
+  int32_t B;
+  int64_t row_begin;
+  fopd_hparams hp;
+  float grad_scale;
+  float* logp;
+  double* row_loss;
+  int32_t* flags;
+};
+
 template <int DT, int NT>
-fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V, int64_t ld,
-                         const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
-                         const int64_t* cu, const int32_t* n_train, const int32_t* n_roll, const float* fresh32,
-                         int32_t B, int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp,
-                         double* row_loss, int32_t* flags, hipStream_t s) {
+fopd_status launch_k14_t(const void* logits, void* dlogits, int64_t T, int64_t V, int64_t ld, const RowPassArgs& a,
+                         int rows_per_cu, hipStream_t s) {
   auto kern = fopd_k14_fused<DT, NT, kUnroll>;
   // dynamic LDS is requested only to cap the workgroups resident per compute unit; the kernel is told
   // once per instantiation and device that it may be given up to a whole CU's worth
   static bool allowed[kMaxDevices] = {};
   if (allow_dynamic_lds(reinterpret_cast<const void*>(kern), static_cast<int>(kLdsPerCu - 1024), allowed) != FOPD_OK)
     return FOPD_EHIP;
-  const size_t pad = kLdsPerCu / static_cast<size_t>(g_opt.k14_rows_per_cu) - 1024;
-  kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
-                                                            token_ids, mask, lb, lq, cu, n_train, n_roll, fresh32, B,
-                                                            row_begin, hp, grad_scale, logp, row_loss, flags);
+  const size_t pad = kLdsPerCu / static_cast<size_t>(rows_per_cu) - 1024;
+  kern<<<dim3(static_cast<unsigned>(T)), dim3(NT), pad, s>>>(logits, dlogits, T, static_cast<int>(V), ld, a.token_ids,
+                                                            a.mask, a.lb, a.lq, a.cu, a.n_train, a.n_roll, a.lag,
+                                                            a.fresh32, a.B, a.row_begin, a.hp, a.grad_scale, a.logp,
+                                                            a.row_loss, a.flags);
   return launched();
 }
 
 fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
-                       const int32_t* token_ids, const uint8_t* mask, const float* lb, const float* lq,
-                       const int64_t* cu, const int32_t* n_train, const int32_t* n_roll, const float* fresh32,
-                       int32_t B, int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp,
-                       double* row_loss, int32_t* flags, hipStream_t s) {
+                       const RowPassArgs& a, hipStream_t s, bool timed) {
   if (T == 0) return FOPD_OK;
-  ScopedTimer timer(2, s);
-#define FOPD_K14_CASE(DTV, NTV)                                                                             \
-  return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, token_ids, mask, lb, lq, cu, n_train, n_roll, fresh32, B, \
-                                row_begin, hp, grad_scale, logp, row_loss, flags, s)
+  const Options opt = current_options();
+  ScopedTimer timer(2, s, timed);
+#define FOPD_K14_CASE(DTV, NTV) return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, a, opt.k14_rows_per_cu, s)
   if (dt == FOPD_BF16) {
-    if (g_opt.k14_threads == 512) FOPD_K14_CASE(FOPD_BF16, 512);
-    if (g_opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_BF16, 1024);
+    if (opt.k14_threads == 512) FOPD_K14_CASE(FOPD_BF16, 512);
+    if (opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_BF16, 1024);
     FOPD_K14_CASE(FOPD_BF16, 256);
   }
-  if (g_opt.k14_threads == 512) FOPD_K14_CASE(FOPD_F32, 512);
-  if (g_opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_F32, 1024);
+  if (opt.k14_threads == 512) FOPD_K14_CASE(FOPD_F32, 512);
+  if (opt.k14_threads == 1024) FOPD_K14_CASE(FOPD_F32, 1024);
   FOPD_K14_CASE(FOPD_F32, 256);
 #undef FOPD_K14_CASE
 }
 
-}  // namespace
-
-extern "C" {
-
-const char* fopd_status_string(int status) {
-  switch (status) {
-    case FOPD_OK: return "ok";
-    case FOPD_EINVAL: return "invalid argument (NULL pointer, negative coefficient or inconsistent optional inputs)";
-    case FOPD_ESHAPE: return "invalid shape (T, V, B, ld)";
-    case FOPD_EALIGN: return "matrix base or row pitch is not 16-byte aligned";
-    case FOPD_EDTYPE: return "unsupported element type";
-    case FOPD_EWORKSPACE: return "workspace missing, misaligned or too small";
-    case FOPD_ETOKEN_RANGE: return "token id outside [0, V) (row treated as masked)";
-    case FOPD_ESEGMENTS: return "sequence lengths negative or not covering the rows of the call";
-    case FOPD_ELAG: return "negative lag";
-    case FOPD_EHIP: return "HIP runtime or launch failure";
-    default: return "unknown status";
-  }
-}
-
-size_t fopd_workspace_bytes(int64_t T, int32_t B) { return Workspace(T, B).total; }
-
-fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
-  if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < 256) return FOPD_EWORKSPACE;
-  fopd_clear_flags<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t*>(workspace));
-  return launched();
-}
-
-fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host) {
-  if (workspace == nullptr) return FOPD_EWORKSPACE;
-  int32_t f = 0;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (hipMemcpyAsync(&f, workspace, sizeof(f), hipMemcpyDeviceToHost, s) != hipSuccess) return FOPD_EHIP;
-  if (hipStreamSynchronize(s) != hipSuccess) return FOPD_EHIP;
-  if (flags_host != nullptr) *flags_host = f;
-  if (f & kFlagToken) return FOPD_ETOKEN_RANGE;
-  if (f & kFlagSegments) return FOPD_ESEGMENTS;
-  if (f & kFlagLag) return FOPD_ELAG;
-  return FOPD_OK;
-}
-
-fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
-                                const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
-                                int64_t* gather_idx, float* entropy, void* workspace, size_t workspace_bytes,
-                                void* stream) {
-  fopd_status st = check_matrix(logits, dt, T, V, ld);
-  if (st != FOPD_OK) return st;
-  if (token_ids == nullptr || logp == nullptr || lse == nullptr) return FOPD_EINVAL;
-  st = check_workspace(workspace, workspace_bytes, T, 0);
-  if (st != FOPD_OK) return st;
-  Workspace w(T, 0);
-  return launch_k1(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, entropy,
-                   at<int32_t>(workspace, w.flags), static_cast<hipStream_t>(stream));
-}
-
-fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
-                                 const float* teacher_logp, const float* teacher_logp_stale, const uint8_t* mask,
-                                 const int32_t* seq_lens, const int32_t* lag, int64_t T, int32_t B,
-                                 fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, int32_t* n_roll,
-                                 float* D_roll, float* D_sup, float* ell, float* cover, float* cover_roll,
-                                 float* freshness, float* agg, void* workspace, size_t workspace_bytes,
-                                 void* stream) {
-  if (T < 0 || B <= 0) return FOPD_ESHAPE;
-  if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || teacher_logp == nullptr ||
-      seq_lens == nullptr || lag == nullptr || freshness == nullptr)
-    return FOPD_EINVAL;
-  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
-  fopd_status st = check_workspace(workspace, workspace_bytes, T, B);
-  if (st != FOPD_OK) return st;
-  Workspace w(T, B);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t* flags = at<int32_t>(workspace, w.flags);
-  int64_t* cu = (cu_seqlens != nullptr) ? cu_seqlens : at<int64_t>(workspace, w.cu);
-  int32_t* nws = at<int32_t>(workspace, w.n_train);
-  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
-  double* f64 = at<double>(workspace, w.fresh64);
-
-  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
-  if ((st = launched()) != FOPD_OK) return st;
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, nullptr, teacher_logp, teacher_logp_stale, mask,
-                                               cu, lag, T, hp, n_train, n_roll, D_roll, D_sup, ell, cover,
-                                               cover_roll, freshness, f64, nws, nrws);
-  if ((st = launched()) != FOPD_OK) return st;
-  if (agg != nullptr) {
-    fopd_aggregate<<<1, kSegThreads, 0, s>>>(f64, nws, nrws, cu, B, agg);
-    if ((st = launched()) != FOPD_OK) return st;
-  }
-  return FOPD_OK;
-}
-
-fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
-                              const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
-                              const float* teacher_logp, const float* teacher_logp_stale,
-                              const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
-                              const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
-                              int64_t row_begin, const float* lse_in, const float* logp_in, float grad_scale,
-                              float* loss,
-                              float* freshness, float* weights, float* logp, void* dlogits,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-  fopd_status st = check_matrix(logits, dt, T, V, ld);
-  if (st != FOPD_OK) return st;
-  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
-  if (B <= 0 || row_begin < 0) return FOPD_ESHAPE;
-  if (token_ids == nullptr || behav_logp == nullptr || teacher_logp == nullptr || seq_lens == nullptr ||
-      lag == nullptr || loss == nullptr)
-    return FOPD_EINVAL;
-  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+// The body of fopd_loss_fwd_bwd once its arguments have been checked.  `timed` = false keeps the optional
+// timing events (whose creation allocates) out of the call.
+fopd_status loss_fwd_bwd_checked(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                 const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                                 const float* teacher_logp, const float* teacher_logp_stale,
+                                 const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                 const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                                 int64_t row_begin, const float* lse_in, const float* logp_in, float grad_scale,
+                                 float* loss, float* freshness, float* weights, float* logp, void* dlogits,
+                                 void* workspace, hipStream_t s, bool timed) {
   const bool scored = (freshness_in != nullptr);
   const bool have_lse = (lse_in != nullptr);
-  if (have_lse != (logp_in != nullptr)) return FOPD_EINVAL;
-  if (!scored && (have_lse || n_train_in != nullptr || row_begin != 0)) return FOPD_EINVAL;
-  if (n_roll_in != nullptr && n_train_in == nullptr) return FOPD_EINVAL;
-  if (scored && n_train_in == nullptr && row_begin != 0) return FOPD_EINVAL;
-  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
-
-  Workspace w(T, B);
-  hipStream_t s = static_cast<hipStream_t>(stream);
+  fopd_status st;
+  const Workspace w(T, B);
   int32_t* flags = at<int32_t>(workspace, w.flags);
   int64_t* cu = at<int64_t>(workspace, w.cu);
   int32_t* nws = at<int32_t>(workspace, w.n_train);
@@ -341,7 +271,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   if ((st = launched()) != FOPD_OK) return st;
 
   // Scores supplied, log-probs not: both passes over each row run in one kernel, and the second
-  // read of the row comes out of the Infinity Cache.
+  // read of the row comes out of the cache.
   if (scored && !have_lse) {
     const int32_t* n_use = n_train_in;
     const int32_t* nr_use = n_roll_in;                  // NULL: the two counts coincide
@@ -351,10 +281,10 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
       n_use = nws;
       nr_use = nrws;
     }
-    st = launch_k14(logits, dlogits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, cu, n_use, nr_use,
-                    freshness_in, B, row_begin, hp, grad_scale, logp, partials, flags, s);
-    if (st != FOPD_OK) return st;
-    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, T, n_use, nr_use, nullptr, freshness_in, B, hp.xi, loss,
+    const RowPassArgs a{token_ids, mask, behav_logp, teacher_logp, cu, n_use, nr_use, lag, freshness_in, B,
+                        row_begin, hp, grad_scale, logp, partials, flags};
+    if ((st = launch_k14(logits, dlogits, dt, T, V, ld, a, s, timed)) != FOPD_OK) return st;
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, T, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi, loss,
                                               weights, freshness);
     return launched();
   }
@@ -363,7 +293,7 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   const float* lse_use = lse_in;
   const float* logp_use = logp_in;
   if (!have_lse) {
-    st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s);
+    st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s, timed);
     if (st != FOPD_OK) return st;
     lse_use = lse_ws;
     logp_use = logp_ws;
@@ -389,21 +319,163 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
   const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
   if (T > 0) {
     fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_use, behav_logp, teacher_logp, mask, cu, n_use, nr_use, f64_use, freshness_in, T, B, row_begin, hp,
-        grad_scale, coef, partials);
+        logp_use, behav_logp, teacher_logp, mask, cu, n_use, nr_use, lag, f64_use, freshness_in, T, B, row_begin, hp,
+        grad_scale, coef, partials, flags);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, f64_use, freshness_in, B, hp.xi, loss,
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
                                             weights, freshness);
   if ((st = launched()) != FOPD_OK) return st;
 
-  return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s);
+  return launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, coef, s, timed);
 }
 
-static fopd_status rollout_kl_impl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
-                                   int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
-                                   float* roll_kl, float* logp, float* lse, float* dlse, float* logq,
-                                   void* workspace, size_t workspace_bytes, void* stream) {
+// Host-checkable conditions of fopd_loss_fwd_bwd other than the workspace.
+fopd_status loss_fwd_bwd_check_args(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                    const int32_t* token_ids, const float* behav_logp, const float* teacher_logp,
+                                    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                    const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                                    int64_t row_begin, const float* lse_in, const float* logp_in, const float* loss,
+                                    const void* dlogits) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0 || row_begin < 0) return FOPD_ESHAPE;
+  if (token_ids == nullptr || behav_logp == nullptr || teacher_logp == nullptr || seq_lens == nullptr ||
+      lag == nullptr || loss == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  const bool scored = (freshness_in != nullptr);
+  const bool have_lse = (lse_in != nullptr);
+  if (have_lse != (logp_in != nullptr)) return FOPD_EINVAL;
+  if (!scored && (have_lse || n_train_in != nullptr || row_begin != 0)) return FOPD_EINVAL;
+  if (n_roll_in != nullptr && n_train_in == nullptr) return FOPD_EINVAL;
+  if (scored && n_train_in == nullptr && row_begin != 0) return FOPD_EINVAL;
+  return FOPD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fopd_status_string(fopd_status status) {
+  switch (status) {
+    case FOPD_OK: return "ok";
+    case FOPD_EINVAL: return "invalid argument (NULL pointer, negative coefficient or inconsistent optional inputs)";
+    case FOPD_ESHAPE: return "invalid shape (T, V, B, ld)";
+    case FOPD_EALIGN: return "matrix base or row pitch is not 16-byte aligned";
+    case FOPD_EDTYPE: return "unsupported element type";
+    case FOPD_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case FOPD_ETOKEN_RANGE: return "token id outside [0, V) (row treated as masked)";
+    case FOPD_ESEGMENTS: return "sequence lengths negative or not covering the rows of the call";
+    case FOPD_ELAG: return "negative lag (sample treated as invalid)";
+    case FOPD_EHIP: return "HIP runtime or launch failure";
+    case FOPD_ESETS: return "mask names two different aligned sets but only one count array was given (rows dropped)";
+    case FOPD_ELIMIT: return "size beyond the fixed limits of the entry point";
+    default: return "unknown status";
+  }
+}
+
+size_t fopd_workspace_bytes(int64_t T, int32_t B) { return Workspace(T, B).total; }
+
+fopd_status fopd_workspace_init(void* workspace, size_t workspace_bytes, void* stream) {
+  if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < 256) return FOPD_EWORKSPACE;
+  fopd_clear_flags<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<int32_t*>(workspace));
+  return launched();
+}
+
+fopd_status fopd_workspace_status(const void* workspace, void* stream, int32_t* flags_host) {
+  if (workspace == nullptr) return FOPD_EWORKSPACE;
+  int32_t f = 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&f, workspace, sizeof(f), hipMemcpyDeviceToHost, s) != hipSuccess) return FOPD_EHIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return FOPD_EHIP;
+  if (flags_host != nullptr) *flags_host = f;
+  return fopd_flags_status(f);
+}
+
+fopd_status fopd_flags_status(int32_t flags) {
+  if (flags & kFlagToken) return FOPD_ETOKEN_RANGE;
+  if (flags & kFlagSegments) return FOPD_ESEGMENTS;
+  if (flags & kFlagLag) return FOPD_ELAG;
+  if (flags & kFlagSets) return FOPD_ESETS;
+  return FOPD_OK;
+}
+
+fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                const int32_t* token_ids, const uint8_t* mask, float* logp, float* lse,
+                                int64_t* gather_idx, float* entropy, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if (token_ids == nullptr || logp == nullptr || lse == nullptr) return FOPD_EINVAL;
+  st = check_workspace(workspace, workspace_bytes, T, 0);
+  if (st != FOPD_OK) return st;
+  Workspace w(T, 0);
+  return launch_k1(logits, dt, T, V, ld, token_ids, mask, logp, lse, gather_idx, entropy,
+                   at<int32_t>(workspace, w.flags), static_cast<hipStream_t>(stream));
+}
+
+fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, const float* roll_kl,
+                                 const float* token_loss, const float* teacher_logp,
+                                 const float* teacher_logp_stale, const uint8_t* mask,
+                                 const int32_t* seq_lens, const int32_t* lag, int64_t T, int32_t B,
+                                 fopd_hparams hp, int64_t* cu_seqlens, int32_t* n_train, int32_t* n_roll,
+                                 float* D_roll, float* D_sup, float* ell, float* cover, float* cover_roll,
+                                 float* freshness, float* agg, void* workspace, size_t workspace_bytes,
+                                 void* stream) {
+  if (T < 0 || B <= 0) return FOPD_ESHAPE;
+  if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || teacher_logp == nullptr ||
+      seq_lens == nullptr || lag == nullptr || freshness == nullptr)
+    return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  fopd_status st = check_workspace(workspace, workspace_bytes, T, B);
+  if (st != FOPD_OK) return st;
+  Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = (cu_seqlens != nullptr) ? cu_seqlens : at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
+  double* f64 = at<double>(workspace, w.fresh64);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, roll_kl, token_loss, teacher_logp, teacher_logp_stale,
+                                               mask, cu, lag, T, hp, n_train, n_roll, D_roll, D_sup, ell, cover,
+                                               cover_roll, freshness, f64, nws, nrws);
+  if ((st = launched()) != FOPD_OK) return st;
+  if (agg != nullptr) {
+    fopd_aggregate<<<1, kSegThreads, 0, s>>>(f64, nws, nrws, lag, cu, B, agg);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  return FOPD_OK;
+}
+
+fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                              const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                              const float* teacher_logp, const float* teacher_logp_stale,
+                              const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                              const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                              int64_t row_begin, const float* lse_in, const float* logp_in, float grad_scale,
+                              float* loss,
+                              float* freshness, float* weights, float* logp, void* dlogits,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  fopd_status st = loss_fwd_bwd_check_args(logits, dt, T, V, ld, token_ids, behav_logp, teacher_logp, seq_lens, lag, B,
+                                           hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in, loss,
+                                           dlogits);
+  if (st != FOPD_OK) return st;
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+  return loss_fwd_bwd_checked(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
+                              seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in,
+                              grad_scale, loss, freshness, weights, logp, dlogits, workspace,
+                              static_cast<hipStream_t>(stream), true);
+}
+
+fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
+                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
+                            float* roll_kl, float* logp, float* lse, float* dlse, float* logq, void* workspace,
+                            size_t workspace_bytes, void* stream) {
   fopd_status st = check_matrix(logits, dt, T, V, ld);
   if (st != FOPD_OK) return st;
   if ((st = check_matrix(logits_stale, dt, T, V, ld_stale)) != FOPD_OK) return st;
@@ -426,25 +498,42 @@ static fopd_status rollout_kl_impl(const void* logits, const void* logits_stale,
   return launched();
 }
 
-fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,
-                            int64_t ld, int64_t ld_stale, const int32_t* token_ids, const uint8_t* mask,
-                            float* roll_kl, float* logp, float* lse, float* dlse, void* workspace,
-                            size_t workspace_bytes, void* stream) {
-  return rollout_kl_impl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, roll_kl, logp, lse, dlse,
-                         nullptr, workspace, workspace_bytes, stream);
-}
-
-// Shared tail of the two-tensor variants: scores from the per-row values, coefficients, loss, gradient.
-static fopd_status two_tensor_tail(const void* logits, const void* second, void* dlogits, fopd_dtype dt, int64_t T,
+// The two-tensor variants share everything but the meaning of the second tensor.
+//   teacher = false  second = stale checkpoint's logits: token_kl is the rollout drift; lq comes from the caller
+//   teacher = true   second = teacher's logits: token_kl is the token loss; lq is read off the second tensor
+// Whole-sample call (freshness_in == NULL): offsets, the pass over both tensors, scores, coefficients, loss,
+// gradient.  Chunk call: the per-row results of fopd_rollout_kl and the scores of fopd_freshness_score come in,
+// and only coefficients, the chunk's share of the loss and the gradient rows are made.
+static fopd_status two_tensor_call(bool teacher, const void* logits, const void* second, fopd_dtype dt, int64_t T,
                                    int64_t V, int64_t ld, int64_t ld_second, const int32_t* token_ids,
-                                   const uint8_t* mask, const float* behav_logp, const float* roll_term,
-                                   const float* ell_term, const float* lq, const float* lq_stale,
-                                   const float* token_kl, const float* logp_ws, const float* lse_ws,
-                                   const float* dlse_ws, const int32_t* lag, int32_t B, fopd_hparams hp,
-                                   float grad_scale, bool anchor_is_kl, float* loss, float* freshness, float* weights,
-                                   void* workspace, hipStream_t s) {
-  Workspace w(T, B);
-  fopd_status st;
+                                   const uint8_t* mask, const float* behav_logp, const float* teacher_logp,
+                                   const float* teacher_logp_stale, const int32_t* seq_lens, const int32_t* lag,
+                                   int32_t B, fopd_hparams hp, const float* freshness_in, const int32_t* n_train_in,
+                                   const int32_t* n_roll_in, int64_t row_begin, const float* lse_in,
+                                   const float* logp_in, const float* dlse_in, const float* token_kl_in,
+                                   float grad_scale, float* loss, float* freshness, float* weights, float* logp,
+                                   float* token_kl, void* dlogits, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(second, dt, T, V, ld_second)) != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0 || row_begin < 0) return FOPD_ESHAPE;
+  if (token_ids == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr) return FOPD_EINVAL;
+  if (teacher ? (behav_logp == nullptr) : (teacher_logp == nullptr)) return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  if (dlogits == second) return FOPD_EINVAL;            // the second tensor is read by both passes
+  const bool chunk = (freshness_in != nullptr);
+  const bool all_in = n_train_in != nullptr && lse_in != nullptr && logp_in != nullptr && dlse_in != nullptr &&
+                      token_kl_in != nullptr;
+  const bool none_in = n_train_in == nullptr && n_roll_in == nullptr && lse_in == nullptr && logp_in == nullptr &&
+                       dlse_in == nullptr && token_kl_in == nullptr && row_begin == 0;
+  if (chunk ? !all_in : !none_in) return FOPD_EINVAL;
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+
+  const Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
   int64_t* cu = at<int64_t>(workspace, w.cu);
   int32_t* nws = at<int32_t>(workspace, w.n_train);
   int32_t* nrws = at<int32_t>(workspace, w.n_roll);
@@ -452,30 +541,71 @@ static fopd_status two_tensor_tail(const void* logits, const void* second, void*
   float* c1 = at<float>(workspace, w.coef);
   float* c2 = at<float>(workspace, w.coef2);
   double* partials = at<double>(workspace, w.partials);
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, roll_term, ell_term, lq, lq_stale, mask, cu, lag, T,
-                                               hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                               f64, nws, nrws);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, chunk ? -1 : T, row_begin + T, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
+
+  const float* lse_use = lse_in;
+  const float* logp_use = logp_in;
+  const float* dlse_use = dlse_in;
+  const float* kl_use = token_kl_in;
+  const int32_t* n_use = n_train_in;
+  const int32_t* nr_use = (n_roll_in != nullptr) ? n_roll_in : n_train_in;
+  const double* f64_use = nullptr;
+  const float* lq_use = teacher_logp;
+  if (!chunk) {
+    float* lse_ws = at<float>(workspace, w.lse);
+    float* dlse_ws = at<float>(workspace, w.dlse);
+    float* logq_ws = at<float>(workspace, w.logq);
+    float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+    float* kl_ws = (token_kl != nullptr) ? token_kl : at<float>(workspace, w.kl);
+    st = fopd_rollout_kl(logits, second, dt, T, V, ld, ld_second, token_ids, mask, kl_ws, logp_ws, lse_ws, dlse_ws,
+                         teacher ? logq_ws : nullptr, workspace, workspace_bytes, stream);
+    if (st != FOPD_OK) return st;
+    if (teacher) lq_use = logq_ws;      // the teacher's log-prob of the sampled token, for D^sup
+    // stale tensor: drift = the full KL, token loss = sampled form; teacher tensor: the other way round
+    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, teacher ? nullptr : kl_ws,
+                                                 teacher ? kl_ws : nullptr, lq_use, teacher_logp_stale, mask, cu, lag,
+                                                 T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                                 nullptr, f64, nws, nrws);
+    if ((st = launched()) != FOPD_OK) return st;
+    lse_use = lse_ws;
+    logp_use = logp_ws;
+    dlse_use = dlse_ws;
+    kl_use = kl_ws;
+    n_use = nws;
+    nr_use = nrws;
+    f64_use = f64;
+  } else {
+    if (logp != nullptr && logp != logp_in && T > 0 &&
+        hipMemcpyAsync(logp, logp_in, static_cast<size_t>(T) * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess)
+      return FOPD_EHIP;
+    if (token_kl != nullptr && token_kl != token_kl_in && T > 0 &&
+        hipMemcpyAsync(token_kl, token_kl_in, static_cast<size_t>(T) * sizeof(float), hipMemcpyDeviceToDevice, s) !=
+            hipSuccess)
+      return FOPD_EHIP;
+  }
+
   const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
   if (T > 0) {
     fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_ws, token_kl, lq, behav_logp, mask, cu, nws, nrws, f64, T, B, hp, grad_scale, anchor_is_kl, c1, c2,
-        partials);
+        logp_use, kl_use, lq_use, behav_logp, mask, cu, n_use, nr_use, lag, f64_use, freshness_in, T, B, row_begin, hp,
+        grad_scale, !teacher, c1, c2, partials);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, nrws, f64, nullptr, B, hp.xi, loss, weights,
-                                            freshness);
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
+                                            weights, freshness);
   if ((st = launched()) != FOPD_OK) return st;
   if (T == 0) return FOPD_OK;
   ScopedTimer timer(1, s);
   const dim3 grid(static_cast<unsigned>(T)), block(kStreamThreads);
   if (dt == FOPD_BF16)
     fopd_k6_grad_kl<FOPD_BF16, kUnroll><<<grid, block, 0, s>>>(logits, second, dlogits, T, static_cast<int>(V), ld,
-                                                               ld_second, token_ids, lse_ws, dlse_ws, token_kl, logp_ws,
+                                                               ld_second, token_ids, lse_use, dlse_use, kl_use, logp_use,
                                                                c1, c2);
   else
     fopd_k6_grad_kl<FOPD_F32, kUnroll><<<grid, block, 0, s>>>(logits, second, dlogits, T, static_cast<int>(V), ld,
-                                                              ld_second, token_ids, lse_ws, dlse_ws, token_kl, logp_ws,
+                                                              ld_second, token_ids, lse_use, dlse_use, kl_use, logp_use,
                                                               c1, c2);
   return launched();
 }
@@ -484,77 +614,32 @@ fopd_status fopd_loss_fwd_bwd_full_kl(const void* logits, const void* logits_sta
                                       int64_t V, int64_t ld, int64_t ld_stale, const int32_t* token_ids,
                                       const uint8_t* mask, const float* teacher_logp,
                                       const float* teacher_logp_stale, const int32_t* seq_lens, const int32_t* lag,
-                                      int32_t B, fopd_hparams hp, float grad_scale, float* loss, float* freshness,
+                                      int32_t B, fopd_hparams hp, const float* freshness_in,
+                                      const int32_t* n_train_in, const int32_t* n_roll_in, int64_t row_begin,
+                                      const float* lse_in, const float* logp_in, const float* dlse_in,
+                                      const float* roll_kl_in, float grad_scale, float* loss, float* freshness,
                                       float* weights, float* logp, float* roll_kl, void* dlogits, void* workspace,
                                       size_t workspace_bytes, void* stream) {
-  fopd_status st = check_matrix(logits, dt, T, V, ld);
-  if (st != FOPD_OK) return st;
-  if ((st = check_matrix(logits_stale, dt, T, V, ld_stale)) != FOPD_OK) return st;
-  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
-  if (B <= 0) return FOPD_ESHAPE;
-  if (token_ids == nullptr || teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr)
-    return FOPD_EINVAL;
-  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
-  if (dlogits == logits_stale) return FOPD_EINVAL;      // the stale logits are read by both passes
-  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
-
-  Workspace w(T, B);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t* flags = at<int32_t>(workspace, w.flags);
-  int64_t* cu = at<int64_t>(workspace, w.cu);
-  float* lse_ws = at<float>(workspace, w.lse);
-  float* dlse_ws = at<float>(workspace, w.dlse);
-  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
-  float* kl_ws = (roll_kl != nullptr) ? roll_kl : at<float>(workspace, w.kl);
-
-  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
-  if ((st = launched()) != FOPD_OK) return st;
-  st = rollout_kl_impl(logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, kl_ws, logp_ws, lse_ws, dlse_ws,
-                       nullptr, workspace, workspace_bytes, stream);
-  if (st != FOPD_OK) return st;
-  return two_tensor_tail(logits, logits_stale, dlogits, dt, T, V, ld, ld_stale, token_ids, mask, nullptr, kl_ws, nullptr,
-                         teacher_logp, teacher_logp_stale, kl_ws, logp_ws, lse_ws, dlse_ws, lag, B, hp, grad_scale,
-                         true, loss, freshness, weights, workspace, s);
+  return two_tensor_call(false, logits, logits_stale, dt, T, V, ld, ld_stale, token_ids, mask, nullptr, teacher_logp,
+                         teacher_logp_stale, seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin,
+                         lse_in, logp_in, dlse_in, roll_kl_in, grad_scale, loss, freshness, weights, logp, roll_kl,
+                         dlogits, workspace, workspace_bytes, stream);
 }
 
 fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teacher_logits, fopd_dtype dt, int64_t T,
                                            int64_t V, int64_t ld, int64_t ld_teacher, const int32_t* token_ids,
                                            const uint8_t* mask, const float* behav_logp,
                                            const float* teacher_logp_stale, const int32_t* seq_lens,
-                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
-                                           float* loss, float* freshness, float* weights, float* logp, float* token_kl,
-                                           void* dlogits, void* workspace, size_t workspace_bytes, void* stream) {
-  fopd_status st = check_matrix(logits, dt, T, V, ld);
-  if (st != FOPD_OK) return st;
-  if ((st = check_matrix(teacher_logits, dt, T, V, ld_teacher)) != FOPD_OK) return st;
-  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
-  if (B <= 0) return FOPD_ESHAPE;
-  if (token_ids == nullptr || behav_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr)
-    return FOPD_EINVAL;
-  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
-  if (dlogits == teacher_logits) return FOPD_EINVAL;     // the teacher logits are read by both passes
-  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
-
-  Workspace w(T, B);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  int32_t* flags = at<int32_t>(workspace, w.flags);
-  int64_t* cu = at<int64_t>(workspace, w.cu);
-  float* lse_ws = at<float>(workspace, w.lse);
-  float* dlse_ws = at<float>(workspace, w.dlse);
-  float* logq_ws = at<float>(workspace, w.logq);
-  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
-  float* kl_ws = (token_kl != nullptr) ? token_kl : at<float>(workspace, w.kl);
-
-  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
-  if ((st = launched()) != FOPD_OK) return st;
-  st = rollout_kl_impl(logits, teacher_logits, dt, T, V, ld, ld_teacher, token_ids, mask, kl_ws, logp_ws, lse_ws, dlse_ws,
-                       logq_ws, workspace, workspace_bytes, stream);
-  if (st != FOPD_OK) return st;
-  // drift from the sampled estimator (behav_logp), token loss from the full KL, teacher log-prob of the
-  // sampled token (for D^sup) from the teacher logits themselves
-  return two_tensor_tail(logits, teacher_logits, dlogits, dt, T, V, ld, ld_teacher, token_ids, mask, behav_logp, nullptr,
-                         kl_ws, logq_ws, teacher_logp_stale, kl_ws, logp_ws, lse_ws, dlse_ws, lag, B, hp, grad_scale,
-                         false, loss, freshness, weights, workspace, s);
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                           const int32_t* n_train_in, const int32_t* n_roll_in, int64_t row_begin,
+                                           const float* lse_in, const float* logp_in, const float* dlse_in,
+                                           const float* token_kl_in, float grad_scale, float* loss, float* freshness,
+                                           float* weights, float* logp, float* token_kl, void* dlogits,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+  return two_tensor_call(true, logits, teacher_logits, dt, T, V, ld, ld_teacher, token_ids, mask, behav_logp, nullptr,
+                         teacher_logp_stale, seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin,
+                         lse_in, logp_in, dlse_in, token_kl_in, grad_scale, loss, freshness, weights, logp, token_kl,
+                         dlogits, workspace, workspace_bytes, stream);
 }
 
 int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,
@@ -630,6 +715,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
 fopd_status fopd_set_option(const char* name, int value) {
   if (name == nullptr) return FOPD_EINVAL;
   const std::string key(name);
+  std::lock_guard<std::mutex> lock(g_state_mutex);
   if (key == "k14_threads") {
     if (value != 256 && value != 512 && value != 1024) return FOPD_EINVAL;
     g_opt.k14_threads = value;
@@ -644,26 +730,34 @@ fopd_status fopd_set_option(const char* name, int value) {
 }
 
 fopd_status fopd_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_state_mutex);
   g_prof.on = (on != 0);
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_reset(void) {
+  std::lock_guard<std::mutex> lock(g_state_mutex);
   g_prof.used[0] = g_prof.used[1] = g_prof.used[2] = g_prof.used[3] = 0;
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host) {
   if (which < 0 || which > 3 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
+  std::vector<hipEvent_t> start, stop;
+  {
+    std::lock_guard<std::mutex> lock(g_state_mutex);
+    start.assign(g_prof.start[which].begin(), g_prof.start[which].begin() + g_prof.used[which]);
+    stop.assign(g_prof.stop[which].begin(), g_prof.stop[which].begin() + g_prof.used[which]);
+  }
   double tot = 0.0;
-  for (size_t i = 0; i < g_prof.used[which]; ++i) {
-    if (hipEventSynchronize(g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;
+  for (size_t i = 0; i < start.size(); ++i) {
+    if (hipEventSynchronize(stop[i]) != hipSuccess) return FOPD_EHIP;
     float ms = 0.f;
-    if (hipEventElapsedTime(&ms, g_prof.start[which][i], g_prof.stop[which][i]) != hipSuccess) return FOPD_EHIP;
+    if (hipEventElapsedTime(&ms, start[i], stop[i]) != hipSuccess) return FOPD_EHIP;
     tot += ms;
   }
   *total_ms_host = tot;
-  *launches_host = static_cast<int64_t>(g_prof.used[which]);
+  *launches_host = static_cast<int64_t>(start.size());
   return FOPD_OK;
 }
 

@@ -35,7 +35,7 @@ constexpr int kGradUnroll = 2;        // A/B-tested in one process; all within 1
 constexpr int kUnroll = 4;            // 16-byte loads in flight per lane and loop trip
 constexpr int kScanThreads = 1024;
 constexpr int kSegThreads = 512;
-enum : int32_t { kFlagToken = 1, kFlagSegments = 2, kFlagLag = 4 };
+enum : int32_t { kFlagToken = 1, kFlagSegments = 2, kFlagLag = 4, kFlagSets = 8 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -327,12 +327,15 @@ __device__ __forceinline__ void block_lse_finish(const LaneState& st, const floa
     //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
     //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
     const double zyL = static_cast<double>(*zy_in) * static_cast<double>(kLog2e);
-    const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
+    const double others = static_cast<double>(RR) + log2(static_cast<double>(SS));   // log2 sum_{v != y}
+    const double a2 = others - zyL;
     const double q = exp2(-fabs(a2));                  // 2^-|a2|, in (0, 1]
     const double l1q = log1p(q) * (1.0 / kLn2);        // log2(1 + 2^-|a2|)
     const double sp = (a2 > 0.0 ? a2 : 0.0) + l1q;
     lp_out = -sp * kLn2;
-    lse_out = (zyL + sp) * kLn2;
+    // the larger of the two parts plus the correction: stays finite when z_y = -inf (lp = -inf) or when
+    // every other logit is -inf (lp = 0)
+    lse_out = ((a2 > 0.0 ? others : zyL) + l1q) * kLn2;
     if (ENT) {
       // H = h(p_y) + (1 - p_y) * H(softmax over the other tokens): the binary entropy of
       // {y, not y} plus the conditional entropy, each a sum of non-negative terms.
@@ -435,9 +438,15 @@ __device__ __forceinline__ bool in_roll_set(const uint8_t* mask, int64_t t) {
   return m != 0 && m != 3;
 }
 
-// ReLU(f - xi); 0 for an invalid sample (either aligned set empty), whatever xi is.
-__device__ __forceinline__ double weight_of(double f, int32_t n_sup, int32_t n_roll, float xi) {
-  if (n_sup <= 0 || n_roll <= 0) return 0.0;
+// A row that is in exactly one of the two sets (mask byte 2 or 3).
+__device__ __forceinline__ bool in_one_set_only(const uint8_t* mask, int64_t t) {
+  return mask != nullptr && (mask[t] == 2 || mask[t] == 3);
+}
+
+// ReLU(f - xi); 0 for an invalid sample (either aligned set empty, or a negative lag, which is also
+// flagged), whatever xi is.
+__device__ __forceinline__ double weight_of(double f, int32_t n_sup, int32_t n_roll, int32_t lag, float xi) {
+  if (n_sup <= 0 || n_roll <= 0 || lag < 0) return 0.0;
   const double w = f - static_cast<double>(xi);
   return w > 0.0 ? w : 0.0;
 }
@@ -555,8 +564,8 @@ template <int DT, int NT, int U>
 __global__ void __launch_bounds__(NT)
 fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
                const uint8_t* mask, const float* behav_logp, const float* teacher_logp, const int64_t* cu,
-               const int32_t* n_train, const int32_t* n_roll, const float* fresh32, int32_t B, int64_t row_begin,
-               fopd_hparams hp, float grad_scale, float* logp, double* row_loss, int32_t* flags) {
+               const int32_t* n_train, const int32_t* n_roll, const int32_t* lag, const float* fresh32, int32_t B,
+               int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss, int32_t* flags) {
   extern __shared__ char occupancy_pad[];      // sized by the host only to cap workgroups per CU
   __shared__ float sh_zy;
   __shared__ float sh_R[NT / 64];
@@ -571,6 +580,11 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
     if (tid == 0) atomicOr(flags, kFlagToken);
     live = false;
   }
+  // one count array for two different sets: the caller left out n_roll_in; the row is dropped and flagged
+  if (live && n_roll == nullptr && in_one_set_only(mask, t)) {
+    if (tid == 0) atomicOr(flags, kFlagSets);
+    live = false;
+  }
   const int64_t gt = row_begin + t;
   double w = 0.0;
   int32_t n = 0, nr = 0;
@@ -578,7 +592,7 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
     const int i = sample_of_row(cu, B, gt);
     n = n_train[i];
     nr = (n_roll != nullptr) ? n_roll[i] : n;
-    w = weight_of(static_cast<double>(fresh32[i]), n, nr, hp.xi);
+    w = weight_of(static_cast<double>(fresh32[i]), n, nr, lag[i], hp.xi);
   }
   if (!live || (w == 0.0 && logp == nullptr)) {   // nothing to learn from this row: no read at all
     if (tid == 0) {
@@ -621,49 +635,78 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 // "kl-diagnostics" as printed, KL(pi^t || pi^r) per row, from a second logits tensor z' (the
 // stale checkpoint replayed on the same prefixes).  With d_v = z_v - z'_v and p = softmax(z):
 //     lse' - lse = log E_p[e^-d],      KL = E_p[d] + log E_p[e^-d].
-// K5 accumulates, on z's running reference, S = sum e_v, W = sum e_v d_v and U = sum (e'_v - e_v)
-// with e'_v = 2^(z'_v log2e - ref): the small quantity E_p[e^-d - 1] = U / S is summed directly,
-// so KL does not come out as the difference of two independently rounded log-sum-exps.
+// Each tensor has its own running reference (its own maximum), so neither sum can overflow however far
+// apart the two rows are: S = sum e_v and W = sum e_v d_v on z's reference, S' = sum e'_v on z''s.
+// For close rows (the case the diagnostic is for) KL is far smaller than either log-sum-exp, so the lanes
+// also sum U = sum (e'_v 2^(ref' - ref) - e_v) directly: E_p[e^-d - 1] = U / S does not come out as the
+// difference of two independently rounded sums.  The finish uses U when every lane's two references stayed
+// within 2^+-100 of each other and |U / S| < 1/2, else lse - lse' from the two (reference, sum) pairs.
 // =========================================================================================
 
 struct LaneStateKl {
-  float r = -1.0e38f;
-  float rL = -1.0e38f * 1.4426950408889634f;
-  float s = 0.f, w = 0.f, u = 0.f;
+  float r = -1.0e38f, rL = -1.0e38f;      // z:  running maximum; reference = ceil(maximum * log2 e)
+  float rs = -1.0e38f, rsL = -1.0e38f;    // z': the same
+  float s = 0.f, w = 0.f, u = 0.f;                              // on z's reference
+  float ss = 0.f;                                               // on z''s reference
+  float c = 1.f;                                                // 2^(rsL - rL), or 0 once the lane is `far`
+  bool far = false;                                             // the references were more than 2^100 apart
 };
+
+constexpr float kKlRefGap = 100.f;
 
 template <int N>
 __device__ __forceinline__ void accumulate_kl(const float* x, const float* xs, LaneStateKl& st) {
-  float bm = x[0];
+  float bm = x[0], bs = xs[0];
 #pragma unroll
-  for (int i = 1; i < N; ++i) bm = fmaxf(bm, x[i]);
-  if (bm > st.r) {
-    const float nrL = bm * kLog2e;
-    const float scale = fast_exp2(st.rL - nrL);
-    st.s *= scale;
-    st.w *= scale;
-    st.u *= scale;
-    st.r = bm;
-    st.rL = nrL;
+  for (int i = 1; i < N; ++i) {
+    bm = fmaxf(bm, x[i]);
+    bs = fmaxf(bs, xs[i]);
   }
-  float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f, u0 = 0.f, u1 = 0.f;
+  if (bm > st.r || bs > st.rs) {                  // rare after the first few vectors
+    // references are whole numbers of log2 units: every rescale below is an exact power of two
+    if (bm > st.r) {
+      const float nrL = ceilf(bm * kLog2e);
+      const float scale = fast_exp2(st.rL - nrL);
+      st.s *= scale;
+      st.w *= scale;
+      st.u *= scale;
+      st.r = bm;
+      st.rL = nrL;
+    }
+    if (bs > st.rs) {
+      const float nrL = ceilf(bs * kLog2e);
+      st.ss *= fast_exp2(st.rsL - nrL);
+      st.rs = bs;
+      st.rsL = nrL;
+    }
+    // "seen": the lane has met a finite entry of that tensor.  One tensor seen and the other not (its
+    // entries were all -inf so far), or references too far apart for 2^gap: the row's finish will not use U.
+    const bool seen = st.r > -1.0e37f, seen_s = st.rs > -1.0e37f;
+    const float gap = st.rsL - st.rL;
+    if (seen != seen_s || (seen && !(fabsf(gap) <= kKlRefGap))) st.far = true;
+    st.c = st.far ? 0.f : fast_exp2(gap);
+  }
+  float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f, u0 = 0.f, u1 = 0.f, b0 = 0.f, b1 = 0.f;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     const float e = fast_exp2(fmaf(x[i], kLog2e, -st.rL));
-    const float es = fast_exp2(fmaf(xs[i], kLog2e, -st.rL));
+    const float es = fast_exp2(fmaf(xs[i], kLog2e, -st.rsL));
     // both -inf (an excluded vocabulary entry) must give d = 0, not NaN
     const float d = fmaxf(x[i], -1.0e30f) - fmaxf(xs[i], -1.0e30f);
     if (i & 1) {
       a1 += e;
+      b1 += es;
       w1 = fmaf(e, d, w1);
-      u1 += es - e;
+      u1 += fmaf(es, st.c, -e);
     } else {
       a0 += e;
+      b0 += es;
       w0 = fmaf(e, d, w0);
-      u0 += es - e;
+      u0 += fmaf(es, st.c, -e);
     }
   }
   st.s += a0 + a1;
+  st.ss += b0 + b1;
   st.w += w0 + w1;
   st.u += u0 + u1;
 }
@@ -695,6 +738,7 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
   }
   __shared__ float sh_zy, sh_zsy;
   __shared__ float sh_R[NT / 64], sh_S[NT / 64], sh_W[NT / 64], sh_U[NT / 64];
+  __shared__ float sh_Rs[NT / 64], sh_Ss[NT / 64], sh_F[NT / 64];
   const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
   const char* rows = static_cast<const char*>(logits_stale) + t * ld_stale * Elem<DT>::kBytes;
   const u32x4* rv = reinterpret_cast<const u32x4*>(row);
@@ -768,52 +812,70 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
       accumulate_kl<1>(&x1, &xs1, st);
     }
   }
-  const float Rw = wave_max(st.rL);
+  const float Rw = wave_max(st.rL), Rsw = wave_max(st.rsL);
   const float scale = fast_exp2(st.rL - Rw);
   const float Sw = wave_sum(st.s * scale), Ww = wave_sum(st.w * scale), Uw = wave_sum(st.u * scale);
+  const float Ssw = wave_sum(st.ss * fast_exp2(st.rsL - Rsw));
+  const float Fw = wave_max(st.far ? 1.f : 0.f);
   const int lane = tid & 63, wv = tid >> 6;
   if (lane == 0) {
     sh_R[wv] = Rw;
     sh_S[wv] = Sw;
     sh_W[wv] = Ww;
     sh_U[wv] = Uw;
+    sh_Rs[wv] = Rsw;
+    sh_Ss[wv] = Ssw;
+    sh_F[wv] = Fw;
   }
   __syncthreads();
   if (tid == 0) {
-    float RR = sh_R[0];
+    float RR = sh_R[0], RRs = sh_Rs[0], far = sh_F[0];
 #pragma unroll
-    for (int i = 1; i < NT / 64; ++i) RR = fmaxf(RR, sh_R[i]);
-    float SS = 0.f, WW = 0.f, UU = 0.f;
+    for (int i = 1; i < NT / 64; ++i) {
+      RR = fmaxf(RR, sh_R[i]);
+      RRs = fmaxf(RRs, sh_Rs[i]);
+      far = fmaxf(far, sh_F[i]);
+    }
+    float SS = 0.f, WW = 0.f, UU = 0.f, SSs = 0.f;
 #pragma unroll
     for (int i = 0; i < NT / 64; ++i) {
       const float sc = fast_exp2(sh_R[i] - RR);
       SS += sh_S[i] * sc;
       WW += sh_W[i] * sc;
       UU += sh_U[i] * sc;
+      SSs += sh_Ss[i] * fast_exp2(sh_Rs[i] - RRs);
     }
+    const double L2e = static_cast<double>(kLog2e);
     const double zy = sh_zy, zsy = sh_zsy;
-    const double zyL = zy * static_cast<double>(kLog2e);
-    const double a2 = (static_cast<double>(RR) + log2(static_cast<double>(SS))) - zyL;
+    const double zyL = zy * L2e, zsyL = zsy * L2e;
+    // current tensor: log-odds of "not y", lp, lse as in the single-tensor pass
+    const double others = static_cast<double>(RR) + log2(static_cast<double>(SS));
+    const double a2 = others - zyL;
     const double q = exp2(-fabs(a2));
-    const double sp = (a2 > 0.0 ? a2 : 0.0) + log1p(q) * (1.0 / kLn2);
-    const double lp = -sp * kLn2;
+    const double l1q = log1p(q) * (1.0 / kLn2);
+    const double lp = -((a2 > 0.0 ? a2 : 0.0) + l1q) * kLn2;
+    const double ls = ((a2 > 0.0 ? others : zyL) + l1q) * kLn2;
     const double p_not = (a2 > 0.0) ? 1.0 / (1.0 + q) : q / (1.0 + q);
     const double p_y = (a2 > 0.0) ? q / (1.0 + q) : 1.0 / (1.0 + q);
-    // E_p[d] and E_p[e^-d - 1]: the other tokens through the lane sums, the sampled token directly
-    double ed = 0.0, eu = 0.0;
-    if (SS > 0.f) {
-      ed = p_not * (static_cast<double>(WW) / static_cast<double>(SS));
-      eu = p_not * (static_cast<double>(UU) / static_cast<double>(SS));
+    // second tensor: its own log-sum-exp from its own (reference, sum) pair
+    const double others_s = static_cast<double>(RRs) + log2(static_cast<double>(SSs));
+    const double a2s = others_s - zsyL;
+    const double ls_s = ((a2s > 0.0 ? others_s : zsyL) + log1p(exp2(-fabs(a2s))) * (1.0 / kLn2)) * kLn2;
+    // E_p[d]: the other tokens through the lane sums, the sampled token directly
+    double ed = 0.0;
+    if (SS > 0.f) ed = p_not * (static_cast<double>(WW) / static_cast<double>(SS));
+    const double dy = fmax(zy, -1.0e30) - fmax(zsy, -1.0e30);
+    if (p_y > 0.0) ed += p_y * dy;
+    // lse - lse': from E_p[e^-d - 1] summed directly when the rows are close, else from the two pairs
+    double dl = ls - ls_s;
+    if (far == 0.f && SS > 0.f) {
+      const double eu = p_not * (static_cast<double>(UU) / static_cast<double>(SS)) + p_y * expm1(-dy);
+      if (fabs(eu) < 0.5) dl = -log1p(eu);
     }
-    const double dy = zy - zsy;
-    ed += p_y * dy;
-    eu += p_y * expm1(-dy);
-    const double dl = -log1p(eu);                 // lse - lse'
     double kl = ed - dl;
     if (kl < 0.0) kl = 0.0;                       // rounding noise of identical rows
     roll_kl[t] = static_cast<float>(kl);
     logp[t] = static_cast<float>(lp);
-    const double ls = (zyL + sp) * kLn2;
     lse[t] = static_cast<float>(ls);
     dlse[t] = static_cast<float>(dl);
     if (logq != nullptr) logq[t] = static_cast<float>(zsy - (ls - dl));   // log softmax(z')[y]
@@ -828,18 +890,21 @@ fopd_k5_kl(const void* logits, const void* logits_stale, int64_t T, int V, int64
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_coef_loss_kl(const float* logp, const float* token_kl, const float* teacher_logp, const float* behav_logp,
                   const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const int32_t* n_roll,
-                  const double* fresh64, int64_t T, int32_t B, fopd_hparams hp, float grad_scale, bool anchor_is_kl,
-                  float* c1, float* c2, double* partials) {
+                  const int32_t* lag, const double* fresh64, const float* fresh32, int64_t T, int32_t B,
+                  int64_t row_begin, fopd_hparams hp, float grad_scale, bool anchor_is_kl, float* c1, float* c2,
+                  double* partials) {
   __shared__ double sh[kStreamThreads / 64];
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
   double lt = 0.0;
   if (t < T) {
     float a = 0.f, b = 0.f;
     const bool sup = in_sup_set(mask, t), roll = in_roll_set(mask, t);
-    if ((sup || roll) && t < cu[B]) {
-      const int i = sample_of_row(cu, B, t);
+    const int64_t gt = row_begin + t;
+    if ((sup || roll) && gt < cu[B]) {
+      const int i = sample_of_row(cu, B, gt);
       const int32_t n = n_train[i], nr = n_roll[i];
-      const double w = weight_of(fresh64[i], n, nr, hp.xi);
+      const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
+      const double w = weight_of(f, n, nr, lag[i], hp.xi);
       if (w > 0.0) {
         const double lp = logp[t], lam = hp.lambda, kl = token_kl[t];
         const double wb = w / static_cast<double>(B);
@@ -1065,7 +1130,7 @@ fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll
     const int32_t ns = static_cast<int32_t>(tns), nr = static_cast<int32_t>(tnr);
     const int64_t H = cu[i + 1] - a;
     double dr = 0.0, ds = 0.0, el = 0.0, cv = 0.0, cvr = 0.0, f = 0.0;
-    if (ns > 0 && nr > 0) {
+    if (ns > 0 && nr > 0 && lag[i] >= 0) {       // a negative lag is flagged by the scan; the sample is invalid
       dr = tr / tnr;
       ds = ts / tns;
       el = tl / tns;
@@ -1093,14 +1158,14 @@ fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll
 // mean_i f_i, mean_i |U_i^roll| / H_i and mean_i |U_i^sup| / H_i over all B samples (one workgroup);
 // an invalid sample adds 0 to all three (Algorithm 1).
 __global__ void __launch_bounds__(kSegThreads)
-fopd_aggregate(const double* fresh64, const int32_t* n_train, const int32_t* n_roll, const int64_t* cu, int32_t B,
-               float* agg) {
+fopd_aggregate(const double* fresh64, const int32_t* n_train, const int32_t* n_roll, const int32_t* lag,
+               const int64_t* cu, int32_t B, float* agg) {
   __shared__ double sh[kSegThreads / 64];
   double sf = 0.0, sc = 0.0, scr = 0.0;
   for (int i = threadIdx.x; i < B; i += kSegThreads) {
     sf += fresh64[i];
     const int64_t H = cu[i + 1] - cu[i];
-    if (n_train[i] > 0 && n_roll[i] > 0) {
+    if (n_train[i] > 0 && n_roll[i] > 0 && lag[i] >= 0) {
       sc += static_cast<double>(n_train[i]) / static_cast<double>(H);
       scr += static_cast<double>(n_roll[i]) / static_cast<double>(H);
     }
@@ -1119,8 +1184,8 @@ fopd_aggregate(const double* fresh64, const int32_t* n_train, const int32_t* n_r
 __global__ void __launch_bounds__(kStreamThreads)
 fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_logp,
                const uint8_t* mask, const int64_t* cu, const int32_t* n_train, const int32_t* n_roll,
-               const double* fresh64, const float* fresh32, int64_t T, int32_t B, int64_t row_begin,
-               fopd_hparams hp, float grad_scale, float* coef, double* partials) {
+               const int32_t* lag, const double* fresh64, const float* fresh32, int64_t T, int32_t B,
+               int64_t row_begin, fopd_hparams hp, float grad_scale, float* coef, double* partials, int32_t* flags) {
   __shared__ double sh[kStreamThreads / 64];
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
   double lt = 0.0;
@@ -1128,12 +1193,14 @@ fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_
     float c = 0.f;
     const int64_t gt = row_begin + t;
     const bool sup = in_sup_set(mask, t), roll = in_roll_set(mask, t);
-    if ((sup || roll) && gt < cu[B]) {
+    if (n_roll == nullptr && in_one_set_only(mask, t)) {
+      atomicOr(flags, kFlagSets);      // one count array for two different sets: the row is dropped
+    } else if ((sup || roll) && gt < cu[B]) {
       const int i = sample_of_row(cu, B, gt);
       const int32_t n = n_train[i];
       const int32_t nr = (n_roll != nullptr) ? n_roll[i] : n;
       const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
-      const double w = weight_of(f, n, nr, hp.xi);
+      const double w = weight_of(f, n, nr, lag[i], hp.xi);
       if (w > 0.0)
         c = coef_and_loss(logp[t], behav_logp[t], teacher_logp[t], w, n, nr, sup, roll, B, hp, grad_scale, &lt);
     }
@@ -1146,7 +1213,7 @@ fopd_coef_loss(const float* logp, const float* behav_logp, const float* teacher_
 // Sums the loss partials in a fixed order; writes the weights and the freshness copy.
 __global__ void __launch_bounds__(kSegThreads)
 fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, const int32_t* n_roll,
-                const double* fresh64, const float* fresh32, int32_t B, float xi, float* loss, float* weights,
+                const int32_t* lag, const double* fresh64, const float* fresh32, int32_t B, float xi, float* loss, float* weights,
                 float* freshness) {
   __shared__ double sh[kSegThreads / 64];
   // eight independent partial sums per lane keep eight loads in flight (nparts is T in the
@@ -1164,7 +1231,8 @@ fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, 
   for (int i = threadIdx.x; i < B; i += kSegThreads) {
     const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
     if (weights != nullptr)
-      weights[i] = static_cast<float>(weight_of(f, n_train[i], (n_roll != nullptr) ? n_roll[i] : n_train[i], xi));
+      weights[i] =
+          static_cast<float>(weight_of(f, n_train[i], (n_roll != nullptr) ? n_roll[i] : n_train[i], lag[i], xi));
     if (freshness != nullptr) freshness[i] = static_cast<float>(f);
   }
 }

@@ -53,7 +53,7 @@ class LossPass:
 
     def freshness_score(self, w, hp=DEFAULT_HPARAMS):
         stale = w["teacher_logp_stale"]
-        fb.fopd_freshness_score(self.logp, w["behav_logp"], None, w["teacher_logp"], stale, w["mask"],
+        fb.fopd_freshness_score(self.logp, w["behav_logp"], None, None, w["teacher_logp"], stale, w["mask"],
                                 w["seq_lens"], w["lag"], self.T, self.B, hp, self.cu_seqlens, self.n_train,
                                 self.n_roll, self.D_roll, self.D_sup, self.ell, self.cover, self.cover_roll,
                                 self.freshness, self.agg, self.workspace)

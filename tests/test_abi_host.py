@@ -103,7 +103,7 @@ def test_freshness_rejects_bad_arguments_before_launch():
     lib = fb.load_library()
 
     def call(logp=4096, seq=4096, lag=4096, f=4096, T=8, B=2, hp=fb.Hparams(1, 1, 0, 0), ws=4096, wsb=1 << 20):
-        return lib.fopd_freshness_score(P(logp), P(4096), None, P(4096), None, None, P(seq), P(lag), T, B, hp,
+        return lib.fopd_freshness_score(P(logp), P(4096), None, None, P(4096), None, None, P(seq), P(lag), T, B, hp,
                                         None, None, None, None, None, None, None, None, P(f), None, P(ws), wsb, None)
 
     assert call(logp=None) == 1

@@ -1,0 +1,212 @@
+"""GPU parity of the two-tensor calls beyond the whole-sample cases of test_gpu_parity.py: a second tensor
+drawn independently of the first (rows arbitrarily far apart), and the chunked long-horizon flow of
+fopd_loss_fwd_bwd_full_kl / fopd_loss_fwd_bwd_full_teacher (Eq. "kl-diagnostics" line 1 as printed, on
+workloads where three [T, V] tensors do not fit and chunks cut samples)."""
+
+import numpy as np
+import pytest
+import torch
+
+from harness import workloads as wl
+from oracle import fopd_oracle as orc
+from paper_2605_17862_amd import binding as fb
+from paper_2605_17862_amd.loss_pass import LossPass
+from parity_util import assert_close, check_grad_rows_full_kl, np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print("[gpu-two-tensor] " + msg, flush=True)
+
+
+def _pass_for(w, alloc_dlogits=True):
+    return LossPass(w["T"], w["V"], w["B"], w["dtype"], ld=w["ld"], device=DEV, alloc_dlogits=alloc_dlogits)
+
+
+def _sync_ok(lp):
+    st, flags = lp.status()
+    assert st == 0 and flags == 0, "device flags %d (%s)" % (flags, fb.fopd_status_string(st))
+
+
+@pytest.mark.parametrize("V,scale", [(32768, 2.0), (5003, 40.0)])
+def test_rollout_kl_with_an_independent_heavy_tailed_second_tensor(V, scale):
+    """The second tensor is drawn on its own (Student-t, 3 degrees of freedom, like the large-vocabulary
+    workload), so the two rows' maxima are tens to thousands of nats apart and the KL is large: each tensor
+    needs its own running reference.  Also rows with -inf entries on one side only, and identical rows."""
+    _say("independent second tensor, V=%d scale=%g" % (V, scale))
+    ld = (V + 7) // 8 * 8
+    a = wl.generate("largevocab", DEV, seed=41, B=2, len_lo=12, len_hi=12, V=V, ld=ld, sigma=scale, row_block=32)
+    b = wl.generate("largevocab", DEV, seed=42, B=2, len_lo=12, len_hi=12, V=V, ld=ld, sigma=scale, row_block=32)
+    T = a["T"]
+    z, zs = a["logits"].clone(), b["logits"].clone()
+    zs[3] = z[3]                                          # identical rows: KL exactly 0
+    z[4, 10:500] = float("-inf")                          # excluded entries on the current side only
+    zs[5, 600:900] = float("-inf")                        # ... on the second side only (KL = +inf unless p = 0 there)
+    z[5, 600:900] = float("-inf")
+    zs[5, 100:200] = float("-inf")
+    z[5, 100:200] = float("-inf")
+    y = a["token_ids"].clone()
+    y[4] = 5
+    y[5] = 7
+    lp = _pass_for(a, alloc_dlogits=False)
+    kl = torch.empty(T, device=DEV)
+    dlse = torch.empty(T, device=DEV)
+    logq = torch.empty(T, device=DEV)
+    fb.fopd_rollout_kl(z, zs, lp.dt, T, V, ld, ld, y, None, kl, lp.logp, lp.lse, dlse, logq, lp.workspace)
+    _sync_ok(lp)
+    z64, zs64 = np64(z)[:, :V], np64(zs)[:, :V]
+    want_kl, lse, lse_s = orc.rollout_kl_full(z64, zs64, None)
+    _, lq = orc.token_logprobs(zs64, np64(y), None)
+    _, lpo = orc.token_logprobs(z64, np64(y), None)
+    assert np.all(np.isfinite(want_kl)) and want_kl.max() > 5.0
+    got = np64(kl)
+    assert np.all(np.isfinite(got)), got
+    assert_close("roll_kl (independent tensors)", got, want_kl, rtol=2e-5, atol=3e-8)
+    assert got[3] == 0.0
+    assert_close("lse", np64(lp.lse), lse, atol=1e-4 + np.spacing(np.abs(lse).astype(np.float32)).astype(np.float64))
+    assert_close("dlse", np64(dlse), lse - lse_s, rtol=2e-6, atol=1e-4)
+    assert_close("logp", np64(lp.logp), lpo, rtol=1e-5, atol=1e-4)
+    assert_close("logq", np64(logq), lq, rtol=2e-6, atol=2e-4)
+
+
+def _chunked_inputs(name, seed, **over):
+    w = wl.generate(name, DEV, seed=seed, row_block=32, **over)
+    return w, w["T"], w["V"], w["B"], w["ld"]
+
+
+@pytest.mark.parametrize("name,over,chunk", [
+    ("coding", dict(B=3, total_len=64, resp_lo=6, resp_hi=16, obs_lo=3, obs_hi=9, V=151936, stale_logit_sigma=0.03), 40),
+    ("tooluse", dict(B=4, turns=2, obs_lo=2, obs_hi=6, resp_lo=4, resp_hi=10, V=5003, ld=5008, stale_logit_sigma=0.05,
+                     lag_hi=24, aligned_split=(0.3, 0.3)), 17),
+])
+def test_full_kl_chunked_flow_matches_whole_call_and_oracle(name, over, chunk):
+    """Phase 1 fopd_rollout_kl per chunk, phase 2 fopd_freshness_score on the O(T) arrays, phase 3
+    fopd_loss_fwd_bwd_full_kl per chunk with the stored per-row values.  Chunks cut samples.  The result
+    must be the whole-sample call's, bit for bit, and both must match the oracle."""
+    _say("chunked full-KL flow on a %s replica, chunks of %d rows" % (name, chunk))
+    w, T, V, B, ld = _chunked_inputs(name, 51, **over)
+    hp, g = (1.0, 1.0, 0.05, 0.5), 2.0
+    whole = _pass_for(w)
+    kl_w = torch.empty(T, device=DEV)
+    fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], whole.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                 w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp,
+                                 None, None, None, 0, None, None, None, None, g, whole.loss, whole.freshness,
+                                 whole.weights, whole.logp, kl_w, whole.dlogits, whole.workspace)
+    _sync_ok(whole)
+    ck = _pass_for(w)
+    kl = torch.empty(T, device=DEV)
+    dlse = torch.empty(T, device=DEV)
+    for a in range(0, T, chunk):
+        b = min(a + chunk, T)
+        fb.fopd_rollout_kl(w["logits"][a:b], w["logits_stale"][a:b], ck.dt, b - a, V, ld, ld, w["token_ids"][a:b],
+                           w["mask"][a:b], kl[a:b], ck.logp[a:b], ck.lse[a:b], dlse[a:b], None, ck.workspace)
+    fb.fopd_freshness_score(ck.logp, None, kl, None, w["teacher_logp"], w["teacher_logp_stale"], w["mask"],
+                            w["seq_lens"], w["lag"], T, B, hp, ck.cu_seqlens, ck.n_train, ck.n_roll, ck.D_roll, ck.D_sup,
+                            ck.ell, ck.cover, ck.cover_roll, ck.freshness, ck.agg, ck.workspace)
+    _sync_ok(ck)
+    assert torch.equal(kl, kl_w) and torch.equal(ck.freshness, whole.freshness)
+    ck.dlogits.fill_(9.0)
+    parts = []
+    stale = w["teacher_logp_stale"]
+    for a in range(0, T, chunk):
+        b = min(a + chunk, T)
+        part = torch.zeros(1, device=DEV)
+        fb.fopd_loss_fwd_bwd_full_kl(w["logits"][a:b], w["logits_stale"][a:b], ck.dt, b - a, V, ld, ld,
+                                     w["token_ids"][a:b], w["mask"][a:b], w["teacher_logp"][a:b],
+                                     None if stale is None else stale[a:b], w["seq_lens"], w["lag"], B, hp,
+                                     ck.freshness, ck.n_train, ck.n_roll, a, ck.lse[a:b], ck.logp[a:b], dlse[a:b],
+                                     kl[a:b], g, part, None, ck.weights, None, None, ck.dlogits[a:b], ck.workspace)
+        parts.append(part)
+    _sync_ok(ck)
+    assert torch.equal(ck.dlogits[:, :V], whole.dlogits[:, :V])
+    if ld > V:
+        assert bool((ck.dlogits[:, V:] == 9.0).all())
+    assert torch.equal(ck.weights, whole.weights)
+    tot = sum(float(p) for p in parts)
+    assert abs(tot - float(whole.loss)) <= 2e-6 * abs(float(whole.loss)) + 1e-12
+    # ... and the oracle
+    z, zs = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+    ref = orc.fopd_loss_fwd_bwd_full_kl(z, zs, np64(w["token_ids"]), np64(w["mask"]), np64(w["teacher_logp"]),
+                                        np64(w["teacher_logp_stale"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                        hp[0], hp[1], hp[2], hp[3], g, out_dtype=w["dtype"])
+    assert_close("freshness", np64(ck.freshness), ref["freshness"], rtol=1e-5)
+    assert abs(tot - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    assert np.array_equal(np64(ck.n_train), ref["n_train"]) and np.array_equal(np64(ck.n_roll), ref["n_roll"])
+    sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]))
+    check_grad_rows_full_kl(np64(ck.dlogits)[:, :V], z, zs, np64(w["token_ids"]), ref, range(T), hp, g, B, sample_of,
+                            w["dtype"])
+
+
+def test_full_teacher_chunked_flow_matches_whole_call_and_oracle():
+    """The same three phases with the teacher's logits as the second tensor: the per-row KL is the token loss
+    (fed to the scores as `token_loss`), the teacher's log-prob of y_t comes out of phase 1 (`logq`)."""
+    _say("chunked distribution-level-teacher flow, chunks of 23 rows")
+    w, T, V, B, ld = _chunked_inputs("coding", 61, B=3, total_len=48, resp_lo=5, resp_hi=12, obs_lo=2, obs_hi=7,
+                                     V=9001, ld=9008, stale_logit_sigma=0.3, aligned_split=(0.25, 0.25))
+    hp, g, chunk = (1.0, 1.0, 0.05, 0.5), 1.5, 23
+    stale = w["teacher_logp"]           # the generator's stored teacher log-prob plays the stale-context one
+    whole = _pass_for(w)
+    kl_w = torch.empty(T, device=DEV)
+    fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], whole.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                      w["behav_logp"], stale, w["seq_lens"], w["lag"], B, hp,
+                                      None, None, None, 0, None, None, None, None, g, whole.loss, whole.freshness,
+                                      whole.weights, whole.logp, kl_w, whole.dlogits, whole.workspace)
+    _sync_ok(whole)
+    ck = _pass_for(w)
+    kl = torch.empty(T, device=DEV)
+    dlse = torch.empty(T, device=DEV)
+    logq = torch.empty(T, device=DEV)
+    for a in range(0, T, chunk):
+        b = min(a + chunk, T)
+        fb.fopd_rollout_kl(w["logits"][a:b], w["logits_stale"][a:b], ck.dt, b - a, V, ld, ld, w["token_ids"][a:b],
+                           w["mask"][a:b], kl[a:b], ck.logp[a:b], ck.lse[a:b], dlse[a:b], logq[a:b], ck.workspace)
+    fb.fopd_freshness_score(ck.logp, w["behav_logp"], None, kl, logq, stale, w["mask"], w["seq_lens"], w["lag"], T, B,
+                            hp, ck.cu_seqlens, ck.n_train, ck.n_roll, ck.D_roll, ck.D_sup, ck.ell, ck.cover,
+                            ck.cover_roll, ck.freshness, ck.agg, ck.workspace)
+    _sync_ok(ck)
+    assert torch.equal(ck.freshness, whole.freshness)
+    parts = []
+    for a in range(0, T, chunk):
+        b = min(a + chunk, T)
+        part = torch.zeros(1, device=DEV)
+        fb.fopd_loss_fwd_bwd_full_teacher(w["logits"][a:b], w["logits_stale"][a:b], ck.dt, b - a, V, ld, ld,
+                                          w["token_ids"][a:b], w["mask"][a:b], w["behav_logp"][a:b], stale[a:b],
+                                          w["seq_lens"], w["lag"], B, hp, ck.freshness, ck.n_train, ck.n_roll, a,
+                                          ck.lse[a:b], ck.logp[a:b], dlse[a:b], kl[a:b], g, part, None, ck.weights,
+                                          None, None, ck.dlogits[a:b], ck.workspace)
+        parts.append(part)
+    _sync_ok(ck)
+    assert torch.equal(ck.dlogits[:, :V], whole.dlogits[:, :V]) and torch.equal(ck.weights, whole.weights)
+    tot = sum(float(p) for p in parts)
+    assert abs(tot - float(whole.loss)) <= 2e-6 * abs(float(whole.loss)) + 1e-12
+    z, zq = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+    ref = orc.fopd_loss_fwd_bwd_full_teacher(z, zq, np64(w["token_ids"]), np64(w["mask"]), np64(w["behav_logp"]),
+                                             np64(stale), np64(w["seq_lens"]), np64(w["lag"]),
+                                             hp[0], hp[1], hp[2], hp[3], g, out_dtype=w["dtype"])
+    assert_close("freshness", np64(ck.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("ell", np64(ck.ell), ref["ell"], rtol=2e-5, atol=1e-6)
+    assert_close("D_sup", np64(ck.D_sup), ref["D_sup"], rtol=2e-5, atol=1e-9)
+    assert abs(tot - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]))
+    check_grad_rows_full_kl(np64(ck.dlogits)[:, :V], z, zq, np64(w["token_ids"]), ref, range(T), hp, g, B, sample_of,
+                            w["dtype"], c2_scales_with_weight=True)
+
+
+def test_two_tensor_chunk_arguments_are_all_or_nothing():
+    w, T, V, B, ld = _chunked_inputs("tiny", 3, B=2, len_lo=5, len_hi=5, V=64, stale_logit_sigma=0.1)
+    lp = _pass_for(w)
+    f = torch.ones(B, device=DEV)
+    with pytest.raises(fb.FopdError) as e:
+        fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                     w["teacher_logp"], None, w["seq_lens"], w["lag"], B, (1, 1, 0, 0),
+                                     f, None, None, 0, None, None, None, None, 1.0, lp.loss, None, None, None, None,
+                                     lp.dlogits, lp.workspace)
+    assert e.value.status == 1
+    with pytest.raises(fb.FopdError) as e:
+        fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                     w["teacher_logp"], None, w["seq_lens"], w["lag"], B, (1, 1, 0, 0),
+                                     None, None, None, 3, None, None, None, None, 1.0, lp.loss, None, None, None, None,
+                                     lp.dlogits, lp.workspace)
+    assert e.value.status == 1

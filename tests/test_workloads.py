@@ -3,7 +3,7 @@
 import numpy as np
 import torch
 
-from paper_2605_17862_amd import workloads as wl
+from harness import workloads as wl
 
 
 def test_tiny_is_as_specified_and_deterministic():
