@@ -40,7 +40,7 @@
  *     (token id outside [0, V), negative lag or length, lengths not adding up to T, a mask that names
  *     two different aligned sets where only one count array was passed) set sticky bits in the first
  *     int32 of the workspace; fopd_workspace_status() reads them.  A row with an out-of-range token id
- *     is treated as masked; a sample with a negative lag is treated as invalid (f_i = w_i = 0, both
+ *     gets lp = lse = 0 and a zero gradient row (its sample still counts it); a sample with a negative lag is treated as invalid (f_i = w_i = 0, both
  *     alignment ratios 0); a row of only one set whose call has no n_roll_in gets a zero gradient row
  *     and adds nothing to the loss.
  *   - Non-finite inputs propagate to non-finite outputs; nothing traps.

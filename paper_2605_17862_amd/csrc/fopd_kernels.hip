@@ -540,14 +540,15 @@ fopd_k4_grad(const void* logits, void* dlogits, int64_t T, int V, int64_t ld,
              const int32_t* token_ids, const float* lse, const float* logp, const float* coef) {
   const int64_t t = blockIdx.x;
   const float c = coef[t];
+  const int y = token_ids[t];
   char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
-  if (c == 0.f) {
+  if (c == 0.f || y < 0 || y >= V) {     // a token id out of range was flagged by the first pass: no gradient
     row_zero<DT, kGradThreads>(orow, V);
     return;
   }
   const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
   // the sampled token's entry c * (p_y - 1) comes from lp_y, which stays accurate as p_y -> 1
-  row_grad<DT, kGradThreads, U, false>(row, orow, V, token_ids[t], c, lse[t] * kLog2e, c * expm1f(logp[t]));
+  row_grad<DT, kGradThreads, U, false>(row, orow, V, y, c, lse[t] * kLog2e, c * expm1f(logp[t]));
 }
 
 // =========================================================================================
@@ -946,7 +947,7 @@ fopd_k6_grad_kl(const void* logits, const void* logits_stale, void* dlogits, int
   const int tid = threadIdx.x;
   const float a = c1[t], b = c2[t];
   char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
-  if (a == 0.f && b == 0.f) {
+  if ((a == 0.f && b == 0.f) || token_ids[t] < 0 || token_ids[t] >= V) {   // out of range: flagged earlier
     row_zero<DT, NT>(orow, V);
     return;
   }

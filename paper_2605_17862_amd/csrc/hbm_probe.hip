@@ -2,10 +2,18 @@
 //
 //   hbm_probe [GiB per buffer, default 8]
 //
-// Launches, five times each, a read-only, a write-only and a copy kernel over buffers of the
-// given size, with the same access shape as the loss kernels (one 256-lane workgroup per
-// 303,872-byte row, 16-byte accesses), and prints the bandwidth of each.  Under
-// `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` the copy kernel gives the counter reading for a
+// Times, five launches each after a warm-up, over buffers of the given size:
+//   row shape (what the loss kernels use: one 256-lane workgroup per 303,872-byte row, 16-byte accesses)
+//     read, write, copy
+//   shapes that do NOT follow the loss kernels, as independent yardsticks for the same bytes
+//     runtime copy      hipMemcpyAsync device-to-device (the runtime's own copy path)
+//     flat copy         a fixed grid of 2048 workgroups striding over the buffer in 16 KB blocks
+//     burst copy        each workgroup loads a 64 KB contiguous chunk into registers, then stores it
+//   read:write mixes, row shape
+//     2r1w              two buffers read, one written (the mix of the two-tensor gradient kernel)
+//     1r2w              one buffer read, two written
+// and prints the bandwidth of each (bytes read + bytes written, over the time).  Under
+// `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` the row-shape copy kernel gives the counter reading for a
 // known number of bytes, which is the scale factor applied to the loss kernels' readings.
 
 #include <hip/hip_runtime.h>
@@ -17,6 +25,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kRowVecs = 18992;   // 151,936 bf16 = 303,872 bytes
+constexpr int kFlatGrid = 2048;   // 8 workgroups per compute unit
+constexpr int kBurst = 16;        // vectors per lane held in registers by the burst copy (64 KB per workgroup)
 
 __global__ void __launch_bounds__(kThreads) hbm_probe_read(const u32x4* in, uint32_t* sink) {
   const u32x4* r = in + static_cast<size_t>(blockIdx.x) * kRowVecs;
@@ -45,6 +55,60 @@ __global__ void __launch_bounds__(kThreads) hbm_probe_copy(const u32x4* in, u32x
   for (int j = threadIdx.x; j < kRowVecs; j += kThreads) o[j] = __builtin_nontemporal_load(r + j);
 }
 
+// n = total number of 16-byte vectors.  Block k of 1024 vectors goes to workgroup k % gridDim.
+__global__ void __launch_bounds__(kThreads) hbm_probe_copy_flat(const u32x4* in, u32x4* out, size_t n) {
+  const size_t step = static_cast<size_t>(gridDim.x) * 4 * kThreads;
+  for (size_t base = static_cast<size_t>(blockIdx.x) * 4 * kThreads; base < n; base += step) {
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t i = base + u * kThreads + threadIdx.x;
+      if (i < n) v[u] = __builtin_nontemporal_load(in + i);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t i = base + u * kThreads + threadIdx.x;
+      if (i < n) __builtin_nontemporal_store(v[u], out + i);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) hbm_probe_copy_burst(const u32x4* in, u32x4* out, size_t n) {
+  const size_t chunk = static_cast<size_t>(kBurst) * kThreads;
+  const size_t step = static_cast<size_t>(gridDim.x) * chunk;
+  for (size_t base = static_cast<size_t>(blockIdx.x) * chunk; base < n; base += step) {
+    u32x4 v[kBurst];
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) {
+      const size_t i = base + u * kThreads + threadIdx.x;
+      if (i < n) v[u] = __builtin_nontemporal_load(in + i);
+    }
+#pragma unroll
+    for (int u = 0; u < kBurst; ++u) {
+      const size_t i = base + u * kThreads + threadIdx.x;
+      if (i < n) __builtin_nontemporal_store(v[u], out + i);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) hbm_probe_2r1w(const u32x4* in1, const u32x4* in2, u32x4* out) {
+  const size_t off = static_cast<size_t>(blockIdx.x) * kRowVecs;
+  for (int j = threadIdx.x; j < kRowVecs; j += kThreads) {
+    const u32x4 a = __builtin_nontemporal_load(in1 + off + j);
+    const u32x4 b = __builtin_nontemporal_load(in2 + off + j);
+    __builtin_nontemporal_store(a ^ b, out + off + j);
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) hbm_probe_1r2w(const u32x4* in, u32x4* out1, u32x4* out2) {
+  const size_t off = static_cast<size_t>(blockIdx.x) * kRowVecs;
+  for (int j = threadIdx.x; j < kRowVecs; j += kThreads) {
+    const u32x4 a = __builtin_nontemporal_load(in + off + j);
+    __builtin_nontemporal_store(a, out1 + off + j);
+    __builtin_nontemporal_store(~a, out2 + off + j);
+  }
+}
+
 #define CHECK(x)                                                                    \
   do {                                                                              \
     hipError_t e_ = (x);                                                            \
@@ -63,26 +127,37 @@ int main(int argc, char** argv) {
   const size_t row_bytes = static_cast<size_t>(kRowVecs) * 16;
   const unsigned rows = static_cast<unsigned>(gib * 1073741824.0 / row_bytes);
   const size_t bytes = rows * row_bytes;
-  u32x4 *a = nullptr, *b = nullptr;
+  const size_t nvec = static_cast<size_t>(rows) * kRowVecs;
+  u32x4 *a = nullptr, *b = nullptr, *c = nullptr;
   uint32_t* sink = nullptr;
   CHECK(hipMalloc(&a, bytes));
   CHECK(hipMalloc(&b, bytes));
+  CHECK(hipMalloc(&c, bytes));
   CHECK(hipMalloc(&sink, 4));
   CHECK(hipMemset(a, 1, bytes));
   CHECK(hipMemset(b, 2, bytes));
+  CHECK(hipMemset(c, 3, bytes));
   hipEvent_t e0, e1;
   CHECK(hipEventCreate(&e0));
   CHECK(hipEventCreate(&e1));
   printf("hbm_probe: %u rows of %zu bytes = %.3f GB per buffer\n", rows, row_bytes, bytes * 1e-9);
-  for (int which = 0; which < 3; ++which) {
-    const char* name = which == 0 ? "read" : which == 1 ? "write" : "copy";
-    const double moved = (which == 2 ? 2.0 : 1.0) * bytes;
+  const char* names[8] = {"read", "write", "copy", "runtime-copy", "flat-copy", "burst-copy", "2r1w", "1r2w"};
+  const double factor[8] = {1.0, 1.0, 2.0, 2.0, 2.0, 2.0, 3.0, 3.0};
+  for (int which = 0; which < 8; ++which) {
+    const double moved = factor[which] * bytes;
     float total = 0.f;
     for (int rep = 0; rep < 6; ++rep) {        // first launch is a warm-up
       CHECK(hipEventRecord(e0, 0));
-      if (which == 0) hbm_probe_read<<<rows, kThreads>>>(a, sink);
-      if (which == 1) hbm_probe_write<<<rows, kThreads>>>(b);
-      if (which == 2) hbm_probe_copy<<<rows, kThreads>>>(a, b);
+      switch (which) {
+        case 0: hbm_probe_read<<<rows, kThreads>>>(a, sink); break;
+        case 1: hbm_probe_write<<<rows, kThreads>>>(b); break;
+        case 2: hbm_probe_copy<<<rows, kThreads>>>(a, b); break;
+        case 3: CHECK(hipMemcpyAsync(b, a, bytes, hipMemcpyDeviceToDevice, 0)); break;
+        case 4: hbm_probe_copy_flat<<<kFlatGrid, kThreads>>>(a, b, nvec); break;
+        case 5: hbm_probe_copy_burst<<<kFlatGrid, kThreads>>>(a, b, nvec); break;
+        case 6: hbm_probe_2r1w<<<rows, kThreads>>>(a, c, b); break;
+        default: hbm_probe_1r2w<<<rows, kThreads>>>(a, b, c); break;
+      }
       CHECK(hipGetLastError());
       CHECK(hipEventRecord(e1, 0));
       CHECK(hipEventSynchronize(e1));
@@ -90,11 +165,13 @@ int main(int argc, char** argv) {
       CHECK(hipEventElapsedTime(&ms, e0, e1));
       if (rep > 0) total += ms;
     }
-    printf("hbm_probe: %-5s %.0f bytes per launch, avg %.3f ms, %.0f GB/s\n", name, moved, total / 5,
+    printf("hbm_probe: %-12s %.0f bytes per launch, avg %.3f ms, %.0f GB/s\n", names[which], moved, total / 5,
            moved / (total / 5) * 1e-6);
+    fflush(stdout);
   }
   CHECK(hipFree(a));
   CHECK(hipFree(b));
+  CHECK(hipFree(c));
   CHECK(hipFree(sink));
   return 0;
 }

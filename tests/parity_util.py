@@ -75,6 +75,50 @@ def coef_uncertainty(ref, hp, grad_scale, n_samples, mask):
     return out
 
 
+# How often the plain bound (2 ulp of the storage type) is not enough and the floor is what lets an element
+# pass.  Filled by check_grad_rows; read (and reset) by floor_report().
+FLOOR_STATS = dict(elements=0, rows=0, beyond_plain=0, rows_beyond_plain=0, tiny=0, sampled_entry=0,
+                   min_rel_uncertainty=np.inf, worst_excess_ulp=0.0)
+
+
+def _count_floor_use(got, want, err, plain_lim, y, c, eps):
+    st = FLOOR_STATS
+    st["elements"] += got.size
+    st["rows"] += 1
+    beyond = ~((err <= plain_lim) | (got == want))
+    if not np.any(beyond):
+        return
+    n = int(beyond.sum())
+    st["beyond_plain"] += n
+    st["rows_beyond_plain"] += 1
+    tiny = beyond & (np.abs(want) < 2.0 ** -120)          # bf16/fp32 subnormal range: flushed to zero
+    st["tiny"] += int(tiny.sum())
+    if beyond[y]:
+        st["sampled_entry"] += 1
+    rest = beyond & ~tiny
+    rest[y] = False
+    if np.any(rest):
+        # the floor exists because c_t is a difference of O(1) quantities: it may only be needed where the
+        # allowed absolute error of c_t is a visible fraction of c_t itself
+        st["min_rel_uncertainty"] = min(st["min_rel_uncertainty"], eps / max(abs(c), 1e-300))
+        st["worst_excess_ulp"] = max(st["worst_excess_ulp"], float(np.max(err[rest] / (plain_lim[rest] / 2.0))))
+
+
+def floor_report(reset=True):
+    """(copy of the counters, one-line summary)."""
+    st = dict(FLOOR_STATS)
+    frac = st["beyond_plain"] / max(st["elements"], 1)
+    line = ("dlogits: %d elements in %d rows compared; %d (%.2e of them, in %d rows) are outside the plain 2-ulp bound "
+            "and pass through the floor: %d in the subnormal range, %d sampled-token entries, the rest in rows whose "
+            "coefficient is uncertain by >= %.1e relative (worst %.1f ulp)"
+            % (st["elements"], st["rows"], st["beyond_plain"], frac, st["rows_beyond_plain"], st["tiny"],
+               st["sampled_entry"], st["min_rel_uncertainty"], st["worst_excess_ulp"]))
+    if reset:
+        FLOOR_STATS.update(elements=0, rows=0, beyond_plain=0, rows_beyond_plain=0, tiny=0, sampled_entry=0,
+                           min_rel_uncertainty=np.inf, worst_excess_ulp=0.0)
+    return st, line
+
+
 def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label=""):
     """got_rows: [R, V] float64 values read back from the GPU; the rest are oracle arrays for the
     same R rows.  Rows whose oracle coefficient is exactly 0 (masked or gated) must be all-zero
@@ -103,6 +147,7 @@ def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label="")
         assert not np.any(bad), "dlogits row %s%d: %d elements off, worst %.3e vs limit %.3e at v=%d (c=%.3e)" % (
             rows_label, r, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]),
             int(np.argmax(err * bad)), coef[r])
+        _count_floor_use(got_rows[r], want, err, lim - floor, int(y[r]), coef[r], eps_c[r])
 
 
 def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_scale, n_samples, sample_of_row, store,

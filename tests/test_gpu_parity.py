@@ -9,8 +9,8 @@ from oracle import fopd_oracle as orc
 from paper_2605_17862_amd import binding as fb
 from harness import workloads as wl
 from paper_2605_17862_amd.loss_pass import DEFAULT_HPARAMS, LossPass
-from parity_util import (assert_close, check_grad_rows, check_grad_rows_full_kl, coef_uncertainty, np64,
-                         oracle_full)
+from parity_util import (assert_close, check_grad_rows, check_grad_rows_full_kl, coef_uncertainty, floor_report,
+                         np64, oracle_full)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -19,6 +19,16 @@ HP = DEFAULT_HPARAMS
 
 def _say(msg):
     print("[gpu-parity] " + msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _dlogits_floor_accounting(request):
+    """After each test: how many gradient elements needed more than the plain 2-ulp bound, and why."""
+    floor_report()
+    yield
+    st, line = floor_report()
+    if st["elements"]:
+        _say("%s: %s" % (request.node.name, line))
 
 
 def _pass_for(w, alloc_dlogits=True):
@@ -769,7 +779,7 @@ def _check_sample(o, i, logp, lse, freshness, weights, st):
     if st is not None:
         assert_close("D_roll %d" % i, np64(st.D_roll[i:i + 1]), o["D_roll"], rtol=2e-5, atol=1e-9)
         assert_close("D_sup %d" % i, np64(st.D_sup[i:i + 1]), o["D_sup"], rtol=2e-5, atol=1e-9)
-        assert_close("ell %d" % i, np64(st.ell[i:i + 1]), o["ell"], rtol=2e-5, atol=1e-9)
+        assert_close("ell %d" % i, np64(st.ell[i:i + 1]), o["ell"], rtol=2e-5, atol=1e-6)
         assert_close("cover %d" % i, np64(st.cover[i:i + 1]), o["cover"], rtol=1e-6)
         assert int(st.n_train[i]) == int(o["n"][0])
 

@@ -71,6 +71,12 @@ def test_rollout_kl_with_an_independent_heavy_tailed_second_tensor(V, scale):
     assert_close("logq", np64(logq), lq, rtol=2e-6, atol=2e-4)
 
 
+def _same_up_to_one_ulp(x, y, dtype):
+    xd, yd = np64(x), np64(y)
+    lim = orc.bf16_ulp(yd) if dtype == "bf16" else 2e-7 * np.abs(yd) + 1e-37
+    assert bool(np.all(np.abs(xd - yd) <= lim)) and float(np.mean(xd == yd)) > 0.9
+
+
 def _chunked_inputs(name, seed, **over):
     w = wl.generate(name, DEV, seed=seed, row_block=32, **over)
     return w, w["T"], w["V"], w["B"], w["ld"]
@@ -84,7 +90,8 @@ def _chunked_inputs(name, seed, **over):
 def test_full_kl_chunked_flow_matches_whole_call_and_oracle(name, over, chunk):
     """Phase 1 fopd_rollout_kl per chunk, phase 2 fopd_freshness_score on the O(T) arrays, phase 3
     fopd_loss_fwd_bwd_full_kl per chunk with the stored per-row values.  Chunks cut samples.  The result
-    must be the whole-sample call's, bit for bit, and both must match the oracle."""
+    must not depend on where the chunks are cut, must be the whole-sample call's up to the last place, and both
+    must match the oracle."""
     _say("chunked full-KL flow on a %s replica, chunks of %d rows" % (name, chunk))
     w, T, V, B, ld = _chunked_inputs(name, 51, **over)
     hp, g = (1.0, 1.0, 0.05, 0.5), 2.0
@@ -108,8 +115,8 @@ def test_full_kl_chunked_flow_matches_whole_call_and_oracle(name, over, chunk):
     _sync_ok(ck)
     assert torch.equal(kl, kl_w) and torch.equal(ck.freshness, whole.freshness)
     ck.dlogits.fill_(9.0)
-    parts = []
     stale = w["teacher_logp_stale"]
+    parts = []
     for a in range(0, T, chunk):
         b = min(a + chunk, T)
         part = torch.zeros(1, device=DEV)
@@ -120,11 +127,22 @@ def test_full_kl_chunked_flow_matches_whole_call_and_oracle(name, over, chunk):
                                      kl[a:b], g, part, None, ck.weights, None, None, ck.dlogits[a:b], ck.workspace)
         parts.append(part)
     _sync_ok(ck)
-    assert torch.equal(ck.dlogits[:, :V], whole.dlogits[:, :V])
+    # one chunk that covers every row: the same bits as many chunks
+    one = _pass_for(w)
+    fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], one.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                 w["teacher_logp"], stale, w["seq_lens"], w["lag"], B, hp, ck.freshness, ck.n_train,
+                                 ck.n_roll, 0, ck.lse, ck.logp, dlse, kl, g, one.loss, None, one.weights, None, None,
+                                 one.dlogits, one.workspace)
+    _sync_ok(one)
+    assert torch.equal(ck.dlogits[:, :V], one.dlogits[:, :V]) and torch.equal(ck.weights, one.weights)
+    # the whole-sample call keeps the scores in float64 between its kernels, the chunked flow passes them as
+    # float32: coefficients may differ in the last place, gradient entries by one unit of the storage type
+    _same_up_to_one_ulp(ck.dlogits[:, :V], whole.dlogits[:, :V], w["dtype"])
     if ld > V:
         assert bool((ck.dlogits[:, V:] == 9.0).all())
-    assert torch.equal(ck.weights, whole.weights)
+    assert_close("weights", np64(ck.weights), np64(whole.weights), rtol=1e-6, atol=1e-9)
     tot = sum(float(p) for p in parts)
+    assert abs(tot - float(one.loss)) <= 2e-6 * abs(float(one.loss)) + 1e-12
     assert abs(tot - float(whole.loss)) <= 2e-6 * abs(float(whole.loss)) + 1e-12
     # ... and the oracle
     z, zs = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
@@ -178,7 +196,8 @@ def test_full_teacher_chunked_flow_matches_whole_call_and_oracle():
                                           None, None, ck.dlogits[a:b], ck.workspace)
         parts.append(part)
     _sync_ok(ck)
-    assert torch.equal(ck.dlogits[:, :V], whole.dlogits[:, :V]) and torch.equal(ck.weights, whole.weights)
+    _same_up_to_one_ulp(ck.dlogits[:, :V], whole.dlogits[:, :V], w["dtype"])
+    assert_close("weights", np64(ck.weights), np64(whole.weights), rtol=1e-6, atol=1e-9)
     tot = sum(float(p) for p in parts)
     assert abs(tot - float(whole.loss)) <= 2e-6 * abs(float(whole.loss)) + 1e-12
     z, zq = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
