@@ -219,6 +219,35 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * fopd_loss_fwd_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving / training loops, harnesses that forbid allocation.  Same arguments, modes, kernels
+ * and results (bit for bit) as fopd_loss_fwd_bwd, except that the scratch memory is an array inside the
+ * library (about 1.3 MB of device memory per GPU, held from module load until the process ends) and
+ * therefore
+ *   - T <= FOPD_STATIC_MAX_ROWS and B <= FOPD_STATIC_MAX_SAMPLES, else FOPD_ELIMIT and nothing is launched
+ *     (long buffers go through it chunk by chunk, exactly like the chunked flow of fopd_loss_fwd_bwd);
+ *   - the sticky device flags live in that array too: they are cleared at the start of every call and, if
+ *     flags_out (a DEVICE int32, may be NULL) is given, copied there at the end (fopd_flags_status decodes them);
+ *   - every call on one GPU uses that GPU's one array: calls that may overlap on a GPU (different streams
+ *     without an ordering between them, several host threads) race and must be serialised by the caller.
+ * The call allocates nothing, frees nothing, records no memset and creates no event (the fopd_profile_* hooks
+ * do not see it).  The first call on a device looks the array's address up (and, when freshness_in is given
+ * without lse_in, sets a kernel attribute): make one call outside any stream capture first.
+ */
+#define FOPD_STATIC_MAX_ROWS 32768
+#define FOPD_STATIC_MAX_SAMPLES 4096
+fopd_status fopd_loss_fwd_bwd_static(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                     const int32_t* token_ids, const uint8_t* mask,
+                                     const float* behav_logp, const float* teacher_logp,
+                                     const float* teacher_logp_stale,
+                                     const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                     const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                                     int64_t row_begin, const float* lse_in, const float* logp_in,
+                                     float grad_scale,
+                                     float* loss, float* freshness, float* weights, float* logp,
+                                     void* dlogits, int32_t* flags_out, void* stream);
+
+/*
  * Full-vocabulary rollout drift, Eq. "kl-diagnostics" first line as printed: per row
  *   roll_kl_t = KL( softmax(z_t) || softmax(z'_t) ),   z' = logits of the stale checkpoint pi^{r(i)}
  * replayed on the same prefixes.  One pass over both tensors (masked rows are not read).

@@ -61,6 +61,23 @@ struct LmWorkspace {
   }
 };
 
+// ---- scratch memory owned by the library, for the entry point that may not allocate -------------------
+// One workspace of the largest size that entry point accepts, as a device array of this module: every GPU the
+// library runs on holds its own copy from module load until the process ends.
+constexpr int64_t kStaticMaxRows = FOPD_STATIC_MAX_ROWS;
+constexpr int32_t kStaticMaxSamples = FOPD_STATIC_MAX_SAMPLES;
+constexpr size_t kStaticBytes = Workspace(kStaticMaxRows, kStaticMaxSamples).total;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+namespace {
+
+// In host code `scratch` is only a handle for the runtime: the array's device address is looked up once per
+// device (with that device current) and kept; host code uses that address, never the symbol's name.
+void* g_scratch_ptr[64] = {};
+
 template <typename P>
 inline P* at(void* ws, size_t off) {
   return reinterpret_cast<P*>(static_cast<char*>(ws) + off);
@@ -148,6 +165,20 @@ inline fopd_status allow_dynamic_lds(const void* kern, int bytes, bool* done) {
   if (done[dev]) return FOPD_OK;
   if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return FOPD_EHIP;
   done[dev] = true;
+  return FOPD_OK;
+}
+
+// Device address of `scratch` on the current device.
+inline fopd_status static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FOPD_EHIP;
+  std::lock_guard<std::mutex> lock(g_state_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FOPD_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
   return FOPD_OK;
 }
 
@@ -470,6 +501,37 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in,
                               grad_scale, loss, freshness, weights, logp, dlogits, workspace,
                               static_cast<hipStream_t>(stream), true);
+}
+
+fopd_status fopd_loss_fwd_bwd_static(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                     const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                                     const float* teacher_logp, const float* teacher_logp_stale,
+                                     const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                     const float* freshness_in, const int32_t* n_train_in, const int32_t* n_roll_in,
+                                     int64_t row_begin, const float* lse_in, const float* logp_in, float grad_scale,
+                                     float* loss, float* freshness, float* weights, float* logp, void* dlogits,
+                                     int32_t* flags_out, void* stream) {
+  fopd_status st = loss_fwd_bwd_check_args(logits, dt, T, V, ld, token_ids, behav_logp, teacher_logp, seq_lens, lag, B,
+                                           hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in, loss,
+                                           dlogits);
+  if (st != FOPD_OK) return st;
+  if (T > kStaticMaxRows || B > kStaticMaxSamples) return FOPD_ELIMIT;
+  void* ws = nullptr;
+  if ((st = static_scratch(&ws)) != FOPD_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // the array keeps the previous call's contents; only the flag words must start at zero (every other
+  // region is written before it is read), and they are cleared by a kernel, not a memset
+  fopd_clear_flags<<<1, 64, 0, s>>>(static_cast<int32_t*>(ws));
+  if ((st = launched()) != FOPD_OK) return st;
+  st = loss_fwd_bwd_checked(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
+                            seq_lens, lag, B, hp, freshness_in, n_train_in, n_roll_in, row_begin, lse_in, logp_in,
+                            grad_scale, loss, freshness, weights, logp, dlogits, ws, s, false);
+  if (st != FOPD_OK) return st;
+  if (flags_out != nullptr) {
+    fopd_copy_flags<<<1, 64, 0, s>>>(static_cast<const int32_t*>(ws), flags_out);
+    st = launched();
+  }
+  return st;
 }
 
 fopd_status fopd_rollout_kl(const void* logits, const void* logits_stale, fopd_dtype dt, int64_t T, int64_t V,

@@ -1026,6 +1026,11 @@ __global__ void fopd_clear_flags(int32_t* flags) {
   if (threadIdx.x < 4) flags[threadIdx.x] = 0;
 }
 
+// Hands the sticky flag word to a caller-owned int32.
+__global__ void fopd_copy_flags(const int32_t* flags, int32_t* out) {
+  if (threadIdx.x == 0) out[0] = flags[0];
+}
+
 // Exclusive scan of seq_lens into cu[0..B] (int64) with one workgroup; checks signs and the
 // total.  need_exact >= 0: the total must equal it; otherwise the total must be >= need_min.
 __global__ void __launch_bounds__(kScanThreads)
