@@ -151,6 +151,46 @@ def lm_head_token_logprobs(hidden, weight, token_ids, mask=None):
     return token_logprobs(lm_head_logits(hidden, weight), token_ids, mask)
 
 
+def lm_head_loss_fwd_bwd(hidden, weight, token_ids, mask, behav_logp, teacher_logp, seq_lens, lag, freshness,
+                         xi, lam, grad_scale=1.0):
+    """Second loop of Algorithm 1 (weights from scores computed beforehand, anchored loss, gradient) when the
+    student's logits are the projection z = hidden . weight^T and are never kept: the gradient is carried
+    through the projection to the hidden states and to the projection matrix,
+        dL/dhidden[t, :] = sum_v dL/dz[t, v] * weight[v, :],    dL/dweight[v, :] = sum_t dL/dz[t, v] * hidden[t, :].
+    The logits stay unrounded (float64 here); the gradient rows dL/dz are rounded to bfloat16, the type the
+    path stores them in between its kernels, before the two contractions ("dhidden", "dweight"); the same two
+    contractions of the unrounded rows are returned as "dhidden_exact", "dweight_exact".
+    freshness: [B] scores from the first loop; the aligned-set counts come from `mask`."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    z = lm_head_logits(hidden, weight)
+    T, V = z.shape
+    if mask is None:
+        mask = np.ones(T, dtype=np.uint8)
+    cu = segment_offsets(seq_lens)
+    if int(cu[-1]) != T:
+        raise ValueError("sequence lengths do not add up to T")
+    for tau in lag:
+        if int(tau) < 0:
+            raise ValueError("negative lag")
+    lse, lp = token_logprobs(z, token_ids, mask)
+    delta, rho, adv, k_roll, k_sup = token_terms(lp, behav_logp, teacher_logp, None)
+    D_roll, _, ell, _, n = sample_statistics(lp, teacher_logp, k_roll, k_sup, mask, cu)
+    _, n_roll, n_valid = roll_coverage(mask, cu)
+    w = freshness_weights(np.asarray(freshness, dtype=np.float64), xi, n_valid)
+    loss = anchored_loss(w, ell, D_roll, lam)
+    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)
+    g = np.zeros((T, V))
+    for t in range(T):
+        g[t] = dlogits_row(z[t], int(token_ids[t]), lse[t], coef[t])
+    gb = round_to_bf16(g)
+    return dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, logits=z, lse=lse, logp=lp, delta=delta, rho=rho, adv=adv,
+                D_roll=D_roll, ell=ell, freshness=np.asarray(freshness, dtype=np.float64), weights=w, loss=loss,
+                coef=coef, dlogits_exact=g, dlogits=gb,
+                dhidden=np.matmul(gb, weight), dweight=np.matmul(gb.T, hidden),
+                dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden))
+
+
 def token_entropy(logits, mask=None):
     """H_t = -sum_v p_v log p_v of softmax(z_t) (the token-level response entropy that App. B logs as a
     monitoring proxy).  Masked rows give 0; entries with p_v = 0 (logit -inf) contribute 0."""

@@ -932,3 +932,94 @@ def test_two_aligned_sets_two_tensor_gradients_by_finite_differences():
             zm[t, v] -= h
             num[t, v] = (surrogate(zp, res["weights"], teacher) - surrogate(zm, res["weights"], teacher)) / (2 * h)
         assert np.max(np.abs(num - res["dlogits_exact"])) < 2e-6 * np.max(np.abs(num)), teacher
+
+
+# ---------------------------------------------------------------------------------------
+# gradient carried through the output projection
+# ---------------------------------------------------------------------------------------
+
+def _projection_case(seed, T_seq=(3, 4), d=5, V=7):
+    rng = _rng(seed)
+    seq = np.array(T_seq, dtype=np.int32)
+    T = int(seq.sum())
+    H = rng.normal(0, 1.0, size=(T, d))
+    W = rng.normal(0, 0.8, size=(V, d))
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    mask = np.array([1, 2, 3, 1, 0, 1, 3][:T], dtype=np.uint8)
+    lp = scipy.special.log_softmax(H @ W.T, axis=1)[np.arange(T), y]
+    lb = lp + rng.normal(0, 0.3, T)
+    lq = np.minimum(lp + rng.normal(-0.3, 0.5, T), 0.0)
+    return dict(H=H, W=W, y=y, mask=mask, lb=lb, lq=lq, seq=seq, lag=np.array([0, 2], dtype=np.int32),
+                f=np.array([0.8, 0.3]))
+
+
+def test_projection_gradient_by_finite_differences_through_hidden_and_weight():
+    """dL/dhidden and dL/dweight of the surrogate whose logits-gradient is the method's semi-gradient
+    (weights and advantage frozen), by central differences through the projection: fixes which operand each
+    contraction takes, along which axis, and that the three dimensions are not mixed up (T, d, V all differ)."""
+    c = _projection_case(3)
+    xi, lam, g = 0.05, 0.7, 1.3
+    res = orc.lm_head_loss_fwd_bwd(c["H"], c["W"], c["y"], c["mask"], c["lb"], c["lq"], c["seq"], c["lag"], c["f"],
+                                   xi, lam, g)
+    T, d = c["H"].shape
+    V = c["W"].shape[0]
+    assert res["dhidden_exact"].shape == (T, d) and res["dweight_exact"].shape == (V, d)
+    wts, B = res["weights"], len(c["seq"])
+    cu, n, nr = res["cu_seqlens"], res["n_train"], res["n_roll"]
+    assert list(n) != list(nr)                                     # the two aligned sets differ in this case
+
+    def surrogate(H, W):
+        lpx = scipy.special.log_softmax(H @ W.T, axis=1)[np.arange(T), c["y"]]
+        tot = 0.0
+        for i in range(B):
+            for t in range(int(cu[i]), int(cu[i + 1])):
+                m = int(c["mask"][t])
+                if m != 0 and m != 2:
+                    tot += g * wts[i] / (B * int(n[i])) * 0.5 * (lpx[t] - c["lq"][t]) ** 2
+                if m != 0 and m != 3:
+                    dlt = lpx[t] - c["lb"][t]
+                    tot += g * wts[i] / (B * int(nr[i])) * lam * (math.exp(dlt) * dlt - math.exp(dlt) + 1.0)
+        return tot
+
+    h = 1e-6
+    for (t, k) in itertools.product(range(T), range(d)):
+        Hp, Hm = c["H"].copy(), c["H"].copy()
+        Hp[t, k] += h
+        Hm[t, k] -= h
+        fd = (surrogate(Hp, c["W"]) - surrogate(Hm, c["W"])) / (2 * h)
+        assert abs(fd - res["dhidden_exact"][t, k]) <= 1e-8 + 1e-6 * abs(fd), (t, k)
+    for (v, k) in itertools.product(range(V), range(d)):
+        Wp, Wm = c["W"].copy(), c["W"].copy()
+        Wp[v, k] += h
+        Wm[v, k] -= h
+        fd = (surrogate(c["H"], Wp) - surrogate(c["H"], Wm)) / (2 * h)
+        assert abs(fd - res["dweight_exact"][v, k]) <= 1e-8 + 1e-6 * abs(fd), (v, k)
+    assert np.any(res["dhidden_exact"][0] != 0.0) and not np.any(res["dhidden_exact"][4])   # row 4 is masked
+
+
+def test_projection_gradient_reduces_to_the_stored_logits_pass_and_rounds_the_rows_once():
+    """With the identity as the projection matrix the hidden states ARE the logits: dL/dhidden must be the
+    bf16-rounded gradient rows of the stored-logits pass with the same supplied scores, and dL/dweight the
+    outer-product sum of those rows with the hidden states (checked entry by entry with integer-valued rows)."""
+    rng = _rng(8)
+    V = 6
+    seq = np.array([2, 3], dtype=np.int32)
+    T = 5
+    H = rng.integers(-3, 4, size=(T, V)).astype(np.float64)
+    y = rng.integers(0, V, size=T).astype(np.int32)
+    mask = np.ones(T, dtype=np.uint8)
+    lp = scipy.special.log_softmax(H, axis=1)[np.arange(T), y]
+    lb, lq = lp - 0.2, lp - 0.4
+    f = np.array([0.9, 0.6])
+    res = orc.lm_head_loss_fwd_bwd(H, np.eye(V), y, mask, lb, lq, seq, [0, 1], f, 0.1, 0.5, 2.0)
+    # the stored-logits pass with weights f - xi: coefficient by hand for row 0 of sample 0 (n = 2, B = 2)
+    c0 = 2.0 * (0.9 - 0.1) / (2 * 2) * ((lq[0] - lp[0]) - 0.5 * math.exp(lp[0] - lb[0]) * (lp[0] - lb[0]))
+    row0 = c0 * (np.exp(H[0] - scipy.special.logsumexp(H[0])) - np.eye(V)[y[0]])
+    np.testing.assert_allclose(res["dlogits_exact"][0], row0, rtol=1e-13, atol=1e-16)
+    np.testing.assert_array_equal(res["dhidden"], res["dlogits"])          # identity projection
+    np.testing.assert_array_equal(res["dlogits"], orc.round_to_bf16(res["dlogits_exact"]))
+    for v in range(V):
+        for k in range(V):
+            want = math.fsum(float(res["dlogits"][t, v]) * float(H[t, k]) for t in range(T))
+            assert abs(res["dweight"][v, k] - want) <= 1e-15
+    assert abs(res["loss"] - ((0.8 * (0.4 + 0.5 * orc.kl_estimator(0.2)) + 0.5 * (0.4 + 0.5 * orc.kl_estimator(0.2))) / 2)) < 1e-14

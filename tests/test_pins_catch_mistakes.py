@@ -101,6 +101,18 @@ MISTAKES = {
         "cover_roll[i] = int(n[i]) / (int(cu[i + 1]) - int(cu[i]))"),
     "validity looks at the supervision set only": ("return cover_roll, n_roll, np.minimum(n, n_roll)",
                                                    "return cover_roll, n_roll, n"),
+    "projection gradient: hidden-state gradient contracts the wrong axis": (
+        "dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden))",
+        "dhidden_exact=np.matmul(g, weight[::-1]), dweight_exact=np.matmul(g.T, hidden))"),
+    "projection gradient: weight gradient pairs rows with the wrong tokens": (
+        "dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden))",
+        "dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden[::-1]))"),
+    "projection gradient: rows not rounded to the storage type before the contractions": (
+        "    gb = round_to_bf16(g)\n    return dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, logits=z,",
+        "    gb = g\n    return dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, logits=z,"),
+    "projection gradient: supplied scores ignored": (
+        "    w = freshness_weights(np.asarray(freshness, dtype=np.float64), xi, n_valid)\n    loss = anchored_loss(w, ell, D_roll, lam)\n    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)\n    g = np.zeros((T, V))",
+        "    w = freshness_weights(np.ones(len(n)), xi, n_valid)\n    loss = anchored_loss(w, ell, D_roll, lam)\n    coef = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)\n    g = np.zeros((T, V))"),
     "stale teacher difference reversed": ("eps = lq - np.asarray(teacher_logp_stale, dtype=np.float64)",
                                           "eps = np.asarray(teacher_logp_stale, dtype=np.float64) - lq"),
 }
