@@ -387,12 +387,50 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
                                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Loss and gradient (second loop of Algorithm 1) when the logits are the output projection of the last hidden
+ * states, z_{t,v} = sum_k hidden[t,k] * weight[v,k], and no [T, V] tensor is ever allocated: the pass is carried
+ * through the projection and returns the gradient with respect to the hidden states and to the projection matrix,
+ *   dhidden[t, :]  = sum_v dL/dz[t, v] * weight[v, :],     dweight[v, :] (+)= sum_t dL/dz[t, v] * hidden[t, :],
+ * with dL/dz[t, v] = c_t (softmax(z_t)_v - [v = y_t]) exactly as in fopd_loss_fwd_bwd.
+ *
+ * The rows are processed in chunks of `rows_chunk`: the chunk's logits are formed on the matrix cores into
+ * scratch memory (fp32, not rounded to a storage type), the log-sum-exp and gradient kernels of the stored-logits
+ * path run on them (the gradient rows are written as bf16, as that path stores them), and two more matrix-core
+ * contractions fold the rows into dhidden and dweight; then the scratch is reused.  All work is bf16 inputs with
+ * fp32 accumulation; the result does not depend on rows_chunk except through the order of the fp32 sums over
+ * rows in dweight.
+ *
+ * The freshness scores must be supplied (Algorithm 1 scores the buffer before its minibatch loop; with no logits
+ * kept, fopd_lm_head_token_logprobs followed by fopd_freshness_score gives them from the same inputs):
+ *   freshness_in [B] f32; n_train_in / n_roll_in [B] int32 from fopd_freshness_score, or NULL to count from `mask`.
+ *
+ *   hidden [T, ldh] bf16, weight [V, ldw] bf16, d a multiple of 64; token_ids, mask, behav_logp, teacher_logp,
+ *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
+ *   rows_chunk   rows per chunk, a multiple of 64 (8192 keeps the scratch near 6.5 GB at V = 151,936, d = 4096)
+ *   loss [1], weights [B] (may be NULL), logp [T], lse [T]: f32 outputs
+ *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0
+ *   workspace    fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) bytes, 256-byte aligned, initialised
+ *                once with fopd_workspace_init; the same sticky flags as the other entry points
+ * The first call in a process sets kernel attributes: make one call before capturing it into a HIP graph.
+ */
+size_t fopd_lm_head_loss_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk);
+fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T,
+                                      int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
+                                      const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
+                                      const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                      const int32_t* n_train_in, const int32_t* n_roll_in, float grad_scale,
+                                      int64_t rows_chunk, float* loss, float* weights, float* logp, float* lse,
+                                      float* dhidden, int64_t lddh, float* dweight, int64_t lddw,
+                                      int accumulate_dweight, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
  * is bracketed by HIP events on the launch stream (process-wide state behind the library's mutex; the
  * events are created on first use, so do not enable it around code that may not allocate).
  * fopd_profile_read is HOST-SYNCHRONOUS (waits for the recorded events).
  *   which: 0 = log-sum-exp pass, 1 = gradient pass, 2 = both passes in one kernel (scores supplied),
- *          3 = projection fused with the log-sum-exp.
+ *          3 = projection fused with the log-sum-exp; of fopd_lm_head_loss_fwd_bwd: 4 = logits contraction,
+ *          5 = dhidden contraction, 6 = dweight contraction.
  */
 fopd_status fopd_profile_enable(int on);
 fopd_status fopd_profile_reset(void);

@@ -21,6 +21,7 @@ SYMBOLS = (
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
     "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
     "fopd_lm_head_workspace_bytes", "fopd_lm_head_token_logprobs",
+    "fopd_lm_head_loss_workspace_bytes", "fopd_lm_head_loss_fwd_bwd",
 )
 
 
@@ -82,6 +83,12 @@ def load_library():
     lib.fopd_lm_head_workspace_bytes.argtypes = [i64]
     lib.fopd_lm_head_token_logprobs.restype = ctypes.c_int
     lib.fopd_lm_head_token_logprobs.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_lm_head_loss_workspace_bytes.restype = sz
+    lib.fopd_lm_head_loss_workspace_bytes.argtypes = [i64, i64, i64, i32, i64]
+    lib.fopd_lm_head_loss_fwd_bwd.restype = ctypes.c_int
+    lib.fopd_lm_head_loss_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32, Hparams,
+                                              vp, vp, vp, f32, i64, vp, vp, vp, vp, vp, i64, vp, i64, ctypes.c_int,
+                                              vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -203,6 +210,29 @@ def fopd_lm_head_token_logprobs(hidden, ldh, weight, ldw, T, V, d, token_ids, ma
         int(T), int(V), int(d), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(logp, torch.float32, "logp"), _ptr(lse, torch.float32, "lse"), p, n, _stream(stream))
     _check(st, "fopd_lm_head_token_logprobs")
+
+
+def fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk):
+    return int(load_library().fopd_lm_head_loss_workspace_bytes(int(T), int(V), int(d), int(B), int(rows_chunk)))
+
+
+def fopd_lm_head_loss_fwd_bwd(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, teacher_logp, seq_lens,
+                              lag, B, hp, freshness_in, n_train_in, n_roll_in, grad_scale, rows_chunk, loss, weights,
+                              logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, workspace, stream=None):
+    import torch
+    f32 = torch.float32
+    p, n = _ws(workspace)
+    st = load_library().fopd_lm_head_loss_fwd_bwd(
+        _ptr(hidden, torch.bfloat16, "hidden"), int(ldh), _ptr(weight, torch.bfloat16, "weight"), int(ldw),
+        int(T), int(V), int(d), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
+        _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"),
+        _ptr(n_roll_in, torch.int32, "n_roll_in"), float(grad_scale), int(rows_chunk),
+        _ptr(loss, f32, "loss"), _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"),
+        _ptr(dhidden, f32, "dhidden"), int(lddh), _ptr(dweight, f32, "dweight"), int(lddw),
+        int(bool(accumulate_dweight)), p, n, _stream(stream))
+    _check(st, "fopd_lm_head_loss_fwd_bwd")
 
 
 def fopd_flags_status(flags):

@@ -12,6 +12,7 @@
 #include "fopd.h"
 #include "fopd_kernels.hip"
 #include "fopd_lm_head.hip"
+#include "fopd_gemm.hip"
 
 namespace {
 
@@ -78,6 +79,39 @@ namespace {
 // device (with that device current) and kept; host code uses that address, never the symbol's name.
 void* g_scratch_ptr[64] = {};
 
+// Workspace of the loss pass through the projection: flags, offsets and counts, the per-chunk O(R) arrays, then
+// the chunk's fp32 logits, its bf16 gradient rows, their transpose, the transposed hidden chunk and the
+// transposed projection matrix.  ldz = V rounded up to 64 (the k-extent of the dL/dhidden contraction).
+struct LmLossWorkspace {
+  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0, gt = 0,
+         ht = 0, wt = 0, total = 0;
+  int64_t ldz = 0, r_pad = 0, n_chunks = 0;
+  LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk) {
+    const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
+    const int64_t t = T < 0 ? 0 : T;
+    const int64_t rc = rows_chunk < 64 ? 64 : rows_chunk;
+    const size_t r = static_cast<size_t>(t < rc ? (t + 63) / 64 * 64 : rc);     // rows of the largest chunk, padded
+    r_pad = static_cast<int64_t>(r);
+    n_chunks = (t + rc - 1) / rc;
+    ldz = (V + 63) / 64 * 64;
+    const size_t v = static_cast<size_t>(V < 0 ? 0 : V), dd = static_cast<size_t>(d < 0 ? 0 : d);
+    size_t off = 0;
+    flags = Workspace::take(off, 4 * sizeof(int32_t));
+    cu = Workspace::take(off, (b + 1) * sizeof(int64_t));
+    n_train = Workspace::take(off, b * sizeof(int32_t));
+    n_roll = Workspace::take(off, b * sizeof(int32_t));
+    coef = Workspace::take(off, r * sizeof(float));
+    partials = Workspace::take(off, (r / kStreamThreads + 2) * sizeof(double));
+    chunk_loss = Workspace::take(off, static_cast<size_t>(n_chunks + 1) * sizeof(float));
+    z = Workspace::take(off, r * static_cast<size_t>(ldz) * sizeof(float));
+    g = Workspace::take(off, r * static_cast<size_t>(ldz) * 2);
+    gt = Workspace::take(off, v * r * 2);
+    ht = Workspace::take(off, dd * r * 2);
+    wt = Workspace::take(off, dd * static_cast<size_t>(ldz) * 2);
+    total = off;
+  }
+};
+
 template <typename P>
 inline P* at(void* ws, size_t off) {
   return reinterpret_cast<P*>(static_cast<char*>(ws) + off);
@@ -108,10 +142,11 @@ inline fopd_status launched() { return hipGetLastError() == hipSuccess ? FOPD_OK
 std::mutex g_state_mutex;
 
 // ---- optional per-kernel timing ---------------------------------------------------------
+constexpr int kProfSlots = 8;
 struct Profiler {
   bool on = false;
-  std::vector<hipEvent_t> start[4], stop[4];
-  size_t used[4] = {0, 0, 0, 0};
+  std::vector<hipEvent_t> start[kProfSlots], stop[kProfSlots];
+  size_t used[kProfSlots] = {};
 } g_prof;
 
 // Brackets the launches made during its lifetime with a pair of events when timing is switched on.
@@ -774,6 +809,156 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   return launched();
 }
 
+size_t fopd_lm_head_loss_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk) {
+  return LmLossWorkspace(T, V, d, B, rows_chunk).total;
+}
+
+// Out[n, m] (+)= sum_k Bn[n, k] Am[m, k] on `s`; `slot` = timing slot of this contraction.
+static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, int64_t M, const __bf16* Bn, int64_t ldb,
+                               int64_t N, int64_t K, float* Out, int64_t ldo, int slot, hipStream_t s) {
+  if (M <= 0 || N <= 0) return FOPD_OK;
+  if (K <= 0 || K % 64 != 0 || M > 2147483647LL || N > 2147483647LL || K > 2147483647LL) return FOPD_ESHAPE;
+  // byte offsets inside one 256-row operand tile are 32-bit
+  if (256 * lda * 2 >= 2147483648LL || 256 * ldb * 2 >= 2147483648LL) return FOPD_ESHAPE;
+  static bool allowed[2][kMaxDevices] = {};
+  const void* kern = accumulate ? reinterpret_cast<const void*>(fopd_gemm_nt<true>)
+                                : reinterpret_cast<const void*>(fopd_gemm_nt<false>);
+  if (allow_dynamic_lds(kern, kGemmLdsBytes, allowed[accumulate ? 1 : 0]) != FOPD_OK) return FOPD_EHIP;
+  const int tiles_m = static_cast<int>((M + kGemmTile - 1) / kGemmTile);
+  const int tiles_n = static_cast<int>((N + kGemmTile - 1) / kGemmTile);
+  const int64_t rounds = static_cast<int64_t>((tiles_m + 7) / 8) * ((tiles_n + 31) / 32);
+  if (rounds * 256 > 2147483647LL) return FOPD_ESHAPE;
+  const dim3 grid(static_cast<unsigned>(rounds * 256)), block(kGemmThreads);
+  ScopedTimer timer(slot, s);
+  if (accumulate)
+    fopd_gemm_nt<true><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
+                                                          static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
+  else
+    fopd_gemm_nt<false><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
+                                                           static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
+  return launched();
+}
+
+static fopd_status launch_transpose(const void* in, int64_t ld_in, int64_t rows, int64_t cols, void* out, int64_t ld_out,
+                                    int64_t rows_pad, hipStream_t s) {
+  if (rows_pad <= 0 || cols <= 0) return FOPD_OK;
+  const dim3 grid(static_cast<unsigned>((rows_pad + 63) / 64), static_cast<unsigned>((cols + 63) / 64));
+  if (grid.y > 65535u) {      // the second grid dimension is short: walk it in slabs
+    for (int64_t c0 = 0; c0 < cols; c0 += 65535LL * 64) {
+      const int64_t cn = (cols - c0 < 65535LL * 64) ? cols - c0 : 65535LL * 64;
+      const dim3 g2(grid.x, static_cast<unsigned>((cn + 63) / 64));
+      fopd_transpose_bf16<<<g2, 256, 0, s>>>(static_cast<const uint16_t*>(in) + c0, ld_in, static_cast<int>(rows),
+                                             static_cast<int>(cn), static_cast<uint16_t*>(out) + c0 * ld_out, ld_out,
+                                             static_cast<int>(rows_pad));
+      if (launched() != FOPD_OK) return FOPD_EHIP;
+    }
+    return FOPD_OK;
+  }
+  fopd_transpose_bf16<<<grid, 256, 0, s>>>(static_cast<const uint16_t*>(in), ld_in, static_cast<int>(rows),
+                                           static_cast<int>(cols), static_cast<uint16_t*>(out), ld_out,
+                                           static_cast<int>(rows_pad));
+  return launched();
+}
+
+fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T,
+                                      int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
+                                      const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
+                                      const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                      const int32_t* n_train_in, const int32_t* n_roll_in, float grad_scale,
+                                      int64_t rows_chunk, float* loss, float* weights, float* logp, float* lse,
+                                      float* dhidden, int64_t lddh, float* dweight, int64_t lddw,
+                                      int accumulate_dweight, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0 || T > 2147483647LL || V <= 0 || V > 2147483647LL - 64 || d <= 0 || d % 64 != 0 || ldh < d || ldw < d ||
+      lddh < d || lddw < d || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
+    return FOPD_ESHAPE;
+  if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
+      teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || freshness_in == nullptr ||
+      loss == nullptr || logp == nullptr || lse == nullptr || dhidden == nullptr || dweight == nullptr)
+    return FOPD_EINVAL;
+  if (n_roll_in != nullptr && n_train_in == nullptr) return FOPD_EINVAL;
+  if (misaligned(hidden, 16) || misaligned(weight, 16) || (ldh * 2) % 16 != 0 || (ldw * 2) % 16 != 0 ||
+      misaligned(dhidden, 16) || misaligned(dweight, 16))
+    return FOPD_EALIGN;
+  const LmLossWorkspace lay(T, V, d, B, rows_chunk);
+  if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
+
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  fopd_status st;
+  int32_t* flags = at<int32_t>(workspace, lay.flags);
+  int64_t* cu = at<int64_t>(workspace, lay.cu);
+  int32_t* nws = at<int32_t>(workspace, lay.n_train);
+  int32_t* nrws = at<int32_t>(workspace, lay.n_roll);
+  float* coef = at<float>(workspace, lay.coef);
+  double* partials = at<double>(workspace, lay.partials);
+  float* chunk_loss = at<float>(workspace, lay.chunk_loss);
+  float* Z = at<float>(workspace, lay.z);
+  __bf16* G = at<__bf16>(workspace, lay.g);
+  __bf16* Gt = at<__bf16>(workspace, lay.gt);
+  __bf16* Ht = at<__bf16>(workspace, lay.ht);
+  __bf16* Wt = at<__bf16>(workspace, lay.wt);
+  const __bf16* Hm = static_cast<const __bf16*>(hidden);
+  const __bf16* Wm = static_cast<const __bf16*>(weight);
+  const int64_t ldz = lay.ldz;
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  const int32_t* n_use = n_train_in;
+  const int32_t* nr_use = n_roll_in;
+  if (n_train_in == nullptr) {
+    fopd_count_train<<<B, kSegThreads, 0, s>>>(mask, cu, T, nws, nrws);
+    if ((st = launched()) != FOPD_OK) return st;
+    n_use = nws;
+    nr_use = nrws;
+  }
+  // the projection matrix with the vocabulary contiguous (zero beyond V), once per call
+  if ((st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
+
+  int64_t ci = 0;
+  for (int64_t a = 0; a < T; a += rows_chunk, ++ci) {
+    const int64_t R = (T - a < rows_chunk) ? T - a : rows_chunk;
+    const int64_t Rp = (R + 63) / 64 * 64;
+    const __bf16* Hc = Hm + a * ldh;
+    // logits of the chunk, fp32, never rounded to the storage type of stored logits
+    if ((st = launch_gemm(false, Wm, ldw, V, Hc, ldh, R, d, Z, ldz, 4, s)) != FOPD_OK) return st;
+    if ((st = launch_k1(Z, FOPD_F32, R, V, ldz, token_ids + a, mask == nullptr ? nullptr : mask + a, logp + a, lse + a,
+                        nullptr, nullptr, flags, s)) != FOPD_OK)
+      return st;
+    const int64_t nblk = (R + kStreamThreads - 1) / kStreamThreads;
+    fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp + a, behav_logp + a, teacher_logp + a, mask == nullptr ? nullptr : mask + a, cu, n_use, nr_use, lag, nullptr,
+        freshness_in, R, B, a, hp, grad_scale, coef, partials, flags);
+    if ((st = launched()) != FOPD_OK) return st;
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi,
+                                              chunk_loss + ci, weights, nullptr);
+    if ((st = launched()) != FOPD_OK) return st;
+    {
+      ScopedTimer timer(1, s);
+      fopd_k4_grad_wide<<<static_cast<unsigned>(R), kGradThreads, 0, s>>>(
+          Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), token_ids + a, lse + a, logp + a, coef);
+      if ((st = launched()) != FOPD_OK) return st;
+    }
+    // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
+    if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dhidden + a * lddh, lddh, 5, s)) != FOPD_OK) return st;
+    // dL/dweight: vocabulary x hidden, contraction over the chunk's rows (zero-padded to a multiple of 64)
+    if ((st = launch_transpose(G, ldz, R, V, Gt, Rp, Rp, s)) != FOPD_OK) return st;
+    if ((st = launch_transpose(Hc, ldh, R, d, Ht, Rp, Rp, s)) != FOPD_OK) return st;
+    const bool acc = (ci > 0) || (accumulate_dweight != 0);
+    if ((st = launch_gemm(acc, Ht, Rp, d, Gt, Rp, V, Rp, dweight, lddw, 6, s)) != FOPD_OK) return st;
+  }
+  if (T == 0) {      // an empty batch: loss 0, the weights of the scores, a zero projection gradient
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi, loss,
+                                              weights, nullptr);
+    if ((st = launched()) != FOPD_OK) return st;
+    if (accumulate_dweight == 0) {
+      fopd_fill_zero_f32<<<static_cast<unsigned>(V), 256, 0, s>>>(dweight, lddw, static_cast<int>(d));
+      return launched();
+    }
+    return FOPD_OK;
+  }
+  fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);
+  return launched();
+}
+
 fopd_status fopd_set_option(const char* name, int value) {
   if (name == nullptr) return FOPD_EINVAL;
   const std::string key(name);
@@ -799,12 +984,12 @@ fopd_status fopd_profile_enable(int on) {
 
 fopd_status fopd_profile_reset(void) {
   std::lock_guard<std::mutex> lock(g_state_mutex);
-  g_prof.used[0] = g_prof.used[1] = g_prof.used[2] = g_prof.used[3] = 0;
+  for (int i = 0; i < kProfSlots; ++i) g_prof.used[i] = 0;
   return FOPD_OK;
 }
 
 fopd_status fopd_profile_read(int which, double* total_ms_host, int64_t* launches_host) {
-  if (which < 0 || which > 3 || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
+  if (which < 0 || which >= kProfSlots || total_ms_host == nullptr || launches_host == nullptr) return FOPD_EINVAL;
   std::vector<hipEvent_t> start, stop;
   {
     std::lock_guard<std::mutex> lock(g_state_mutex);

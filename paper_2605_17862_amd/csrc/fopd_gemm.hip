@@ -1,0 +1,276 @@
+// Dense bf16 contractions on the matrix cores of gfx950 (CDNA4), and the small kernels around them, for the
+// loss pass whose logits are the output projection of the hidden states and are made chunk by chunk:
+//
+//   fopd_gemm_nt            Out[n, m] (+)= sum_k Bn[n, k] * Am[m, k]     bf16 in, fp32 accumulate, fp32 out
+//   fopd_transpose_bf16     out[c, r] = in[r, c], zero-padded along r    (brings an operand into k-contiguous form)
+//   fopd_k4_grad_wide       gradient rows from fp32 logits to bf16        c_t (softmax(z_t) - onehot)
+//
+// The three contractions of one chunk of R rows (d hidden size, V vocabulary) all have this one form, both
+// operands k-contiguous:
+//   logits      Z[R, V]   = H[R, d]     . W[V, d]^T          n = row,   m = vocabulary entry, k = hidden element
+//   dL/dhidden  dH[R, d]  = dZ[R, V]    . (W^T)[d, V]^T      n = row,   m = hidden element,   k = vocabulary entry
+//   dL/dweight  dW[V, d] += (dZ^T)[V, R] . (H^T)[d, R]^T     n = vocabulary entry, m = hidden element, k = row
+//
+// Tiling and memory pipeline are those of the projection kernel fused with the log-sum-exp
+// (fopd_lm_head.hip): a workgroup of eight wavefronts (2 along m x 4 along n) owns a 256 x 256 tile of the
+// result; each wavefront holds 128 (m) x 64 (n) of it as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16;
+// stages of 32 k-elements of both operand tiles are filled by direct global -> LDS loads and read back as
+// 16-byte fragments through an XOR-swizzled map without bank conflicts.  The m side of the instruction is the
+// side a lane holds four consecutive entries of, so it is the contiguous side of the output.
+
+#ifndef FOPD_GEMM_HIP_
+#define FOPD_GEMM_HIP_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fopd_kernels.hip"
+#include "fopd_lm_head.hip"
+
+namespace fopd {
+
+constexpr int kGemmTile = kLmTile;          // 256 x 256 result tile
+constexpr int kGemmThreads = kLmThreads;    // 8 wavefronts
+constexpr int kGemmLdsBytes = kLmStages * kLmStageBytes;
+
+// ACCUMULATE = false: Out = product; true: Out += product (the caller's array holds the running sum).
+// K must be a positive multiple of 64; rows past the end of an operand are clamped (re-read) and their
+// results discarded.  Byte offsets inside one 256-row operand tile must fit 32 bits (checked on the host).
+template <bool ACCUMULATE>
+__global__ void __launch_bounds__(kGemmThreads)
+fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __restrict__ Bn, int64_t ldb, int N,
+             int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
+  extern __shared__ __align__(16) unsigned char gemm_smem[];
+  constexpr int WN = 4;
+  constexpr int NJ = 8 / WN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // Workgroups go to the eight XCDs in turn (id mod 8).  The 32 that an XCD runs together are 4 tiles along n
+  // x 8 tiles along m, so that each L2 serves 4 + 8 operand tiles to 32 users.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int m_blocks = (tiles_m + 7) >> 3;
+  const int round = slot >> 5;
+  const int tile_m = ((round % m_blocks) << 3) + ((slot >> 2) & 7);
+  const int tile_n = ((((round / m_blocks) << 3) + xcd) << 2) + (slot & 3);
+  if (tile_m >= tiles_m || tile_n >= tiles_n) return;      // whole workgroup, before any barrier
+  const int m0 = tile_m * kGemmTile, n0 = tile_n * kGemmTile;
+
+  // global -> LDS copy: see the projection kernel.  Wavefront w issues instructions 2 w and 2 w + 1 of each
+  // operand tile; instruction q fills rows 16 q .. 16 q + 15; lane i writes (row 16 q + i / 4, slot i % 4) and
+  // fetches logical 16-byte chunk (i % 4) ^ ((i / 16) % 4) of that row.
+  const int cp_row = wave * 32 + (lane >> 2);
+  const int cp_chunk = (lane & 3) ^ ((lane >> 4) & 3);
+  const int cp_lds = wave * 2048;
+  const char* Ab = reinterpret_cast<const char*>(Am) + static_cast<int64_t>(m0) * lda * 2;
+  const char* Bb = reinterpret_cast<const char*>(Bn) + static_cast<int64_t>(n0) * ldb * 2;
+  uint32_t a_src[2], b_src[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    a_src[q] = static_cast<uint32_t>(min(cp_row + 16 * q, M - 1 - m0)) * static_cast<uint32_t>(lda) * 2u + cp_chunk * 16;
+    b_src[q] = static_cast<uint32_t>(min(cp_row + 16 * q, N - 1 - n0)) * static_cast<uint32_t>(ldb) * 2u + cp_chunk * 16;
+  }
+  auto load_pair = [&](int ko, int pb) {
+    const int64_t kb = static_cast<int64_t>(ko) * 2;
+    unsigned char* dst = gemm_smem + 2 * pb * kLmStageBytes + cp_lds;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      lm_load_to_lds(Ab + kb, a_src[q], dst + q * 1024);
+      lm_load_to_lds(Ab + kb + 64, a_src[q], dst + kLmStageBytes + q * 1024);
+      lm_load_to_lds(Bb + kb, b_src[q], dst + kLmOperandBytes + q * 1024);
+      lm_load_to_lds(Bb + kb + 64, b_src[q], dst + kLmStageBytes + kLmOperandBytes + q * 1024);
+    }
+  };
+
+  const int frag_row = (lane & 31) * 64;
+  const int a_off = wm * 128 * 64 + frag_row;
+  const int b_off = kLmOperandBytes + wn * NJ * 32 * 64 + frag_row;
+  int xk[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) xk[ks] = ((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) << 4;
+
+  f32x16 acc[4][NJ];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int n_pairs = K / 64;
+  int p_ld = 0;
+  auto request_next = [&](int pb) {           // the last pair is requested again at the tail (never read)
+    load_pair(p_ld * 64, pb);
+    if (p_ld + 1 < n_pairs) ++p_ld;
+  };
+
+  bf16x8 fa[2][4], fb[2][NJ];
+  auto read_frags = [&](int buf, const unsigned char* stage, int ks) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 2048 + xk[ks]);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 2048 + xk[ks]);
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+  };
+
+  // Same schedule as the projection kernel: two pairs of stages in the LDS; while pair p multiplies, pair p + 1
+  // lands; one barrier per pair.  Loads complete in order: after the prologue's two requests (8 instructions per
+  // wavefront each), "at most 8 outstanding" means pair 0 has landed.
+  request_next(0);
+  request_next(1);
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  __syncthreads();
+  read_frags(0, gemm_smem, 0);
+  for (int p = 0; p < n_pairs; ++p) {
+    const int pb = p & 1;
+    const unsigned char* lo = gemm_smem + 2 * pb * kLmStageBytes;
+    const unsigned char* hi = lo + kLmStageBytes;
+    const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kLmStageBytes;
+    read_frags(1, lo, 1);
+    multiply(0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(0, hi, 0);
+    multiply(1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(1, hi, 1);
+    multiply(0);
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    request_next(pb);
+    read_frags(0, next, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
+
+  // Result register r of block (i, j): m = 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's 128,
+  // n = 32 j + lane % 32 of its 64.  Four consecutive m per lane: one 16-byte access when they all exist.
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int n = n0 + wn * 64 + 32 * j + (lane & 31);
+    if (n >= N) continue;
+    float* orow = Out + static_cast<int64_t>(n) * ldo;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m = m0 + wm * 128 + 32 * i + 8 * g + ((lane >> 5) << 2);
+        if (m + 3 < M && (ldo & 3) == 0) {
+          float4* p = reinterpret_cast<float4*>(orow + m);
+          float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
+          if (ACCUMULATE) {
+            const float4 o = *p;
+            v.x += o.x;
+            v.y += o.y;
+            v.z += o.z;
+            v.w += o.w;
+          }
+          *p = v;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (m + e < M) {
+              if (ACCUMULATE) orow[m + e] += acc[i][j][4 * g + e];
+              else orow[m + e] = acc[i][j][4 * g + e];
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// out[c, r] = in[r, c] for r < rows, c < cols; out[c, r] = 0 for rows <= r < rows_pad.  64 x 64 tiles through
+// the LDS; grid (ceil(rows_pad / 64), ceil(cols / 64)), 256 lanes.
+__global__ void __launch_bounds__(256)
+fopd_transpose_bf16(const uint16_t* __restrict__ in, int64_t ld_in, int rows, int cols, uint16_t* __restrict__ out,
+                    int64_t ld_out, int rows_pad) {
+  __shared__ uint16_t tile[64][66];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int rr = ty; rr < 64; rr += 4) {
+    const int r = r0 + rr, c = c0 + tx;
+    tile[rr][tx] = (r < rows && c < cols) ? in[static_cast<int64_t>(r) * ld_in + c] : static_cast<uint16_t>(0);
+  }
+  __syncthreads();
+  for (int cc = ty; cc < 64; cc += 4) {
+    const int c = c0 + cc, r = r0 + tx;
+    if (c < cols && r < rows_pad) out[static_cast<int64_t>(c) * ld_out + r] = tile[tx][cc];
+  }
+}
+
+// Gradient rows of one chunk from fp32 logits (ldz floats per row) to bf16 (ldg entries per row):
+//   g[t, v] = c_t (exp(z[t, v] - lse_t) - [v == y_t]),  columns V .. ldg - 1 written as zeros
+// (they are the zero padding of the contraction that follows).  One workgroup per row; rows with c_t == 0 or
+// an out-of-range token id are zero-filled without reading the logits.
+__global__ void __launch_bounds__(kGradThreads)
+fopd_k4_grad_wide(const float* __restrict__ Z, int64_t ldz, uint16_t* __restrict__ G, int64_t ldg, int V,
+                  const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
+                  const float* __restrict__ logp, const float* __restrict__ coef) {
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const float c = coef[t];
+  const int y = token_ids[t];
+  uint16_t* orow = G + t * ldg;
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int nvec_out = static_cast<int>(ldg / 8);
+  if (c == 0.f || y < 0 || y >= V) {
+    const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+    for (int j = tid; j < nvec_out; j += kGradThreads) __builtin_nontemporal_store(zero, ov + j);
+    return;
+  }
+  const float lseL = lse[t] * kLog2e;
+  const float gy = c * expm1f(logp[t]);
+  const float* zrow = Z + t * ldz;
+  const u32x4* zv = reinterpret_cast<const u32x4*>(zrow);
+  const int nfull = V / 8;                       // output vectors made of eight existing logits
+  for (int j = tid; j < nfull; j += kGradThreads) {
+    const u32x4 q0 = __builtin_nontemporal_load(zv + 2 * j);
+    const u32x4 q1 = __builtin_nontemporal_load(zv + 2 * j + 1);
+    float x[8];
+    unpack<FOPD_F32>(q0, x);
+    unpack<FOPD_F32>(q1, x + 4);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+    if (j == (y >> 3)) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e == (y & 7)) x[e] = gy;
+    }
+    __builtin_nontemporal_store(pack<FOPD_BF16>(x), ov + j);
+  }
+  for (int v = nfull * 8 + tid; v < static_cast<int>(ldg); v += kGradThreads) {    // ragged tail, then the padding
+    float g = 0.f;
+    if (v < V) {
+      g = c * fast_exp2(fmaf(zrow[v], kLog2e, -lseL));
+      if (v == y) g = gy;
+    }
+    store_elem<FOPD_BF16>(orow, v, g);
+  }
+}
+
+// Zeroes the first `cols` entries of every row (one workgroup per row) of an fp32 matrix.
+__global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld, int cols) {
+  float* row = out + static_cast<int64_t>(blockIdx.x) * ld;
+  for (int c = threadIdx.x; c < cols; c += 256) row[c] = 0.f;
+}
+
+// loss = sum of the per-chunk shares, in chunk order.
+__global__ void fopd_sum_chunks(const float* chunk_loss, int n, float* loss) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += static_cast<double>(chunk_loss[i]);
+    loss[0] = static_cast<float>(s);
+  }
+}
+
+}  // namespace fopd
+
+#endif  // FOPD_GEMM_HIP_

@@ -1,0 +1,160 @@
+"""GPU parity of fopd_lm_head_loss_fwd_bwd: the second loop of Algorithm 1 on logits that are the projection of
+the hidden states and exist only chunk by chunk, with the gradient carried to the hidden states and to the
+projection matrix on the matrix cores.  Oracle: lm_head_loss_fwd_bwd (float64)."""
+
+import numpy as np
+import pytest
+import torch
+
+from harness import workloads as wl
+from oracle import fopd_oracle as orc
+from paper_2605_17862_amd import binding as fb
+from parity_util import assert_close, coef_uncertainty, np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print("[gpu-projection-loss] " + msg, flush=True)
+
+
+def _aligned(nbytes):
+    ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=DEV)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + nbytes]
+    fb.fopd_workspace_init(ws)
+    return ws
+
+
+def _scores_from_the_oracle(w, hp):
+    """First loop of Algorithm 1 in the oracle (float64), rounded to the float32 array both sides receive."""
+    d = w["d"]
+    lse, lp = orc.lm_head_token_logprobs(np64(w["hidden"])[:, :d], np64(w["weight"])[:, :d], np64(w["token_ids"]),
+                                         np64(w["mask"]))
+    _, _, _, k_roll, k_sup = orc.token_terms(lp, np64(w["behav_logp"]), np64(w["teacher_logp"]), None)
+    cu = orc.segment_offsets(w["seq_lens_host"])
+    D_roll, D_sup, _, _, _ = orc.sample_statistics(lp, np64(w["teacher_logp"]), k_roll, k_sup, np64(w["mask"]), cu)
+    _, _, n_valid = orc.roll_coverage(np64(w["mask"]), cu)
+    f = orc.freshness_score(D_roll, D_sup, w["lag_host"], n_valid, hp[0], hp[1])
+    return f.astype(np.float32)
+
+
+def _run(w, hp, g, rows_chunk, f32_scores, accumulate=False, dweight=None, counts=None):
+    T, V, d, B = w["T"], w["V"], w["d"], w["B"]
+    ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+    out = dict(loss=torch.full((1,), 7.0, device=DEV), weights=torch.empty(B, device=DEV),
+               logp=torch.full((T,), 7.0, device=DEV), lse=torch.full((T,), 7.0, device=DEV),
+               dhidden=torch.full((T, d), 7.0, device=DEV),
+               dweight=torch.full((V, d), 7.0, device=DEV) if dweight is None else dweight, ws=ws)
+    n_in, nr_in = (None, None) if counts is None else counts
+    fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                 w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp,
+                                 torch.from_numpy(f32_scores).to(DEV), n_in, nr_in, g, rows_chunk, out["loss"],
+                                 out["weights"], out["logp"], out["lse"], out["dhidden"], d, out["dweight"], d,
+                                 accumulate, ws)
+    torch.cuda.synchronize()
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    return out
+
+
+def _compare(w, hp, g, out, f32_scores):
+    d, V, B = w["d"], w["V"], w["B"]
+    H, W = np64(w["hidden"])[:, :d], np64(w["weight"])[:, :d]
+    mask = np64(w["mask"])
+    ref = orc.lm_head_loss_fwd_bwd(H, W, np64(w["token_ids"]), mask, np64(w["behav_logp"]), np64(w["teacher_logp"]),
+                                   w["seq_lens_host"], w["lag_host"], f32_scores.astype(np.float64), hp[2], hp[3], g)
+    assert_close("logp", np64(out["logp"]), ref["logp"], atol=1e-4)
+    assert_close("lse", np64(out["lse"]), ref["lse"], atol=1e-4)
+    assert_close("weights", np64(out["weights"]), ref["weights"], rtol=1e-6, atol=1e-9)
+    assert abs(float(out["loss"]) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12, (float(out["loss"]), ref["loss"])
+    # The gradient rows the GPU contracts are bf16 values within 2 ulp (plus the coefficient's own uncertainty)
+    # of the oracle's bf16 rows; each output is a sum of such rows times exact bf16 operands, in fp32:
+    #   |dH - dH_ref| <= sum_v (2^-7 |g| + |p - onehot| eps_c) |W|  +  2^-20 sum_v |g| |W|
+    eps_c = coef_uncertainty(ref, hp, g, B, mask)
+    pm = np.exp(ref["logits"] - ref["lse"][:, None])
+    pm[np.arange(len(pm)), np64(w["token_ids"])] -= 1.0
+    pm[mask == 0] = 0.0
+    dg = 2.0 ** -7 * np.abs(ref["dlogits"]) + np.abs(pm) * eps_c[:, None] + 2.0 ** -20 * np.abs(ref["dlogits"])
+    lim_h = dg @ np.abs(W) + 1e-30
+    lim_w = dg.T @ np.abs(H) + 1e-30
+    got_h, got_w = np64(out["dhidden"]), np64(out["dweight"])
+    err_h, err_w = np.abs(got_h - ref["dhidden"]), np.abs(got_w - ref["dweight"])
+    assert np.all(err_h <= lim_h), "dhidden: worst error / bound %.3f at %s" % (
+        float((err_h / lim_h).max()), np.unravel_index(np.argmax(err_h / lim_h), err_h.shape))
+    assert np.all(err_w <= lim_w), "dweight: worst error / bound %.3f at %s" % (
+        float((err_w / lim_w).max()), np.unravel_index(np.argmax(err_w / lim_w), err_w.shape))
+    # what is actually observed, against the scale of the result (the bound above is a worst case)
+    rel_h = float(err_h.max() / np.abs(ref["dhidden"]).max())
+    rel_w = float(err_w.max() / np.abs(ref["dweight"]).max())
+    _say("max |err| / max |value|: dhidden %.2e, dweight %.2e; worst err / bound: %.3f, %.3f"
+         % (rel_h, rel_w, float((err_h / lim_h).max()), float((err_w / lim_w).max())))
+    assert rel_h < 2e-3 and rel_w < 2e-3
+    dead = mask == 0
+    assert not np.any(got_h[dead]) and np.any(got_h[~dead])
+    return ref
+
+
+CASES = {
+    # T-split, d, V, ldh, ldw, masked_every, rows_chunk: ragged tiles on every side, several chunks, a ragged last chunk
+    "ragged": ((90, 130, 80), 128, 1000, 136, 128, 7, 128),
+    "one_chunk": ((40, 60), 64, 5003, 64, 72, 0, 256),
+    "exact_tiles": ((256, 256), 192, 2048, 192, 192, 0, 256),
+    "wide_vocab": ((150, 170, 200), 256, 40000, 256, 256, 5, 192),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_projection_loss_and_gradients(name):
+    seq, d, V, ldh, ldw, every, rows_chunk = CASES[name]
+    T = sum(seq)
+    _say("%s: T=%d d=%d V=%d chunks of %d rows" % (name, T, d, V, rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=5, masked_every=every, ldh=ldh, ldw=ldw)
+    lag = [0, 3, 40][:len(seq)]                       # the third sample, where there is one, is gated
+    w = wl.attach_loss_inputs(h, seq, lag, seed=5)
+    hp, g = (1.0, 1.0, 0.05, 0.3), 1.7
+    f = _scores_from_the_oracle(w, hp)
+    out = _run(w, hp, g, rows_chunk, f)
+    ref = _compare(w, hp, g, out, f)
+    if len(seq) == 3:
+        assert ref["weights"][2] == 0.0 and float(out["weights"][2]) == 0.0
+        assert not bool(out["dhidden"][seq[0] + seq[1]:].any())
+
+
+def test_projection_loss_accumulates_into_dweight_and_ignores_the_chunk_size():
+    seq, d, V = (70, 50), 128, 3000
+    T = sum(seq)
+    h = wl.generate_lm_head(T, d, V, DEV, seed=9, masked_every=6)
+    w = wl.attach_loss_inputs(h, seq, [1, 2], seed=9)
+    hp, g = (1.0, 1.0, 0.0, 0.2), 1.0
+    f = _scores_from_the_oracle(w, hp)
+    one = _run(w, hp, g, 1024, f)                                 # a single chunk
+    many = _run(w, hp, g, 64, f)                                  # two chunks (64 + 56 rows)
+    assert torch.equal(one["logp"], many["logp"]) and torch.equal(one["dhidden"], many["dhidden"])
+    assert torch.allclose(one["dweight"], many["dweight"], rtol=1e-5, atol=1e-9)     # fp32 sums over rows, other order
+    assert abs(float(one["loss"]) - float(many["loss"])) <= 2e-6 * abs(float(one["loss"]))
+    base = torch.full((V, d), 0.5, device=DEV)
+    acc = _run(w, hp, g, 64, f, accumulate=True, dweight=base.clone())
+    assert torch.allclose(acc["dweight"], many["dweight"] + 0.5, rtol=1e-6, atol=1e-7)
+    # counts passed in instead of taken from the mask: the same result
+    cu = orc.segment_offsets(w["seq_lens_host"])
+    n = torch.from_numpy(orc.trainable_counts(np64(w["mask"]), cu)).to(DEV)
+    given = _run(w, hp, g, 64, f, counts=(n, None))
+    assert torch.equal(given["dhidden"], many["dhidden"]) and torch.equal(given["dweight"], many["dweight"])
+
+
+def test_projection_loss_rejects_bad_arguments():
+    h = wl.generate_lm_head(64, 64, 100, DEV, seed=1)
+    w = wl.attach_loss_inputs(h, (64,), [0], seed=1)
+    f = np.ones(1, dtype=np.float32)
+    with pytest.raises(fb.FopdError) as e:
+        _run(w, (1, 1, 0, 0), 1.0, 100, f)                        # rows_chunk not a multiple of 64
+    assert e.value.status == 2
+    ws = _aligned(1024)
+    t = torch.empty(64, device=DEV)
+    with pytest.raises(fb.FopdError) as e:
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], 64, w["weight"], 64, 64, 100, 64, w["token_ids"], None, w["behav_logp"],
+                                     w["teacher_logp"], w["seq_lens"], w["lag"], 1, (1, 1, 0, 0),
+                                     torch.ones(1, device=DEV), None, None, 1.0, 64, t[:1], None, t, t.clone(),
+                                     torch.empty(64, 64, device=DEV), 64, torch.empty(100, 64, device=DEV), 64, 0, ws)
+    assert e.value.status == 5                                     # workspace too small
