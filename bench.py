@@ -180,6 +180,91 @@ def bench_lm_head(args, torch, fb, wl, steps=None):
                      "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}
 
 
+def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=8192):
+    """Result record for fopd_lm_head_loss_fwd_bwd: loss, dL/dhidden and dL/dweight from hidden states (d = 4096),
+    the [V, d] projection and scores computed beforehand, on the rows, mask and lags of the workload; the
+    logits exist only as one chunk of `rows_chunk` rows at a time."""
+    import numpy as np
+    steps = args.steps if steps is None else steps
+    seq_lens, mask = wl.structure_only(args.workload, seed=0)
+    lag = np.random.RandomState(0).randint(0, 5, size=len(seq_lens)).astype(np.int32)
+    T, d, V, B = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"]), len(seq_lens)
+    w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, "cuda:0", seed=0), seq_lens, lag, seed=0)
+    w["mask"] = torch.from_numpy(mask).to("cuda:0")
+
+    def aligned(nbytes):
+        ws = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda:0")
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + nbytes]
+        fb.fopd_workspace_init(ws)
+        return ws
+
+    f32 = dict(dtype=torch.float32, device="cuda:0")
+    logp, lse = torch.empty(T, **f32), torch.empty(T, **f32)
+    # first loop of Algorithm 1 without logits: log-probs from the fused projection kernel, then the scores
+    ws1 = aligned(fb.fopd_lm_head_workspace_bytes(T))
+    fb.fopd_lm_head_token_logprobs(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"], logp, lse, ws1)
+    ws2 = aligned(fb.fopd_workspace_bytes(T, B))
+    fresh, n_train, n_roll = torch.empty(B, **f32), torch.empty(B, dtype=torch.int32, device="cuda:0"), \
+        torch.empty(B, dtype=torch.int32, device="cuda:0")
+    fb.fopd_freshness_score(logp, w["behav_logp"], None, None, w["teacher_logp"], None, w["mask"], w["seq_lens"],
+                            w["lag"], T, B, hp, None, n_train, n_roll, None, None, None, None, None, fresh, None, ws2)
+    del ws1, ws2
+    ws = aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+    loss, weights = torch.empty(1, **f32), torch.empty(B, **f32)
+    dh, dw = torch.empty(T, d, **f32), torch.empty(V, d, **f32)
+
+    def step():
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
+                                     w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, fresh, n_train, n_roll, 1.0,
+                                     rows_chunk, loss, weights, logp, lse, dh, d, dw, d, 0, ws)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fb.fopd_profile_enable(False)
+    st, flags = fb.fopd_workspace_status(ws)
+    if st != 0:
+        sys.exit("device flags set: %d" % flags)
+    n_chunks = (T + rows_chunk - 1) // rows_chunk
+    ldz = (V + 63) // 64 * 64
+    rp = sum(((min(rows_chunk, T - a) + 63) // 64) * 64 for a in range(0, T, rows_chunk))
+    # flops actually issued per call, operand padding included: logits, dhidden, dweight contractions
+    flops = {4: 2.0 * T * V * d, 5: 2.0 * T * ldz * d, 6: 2.0 * rp * V * d}
+    names = {4: "logits = hidden . weight^T", 5: "dhidden = dlogits . weight", 6: "dweight += dlogits^T . hidden"}
+    kern, tot_ms = {}, 0.0
+    for slot in (4, 5, 6):
+        ms, n = fb.fopd_profile_read(slot)
+        per_call_s = ms / steps * 1e-3
+        tot_ms += ms / steps
+        kern[names[slot]] = {"ms_per_call": ms / steps, "launches_per_call": n // steps,
+                             "TFLOP/s": flops[slot] / per_call_s / 1e12,
+                             "frac": flops[slot] / per_call_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    all_flops = sum(flops.values())
+    return {
+        "metric": "tokens/s, OPD loss fwd+bwd through the output projection (dL/dhidden, dL/dweight; logits only "
+                  "chunk-wise), V=%d d=%d bf16" % (V, d),
+        "value": int(((mask != 0) & (mask != 2)).sum()) * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d, "rows_chunk": rows_chunk,
+                   "chunks": n_chunks, "call": "fopd_lm_head_loss_fwd_bwd",
+                   "scratch_GB": fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "fopd_gemm_nt (three contractions per chunk)",
+                     "achieved": all_flops / (tot_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": all_flops / (tot_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "flops_per_launch": all_flops / (3 * n_chunks), "avg_ms": tot_ms / (3 * n_chunks)},
+        "kernels": kern,
+        "outside_the_contractions_ms": elapsed / steps * 1e3 - tot_ms}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -189,7 +274,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-projection", action="store_true",
                     help="skip the projection-fused log-prob measurement reported beside the headline")
-    ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head"), default="default",
+    ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head", "lm_head_loss"),
+                    default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
                          "(stale-checkpoint) logits tensor; lm_head: token log-probs from hidden states with "
                          "the output projection fused in.  Each is reported as its own line, not the headline")
@@ -211,6 +297,9 @@ def main():
         return bench_full_kl(args, torch, fb, wl, LossPass, hp)
     if args.variant == "lm_head":
         print(json.dumps(bench_lm_head(args, torch, fb, wl)))
+        return
+    if args.variant == "lm_head_loss":
+        print(json.dumps(bench_lm_head_loss(args, torch, fb, wl, hp)))
         return
     w = wl.generate(args.workload, "cuda:0", seed=0)
     T, V, B = w["T"], w["V"], w["B"]

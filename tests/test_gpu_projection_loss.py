@@ -101,6 +101,7 @@ CASES = {
     "one_chunk": ((40, 60), 64, 5003, 64, 72, 0, 256),
     "exact_tiles": ((256, 256), 192, 2048, 192, 192, 0, 256),
     "wide_vocab": ((150, 170, 200), 256, 40000, 256, 256, 5, 192),
+    "full_vocab": ((300, 350, 400), 256, 151936, 256, 256, 9, 512),
 }
 
 
@@ -158,3 +159,65 @@ def test_projection_loss_rejects_bad_arguments():
                                      torch.ones(1, device=DEV), None, None, 1.0, 64, t[:1], None, t, t.clone(),
                                      torch.empty(64, 64, device=DEV), 64, torch.empty(100, 64, device=DEV), 64, 0, ws)
     assert e.value.status == 5                                     # workspace too small
+
+
+def test_projection_loss_at_benchmark_size_sampled_rows():
+    """The benchmark's shape (rows, mask and lags of the reasoning workload, d = 4096, V = 151,936, chunks of 8192
+    rows).  The scores are an input of this call (Algorithm 1 computes them in its first loop), so seeded values
+    are supplied; the oracle then gives, row by row, the log-prob, the coefficient, the bf16 gradient row and its
+    contraction with the projection matrix for sampled rows.  dweight is tied to dhidden by the identity
+    <dhidden, hidden> = sum_{t,v} dz[t,v] z[t,v] = <dweight, weight>, which holds at any size."""
+    seq, mask = wl.structure_only("reasoning", seed=0)
+    T, d, V, B, rows_chunk = int(seq.sum()), 4096, 151936, len(seq), 8192
+    _say("benchmark size: T=%d d=%d V=%d, %d chunks: generating ..." % (T, d, V, (T + rows_chunk - 1) // rows_chunk))
+    lag = np.random.RandomState(0).randint(0, 5, size=B).astype(np.int32)
+    w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, DEV, seed=0), seq, lag, seed=0)
+    hp, g = (1.0, 1.0, 0.05, 0.1), 1.0
+    f = np.random.RandomState(5).uniform(0.0, 1.0, size=B).astype(np.float32)
+    f[3] = 0.01                                                   # one sample gated by the threshold
+    _say("running the call")
+    out = _run(w, hp, g, rows_chunk, f)
+    cu = orc.segment_offsets(seq)
+    n = orc.trainable_counts(mask, cu)
+    wts = orc.freshness_weights(f.astype(np.float64), hp[2], n)
+    assert_close("weights", np64(out["weights"]), wts, rtol=1e-6, atol=1e-9)
+    W64 = np64(w["weight"])
+    rs = np.random.RandomState(11)
+    rows = sorted(set(rs.randint(0, T, size=10).tolist() + [0, T - 1, int(cu[3]) + 1, rows_chunk - 1, rows_chunk]))
+    lb, lq, y = np64(w["behav_logp"]), np64(w["teacher_logp"]), np64(w["token_ids"])
+    worst = 0.0
+    for t in rows:
+        i = int(np.searchsorted(cu, t, side="right") - 1)
+        h = np64(w["hidden"][t])
+        z = orc.lm_head_logits(h[None, :], W64)
+        lse, lp = orc.token_logprobs(z, y[t:t + 1], None)
+        assert abs(float(out["logp"][t]) - lp[0]) <= 1e-4 and abs(float(out["lse"][t]) - lse[0]) <= 1e-4
+        delta, rho, adv, _, _ = orc.token_terms(lp, lb[t:t + 1], lq[t:t + 1], None)
+        c = g * wts[i] / (B * int(n[i])) * (adv[0] - hp[3] * rho[0] * delta[0])
+        grow = orc.round_to_bf16(orc.dlogits_row(z[0], int(y[t]), lse[0], c))
+        want = grow @ W64
+        pm = np.exp(z[0] - lse[0])
+        pm[int(y[t])] -= 1.0
+        eps_c = abs(g) / (B * int(n[i])) * wts[i] * 4e-6
+        lim = (2.0 ** -7 * np.abs(grow) + np.abs(pm) * eps_c + 2.0 ** -20 * np.abs(grow)) @ np.abs(W64) + 1e-30
+        got = np64(out["dhidden"][t])
+        err = np.abs(got - want)
+        assert np.all(err <= lim), "dhidden row %d: worst error / bound %.3f" % (t, float((err / lim).max()))
+        if wts[i] == 0.0:
+            assert not np.any(got)
+        else:
+            worst = max(worst, float(err.max() / np.abs(want).max()))
+    _say("%d sampled rows ok; max |err| / max |row| of dhidden %.2e" % (len(rows), worst))
+    assert worst < 2e-3
+    lhs = float((out["dhidden"].double() * w["hidden"].double()).sum())
+    rhs = float((out["dweight"].double() * w["weight"].double()).sum())
+    scale = float((out["dhidden"].double() * w["hidden"].double()).abs().sum())
+    _say("<dhidden, hidden> = %.9e, <dweight, weight> = %.9e (sum of magnitudes %.3e)" % (lhs, rhs, scale))
+    assert abs(lhs - rhs) <= 1e-5 * scale
+    # the loss is the sum of the per-row terms of the library's own log-probs
+    lp_gpu = np64(out["logp"])
+    per_row_w = np.repeat(wts / (B * np.maximum(n, 1)), seq)
+    dl = lp_gpu - lb
+    terms = per_row_w * ((lp_gpu - lq) + hp[3] * (np.exp(dl) * dl - np.exp(dl) + 1.0))
+    L = float(np.sum(terms[mask != 0]))
+    assert abs(float(out["loss"]) - L) <= 1e-5 * abs(L)
