@@ -81,7 +81,7 @@ FLOOR_STATS = dict(elements=0, rows=0, beyond_plain=0, rows_beyond_plain=0, tiny
                    min_rel_uncertainty=np.inf, worst_excess_ulp=0.0)
 
 
-def _count_floor_use(got, want, err, plain_lim, y, c, eps):
+def _count_floor_use(got, want, err, plain_lim, y, c, eps, half_plain_rel):
     st = FLOOR_STATS
     st["elements"] += got.size
     st["rows"] += 1
@@ -100,7 +100,10 @@ def _count_floor_use(got, want, err, plain_lim, y, c, eps):
     if np.any(rest):
         # the floor exists because c_t is a difference of O(1) quantities: it may only be needed where the
         # allowed absolute error of c_t is a visible fraction of c_t itself
-        st["min_rel_uncertainty"] = min(st["min_rel_uncertainty"], eps / max(abs(c), 1e-300))
+        rel = eps / max(abs(c), 1e-300)
+        assert rel >= half_plain_rel, ("an element needs the floor although its row's coefficient is uncertain by only "
+                                       "%.2e relative (c = %.3e)" % (rel, c))
+        st["min_rel_uncertainty"] = min(st["min_rel_uncertainty"], rel)
         st["worst_excess_ulp"] = max(st["worst_excess_ulp"], float(np.max(err[rest] / (plain_lim[rest] / 2.0))))
 
 
@@ -147,7 +150,8 @@ def check_grad_rows(got_rows, z_rows, y, lse, coef, eps_c, store, rows_label="")
         assert not np.any(bad), "dlogits row %s%d: %d elements off, worst %.3e vs limit %.3e at v=%d (c=%.3e)" % (
             rows_label, r, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]),
             int(np.argmax(err * bad)), coef[r])
-        _count_floor_use(got_rows[r], want, err, lim - floor, int(y[r]), coef[r], eps_c[r])
+        _count_floor_use(got_rows[r], want, err, lim - floor, int(y[r]), coef[r], eps_c[r],
+                         2.0 ** -8 if store == "bf16" else 1e-5)
 
 
 def check_grad_rows_full_kl(got_rows, z_rows, zs_rows, y, ref, rows, hp, grad_scale, n_samples, sample_of_row, store,

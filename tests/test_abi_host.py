@@ -118,7 +118,8 @@ def test_freshness_rejects_bad_arguments_before_launch():
 def test_profile_read_argument_checks():
     lib = fb.load_library()
     ms, n = ctypes.c_double(), ctypes.c_int64()
-    assert lib.fopd_profile_read(4, ctypes.byref(ms), ctypes.byref(n)) == 1
+    assert lib.fopd_profile_read(8, ctypes.byref(ms), ctypes.byref(n)) == 1
+    assert lib.fopd_profile_read(-1, ctypes.byref(ms), ctypes.byref(n)) == 1
     assert lib.fopd_profile_read(0, None, ctypes.byref(n)) == 1
     assert lib.fopd_profile_reset() == 0
     assert lib.fopd_profile_read(0, ctypes.byref(ms), ctypes.byref(n)) == 0 and n.value == 0

@@ -857,8 +857,9 @@ def test_reasoning_full_size_sampled_parity():
     # whole samples for the oracle: shortest first until at least 4 samples and 8k rows
     chosen, rows = _pick_samples(w["seq_lens_host"], 4, 8192)
     _say("oracle on samples %s (%d rows)" % (chosen, rows))
+    oracle_samples = {}
     for i in chosen:
-        o = _oracle_sample(w, i, cu, HP, B)
+        o = oracle_samples[i] = _oracle_sample(w, i, cu, HP, B)
         _check_sample(o, i, lp.logp, st.lse, lp.freshness, lp.weights, st)
         picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 6).astype(int))
         _check_sample_grad_rows(o, i, w, lambda rows_: lp.dlogits[torch.from_numpy(rows_).to(DEV)], picks)
@@ -869,6 +870,23 @@ def test_reasoning_full_size_sampled_parity():
     assert abs(float(lp.loss) - Ls) <= 2e-6 * abs(Ls)
     _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights)
     assert_close("agg f", float(st.agg[0]), float(np.mean(np64(lp.freshness))), rtol=1e-6)
+    # the call the benchmark also times: scores supplied, both passes over a row in one kernel, at this size
+    _say("scores-supplied call at full size")
+    f_in, first_loss, first_logp = lp.freshness.clone(), float(lp.loss), lp.logp.clone()
+    lp.dlogits.fill_(2.0)
+    lp.logp.fill_(2.0)
+    fb.fopd_loss_fwd_bwd(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                         w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, HP, f_in,
+                         None, None, 0, None, None, 1.0, lp.loss, None, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    assert torch.equal(lp.logp, first_logp)                       # 256 lanes per row: the bits of the separate kernels
+    assert abs(float(lp.loss) - first_loss) <= 2e-6 * abs(first_loss)
+    for i in chosen:
+        o = oracle_samples[i]
+        assert abs(float(lp.weights[i]) - o["w"][0]) <= 1e-5 * o["f"][0]
+        picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 6).astype(int))
+        _check_sample_grad_rows(o, i, w, lambda rows_: lp.dlogits[torch.from_numpy(rows_).to(DEV)], picks)
+    _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights, n_rows=24)
 
 
 def test_tooluse_full_size_sampled_parity():
@@ -925,6 +943,12 @@ def test_coding_full_size_chunked_flow():
     _check_sample(o, i, full.logp, full.lse, full.freshness,
                   torch.clamp(full.freshness - HP[2], min=0.0), full)
     assert o["D_sup"][0] > 0
+    # three more whole samples (one fresh, the others in lag order): log-probs, drift, loss term, score, weight
+    others = [int(j) for j in np.argsort(lagh, kind="stable") if int(j) != i][:3]
+    for j in others:
+        _say("oracle on sample %d (lag %d): log-probs and per-sample values" % (j, lagh[j]))
+        oj = _oracle_sample(w, j, cu, HP, B)
+        _check_sample(oj, j, full.logp, full.lse, full.freshness, torch.clamp(full.freshness - HP[2], min=0.0), full)
     live = np.flatnonzero(o["mask"])
     picks = np.concatenate([live[np.linspace(0, len(live) - 1, 6).astype(int)], np.flatnonzero(o["mask"] == 0)[:2]])
     picks_global = set((picks + o["a"]).tolist())
