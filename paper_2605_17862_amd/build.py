@@ -8,6 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "lib", "libfopd.so")
 PROBE = os.path.join(PKG, "lib", "hbm_probe")
+GEMM_PROBE = os.path.join(PKG, "lib", "gemm_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -27,7 +28,7 @@ def _run(cmd, what, verbose):
 
 
 def build_library(verbose=False):
-    """Compiles the C-ABI library and the bandwidth probe.  Returns the library's path."""
+    """Compiles the C-ABI library and the two probe programs.  Returns the library's path."""
     os.makedirs(os.path.dirname(LIB), exist_ok=True)
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     _run([hipcc] + HIPCC_FLAGS + [
@@ -37,6 +38,9 @@ def build_library(verbose=False):
     probe_flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
     _run([hipcc] + probe_flags + ["-o", PROBE, os.path.join(PKG, "csrc", "hbm_probe.hip")],
          "hbm_probe", verbose)
+    _run([hipcc] + probe_flags + ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
+                                  "-o", GEMM_PROBE, os.path.join(PKG, "csrc", "gemm_probe.hip")],
+         "gemm_probe", verbose)
     return LIB
 
 

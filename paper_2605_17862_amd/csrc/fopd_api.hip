@@ -825,7 +825,7 @@ static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, i
                                 : reinterpret_cast<const void*>(fopd_gemm_nt<false>);
   if (allow_dynamic_lds(kern, kGemmLdsBytes, allowed[accumulate ? 1 : 0]) != FOPD_OK) return FOPD_EHIP;
   const int tiles_m = static_cast<int>((M + kGemmTile - 1) / kGemmTile);
-  const int tiles_n = static_cast<int>((N + kGemmTile - 1) / kGemmTile);
+  const int tiles_n = static_cast<int>((N + kGemmTileN - 1) / kGemmTileN);
   const int64_t rounds = static_cast<int64_t>((tiles_m + 7) / 8) * ((tiles_n + 31) / 32);
   if (rounds * 256 > 2147483647LL) return FOPD_ESHAPE;
   const dim3 grid(static_cast<unsigned>(rounds * 256)), block(kGemmThreads);

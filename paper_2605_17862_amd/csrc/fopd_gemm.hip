@@ -30,19 +30,45 @@
 namespace fopd {
 
 constexpr int kGemmTile = kLmTile;          // 256 x 256 result tile
-constexpr int kGemmThreads = kLmThreads;    // 8 wavefronts
-constexpr int kGemmLdsBytes = kLmStages * kLmStageBytes;
+constexpr int kGemmWavesM = 2, kGemmWavesN = 4;   // eight wavefronts of 128 x 64: the faster of the measured shapes
+constexpr int kGemmThreads = 64 * kGemmWavesM * kGemmWavesN;
+// Extent of the result tile along n and bytes of LDS (four stages of both operand tiles) for WN wavefronts along n
+// holding TJ 32-row blocks each.
+constexpr int gemm_tile_n(int wn, int tj) { return 32 * tj * wn; }
+constexpr int gemm_lds_bytes(int wn, int tj) { return kLmStages * (kLmOperandBytes + gemm_tile_n(wn, tj) * 64); }
+constexpr int kGemmTileN = gemm_tile_n(kGemmWavesN, 8 / kGemmWavesN);
+constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 
 // ACCUMULATE = false: Out = product; true: Out += product (the caller's array holds the running sum).
 // K must be a positive multiple of 64; rows past the end of an operand are clamped (re-read) and their
 // results discarded.  Byte offsets inside one 256-row operand tile must fit 32 bits (checked on the host).
-template <bool ACCUMULATE>
-__global__ void __launch_bounds__(kGemmThreads)
+//
+// WM x WN wavefronts share the 256 x 256 tile, each holding (256 / WM) x (256 / WN) of it.  2 x 2 (four
+// wavefronts, one per SIMD, 128 x 128 each = 256 accumulator registers) reads a third less from the LDS per
+// flop than 2 x 4 (eight wavefronts of 128 x 64): with 2 x 4 the LDS carries 192 KB of fragment reads + 64 KB of
+// direct-load writes per 64 k-elements, as many cycles at 128 bytes per clock as the matrix cores need at full
+// rate; the timing variants below show the loop bound there, not by the L2.
+//
+// PROBE != 0 are timing variants for the bound analysis (built only into the gemm_probe program; their results
+// are wrong on purpose, every access stays inside the same buffers):
+//   1  every stage re-reads k = 0..63 of the operand tiles: all global loads hit the L1 after the first
+//   2  no global loads after the prologue: LDS reads + matrix cores only
+//   3  global loads as usual, fragments read once: no LDS reads in the loop
+//   4  neither: matrix-core issue only
+template <bool ACCUMULATE, int PROBE = 0, int WM = kGemmWavesM, int WN = kGemmWavesN, int TJ = 8 / WN>
+__global__ void __launch_bounds__(64 * WM * WN)
 fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __restrict__ Bn, int64_t ldb, int N,
              int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
   extern __shared__ __align__(16) unsigned char gemm_smem[];
-  constexpr int WN = 4;
-  constexpr int NJ = 8 / WN;
+  constexpr int WAVES = WM * WN;
+  constexpr int TI = 8 / WM;                   // 32-row blocks along m per wavefront
+  constexpr int TN = 32 * TJ * WN;             // tile extent along n (TJ 32-row blocks per wavefront): 256, 320 or 384
+  constexpr int CPA = 16 / WAVES;              // direct-load instructions per stage and wavefront: m-side tile,
+  constexpr int CPB = (TN / 16) / WAVES;       // n-side tile
+  constexpr int kABytes = kLmOperandBytes;     // one stage of the m-side tile: 256 rows x 64 bytes
+  constexpr int kStage = kABytes + TN * 64;    // one stage of both tiles
+  static_assert(WAVES == 4 || WAVES == 8, "four or eight wavefronts");
+  static_assert((TN / 16) % WAVES == 0, "the n-side tile must split evenly over the wavefronts");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
@@ -54,84 +80,103 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
   const int tile_m = ((round % m_blocks) << 3) + ((slot >> 2) & 7);
   const int tile_n = ((((round / m_blocks) << 3) + xcd) << 2) + (slot & 3);
   if (tile_m >= tiles_m || tile_n >= tiles_n) return;      // whole workgroup, before any barrier
-  const int m0 = tile_m * kGemmTile, n0 = tile_n * kGemmTile;
+  const int m0 = tile_m * kGemmTile, n0 = tile_n * TN;
 
-  // global -> LDS copy: see the projection kernel.  Wavefront w issues instructions 2 w and 2 w + 1 of each
-  // operand tile; instruction q fills rows 16 q .. 16 q + 15; lane i writes (row 16 q + i / 4, slot i % 4) and
-  // fetches logical 16-byte chunk (i % 4) ^ ((i / 16) % 4) of that row.
-  const int cp_row = wave * 32 + (lane >> 2);
+  // global -> LDS copy: see the projection kernel.  An operand tile of a stage is 16 wave instructions of 1 KB;
+  // wavefront w issues instructions CPQ w .. CPQ w + CPQ - 1; instruction q fills rows 16 q .. 16 q + 15; lane i
+  // writes (row 16 q + i / 4, slot i % 4) and fetches logical 16-byte chunk (i % 4) ^ ((i / 16) % 4) of that row.
   const int cp_chunk = (lane & 3) ^ ((lane >> 4) & 3);
-  const int cp_lds = wave * 2048;
   const char* Ab = reinterpret_cast<const char*>(Am) + static_cast<int64_t>(m0) * lda * 2;
   const char* Bb = reinterpret_cast<const char*>(Bn) + static_cast<int64_t>(n0) * ldb * 2;
-  uint32_t a_src[2], b_src[2];
+  uint32_t a_src[CPA], b_src[CPB];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    a_src[q] = static_cast<uint32_t>(min(cp_row + 16 * q, M - 1 - m0)) * static_cast<uint32_t>(lda) * 2u + cp_chunk * 16;
-    b_src[q] = static_cast<uint32_t>(min(cp_row + 16 * q, N - 1 - n0)) * static_cast<uint32_t>(ldb) * 2u + cp_chunk * 16;
-  }
+  for (int q = 0; q < CPA; ++q)
+    a_src[q] = static_cast<uint32_t>(min((wave * CPA + q) * 16 + (lane >> 2), M - 1 - m0)) * static_cast<uint32_t>(lda) * 2u +
+               cp_chunk * 16;
+#pragma unroll
+  for (int q = 0; q < CPB; ++q)
+    b_src[q] = static_cast<uint32_t>(min((wave * CPB + q) * 16 + (lane >> 2), N - 1 - n0)) * static_cast<uint32_t>(ldb) * 2u +
+               cp_chunk * 16;
   auto load_pair = [&](int ko, int pb) {
     const int64_t kb = static_cast<int64_t>(ko) * 2;
-    unsigned char* dst = gemm_smem + 2 * pb * kLmStageBytes + cp_lds;
+    unsigned char* dst = gemm_smem + 2 * pb * kStage;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      lm_load_to_lds(Ab + kb, a_src[q], dst + q * 1024);
-      lm_load_to_lds(Ab + kb + 64, a_src[q], dst + kLmStageBytes + q * 1024);
-      lm_load_to_lds(Bb + kb, b_src[q], dst + kLmOperandBytes + q * 1024);
-      lm_load_to_lds(Bb + kb + 64, b_src[q], dst + kLmStageBytes + kLmOperandBytes + q * 1024);
+    for (int q = 0; q < CPA; ++q) {
+      lm_load_to_lds(Ab + kb, a_src[q], dst + (wave * CPA + q) * 1024);
+      lm_load_to_lds(Ab + kb + 64, a_src[q], dst + kStage + (wave * CPA + q) * 1024);
+    }
+#pragma unroll
+    for (int q = 0; q < CPB; ++q) {
+      lm_load_to_lds(Bb + kb, b_src[q], dst + kABytes + (wave * CPB + q) * 1024);
+      lm_load_to_lds(Bb + kb + 64, b_src[q], dst + kStage + kABytes + (wave * CPB + q) * 1024);
     }
   };
 
   const int frag_row = (lane & 31) * 64;
-  const int a_off = wm * 128 * 64 + frag_row;
-  const int b_off = kLmOperandBytes + wn * NJ * 32 * 64 + frag_row;
+  const int a_off = wm * TI * 32 * 64 + frag_row;
+  const int b_off = kABytes + wn * TJ * 32 * 64 + frag_row;
   int xk[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) xk[ks] = ((2 * ks + (lane >> 5)) ^ ((lane >> 2) & 3)) << 4;
 
-  f32x16 acc[4][NJ];
+  f32x16 acc[TI][TJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int n_pairs = K / 64;
   int p_ld = 0;
   auto request_next = [&](int pb) {           // the last pair is requested again at the tail (never read)
-    load_pair(p_ld * 64, pb);
+    if (PROBE == 2 || PROBE == 4) return;
+    load_pair(PROBE == 1 ? 0 : p_ld * 64, pb);
     if (p_ld + 1 < n_pairs) ++p_ld;
   };
 
-  bf16x8 fa[2][4], fb[2][NJ];
+  bf16x8 fa[2][TI], fb[2][TJ];
+  bool in_loop = false;
   auto read_frags = [&](int buf, const unsigned char* stage, int ks) {
+    if ((PROBE == 3 || PROBE == 4) && in_loop) return;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 2048 + xk[ks]);
+    for (int i = 0; i < TI; ++i) fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 2048 + xk[ks]);
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 2048 + xk[ks]);
+    for (int j = 0; j < TJ; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 2048 + xk[ks]);
   };
   auto multiply = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-      for (int j = 0; j < NJ; ++j)
+      for (int j = 0; j < TJ; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
   };
 
   // Same schedule as the projection kernel: two pairs of stages in the LDS; while pair p multiplies, pair p + 1
-  // lands; one barrier per pair.  Loads complete in order: after the prologue's two requests (8 instructions per
-  // wavefront each), "at most 8 outstanding" means pair 0 has landed.
+  // lands; one barrier per pair.  Loads complete in order: after the prologue's two requests (4 CPQ instructions
+  // per wavefront each), "at most 4 CPQ outstanding" means pair 0 has landed.
+  if (PROBE == 2 || PROBE == 4) {             // the probes without loads still start from loaded stages
+    load_pair(0, 0);
+    load_pair(0, 1);
+  }
   request_next(0);
   request_next(1);
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  // "at most one pair's worth of own loads outstanding": 2 (CPA + CPB) instructions per wavefront and pair
+  if (2 * (CPA + CPB) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if (2 * (CPA + CPB) == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (2 * (CPA + CPB) == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+  static_assert(2 * (CPA + CPB) == 8 || 2 * (CPA + CPB) == 16 || 2 * (CPA + CPB) == 18 || 2 * (CPA + CPB) == 20,
+                "wait count of the prologue");
   __syncthreads();
   read_frags(0, gemm_smem, 0);
+  if (PROBE == 3 || PROBE == 4) read_frags(1, gemm_smem, 1);
+  in_loop = true;
   for (int p = 0; p < n_pairs; ++p) {
     const int pb = p & 1;
-    const unsigned char* lo = gemm_smem + 2 * pb * kLmStageBytes;
-    const unsigned char* hi = lo + kLmStageBytes;
-    const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kLmStageBytes;
+    const unsigned char* lo = gemm_smem + 2 * pb * kStage;
+    const unsigned char* hi = lo + kStage;
+    const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
     read_frags(1, lo, 1);
     multiply(0);
     __builtin_amdgcn_sched_barrier(0);
@@ -150,18 +195,18 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
 
-  // Result register r of block (i, j): m = 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's 128,
-  // n = 32 j + lane % 32 of its 64.  Four consecutive m per lane: one 16-byte access when they all exist.
+  // Result register r of block (i, j): m = 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's rows,
+  // n = 32 j + lane % 32 of its columns.  Four consecutive m per lane: one 16-byte access when they all exist.
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int n = n0 + wn * 64 + 32 * j + (lane & 31);
+  for (int j = 0; j < TJ; ++j) {
+    const int n = n0 + wn * TJ * 32 + 32 * j + (lane & 31);
     if (n >= N) continue;
     float* orow = Out + static_cast<int64_t>(n) * ldo;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TI; ++i) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int m = m0 + wm * 128 + 32 * i + 8 * g + ((lane >> 5) << 2);
+        const int m = m0 + wm * TI * 32 + 32 * i + 8 * g + ((lane >> 5) << 2);
         if (m + 3 < M && (ldo & 3) == 0) {
           float4* p = reinterpret_cast<float4*>(orow + m);
           float4 v = make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);

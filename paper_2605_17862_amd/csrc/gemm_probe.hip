@@ -1,0 +1,107 @@
+// Timing of the bf16 contraction kernel and of its bound-analysis variants on one shape.
+//
+//   gemm_probe [N rows, default 8192] [M, default 151936] [K, default 4096]
+//
+// Out[N, M] = Bn[N, K] . Am[M, K]^T with fopd_gemm_nt (the kernel behind the three contractions of the loss pass
+// through the projection; its main loop is that of the projection kernel fused with the log-sum-exp).  Prints,
+// for the shipped wavefront shape and for the alternative one, the rate of the whole loop and of four variants
+// that each leave one part of the loop out (their results are wrong on purpose): all global loads hitting the
+// L1, no global loads, no LDS reads, matrix cores only.  (Tiles wider than 256 x 256 -- 256 x 320, 256 x 384 with
+// four wavefronts -- need more than 256 accumulator registers per lane; hipcc spills 236 .. 712 registers per
+// lane for them, so they are not built.)
+// Under `rocprofv3 --pmc ...` the same program gives the counters of each variant.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "fopd_gemm.hip"
+
+#define CHECK(x)                                                                     \
+  do {                                                                               \
+    hipError_t e_ = (x);                                                             \
+    if (e_ != hipSuccess) {                                                          \
+      fprintf(stderr, "gemm_probe: %s failed: %s\n", #x, hipGetErrorString(e_));     \
+      return 1;                                                                      \
+    }                                                                                \
+  } while (0)
+
+__global__ void gemm_probe_fill(uint16_t* p, size_t n, uint32_t seed) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x) {
+    uint32_t h = static_cast<uint32_t>(i) * 2654435761u + seed;
+    h ^= h >> 15;
+    // bf16 values in [-1, 1): sign, exponent 0x7e or below, 7 mantissa bits
+    p[i] = static_cast<uint16_t>(((h & 1u) << 15) | (0x3f00u + ((h >> 8) & 0x7fu)));
+  }
+}
+
+template <int PROBE, int WM, int WN, int TJ>
+static int run(const char* name, const __bf16* A, int64_t lda, int M, const __bf16* B, int64_t ldb, int N, int K,
+               float* out, hipEvent_t e0, hipEvent_t e1) {
+  using namespace fopd;
+  auto kern = fopd_gemm_nt<false, PROBE, WM, WN, TJ>;
+  constexpr int lds = gemm_lds_bytes(WN, TJ), tn = gemm_tile_n(WN, TJ);
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    printf("gemm_probe: %-34s not runnable: %d bytes of LDS refused\n", name, lds);
+    return 0;
+  }
+  const int tiles_m = (M + kGemmTile - 1) / kGemmTile, tiles_n = (N + tn - 1) / tn;
+  const unsigned grid = static_cast<unsigned>(((tiles_m + 7) / 8) * ((tiles_n + 31) / 32) * 256);
+  float total = 0.f;
+  for (int rep = 0; rep < 4; ++rep) {          // first launch is a warm-up
+    CHECK(hipEventRecord(e0, 0));
+    kern<<<grid, 64 * WM * WN, lds>>>(A, lda, M, B, ldb, N, K, out, M, tiles_m, tiles_n);
+    CHECK(hipGetLastError());
+    CHECK(hipEventRecord(e1, 0));
+    CHECK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    CHECK(hipEventElapsedTime(&ms, e0, e1));
+    if (rep > 0) total += ms;
+  }
+  const double flops = 2.0 * M * static_cast<double>(N) * K;
+  printf("gemm_probe: %-34s avg %.3f ms, %.0f TFLOP/s (%.3f of 2500)\n", name, total / 3, flops / (total / 3) * 1e-9,
+         flops / (total / 3) * 1e-9 / 2500.0);
+  fflush(stdout);
+  return 0;
+}
+
+int main(int argc, char** argv) {
+  const int N = (argc > 1) ? atoi(argv[1]) : 8192;
+  const int M = (argc > 2) ? atoi(argv[2]) : 151936;
+  const int K = (argc > 3) ? atoi(argv[3]) : 4096;
+  if (N < 1 || N > 65536 || M < 4 || M > 262144 || M % 4 != 0 || K < 64 || K > 16384 || K % 64 != 0) {
+    fprintf(stderr, "gemm_probe: N in [1, 65536], M in [4, 262144] and a multiple of 4, K a multiple of 64 in [64, 16384]\n");
+    return 2;
+  }
+  __bf16 *A = nullptr, *B = nullptr;
+  float* out = nullptr;
+  CHECK(hipMalloc(&A, static_cast<size_t>(M) * K * 2));
+  CHECK(hipMalloc(&B, static_cast<size_t>(N) * K * 2));
+  CHECK(hipMalloc(&out, static_cast<size_t>(N) * M * 4));
+  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(A), static_cast<size_t>(M) * K, 1u);
+  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(B), static_cast<size_t>(N) * K, 2u);
+  CHECK(hipDeviceSynchronize());
+  hipEvent_t e0, e1;
+  CHECK(hipEventCreate(&e0));
+  CHECK(hipEventCreate(&e1));
+  printf("gemm_probe: Out[%d, %d] = Bn[%d, %d] . Am[%d, %d]^T, bf16 in, fp32 out\n", N, M, N, K, M, K);
+#define FOPD_PROBE_SET(WM, WN, TJ)                                                                  \
+  if (run<0, WM, WN, TJ>("whole loop", A, K, M, B, K, N, K, out, e0, e1)) return 1;                 \
+  if (run<1, WM, WN, TJ>("all global loads hit the L1", A, K, M, B, K, N, K, out, e0, e1)) return 1; \
+  if (run<2, WM, WN, TJ>("no global loads", A, K, M, B, K, N, K, out, e0, e1)) return 1;            \
+  if (run<3, WM, WN, TJ>("no LDS reads", A, K, M, B, K, N, K, out, e0, e1)) return 1;               \
+  if (run<4, WM, WN, TJ>("matrix cores only", A, K, M, B, K, N, K, out, e0, e1)) return 1;
+  printf("gemm_probe: tile 256 x 256, eight wavefronts of 128 x 64 (the shipped shape)\n");
+  FOPD_PROBE_SET(2, 4, 2)
+  printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
+  FOPD_PROBE_SET(2, 2, 4)
+#undef FOPD_PROBE_SET
+  CHECK(hipFree(A));
+  CHECK(hipFree(B));
+  CHECK(hipFree(out));
+  return 0;
+}
