@@ -1,6 +1,6 @@
 // Timing of the bf16 contraction kernel and of its bound-analysis variants on one shape.
 //
-//   gemm_probe [N rows, default 8192] [M, default 151936] [K, default 4096]
+//   gemm_probe [N rows, default 8192] [M, default 151936] [K, default 4096] [row padding in elements, default 0]
 //
 // Out[N, M] = Bn[N, K] . Am[M, K]^T with fopd_gemm_nt (the kernel behind the three contractions of the loss pass
 // through the projection; its main loop is that of the projection kernel fused with the log-sum-exp).  Prints,
@@ -73,28 +73,32 @@ int main(int argc, char** argv) {
   const int N = (argc > 1) ? atoi(argv[1]) : 8192;
   const int M = (argc > 2) ? atoi(argv[2]) : 151936;
   const int K = (argc > 3) ? atoi(argv[3]) : 4096;
-  if (N < 1 || N > 65536 || M < 4 || M > 262144 || M % 4 != 0 || K < 64 || K > 16384 || K % 64 != 0) {
+  const int pad = (argc > 4) ? atoi(argv[4]) : 0;       // extra elements per operand row (row pitch K + pad)
+  if (N < 1 || N > 65536 || M < 4 || M > 262144 || M % 4 != 0 || K < 64 || K > 16384 || K % 64 != 0 || pad < 0 ||
+      pad > 4096 || pad % 8 != 0) {
     fprintf(stderr, "gemm_probe: N in [1, 65536], M in [4, 262144] and a multiple of 4, K a multiple of 64 in [64, 16384]\n");
     return 2;
   }
   __bf16 *A = nullptr, *B = nullptr;
   float* out = nullptr;
-  CHECK(hipMalloc(&A, static_cast<size_t>(M) * K * 2));
-  CHECK(hipMalloc(&B, static_cast<size_t>(N) * K * 2));
+  const int64_t ld = K + pad;
+  CHECK(hipMalloc(&A, static_cast<size_t>(M) * ld * 2));
+  CHECK(hipMalloc(&B, static_cast<size_t>(N) * ld * 2));
   CHECK(hipMalloc(&out, static_cast<size_t>(N) * M * 4));
-  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(A), static_cast<size_t>(M) * K, 1u);
-  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(B), static_cast<size_t>(N) * K, 2u);
+  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(A), static_cast<size_t>(M) * ld, 1u);
+  gemm_probe_fill<<<4096, 256>>>(reinterpret_cast<uint16_t*>(B), static_cast<size_t>(N) * ld, 2u);
   CHECK(hipDeviceSynchronize());
   hipEvent_t e0, e1;
   CHECK(hipEventCreate(&e0));
   CHECK(hipEventCreate(&e1));
-  printf("gemm_probe: Out[%d, %d] = Bn[%d, %d] . Am[%d, %d]^T, bf16 in, fp32 out\n", N, M, N, K, M, K);
+  printf("gemm_probe: Out[%d, %d] = Bn[%d, %d] . Am[%d, %d]^T, bf16 in, fp32 out, operand row pitch %ld elements\n", N,
+         M, N, K, M, K, static_cast<long>(ld));
 #define FOPD_PROBE_SET(WM, WN, TJ)                                                                  \
-  if (run<0, WM, WN, TJ>("whole loop", A, K, M, B, K, N, K, out, e0, e1)) return 1;                 \
-  if (run<1, WM, WN, TJ>("all global loads hit the L1", A, K, M, B, K, N, K, out, e0, e1)) return 1; \
-  if (run<2, WM, WN, TJ>("no global loads", A, K, M, B, K, N, K, out, e0, e1)) return 1;            \
-  if (run<3, WM, WN, TJ>("no LDS reads", A, K, M, B, K, N, K, out, e0, e1)) return 1;               \
-  if (run<4, WM, WN, TJ>("matrix cores only", A, K, M, B, K, N, K, out, e0, e1)) return 1;
+  if (run<0, WM, WN, TJ>("whole loop", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;                 \
+  if (run<1, WM, WN, TJ>("all global loads hit the L1", A, ld, M, B, ld, N, K, out, e0, e1)) return 1; \
+  if (run<2, WM, WN, TJ>("no global loads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;            \
+  if (run<3, WM, WN, TJ>("no LDS reads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;               \
+  if (run<4, WM, WN, TJ>("matrix cores only", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, eight wavefronts of 128 x 64 (the shipped shape)\n");
   FOPD_PROBE_SET(2, 4, 2)
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
