@@ -210,12 +210,13 @@ def bench_lm_head(args, torch, fb, wl, steps=None):
                      "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}
 
 
-def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=8192):
+def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
     """Result record for fopd_lm_head_loss_fwd_bwd: loss, dL/dhidden and dL/dweight from hidden states (d = 4096),
     the [V, d] projection and scores computed beforehand, on the rows, mask and lags of the workload; the
     logits exist only as one chunk of `rows_chunk` rows at a time."""
     import numpy as np
     steps = args.steps if steps is None else steps
+    rows_chunk = args.rows_chunk if rows_chunk is None else rows_chunk
     seq_lens, mask = wl.structure_only(args.workload, seed=0)
     lag = np.random.RandomState(0).randint(0, 5, size=len(seq_lens)).astype(np.int32)
     T, d, V, B = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"]), len(seq_lens)
@@ -304,6 +305,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-projection", action="store_true",
                     help="skip the projection-fused log-prob measurement reported beside the headline")
+    ap.add_argument("--rows-chunk", type=int, default=8192,
+                    help="rows per chunk of the loss pass through the projection (--variant lm_head_loss)")
     ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head", "lm_head_loss"),
                     default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
@@ -430,6 +433,13 @@ def main():
         out["projection_fused"] = {"call": rec["config"]["call"], "d": rec["config"]["d"],
                                    "ms_per_call": rec["ms_per_step"], "tokens/s": rec["value"],
                                    "roofline": rec["roofline"]}
+        # and the step behind it: loss and gradient carried through the projection (--variant lm_head_loss)
+        del rec, w
+        rec = bench_lm_head_loss(args, torch, fb, wl, hp, steps=2)
+        out["projection_loss"] = {"call": rec["config"]["call"], "d": rec["config"]["d"],
+                                  "rows_chunk": rec["config"]["rows_chunk"], "scratch_GB": rec["config"]["scratch_GB"],
+                                  "ms_per_call": rec["ms_per_step"], "tokens/s": rec["value"],
+                                  "roofline": rec["roofline"], "kernels": rec["kernels"]}
     print(json.dumps(out))
 
 

@@ -55,7 +55,12 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 //   2  no global loads after the prologue: LDS reads + matrix cores only
 //   3  global loads as usual, fragments read once: no LDS reads in the loop
 //   4  neither: matrix-core issue only
-template <bool ACCUMULATE, int PROBE = 0, int WM = kGemmWavesM, int WN = kGemmWavesN, int TJ = 8 / WN>
+//
+// VIA_REGS: the operand stages travel global -> vector registers -> LDS (ordinary loads, then ds_write_b128 to the
+// same swizzled slots) instead of global -> LDS directly; the loads of pair p + 2 are in flight during the whole
+// of pair p and are written to the LDS at the start of pair p + 1.
+template <bool ACCUMULATE, int PROBE = 0, int WM = kGemmWavesM, int WN = kGemmWavesN, int TJ = 8 / WN,
+          bool VIA_REGS = false>
 __global__ void __launch_bounds__(64 * WM * WN)
 fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __restrict__ Bn, int64_t ldb, int N,
              int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
@@ -112,6 +117,36 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     }
   };
 
+  // the same stages through vector registers: lane i of instruction q holds what the direct load would have put
+  // at LDS offset 1024 q + 16 i
+  u32x4 staged[VIA_REGS ? 2 * (CPA + CPB) : 1];
+  auto load_regs = [&](int ko) {
+    const int64_t kb = static_cast<int64_t>(ko) * 2;
+#pragma unroll
+    for (int q = 0; q < CPA; ++q) {
+      staged[2 * q] = *reinterpret_cast<const u32x4*>(Ab + kb + a_src[q]);
+      staged[2 * q + 1] = *reinterpret_cast<const u32x4*>(Ab + kb + 64 + a_src[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < CPB; ++q) {
+      staged[2 * CPA + 2 * q] = *reinterpret_cast<const u32x4*>(Bb + kb + b_src[q]);
+      staged[2 * CPA + 2 * q + 1] = *reinterpret_cast<const u32x4*>(Bb + kb + 64 + b_src[q]);
+    }
+  };
+  auto write_lds = [&](int pb) {
+    unsigned char* dst = gemm_smem + 2 * pb * kStage + lane * 16;
+#pragma unroll
+    for (int q = 0; q < CPA; ++q) {
+      *reinterpret_cast<u32x4*>(dst + (wave * CPA + q) * 1024) = staged[2 * q];
+      *reinterpret_cast<u32x4*>(dst + kStage + (wave * CPA + q) * 1024) = staged[2 * q + 1];
+    }
+#pragma unroll
+    for (int q = 0; q < CPB; ++q) {
+      *reinterpret_cast<u32x4*>(dst + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q];
+      *reinterpret_cast<u32x4*>(dst + kStage + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q + 1];
+    }
+  };
+
   const int frag_row = (lane & 31) * 64;
   const int a_off = wm * TI * 32 * 64 + frag_row;
   const int b_off = kABytes + wn * TJ * 32 * 64 + frag_row;
@@ -152,48 +187,80 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
   };
 
-  // Same schedule as the projection kernel: two pairs of stages in the LDS; while pair p multiplies, pair p + 1
-  // lands; one barrier per pair.  Loads complete in order: after the prologue's two requests (4 CPQ instructions
-  // per wavefront each), "at most 4 CPQ outstanding" means pair 0 has landed.
-  if (PROBE == 2 || PROBE == 4) {             // the probes without loads still start from loaded stages
-    load_pair(0, 0);
-    load_pair(0, 1);
-  }
-  request_next(0);
-  request_next(1);
-  // "at most one pair's worth of own loads outstanding": 2 (CPA + CPB) instructions per wavefront and pair
-  if (2 * (CPA + CPB) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else if (2 * (CPA + CPB) == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else if (2 * (CPA + CPB) == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
-  static_assert(2 * (CPA + CPB) == 8 || 2 * (CPA + CPB) == 16 || 2 * (CPA + CPB) == 18 || 2 * (CPA + CPB) == 20,
-                "wait count of the prologue");
-  __syncthreads();
-  read_frags(0, gemm_smem, 0);
-  if (PROBE == 3 || PROBE == 4) read_frags(1, gemm_smem, 1);
-  in_loop = true;
-  for (int p = 0; p < n_pairs; ++p) {
-    const int pb = p & 1;
-    const unsigned char* lo = gemm_smem + 2 * pb * kStage;
-    const unsigned char* hi = lo + kStage;
-    const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
-    read_frags(1, lo, 1);
-    multiply(0);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(0, hi, 0);
-    multiply(1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(1, hi, 1);
-    multiply(0);
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  if constexpr (VIA_REGS) {
+    // pair 0 into the LDS, pair 1 into registers; then, per pair p: registers (pair p + 1) -> the buffers pair
+    // p - 1 has left, loads of pair p + 2 -> registers, multiply pair p, barrier.
+    load_regs(0);
+    write_lds(0);
+    load_regs(n_pairs > 1 ? 64 : 0);
     __syncthreads();
-    request_next(pb);
-    read_frags(0, next, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    multiply(1);
+    read_frags(0, gemm_smem, 0);
+    for (int p = 0; p < n_pairs; ++p) {
+      const int pb = p & 1;
+      const unsigned char* lo = gemm_smem + 2 * pb * kStage;
+      const unsigned char* hi = lo + kStage;
+      const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
+      write_lds(pb ^ 1);                                     // pair p + 1 (the compiler waits for its loads)
+      load_regs(min(p + 2, n_pairs - 1) * 64);               // pair p + 2; the last pair again at the tail
+      read_frags(1, lo, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(0, hi, 0);
+      multiply(1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(1, hi, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      read_frags(0, next, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1);
+    }
+  } else {
+    // Same schedule as the projection kernel: two pairs of stages in the LDS; while pair p multiplies, pair p + 1
+    // lands; one barrier per pair.  Loads complete in order: after the prologue's two requests (4 CPQ instructions
+    // per wavefront each), "at most 4 CPQ outstanding" means pair 0 has landed.
+    if (PROBE == 2 || PROBE == 4) {             // the probes without loads still start from loaded stages
+      load_pair(0, 0);
+      load_pair(0, 1);
+    }
+    request_next(0);
+    request_next(1);
+    // "at most one pair's worth of own loads outstanding": 2 (CPA + CPB) instructions per wavefront and pair
+    if (2 * (CPA + CPB) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    else if (2 * (CPA + CPB) == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (2 * (CPA + CPB) == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+    static_assert(2 * (CPA + CPB) == 8 || 2 * (CPA + CPB) == 16 || 2 * (CPA + CPB) == 18 || 2 * (CPA + CPB) == 20,
+                  "wait count of the prologue");
+    __syncthreads();
+    read_frags(0, gemm_smem, 0);
+    if (PROBE == 3 || PROBE == 4) read_frags(1, gemm_smem, 1);
+    in_loop = true;
+    for (int p = 0; p < n_pairs; ++p) {
+      const int pb = p & 1;
+      const unsigned char* lo = gemm_smem + 2 * pb * kStage;
+      const unsigned char* hi = lo + kStage;
+      const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
+      read_frags(1, lo, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(0, hi, 0);
+      multiply(1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(1, hi, 1);
+      multiply(0);
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      request_next(pb);
+      read_frags(0, next, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(1);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
+
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
 
   // Result register r of block (i, j): m = 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4 of the wavefront's rows,
   // n = 32 j + lane % 32 of its columns.  Four consecutive m per lane: one 16-byte access when they all exist.

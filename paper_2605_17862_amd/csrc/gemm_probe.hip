@@ -37,11 +37,11 @@ __global__ void gemm_probe_fill(uint16_t* p, size_t n, uint32_t seed) {
   }
 }
 
-template <int PROBE, int WM, int WN, int TJ>
+template <int PROBE, int WM, int WN, int TJ, bool VIA_REGS = false>
 static int run(const char* name, const __bf16* A, int64_t lda, int M, const __bf16* B, int64_t ldb, int N, int K,
                float* out, hipEvent_t e0, hipEvent_t e1) {
   using namespace fopd;
-  auto kern = fopd_gemm_nt<false, PROBE, WM, WN, TJ>;
+  auto kern = fopd_gemm_nt<false, PROBE, WM, WN, TJ, VIA_REGS>;
   constexpr int lds = gemm_lds_bytes(WN, TJ), tn = gemm_tile_n(WN, TJ);
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds) !=
       hipSuccess) {
@@ -101,8 +101,10 @@ int main(int argc, char** argv) {
   if (run<4, WM, WN, TJ>("matrix cores only", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, eight wavefronts of 128 x 64 (the shipped shape)\n");
   FOPD_PROBE_SET(2, 4, 2)
+  if (run<0, 2, 4, 2, true>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
   FOPD_PROBE_SET(2, 2, 4)
+  if (run<0, 2, 2, 4, true>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
 #undef FOPD_PROBE_SET
   CHECK(hipFree(A));
   CHECK(hipFree(B));
