@@ -420,7 +420,8 @@ def main():
     }
     k14_avg_s = k14_ms / max(k14_n, 1) * 1e-3
     out["scores_supplied"] = {
-        "call": "fopd_loss_fwd_bwd with freshness_in (kernel fopd_k14_fused: HBM sees one read and one write)",
+        "call": "fopd_loss_fwd_bwd with freshness_in (kernel fopd_k14_regs: each row is held in registers between "
+                "the two passes, the logits cross the memory system once)",
         "ms_per_call": scored_elapsed / args.steps * 1e3, "tokens/s": n_train * args.steps / scored_elapsed,
         "kernel_avg_ms": k14_avg_s * 1e3, "GB/s": k4_bytes / k14_avg_s / 1e9,
         "frac": k4_bytes / k14_avg_s / 1e9 / HBM_PEAK_GBS}

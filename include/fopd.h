@@ -191,8 +191,9 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
  *                          fopd_freshness_score, or NULL when the two sets coincide (a 0/1 mask);
  *                          only with n_train_in.  (n_train_in without n_roll_in on a mask that does hold
  *                          bytes 2 or 3 raises the FOPD_ESETS flag and drops those rows.)
- *                          Without lse_in the logits are still read from HBM only once: one kernel
- *                          makes both passes over each row while it is cache-resident.
+ *                          Without lse_in one kernel makes both passes over each row: with the row held in
+ *                          registers when it fits (see fopd_set_option "k14_regs"), so that the logits are read
+ *                          from memory once, else re-reading it right after the first pass.
  *   lse_in / logp_in     : both or neither.  When given ([T] f32, the outputs of
  *                          fopd_token_logprobs for these rows) the logits are read only by the
  *                          gradient pass.  Requires freshness_in.
@@ -356,8 +357,12 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
  * Launch-shape options (process-wide; a call reads them once, under the library's mutex, when it starts):
  *   "k14_threads"      256, 512 or 1024 lanes per row in the kernel that makes both passes over a row
  *                      (used when freshness_in is given without lse_in); default 256
- *   "k14_rows_per_cu"  1..8 rows in flight per compute unit in that kernel; default 6 (the second
- *                      pass over a row is served from cache only while few rows are in flight).
+ *   "k14_rows_per_cu"  1..8 rows in flight per compute unit in that kernel; default 6.
+ *   "k14_regs"         1 (default): in that same call, a row of 2049 .. 19456 16-byte vectors (bf16: 16,392 <= V <=
+ *                      155,648; fp32: half that) is held in registers between the two passes by a workgroup of
+ *                      1024 lanes, so that the logits cross the memory system once; 0: always the kernel above.
+ *                      The 1024-lane partition sums a row in another order than fopd_token_logprobs does, so
+ *                      log-probs may differ from that call's in the last place.
  * Returns FOPD_EINVAL for an unknown name or a value outside the stated set.
  */
 fopd_status fopd_set_option(const char* name, int value);

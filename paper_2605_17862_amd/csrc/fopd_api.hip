@@ -181,6 +181,7 @@ struct ScopedTimer {
 struct Options {
   int k14_threads = 256;          // lanes per row in the two-pass-per-row kernel
   int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
+  int k14_regs = 1;               // 1: rows that fit (16-byte vectors <= 1024 x 19) are held in registers between the passes
 } g_opt;
 
 inline Options current_options() {
@@ -295,6 +296,20 @@ fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t
   if (T == 0) return FOPD_OK;
   const Options opt = current_options();
   ScopedTimer timer(2, s, timed);
+  constexpr int kRegRowVectors = 19;
+  const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
+  if (opt.k14_regs != 0 && nvec <= static_cast<int64_t>(kRegRowThreads) * kRegRowVectors && nvec > 2 * kRegRowThreads) {
+    const dim3 grid(static_cast<unsigned>(T)), block(kRegRowThreads);
+    if (dt == FOPD_BF16)
+      fopd_k14_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(
+          logits, dlogits, T, static_cast<int>(V), ld, a.token_ids, a.mask, a.lb, a.lq, a.cu, a.n_train, a.n_roll, a.lag,
+          a.fresh32, a.B, a.row_begin, a.hp, a.grad_scale, a.logp, a.row_loss, a.flags);
+    else
+      fopd_k14_regs<FOPD_F32, kRegRowVectors><<<grid, block, 0, s>>>(
+          logits, dlogits, T, static_cast<int>(V), ld, a.token_ids, a.mask, a.lb, a.lq, a.cu, a.n_train, a.n_roll, a.lag,
+          a.fresh32, a.B, a.row_begin, a.hp, a.grad_scale, a.logp, a.row_loss, a.flags);
+    return launched();
+  }
 #define FOPD_K14_CASE(DTV, NTV) return launch_k14_t<DTV, NTV>(logits, dlogits, T, V, ld, a, opt.k14_rows_per_cu, s)
   if (dt == FOPD_BF16) {
     if (opt.k14_threads == 512) FOPD_K14_CASE(FOPD_BF16, 512);
@@ -966,6 +981,11 @@ fopd_status fopd_set_option(const char* name, int value) {
   if (key == "k14_threads") {
     if (value != 256 && value != 512 && value != 1024) return FOPD_EINVAL;
     g_opt.k14_threads = value;
+    return FOPD_OK;
+  }
+  if (key == "k14_regs") {
+    if (value != 0 && value != 1) return FOPD_EINVAL;
+    g_opt.k14_regs = value;
     return FOPD_OK;
   }
   if (key == "k14_rows_per_cu") {

@@ -632,6 +632,147 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 }
 
 // =========================================================================================
+// K14R: the same call with the row held in registers between the two passes: 1024 lanes x NV 16-byte vectors
+// (NV = 19 holds a 303,872-byte row), one workgroup per compute unit.  HBM and the fabric see a single read and a
+// single write per row; the price is that a compute unit works on one row at a time, so its load phase, the
+// reduction and its store phase do not overlap with each other.  Rows longer than 1024 NV vectors do not fit and
+// take fopd_k14_fused.
+// =========================================================================================
+
+constexpr int kRegRowThreads = 1024;
+
+template <int DT, int NV>
+__global__ void __launch_bounds__(kRegRowThreads)
+fopd_k14_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
+              const uint8_t* mask, const float* behav_logp, const float* teacher_logp, const int64_t* cu,
+              const int32_t* n_train, const int32_t* n_roll, const int32_t* lag, const float* fresh32, int32_t B,
+              int64_t row_begin, fopd_hparams hp, float grad_scale, float* logp, double* row_loss, int32_t* flags) {
+  constexpr int NT = kRegRowThreads;
+  constexpr int E = Elem<DT>::kPerVec;
+  __shared__ float sh_zy;
+  __shared__ float sh_R[NT / 64];
+  __shared__ float sh_S[NT / 64];
+  __shared__ float sh_c, sh_lseL, sh_gy;
+  const int64_t t = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int y = token_ids[t];
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  bool live = (mask == nullptr) || (mask[t] != 0);
+  if (live && (y < 0 || y >= V)) {
+    if (tid == 0) atomicOr(flags, kFlagToken);
+    live = false;
+  }
+  if (live && n_roll == nullptr && in_one_set_only(mask, t)) {
+    if (tid == 0) atomicOr(flags, kFlagSets);
+    live = false;
+  }
+  const int64_t gt = row_begin + t;
+  double w = 0.0;
+  int32_t n = 0, nr = 0;
+  if (live && gt < cu[B]) {
+    const int i = sample_of_row(cu, B, gt);
+    n = n_train[i];
+    nr = (n_roll != nullptr) ? n_roll[i] : n;
+    w = weight_of(static_cast<double>(fresh32[i]), n, nr, lag[i], hp.xi);
+  }
+  if (!live || (w == 0.0 && logp == nullptr)) {
+    if (tid == 0) {
+      if (logp != nullptr) logp[t] = 0.f;
+      row_loss[t] = 0.0;
+    }
+    row_zero<DT, NT>(orow, V);
+    return;
+  }
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+  u32x4* ov = reinterpret_cast<u32x4*>(orow);
+  const int nvec = V / E;                      // <= NT * NV, checked on the host
+  const int jy = y / E, ey = y % E;
+  const float kNegInf = -__builtin_inff();
+  // the whole row: every load is issued before the first value is used
+  u32x4 q[NV];
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int j = tid + u * NT;
+    if (j < nvec) q[u] = __builtin_nontemporal_load(rv + j);
+  }
+  const int tail_idx = nvec * E + tid;         // ragged tail: fewer than E elements
+  float tail_x = 0.f;
+  if (tail_idx < V) tail_x = load_elem<DT>(row, tail_idx);
+  LaneState st;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int j = tid + u * NT;
+    if (j < nvec) {
+      float x[E];
+      unpack<DT>(q[u], x);
+      if (j == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+          if (e == ey) {
+            sh_zy = x[e];
+            x[e] = kNegInf;
+          }
+        }
+      }
+      accumulate<E, false>(x, st);
+    }
+  }
+  if (tail_idx < V) {
+    float x1 = tail_x;
+    if (tail_idx == y) {
+      sh_zy = x1;
+      x1 = kNegInf;
+    }
+    accumulate<1, false>(&x1, st);
+  }
+  double lp, ls, ent;
+  block_lse_finish<NT, false>(st, &sh_zy, sh_R, sh_S, nullptr, lp, ls, ent);
+  if (tid == 0) {
+    const float lp32 = static_cast<float>(lp);
+    const float lse32 = static_cast<float>(ls);
+    if (logp != nullptr) logp[t] = lp32;
+    float c = 0.f;
+    double lt = 0.0;
+    if (w > 0.0)
+      c = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], w, n, nr, in_sup_set(mask, t),
+                        in_roll_set(mask, t), B, hp, grad_scale, &lt);
+    row_loss[t] = lt;
+    sh_c = c;
+    sh_lseL = lse32 * kLog2e;
+    sh_gy = c * expm1f(lp32);
+  }
+  __syncthreads();
+  const float c = sh_c;
+  if (c == 0.f) {
+    row_zero<DT, NT>(orow, V);
+    return;
+  }
+  const float lseL = sh_lseL, gy = sh_gy;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int j = tid + u * NT;
+    if (j < nvec) {
+      float x[E];
+      unpack<DT>(q[u], x);
+#pragma unroll
+      for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+      if (j == jy) {
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          if (e == ey) x[e] = gy;
+      }
+      __builtin_nontemporal_store(pack<DT>(x), ov + j);
+    }
+  }
+  if (tail_idx < V) {
+    float g = c * fast_exp2(fmaf(tail_x, kLog2e, -lseL));
+    if (tail_idx == y) g = gy;
+    store_elem<DT>(orow, tail_idx, g);
+  }
+}
+
+// =========================================================================================
 // K5 / K6: the same two passes when the rollout drift is the full-vocabulary KL of Eq.
 // "kl-diagnostics" as printed, KL(pi^t || pi^r) per row, from a second logits tensor z' (the
 // stale checkpoint replayed on the same prefixes).  With d_v = z_v - z'_v and p = softmax(z):
