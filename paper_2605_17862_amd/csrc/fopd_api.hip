@@ -836,8 +836,8 @@ static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, i
   // byte offsets inside one 256-row operand tile are 32-bit
   if (256 * lda * 2 >= 2147483648LL || 256 * ldb * 2 >= 2147483648LL) return FOPD_ESHAPE;
   static bool allowed[2][kMaxDevices] = {};
-  const void* kern = accumulate ? reinterpret_cast<const void*>(fopd_gemm_nt<true>)
-                                : reinterpret_cast<const void*>(fopd_gemm_nt<false>);
+  const void* kern = accumulate ? reinterpret_cast<const void*>(fopd_gemm_nt<true, 0>)
+                                : reinterpret_cast<const void*>(fopd_gemm_nt<false, 0>);
   if (allow_dynamic_lds(kern, kGemmLdsBytes, allowed[accumulate ? 1 : 0]) != FOPD_OK) return FOPD_EHIP;
   const int tiles_m = static_cast<int>((M + kGemmTile - 1) / kGemmTile);
   const int tiles_n = static_cast<int>((N + kGemmTileN - 1) / kGemmTileN);
@@ -846,10 +846,10 @@ static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, i
   const dim3 grid(static_cast<unsigned>(rounds * 256)), block(kGemmThreads);
   ScopedTimer timer(slot, s);
   if (accumulate)
-    fopd_gemm_nt<true><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
+    fopd_gemm_nt<true, 0><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
                                                           static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
   else
-    fopd_gemm_nt<false><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
+    fopd_gemm_nt<false, 0><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
                                                            static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
   return launched();
 }

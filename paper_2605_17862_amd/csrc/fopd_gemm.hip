@@ -31,6 +31,7 @@ namespace fopd {
 
 constexpr int kGemmTile = kLmTile;          // 256 x 256 result tile
 constexpr int kGemmWavesM = 2, kGemmWavesN = 4;   // eight wavefronts of 128 x 64: the faster of the measured shapes
+constexpr int kGemmStaging = 4;                   // operand stages go through registers, a quarter of a pair per slice
 constexpr int kGemmThreads = 64 * kGemmWavesM * kGemmWavesN;
 // Extent of the result tile along n and bytes of LDS (four stages of both operand tiles) for WN wavefronts along n
 // holding TJ 32-row blocks each.
@@ -55,12 +56,17 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 //   2  no global loads after the prologue: LDS reads + matrix cores only
 //   3  global loads as usual, fragments read once: no LDS reads in the loop
 //   4  neither: matrix-core issue only
+//   5  the first direct-load instruction of the n-side tile left out: 25 % (eight wavefronts) or 12.5 % (four) fewer
+//      bytes through the L1, as a wider tile would need per flop
 //
-// VIA_REGS: the operand stages travel global -> vector registers -> LDS (ordinary loads, then ds_write_b128 to the
-// same swizzled slots) instead of global -> LDS directly; the loads of pair p + 2 are in flight during the whole
-// of pair p and are written to the LDS at the start of pair p + 1.
+// VIA_REGS != 0: the operand stages travel global -> vector registers -> LDS (ordinary loads, then ds_write_b128 to
+// the same swizzled slots) instead of global -> LDS directly.  1: the loads of pair p + 2 are issued at the start
+// of pair p and written to the LDS at the start of pair p + 1; 2, 3: the same with the loads issued in two / four
+// portions over the pair; 4 (shipped): each of the four 16-k slices of a pair writes one quarter of pair p + 1 to
+// the LDS and requests the same quarter of pair p + 2, so that every load has a whole pair to land and the L1 sees
+// an even stream of requests instead of a burst behind each barrier (measured: 0.45 -> 0.50 of peak).
 template <bool ACCUMULATE, int PROBE = 0, int WM = kGemmWavesM, int WN = kGemmWavesN, int TJ = 8 / WN,
-          bool VIA_REGS = false>
+          int VIA_REGS = kGemmStaging>
 __global__ void __launch_bounds__(64 * WM * WN)
 fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __restrict__ Bn, int64_t ldb, int N,
              int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
@@ -112,6 +118,7 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     }
 #pragma unroll
     for (int q = 0; q < CPB; ++q) {
+      if (PROBE == 5 && q == 0) continue;     // a quarter (8 wavefronts) or an eighth (4) of the fill left out
       lm_load_to_lds(Bb + kb, b_src[q], dst + kABytes + (wave * CPB + q) * 1024);
       lm_load_to_lds(Bb + kb + 64, b_src[q], dst + kStage + kABytes + (wave * CPB + q) * 1024);
     }
@@ -120,17 +127,43 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
   // the same stages through vector registers: lane i of instruction q holds what the direct load would have put
   // at LDS offset 1024 q + 16 i
   u32x4 staged[VIA_REGS ? 2 * (CPA + CPB) : 1];
-  auto load_regs = [&](int ko) {
+  auto load_regs_a = [&](int ko) {
     const int64_t kb = static_cast<int64_t>(ko) * 2;
 #pragma unroll
     for (int q = 0; q < CPA; ++q) {
       staged[2 * q] = *reinterpret_cast<const u32x4*>(Ab + kb + a_src[q]);
       staged[2 * q + 1] = *reinterpret_cast<const u32x4*>(Ab + kb + 64 + a_src[q]);
     }
+  };
+  auto load_regs_b = [&](int ko) {
+    const int64_t kb = static_cast<int64_t>(ko) * 2;
 #pragma unroll
     for (int q = 0; q < CPB; ++q) {
       staged[2 * CPA + 2 * q] = *reinterpret_cast<const u32x4*>(Bb + kb + b_src[q]);
       staged[2 * CPA + 2 * q + 1] = *reinterpret_cast<const u32x4*>(Bb + kb + 64 + b_src[q]);
+    }
+  };
+  auto load_regs = [&](int ko) {
+    load_regs_a(ko);
+    load_regs_b(ko);
+  };
+  // one quarter of a pair's loads: group g = 0, 1 the first / second half of the m-side instructions, 2, 3 of the n-side
+  auto load_regs_quarter = [&](int ko, int g) {
+    const int64_t kb = static_cast<int64_t>(ko) * 2;
+    if (g < 2) {
+#pragma unroll
+      for (int q = 0; q < CPA; ++q) {
+        if ((q * 2) / CPA != g) continue;
+        staged[2 * q] = *reinterpret_cast<const u32x4*>(Ab + kb + a_src[q]);
+        staged[2 * q + 1] = *reinterpret_cast<const u32x4*>(Ab + kb + 64 + a_src[q]);
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < CPB; ++q) {
+        if ((q * 2) / CPB != g - 2) continue;
+        staged[2 * CPA + 2 * q] = *reinterpret_cast<const u32x4*>(Bb + kb + b_src[q]);
+        staged[2 * CPA + 2 * q + 1] = *reinterpret_cast<const u32x4*>(Bb + kb + 64 + b_src[q]);
+      }
     }
   };
   auto write_lds = [&](int pb) {
@@ -144,6 +177,25 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     for (int q = 0; q < CPB; ++q) {
       *reinterpret_cast<u32x4*>(dst + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q];
       *reinterpret_cast<u32x4*>(dst + kStage + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q + 1];
+    }
+  };
+
+  auto write_lds_quarter = [&](int pb, int g) {
+    unsigned char* dst = gemm_smem + 2 * pb * kStage + lane * 16;
+    if (g < 2) {
+#pragma unroll
+      for (int q = 0; q < CPA; ++q) {
+        if ((q * 2) / CPA != g) continue;
+        *reinterpret_cast<u32x4*>(dst + (wave * CPA + q) * 1024) = staged[2 * q];
+        *reinterpret_cast<u32x4*>(dst + kStage + (wave * CPA + q) * 1024) = staged[2 * q + 1];
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < CPB; ++q) {
+        if ((q * 2) / CPB != g - 2) continue;
+        *reinterpret_cast<u32x4*>(dst + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q];
+        *reinterpret_cast<u32x4*>(dst + kStage + kABytes + (wave * CPB + q) * 1024) = staged[2 * CPA + 2 * q + 1];
+      }
     }
   };
 
@@ -200,18 +252,35 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
       const unsigned char* lo = gemm_smem + 2 * pb * kStage;
       const unsigned char* hi = lo + kStage;
       const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
-      write_lds(pb ^ 1);                                     // pair p + 1 (the compiler waits for its loads)
-      load_regs(min(p + 2, n_pairs - 1) * 64);               // pair p + 2; the last pair again at the tail
+      const int k_next = min(p + 2, n_pairs - 1) * 64;       // pair p + 2; the last pair again at the tail
+      if (VIA_REGS == 4) {
+        // every quarter of pair p + 1 goes to the LDS a whole pair after it was requested, and the request for
+        // the same quarter of pair p + 2 follows at once: loads and LDS writes are spread evenly over the pair
+        write_lds_quarter(pb ^ 1, 0);
+        load_regs_quarter(k_next, 0);
+      } else {
+        write_lds(pb ^ 1);                                   // pair p + 1 (the compiler waits for its loads)
+        if (VIA_REGS == 2) load_regs_a(k_next);
+        else if (VIA_REGS == 3) load_regs_quarter(k_next, 0);
+        else load_regs(k_next);
+      }
       read_frags(1, lo, 1);
       multiply(0);
       __builtin_amdgcn_sched_barrier(0);
+      if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 1);
+      if (VIA_REGS >= 3) load_regs_quarter(k_next, 1);
       read_frags(0, hi, 0);
       multiply(1);
       __builtin_amdgcn_sched_barrier(0);
+      if (VIA_REGS == 2) load_regs_b(k_next);
+      if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 2);
+      if (VIA_REGS >= 3) load_regs_quarter(k_next, 2);
       read_frags(1, hi, 1);
       multiply(0);
       __builtin_amdgcn_sched_barrier(0);
+      if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 3);
       __syncthreads();
+      if (VIA_REGS >= 3) load_regs_quarter(k_next, 3);
       read_frags(0, next, 0);
       __builtin_amdgcn_sched_barrier(0);
       multiply(1);
@@ -227,7 +296,8 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     request_next(0);
     request_next(1);
     // "at most one pair's worth of own loads outstanding": 2 (CPA + CPB) instructions per wavefront and pair
-    if (2 * (CPA + CPB) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+    if (PROBE == 5) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (2 * (CPA + CPB) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else if (2 * (CPA + CPB) == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
     else if (2 * (CPA + CPB) == 18) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(20)" ::: "memory");

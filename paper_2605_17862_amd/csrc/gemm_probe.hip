@@ -37,7 +37,7 @@ __global__ void gemm_probe_fill(uint16_t* p, size_t n, uint32_t seed) {
   }
 }
 
-template <int PROBE, int WM, int WN, int TJ, bool VIA_REGS = false>
+template <int PROBE, int WM, int WN, int TJ, int VIA_REGS>
 static int run(const char* name, const __bf16* A, int64_t lda, int M, const __bf16* B, int64_t ldb, int N, int K,
                float* out, hipEvent_t e0, hipEvent_t e1) {
   using namespace fopd;
@@ -94,17 +94,22 @@ int main(int argc, char** argv) {
   printf("gemm_probe: Out[%d, %d] = Bn[%d, %d] . Am[%d, %d]^T, bf16 in, fp32 out, operand row pitch %ld elements\n", N,
          M, N, K, M, K, static_cast<long>(ld));
 #define FOPD_PROBE_SET(WM, WN, TJ)                                                                  \
-  if (run<0, WM, WN, TJ>("whole loop", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;                 \
-  if (run<1, WM, WN, TJ>("all global loads hit the L1", A, ld, M, B, ld, N, K, out, e0, e1)) return 1; \
-  if (run<2, WM, WN, TJ>("no global loads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;            \
-  if (run<3, WM, WN, TJ>("no LDS reads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;               \
-  if (run<4, WM, WN, TJ>("matrix cores only", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, WM, WN, TJ, 0>("whole loop, direct global -> LDS loads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1; \
+  if (run<1, WM, WN, TJ, 0>("all global loads hit the L1", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;            \
+  if (run<2, WM, WN, TJ, 0>("no global loads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;                        \
+  if (run<3, WM, WN, TJ, 0>("no LDS reads", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;                           \
+  if (run<4, WM, WN, TJ, 0>("matrix cores only", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;                      \
+  if (run<5, WM, WN, TJ, 0>("part of the n-side fill left out", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, eight wavefronts of 128 x 64 (the shipped shape)\n");
   FOPD_PROBE_SET(2, 4, 2)
-  if (run<0, 2, 4, 2, true>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 4, 2, 1>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 4, 2, 2>("  ... n-side loads issued mid-pair", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 4, 2, 3>("  ... a quarter of the loads per slice", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 4, 2, 4>("  ... and of the LDS writes (shipped)", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
   FOPD_PROBE_SET(2, 2, 4)
-  if (run<0, 2, 2, 4, true>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 2, 4, 1>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<0, 2, 2, 4, 4>("  ... a quarter of a pair per slice", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
 #undef FOPD_PROBE_SET
   CHECK(hipFree(A));
   CHECK(hipFree(B));
