@@ -19,19 +19,19 @@
 //
 // Memory pipeline.  A stage is 32 hidden elements of both tiles (2 x 16 KB); the LDS holds two pairs of
 // stages (128 KB of the CU's 160 KB), a pair being 64 hidden elements, i.e. whole 128-byte lines of
-// both matrices.  Stages are filled by direct global -> LDS loads (16 bytes per lane, lane i of a wave
-// instruction writes LDS bytes [base + 16 i, + 16)); no vector register ever holds a tile.  The two
-// halves of a line are requested back to back so that the second one hits in the L1; the next pair
-// is requested as soon as its buffers are free and has a whole pair of matrix work to arrive.
-// Measured on MI355X: with every load hitting the L1 the same loop runs 25 % faster, whatever the L2
-// hit rate and however far ahead the loads are issued: the L2 -> L1 path, 64 KB per 64 hidden elements
-// and compute unit, is what bounds this kernel (counters: 358 cycles per 128-byte L1 miss and about 57
-// of them in flight per compute unit, i.e. about 20 bytes per cycle where full MFMA rate needs 32).
+// both matrices.  A pair travels global -> vector registers -> LDS in four quarters, one per 16-element slice
+// of the pair being multiplied: each slice writes one quarter of the next pair to the LDS and requests the same
+// quarter of the pair after it, so every load has a whole pair of matrix work to land and the L1 sees an even
+// stream of requests.  (Direct global -> LDS loads, 16 bytes per lane with lane i writing LDS bytes
+// [base + 16 i, + 16), were used first: they can only be issued in a burst behind the barrier that frees the
+// buffers, which costs 9 % on this loop.)  The slots are those a direct load would fill, so the map below holds.
+// Measured on MI355X: this loop is bound by the L1 miss path from the L2, about 17 - 19 bytes per clock and
+// compute unit where full MFMA rate on a 256 x 256 tile needs 32 (timing variants and counters: gemm_probe).
 // LDS rows are 64 bytes; the LDS serves 16 lanes x 16 bytes per clock (64 banks), so the 16 rows that a
 // quarter-wave reads at one logical 16-byte chunk must land on 16 different chunk slots modulo 16:
 // the chunk index is XOR-ed with bits 2..3 of the row (rows r .. r + 3 already differ by 4 slots).
-// Because the LDS side of a direct load is fixed by the lane number, the permutation is applied on
-// the global side: lane i fetches the chunk that belongs in slot i.
+// The LDS side of a slot is fixed by the lane number (as a direct load fixes it), so the permutation is applied
+// on the global side: lane i fetches the chunk that belongs in slot i.
 
 #ifndef FOPD_LM_HEAD_HIP_
 #define FOPD_LM_HEAD_HIP_
@@ -123,21 +123,30 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   for (int q = 0; q < 2; ++q)
     h_off[q] = static_cast<uint32_t>(min(cp_row + 16 * q, T - 1 - t0)) * static_cast<uint32_t>(ldh) * 2u + cp_chunk * 16;
 
-  // the two stages that hold vocabulary tile `vtile`, hidden elements ko .. ko + 63, into LDS stages
-  // 2 pb and 2 pb + 1; the two halves of each 128-byte line are requested back to back
-  auto load_pair = [&](int vtile, int ko, int pb) {
+  // The two stages that hold vocabulary tile `vtile`, hidden elements ko .. ko + 63, travel through vector
+  // registers in four quarters (ordinary 16-byte loads, then ds_write_b128 to LDS offset 1024 q + 16 lane of
+  // instruction q): one quarter = one instruction of one operand, both halves of its 128-byte lines, requested
+  // back to back.  Group g = 0, 1: weight rows, instruction 0 / 1; 2, 3: hidden rows.
+  u32x4 staged[8];
+  auto load_quarter = [&](int vtile, int ko, int g) {
     const int64_t kb = static_cast<int64_t>(ko) * 2;
-    const int last = V - 1 - vtile * kLmTile;
-    const char* wsrc = Wb + static_cast<int64_t>(vtile) * kLmTile * ldw * 2 + kb;
-    unsigned char* dst = lm_smem + 2 * pb * kLmStageBytes + cp_lds;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    const int q = g & 1;
+    if (g < 2) {
+      const int last = V - 1 - vtile * kLmTile;
+      const char* wsrc = Wb + static_cast<int64_t>(vtile) * kLmTile * ldw * 2 + kb;
       const uint32_t w_off = static_cast<uint32_t>(min(cp_row + 16 * q, last)) * ldw2 + cp_chunk * 16;
-      lm_load_to_lds(wsrc, w_off, dst + q * 1024);
-      lm_load_to_lds(wsrc + 64, w_off, dst + kLmStageBytes + q * 1024);
-      lm_load_to_lds(Hb + kb, h_off[q], dst + kLmOperandBytes + q * 1024);
-      lm_load_to_lds(Hb + kb + 64, h_off[q], dst + kLmStageBytes + kLmOperandBytes + q * 1024);
+      staged[2 * g] = *reinterpret_cast<const u32x4*>(wsrc + w_off);
+      staged[2 * g + 1] = *reinterpret_cast<const u32x4*>(wsrc + 64 + w_off);
+    } else {
+      staged[2 * g] = *reinterpret_cast<const u32x4*>(Hb + kb + h_off[q]);
+      staged[2 * g + 1] = *reinterpret_cast<const u32x4*>(Hb + kb + 64 + h_off[q]);
     }
+  };
+  auto write_quarter = [&](int pb, int g) {
+    unsigned char* dst = lm_smem + 2 * pb * kLmStageBytes + cp_lds + (g & 1) * 1024 + lane * 16 +
+                         (g < 2 ? 0 : kLmOperandBytes);
+    *reinterpret_cast<u32x4*>(dst) = staged[2 * g];
+    *reinterpret_cast<u32x4*>(dst + kLmStageBytes) = staged[2 * g + 1];
   };
 
   // LDS -> fragment: lane reads row (lane % 32) of a 32-row block, hidden elements
@@ -158,11 +167,10 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   }
 
   // (vt_ld, kt_ld) is the next pair to request; it stops at the last pair, which the tail requests
-  // again (into a free buffer, never read) instead of branching.
+  // again (never read) instead of branching.
   int vt_ld = vt_begin, kt_ld = 0, s_ld = 0;
   const int n_pairs = n_iter / 2, nkp = nk / 2;
-  auto request_next = [&](int pb) {
-    load_pair(vt_ld, kt_ld * 64, pb);
+  auto advance_next = [&]() {
     if (s_ld + 1 < n_pairs) {
       ++s_ld;
       if (++kt_ld == nkp) {
@@ -221,19 +229,29 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
     }
   };
 
-  // Schedule of pair p (buffers 2 (p % 2) and 2 (p % 2) + 1), four 16-element slices:
-  //   read slice 1 | multiply slice 0 (read at the end of pair p - 1)
-  //   read slice 2 | multiply slice 1
-  //   read slice 3 | multiply slice 2
-  //   wait for the own loads of pair p + 1, barrier: pair p + 1 is complete and pair p fully read
-  //   request pair p + 2 into the buffers of p, read slice 0 of p + 1 | multiply slice 3
-  // so neither the barrier nor the LDS latency after it leaves the matrix cores without work.
-  // Loads complete in order: after the prologue's two requests (8 instructions per wavefront each),
-  // "at most 8 outstanding" means pair 0 has landed; in the loop only pair p + 1 is outstanding.
+  // Schedule of pair p (buffers 2 (p % 2) and 2 (p % 2) + 1), four 16-element slices.  The registers `staged` hold
+  // pair p + 1, requested a whole pair earlier; slice s of pair p
+  //   writes quarter s of pair p + 1 to the other pair of buffers (free since the barrier that ended pair p - 1),
+  //   requests quarter s of pair p + 2 into the same registers,
+  //   reads the fragments of the next slice and multiplies the current one;
+  // the one barrier per pair sits in slice 3, after the last write: behind it pair p + 1 is complete and pair p
+  // fully read.  Loads and LDS writes are thus spread evenly over the pair (a burst of requests behind each
+  // barrier, as direct global -> LDS loads give, costs 9 % on this loop).
   if (n_iter > 0) {
-    request_next(0);
-    request_next(1);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+#pragma unroll
+    for (int g = 0; g < 4; ++g) load_quarter(vt_ld, kt_ld * 64, g);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) write_quarter(0, g);
+    advance_next();
+    // in the order the loop keeps (the wait counts at the loop's head assume the less favourable of the two
+    // orders that reach it, so a prologue that requests the quarters in another order shortens every wait)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      __builtin_amdgcn_sched_barrier(0);
+      load_quarter(vt_ld, kt_ld * 64, g);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    advance_next();
   }
   __syncthreads();
   if (n_iter > 0) read_frags(0, lm_smem, 0);
@@ -252,18 +270,26 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
       const unsigned char* lo = lm_smem + 2 * pb * kLmStageBytes;
       const unsigned char* hi = lo + kLmStageBytes;
       const unsigned char* next = lm_smem + 2 * (pb ^ 1) * kLmStageBytes;
+      const int vt_nx = vt_ld, ko_nx = kt_ld * 64;          // pair p + 2
+      write_quarter(pb ^ 1, 0);
+      load_quarter(vt_nx, ko_nx, 0);
       read_frags(1, lo, 1);
       multiply(0);
       __builtin_amdgcn_sched_barrier(0);
+      write_quarter(pb ^ 1, 1);
+      load_quarter(vt_nx, ko_nx, 1);
       read_frags(0, hi, 0);
       multiply(1);
       __builtin_amdgcn_sched_barrier(0);
+      write_quarter(pb ^ 1, 2);
+      load_quarter(vt_nx, ko_nx, 2);
       read_frags(1, hi, 1);
       multiply(0);
       __builtin_amdgcn_sched_barrier(0);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      write_quarter(pb ^ 1, 3);
       __syncthreads();
-      request_next(pb);
+      load_quarter(vt_nx, ko_nx, 3);
+      advance_next();
       read_frags(0, next, 0);
       __builtin_amdgcn_sched_barrier(0);
       multiply(1);
@@ -275,7 +301,6 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   }
 
   // half-waves, then the two wavefronts that share these tokens, then one pair per token and strip
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // the tail's unused requests still target the LDS
   __syncthreads();
   float2* ex = reinterpret_cast<float2*>(lm_smem + kLmStages * kLmStageBytes);
 #pragma unroll
