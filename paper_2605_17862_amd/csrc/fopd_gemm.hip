@@ -52,12 +52,16 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 //
 // PROBE != 0 are timing variants for the bound analysis (built only into the gemm_probe program; their results
 // are wrong on purpose, every access stays inside the same buffers):
-//   1  every stage re-reads k = 0..63 of the operand tiles: all global loads hit the L1 after the first
+//   1  every stage re-reads k = 0..63 of the operand tiles: with direct loads every request is an L2 hit on a hot
+//      line (direct loads do not allocate in the L1); with loads through registers every request hits the L1
 //   2  no global loads after the prologue: LDS reads + matrix cores only
 //   3  global loads as usual, fragments read once: no LDS reads in the loop
 //   4  neither: matrix-core issue only
 //   5  the first direct-load instruction of the n-side tile left out: 25 % (eight wavefronts) or 12.5 % (four) fewer
 //      bytes through the L1, as a wider tile would need per flop
+//   6  (register staging only) each line of pair p + 3 is requested once per XCD a pair before its loads, by one of
+//      the workgroups that share the tile: lower miss latency, no gain in time
+//   7  the wavefront raises its priority while it issues matrix instructions: no gain
 //
 // VIA_REGS != 0: the operand stages travel global -> vector registers -> LDS (ordinary loads, then ds_write_b128 to
 // the same swizzled slots) instead of global -> LDS directly.  1: the loads of pair p + 2 are issued at the start
@@ -232,13 +236,23 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     for (int j = 0; j < TJ; ++j) fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 2048 + xk[ks]);
   };
   auto multiply = [&](int buf) {
+    if (PROBE == 7) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int i = 0; i < TI; ++i)
 #pragma unroll
       for (int j = 0; j < TJ; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    if (PROBE == 7) __builtin_amdgcn_s_setprio(0);
   };
 
+  [[maybe_unused]] uint32_t pf_word = 0;
+  [[maybe_unused]] const char* pf_base = Ab;
+  if constexpr (PROBE == 6) {
+    static_assert(PROBE != 6 || (WAVES == 8 && TN == 256 && VIA_REGS == 4), "written for the shipped shape");
+    const int u = wave * 12 + min(lane, 11);                 // line 0 .. 95 of this workgroup's share
+    if (u < 64) pf_base = Ab + static_cast<int64_t>(min(64 * (slot & 3) + u, M - 1 - m0)) * lda * 2;
+    else pf_base = Bb + static_cast<int64_t>(min(32 * ((slot >> 2) & 7) + (u - 64), N - 1 - n0)) * ldb * 2;
+  }
   if constexpr (VIA_REGS) {
     // pair 0 into the LDS, pair 1 into registers; then, per pair p: registers (pair p + 1) -> the buffers pair
     // p - 1 has left, loads of pair p + 2 -> registers, multiply pair p, barrier.
@@ -252,7 +266,8 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
       const unsigned char* lo = gemm_smem + 2 * pb * kStage;
       const unsigned char* hi = lo + kStage;
       const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kStage;
-      const int k_next = min(p + 2, n_pairs - 1) * 64;       // pair p + 2; the last pair again at the tail
+      // pair p + 2; the last pair again at the tail
+      const int k_next = (PROBE == 1) ? 0 : min(p + 2, n_pairs - 1) * 64;
       if (VIA_REGS == 4) {
         // every quarter of pair p + 1 goes to the LDS a whole pair after it was requested, and the request for
         // the same quarter of pair p + 2 follows at once: loads and LDS writes are spread evenly over the pair
@@ -281,6 +296,12 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
       if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 3);
       __syncthreads();
       if (VIA_REGS >= 3) load_regs_quarter(k_next, 3);
+      if constexpr (PROBE == 6) {
+        // pair p + 3 into the L2, a pair before its loads are issued: each of its lines is requested by one of
+        // the workgroups that share the operand tile (m-side: 4 workgroups, 64 rows each; n-side: 8, 32 rows each)
+        asm volatile("" ::"v"(pf_word));                     // the previous request has returned
+        if (lane < 12) pf_word = *reinterpret_cast<const uint32_t*>(pf_base + static_cast<int64_t>(min(p + 3, n_pairs - 1)) * 128);
+      }
       read_frags(0, next, 0);
       __builtin_amdgcn_sched_barrier(0);
       multiply(1);
