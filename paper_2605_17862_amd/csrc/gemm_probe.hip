@@ -109,6 +109,8 @@ int main(int argc, char** argv) {
   if (run<1, 2, 4, 2, 4>("  ... all global loads hit the L1", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<6, 2, 4, 2, 4>("  ... lines requested a pair ahead", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<7, 2, 4, 2, 4>("  ... wave priority raised for MFMAs", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<8, 2, 4, 2, 4>("  ... no result stores", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<9, 2, 4, 2, 4>("  ... non-temporal result stores", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
   FOPD_PROBE_SET(2, 2, 4)
   if (run<0, 2, 2, 4, 1>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
