@@ -288,7 +288,7 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
         "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d, "rows_chunk": rows_chunk,
                    "chunks": n_chunks, "call": "fopd_lm_head_loss_fwd_bwd",
                    "scratch_GB": fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) / 1e9},
-        "roofline": {"bound": "mfma", "kernel": "fopd_gemm_nt (three contractions per chunk)",
+        "roofline": {"bound": "mfma", "kernel": "fopd_gemm_nt, fopd_gemm_tn (three contractions per chunk)",
                      "achieved": all_flops / (tot_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": all_flops / (tot_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "flops_per_launch": all_flops / (3 * n_chunks), "avg_ms": tot_ms / (3 * n_chunks)},

@@ -411,7 +411,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *
  *   hidden [T, ldh] bf16, weight [V, ldw] bf16, d a multiple of 64; token_ids, mask, behav_logp, teacher_logp,
  *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
- *   rows_chunk   rows per chunk, a multiple of 64 (8192 keeps the scratch near 6.5 GB at V = 151,936, d = 4096)
+ *   rows_chunk   rows per chunk, a multiple of 64 (8192 keeps the scratch at 8.7 GB at V = 151,936, d = 4096)
  *   loss [1], weights [B] (may be NULL), logp [T], lse [T]: f32 outputs
  *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0
  *   workspace    fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) bytes, 256-byte aligned, initialised

@@ -80,11 +80,11 @@ namespace {
 void* g_scratch_ptr[64] = {};
 
 // Workspace of the loss pass through the projection: flags, offsets and counts, the per-chunk O(R) arrays, then
-// the chunk's fp32 logits, its bf16 gradient rows, their transpose, the transposed hidden chunk and the
-// transposed projection matrix.  ldz = V rounded up to 64 (the k-extent of the dL/dhidden contraction).
+// the chunk's fp32 logits, its bf16 gradient rows and the transposed projection matrix.  ldz = V rounded up to 64
+// (the k-extent of the dL/dhidden contraction).
 struct LmLossWorkspace {
-  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0, gt = 0,
-         ht = 0, wt = 0, total = 0;
+  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0, wt = 0,
+         total = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
   LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
@@ -105,8 +105,6 @@ struct LmLossWorkspace {
     chunk_loss = Workspace::take(off, static_cast<size_t>(n_chunks + 1) * sizeof(float));
     z = Workspace::take(off, r * static_cast<size_t>(ldz) * sizeof(float));
     g = Workspace::take(off, r * static_cast<size_t>(ldz) * 2);
-    gt = Workspace::take(off, v * r * 2);
-    ht = Workspace::take(off, dd * r * 2);
     wt = Workspace::take(off, dd * static_cast<size_t>(ldz) * 2);
     total = off;
   }
@@ -854,6 +852,36 @@ static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, i
   return launched();
 }
 
+// Out[n, m] (+)= sum_{k < K} Bk[k, n] Ak[k, m] on `s`; Ak has rows_a readable rows, Bk has K and zeros where a row
+// is not to count.
+static fopd_status launch_gemm_tn(bool accumulate, const __bf16* Ak, int64_t lda, int64_t M, int64_t rows_a,
+                                  const __bf16* Bk, int64_t ldb, int64_t N, int64_t K, float* Out, int64_t ldo, int slot,
+                                  hipStream_t s) {
+  if (M <= 0 || N <= 0) return FOPD_OK;
+  if (K <= 0 || K % 64 != 0 || rows_a < 1 || rows_a > K || M > 2147483647LL || N > 2147483647LL || K > 2147483647LL ||
+      M % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0 || lda < M || ldb < (N + 7) / 8 * 8)
+    return FOPD_ESHAPE;
+  static bool allowed[2][kMaxDevices] = {};
+  const void* kern = accumulate ? reinterpret_cast<const void*>(fopd_gemm_tn<true>)
+                                : reinterpret_cast<const void*>(fopd_gemm_tn<false>);
+  if (allow_dynamic_lds(kern, kTnLdsBytes, allowed[accumulate ? 1 : 0]) != FOPD_OK) return FOPD_EHIP;
+  const int tiles_m = static_cast<int>((M + kGemmTile - 1) / kGemmTile);
+  const int tiles_n = static_cast<int>((N + kGemmTileN - 1) / kGemmTileN);
+  const int64_t rounds = static_cast<int64_t>((tiles_m + 7) / 8) * ((tiles_n + 31) / 32);
+  if (rounds * 256 > 2147483647LL) return FOPD_ESHAPE;
+  const dim3 grid(static_cast<unsigned>(rounds * 256)), block(kGemmThreads);
+  ScopedTimer timer(slot, s);
+  if (accumulate)
+    fopd_gemm_tn<true><<<grid, block, kTnLdsBytes, s>>>(Ak, lda, static_cast<int>(M), static_cast<int>(rows_a), Bk, ldb,
+                                                       static_cast<int>(N), static_cast<int>(K), Out, ldo, tiles_m,
+                                                       tiles_n);
+  else
+    fopd_gemm_tn<false><<<grid, block, kTnLdsBytes, s>>>(Ak, lda, static_cast<int>(M), static_cast<int>(rows_a), Bk, ldb,
+                                                        static_cast<int>(N), static_cast<int>(K), Out, ldo, tiles_m,
+                                                        tiles_n);
+  return launched();
+}
+
 static fopd_status launch_transpose(const void* in, int64_t ld_in, int64_t rows, int64_t cols, void* out, int64_t ld_out,
                                     int64_t rows_pad, hipStream_t s) {
   if (rows_pad <= 0 || cols <= 0) return FOPD_OK;
@@ -908,8 +936,6 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   float* chunk_loss = at<float>(workspace, lay.chunk_loss);
   float* Z = at<float>(workspace, lay.z);
   __bf16* G = at<__bf16>(workspace, lay.g);
-  __bf16* Gt = at<__bf16>(workspace, lay.gt);
-  __bf16* Ht = at<__bf16>(workspace, lay.ht);
   __bf16* Wt = at<__bf16>(workspace, lay.wt);
   const __bf16* Hm = static_cast<const __bf16*>(hidden);
   const __bf16* Wm = static_cast<const __bf16*>(weight);
@@ -954,11 +980,15 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     }
     // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
     if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dhidden + a * lddh, lddh, 5, s)) != FOPD_OK) return st;
-    // dL/dweight: vocabulary x hidden, contraction over the chunk's rows (zero-padded to a multiple of 64)
-    if ((st = launch_transpose(G, ldz, R, V, Gt, Rp, Rp, s)) != FOPD_OK) return st;
-    if ((st = launch_transpose(Hc, ldh, R, d, Ht, Rp, Rp, s)) != FOPD_OK) return st;
+    // dL/dweight: vocabulary x hidden, contraction over the chunk's rows, both operands as they are stored; the
+    // gradient rows past the chunk's end, up to a multiple of 64, are zero
+    if (Rp > R) {
+      fopd_fill_zero_f32<<<static_cast<unsigned>(Rp - R), 256, 0, s>>>(reinterpret_cast<float*>(G + R * ldz), ldz / 2,
+                                                                     static_cast<int>(ldz / 2));
+      if ((st = launched()) != FOPD_OK) return st;
+    }
     const bool acc = (ci > 0) || (accumulate_dweight != 0);
-    if ((st = launch_gemm(acc, Ht, Rp, d, Gt, Rp, V, Rp, dweight, lddw, 6, s)) != FOPD_OK) return st;
+    if ((st = launch_gemm_tn(acc, Hc, ldh, d, R, G, ldz, V, Rp, dweight, lddw, 6, s)) != FOPD_OK) return st;
   }
   if (T == 0) {      // an empty batch: loss 0, the weights of the scores, a zero projection gradient
     fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi, loss,

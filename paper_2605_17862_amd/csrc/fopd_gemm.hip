@@ -2,21 +2,23 @@
 // loss pass whose logits are the output projection of the hidden states and are made chunk by chunk:
 //
 //   fopd_gemm_nt            Out[n, m] (+)= sum_k Bn[n, k] * Am[m, k]     bf16 in, fp32 accumulate, fp32 out
+//   fopd_gemm_tn            Out[n, m] (+)= sum_k Bk[k, n] * Ak[k, m]     the same with both operands k-major
 //   fopd_transpose_bf16     out[c, r] = in[r, c], zero-padded along r    (brings an operand into k-contiguous form)
 //   fopd_k4_grad_wide       gradient rows from fp32 logits to bf16        c_t (softmax(z_t) - onehot)
 //
-// The three contractions of one chunk of R rows (d hidden size, V vocabulary) all have this one form, both
-// operands k-contiguous:
-//   logits      Z[R, V]   = H[R, d]     . W[V, d]^T          n = row,   m = vocabulary entry, k = hidden element
-//   dL/dhidden  dH[R, d]  = dZ[R, V]    . (W^T)[d, V]^T      n = row,   m = hidden element,   k = vocabulary entry
-//   dL/dweight  dW[V, d] += (dZ^T)[V, R] . (H^T)[d, R]^T     n = vocabulary entry, m = hidden element, k = row
+// The three contractions of one chunk of R rows (d hidden size, V vocabulary):
+//   logits      Z[R, V]   = H[R, d]  . W[V, d]^T          nt: n = row, m = vocabulary entry, k = hidden element
+//   dL/dhidden  dH[R, d]  = dZ[R, V] . (W^T)[d, V]^T      nt: n = row, m = hidden element, k = vocabulary entry
+//                                                         (W^T is formed once per call)
+//   dL/dweight  dW[V, d] += dZ[R, V]^T . H[R, d]          tn: n = vocabulary entry, m = hidden element, k = row
 //
 // Tiling and memory pipeline are those of the projection kernel fused with the log-sum-exp
 // (fopd_lm_head.hip): a workgroup of eight wavefronts (2 along m x 4 along n) owns a 256 x 256 tile of the
 // result; each wavefront holds 128 (m) x 64 (n) of it as 4 x 2 accumulators of v_mfma_f32_32x32x16_bf16;
-// stages of 32 k-elements of both operand tiles are filled by direct global -> LDS loads and read back as
-// 16-byte fragments through an XOR-swizzled map without bank conflicts.  The m side of the instruction is the
-// side a lane holds four consecutive entries of, so it is the contiguous side of the output.
+// stages of 32 k-elements of both operand tiles reach the LDS through vector registers, a quarter of a pair of
+// stages per 16-k slice, and are read back as 16-byte fragments through an XOR-swizzled map without bank
+// conflicts.  The n-side fragment is the instruction's first operand: the 32 lanes of a half-wave then hold
+// consecutive m of one output row, the contiguous side of the output.
 
 #ifndef FOPD_GEMM_HIP_
 #define FOPD_GEMM_HIP_
@@ -47,8 +49,8 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 // WM x WN wavefronts share the 256 x 256 tile, each holding (256 / WM) x (256 / WN) of it.  2 x 2 (four
 // wavefronts, one per SIMD, 128 x 128 each = 256 accumulator registers) reads a third less from the LDS per
 // flop than 2 x 4 (eight wavefronts of 128 x 64): with 2 x 4 the LDS carries 192 KB of fragment reads + 64 KB of
-// direct-load writes per 64 k-elements, as many cycles at 128 bytes per clock as the matrix cores need at full
-// rate; the timing variants below show the loop bound there, not by the L2.
+// stage writes per 64 k-elements, as many cycles at 128 bytes per clock as the matrix cores need at full rate.
+// Measured, 2 x 4 is the faster shape; the timing variants below show what the loop loses where.
 //
 // PROBE != 0 are timing variants for the bound analysis (built only into the gemm_probe program; their results
 // are wrong on purpose, every access stays inside the same buffers):
@@ -383,6 +385,180 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
         if (m + 32 * i < M) {
           if (ACCUMULATE) orow[m + 32 * i] += acc[i][j][r];
           else if (PROBE == 9) __builtin_nontemporal_store(acc[i][j][r], orow + m + 32 * i);
+          else orow[m + 32 * i] = acc[i][j][r];
+        }
+      }
+    }
+}
+
+// The same contraction with both operands k-major (the contraction index is the row index of both matrices):
+//
+//   fopd_gemm_tn            Out[n, m] (+)= sum_{k < K} Bk[k, n] * Ak[k, m]
+//
+// which is the weight gradient as its operands are stored, dW[v, j] += sum_t dZ[t, v] H[t, j], without a transposed
+// copy of either.  Tiling, register staging in quarters, barrier placement and the result stores are those of
+// fopd_gemm_nt; what differs is the LDS layout and how fragments leave it.  A stage holds 32 k-rows of both
+// operand tiles as they are in memory (256 consecutive m or n per row, 512 bytes), row pitch 576 bytes so that
+// consecutive rows start 16 banks apart.  A fragment of the matrix instruction (lane = one m, eight consecutive k)
+// is two LDS transpose reads (ds_read_b64_tr_b16): within a group of 16 lanes, lane 4 e + q supplies the address of
+// four consecutive 16-bit entries and lane i receives entry i % 4 of the lanes 4 e + i / 4, e = 0..3 (measured
+// with an in-bounds probe); with lane 4 e + q pointing at row k + e, entries m + 4 q .. 4 q + 3, lane i gets rows
+// k .. k + 3 of entry m + i.  The 32 lanes of a pass read 4 rows x 64 bytes: all 64 banks once.
+//
+// K must be a positive multiple of 64.  Ak has rows_a (1 <= rows_a <= K) readable rows; rows rows_a .. K - 1 are
+// taken from row rows_a - 1, so the caller's Bk must hold zeros in every row that is not to count (Bk has K
+// readable rows).  M and N need not be multiples of the tile: 16-byte pieces past entry M - 1 / N - 1 of a row are
+// clamped (re-read) and their results discarded; M % 8 == 0, lda % 8 == 0, ldb % 8 == 0, and every row of Bk is
+// readable up to N rounded up to 8 (ldb is at least that).
+constexpr int kTnPitch = 576;                               // bytes per k-row of an operand tile in the LDS
+constexpr int kTnOperandBytes = 32 * kTnPitch;              // one operand tile of one stage
+constexpr int kTnStageBytes = 2 * kTnOperandBytes;
+constexpr int kTnLdsBytes = kLmStages * kTnStageBytes;      // 147,456 of the 163,840 bytes
+
+typedef short tn_i16x4 __attribute__((ext_vector_type(4)));
+typedef short tn_i16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 tn_read_fragment(const unsigned char* p) {
+  typedef __attribute__((address_space(3))) tn_i16x4* lds_ptr;
+  const tn_i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const tn_i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * kTnPitch));
+  const tn_i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, both);
+}
+
+template <bool ACCUMULATE>
+__global__ void __launch_bounds__(kGemmThreads)
+fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, const __bf16* __restrict__ Bk, int64_t ldb,
+             int N, int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
+  extern __shared__ __align__(16) unsigned char gemm_smem[];
+  constexpr int WM = kGemmWavesM, WN = kGemmWavesN, TI = 8 / WM, TJ = 8 / WN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  // tile order: as fopd_gemm_nt (32 workgroups of an XCD = 4 tiles along n x 8 along m)
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int m_blocks = (tiles_m + 7) >> 3;
+  const int round = slot >> 5;
+  const int tile_m = ((round % m_blocks) << 3) + ((slot >> 2) & 7);
+  const int tile_n = ((((round / m_blocks) << 3) + xcd) << 2) + (slot & 3);
+  if (tile_m >= tiles_m || tile_n >= tiles_n) return;      // whole workgroup, before any barrier
+  const int m0 = tile_m * kGemmTile, n0 = tile_n * kGemmTileN;
+
+  // global -> registers -> LDS.  A pair of stages is 64 k-rows of 512 bytes per operand = 2048 pieces of 16 bytes,
+  // four per lane: piece u of stage h is row 32 h + 16 u + tid / 32 of the pair, entries 8 (tid % 32) .. + 7 of
+  // the tile; a wave instruction covers two whole rows of the tile.
+  const int krow = tid >> 5;
+  const int a_piece = min((m0 >> 3) + (tid & 31), (M >> 3) - 1);
+  const int b_piece = min((n0 >> 3) + (tid & 31), ((N + 7) >> 3) - 1);
+  const char* Ab = reinterpret_cast<const char*>(Ak) + static_cast<int64_t>(a_piece) * 16;
+  const char* Bb = reinterpret_cast<const char*>(Bk) + static_cast<int64_t>(b_piece) * 16;
+  const int64_t lda2 = lda * 2, ldb2 = ldb * 2;
+  const int lds_piece = krow * kTnPitch + (tid & 31) * 16;
+  u32x4 staged[8];
+  // quarter g of the pair that starts at row k0: g = 0, 1 the m-side operand's stage 0 / 1, g = 2, 3 the n-side's
+  auto load_quarter = [&](int k0, int g) {
+    const int h = g & 1;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int k = k0 + 32 * h + 16 * u + krow;
+      if (g < 2) staged[2 * g + u] = *reinterpret_cast<const u32x4*>(Ab + static_cast<int64_t>(min(k, rows_a - 1)) * lda2);
+      else staged[2 * g + u] = *reinterpret_cast<const u32x4*>(Bb + static_cast<int64_t>(k) * ldb2);
+    }
+  };
+  auto write_quarter = [&](int pb, int g) {
+    unsigned char* dst = gemm_smem + (2 * pb + (g & 1)) * kTnStageBytes + (g < 2 ? 0 : kTnOperandBytes) + lds_piece;
+    *reinterpret_cast<u32x4*>(dst) = staged[2 * g];
+    *reinterpret_cast<u32x4*>(dst + 16 * kTnPitch) = staged[2 * g + 1];
+  };
+
+  // LDS -> fragment: lane 16 g + 4 e + q points at row 8 (g / 2) + e (+ 4 for the second read), entries
+  // 16 (g % 2) + 4 q .. + 3 of a 32-entry block
+  const int frag_off = (((lane >> 5) << 3) + ((lane >> 2) & 3)) * kTnPitch + (((lane >> 4) & 1) << 5) + ((lane & 3) << 3);
+  const int a_off = frag_off + wm * TI * 64;
+  const int b_off = kTnOperandBytes + frag_off + wn * TJ * 64;
+
+  f32x16 acc[TI][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i)
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  bf16x8 fa[2][TI], fb[2][TJ];
+  auto read_frags = [&](int buf, const unsigned char* stage, int ks) {
+    const unsigned char* base = stage + ks * 16 * kTnPitch;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) fa[buf][i] = tn_read_fragment(base + a_off + i * 64);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) fb[buf][j] = tn_read_fragment(base + b_off + j * 64);
+  };
+  auto multiply = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+  };
+
+  // pair 0 into the LDS, pair 1 into registers (requested in the order the loop keeps); then per pair p and 16-k
+  // slice s: quarter s of pair p + 1 -> LDS, request quarter s of pair p + 2, multiply slice s of pair p
+  const int n_pairs = K / 64;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) load_quarter(0, g);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) write_quarter(0, g);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    __builtin_amdgcn_sched_barrier(0);
+    load_quarter(n_pairs > 1 ? 64 : 0, g);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  read_frags(0, gemm_smem, 0);
+  for (int p = 0; p < n_pairs; ++p) {
+    const int pb = p & 1;
+    const unsigned char* lo = gemm_smem + 2 * pb * kTnStageBytes;
+    const unsigned char* hi = lo + kTnStageBytes;
+    const unsigned char* next = gemm_smem + 2 * (pb ^ 1) * kTnStageBytes;
+    const int k_next = min(p + 2, n_pairs - 1) * 64;       // pair p + 2; the last pair again at the tail
+    write_quarter(pb ^ 1, 0);
+    load_quarter(k_next, 0);
+    read_frags(1, lo, 1);
+    multiply(0);
+    __builtin_amdgcn_sched_barrier(0);
+    write_quarter(pb ^ 1, 1);
+    load_quarter(k_next, 1);
+    read_frags(0, hi, 0);
+    multiply(1);
+    __builtin_amdgcn_sched_barrier(0);
+    write_quarter(pb ^ 1, 2);
+    load_quarter(k_next, 2);
+    read_frags(1, hi, 1);
+    multiply(0);
+    __builtin_amdgcn_sched_barrier(0);
+    write_quarter(pb ^ 1, 3);
+    __syncthreads();
+    load_quarter(k_next, 3);
+    read_frags(0, next, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(1);
+  }
+
+  // result stores: as fopd_gemm_nt (register r of block (i, j): n = 32 j + 8 (r / 4) + 4 (lane / 32) + r % 4,
+  // m = 32 i + lane % 32)
+  const int m = m0 + wm * TI * 32 + (lane & 31);
+#pragma unroll
+  for (int j = 0; j < TJ; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int n = n0 + wn * TJ * 32 + 32 * j + ((r >> 2) << 3) + ((lane >> 5) << 2) + (r & 3);
+      if (n >= N) continue;
+      float* orow = Out + static_cast<int64_t>(n) * ldo;
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+        if (m + 32 * i < M) {
+          if (ACCUMULATE) orow[m + 32 * i] += acc[i][j][r];
           else orow[m + 32 * i] = acc[i][j][r];
         }
       }
