@@ -202,6 +202,23 @@ inline fopd_status allow_dynamic_lds(const void* kern, int bytes, bool* done) {
   return FOPD_OK;
 }
 
+// Compute units of the current device (256 when the runtime cannot say).
+inline int compute_units() {
+  static int cached[kMaxDevices] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  std::lock_guard<std::mutex> lock(g_state_mutex);
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 // Device address of `scratch` on the current device.
 inline fopd_status static_scratch(void** out) {
   int dev = 0;
@@ -297,7 +314,9 @@ fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t
   constexpr int kRegRowVectors = 19;
   const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
   if (opt.k14_regs != 0 && nvec <= static_cast<int64_t>(kRegRowThreads) * kRegRowVectors && nvec > 2 * kRegRowThreads) {
-    const dim3 grid(static_cast<unsigned>(T)), block(kRegRowThreads);
+    // one resident workgroup per compute unit, each walking rows in steps of the grid
+    const int64_t cus = compute_units();
+    const dim3 grid(static_cast<unsigned>(T < cus ? T : cus)), block(kRegRowThreads);
     if (dt == FOPD_BF16)
       fopd_k14_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(
           logits, dlogits, T, static_cast<int>(V), ld, a.token_ids, a.mask, a.lb, a.lq, a.cu, a.n_train, a.n_roll, a.lag,

@@ -288,13 +288,52 @@ __device__ __forceinline__ void row_lse(const char* row, int V, int y, LaneState
   }
 }
 
-// Merges the lanes' states; thread 0 returns lp, lse (and with ENT the row entropy) in fp64, the
-// other lanes return zeros.  Contains one __syncthreads.  sh_R / sh_S / sh_W hold NT/64 floats each.
+// Thread 0's part of the row's finish: merges the n_waves (reference, sum) pairs that the wavefronts left in
+// sh_R / sh_S (and the entropy sums in sh_W with ENT) and forms lp, lse (and the row entropy) in fp64.
+template <bool ENT>
+__device__ __forceinline__ void lse_from_partials(const float* zy_in, const float* sh_R, const float* sh_S,
+                                                  const float* sh_W, int n_waves, double& lp_out, double& lse_out,
+                                                  double& ent_out) {
+  float RR = sh_R[0];
+  for (int i = 1; i < n_waves; ++i) RR = fmaxf(RR, sh_R[i]);
+  float SS = 0.f, WW = 0.f;
+  for (int i = 0; i < n_waves; ++i) {
+    float si = sh_S[i], wi = ENT ? sh_W[i] : 0.f;
+    rebase(sh_R[i], RR, si, wi, ENT);
+    SS += si;
+    WW += wi;
+  }
+  // Everything below is in log2 units of the scaled logits x * kLog2e.
+  //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
+  //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
+  const double zyL = static_cast<double>(*zy_in) * static_cast<double>(kLog2e);
+  const double others = static_cast<double>(RR) + log2(static_cast<double>(SS));   // log2 sum_{v != y}
+  const double a2 = others - zyL;
+  const double q = exp2(-fabs(a2));                  // 2^-|a2|, in (0, 1]
+  const double l1q = log1p(q) * (1.0 / kLn2);        // log2(1 + 2^-|a2|)
+  const double sp = (a2 > 0.0 ? a2 : 0.0) + l1q;
+  lp_out = -sp * kLn2;
+  // the larger of the two parts plus the correction: stays finite when z_y = -inf (lp = -inf) or when
+  // every other logit is -inf (lp = 0)
+  lse_out = ((a2 > 0.0 ? others : zyL) + l1q) * kLn2;
+  ent_out = 0.0;
+  if (ENT) {
+    // H = h(p_y) + (1 - p_y) * H(softmax over the other tokens): the binary entropy of
+    // {y, not y} plus the conditional entropy, each a sum of non-negative terms.
+    const double a = fabs(a2);
+    const double h2 = (a < 1.0e300) ? l1q + a * q / (1.0 + q) : 0.0;
+    const double p_not = (a2 > 0.0) ? 1.0 / (1.0 + q) : q / (1.0 + q);
+    double h_ex = 0.0;
+    if (SS > 0.f) h_ex = log2(static_cast<double>(SS)) - static_cast<double>(WW) / static_cast<double>(SS);
+    if (h_ex < 0.0) h_ex = 0.0;
+    ent_out = (h2 + p_not * h_ex) * kLn2;
+  }
+}
+
+// The wavefronts' part: a common reference per wavefront, then its (reference, sum) pair into sh_R / sh_S
+// (sh_W with ENT), NT/64 floats each.  Ends with the one __syncthreads of the finish.
 template <int NT, bool ENT>
-__device__ __forceinline__ void block_lse_finish(const LaneState& st, const float* zy_in, float* sh_R,
-                                                 float* sh_S, float* sh_W, double& lp_out, double& lse_out,
-                                                 double& ent_out) {
-  // common reference first, then one rebase per lane
+__device__ __forceinline__ void block_lse_merge(const LaneState& st, float* sh_R, float* sh_S, float* sh_W) {
   const float Rw = wave_max(st.rL);
   float ls = st.s, lw = st.w;
   rebase(st.rL, Rw, ls, lw, ENT);
@@ -308,46 +347,19 @@ __device__ __forceinline__ void block_lse_finish(const LaneState& st, const floa
     if (ENT) sh_W[w] = Ww;
   }
   __syncthreads();
+}
+
+// Merges the lanes' states; thread 0 returns lp, lse (and with ENT the row entropy) in fp64, the
+// other lanes return zeros.  Contains one __syncthreads.  sh_R / sh_S / sh_W hold NT/64 floats each.
+template <int NT, bool ENT>
+__device__ __forceinline__ void block_lse_finish(const LaneState& st, const float* zy_in, float* sh_R,
+                                                 float* sh_S, float* sh_W, double& lp_out, double& lse_out,
+                                                 double& ent_out) {
+  block_lse_merge<NT, ENT>(st, sh_R, sh_S, sh_W);
   lp_out = 0.0;
   lse_out = 0.0;
   ent_out = 0.0;
-  if (threadIdx.x == 0) {
-    float RR = sh_R[0];
-#pragma unroll
-    for (int i = 1; i < NT / 64; ++i) RR = fmaxf(RR, sh_R[i]);
-    float SS = 0.f, WW = 0.f;
-#pragma unroll
-    for (int i = 0; i < NT / 64; ++i) {
-      float si = sh_S[i], wi = ENT ? sh_W[i] : 0.f;
-      rebase(sh_R[i], RR, si, wi, ENT);
-      SS += si;
-      WW += wi;
-    }
-    // Everything below is in log2 units of the scaled logits x * kLog2e.
-    //   a2 = log2( sum_{v != y} 2^(x_v) / 2^(x_y) )   log-odds of "not y"
-    //   lp = -log(1 + 2^a2),  lse = x_y + log(1 + 2^a2)
-    const double zyL = static_cast<double>(*zy_in) * static_cast<double>(kLog2e);
-    const double others = static_cast<double>(RR) + log2(static_cast<double>(SS));   // log2 sum_{v != y}
-    const double a2 = others - zyL;
-    const double q = exp2(-fabs(a2));                  // 2^-|a2|, in (0, 1]
-    const double l1q = log1p(q) * (1.0 / kLn2);        // log2(1 + 2^-|a2|)
-    const double sp = (a2 > 0.0 ? a2 : 0.0) + l1q;
-    lp_out = -sp * kLn2;
-    // the larger of the two parts plus the correction: stays finite when z_y = -inf (lp = -inf) or when
-    // every other logit is -inf (lp = 0)
-    lse_out = ((a2 > 0.0 ? others : zyL) + l1q) * kLn2;
-    if (ENT) {
-      // H = h(p_y) + (1 - p_y) * H(softmax over the other tokens): the binary entropy of
-      // {y, not y} plus the conditional entropy, each a sum of non-negative terms.
-      const double a = fabs(a2);
-      const double h2 = (a < 1.0e300) ? l1q + a * q / (1.0 + q) : 0.0;
-      const double p_not = (a2 > 0.0) ? 1.0 / (1.0 + q) : q / (1.0 + q);
-      double h_ex = 0.0;
-      if (SS > 0.f) h_ex = log2(static_cast<double>(SS)) - static_cast<double>(WW) / static_cast<double>(SS);
-      if (h_ex < 0.0) h_ex = 0.0;
-      ent_out = (h2 + p_not * h_ex) * kLn2;
-    }
-  }
+  if (threadIdx.x == 0) lse_from_partials<ENT>(zy_in, sh_R, sh_S, sh_W, NT / 64, lp_out, lse_out, ent_out);
 }
 
 // Gradient row: g_v = c * 2^(x_v log2e - lseL), the sampled token's entry replaced by gy.
@@ -634,12 +646,21 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 // =========================================================================================
 // K14R: the same call with the row held in registers between the two passes: 1024 lanes x NV 16-byte vectors
 // (NV = 19 holds a 303,872-byte row), one workgroup per compute unit.  HBM and the fabric see a single read and a
-// single write per row; the price is that a compute unit works on one row at a time, so its load phase, the
-// reduction and its store phase do not overlap with each other.  Rows longer than 1024 NV vectors do not fit and
-// take fopd_k14_fused.
+// single write per row.  A workgroup walks rows blockIdx, blockIdx + gridDim, ...: while it stores the gradient of
+// one row it requests the next one into the registers the stores have just released, so that a compute unit's
+// reads and writes overlap and the next row's latency hides behind the store phase; only the reduction between
+// them is exposed.  Rows longer than 1024 NV vectors do not fit and take fopd_k14_fused.
 // =========================================================================================
 
 constexpr int kRegRowThreads = 1024;
+
+// What a workgroup knows about a row before touching its logits.
+struct RegRowInfo {
+  bool load = false;     // the row's logits are needed (live, and either a weight or a log-prob to report)
+  int y = 0;
+  double w = 0.0;
+  int32_t n = 0, nr = 0;
+};
 
 template <int DT, int NV>
 __global__ void __launch_bounds__(kRegRowThreads)
@@ -652,123 +673,174 @@ fopd_k14_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, c
   __shared__ float sh_zy;
   __shared__ float sh_R[NT / 64];
   __shared__ float sh_S[NT / 64];
-  __shared__ float sh_c, sh_lseL, sh_gy;
-  const int64_t t = blockIdx.x;
+  __shared__ float sh_out[3];                  // c_t, lse_t log2 e, the sampled token's entry
   const int tid = threadIdx.x;
-  const int y = token_ids[t];
-  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
-  bool live = (mask == nullptr) || (mask[t] != 0);
-  if (live && (y < 0 || y >= V)) {
-    if (tid == 0) atomicOr(flags, kFlagToken);
-    live = false;
-  }
-  if (live && n_roll == nullptr && in_one_set_only(mask, t)) {
-    if (tid == 0) atomicOr(flags, kFlagSets);
-    live = false;
-  }
-  const int64_t gt = row_begin + t;
-  double w = 0.0;
-  int32_t n = 0, nr = 0;
-  if (live && gt < cu[B]) {
-    const int i = sample_of_row(cu, B, gt);
-    n = n_train[i];
-    nr = (n_roll != nullptr) ? n_roll[i] : n;
-    w = weight_of(static_cast<double>(fresh32[i]), n, nr, lag[i], hp.xi);
-  }
-  if (!live || (w == 0.0 && logp == nullptr)) {
-    if (tid == 0) {
+  const int nvec = V / E;                      // <= NT * NV, checked on the host
+  const int tail_idx = nvec * E + tid;         // ragged tail: fewer than E elements
+  const float kNegInf = -__builtin_inff();
+
+  // the same for every lane of the workgroup
+  auto classify = [&](int64_t t) {
+    RegRowInfo r;
+    if (t >= T) return r;
+    r.y = token_ids[t];
+    bool live = (mask == nullptr) || (mask[t] != 0);
+    if (live && (r.y < 0 || r.y >= V)) {
+      if (tid == 0) atomicOr(flags, kFlagToken);
+      live = false;
+    }
+    if (live && n_roll == nullptr && in_one_set_only(mask, t)) {
+      if (tid == 0) atomicOr(flags, kFlagSets);
+      live = false;
+    }
+    const int64_t gt = row_begin + t;
+    if (live && gt < cu[B]) {
+      const int i = sample_of_row(cu, B, gt);
+      r.n = n_train[i];
+      r.nr = (n_roll != nullptr) ? n_roll[i] : r.n;
+      r.w = weight_of(static_cast<double>(fresh32[i]), r.n, r.nr, lag[i], hp.xi);
+    }
+    r.load = live && !(r.w == 0.0 && logp == nullptr);
+    // the same in every lane: kept in scalar registers, the vector registers belong to the row
+    r.y = __builtin_amdgcn_readfirstlane(r.y);
+    r.n = __builtin_amdgcn_readfirstlane(r.n);
+    r.nr = __builtin_amdgcn_readfirstlane(r.nr);
+    r.load = __builtin_amdgcn_readfirstlane(r.load ? 1 : 0) != 0;
+    const uint64_t wb = __builtin_bit_cast(uint64_t, r.w);
+    const uint32_t wlo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(wb));
+    const uint32_t whi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(wb >> 32));
+    r.w = __builtin_bit_cast(double, (static_cast<uint64_t>(whi) << 32) | wlo);
+    return r;
+  };
+  // Rows are read and written through buffer descriptors (base of the row, extent = its whole 16-byte vectors):
+  // a lane's address is the descriptor plus a 32-bit byte offset, lanes past the extent read zeros and their
+  // stores are dropped by the hardware, and "no next row" is a descriptor of extent 0.  So the store phase has
+  // no branch around a load or a store, and no 64-bit address per lane: the vector registers belong to the row.
+  // The offsets are formed where they are used, from a value the compiler must take as new each time (hoisted out
+  // of the row loop, the 19 offsets would be spilled around the row).
+  const uint32_t row_bytes = static_cast<uint32_t>(nvec) * 16u;
+  auto row_of = [&](int64_t t) { return static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes; };
+  auto descriptor = [&](const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, static_cast<int>(bytes), 0x00020000);
+  };
+  const uint32_t off0 = static_cast<uint32_t>(tid) * 16u;
+  auto lane_off = [&](int u) {
+    uint32_t o = off0;
+    asm volatile("" : "+v"(o));
+    return o + static_cast<uint32_t>(u) * (NT * 16u);
+  };
+  constexpr int kNonTemporal = 2;              // cache-policy bits of the buffer instructions: nt
+  constexpr uint32_t kNegInfPacked = (DT == FOPD_BF16) ? 0xff80ff80u : 0xff800000u;
+
+  // One trip per row, plus one before the first row that only requests it: every trip ends with the same loop
+  // that stores the current row's gradient (if it has one) and requests the next row, so the row's registers are
+  // written in one place only.
+  u32x4 q[NV];
+  float tail_x = 0.f;
+  RegRowInfo cur;                              // the trip before the first row: nothing to reduce or store
+  bool have_row = false;
+  int64_t t = static_cast<int64_t>(blockIdx.x) - gridDim.x;
+  while (true) {
+    const int64_t tn = t + gridDim.x;
+    const RegRowInfo nxt = classify(tn);
+    const char* nv = row_of(nxt.load ? tn : 0);      // never dereferenced unless nxt.load
+    const auto rs_next = descriptor(nv, nxt.load ? row_bytes : 0u);
+    char* orow = static_cast<char*>(dlogits) + (have_row ? t : 0) * ld * Elem<DT>::kBytes;
+    const int y = cur.y, jy = y / E, ey = y % E;
+    float c = 0.f, lseL = 0.f, gy = 0.f;
+    if (have_row && !cur.load && tid == 0) {
       if (logp != nullptr) logp[t] = 0.f;
       row_loss[t] = 0.0;
     }
-    row_zero<DT, NT>(orow, V);
-    return;
-  }
-  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
-  const u32x4* rv = reinterpret_cast<const u32x4*>(row);
-  u32x4* ov = reinterpret_cast<u32x4*>(orow);
-  const int nvec = V / E;                      // <= NT * NV, checked on the host
-  const int jy = y / E, ey = y % E;
-  const float kNegInf = -__builtin_inff();
-  // the whole row: every load is issued before the first value is used
-  u32x4 q[NV];
+    if (cur.load) {
+      LaneState st;
 #pragma unroll
-  for (int u = 0; u < NV; ++u) {
-    const int j = tid + u * NT;
-    if (j < nvec) q[u] = __builtin_nontemporal_load(rv + j);
-  }
-  const int tail_idx = nvec * E + tid;         // ragged tail: fewer than E elements
-  float tail_x = 0.f;
-  if (tail_idx < V) tail_x = load_elem<DT>(row, tail_idx);
-  LaneState st;
+      for (int u = 0; u < NV; ++u) {
+        // the offset is made to depend on the running sum: the compiler otherwise unpacks all vectors first
+        // and accumulates afterwards, which needs the row's registers a second time
+        uint32_t o = off0;
+        asm volatile("" : "+v"(o) : "v"(st.s));
+        const int j = static_cast<int>((o + static_cast<uint32_t>(u) * (NT * 16u)) >> 4);
+        u32x4 v = q[u];
+        if (j >= nvec) v = u32x4{kNegInfPacked, kNegInfPacked, kNegInfPacked, kNegInfPacked};   // selects
+        float x[E];
+        unpack<DT>(v, x);
+        if (j == jy) {
 #pragma unroll
-  for (int u = 0; u < NV; ++u) {
-    const int j = tid + u * NT;
-    if (j < nvec) {
-      float x[E];
-      unpack<DT>(q[u], x);
-      if (j == jy) {
-#pragma unroll
-        for (int e = 0; e < E; ++e) {
-          if (e == ey) {
-            sh_zy = x[e];
-            x[e] = kNegInf;
+          for (int e = 0; e < E; ++e) {
+            if (e == ey) {
+              sh_zy = x[e];
+              x[e] = kNegInf;
+            }
           }
         }
+        accumulate<E, false>(x, st);
+        __builtin_amdgcn_sched_barrier(0);     // one vector at a time: unpacked early, the row would not fit
       }
-      accumulate<E, false>(x, st);
-    }
-  }
-  if (tail_idx < V) {
-    float x1 = tail_x;
-    if (tail_idx == y) {
-      sh_zy = x1;
-      x1 = kNegInf;
-    }
-    accumulate<1, false>(&x1, st);
-  }
-  double lp, ls, ent;
-  block_lse_finish<NT, false>(st, &sh_zy, sh_R, sh_S, nullptr, lp, ls, ent);
-  if (tid == 0) {
-    const float lp32 = static_cast<float>(lp);
-    const float lse32 = static_cast<float>(ls);
-    if (logp != nullptr) logp[t] = lp32;
-    float c = 0.f;
-    double lt = 0.0;
-    if (w > 0.0)
-      c = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], w, n, nr, in_sup_set(mask, t),
-                        in_roll_set(mask, t), B, hp, grad_scale, &lt);
-    row_loss[t] = lt;
-    sh_c = c;
-    sh_lseL = lse32 * kLog2e;
-    sh_gy = c * expm1f(lp32);
-  }
-  __syncthreads();
-  const float c = sh_c;
-  if (c == 0.f) {
-    row_zero<DT, NT>(orow, V);
-    return;
-  }
-  const float lseL = sh_lseL, gy = sh_gy;
-#pragma unroll
-  for (int u = 0; u < NV; ++u) {
-    const int j = tid + u * NT;
-    if (j < nvec) {
-      float x[E];
-      unpack<DT>(q[u], x);
-#pragma unroll
-      for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
-      if (j == jy) {
-#pragma unroll
-        for (int e = 0; e < E; ++e)
-          if (e == ey) x[e] = gy;
+      if (tail_idx < V) {
+        float x1 = tail_x;
+        if (tail_idx == y) {
+          sh_zy = x1;
+          x1 = kNegInf;
+        }
+        accumulate<1, false>(&x1, st);
       }
-      __builtin_nontemporal_store(pack<DT>(x), ov + j);
+      block_lse_merge<NT, false>(st, sh_R, sh_S, nullptr);
+      if (tid == 0) {
+        double lp, ls, ent;
+        lse_from_partials<false>(&sh_zy, sh_R, sh_S, nullptr, NT / 64, lp, ls, ent);
+        const float lp32 = static_cast<float>(lp);
+        const float lse32 = static_cast<float>(ls);
+        if (logp != nullptr) logp[t] = lp32;
+        float c0 = 0.f;
+        double lt = 0.0;
+        if (cur.w > 0.0)
+          c0 = coef_and_loss(static_cast<double>(lp32), behav_logp[t], teacher_logp[t], cur.w, cur.n, cur.nr,
+                             in_sup_set(mask, t), in_roll_set(mask, t), B, hp, grad_scale, &lt);
+        row_loss[t] = lt;
+        sh_out[0] = c0;
+        sh_out[1] = lse32 * kLog2e;
+        sh_out[2] = c0 * expm1f(lp32);
+      }
+      __syncthreads();
+      c = sh_out[0];
+      lseL = sh_out[1];
+      gy = sh_out[2];
     }
-  }
-  if (tail_idx < V) {
-    float g = c * fast_exp2(fmaf(tail_x, kLog2e, -lseL));
-    if (tail_idx == y) g = gy;
-    store_elem<DT>(orow, tail_idx, g);
+    const bool grad = (c != 0.f);              // the same in every lane
+    if (have_row && !grad) row_zero<DT, NT>(orow, V);
+    const auto rs_out = descriptor(orow, grad ? row_bytes : 0u);     // extent 0: every store dropped
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const uint32_t o = lane_off(u);
+      if (grad) {
+        float x[E];
+        unpack<DT>(q[u], x);
+#pragma unroll
+        for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+        if (static_cast<int>(o >> 4) == jy) {
+#pragma unroll
+          for (int e = 0; e < E; ++e)
+            if (e == ey) x[e] = gy;
+        }
+        __builtin_amdgcn_raw_buffer_store_b128(pack<DT>(x), rs_out, o, 0, kNonTemporal);
+      }
+      q[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_next, o, 0, kNonTemporal);   // the register is free again
+      __builtin_amdgcn_sched_barrier(0);       // one vector at a time
+    }
+    if (tail_idx < V) {
+      if (grad) {
+        float g = c * fast_exp2(fmaf(tail_x, kLog2e, -lseL));
+        if (tail_idx == y) g = gy;
+        store_elem<DT>(orow, tail_idx, g);
+      }
+      if (nxt.load) tail_x = load_elem<DT>(nv, tail_idx);
+    }
+    // sh_out is rewritten only after the next row's reduction, which has a barrier of its own
+    if (tn >= T) break;
+    t = tn;
+    cur = nxt;
+    have_row = true;
   }
 }
 
