@@ -573,11 +573,13 @@ def round_to_f32(x):
 
 def fopd_loss_fwd_bwd(logits, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
                       seq_lens, lag, alpha, beta, xi, lam, grad_scale=1.0,
-                      out_dtype="f32", want_dlogits=True, ld=None):
+                      out_dtype="f32", want_dlogits=True, ld=None, unit_rows=False):
     """Runs every step on whole arrays and returns a dict of all intermediate and final values.
 
     logits: [T, V] float array (bf16 inputs must be widened exactly by the caller).
     out_dtype: "f32" or "bf16" - the storage type dlogits is rounded to.
+    unit_rows: also return the gradient rows at unit sample weight (coef_unit, unit_rows_exact, unit_rows):
+    dlogits_exact[t] = weights[i(t)] * unit_rows_exact[t].
     """
     logits = np.asarray(logits)
     T, V = logits.shape
@@ -605,4 +607,16 @@ def fopd_loss_fwd_bwd(logits, token_ids, mask, behav_logp, teacher_logp, teacher
             g[t] = dlogits_row(logits[t], int(token_ids[t]), lse[t], coef[t])
         res["dlogits_exact"] = g
         res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
+    if unit_rows:
+        # The weight is a constant of the sample in the gradient (Algorithm 1 applies it to the sample's loss
+        # term; Eq. weight is not differentiated), so dL/dz_t = w_i u_t with u_t the row's gradient at w_i = 1:
+        # only w_i needs every row of the sample, u_t needs row t alone.  Invalid samples have no loss term.
+        ones = np.where(np.asarray(n_valid) > 0, 1.0, 0.0)
+        coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, grad_scale, n_roll=n_roll)
+        res["coef_unit"] = coef_unit
+        u = np.zeros((T, V), dtype=np.float64)
+        for t in range(T):
+            u[t] = dlogits_row(logits[t], int(token_ids[t]), lse[t], coef_unit[t])
+        res["unit_rows_exact"] = u
+        res["unit_rows"] = round_to_bf16(u) if out_dtype == "bf16" else round_to_f32(u)
     return res

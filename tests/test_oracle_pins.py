@@ -862,6 +862,58 @@ def test_two_aligned_sets_gradient_by_finite_differences():
     assert np.max(np.abs(num - res["dlogits_exact"])) < 1e-6 * np.max(np.abs(num))
 
 
+def test_unit_rows_are_the_gradient_of_the_sample_terms_and_scale_to_the_full_gradient():
+    """Gradient rows at unit sample weight (the weight is a constant of the sample in the semi-gradient):
+    (a) they are the finite-difference gradient of G(z) = g/B sum over valid samples of (l_i-surrogate + lambda
+    D_i^roll), written here with scipy's log-softmax and no weight at all; (b) weight x unit row is the full
+    gradient row, also for gated samples (unit row non-zero, product zero); (c) an invalid sample has zero rows."""
+    c = _two_set_case(36)
+    T, V = c["z"].shape
+    hp = dict(alpha=0.5, beta=0.5, xi=0.5, lam=0.8)             # gates the sample with lag 1
+    res = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                grad_scale=1.7, unit_rows=True, **hp)
+    B = len(c["seq"])
+    cu = orc.segment_offsets(c["seq"])
+    n_sup, n_roll = orc.trainable_counts(c["mask"], cu), orc.roll_counts(c["mask"], cu)
+    sample_of = np.repeat(np.arange(B), c["seq"])
+
+    def G(zz):
+        lp_all = scipy.special.log_softmax(zz, axis=1)
+        tot = 0.0
+        for t in range(T):
+            i = sample_of[t]
+            if n_sup[i] == 0 or n_roll[i] == 0:
+                continue
+            lp = lp_all[t, c["y"][t]]
+            if c["mask"][t] in (1, 3):
+                tot += 1.7 / (B * n_sup[i]) * 0.5 * (lp - c["lq"][t]) ** 2
+            if c["mask"][t] in (1, 2):
+                d = lp - c["lb"][t]
+                tot += 1.7 / (B * n_roll[i]) * hp["lam"] * (math.exp(d) * d - math.exp(d) + 1.0)
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = c["z"].copy(), c["z"].copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (G(zp) - G(zm)) / (2 * h)
+    u = res["unit_rows_exact"]
+    assert np.max(np.abs(num)) > 1e-3 and np.max(np.abs(num - u)) < 1e-6 * np.max(np.abs(num))
+    w_rows = np.repeat(res["weights"], c["seq"])[:, None]
+    np.testing.assert_allclose(w_rows * u, res["dlogits_exact"], rtol=1e-14, atol=0.0)
+    gated = [i for i in range(B) if res["weights"][i] == 0.0 and min(n_sup[i], n_roll[i]) > 0]
+    live = [i for i in range(B) if res["weights"][i] > 0.0]
+    invalid = [i for i in range(B) if min(n_sup[i], n_roll[i]) == 0]
+    assert gated and live and invalid                                 # the case holds all three kinds
+    for i in gated:
+        assert np.any(u[cu[i]:cu[i + 1]] != 0.0) and np.all(res["dlogits_exact"][cu[i]:cu[i + 1]] == 0.0)
+    for i in invalid:
+        assert np.all(u[cu[i]:cu[i + 1]] == 0.0)
+    assert np.array_equal(res["unit_rows"], orc.round_to_f32(u))
+
+
 def test_two_aligned_sets_in_the_two_tensor_variants():
     """Full-vocabulary drift and distribution-level loss with the sets apart: D^roll over U^roll, the
     token loss over U^sup, checked against the definitions evaluated with scipy."""

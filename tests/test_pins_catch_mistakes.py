@@ -53,6 +53,11 @@ MISTAKES = {
     "roll coverage reported as sup coverage": (
         "mroll = mbar if cover_roll is None else math.fsum(float(x) for x in cover_roll) / B", "mroll = mbar"),
     "aligned sets swapped": ("    return int(m) != 0 and int(m) != 2\n", "    return int(m) != 0 and int(m) != 3\n"),
+    "unit rows keep the sample weight": (
+        "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, grad_scale, n_roll=n_roll)",
+        "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)"),
+    "unit rows for a sample with one aligned set empty": (
+        "ones = np.where(np.asarray(n_valid) > 0, 1.0, 0.0)", "ones = np.where(np.asarray(n) > 0, 1.0, 0.0)"),
     "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
     "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
                                       "return float(np.log(np.sum(np.exp(z - mx))))"),
