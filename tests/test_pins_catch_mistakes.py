@@ -56,8 +56,9 @@ MISTAKES = {
     "unit rows keep the sample weight": (
         "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, grad_scale, n_roll=n_roll)",
         "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, w, lam, grad_scale, n_roll=n_roll)"),
-    "unit rows for a sample with one aligned set empty": (
-        "ones = np.where(np.asarray(n_valid) > 0, 1.0, 0.0)", "ones = np.where(np.asarray(n) > 0, 1.0, 0.0)"),
+    "unit rows lose the upstream scale": (
+        "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, grad_scale, n_roll=n_roll)",
+        "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, 1.0, n_roll=n_roll)"),
     "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
     "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
                                       "return float(np.log(np.sum(np.exp(z - mx))))"),
