@@ -379,6 +379,26 @@ def main():
     scored_elapsed = time.perf_counter() - t1
     fb.fopd_profile_enable(False)
     k14_ms, k14_n = fb.fopd_profile_read(2)
+
+    # Also beside the headline: the whole pass (log-probs, scores, weights, loss, gradient rows) with the logits
+    # read once.  The rows come out at unit sample weight (dL/dz_t = w_i u_t; the caller folds the weight into
+    # the next operation), so this is not the headline's output and is reported separately.
+    def unit_call():
+        fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                                  w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, 1.0,
+                                  lp.loss, lp.freshness, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+
+    for _ in range(args.warmup):
+        unit_call()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        unit_call()
+    torch.cuda.synchronize()
+    unit_elapsed = time.perf_counter() - t2
+    st, flags = lp.status()
+    if st != 0:
+        sys.exit("device flags set: %d" % flags)
     ms_per_step = elapsed / args.steps * 1e3
     n_train = w["n_trainable"]
 
@@ -425,6 +445,13 @@ def main():
         "ms_per_call": scored_elapsed / args.steps * 1e3, "tokens/s": n_train * args.steps / scored_elapsed,
         "kernel_avg_ms": k14_avg_s * 1e3, "GB/s": k4_bytes / k14_avg_s / 1e9,
         "frac": k4_bytes / k14_avg_s / 1e9 / HBM_PEAK_GBS}
+    unit_bytes = k1_rows * 2 * V * e + (T - k1_rows) * V * e + T * side
+    out["single_read_unit_rows"] = {
+        "call": "fopd_loss_fwd_bwd_unit (whole pass with each logits row read once: log-probs, scores, weights, loss, "
+                "and the gradient rows at unit sample weight, dL/dz_t = w_i u_t)",
+        "ms_per_call": unit_elapsed / args.steps * 1e3, "tokens/s": n_train * args.steps / unit_elapsed,
+        "GB/s": unit_bytes / (unit_elapsed / args.steps) / 1e9,
+        "frac": unit_bytes / (unit_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, hp)
     if not args.no_projection:

@@ -220,6 +220,35 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same pass with the logits read once: gradient rows at unit sample weight.
+ *
+ * In dL/dz_t = c_t (softmax(z_t) - onehot(y_t)) only the factor w_i of c_t (Eq. "weight", a constant of the
+ * sample in the gradient: Algorithm 1 applies it to the sample's loss term) needs every row of the sample; the
+ * rest, u_t = g / B ( [t in U^sup] A_t / |U_i^sup| - [t in U^roll] lambda rho_t delta_t / |U_i^roll| )
+ * (softmax(z_t) - onehot(y_t)), needs row t alone.  fopd_loss_fwd_bwd therefore reads the logits twice (log-probs,
+ * then scores, then gradient); this call reads each row once, writes u_t and returns the weights:
+ *     dL/dz_t = weights[i(t)] * unit_rows[t].
+ * The caller applies the row scale where it is cheapest: it commutes with whatever consumes the rows next (the
+ * output projection's backward contractions: scale the [T, d] result or operand instead of the [T, V] rows).
+ * A gated sample (w_i = 0 < f_i) has non-zero unit rows and weight 0; an invalid sample (an aligned set empty,
+ * negative lag) has zero rows.  loss, freshness, weights and logp are those of fopd_loss_fwd_bwd on the same
+ * inputs, formed by the same kernels from these log-probs (which come from the 1024-lane row partition when the
+ * row is held in registers, see fopd_set_option "k14_regs": last-place differences from fopd_token_logprobs).
+ * Whole samples only (sum(seq_lens) == T).  Rows too long for the registers (more than 19456 16-byte vectors)
+ * are read twice by this call too, the second time right after the first.
+ *   arguments as in fopd_loss_fwd_bwd; unit_rows [T, ld] of `dt` out, MAY alias `logits`
+ */
+fopd_status fopd_loss_fwd_bwd_unit(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                   const int32_t* token_ids, const uint8_t* mask,
+                                   const float* behav_logp, const float* teacher_logp,
+                                   const float* teacher_logp_stale,
+                                   const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                   float grad_scale,
+                                   float* loss, float* freshness, float* weights, float* logp,
+                                   void* unit_rows,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * fopd_loss_fwd_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
  * capture, tight serving / training loops, harnesses that forbid allocation.  Same arguments, modes, kernels
  * and results (bit for bit) as fopd_loss_fwd_bwd, except that the scratch memory is an array inside the

@@ -17,7 +17,7 @@ FOPD_BF16 = 1
 
 SYMBOLS = (
     "fopd_status_string", "fopd_workspace_bytes", "fopd_workspace_init", "fopd_workspace_status", "fopd_flags_status",
-    "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd", "fopd_loss_fwd_bwd_static",
+    "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd", "fopd_loss_fwd_bwd_unit", "fopd_loss_fwd_bwd_static",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
     "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
     "fopd_lm_head_workspace_bytes", "fopd_lm_head_token_logprobs",
@@ -105,6 +105,9 @@ def load_library():
     lib.fopd_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                       vp, vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fopd_loss_fwd_bwd_unit.restype = ctypes.c_int
+    lib.fopd_loss_fwd_bwd_unit.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
+                                           f32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fopd_loss_fwd_bwd_static.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_static.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                              vp, vp, vp, i64, vp, vp, f32, vp, vp, vp, vp, vp, vp, vp]
@@ -280,6 +283,25 @@ def fopd_loss_fwd_bwd(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher
         _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
         _ptr(logp, f32, "logp"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
     _check(st, "fopd_loss_fwd_bwd")
+
+
+def fopd_loss_fwd_bwd_unit(logits, dt, T, V, ld, token_ids, mask, behav_logp, teacher_logp, teacher_logp_stale,
+                           seq_lens, lag, B, hp, grad_scale, loss, freshness, weights, logp, unit_rows, workspace,
+                           stream=None):
+    import torch
+    f32 = torch.float32
+    mat = (torch.float32, torch.bfloat16)
+    p, n = _ws(workspace)
+    st = load_library().fopd_loss_fwd_bwd_unit(
+        _ptr(logits, mat, "logits"), int(dt), int(T), int(V), int(ld),
+        _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(teacher_logp_stale, f32, "teacher_logp_stale"),
+        _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
+        float(grad_scale), _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"),
+        _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"), _ptr(unit_rows, mat, "unit_rows"), p, n,
+        _stream(stream))
+    _check(st, "fopd_loss_fwd_bwd_unit")
 
 
 FOPD_STATIC_MAX_ROWS = 32768

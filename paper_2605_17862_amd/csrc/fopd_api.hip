@@ -570,6 +570,52 @@ fopd_status fopd_loss_fwd_bwd(const void* logits, fopd_dtype dt, int64_t T, int6
                               static_cast<hipStream_t>(stream), true);
 }
 
+fopd_status fopd_loss_fwd_bwd_unit(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                   const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                                   const float* teacher_logp, const float* teacher_logp_stale,
+                                   const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp,
+                                   float grad_scale, float* loss, float* freshness, float* weights, float* logp,
+                                   void* unit_rows, void* workspace, size_t workspace_bytes, void* stream) {
+  fopd_status st = loss_fwd_bwd_check_args(logits, dt, T, V, ld, token_ids, behav_logp, teacher_logp, seq_lens, lag, B,
+                                           hp, nullptr, nullptr, nullptr, 0, nullptr, nullptr, loss, unit_rows);
+  if (st != FOPD_OK) return st;
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Workspace w(T, B);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
+  double* f64 = at<double>(workspace, w.fresh64);
+  float* coef = at<float>(workspace, w.coef);
+  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+  double* partials = at<double>(workspace, w.partials);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, T, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  fopd_count_train<<<B, kSegThreads, 0, s>>>(mask, cu, T, nws, nrws);
+  if ((st = launched()) != FOPD_OK) return st;
+  // the one pass over the logits: log-probs and the rows at unit weight (no scores: fresh32 == nullptr)
+  const RowPassArgs a{token_ids, mask, behav_logp, teacher_logp, cu, nws, nrws, lag, nullptr, B,
+                      0, hp, grad_scale, logp_ws, partials, flags};
+  if ((st = launch_k14(logits, unit_rows, dt, T, V, ld, a, s, true)) != FOPD_OK) return st;
+  // scores, weights and the loss from the log-probs, exactly as the two-pass call forms them
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, nullptr, nullptr, teacher_logp, teacher_logp_stale,
+                                               mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                               nullptr, nullptr, nullptr, f64, nws, nrws);
+  if ((st = launched()) != FOPD_OK) return st;
+  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
+  if (T > 0) {
+    fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp_ws, behav_logp, teacher_logp, mask, cu, nws, nrws, lag, f64, nullptr, T, B, 0, hp, grad_scale, coef,
+        partials, flags);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, nrws, lag, f64, nullptr, B, hp.xi, loss, weights,
+                                            freshness);
+  return launched();
+}
+
 fopd_status fopd_loss_fwd_bwd_static(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                                      const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
                                      const float* teacher_logp, const float* teacher_logp_stale,

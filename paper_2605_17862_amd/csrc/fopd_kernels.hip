@@ -463,6 +463,14 @@ __device__ __forceinline__ double weight_of(double f, int32_t n_sup, int32_t n_r
   return w > 0.0 ? w : 0.0;
 }
 
+// The weight of the kernels that make both passes over a row: from the supplied scores, or, when there are none
+// (fresh32 == nullptr: the gradient rows are wanted at unit sample weight), 1 for a valid sample and 0 otherwise.
+__device__ __forceinline__ double row_pass_weight(const float* fresh32, int i, int32_t n_sup, int32_t n_roll,
+                                                  int32_t lag, float xi) {
+  if (fresh32 == nullptr) return (n_sup <= 0 || n_roll <= 0 || lag < 0) ? 0.0 : 1.0;
+  return weight_of(static_cast<double>(fresh32[i]), n_sup, n_roll, lag, xi);
+}
+
 // Row coefficient c_t and the row's share of the loss, from the fp32-rounded log-prob:
 //   c_t = g w / B ( [t in U^sup] (lq - lp) / |U^sup|  -  [t in U^roll] lambda rho d / |U^roll| ).
 __device__ __forceinline__ float coef_and_loss(double lp, double lb, double lq, double w, int32_t n_sup,
@@ -605,7 +613,7 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
     const int i = sample_of_row(cu, B, gt);
     n = n_train[i];
     nr = (n_roll != nullptr) ? n_roll[i] : n;
-    w = weight_of(static_cast<double>(fresh32[i]), n, nr, lag[i], hp.xi);
+    w = row_pass_weight(fresh32, i, n, nr, lag[i], hp.xi);
   }
   if (!live || (w == 0.0 && logp == nullptr)) {   // nothing to learn from this row: no read at all
     if (tid == 0) {
@@ -698,7 +706,7 @@ fopd_k14_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, c
       const int i = sample_of_row(cu, B, gt);
       r.n = n_train[i];
       r.nr = (n_roll != nullptr) ? n_roll[i] : r.n;
-      r.w = weight_of(static_cast<double>(fresh32[i]), r.n, r.nr, lag[i], hp.xi);
+      r.w = row_pass_weight(fresh32, i, r.n, r.nr, lag[i], hp.xi);
     }
     r.load = live && !(r.w == 0.0 && logp == nullptr);
     // the same in every lane: kept in scalar registers, the vector registers belong to the row

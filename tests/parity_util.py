@@ -37,14 +37,14 @@ def np64(t):
     return t.detach().cpu().double().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
 
 
-def oracle_full(w, hp, grad_scale=1.0, want_dlogits=True):
+def oracle_full(w, hp, grad_scale=1.0, want_dlogits=True, unit_rows=False):
     """The oracle on a whole (small) workload."""
     alpha, beta, xi, lam = hp
     V = w["V"]
     return orc.fopd_loss_fwd_bwd(np64(w["logits"])[:, :V], np64(w["token_ids"]), np64(w["mask"]),
                                  np64(w["behav_logp"]), np64(w["teacher_logp"]), np64(w["teacher_logp_stale"]),
                                  np64(w["seq_lens"]), np64(w["lag"]), alpha, beta, xi, lam, grad_scale,
-                                 out_dtype=w["dtype"], want_dlogits=want_dlogits, ld=w["ld"])
+                                 out_dtype=w["dtype"], want_dlogits=want_dlogits, ld=w["ld"], unit_rows=unit_rows)
 
 
 def assert_close(name, got, want, rtol=0.0, atol=0.0):

@@ -496,6 +496,66 @@ def test_two_passes_per_row_kernel_matches_separate_kernels(threads, rows_per_cu
         fb.fopd_set_option("k14_regs", 1)
 
 
+@pytest.mark.parametrize("dtype,V,ld,workload", [("bf16", 16392, 16392, "tooluse"), ("bf16", 151936, 151936, "tooluse"),
+                                                 ("bf16", 5003, 5008, "tooluse"), ("f32", 9001, 9004, "tooluse"),
+                                                 ("bf16", 20000, 20000, "two_sets")])
+def test_single_read_call_returns_rows_at_unit_weight(dtype, V, ld, workload):
+    """fopd_loss_fwd_bwd_unit reads each row once and returns u_t with dL/dz_t = w_i u_t.  Against the oracle:
+    the rows at unit weight (2 ulp of the storage type plus the coefficient floor of the log-prob error alone:
+    no score enters u_t), log-probs, scores, weights and loss; a gated sample keeps non-zero rows under weight 0,
+    an invalid one has zero rows; and weight x row reproduces the two-read call's gradient."""
+    _say("single-read call, rows at unit weight: %s V=%d (%s)" % (dtype, V, workload))
+    if workload == "two_sets":
+        w = wl.generate("tooluse", DEV, seed=41, B=6, turns=2, obs_lo=2, obs_hi=5, resp_lo=3, resp_hi=8, V=V, ld=ld,
+                        dtype=dtype, boost=4, lag_lo=0, lag_hi=30, row_block=32, aligned_split=(0.3, 0.3))
+    else:
+        w = wl.generate("tooluse", DEV, seed=17, B=6, turns=2, obs_lo=2, obs_hi=5, resp_lo=3, resp_hi=9, V=V, ld=ld,
+                        dtype=dtype, boost=min(4, V), lag_lo=0, lag_hi=30, row_block=32)
+    T, B = w["T"], w["B"]
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 0.75
+    ref = oracle_full(w, hp, gs, want_dlogits=True, unit_rows=True)
+    lp = _pass_for(w)
+    lp.dlogits.fill_(7.0)
+    fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"],
+                              w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, gs, lp.loss,
+                              lp.freshness, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    live = np64(w["mask"]) != 0
+    assert_close("logp", np64(lp.logp), ref["logp"], atol=1e-4)
+    assert_close("logp (relative)", np64(lp.logp)[live], ref["logp"][live], rtol=1e-5, atol=2e-6)
+    assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(lp.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12, (float(lp.loss), ref["loss"])
+    valid = np.minimum(ref["n_train"], ref["n_roll"]) > 0
+    unit_ref = dict(ref, weights=valid.astype(np.float64), freshness=np.zeros(B))
+    eps_c = coef_uncertainty(unit_ref, hp, gs, B, np64(w["mask"]))
+    got = np64(lp.dlogits)
+    y = ref["gather_idx"] - np.arange(T) * ld
+    check_grad_rows(got[:, :V], np64(w["logits"])[:, :V], y, ref["lse"], ref["coef_unit"], eps_c, dtype)
+    if ld > V:
+        assert bool((lp.dlogits[:, V:] == 7.0).all())
+    cu = ref["cu_seqlens"]
+    gated = [i for i in range(B) if valid[i] and ref["weights"][i] == 0.0]
+    assert gated and bool(np.any(ref["weights"] > 0))
+    for i in gated:
+        assert float(lp.weights[i]) == 0.0 and bool(np.any(got[cu[i]:cu[i + 1], :V] != 0.0))
+    for i in range(B):
+        if not valid[i]:
+            assert bool(np.all(got[cu[i]:cu[i + 1], :V] == 0.0))
+    # weight x row against the two-read call: the product is rounded a second time
+    two = _pass_for(w)
+    two.loss_fwd_bwd(w, hp, gs)
+    _sync_ok(two)
+    w_rows = np.repeat(np64(lp.weights), np64(w["seq_lens"]).astype(np.int64))[:, None]
+    full = np64(two.dlogits)[:, :V]
+    ulp = orc.bf16_ulp(full) if dtype == "bf16" else np.abs(full) * 2.0 ** -23
+    prod = w_rows * got[:, :V]
+    eps_rows = coef_uncertainty(ref, hp, gs, B, np64(w["mask"]))[:, None] * 2.0
+    assert bool(np.all(np.abs(prod - full) <= 2.0 * ulp + eps_rows + 1e-30))
+    assert abs(float(two.loss) - float(lp.loss)) <= 2e-6 * abs(float(two.loss)) + 1e-12
+    assert torch.allclose(two.weights, lp.weights, rtol=2e-6, atol=1e-7)
+
+
 # ---------------------------------------------------------------------------------------
 # full-vocabulary rollout drift (the diagnostic as printed in the paper)
 # ---------------------------------------------------------------------------------------
