@@ -857,8 +857,12 @@ def _oracle_sample(w, i, cu, hp, B, logits=None, block=2048):
     coef = orc.grad_coefficients(delta, rho, adv, mask, cu1, n, wt, hp[3], 1.0, n_samples=B)
     ref = dict(coef=coef, cu_seqlens=cu1, n_train=n, freshness=f, weights=wt, adv=adv, rho=rho, delta=delta)
     eps_c = coef_uncertainty(ref, hp, 1.0, B, mask)
+    # the same at unit sample weight (what the single-read call writes): no score enters
+    ones = (n > 0).astype(np.float64)
+    coef_unit = orc.grad_coefficients(delta, rho, adv, mask, cu1, n, ones, hp[3], 1.0, n_samples=B)
+    eps_unit = coef_uncertainty(dict(ref, weights=ones, freshness=np.zeros(1)), hp, 1.0, B, mask)
     return dict(a=a, b=b, y=y, mask=mask, lse=lse, logp=lpo, D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover,
-                n=n, f=f, w=wt, coef=coef, eps_c=eps_c)
+                n=n, f=f, w=wt, coef=coef, eps_c=eps_c, coef_unit=coef_unit, eps_unit=eps_unit)
 
 
 def _check_sample(o, i, logp, lse, freshness, weights, st):
@@ -879,7 +883,7 @@ def _check_sample(o, i, logp, lse, freshness, weights, st):
         assert int(st.n_train[i]) == int(o["n"][0])
 
 
-def _check_sample_grad_rows(o, i, w, get_rows, picks, logits=None):
+def _check_sample_grad_rows(o, i, w, get_rows, picks, logits=None, unit=False):
     """picks: row numbers inside the sample; get_rows(global_rows) returns the GPU gradient rows."""
     V = w["V"]
     src = w["logits"] if logits is None else logits
@@ -887,7 +891,8 @@ def _check_sample_grad_rows(o, i, w, get_rows, picks, logits=None):
     idx = torch.from_numpy(np.asarray(picks) + o["a"] - off).to(DEV)
     z = np64(src[idx][:, :V])
     got = np64(get_rows(np.asarray(picks) + o["a"]))[:, :V]
-    check_grad_rows(got, z, o["y"][picks], o["lse"][picks], o["coef"][picks], o["eps_c"][picks], w["dtype"],
+    coef, eps = ("coef_unit", "eps_unit") if unit else ("coef", "eps_c")
+    check_grad_rows(got, z, o["y"][picks], o["lse"][picks], o[coef][picks], o[eps][picks], w["dtype"],
                     rows_label="s%d:" % i)
 
 
@@ -983,6 +988,26 @@ def test_reasoning_full_size_sampled_parity():
         picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 6).astype(int))
         _check_sample_grad_rows(o, i, w, lambda rows_: lp.dlogits[torch.from_numpy(rows_).to(DEV)], picks)
     _row_properties(w, cu, lambda t: lp.dlogits[t], lp.weights, n_rows=24)
+    # the whole pass with the logits read once, at this size: rows at unit sample weight, scores, weights, loss
+    _say("single-read call at full size")
+    lp.dlogits.fill_(2.0)
+    lp.logp.fill_(2.0)
+    lp.weights.fill_(2.0)
+    lp.freshness.fill_(2.0)
+    fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                              w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, HP, 1.0, lp.loss,
+                              lp.freshness, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    assert torch.allclose(lp.logp, first_logp, rtol=2e-6, atol=2e-6)
+    assert abs(float(lp.loss) - first_loss) <= 2e-6 * abs(first_loss)
+    assert torch.allclose(lp.freshness, f_in, rtol=2e-6, atol=0.0)
+    for i in chosen:
+        o = oracle_samples[i]
+        assert abs(float(lp.freshness[i]) - o["f"][0]) <= 1e-5 * o["f"][0]
+        assert abs(float(lp.weights[i]) - o["w"][0]) <= 1e-5 * o["f"][0]
+        picks = np.unique(np.linspace(0, o["b"] - o["a"] - 1, 6).astype(int))
+        _check_sample_grad_rows(o, i, w, lambda rows_: lp.dlogits[torch.from_numpy(rows_).to(DEV)], picks, unit=True)
+    _row_properties(w, cu, lambda t: lp.dlogits[t], torch.ones_like(lp.weights), n_rows=24)
 
 
 def test_tooluse_full_size_sampled_parity():
