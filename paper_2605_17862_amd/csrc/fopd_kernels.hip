@@ -657,7 +657,9 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 // single write per row.  A workgroup walks rows blockIdx, blockIdx + gridDim, ...: while it stores the gradient of
 // one row it requests the next one into the registers the stores have just released, so that a compute unit's
 // reads and writes overlap and the next row's latency hides behind the store phase; only the reduction between
-// them is exposed.  Rows longer than 1024 NV vectors do not fit and take fopd_k14_fused.
+// them is exposed.  Rows longer than 1024 NV vectors do not fit and take fopd_k14_fused.  Without scores
+// (fresh32 == nullptr) both kernels take weight 1 for every valid sample: the rows at unit sample weight of
+// fopd_loss_fwd_bwd_unit, which needs the logits only once because the scores follow from the log-probs written here.
 // =========================================================================================
 
 constexpr int kRegRowThreads = 1024;
