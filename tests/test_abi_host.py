@@ -99,6 +99,33 @@ def test_loss_rejects_bad_arguments_before_launch():
     assert _loss(lib, wsb=256) == 5
 
 
+def _unit(lib, **kw):
+    a = dict(logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, mask=None, lb=4096, lq=4096, lqs=None,
+             seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), g=1.0, loss=4096, f=None, w=None, lp=None,
+             rows=8192, ws=4096, wsb=1 << 20)
+    a.update(kw)
+    return lib.fopd_loss_fwd_bwd_unit(P(a["logits"]), a["dt"], a["T"], a["V"], a["ld"], P(a["ids"]), P(a["mask"]),
+                                      P(a["lb"]), P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"],
+                                      a["hp"], a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]),
+                                      P(a["rows"]), P(a["ws"]), a["wsb"], None)
+
+
+def test_single_read_call_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _unit(lib, logits=None) == 1
+    assert _unit(lib, rows=None) == 1
+    assert _unit(lib, loss=None) == 1
+    assert _unit(lib, lq=None) == 1
+    assert _unit(lib, lag=None) == 1
+    assert _unit(lib, B=0) == 2
+    assert _unit(lib, V=0) == 2
+    assert _unit(lib, dt=3) == 4
+    assert _unit(lib, hp=fb.Hparams(1, -2, 0, 0)) == 1
+    assert _unit(lib, rows=8192 + 2) == 3
+    assert _unit(lib, ws=None) == 5
+    assert _unit(lib, wsb=64) == 5
+
+
 def test_freshness_rejects_bad_arguments_before_launch():
     lib = fb.load_library()
 
