@@ -264,6 +264,25 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
     st, flags = fb.fopd_workspace_status(ws)
     if st != 0:
         sys.exit("device flags set: %d" % flags)
+    # the same call with no scores supplied: they are formed inside, per chunk of whole samples, so that a step
+    # from hidden states projects once instead of twice (possible when every sample fits into a chunk)
+    inside = None
+    if int(seq_lens.max()) <= rows_chunk:
+        def step_inside():
+            fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"],
+                                         w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None,
+                                         None, 1.0, rows_chunk, loss, weights, logp, lse, dh, d, dw, d, 0, ws,
+                                         seq_lens_host=seq_lens, freshness=fresh)
+        step_inside()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(steps):
+            step_inside()
+        torch.cuda.synchronize()
+        inside = (time.perf_counter() - t1) / steps * 1e3
+        st, flags = fb.fopd_workspace_status(ws)
+        if st != 0:
+            sys.exit("device flags set: %d" % flags)
     n_chunks = (T + rows_chunk - 1) // rows_chunk
     ldz = (V + 63) // 64 * 64
     rp = sum(((min(rows_chunk, T - a) + 63) // 64) * 64 for a in range(0, T, rows_chunk))
@@ -293,7 +312,11 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
                      "frac": all_flops / (tot_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "flops_per_launch": all_flops / (3 * n_chunks), "avg_ms": tot_ms / (3 * n_chunks)},
         "kernels": kern,
-        "outside_the_contractions_ms": elapsed / steps * 1e3 - tot_ms}
+        "outside_the_contractions_ms": elapsed / steps * 1e3 - tot_ms,
+        "scores_formed_inside": None if inside is None else {
+            "call": "fopd_lm_head_loss_fwd_bwd with freshness_in = NULL (chunks of whole samples; scoring, loss and both "
+                    "gradients with one projection per step)",
+            "ms_per_call": inside, "tokens/s": int(((mask != 0) & (mask != 2)).sum()) / (inside * 1e-3)}}
 
 
 def main():
@@ -467,7 +490,8 @@ def main():
         out["projection_loss"] = {"call": rec["config"]["call"], "d": rec["config"]["d"],
                                   "rows_chunk": rec["config"]["rows_chunk"], "scratch_GB": rec["config"]["scratch_GB"],
                                   "ms_per_call": rec["ms_per_step"], "tokens/s": rec["value"],
-                                  "roofline": rec["roofline"], "kernels": rec["kernels"]}
+                                  "roofline": rec["roofline"], "kernels": rec["kernels"],
+                                  "scores_formed_inside": rec["scores_formed_inside"]}
     print(json.dumps(out))
 
 

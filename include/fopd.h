@@ -434,14 +434,23 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  * fp32 accumulation; the result does not depend on rows_chunk except through the order of the fp32 sums over
  * rows in dweight.
  *
- * The freshness scores must be supplied (Algorithm 1 scores the buffer before its minibatch loop; with no logits
- * kept, fopd_lm_head_token_logprobs followed by fopd_freshness_score gives them from the same inputs):
- *   freshness_in [B] f32; n_train_in / n_roll_in [B] int32 from fopd_freshness_score, or NULL to count from `mask`.
+ * Scores, two ways:
+ *   freshness_in != NULL  [B] f32 scores formed earlier (Algorithm 1 scores the buffer before its minibatch loop;
+ *                         with no logits kept, fopd_lm_head_token_logprobs followed by fopd_freshness_score gives
+ *                         them from the same inputs); n_train_in / n_roll_in [B] int32 from fopd_freshness_score,
+ *                         or NULL to count from `mask`.  Chunks are rows_chunk rows each and may cut samples.
+ *   freshness_in == NULL  the scores are formed inside the call from the chunk's own log-probs, as
+ *                         fopd_loss_fwd_bwd does when it is given none: the projection is then computed once per
+ *                         step, not twice.  Chunks gather whole samples (as many as fit into rows_chunk rows), so
+ *                         the host must know the lengths: seq_lens_host [B] int32 (HOST memory, the same values
+ *                         as seq_lens), every sample at most rows_chunk rows long (else FOPD_ESHAPE), n_train_in
+ *                         and n_roll_in NULL.  D^sup is 0 in this mode (no stale teacher log-probs are taken).
  *
  *   hidden [T, ldh] bf16, weight [V, ldw] bf16, d a multiple of 64; token_ids, mask, behav_logp, teacher_logp,
  *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
  *   rows_chunk   rows per chunk, a multiple of 64 (8192 keeps the scratch at 8.7 GB at V = 151,936, d = 4096)
- *   loss [1], weights [B] (may be NULL), logp [T], lse [T]: f32 outputs
+ *   loss [1], freshness [B] (may be NULL; a copy of freshness_in when that is given), weights [B] (may be NULL),
+ *   logp [T], lse [T]: f32 outputs
  *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0
  *   workspace    fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) bytes, 256-byte aligned, initialised
  *                once with fopd_workspace_init; the same sticky flags as the other entry points
@@ -452,8 +461,9 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
                                       int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
                                       const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
                                       const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
-                                      const int32_t* n_train_in, const int32_t* n_roll_in, float grad_scale,
-                                      int64_t rows_chunk, float* loss, float* weights, float* logp, float* lse,
+                                      const int32_t* n_train_in, const int32_t* n_roll_in,
+                                      const int32_t* seq_lens_host, float grad_scale, int64_t rows_chunk,
+                                      float* loss, float* freshness, float* weights, float* logp, float* lse,
                                       float* dhidden, int64_t lddh, float* dweight, int64_t lddw,
                                       int accumulate_dweight, void* workspace, size_t workspace_bytes, void* stream);
 

@@ -87,8 +87,8 @@ def load_library():
     lib.fopd_lm_head_loss_workspace_bytes.argtypes = [i64, i64, i64, i32, i64]
     lib.fopd_lm_head_loss_fwd_bwd.restype = ctypes.c_int
     lib.fopd_lm_head_loss_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32, Hparams,
-                                              vp, vp, vp, f32, i64, vp, vp, vp, vp, vp, i64, vp, i64, ctypes.c_int,
-                                              vp, sz, vp]
+                                              vp, vp, vp, vp, f32, i64, vp, vp, vp, vp, vp, vp, i64, vp, i64,
+                                              ctypes.c_int, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -221,18 +221,33 @@ def fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk):
 
 def fopd_lm_head_loss_fwd_bwd(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, teacher_logp, seq_lens,
                               lag, B, hp, freshness_in, n_train_in, n_roll_in, grad_scale, rows_chunk, loss, weights,
-                              logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, workspace, stream=None):
+                              logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, workspace, stream=None,
+                              seq_lens_host=None, freshness=None):
+    """seq_lens_host: the sample lengths in HOST memory (a CPU int32 tensor, a numpy array or a list), needed when
+    freshness_in is None (the scores are then formed inside the call); freshness: [B] f32 output or None."""
+    import numpy as np
     import torch
     f32 = torch.float32
     p, n = _ws(workspace)
+    host = None
+    if seq_lens_host is not None:
+        if isinstance(seq_lens_host, torch.Tensor):
+            if seq_lens_host.is_cuda:
+                raise TypeError("seq_lens_host must be in host memory")
+            seq_lens_host = seq_lens_host.numpy()
+        host = np.ascontiguousarray(np.asarray(seq_lens_host), dtype=np.int32)
+        if host.shape != (int(B),):
+            raise ValueError("seq_lens_host must hold B lengths")
     st = load_library().fopd_lm_head_loss_fwd_bwd(
         _ptr(hidden, torch.bfloat16, "hidden"), int(ldh), _ptr(weight, torch.bfloat16, "weight"), int(ldw),
         int(T), int(V), int(d), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
         _ptr(behav_logp, f32, "behav_logp"), _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(seq_lens, torch.int32, "seq_lens"), _ptr(lag, torch.int32, "lag"), int(B), _hp(hp),
         _ptr(freshness_in, f32, "freshness_in"), _ptr(n_train_in, torch.int32, "n_train_in"),
-        _ptr(n_roll_in, torch.int32, "n_roll_in"), float(grad_scale), int(rows_chunk),
-        _ptr(loss, f32, "loss"), _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"),
+        _ptr(n_roll_in, torch.int32, "n_roll_in"),
+        None if host is None else ctypes.c_void_p(host.ctypes.data), float(grad_scale), int(rows_chunk),
+        _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"),
+        _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"),
         _ptr(dhidden, f32, "dhidden"), int(lddh), _ptr(dweight, f32, "dweight"), int(lddw),
         int(bool(accumulate_dweight)), p, n, _stream(stream))
     _check(st, "fopd_lm_head_loss_fwd_bwd")

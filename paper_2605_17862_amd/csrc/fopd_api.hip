@@ -83,8 +83,8 @@ void* g_scratch_ptr[64] = {};
 // the chunk's fp32 logits, its bf16 gradient rows and the transposed projection matrix.  ldz = V rounded up to 64
 // (the k-extent of the dL/dhidden contraction).
 struct LmLossWorkspace {
-  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0, wt = 0,
-         total = 0;
+  size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, fresh64 = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0,
+         wt = 0, total = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
   LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
@@ -100,9 +100,11 @@ struct LmLossWorkspace {
     cu = Workspace::take(off, (b + 1) * sizeof(int64_t));
     n_train = Workspace::take(off, b * sizeof(int32_t));
     n_roll = Workspace::take(off, b * sizeof(int32_t));
+    fresh64 = Workspace::take(off, b * sizeof(double));
     coef = Workspace::take(off, r * sizeof(float));
     partials = Workspace::take(off, (r / kStreamThreads + 2) * sizeof(double));
-    chunk_loss = Workspace::take(off, static_cast<size_t>(n_chunks + 1) * sizeof(float));
+    // chunks that follow sample boundaries (scores formed inside the call) are at most n_chunks + B
+    chunk_loss = Workspace::take(off, (static_cast<size_t>(n_chunks) + b + 1) * sizeof(float));
     z = Workspace::take(off, r * static_cast<size_t>(ldz) * sizeof(float));
     g = Workspace::take(off, r * static_cast<size_t>(ldz) * 2);
     wt = Workspace::take(off, dd * static_cast<size_t>(ldz) * 2);
@@ -972,23 +974,57 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
                                       int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
                                       const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
                                       const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
-                                      const int32_t* n_train_in, const int32_t* n_roll_in, float grad_scale,
-                                      int64_t rows_chunk, float* loss, float* weights, float* logp, float* lse,
-                                      float* dhidden, int64_t lddh, float* dweight, int64_t lddw,
-                                      int accumulate_dweight, void* workspace, size_t workspace_bytes, void* stream) {
+                                      const int32_t* n_train_in, const int32_t* n_roll_in,
+                                      const int32_t* seq_lens_host, float grad_scale, int64_t rows_chunk, float* loss,
+                                      float* freshness, float* weights, float* logp, float* lse, float* dhidden,
+                                      int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
   if (T < 0 || T > 2147483647LL || V <= 0 || V > 2147483647LL - 64 || d <= 0 || d % 64 != 0 || ldh < d || ldw < d ||
       lddh < d || lddw < d || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
     return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
-      teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || freshness_in == nullptr ||
-      loss == nullptr || logp == nullptr || lse == nullptr || dhidden == nullptr || dweight == nullptr)
+      teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr || logp == nullptr ||
+      lse == nullptr || dhidden == nullptr || dweight == nullptr)
     return FOPD_EINVAL;
+  const bool scored = (freshness_in != nullptr);
+  // without scores they are formed inside the call, per chunk: the chunks then follow sample boundaries, which
+  // the host must know
+  if (!scored && (seq_lens_host == nullptr || n_train_in != nullptr || n_roll_in != nullptr)) return FOPD_EINVAL;
   if (n_roll_in != nullptr && n_train_in == nullptr) return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
   if (misaligned(hidden, 16) || misaligned(weight, 16) || (ldh * 2) % 16 != 0 || (ldw * 2) % 16 != 0 ||
       misaligned(dhidden, 16) || misaligned(dweight, 16))
     return FOPD_EALIGN;
   const LmLossWorkspace lay(T, V, d, B, rows_chunk);
   if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
+
+  // The chunks: [row begin, rows, first sample, one past the last sample].  With scores supplied they are
+  // rows_chunk rows each and may cut samples; without, whole samples are gathered up to rows_chunk rows.
+  struct Chunk {
+    int64_t a, R;
+    int32_t i0, i1;
+  };
+  std::vector<Chunk> chunks;
+  if (scored) {
+    for (int64_t a = 0; a < T; a += rows_chunk) chunks.push_back({a, (T - a < rows_chunk) ? T - a : rows_chunk, 0, 0});
+  } else {
+    int64_t a = 0, rows = 0;
+    int32_t i0 = 0;
+    for (int32_t i = 0; i < B; ++i) {
+      const int64_t len = seq_lens_host[i];
+      if (len < 0 || len > rows_chunk) return FOPD_ESHAPE;      // a sample must fit into one chunk
+      if (rows + len > rows_chunk) {
+        chunks.push_back({a, rows, i0, i});
+        a += rows;
+        rows = 0;
+        i0 = i;
+      }
+      rows += len;
+    }
+    if (a + rows != T) return FOPD_ESHAPE;                       // the lengths must add up to T
+    if (rows > 0) chunks.push_back({a, rows, i0, B});
+    else if (!chunks.empty()) chunks.back().i1 = B;              // trailing empty samples
+  }
 
   hipStream_t s = static_cast<hipStream_t>(stream);
   fopd_status st;
@@ -996,6 +1032,7 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   int64_t* cu = at<int64_t>(workspace, lay.cu);
   int32_t* nws = at<int32_t>(workspace, lay.n_train);
   int32_t* nrws = at<int32_t>(workspace, lay.n_roll);
+  double* f64 = at<double>(workspace, lay.fresh64);
   float* coef = at<float>(workspace, lay.coef);
   double* partials = at<double>(workspace, lay.partials);
   float* chunk_loss = at<float>(workspace, lay.chunk_loss);
@@ -1005,6 +1042,7 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   const __bf16* Hm = static_cast<const __bf16*>(hidden);
   const __bf16* Wm = static_cast<const __bf16*>(weight);
   const int64_t ldz = lay.ldz;
+  const double* f64_use = scored ? nullptr : f64;
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
@@ -1016,12 +1054,29 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     n_use = nws;
     nr_use = nrws;
   }
+  if (T == 0) {      // an empty batch: loss 0, the weights of the scores, a zero projection gradient
+    if (!scored) {
+      fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp, behav_logp, nullptr, nullptr, teacher_logp, nullptr, mask, cu,
+                                                   lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                                   nullptr, nullptr, f64, nws, nrws);
+      if ((st = launched()) != FOPD_OK) return st;
+    }
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
+                                              weights, freshness);
+    if ((st = launched()) != FOPD_OK) return st;
+    if (accumulate_dweight == 0) {
+      fopd_fill_zero_f32<<<static_cast<unsigned>(V), 256, 0, s>>>(dweight, lddw, static_cast<int>(d));
+      return launched();
+    }
+    return FOPD_OK;
+  }
   // the projection matrix with the vocabulary contiguous (zero beyond V), once per call
   if ((st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
 
   int64_t ci = 0;
-  for (int64_t a = 0; a < T; a += rows_chunk, ++ci) {
-    const int64_t R = (T - a < rows_chunk) ? T - a : rows_chunk;
+  for (const Chunk& c : chunks) {
+    const int64_t a = c.a, R = c.R;
+    if (R == 0) continue;
     const int64_t Rp = (R + 63) / 64 * 64;
     const __bf16* Hc = Hm + a * ldh;
     // logits of the chunk, fp32, never rounded to the storage type of stored logits
@@ -1029,13 +1084,21 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     if ((st = launch_k1(Z, FOPD_F32, R, V, ldz, token_ids + a, mask == nullptr ? nullptr : mask + a, logp + a, lse + a,
                         nullptr, nullptr, flags, s)) != FOPD_OK)
       return st;
+    if (!scored) {
+      // the chunk holds whole samples: their scores follow from the log-probs just made
+      fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
+          logp, behav_logp, nullptr, nullptr, teacher_logp, nullptr, mask, cu + c.i0, lag + c.i0, T, hp, nullptr, nullptr,
+          nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, f64 + c.i0, nws + c.i0, nrws + c.i0);
+      if ((st = launched()) != FOPD_OK) return st;
+    }
     const int64_t nblk = (R + kStreamThreads - 1) / kStreamThreads;
     fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp + a, behav_logp + a, teacher_logp + a, mask == nullptr ? nullptr : mask + a, cu, n_use, nr_use, lag, nullptr,
+        logp + a, behav_logp + a, teacher_logp + a, mask == nullptr ? nullptr : mask + a, cu, n_use, nr_use, lag, f64_use,
         freshness_in, R, B, a, hp, grad_scale, coef, partials, flags);
     if ((st = launched()) != FOPD_OK) return st;
-    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi,
-                                              chunk_loss + ci, weights, nullptr);
+    // (weights and scores of samples whose chunk is still to come are overwritten by the later calls)
+    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi,
+                                              chunk_loss + ci, weights, freshness);
     if ((st = launched()) != FOPD_OK) return st;
     {
       ScopedTimer timer(1, s);
@@ -1054,16 +1117,7 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     }
     const bool acc = (ci > 0) || (accumulate_dweight != 0);
     if ((st = launch_gemm_tn(acc, Hc, ldh, d, R, G, ldz, V, Rp, dweight, lddw, 6, s)) != FOPD_OK) return st;
-  }
-  if (T == 0) {      // an empty batch: loss 0, the weights of the scores, a zero projection gradient
-    fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, nullptr, freshness_in, B, hp.xi, loss,
-                                              weights, nullptr);
-    if ((st = launched()) != FOPD_OK) return st;
-    if (accumulate_dweight == 0) {
-      fopd_fill_zero_f32<<<static_cast<unsigned>(V), 256, 0, s>>>(dweight, lddw, static_cast<int>(d));
-      return launched();
-    }
-    return FOPD_OK;
+    ++ci;
   }
   fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);
   return launched();

@@ -219,6 +219,38 @@ def test_projection_entry_point_rejects_bad_arguments_before_launch():
     assert _lmh(lib, T=0) == 0                   # nothing to do, nothing launched
 
 
+def _lml(lib, **kw):
+    a = dict(hidden=4096, ldh=64, weight=4096, ldw=64, T=128, V=100, d=64, ids=4096, lb=4096, lq=4096, seq=4096, lag=4096,
+             B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), fin=4096, nin=None, nroll=None, host=None, chunk=64, loss=4096,
+             f=None, w=None, lp=4096, lse=4096, dh=8192, dw=8192, ws=4096, wsb=1 << 24)
+    a.update(kw)
+    host = a["host"]
+    keep = (ctypes.c_int32 * len(host))(*host) if host is not None else None
+    return lib.fopd_lm_head_loss_fwd_bwd(P(a["hidden"]), a["ldh"], P(a["weight"]), a["ldw"], a["T"], a["V"], a["d"],
+                                         P(a["ids"]), None, P(a["lb"]), P(a["lq"]), P(a["seq"]), P(a["lag"]), a["B"],
+                                         a["hp"], P(a["fin"]), P(a["nin"]), P(a["nroll"]),
+                                         None if keep is None else ctypes.cast(keep, ctypes.c_void_p), 1.0, a["chunk"],
+                                         P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]), P(a["lse"]), P(a["dh"]), 64,
+                                         P(a["dw"]), 64, 0, P(a["ws"]), a["wsb"], None)
+
+
+def test_projection_loss_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _lml(lib, hidden=None) == 1
+    assert _lml(lib, dw=None) == 1
+    assert _lml(lib, chunk=32) == 2                               # rows per chunk: a multiple of 64
+    assert _lml(lib, d=96, ldh=96, ldw=96) == 2
+    assert _lml(lib, nroll=4096) == 1                             # roll counts only together with the sup counts
+    assert _lml(lib, hp=fb.Hparams(-1, 1, 0, 0)) == 1
+    assert _lml(lib, wsb=4096) == 5
+    # scores formed inside the call: the host needs the lengths, whole samples per chunk, lengths adding up to T
+    assert _lml(lib, fin=None) == 1
+    assert _lml(lib, fin=None, host=[64, 64], nin=4096) == 1
+    assert _lml(lib, fin=None, host=[100, 28]) == 2               # a sample longer than a chunk
+    assert _lml(lib, fin=None, host=[64, 32]) == 2                # 96 rows, T = 128
+    assert _lml(lib, fin=None, host=[-1, 129]) == 2
+
+
 def test_projection_workspace_bytes():
     a = fb.fopd_lm_head_workspace_bytes(1)
     b = fb.fopd_lm_head_workspace_bytes(256)

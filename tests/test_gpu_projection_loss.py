@@ -161,6 +161,51 @@ def test_projection_loss_accumulates_into_dweight_and_ignores_the_chunk_size():
     assert torch.equal(given["dhidden"], many["dhidden"]) and torch.equal(given["dweight"], many["dweight"])
 
 
+@pytest.mark.parametrize("seq,rows_chunk,lag", [((90, 130, 80), 192, (0, 3, 40)), ((40, 0, 60, 30, 50, 70), 128, (0, 1, 2, 45, 0, 3)),
+                                                ((64, 64), 64, (1, 0)), ((50, 0, 0), 64, (0, 0, 0))])
+def test_projection_loss_forms_the_scores_itself_when_given_none(seq, rows_chunk, lag):
+    """freshness_in = None: chunks gather whole samples and the scores come from the chunk's own log-probs, as in
+    fopd_loss_fwd_bwd without scores.  The scores are checked against the oracle's (1e-5 relative), everything
+    else against the oracle evaluated at the scores the call reports; and the call with those scores supplied
+    gives the same gradients."""
+    T, d, V = sum(seq), 128, 3000
+    _say("scores formed inside the call: samples %s, chunks of at most %d rows" % (list(seq), rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=21, masked_every=6)
+    w = wl.attach_loss_inputs(h, seq, list(lag), seed=21)
+    hp, g, B = (1.0, 1.0, 0.05, 0.3), 1.3, len(seq)
+    ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+    out = dict(loss=torch.full((1,), 7.0, device=DEV), weights=torch.full((B,), 7.0, device=DEV),
+               freshness=torch.full((B,), 7.0, device=DEV), logp=torch.full((T,), 7.0, device=DEV),
+               lse=torch.full((T,), 7.0, device=DEV), dhidden=torch.full((T, d), 7.0, device=DEV),
+               dweight=torch.full((V, d), 7.0, device=DEV))
+    fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                 w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None, None, g,
+                                 rows_chunk, out["loss"], out["weights"], out["logp"], out["lse"], out["dhidden"], d,
+                                 out["dweight"], d, False, ws, seq_lens_host=w["seq_lens_host"], freshness=out["freshness"])
+    torch.cuda.synchronize()
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    f_exact = _scores_from_the_oracle(w, hp).astype(np.float64)
+    f_gpu = np64(out["freshness"])
+    assert_close("freshness", f_gpu, f_exact, rtol=1e-5)
+    gated = [i for i in range(B) if 0.0 < f_exact[i] < 0.05]
+    if any(x >= 40 for x in lag):
+        assert gated and all(float(out["weights"][i]) == 0.0 for i in gated)
+    _compare(w, hp, g, out, f_gpu.astype(np.float32), check_scale=T > 60)
+    again = _run(w, hp, g, 64, f_gpu.astype(np.float32))          # scores supplied, chunks that cut samples
+    assert torch.equal(again["logp"], out["logp"])
+    assert torch.allclose(again["dhidden"], out["dhidden"], rtol=2e-2, atol=1e-6 * float(out["dhidden"].abs().max()))
+    assert torch.allclose(again["dweight"], out["dweight"], rtol=2e-2, atol=1e-5 * float(out["dweight"].abs().max()))
+    # a sample longer than a chunk cannot be scored inside the call
+    if max(seq) > 64:
+        with pytest.raises(fb.FopdError) as e:
+            fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                         w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None,
+                                         None, g, 64, out["loss"], out["weights"], out["logp"], out["lse"],
+                                         out["dhidden"], d, out["dweight"], d, False, ws,
+                                         seq_lens_host=w["seq_lens_host"])
+        assert e.value.status == 2
+
+
 def test_projection_loss_rejects_bad_arguments():
     h = wl.generate_lm_head(64, 64, 100, DEV, seed=1)
     w = wl.attach_loss_inputs(h, (64,), [0], seed=1)
