@@ -181,6 +181,12 @@ __device__ __forceinline__ void rebase(float from, float to, float& s, float& w,
   s *= scale;
 }
 
+// max(x, -1e30) for a value that is never NaN: one v_med3_f32.  (fmaxf costs a second instruction here, the
+// canonicalisation of its operand that IEEE maximum semantics ask for.)
+__device__ __forceinline__ float floor_minus_inf(float x) {
+  return __builtin_amdgcn_fmed3f(x, -1.0e30f, __builtin_inff());
+}
+
 template <int N, bool ENT>
 __device__ __forceinline__ void accumulate(const float* x, LaneState& st) {
   float bm = x[0];
@@ -198,12 +204,12 @@ __device__ __forceinline__ void accumulate(const float* x, LaneState& st) {
     const float t0 = fmaf(x[i], kLog2e, -st.rL);
     const float e0 = fast_exp2(t0);
     a0 += e0;
-    if (ENT) w0 = fmaf(e0, fmaxf(t0, -1.0e30f), w0);       // t = -inf has e = 0: keep 0 * t finite
+    if (ENT) w0 = fmaf(e0, floor_minus_inf(t0), w0);       // t = -inf has e = 0: keep 0 * t finite
     if (i + 1 < N) {
       const float t1 = fmaf(x[i + 1], kLog2e, -st.rL);
       const float e1 = fast_exp2(t1);
       a1 += e1;
-      if (ENT) w1 = fmaf(e1, fmaxf(t1, -1.0e30f), w1);
+      if (ENT) w1 = fmaf(e1, floor_minus_inf(t1), w1);
     }
   }
   st.s += a0 + a1;
@@ -910,23 +916,35 @@ __device__ __forceinline__ void accumulate_kl(const float* x, const float* xs, L
     if (seen != seen_s || (seen && !(fabsf(gap) <= kKlRefGap))) st.far = true;
     st.c = st.far ? 0.f : fast_exp2(gap);
   }
+  // two chains per sum; the first two entries start them (no additions to zero)
   float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f, u0 = 0.f, u1 = 0.f, b0 = 0.f, b1 = 0.f;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
     const float e = fast_exp2(fmaf(x[i], kLog2e, -st.rL));
     const float es = fast_exp2(fmaf(xs[i], kLog2e, -st.rsL));
     // both -inf (an excluded vocabulary entry) must give d = 0, not NaN
-    const float d = fmaxf(x[i], -1.0e30f) - fmaxf(xs[i], -1.0e30f);
-    if (i & 1) {
+    const float d = floor_minus_inf(x[i]) - floor_minus_inf(xs[i]);
+    const float du = fmaf(es, st.c, -e);
+    if (i == 0) {
+      a0 = e;
+      b0 = es;
+      w0 = e * d;
+      u0 = du;
+    } else if (i == 1) {
+      a1 = e;
+      b1 = es;
+      w1 = e * d;
+      u1 = du;
+    } else if (i & 1) {
       a1 += e;
       b1 += es;
       w1 = fmaf(e, d, w1);
-      u1 += fmaf(es, st.c, -e);
+      u1 += du;
     } else {
       a0 += e;
       b0 += es;
       w0 = fmaf(e, d, w0);
-      u0 += fmaf(es, st.c, -e);
+      u0 += du;
     }
   }
   st.s += a0 + a1;
@@ -1186,7 +1204,7 @@ fopd_k6_grad_kl(const void* logits, const void* logits_stale, void* dlogits, int
   const float k0 = a - b * (dlse[t] + roll_kl[t]);     // factor = k0 + c2 d_u
   const float lp = logp[t];
   auto grad_of = [&](float x, float xs) {
-    const float d = fmaxf(x, -1.0e30f) - fmaxf(xs, -1.0e30f);
+    const float d = floor_minus_inf(x) - floor_minus_inf(xs);
     return fast_exp2(fmaf(x, kLog2e, -lseL)) * fmaf(b, d, k0);
   };
   auto grad_y = [&](float x, float xs) {               // c1 (p_y - 1) + c2 p_y (...), accurate as p_y -> 1
