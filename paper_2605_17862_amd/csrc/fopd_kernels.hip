@@ -181,10 +181,13 @@ __device__ __forceinline__ void rebase(float from, float to, float& s, float& w,
   s *= scale;
 }
 
-// max(x, -1e30) for a value that is never NaN: one v_med3_f32.  (fmaxf costs a second instruction here, the
-// canonicalisation of its operand that IEEE maximum semantics ask for.)
+// max(x, -1e30) as one integer instruction: among floats with the sign bit set the bit pattern grows with the
+// magnitude, and every pattern without the sign bit is smaller, so an unsigned minimum with the pattern of -1e30
+// replaces exactly the values below it (-inf included).  fmaxf costs two instructions here (the canonicalisation
+// of its operand that IEEE maximum semantics ask for comes first).
 __device__ __forceinline__ float floor_minus_inf(float x) {
-  return __builtin_amdgcn_fmed3f(x, -1.0e30f, __builtin_inff());
+  const uint32_t kFloorBits = 0xf149f2cau;             // -1e30f
+  return __uint_as_float(min(__float_as_uint(x), kFloorBits));
 }
 
 template <int N, bool ENT>
