@@ -192,27 +192,30 @@ __device__ __forceinline__ float floor_minus_inf(float x) {
 
 template <int N, bool ENT>
 __device__ __forceinline__ void accumulate(const float* x, LaneState& st) {
-  float bm = x[0];
+  // The maximum starts from the running one, so that every step is a three-operand maximum of the chain and two
+  // entries (a two-operand first step costs two extra instructions: hipcc canonicalises both of its operands).
+  float bm = st.r;
 #pragma unroll
-  for (int i = 1; i < N; ++i) bm = fmaxf(bm, x[i]);
+  for (int i = 0; i < N; ++i) bm = fmaxf(bm, x[i]);
   if (bm > st.r) {                    // rare after the first few vectors
     const float nrL = bm * kLog2e;
     rebase(st.rL, nrL, st.s, st.w, ENT);
     st.r = bm;
     st.rL = nrL;
   }
+  // two chains per sum, started by the first two entries (no additions to zero)
   float a0 = 0.f, a1 = 0.f, w0 = 0.f, w1 = 0.f;
 #pragma unroll
   for (int i = 0; i < N; i += 2) {
     const float t0 = fmaf(x[i], kLog2e, -st.rL);
     const float e0 = fast_exp2(t0);
-    a0 += e0;
-    if (ENT) w0 = fmaf(e0, floor_minus_inf(t0), w0);       // t = -inf has e = 0: keep 0 * t finite
+    a0 = (i == 0) ? e0 : a0 + e0;
+    if (ENT) w0 = (i == 0) ? e0 * floor_minus_inf(t0) : fmaf(e0, floor_minus_inf(t0), w0);   // t = -inf has e = 0: keep 0 * t finite
     if (i + 1 < N) {
       const float t1 = fmaf(x[i + 1], kLog2e, -st.rL);
       const float e1 = fast_exp2(t1);
-      a1 += e1;
-      if (ENT) w1 = fmaf(e1, floor_minus_inf(t1), w1);
+      a1 = (i == 0) ? e1 : a1 + e1;
+      if (ENT) w1 = (i == 0) ? e1 * floor_minus_inf(t1) : fmaf(e1, floor_minus_inf(t1), w1);
     }
   }
   st.s += a0 + a1;
@@ -827,22 +830,31 @@ fopd_k14_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, c
       gy = sh_out[2];
     }
     const bool grad = (c != 0.f);              // the same in every lane
+    const float shiftL = log2f(fabsf(c)) - lseL;
+    const uint32_t sign_bits = (c < 0.f) ? ((DT == FOPD_BF16) ? 0x80008000u : 0x80000000u) : 0u;
+    const float gy_abs = (c < 0.f) ? -gy : gy;           // the sign is put back with all the others
     if (have_row && !grad) row_zero<DT, NT>(orow, V);
     const auto rs_out = descriptor(orow, grad ? row_bytes : 0u);     // extent 0: every store dropped
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
       const uint32_t o = lane_off(u);
       if (grad) {
+        // |c| 2^t = 2^(t + log2 |c|): the factor goes into the exponent and its sign onto the packed result
         float x[E];
         unpack<DT>(q[u], x);
 #pragma unroll
-        for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+        for (int e = 0; e < E; ++e) x[e] = fast_exp2(fmaf(x[e], kLog2e, shiftL));
         if (static_cast<int>(o >> 4) == jy) {
 #pragma unroll
           for (int e = 0; e < E; ++e)
-            if (e == ey) x[e] = gy;
+            if (e == ey) x[e] = gy_abs;
         }
-        __builtin_amdgcn_raw_buffer_store_b128(pack<DT>(x), rs_out, o, 0, kNonTemporal);
+        u32x4 packed = pack<DT>(x);
+        packed.x ^= sign_bits;
+        packed.y ^= sign_bits;
+        packed.z ^= sign_bits;
+        packed.w ^= sign_bits;
+        __builtin_amdgcn_raw_buffer_store_b128(packed, rs_out, o, 0, kNonTemporal);
       }
       q[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_next, o, 0, kNonTemporal);   // the register is free again
       __builtin_amdgcn_sched_barrier(0);       // one vector at a time
