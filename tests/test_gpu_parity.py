@@ -667,6 +667,55 @@ def test_replay_from_a_hip_graph():
     _sync_ok(g2)
 
 
+def test_replay_of_the_row_in_registers_kernel_from_a_hip_graph():
+    """The same for the kernel that holds a row in registers (rows of 2049 16-byte vectors), in both of its uses:
+    the scores-supplied call and the single-read call."""
+    _say("HIP graph capture and replay: scores-supplied and single-read calls, rows held in registers")
+    w = wl.generate("tooluse", DEV, seed=23, B=5, turns=2, obs_lo=2, obs_hi=5, resp_lo=3, resp_hi=9, V=16392, ld=16392,
+                    dtype="bf16", boost=4, lag_lo=0, lag_hi=30, row_block=32)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+
+    def unit(lp):
+        fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"],
+                                  w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, HP, 1.0, lp.loss,
+                                  lp.freshness, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+
+    def scored(lp, f_in):
+        fb.fopd_loss_fwd_bwd(w["logits"], lp.dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"], w["teacher_logp"],
+                             w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, HP, f_in, None, None, 0, None, None,
+                             1.0, lp.loss, None, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+
+    e1, e2 = _pass_for(w), _pass_for(w)
+    unit(e1)                                           # eager; also the first call outside any capture
+    torch.cuda.synchronize()
+    f_in = e1.freshness.clone()
+    scored(e2, f_in)
+    torch.cuda.synchronize()
+    g1, g2 = _pass_for(w), _pass_for(w)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        unit(g1)
+        scored(g2, f_in)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        g1.dlogits.fill_(float(rep))
+        g2.dlogits.fill_(float(rep))
+        g1.loss.zero_()
+        g1.weights.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g1.dlogits, e1.dlogits) and torch.equal(g1.loss, e1.loss) and torch.equal(g1.weights, e1.weights)
+        assert torch.equal(g1.freshness, e1.freshness) and torch.equal(g1.logp, e1.logp)
+        assert torch.equal(g2.dlogits, e2.dlogits) and torch.equal(g2.loss, e2.loss)
+    _sync_ok(g1)
+    _sync_ok(g2)
+
+
 @pytest.mark.parametrize("name", ["reasoning", "coding", "tiny"])
 def test_full_teacher_distribution_variant(name):
     """Token loss = KL(student || teacher) from the teacher's full logits (here: the generator's second
