@@ -328,7 +328,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-projection", action="store_true",
                     help="skip the projection-fused log-prob measurement reported beside the headline")
-    ap.add_argument("--rows-chunk", type=int, default=8192,
+    ap.add_argument("--rows-chunk", type=int, default=16384,
                     help="rows per chunk of the loss pass through the projection (--variant lm_head_loss)")
     ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head", "lm_head_loss"),
                     default="default",
