@@ -1093,6 +1093,34 @@ def test_tooluse_full_size_sampled_parity():
     assert_close("agg cover", float(st.agg[1]), float(np.mean(np64(st.cover))), rtol=1e-6)
 
 
+def test_tooluse_full_size_single_read_in_place():
+    """The single-read call at full size on rows with masked spans, written in place: rows at unit weight for sampled
+    rows of whole samples, masked rows zero, scores and weights against the oracle."""
+    _say("tooluse at full size, single-read call in place: generating ...")
+    w = wl.generate("tooluse", DEV, seed=0)
+    T, V, B = w["T"], w["V"], w["B"]
+    chosen, rows = _pick_samples(w["seq_lens_host"], 2, 8192)
+    cu = orc.segment_offsets(w["seq_lens_host"])
+    saved = {i: w["logits"][int(cu[i]):int(cu[i + 1])].clone() for i in chosen}
+    lp = _pass_for(w, alloc_dlogits=False)
+    fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                              w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, HP, 1.0, lp.loss,
+                              lp.freshness, lp.weights, lp.logp, w["logits"], lp.workspace)
+    _sync_ok(lp)
+    _say("oracle on samples %s (%d rows)" % (chosen, rows))
+    for i in chosen:
+        o = _oracle_sample(w, i, cu, HP, B, logits=saved[i])
+        assert_close("logp sample %d" % i, np64(lp.logp[o["a"]:o["b"]]), o["logp"], atol=1e-4)
+        f = o["f"][0]
+        assert abs(float(lp.freshness[i]) - f) <= 1e-5 * f and abs(float(lp.weights[i]) - o["w"][0]) <= 1e-5 * f
+        live = np.flatnonzero(o["mask"])
+        dead = np.flatnonzero(o["mask"] == 0)
+        picks = np.concatenate([live[np.linspace(0, len(live) - 1, 4).astype(int)], dead[:2]])
+        _check_sample_grad_rows(o, i, w, lambda rows_: w["logits"][torch.from_numpy(rows_).to(DEV)], picks,
+                                logits=saved[i], unit=True)
+    _row_properties(w, cu, lambda t: w["logits"][t], torch.ones_like(lp.weights))
+
+
 def test_coding_full_size_chunked_flow():
     _say("coding at full size (B=8 x 32768, V=151936), processed in chunks of 16384 rows: generating ...")
     w = wl.generate("coding", DEV, seed=0)
