@@ -667,6 +667,66 @@ def test_replay_from_a_hip_graph():
     _sync_ok(g2)
 
 
+@pytest.mark.parametrize("dtype,V,seed", [("bf16", 20008, 3), ("f32", 9004, 4), ("bf16", 155648, 5)])
+def test_row_in_registers_kernel_walks_many_rows_per_workgroup(dtype, V, seed):
+    """More rows than compute units, so that every workgroup of the row-in-registers kernel walks several rows
+    (masked, gated, live and invalid ones in any order) and requests the next row while storing the current one.
+    Compared with the kernel that re-reads the row (256 lanes, the bits of the separate kernels): another summation
+    order, so entries may differ by one unit of the storage type; masked and gated rows are zero in both."""
+    _say("row-in-registers kernel over many rows per workgroup: %s V=%d" % (dtype, V))
+    w = wl.generate("tooluse", DEV, seed=seed, B=40, turns=3, obs_lo=0, obs_hi=9, resp_lo=1, resp_hi=24, V=V, ld=V,
+                    dtype=dtype, boost=4, lag_lo=0, lag_hi=40, row_block=64, aligned_split=(0.2, 0.2))
+    T, B = w["T"], w["B"]
+    assert T > 600
+    hp = (1.0, 1.0, 0.05, 0.3)
+    st = _pass_for(w)
+    st.token_logprobs(w)
+    st.freshness_score(w, hp)
+    _sync_ok(st)
+    f_gpu, n_gpu, nr_gpu = st.freshness.clone(), st.n_train.clone(), st.n_roll.clone()
+    assert bool((f_gpu < 0.05).any()) and bool((f_gpu > 0.05).any())
+
+    def call(lp):
+        lp.dlogits.fill_(3.0)
+        fb.fopd_loss_fwd_bwd(w["logits"], lp.dt, T, V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                             w["teacher_logp"], None, w["seq_lens"], w["lag"], B, hp, f_gpu, n_gpu, nr_gpu, 0, None, None,
+                             0.5, lp.loss, None, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+        _sync_ok(lp)
+
+    regs, plain = _pass_for(w), _pass_for(w)
+    call(regs)
+    try:
+        fb.fopd_set_option("k14_regs", 0)
+        call(plain)
+    finally:
+        fb.fopd_set_option("k14_regs", 1)
+    assert torch.equal(regs.weights, plain.weights)
+    assert torch.allclose(regs.logp, plain.logp, rtol=2e-6, atol=2e-6)
+    assert abs(float(regs.loss) - float(plain.loss)) <= 2e-6 * abs(float(plain.loss)) + 1e-12
+    x, y_ = np64(regs.dlogits), np64(plain.dlogits)
+    if dtype == "bf16":
+        # a coefficient that nearly cancels moves by more than one unit when lp moves in its last place: rows
+        # are compared relative to their own largest entry as well
+        # (a fresh sample's roll-only row has delta = lp - lb = 0 up to that last place: its whole row is ~1e-7 of
+        # the others, or exactly zero, hence the bound relative to the largest entry of the matrix)
+        row_scale = np.max(np.abs(y_), axis=1, keepdims=True)
+        ok = ((np.abs(x - y_) <= orc.bf16_ulp(y_)) | (np.abs(x - y_) <= 2e-2 * row_scale)
+              | (np.abs(x - y_) <= 1e-6 * np.max(np.abs(y_))))
+        assert bool(np.all(ok)) and float(np.mean(x == y_)) > 0.97
+    else:
+        # fp32 storage shows the last place of lse in every entry, and a nearly cancelling coefficient moves more
+        row_scale = np.max(np.abs(y_), axis=1, keepdims=True)
+        ok = ((np.abs(x - y_) <= 1e-5 * np.abs(y_)) | (np.abs(x - y_) <= 2e-2 * row_scale)
+              | (np.abs(x - y_) <= 1e-6 * np.max(np.abs(y_))))
+        assert bool(np.all(ok))
+        close = np.abs(x - y_) <= 1e-5 * np.abs(y_) + 1e-30
+        assert float(np.mean(close)) > 0.97
+    # rows of masked tokens and of gated or invalid samples: exactly zero
+    wrow = np.repeat(np64(regs.weights), np64(w["seq_lens"]).astype(np.int64))
+    dead = (np64(w["mask"]) == 0) | (wrow == 0.0)
+    assert dead.any() and not np.any(x[dead])
+
+
 def test_replay_of_the_row_in_registers_kernel_from_a_hip_graph():
     """The same for the kernel that holds a row in registers (rows of 2049 16-byte vectors), in both of its uses:
     the scores-supplied call and the single-read call."""
