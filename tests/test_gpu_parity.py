@@ -556,6 +556,33 @@ def test_single_read_call_returns_rows_at_unit_weight(dtype, V, ld, workload):
     assert torch.allclose(two.weights, lp.weights, rtol=2e-6, atol=1e-7)
 
 
+def test_single_read_call_without_a_mask_counts_every_row():
+    """A NULL mask means that every row is in both aligned sets, and a NULL stale teacher log-prob means
+    D^sup = 0: checked against the oracle given a mask of ones and the fresh teacher log-probs as the stale ones."""
+    _say("single-read call, no mask and no stale teacher log-probs")
+    w = wl.generate("tooluse", DEV, seed=23, B=5, turns=2, obs_lo=0, obs_hi=0, resp_lo=3, resp_hi=9, V=16392,
+                    ld=16392, dtype="bf16", boost=4, lag_lo=0, lag_hi=30, row_block=32)
+    T, B, V, ld = w["T"], w["B"], w["V"], w["ld"]
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 1.0
+    full = dict(w, mask=torch.ones(T, dtype=torch.uint8, device=DEV), teacher_logp_stale=w["teacher_logp"])
+    ref = oracle_full(full, hp, gs, want_dlogits=True, unit_rows=True)
+    assert float(np.max(np.abs(ref["D_sup"]))) == 0.0
+    lp = _pass_for(w)
+    fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, ld, w["token_ids"], None, w["behav_logp"], w["teacher_logp"],
+                              None, w["seq_lens"], w["lag"], B, hp, gs, lp.loss, lp.freshness, lp.weights, lp.logp,
+                              lp.dlogits, lp.workspace)
+    _sync_ok(lp)
+    assert_close("logp", np64(lp.logp), ref["logp"], rtol=1e-5, atol=2e-6)
+    assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(lp.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12, (float(lp.loss), ref["loss"])
+    valid = np.minimum(ref["n_train"], ref["n_roll"]) > 0
+    unit_ref = dict(ref, weights=valid.astype(np.float64), freshness=np.zeros(B))
+    eps_c = coef_uncertainty(unit_ref, hp, gs, B, np.ones(T))
+    y = ref["gather_idx"] - np.arange(T) * ld
+    check_grad_rows(np64(lp.dlogits)[:, :V], np64(w["logits"])[:, :V], y, ref["lse"], ref["coef_unit"], eps_c, "bf16")
+
+
 # ---------------------------------------------------------------------------------------
 # full-vocabulary rollout drift (the diagnostic as printed in the paper)
 # ---------------------------------------------------------------------------------------
