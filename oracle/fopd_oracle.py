@@ -32,6 +32,11 @@ Readings of the paper that this oracle fixes (the paper leaves them open):
   sample is gated or invalid (Algorithm 1, anchored minibatch loss).
 * Freshness weights are constants in the gradient (Algorithm 1 scores the buffer before the
   minibatch loop).
+* A teacher stored as k tokens per row with their log-probabilities (the paper names distribution-level
+  teacher supervision but no storage format) gives the token loss as the reverse KL between the two
+  distributions coarsened to the k listed tokens plus one event for every other token; the teacher's
+  probability of that last event is what its listed tokens leave of 1, not below a floor the caller passes.
+  Listing every token gives the full KL; coarsening can only lower it.
 
 Hyper-parameter values are not given by the paper: parity on them is unpinned by the paper
 and rests on both sides receiving the same numbers.
@@ -474,6 +479,123 @@ def fopd_loss_fwd_bwd_full_teacher(logits, teacher_logits, token_ids, mask, beha
         for t in range(T):
             g[t] = dlogits_row_full_kl(logits[t], teacher_logits[t], int(token_ids[t]), lse[t], lse_q[t], tok_kl[t],
                                        c1[t], c2[t])
+        res["dlogits_exact"] = g
+        res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
+    return res
+
+
+# ----------------------------------------------------------------------------------------
+# teacher given on k tokens per row (Eq. "sample-aggregated-loss" with a distribution-level l whose teacher
+# side is stored as the k most likely tokens and their log-probabilities)
+# ----------------------------------------------------------------------------------------
+
+def topk_buckets(V, ids):
+    """The slots of a row that name a token (0 <= id < V); any other id marks an unused slot.  The named
+    tokens must be distinct."""
+    used = [j for j in range(len(ids)) if 0 <= int(ids[j]) < V]
+    named = [int(ids[j]) for j in used]
+    if len(set(named)) != len(named):
+        raise ValueError("the tokens of a row's teacher list must be distinct")
+    return used, named
+
+
+def topk_token_loss_row(z, ids, logq, rest_floor):
+    """Reverse KL between the student's distribution softmax(z) and the teacher's, both coarsened to the
+    events {token ids[0]}, ..., {token ids[k-1]}, {any other token}: the teacher's probabilities of the k
+    tokens are exp(logq) and the last event has what is left of 1, but at least rest_floor.
+
+      l = sum_j P_j (log P_j - logq_j) + P_rest (log P_rest - log Q_rest)
+
+    Returns (l, G) with G[u] = log P_b - log Q_b for the event b that holds token u:
+    d l / d z_u = p_u (G[u] - l).  An event of student probability 0 adds 0."""
+    z = np.asarray(z, dtype=np.float64)
+    V = z.shape[0]
+    used, named = topk_buckets(V, ids)
+    logp = z - row_logsumexp(z)
+    p = np.exp(logp)
+    G = np.zeros(V)
+    ell = 0.0
+    in_list = np.zeros(V, dtype=bool)
+    q_listed = 0.0
+    for j, u in zip(used, named):
+        in_list[u] = True
+        q_listed += math.exp(float(logq[j]))
+        G[u] = logp[u] - float(logq[j])
+        if p[u] > 0.0:
+            ell += p[u] * G[u]
+    q_rest = max(1.0 - q_listed, float(rest_floor))
+    p_rest = float(np.sum(p[~in_list]))
+    if p_rest > 0.0:
+        g_rest = math.log(p_rest) - math.log(q_rest)
+        ell += p_rest * g_rest
+        G[~in_list] = g_rest
+    return ell, G
+
+
+def dlogits_row_topk(z, y, ids, logq, rest_floor, c1_t, c2_t):
+    """One gradient row of the pass with the teacher given on k tokens:
+    c1 (p - onehot) + c2 p (G - l), G and l as in topk_token_loss_row."""
+    z = np.asarray(z, dtype=np.float64)
+    if c1_t == 0.0 and c2_t == 0.0:
+        return np.zeros_like(z)
+    ell, G = topk_token_loss_row(z, ids, logq, rest_floor)
+    p = np.exp(z - row_logsumexp(z))
+    g = p * (c1_t + c2_t * (np.where(p > 0.0, G, 0.0) - ell))
+    g[y] -= c1_t
+    return g
+
+
+def fopd_loss_fwd_bwd_topk_teacher(logits, token_ids, mask, behav_logp, topk_ids, topk_logp, rest_floor,
+                                   teacher_logp, teacher_logp_stale, seq_lens, lag, alpha, beta, xi, lam,
+                                   grad_scale=1.0, out_dtype="f32", want_dlogits=True):
+    """The whole pass with a distribution-level token loss against a teacher that is stored as k tokens per row
+    (topk_ids [T, k], topk_logp [T, k]): l_t = topk_token_loss_row.  The rollout drift keeps the sampled-token
+    estimator; the supervision drift uses the sampled token's teacher log-probabilities when both arrays are
+    given (teacher_logp, teacher_logp_stale) and is 0 otherwise.  Steps in Algorithm 1's order."""
+    logits = np.asarray(logits)
+    T, V = logits.shape
+    if mask is None:
+        mask = np.ones(T, dtype=np.uint8)
+    cu = segment_offsets(seq_lens)
+    if int(cu[-1]) != T:
+        raise ValueError("sequence lengths do not add up to T")
+    lse, lp = token_logprobs(logits, token_ids, mask)
+    tok = np.zeros(T)
+    for t in range(T):
+        if in_sup_set(mask[t]):
+            tok[t], _ = topk_token_loss_row(logits[t], topk_ids[t], topk_logp[t], rest_floor)
+    lb = np.asarray(behav_logp, dtype=np.float64)
+    delta = lp - lb
+    rho = np.exp(delta)
+    k_roll = kl_estimator(delta)
+    if teacher_logp is None or teacher_logp_stale is None:
+        k_sup = np.zeros(T)
+    else:
+        k_sup = kl_estimator(np.asarray(teacher_logp, dtype=np.float64) -
+                             np.asarray(teacher_logp_stale, dtype=np.float64))
+    B = cu.shape[0] - 1
+    D_roll, D_sup, ell, cover, n = sample_statistics(lp, np.zeros(T), k_roll, k_sup, mask, cu, token_loss=tok)
+    cover_roll, n_roll, n_valid = roll_coverage(mask, cu)
+    f = freshness_score(D_roll, D_sup, lag, n_valid, alpha, beta)
+    agg = buffer_aggregates(f, cover, cover_roll)
+    w = freshness_weights(f, xi, n_valid)
+    loss = anchored_loss(w, ell, D_roll, lam)
+    c1, c2 = np.zeros(T), np.zeros(T)
+    for i in range(B):
+        if int(n_valid[i]) == 0 or w[i] == 0.0:
+            continue
+        for t in range(int(cu[i]), int(cu[i + 1])):
+            if in_roll_set(mask[t]):
+                c1[t] = -grad_scale * w[i] / (B * int(n_roll[i])) * lam * rho[t] * delta[t]
+            if in_sup_set(mask[t]):
+                c2[t] = grad_scale * w[i] / (B * int(n[i]))
+    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, lse=lse, logp=lp, token_loss=tok, delta=delta, rho=rho,
+               adv=-lam * rho * delta, D_roll=D_roll, D_sup=D_sup, ell=ell, cover=cover, cover_roll=cover_roll,
+               freshness=f, agg=agg, weights=w, loss=loss, c1=c1, c2=c2)
+    if want_dlogits:
+        g = np.zeros((T, V))
+        for t in range(T):
+            g[t] = dlogits_row_topk(logits[t], int(token_ids[t]), topk_ids[t], topk_logp[t], rest_floor, c1[t], c2[t])
         res["dlogits_exact"] = g
         res["dlogits"] = round_to_bf16(g) if out_dtype == "bf16" else round_to_f32(g)
     return res

@@ -1075,3 +1075,148 @@ def test_projection_gradient_reduces_to_the_stored_logits_pass_and_rounds_the_ro
             want = math.fsum(float(res["dlogits"][t, v]) * float(H[t, k]) for t in range(T))
             assert abs(res["dweight"][v, k] - want) <= 1e-15
     assert abs(res["loss"] - ((0.8 * (0.4 + 0.5 * orc.kl_estimator(0.2)) + 0.5 * (0.4 + 0.5 * orc.kl_estimator(0.2))) / 2)) < 1e-14
+
+
+# ---------------------------------------------------------------------------------------
+# distribution-level token loss against a teacher stored as k tokens per row
+# ---------------------------------------------------------------------------------------
+
+def test_topk_teacher_hand_worked_rows():
+    """The two rows of tests/golden/topk_teacher_hand_worked.txt: loss, per-token G and gradient literals worked by
+    hand (slots out of vocabulary order; the floor of the rest binding in the second row)."""
+    want = {}
+    for line in open(os.path.join(GOLDEN, "topk_teacher_hand_worked.txt")):
+        if line.strip() and not line.startswith("#"):
+            name, *vals = line.split()
+            want[name] = np.array([float(v) for v in vals])
+    zA = np.log(np.array([4.0, 2.0, 1.0, 1.0]))
+    ell, G = orc.topk_token_loss_row(zA, [1, 0], [math.log(0.5), math.log(0.25)], 1e-6)
+    assert abs(ell - want["A_loss"][0]) < 1e-15
+    np.testing.assert_allclose(G, want["A_G"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(orc.dlogits_row_topk(zA, 3, [1, 0], [math.log(0.5), math.log(0.25)], 1e-6, 0.0, 1.0),
+                               want["A_grad"], rtol=0, atol=1e-15)
+    zB = np.zeros(2)
+    ell, G = orc.topk_token_loss_row(zB, [0], [0.0], 1.0 / 512.0)
+    assert abs(ell - want["B_loss"][0]) < 1e-15
+    np.testing.assert_allclose(G, want["B_G"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(orc.dlogits_row_topk(zB, 0, [0], [0.0], 1.0 / 512.0, 0.0, 1.0), want["B_grad"],
+                               rtol=0, atol=1e-15)
+    # the anchor's share of the row is the default path's: c1 (p - onehot)
+    np.testing.assert_allclose(orc.dlogits_row_topk(zA, 3, [1, 0], [math.log(0.5), math.log(0.25)], 1e-6, 2.0, 0.0),
+                               2.0 * (np.array([0.5, 0.25, 0.125, 0.125]) - np.array([0, 0, 0, 1.0])), atol=1e-15)
+
+
+def test_topk_teacher_full_list_is_the_kl_and_coarsening_never_raises_it():
+    """With every token listed the loss is KL(p || q) (scipy's rel_entr); merging tokens into the rest can only
+    lower it (log-sum inequality), so nested lists give a non-decreasing sequence below the full KL; the order of
+    the slots and unused slots (ids outside the vocabulary) do not matter; an empty list gives 0 and no gradient;
+    a token listed twice is refused."""
+    rng = _rng(91)
+    V = 13
+    for _ in range(6):
+        z = rng.normal(0, 2.0, V)
+        zq = rng.normal(0, 2.0, V)
+        p = scipy.special.softmax(z)
+        logq = scipy.special.log_softmax(zq)
+        full = float(np.sum(scipy.special.rel_entr(p, np.exp(logq))))
+        order = np.argsort(-logq)                       # the teacher's own ranking
+        ell_all, G_all = orc.topk_token_loss_row(z, order, logq[order], 1e-12)
+        assert abs(ell_all - full) < 1e-13
+        np.testing.assert_allclose(G_all, scipy.special.log_softmax(z) - logq, atol=1e-13)
+        prev = -1e-15
+        for k in range(0, V + 1):
+            ids = order[:k]
+            ell, _ = orc.topk_token_loss_row(z, ids, logq[ids], 1e-12)
+            assert prev - 1e-13 <= ell <= full + 1e-13, (k, ell, prev, full)
+            prev = ell
+        ids = order[:5]
+        a, Ga = orc.topk_token_loss_row(z, ids, logq[ids], 1e-12)
+        perm = rng.permutation(5)
+        b, Gb = orc.topk_token_loss_row(z, ids[perm], logq[ids][perm], 1e-12)
+        padded_ids = np.concatenate([[-1], ids[:2], [V], ids[2:], [V + 7]])
+        padded_lq = np.concatenate([[-0.1], logq[ids][:2], [-0.2], logq[ids][2:], [0.0]])
+        c, Gc = orc.topk_token_loss_row(z, padded_ids, padded_lq, 1e-12)
+        assert abs(a - b) < 1e-14 and abs(a - c) < 1e-14
+        np.testing.assert_allclose(Ga, Gb, atol=1e-14)
+        np.testing.assert_allclose(Ga, Gc, atol=1e-14)
+        e0, _ = orc.topk_token_loss_row(z, [-1, -1], [0.0, 0.0], 1e-12)
+        assert abs(e0) < 1e-15
+        assert np.max(np.abs(orc.dlogits_row_topk(z, 2, [-1, -1], [0.0, 0.0], 1e-12, 0.0, 1.0))) < 1e-15
+    with pytest.raises(ValueError):
+        orc.topk_token_loss_row(np.zeros(5), [1, 3, 1], [-1.0, -1.0, -1.0], 1e-6)
+
+
+def test_topk_teacher_pass_by_finite_differences_and_per_sample_means():
+    """Whole pass on two aligned sets: finite differences of
+    F(z) = sum_t w_i g / B ( [t in U^sup] l_t(z_t) / |U^sup| + [t in U^roll] lambda k(lp_t - lb_t) / |U^roll| ),
+    with l_t written here from scipy's softmax and explicit event sums (weights frozen); l_i is the mean of l_t over
+    U^sup; D^sup comes from the two sampled-token teacher arrays and is 0 when either is missing."""
+    c = _two_set_case(52)
+    rng = _rng(53)
+    T, V = c["z"].shape
+    B = len(c["seq"])
+    k = 4
+    zq = c["z"] + rng.normal(0, 0.8, size=(T, V))
+    logq_all = scipy.special.log_softmax(zq, axis=1)
+    ids = np.argsort(-logq_all, axis=1)[:, :k].astype(np.int32)
+    ids[1, 2] = -1                                      # an unused slot
+    lq_list = np.take_along_axis(logq_all, np.maximum(ids, 0), axis=1)
+    floor = 1e-4
+    cu = orc.segment_offsets(c["seq"])
+    n_sup, n_roll = orc.trainable_counts(c["mask"], cu), orc.roll_counts(c["mask"], cu)
+    sample_of = np.repeat(np.arange(B), c["seq"])
+    lam, g = 0.6, 1.3
+    res = orc.fopd_loss_fwd_bwd_topk_teacher(c["z"], c["y"], c["mask"], c["lb"], ids, lq_list, floor, c["lq"],
+                                             c["lqs"], c["seq"], c["lag"], 0.4, 0.4, 0.01, lam, grad_scale=g)
+    assert np.any(res["weights"] > 0)
+
+    def token_loss(zrow, t):
+        p = scipy.special.softmax(zrow)
+        listed = [int(u) for u in ids[t] if 0 <= u < V]
+        tot, p_in, q_in = 0.0, 0.0, 0.0
+        for j, u in enumerate(ids[t]):
+            if 0 <= u < V:
+                tot += p[u] * (math.log(p[u]) - lq_list[t, j])
+                p_in += p[u]
+                q_in += math.exp(lq_list[t, j])
+        p_rest = sum(p[u] for u in range(V) if u not in listed)
+        return tot + p_rest * (math.log(p_rest) - math.log(max(1.0 - q_in, floor)))
+
+    for i in range(B):
+        rows = [t for t in range(int(cu[i]), int(cu[i + 1])) if c["mask"][t] in (1, 3)]
+        if n_sup[i] and n_roll[i]:
+            assert abs(res["ell"][i] - sum(token_loss(c["z"][t], t) for t in rows) / len(rows)) < 1e-13
+    ref = orc.fopd_loss_fwd_bwd(c["z"], c["y"], c["mask"], c["lb"], c["lq"], c["lqs"], c["seq"], c["lag"],
+                                0.4, 0.4, 0.01, lam)
+    np.testing.assert_allclose(res["D_sup"], ref["D_sup"], atol=1e-15)      # same sampled-token arrays
+    np.testing.assert_allclose(res["D_roll"], ref["D_roll"], atol=1e-15)
+    none = orc.fopd_loss_fwd_bwd_topk_teacher(c["z"], c["y"], c["mask"], c["lb"], ids, lq_list, floor, c["lq"], None,
+                                              c["seq"], c["lag"], 0.4, 0.4, 0.01, lam)
+    assert np.all(none["D_sup"] == 0.0) and np.any(ref["D_sup"] > 0.0)
+
+    def surrogate(zz, w):
+        lp_all = scipy.special.log_softmax(zz, axis=1)
+        tot = 0.0
+        for t in range(T):
+            i = sample_of[t]
+            if w[i] == 0.0:
+                continue
+            if c["mask"][t] in (1, 3):
+                tot += g * w[i] / (B * n_sup[i]) * token_loss(zz[t], t)
+            if c["mask"][t] in (1, 2):
+                d = lp_all[t, c["y"][t]] - c["lb"][t]
+                tot += g * w[i] / (B * n_roll[i]) * lam * (math.exp(d) * d - math.exp(d) + 1.0)
+        return tot
+
+    h = 1e-6
+    num = np.zeros((T, V))
+    for t, v in itertools.product(range(T), range(V)):
+        zp, zm = c["z"].copy(), c["z"].copy()
+        zp[t, v] += h
+        zm[t, v] -= h
+        num[t, v] = (surrogate(zp, res["weights"]) - surrogate(zm, res["weights"])) / (2 * h)
+    assert np.max(np.abs(num - res["dlogits_exact"])) < 2e-6 * np.max(np.abs(num))
+    # the loss value itself
+    w = res["weights"]
+    want = sum(w[i] * (res["ell"][i] + lam * res["D_roll"][i]) for i in range(B)) / B
+    assert abs(res["loss"] - want) < 1e-15

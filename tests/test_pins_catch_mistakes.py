@@ -59,6 +59,23 @@ MISTAKES = {
     "unit rows lose the upstream scale": (
         "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, grad_scale, n_roll=n_roll)",
         "coef_unit = grad_coefficients(delta, rho, adv, mask, cu, n, ones, lam, 1.0, n_roll=n_roll)"),
+    "listed-token teacher: the rest event dropped": (
+        "        ell += p_rest * g_rest\n        G[~in_list] = g_rest", "        G[~in_list] = g_rest"),
+    "listed-token teacher: forward instead of reverse KL": (
+        "        G[u] = logp[u] - float(logq[j])\n        if p[u] > 0.0:\n            ell += p[u] * G[u]",
+        "        G[u] = logp[u] - float(logq[j])\n        if p[u] > 0.0:\n            ell -= math.exp(float(logq[j])) * G[u]"),
+    "listed-token teacher: rest of the teacher not floored": (
+        "q_rest = max(1.0 - q_listed, float(rest_floor))", "q_rest = max(1.0 - q_listed, 1e-300)"),
+    "listed-token teacher: rest of the student taken as one token": (
+        "p_rest = float(np.sum(p[~in_list]))", "p_rest = float(np.max(p[~in_list])) if np.any(~in_list) else 0.0"),
+    "listed-token teacher: gradient not centred by the loss": (
+        "g = p * (c1_t + c2_t * (np.where(p > 0.0, G, 0.0) - ell))", "g = p * (c1_t + c2_t * np.where(p > 0.0, G, 0.0))"),
+    "listed-token teacher: token loss normalised by the rollout count": (
+        "            if in_sup_set(mask[t]):\n                c2[t] = grad_scale * w[i] / (B * int(n[i]))\n    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, lse=lse, logp=lp, token_loss=tok",
+        "            if in_sup_set(mask[t]):\n                c2[t] = grad_scale * w[i] / (B * int(n_roll[i]))\n    res = dict(cu_seqlens=cu, n_train=n, n_roll=n_roll, lse=lse, logp=lp, token_loss=tok"),
+    "listed-token teacher: supervision drift kept without the stale array": (
+        "    if teacher_logp is None or teacher_logp_stale is None:\n        k_sup = np.zeros(T)",
+        "    if teacher_logp is None:\n        k_sup = np.zeros(T)\n    elif teacher_logp_stale is None:\n        k_sup = kl_estimator(np.asarray(teacher_logp, dtype=np.float64))"),
     "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
     "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
                                       "return float(np.log(np.sum(np.exp(z - mx))))"),
