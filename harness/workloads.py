@@ -107,6 +107,9 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     two aligned sets of a sample differ.  stale_logit_sigma=s (> 0) also returns `logits_stale`:
     the logits a stale checkpoint would give on the same prefixes, logits + s * lag_i * N(0, 1)
     per entry (identical to the current ones for lag 0), for the full-vocabulary drift diagnostic.
+    teacher_list=(k, s) also returns `list_ids` [T, k] int32 and `list_logp` [T, k] f32: the k most likely tokens
+    of a teacher whose logits are logits + s * N(0, 1) per entry, and their log-probabilities (the tensor library's
+    top-k and log-softmax: input preparation), from a generator of their own so that the other arrays do not change.
     """
     cfg = dict(CONFIGS[name])
     cfg.update(overrides)
@@ -133,11 +136,24 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
     lag_rows = torch.from_numpy(np.repeat(lag, seq_lens).astype(np.float32)).to(dev)
     token_ids = torch.empty(T, dtype=torch.int32, device=dev)
     ref_logp = torch.empty(T, dtype=torch.float32, device=dev)
+    list_ids = list_logp = None
+    if "teacher_list" in cfg:
+        list_k, list_sigma = int(cfg["teacher_list"][0]), float(cfg["teacher_list"][1])
+        list_ids = torch.empty(T, list_k, dtype=torch.int32, device=dev)
+        list_logp = torch.empty(T, list_k, dtype=torch.float32, device=dev)
+        gen_list = torch.Generator(device=dev)
+        gen_list.manual_seed(seed * 1000003 + 31)
     for a in range(0, T, row_block):
         b = min(a + row_block, T)
         zraw = _logit_rows(cfg, b - a, V, gen, dev)
         z = zraw.to(dtype)
         logits[a:b, :V] = z
+        if list_ids is not None:
+            zq = z.float() + list_sigma * torch.randn(b - a, V, generator=gen_list, device=dev)
+            top = torch.topk(zq, list_k, dim=1)
+            list_ids[a:b] = top.indices.to(torch.int32)
+            list_logp[a:b] = top.values - torch.logsumexp(zq, dim=1, keepdim=True)
+            del zq, top
         if logits_stale is not None:
             drift = torch.randn(b - a, V, generator=gen, device=dev) * (stale_sigma * lag_rows[a:b, None])
             logits_stale[a:b, :V] = torch.where(lag_rows[a:b, None] > 0, (zraw + drift).to(dtype), z)
@@ -162,7 +178,8 @@ def generate(name, device="cpu", seed=0, row_block=1024, ld=None, **overrides):
 
     return dict(name=name, cfg=cfg, T=T, V=V, ld=ld, B=int(cfg["B"]), dtype=cfg["dtype"],
                 logits=logits, logits_stale=logits_stale, token_ids=token_ids, mask=torch.from_numpy(mask).to(dev),
-                behav_logp=behav, teacher_logp=teacher, teacher_logp_stale=stale,
+                behav_logp=behav, teacher_logp=teacher, teacher_logp_stale=stale, list_ids=list_ids,
+                list_logp=list_logp,
                 seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
                 seq_lens_host=seq_lens, lag_host=lag, mask_host=mask,
                 n_trainable=int(((mask != 0) & (mask != 2)).sum()))

@@ -356,6 +356,44 @@ fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teach
                                            void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The whole pass with a distribution-level token loss against a teacher that is stored as k tokens per row with
+ * their log-probabilities, instead of a [T, V] tensor of teacher logits (Eq. "sample-aggregated-loss" with l a
+ * KL between distributions; the paper names distribution-level teacher supervision and no storage format, so the
+ * coarsening below is this library's reading).  Both distributions are reduced to the k + 1 events {listed token
+ * 1}, ..., {listed token k}, {any other token}:
+ *   P_j = softmax(z_t)[id_j],  P_rest = 1 - sum_j P_j;   Q_j = exp(lq_j),  Q_rest = max(1 - sum_j Q_j, rest_floor)
+ *   l_t = sum_j P_j (log P_j - lq_j) + P_rest (log P_rest - log Q_rest)          (an event with P = 0 adds 0)
+ * Listing every token gives the full KL( softmax(z_t) || teacher ); merging tokens into the rest can only lower it.
+ *   dL/dz_{t,u} = c1_t (p_u - [u = y_t]) + c2_t p_u (G_u - l_t),   G_u = log P_b - log Q_b of the event b holding u,
+ *   c1_t = -g [t in U^roll] w_i / (B |U_i^roll|) lambda rho_t delta_t,   c2_t = g [t in U^sup] w_i / (B |U_i^sup|).
+ * The rollout drift keeps the sampled-token estimator on behav_logp.  The logits are read twice and the gradient
+ * written once, as in fopd_loss_fwd_bwd; the k listed entries per row are gathered and corrected by two small
+ * kernels.
+ *   list_ids   [T, k] int32  the listed tokens of each row, distinct; an id outside [0, V) marks an unused slot
+ *   list_logp  [T, k] f32    their teacher log-probabilities (<= 0; unused slots are ignored)
+ *   k          1 .. 4096;  rest_floor in (0, 1]: the least probability the teacher keeps for "any other token"
+ *   teacher_logp, teacher_logp_stale  [T] f32 or NULL: the sampled token's teacher log-probabilities under the
+ *              current and the stale context, for D^sup only; D^sup = 0 unless both are given
+ *              (teacher_logp_stale without teacher_logp is FOPD_EINVAL)
+ *   loss [1], freshness [B] or NULL, weights [B] or NULL, logp [T] or NULL, token_loss [T] or NULL (l_t; 0 outside
+ *   U^sup): f32 outputs; dlogits [T, ld] in the logits' type, may alias logits
+ *   workspace  fopd_topk_workspace_bytes(T, B, k) bytes, 256-byte aligned, initialised once with
+ *              fopd_workspace_init; sticky flags as in fopd_loss_fwd_bwd
+ * Whole samples only (seq_lens must add up to T).  A row whose listed ids repeat a token has an undefined loss
+ * and gradient at that token (not checked).
+ */
+size_t fopd_topk_workspace_bytes(int64_t T, int32_t B, int32_t k);
+fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                           const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                                           const int32_t* list_ids, const float* list_logp, int32_t k,
+                                           float rest_floor, const float* teacher_logp,
+                                           const float* teacher_logp_stale, const int32_t* seq_lens,
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
+                                           float* loss, float* freshness, float* weights, float* logp,
+                                           float* token_loss, void* dlogits, void* workspace, size_t workspace_bytes,
+                                           void* stream);
+
+/*
  * Adaptive refresh test (Sec. 4.2, refresh condition; Algorithm 1, step after the aggregates; App. B:
  * the rule may fire at most once every `min_interval` optimizer steps, 200 in the paper).  HOST ONLY: all
  * pointers are host pointers and nothing touches the GPU.  `agg_host` is a host copy of the `agg` output

@@ -819,6 +819,96 @@ fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teach
                          dlogits, workspace, workspace_bytes, stream);
 }
 
+size_t fopd_topk_workspace_bytes(int64_t T, int32_t B, int32_t k) {
+  const size_t t = static_cast<size_t>(T < 0 ? 0 : T), kk = static_cast<size_t>(k < 0 ? 0 : k);
+  return Workspace(T, B).total + 2 * align_up(t * kk * sizeof(float), 256);
+}
+
+fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                           const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
+                                           const int32_t* list_ids, const float* list_logp, int32_t k,
+                                           float rest_floor, const float* teacher_logp,
+                                           const float* teacher_logp_stale, const int32_t* seq_lens,
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
+                                           float* loss, float* freshness, float* weights, float* logp,
+                                           float* token_loss, void* dlogits, void* workspace, size_t workspace_bytes,
+                                           void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
+  if (B <= 0 || k < 1 || k > 4096) return FOPD_ESHAPE;
+  if (token_ids == nullptr || behav_logp == nullptr || list_ids == nullptr || list_logp == nullptr ||
+      seq_lens == nullptr || lag == nullptr || loss == nullptr)
+    return FOPD_EINVAL;
+  if (teacher_logp_stale != nullptr && teacher_logp == nullptr) return FOPD_EINVAL;
+  if (!(rest_floor > 0.f) || !(rest_floor <= 1.f)) return FOPD_EINVAL;
+  if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
+  if (workspace_bytes < fopd_topk_workspace_bytes(T, B, k)) return FOPD_EWORKSPACE;
+
+  const Workspace w(T, B);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int32_t* flags = at<int32_t>(workspace, w.flags);
+  int64_t* cu = at<int64_t>(workspace, w.cu);
+  int32_t* nws = at<int32_t>(workspace, w.n_train);
+  int32_t* nrws = at<int32_t>(workspace, w.n_roll);
+  double* f64 = at<double>(workspace, w.fresh64);
+  float* c1 = at<float>(workspace, w.coef);
+  float* c2 = at<float>(workspace, w.coef2);
+  float* lse_ws = at<float>(workspace, w.lse);
+  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+  float* tl_ws = (token_loss != nullptr) ? token_loss : at<float>(workspace, w.kl);
+  float* g_rest = at<float>(workspace, w.dlse);
+  float* row_coef = at<float>(workspace, w.logq);
+  double* partials = at<double>(workspace, w.partials);
+  const size_t list_bytes = align_up(static_cast<size_t>(T) * static_cast<size_t>(k) * sizeof(float), 256);
+  float* p_list = at<float>(workspace, w.total);
+  float* h_list = at<float>(workspace, w.total + list_bytes);
+
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, T, cu, flags);
+  if ((st = launched()) != FOPD_OK) return st;
+  if ((st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s)) != FOPD_OK)
+    return st;
+  if (T > 0) {
+    const dim3 grid(static_cast<unsigned>(T)), block(kListThreads);
+    if (dt == FOPD_BF16)
+      fopd_topk_terms<FOPD_BF16><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
+                                                       list_logp, k, rest_floor, lse_ws, tl_ws, g_rest, p_list, h_list);
+    else
+      fopd_topk_terms<FOPD_F32><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
+                                                      list_logp, k, rest_floor, lse_ws, tl_ws, g_rest, p_list, h_list);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  // token loss = the distribution-level value per row; rollout drift = the sampled estimator; D^sup from the two
+  // sampled-token arrays when both are there
+  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, nullptr, tl_ws, teacher_logp, teacher_logp_stale,
+                                               mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                               nullptr, nullptr, nullptr, f64, nws, nrws);
+  if ((st = launched()) != FOPD_OK) return st;
+  const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
+  if (T > 0) {
+    fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+        logp_ws, tl_ws, nullptr, behav_logp, mask, cu, nws, nrws, lag, f64, nullptr, T, B, 0, hp, grad_scale, false, c1,
+        c2, partials);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, nrws, lag, f64, nullptr, B, hp.xi, loss, weights,
+                                            freshness);
+  if ((st = launched()) != FOPD_OK) return st;
+  if (T == 0) return FOPD_OK;
+  fopd_topk_row_coef<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(c1, c2, g_rest, T, row_coef);
+  if ((st = launched()) != FOPD_OK) return st;
+  if ((st = launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_ws, logp_ws, row_coef, s)) != FOPD_OK) return st;
+  const dim3 grid(static_cast<unsigned>(T)), block(kListThreads);
+  if (dt == FOPD_BF16)
+    fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
+                                                     logp_ws, c1, c2, g_rest, p_list, h_list);
+  else
+    fopd_topk_fixup<FOPD_F32><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
+                                                    logp_ws, c1, c2, g_rest, p_list, h_list);
+  return launched();
+}
+
 int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_host, fopd_refresh_state* state_host,
                         int64_t step, int32_t* reason_host) {
   if (agg_host == nullptr || cfg_host == nullptr || state_host == nullptr || cfg_host->min_interval < 1) return -1;

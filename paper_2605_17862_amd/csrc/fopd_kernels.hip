@@ -1376,7 +1376,8 @@ fopd_segment_stats(const float* logp, const float* behav_logp, const float* roll
       cr += 1.0;
     }
     if (sup) {
-      const double lq = teacher_logp[t];
+      // (no teacher log-prob of the sampled token is needed when the token loss is supplied and D^sup is 0)
+      const double lq = (teacher_logp != nullptr) ? static_cast<double>(teacher_logp[t]) : 0.0;
       if (teacher_logp_stale != nullptr) ss += kl_term(lq - static_cast<double>(teacher_logp_stale[t]), nullptr);
       // token loss: a distribution-level value if the caller has one, else the sampled-token form
       sl += (ell_term != nullptr) ? static_cast<double>(ell_term[t]) : lp - lq;
@@ -1497,6 +1498,115 @@ fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, 
           static_cast<float>(weight_of(f, n_train[i], (n_roll != nullptr) ? n_roll[i] : n_train[i], lag[i], xi));
     if (freshness != nullptr) freshness[i] = static_cast<float>(f);
   }
+}
+
+// =========================================================================================
+// Teacher stored as k tokens per row (ids and log-probabilities): the distribution-level token loss is the
+// reverse KL between the student's and the teacher's distributions coarsened to the events {listed token 1},
+// ..., {listed token k}, {any other token} (Eq. "sample-aggregated-loss" with a distribution-level l):
+//   l_t = sum_j P_j (log P_j - lq_j) + P_rest (log P_rest - log Q_rest),   Q_rest = max(1 - sum_j e^{lq_j}, floor)
+//   d l_t / d z_u = p_u (G_u - l_t),   G_u = log P_b - log Q_b of the event b that holds token u.
+// Every token outside the list has the same G, so the gradient row is the ordinary stream c p_u with one
+// coefficient per row, corrected at the k listed tokens and at the sampled one.
+// =========================================================================================
+
+constexpr int kListThreads = 64;      // one wavefront per row
+
+// Per row of U^sup: gathers the listed logits, forms l_t, G_rest - l_t and, per slot, p_j and h_j = p_j (G_j - l_t).
+// A slot whose id is outside [0, V) is unused.  Rows outside U^sup (and rows whose sampled token is out of range:
+// lse = 0 there) get zeros.
+template <int DT>
+__global__ void __launch_bounds__(kListThreads)
+fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const uint8_t* mask,
+                const int32_t* list_ids, const float* list_logp, int k, float rest_floor, const float* lse,
+                float* token_loss, float* g_rest, float* p_list, float* h_list) {
+  const int64_t t = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int y = token_ids[t];
+  const bool live = in_sup_set(mask, t) && y >= 0 && y < V;
+  const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const double ls = lse[t];
+  double sp = 0.0, sq = 0.0, sl = 0.0;
+  if (live) {
+    for (int j = lane; j < k; j += kListThreads) {
+      const int id = list_ids[t * k + j];
+      if (id < 0 || id >= V) continue;
+      const double lq = list_logp[t * k + j];
+      const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
+      const double pj = exp(lp);
+      sp += pj;
+      sq += exp(lq);
+      if (pj > 0.0) sl += pj * (lp - lq);
+    }
+  }
+  sp = wave_sum(sp);
+  sq = wave_sum(sq);
+  sl = wave_sum(sl);
+  double ell = 0.0, gr = 0.0;
+  if (live) {
+    const double p_rest = 1.0 - sp, q_rest = fmax(1.0 - sq, static_cast<double>(rest_floor));
+    // what fp32 log-probs leave of 1 is noise below 1e-30: the rest then holds no token worth a gradient
+    gr = log(fmax(p_rest, 1e-30)) - log(q_rest);
+    ell = sl + (p_rest > 0.0 ? p_rest * gr : 0.0);
+  }
+  for (int j = lane; j < k; j += kListThreads) {
+    float pj = 0.f, hj = 0.f;
+    if (live) {
+      const int id = list_ids[t * k + j];
+      if (id >= 0 && id < V) {
+        const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
+        const double p = exp(lp);
+        pj = static_cast<float>(p);
+        hj = (p > 0.0) ? static_cast<float>(p * ((lp - static_cast<double>(list_logp[t * k + j])) - ell)) : 0.f;
+      }
+    }
+    p_list[t * k + j] = pj;
+    h_list[t * k + j] = hj;
+  }
+  if (lane == 0) {
+    token_loss[t] = static_cast<float>(ell);
+    g_rest[t] = static_cast<float>(gr - ell);
+  }
+}
+
+// The stream's coefficient of a row: c1 + c2 (G_rest - l_t).
+__global__ void __launch_bounds__(kStreamThreads)
+fopd_topk_row_coef(const float* c1, const float* c2, const float* g_rest, int64_t T, float* coef) {
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * kStreamThreads + threadIdx.x;
+  if (t < T) coef[t] = static_cast<float>(static_cast<double>(c1[t]) + static_cast<double>(c2[t]) * static_cast<double>(g_rest[t]));
+}
+
+// After the gradient stream has written c p_u everywhere (and c expm1(lp) at the sampled token): the k listed
+// entries become c1 (p_j - [j is the sampled token]) + c2 h_j, and the sampled token's entry, if it is not listed,
+// c1 (p_y - 1) + c2 (G_rest - l_t) p_y.  Rows without a token-loss share (c2 = 0) are already right.
+template <int DT>
+__global__ void __launch_bounds__(kListThreads)
+fopd_topk_fixup(void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const int32_t* list_ids, int k,
+                const float* logp, const float* c1, const float* c2, const float* g_rest, const float* p_list,
+                const float* h_list) {
+  const int64_t t = blockIdx.x;
+  const int lane = threadIdx.x;
+  const float a = c1[t], b = c2[t];
+  const int y = token_ids[t];
+  if (b == 0.f || y < 0 || y >= V) return;
+  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  const float py_m1 = expm1f(logp[t]);                     // p_y - 1, accurate as p_y -> 1
+  bool mine = false;
+  for (int j = lane; j < k; j += kListThreads) {
+    const int id = list_ids[t * k + j];
+    if (id < 0 || id >= V) continue;
+    const float pj = p_list[t * k + j], hj = h_list[t * k + j];
+    float g;
+    if (id == y) {
+      mine = true;
+      g = fmaf(a, py_m1, b * hj);
+    } else {
+      g = fmaf(a, pj, b * hj);
+    }
+    store_elem<DT>(orow, id, g);
+  }
+  const bool listed = __any(mine ? 1 : 0) != 0;
+  if (!listed && lane == 0) store_elem<DT>(orow, y, fmaf(a, py_m1, b * g_rest[t] * (py_m1 + 1.0f)));
 }
 
 }  // namespace fopd

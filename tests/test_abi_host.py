@@ -126,6 +126,44 @@ def test_single_read_call_rejects_bad_arguments_before_launch():
     assert _unit(lib, wsb=64) == 5
 
 
+def _listed(lib, **kw):
+    a = dict(logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, mask=None, lb=4096, lids=4096, llq=4096, k=4, floor=1e-4,
+             lq=None, lqs=None, seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), g=1.0, loss=4096, f=None,
+             w=None, lp=None, tl=None, dl=8192, ws=4096, wsb=1 << 20)
+    a.update(kw)
+    return lib.fopd_loss_fwd_bwd_topk_teacher(P(a["logits"]), a["dt"], a["T"], a["V"], a["ld"], P(a["ids"]),
+                                              P(a["mask"]), P(a["lb"]), P(a["lids"]), P(a["llq"]), a["k"], a["floor"],
+                                              P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"], a["hp"],
+                                              a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]), P(a["tl"]),
+                                              P(a["dl"]), P(a["ws"]), a["wsb"], None)
+
+
+def test_listed_teacher_call_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _listed(lib, logits=None) == 1
+    assert _listed(lib, dl=None) == 1
+    assert _listed(lib, lids=None) == 1
+    assert _listed(lib, llq=None) == 1
+    assert _listed(lib, lb=None) == 1
+    assert _listed(lib, loss=None) == 1
+    assert _listed(lib, lqs=4096) == 1                      # the stale array without the current one
+    assert _listed(lib, floor=0.0) == 1
+    assert _listed(lib, floor=1.5) == 1
+    assert _listed(lib, floor=float("nan")) == 1
+    assert _listed(lib, hp=fb.Hparams(-1, 1, 0, 0)) == 1
+    assert _listed(lib, k=0) == 2
+    assert _listed(lib, k=5000) == 2
+    assert _listed(lib, B=0) == 2
+    assert _listed(lib, V=0) == 2
+    assert _listed(lib, dt=3) == 4
+    assert _listed(lib, dl=8192 + 2) == 3
+    assert _listed(lib, ws=None) == 5
+    need = fb.fopd_topk_workspace_bytes(8, 2, 4)
+    assert need == fb.fopd_workspace_bytes(8, 2) + 2 * 256
+    assert _listed(lib, wsb=need - 1) == 5
+    assert fb.fopd_topk_workspace_bytes(163894, 64, 64) == fb.fopd_workspace_bytes(163894, 64) + 2 * 163894 * 64 * 4
+
+
 def test_freshness_rejects_bad_arguments_before_launch():
     lib = fb.load_library()
 

@@ -1,0 +1,292 @@
+"""GPU parity of fopd_loss_fwd_bwd_topk_teacher: the distribution-level token loss against a teacher stored as
+k tokens per row (Eq. "sample-aggregated-loss" with l a KL between the two distributions coarsened to the listed
+tokens plus one event for the rest), against the float64 oracle.
+
+Tolerances (derived from the arithmetic; the path's own are in parity_util.py).  The kernels take lp_j = z_j - lse
+with lse in fp32 (1e-6 absolute), so every listed probability carries 1e-6 relative and the student's rest,
+1 - sum_j P_j, 1e-6 absolute (more when few fp32 digits are left of it):
+  token loss l_t    2e-5 relative + 1e-6 (|G_rest| + 3): d l / d P_rest = G_rest + 1
+  G of a listed token 2e-6 absolute; G_rest 2e-6 + 2e-6 / P_rest
+  dlogits           2 ulp of the storage type (2e-5 relative for fp32) plus the floor
+                    |p_u - [u = y]| eps_c1 + p_u (|G_u - l| eps_c2 + |c2| (dG_u + dl)),
+                    eps_c1, eps_c2 the absolute uncertainties of the two row coefficients that the tolerances on
+                    lp and f_i already allow (as for the other variants)."""
+
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from harness import workloads as wl
+from oracle import fopd_oracle as orc
+from paper_2605_17862_amd import binding as fb
+from parity_util import EPS_A, EPS_F, assert_close, np64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+FLOOR = 1e-4
+
+
+def _say(msg):
+    print("[gpu-topk-teacher] " + msg, flush=True)
+
+
+class _Buffers:
+    def __init__(self, T, V, B, k, dtype, ld):
+        f32 = dict(dtype=torch.float32, device=DEV)
+        self.dt = fb.FOPD_BF16 if dtype == "bf16" else fb.FOPD_F32
+        self.loss = torch.empty(1, **f32)
+        self.freshness = torch.empty(B, **f32)
+        self.weights = torch.empty(B, **f32)
+        self.logp = torch.empty(T, **f32)
+        self.token_loss = torch.empty(T, **f32)
+        self.dlogits = torch.empty(T, ld, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device=DEV)
+        nbytes = fb.fopd_topk_workspace_bytes(T, B, k)
+        raw = torch.empty(nbytes + 256, dtype=torch.uint8, device=DEV)
+        off = (-raw.data_ptr()) % 256
+        self.workspace = raw[off:off + nbytes]
+        fb.fopd_workspace_init(self.workspace)
+
+    def ok(self):
+        st, flags = fb.fopd_workspace_status(self.workspace)
+        assert st == 0 and flags == 0, "device flags %d (%s)" % (flags, fb.fopd_status_string(st))
+
+
+def _call(w, buf, k, hp, gs, dlogits=None, stale=True, logits=None):
+    fb.fopd_loss_fwd_bwd_topk_teacher(
+        w["logits"] if logits is None else logits, buf.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"],
+        w["behav_logp"], w["list_ids"], w["list_logp"], k, FLOOR, w["teacher_logp"],
+        w["teacher_logp_stale"] if stale else None, w["seq_lens"], w["lag"], w["B"], hp, gs, buf.loss, buf.freshness,
+        buf.weights, buf.logp, buf.token_loss, buf.dlogits if dlogits is None else dlogits, buf.workspace)
+
+
+def _oracle(w, hp, gs, stale=True, rows=None, n_samples=None):
+    V = w["V"]
+    sl = slice(None) if rows is None else slice(rows[0], rows[1])
+    seq = np64(w["seq_lens"]) if rows is None else np.array([rows[1] - rows[0]], dtype=np.int64)
+    lag = np64(w["lag"]) if rows is None else np64(w["lag"])[rows[2]:rows[2] + 1]
+    g = gs if n_samples is None else gs / n_samples         # one sample of a larger call: 1/B of the whole call
+    lqs = w["teacher_logp_stale"] if stale else None
+    return orc.fopd_loss_fwd_bwd_topk_teacher(
+        np64(w["logits"][sl])[:, :V], np64(w["token_ids"][sl]), np64(w["mask"][sl]), np64(w["behav_logp"][sl]),
+        np64(w["list_ids"][sl]), np64(w["list_logp"][sl]), FLOOR, np64(w["teacher_logp"][sl]),
+        None if lqs is None else np64(lqs[sl]), seq, lag, hp[0], hp[1], hp[2], hp[3], grad_scale=g,
+        out_dtype=w["dtype"], want_dlogits=False)
+
+
+def _token_loss_tolerance(z_row, ids, lq):
+    ell, G = orc.topk_token_loss_row(z_row, ids, lq, FLOOR)
+    V = z_row.shape[0]
+    listed = np.zeros(V, dtype=bool)
+    listed[[int(u) for u in ids if 0 <= int(u) < V]] = True
+    p = np.exp(z_row - orc.row_logsumexp(z_row))
+    p_rest = float(np.sum(p[~listed]))
+    g_rest = float(G[~listed][0]) if np.any(~listed) and p_rest > 0.0 else 0.0
+    return ell, G, listed, p, p_rest, 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0)
+
+
+def _check_rows(got_rows, w, ref, rows, hp, gs, n_samples, sample_of_row, offset=0, z_rows=None):
+    """got_rows[k] is the GPU gradient row of global row rows[k]; ref holds oracle arrays indexed by row - offset."""
+    V, store = w["V"], w["dtype"]
+    lam = hp[3]
+    for k, t in enumerate(rows):
+        r = t - offset
+        z = np64(w["logits"][t])[:V] if z_rows is None else z_rows[k]
+        ids, lq, y = np64(w["list_ids"][t]), np64(w["list_logp"][t]), int(w["token_ids"][t])
+        c1, c2 = ref["c1"][r], ref["c2"][r]
+        i = sample_of_row[r]
+        f, wt = ref["freshness"][i], ref["weights"][i]
+        n_sup, n_roll = int(ref["n_train"][i]), int(ref["n_roll"][i])
+        if c1 == 0.0 and c2 == 0.0 and (min(n_sup, n_roll) == 0 or f < hp[2] * (1 - 1e-4) or int(w["mask_host"][t]) == 0):
+            assert not np.any(got_rows[k]), "row %d must be exactly zero" % t
+            continue
+        exact = orc.dlogits_row_topk(z, y, ids, lq, FLOOR, c1, c2)
+        ell, G, listed, p, p_rest, eps_l = _token_loss_tolerance(z, ids, lq)
+        pm = p.copy()
+        pm[y] -= 1.0
+        m = int(w["mask_host"][t])
+        eps_c1 = (abs(gs) / (n_samples * n_roll) * lam * (wt * EPS_A + EPS_F * f * abs(ref["rho"][r] * ref["delta"][r]))
+                  if m in (1, 2) else 0.0)
+        eps_c2 = abs(gs) / (n_samples * n_sup) * EPS_F * f if m in (1, 3) else 0.0
+        dG = np.where(listed, 2e-6, 2e-6 + 2e-6 / max(p_rest, 1e-30))
+        floor = np.abs(pm) * eps_c1 + p * (np.abs(G - ell) * eps_c2 + abs(c2) * (dG + eps_l)) + 2.0 ** -126
+        floor[y] += (abs(c1) + eps_c1) * 4.0 * np.spacing(max(abs(ref["lse"][r]), 1.0))
+        if store == "bf16":
+            want = orc.round_to_bf16(exact)
+            lim = 2.0 * orc.bf16_ulp(want) + floor
+        else:
+            want = orc.round_to_f32(exact)
+            lim = 2e-5 * np.abs(want) + floor
+        err = np.abs(got_rows[k] - want)
+        bad = ~((err <= lim) | (got_rows[k] == want))
+        assert not np.any(bad), "row %d: %d elements off, worst %.3e vs limit %.3e at u=%d (listed: %s, y=%d)" % (
+            t, int(bad.sum()), float(err[bad].max()), float(lim[np.argmax(err * bad)]), int(np.argmax(err * bad)),
+            bool(listed[int(np.argmax(err * bad))]), y)
+
+
+def _compare(w, k, hp, gs, stale=True, in_place=False):
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    ref = _oracle(w, hp, gs, stale=stale)
+    buf = _Buffers(T, V, B, k, w["dtype"], ld)
+    buf.dlogits.fill_(7.0)
+    saved = w["logits"].clone()
+    if in_place:
+        _call(w, buf, k, hp, gs, dlogits=w["logits"], stale=stale)
+        out = w["logits"]
+    else:
+        _call(w, buf, k, hp, gs, stale=stale)
+        out = buf.dlogits
+    buf.ok()
+    live = np64(w["mask"]) != 0
+    sup = (np64(w["mask"]) != 0) & (np64(w["mask"]) != 2)
+    assert_close("logp", np64(buf.logp)[live], ref["logp"][live], rtol=1e-5, atol=2e-6)
+    z64 = np64(saved)[:, :V]
+    ids, lq = np64(w["list_ids"]), np64(w["list_logp"])
+    got_tl = np64(buf.token_loss)
+    for t in range(T):
+        if sup[t]:
+            tol = _token_loss_tolerance(z64[t], ids[t], lq[t])[5]
+            assert abs(got_tl[t] - ref["token_loss"][t]) <= tol, (t, got_tl[t], ref["token_loss"][t], tol)
+        else:
+            assert got_tl[t] == 0.0
+    assert_close("freshness", np64(buf.freshness), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(buf.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(buf.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12, (float(buf.loss), ref["loss"])
+    sample_of_row = np.repeat(np.arange(B), np64(w["seq_lens"]).astype(np.int64))
+    src = dict(w, logits=saved)
+    _check_rows(np64(out)[:, :V], src, ref, list(range(T)), hp, gs, B, sample_of_row)
+    if ld > V and not in_place:
+        assert bool((out[:, V:] == 7.0).all())
+    if in_place:
+        w["logits"].copy_(saved)
+    return ref, buf
+
+
+CASES = {
+    "bf16 full vocabulary": dict(dtype="bf16", V=151936, k=64, B=5),
+    "bf16 ragged tail, pitch, k over a wavefront": dict(dtype="bf16", V=5003, ld=5008, k=100, B=6),
+    "f32": dict(dtype="f32", V=9001, ld=9004, k=7, B=6),
+    "two aligned sets": dict(dtype="bf16", V=20000, k=16, B=6, aligned_split=(0.3, 0.3)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_topk_teacher_pass_matches_the_oracle(name):
+    c = dict(CASES[name])
+    k = c.pop("k")
+    _say("whole pass: %s" % name)
+    w = wl.generate("tooluse", DEV, seed=61, turns=2, obs_lo=2, obs_hi=5, resp_lo=3, resp_hi=9, boost=4, lag_lo=0,
+                    lag_hi=30, row_block=32, teacher_list=(k, 0.7), **c)
+    # unused slots in some rows, a listed sampled token in some, and one row listing nothing
+    w["list_ids"][1, 0] = -1
+    w["list_ids"][2, k - 1] = w["V"] + 5
+    w["list_ids"][4, :] = -1
+    for t in (0, 3, 5):
+        if not bool((w["list_ids"][t] == w["token_ids"][t]).any()):
+            w["list_ids"][t, k // 2] = w["token_ids"][t]
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 0.75
+    ref, buf = _compare(w, k, hp, gs)
+    valid = np.minimum(ref["n_train"], ref["n_roll"]) > 0
+    assert np.any(ref["weights"] > 0) and np.any(valid & (ref["weights"] == 0.0))      # live and gated samples
+    listed_y = (w["list_ids"] == w["token_ids"][:, None]).any(dim=1)
+    assert bool(listed_y.any()) and not bool(listed_y.all())
+
+
+def test_topk_teacher_in_place_without_the_stale_array_and_rerun():
+    """dlogits aliasing logits; D^sup = 0 when the stale array is missing; a second run gives the same bits."""
+    _say("in place, no stale teacher log-probs, rerun")
+    k = 32
+    w = wl.generate("tooluse", DEV, seed=62, B=5, turns=2, obs_lo=1, obs_hi=4, resp_lo=3, resp_hi=9, V=16392,
+                    dtype="bf16", boost=4, lag_lo=0, lag_hi=20, row_block=32, teacher_list=(k, 0.5))
+    hp, gs = (1.0, 1.0, 0.05, 0.2), 1.0
+    ref, buf = _compare(w, k, hp, gs, stale=False, in_place=True)
+    assert np.all(ref["D_sup"] == 0.0)
+    first = buf.dlogits.clone()
+    buf2 = _Buffers(w["T"], w["V"], w["B"], k, w["dtype"], w["ld"])
+    _call(w, buf, k, hp, gs, stale=False)
+    _call(w, buf2, k, hp, gs, stale=False)
+    buf.ok()
+    buf2.ok()
+    assert torch.equal(buf.dlogits, buf2.dlogits) and torch.equal(buf.loss, buf2.loss)
+    saved = w["logits"].clone()
+    _call(w, buf2, k, hp, gs, dlogits=w["logits"], stale=False)
+    assert torch.equal(w["logits"], buf.dlogits)
+    w["logits"].copy_(saved)
+    del first
+
+
+def test_topk_teacher_listing_every_token_is_the_full_teacher_call():
+    """With every token listed the coarsened loss is the full KL: the token loss, scores, loss and gradient agree
+    with fopd_loss_fwd_bwd_full_teacher on the teacher's logits (both against the oracle elsewhere; here the two
+    GPU calls against each other, to the path's tolerances).  What fp32 leaves of 1 on either side is noise of
+    about 1e-6, so the floor of the rest is put there: a far smaller floor would turn that noise into
+    1e-6 log(1e-6 / floor) of token loss."""
+    _say("every token listed against the full-teacher call")
+    V, k = 640, 640
+    w = wl.generate("tooluse", DEV, seed=63, B=4, turns=2, obs_lo=1, obs_hi=3, resp_lo=3, resp_hi=8, V=V, dtype="f32",
+                    boost=4, lag_lo=0, lag_hi=10, row_block=32, teacher_list=(k, 0.6))
+    T, B = w["T"], w["B"]
+    # teacher logits whose log-softmax is the listed log-probabilities
+    zq = torch.full((T, V), 0.0, device=DEV)
+    zq.scatter_(1, w["list_ids"].long(), w["list_logp"])
+    hp, gs = (1.0, 0.0, 0.05, 0.3), 1.0
+    buf = _Buffers(T, V, B, k, "f32", V)
+    fb.fopd_loss_fwd_bwd_topk_teacher(w["logits"], buf.dt, T, V, V, w["token_ids"], w["mask"], w["behav_logp"],
+                                      w["list_ids"], w["list_logp"], k, 1e-6, None, None, w["seq_lens"], w["lag"], B, hp,
+                                      gs, buf.loss, buf.freshness, buf.weights, buf.logp, buf.token_loss, buf.dlogits,
+                                      buf.workspace)
+    buf.ok()
+    other = _Buffers(T, V, B, 1, "f32", V)
+    fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], zq, other.dt, T, V, V, V, w["token_ids"], w["mask"], w["behav_logp"],
+                                      None, w["seq_lens"], w["lag"], B, hp, None, None, None, 0, None, None, None, None,
+                                      gs, other.loss, other.freshness, other.weights, other.logp, other.token_loss,
+                                      other.dlogits, other.workspace)
+    other.ok()
+    assert_close("token loss", np64(buf.token_loss), np64(other.token_loss), rtol=2e-5, atol=6e-6)
+    assert_close("weights", np64(buf.weights), np64(other.weights), rtol=2e-5, atol=1e-7)
+    assert abs(float(buf.loss) - float(other.loss)) <= 2e-5 * abs(float(other.loss))
+    a, b = np64(buf.dlogits), np64(other.dlogits)
+    scale = np.max(np.abs(b), axis=1, keepdims=True)
+    # each call's l_t is within 6e-6 of the exact one, and an entry is c2 p_u (G_u - l_t): a consistency check
+    assert np.all(np.abs(a - b) <= 2e-5 * np.abs(b) + 2e-4 * scale)
+
+
+def test_topk_teacher_reasoning_full_size_sampled():
+    """The bench's workload at full size (B = 64 ragged sequences, V = 151,936 bf16, k = 64): two whole samples
+    through the oracle (log-probs, token loss, score, weight) and gradient rows picked from them."""
+    k = 64
+    _say("reasoning at full size, k = %d" % k)
+    w = wl.generate("reasoning", DEV, seed=0, teacher_list=(k, 0.5))
+    T, V, B = w["T"], w["V"], w["B"]
+    hp, gs = (1.0, 1.0, 0.05, 0.1), 1.0
+    buf = _Buffers(T, V, B, k, "bf16", w["ld"])
+    _call(w, buf, k, hp, gs)
+    buf.ok()
+    cu = np.concatenate([[0], np.cumsum(w["seq_lens_host"])]).astype(np.int64)
+    order = np.argsort(w["seq_lens_host"])
+    rng = np.random.RandomState(5)
+    for i in (int(order[0]), int(order[1])):
+        a, b = int(cu[i]), int(cu[i + 1])
+        _say("  sample %d: rows %d..%d" % (i, a, b))
+        ref = _oracle(w, hp, gs, rows=(a, b, i), n_samples=B)
+        assert_close("logp", np64(buf.logp[a:b]), ref["logp"], rtol=1e-5, atol=2e-6)
+        f = ref["freshness"][0]
+        assert abs(float(buf.freshness[i]) - f) <= 1e-5 * f
+        assert abs(float(buf.weights[i]) - ref["weights"][0]) <= 1e-5 * f
+        picks = sorted(rng.choice(b - a, size=6, replace=False).tolist())
+        z_rows = [np64(w["logits"][a + r])[:V] for r in picks]
+        got_tl = np64(buf.token_loss[a:b])
+        for r, z in zip(picks, z_rows):
+            tol = _token_loss_tolerance(z, np64(w["list_ids"][a + r]), np64(w["list_logp"][a + r]))[5]
+            assert abs(got_tl[r] - ref["token_loss"][r]) <= tol
+        # the sample's mean token loss enters its share of the loss; compare the mean over all its rows
+        assert abs(float(np.mean(got_tl)) - float(np.mean(ref["token_loss"]))) <= 2e-5 * abs(float(np.mean(ref["token_loss"]))) + 2e-6
+        got = np64(buf.dlogits[torch.tensor([a + r for r in picks], device=DEV)])[:, :V]
+        _check_rows(got, w, ref, [a + r for r in picks], hp, gs, B, np.zeros(b - a, dtype=np.int64), offset=a,
+                    z_rows=z_rows)
+    # property at any size: every row of a live sample sums to ~0 relative to its largest entry is not exact in
+    # bf16; instead: rows of gated samples are exactly zero
+    wts = np64(buf.weights)
+    for i in np.nonzero(wts == 0.0)[0][:2]:
+        assert not bool(buf.dlogits[int(cu[i]):int(cu[i + 1])].any())
