@@ -157,6 +157,71 @@ def bench_full_kl(args, torch, fb, wl, LossPass, hp):
                                    "frac": k5_bytes / k5_s / 1e9 / HBM_PEAK_GBS}}}))
 
 
+def bench_topk_teacher(args, torch, fb, wl, hp):
+    """One JSON line for fopd_loss_fwd_bwd_topk_teacher: the bench workload plus a teacher stored as --list-k tokens
+    per row.  The two streaming kernels are those of the headline; the list is handled by two small kernels."""
+    k = args.list_k
+    w = wl.generate(args.workload, "cuda:0", seed=0, teacher_list=(k, 0.5))
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    dev = "cuda:0"
+    f32 = dict(dtype=torch.float32, device=dev)
+    dt = fb.FOPD_BF16 if w["dtype"] == "bf16" else fb.FOPD_F32
+    loss, fresh, weights = torch.empty(1, **f32), torch.empty(B, **f32), torch.empty(B, **f32)
+    logp, token_loss = torch.empty(T, **f32), torch.empty(T, **f32)
+    dlogits = torch.empty_like(w["logits"])
+    nbytes = fb.fopd_topk_workspace_bytes(T, B, k)
+    raw = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    off = (-raw.data_ptr()) % 256
+    ws = raw[off:off + nbytes]
+    fb.fopd_workspace_init(ws)
+
+    def step():
+        fb.fopd_loss_fwd_bwd_topk_teacher(w["logits"], dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"],
+                                          w["list_ids"], w["list_logp"], k, 1e-4, w["teacher_logp"],
+                                          w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, 1.0, loss, fresh,
+                                          weights, logp, token_loss, dlogits, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    fb.fopd_profile_reset()
+    fb.fopd_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    fb.fopd_profile_enable(False)
+    st, flags = fb.fopd_workspace_status(ws)
+    if st != 0 or flags != 0:
+        sys.exit("bench.py: device flags %d" % flags)
+    k1_ms, n1 = fb.fopd_profile_read(0)
+    k4_ms, n4 = fb.fopd_profile_read(1)
+    import numpy as np
+    e = 2 if w["dtype"] == "bf16" else 4
+    live = int((w["mask_host"] != 0).sum())
+    per_row_w = np.repeat(weights.cpu().numpy(), w["seq_lens_host"])
+    grad_rows = int(((w["mask_host"] != 0) & (per_row_w > 0)).sum())
+    k1_bytes = live * V * e
+    k4_bytes = grad_rows * 2 * V * e + (T - grad_rows) * V * e
+    k1_s, k4_s = k1_ms / max(n1, 1) * 1e-3, k4_ms / max(n4, 1) * 1e-3
+    ms = elapsed / args.steps * 1e3
+    print(json.dumps({
+        "metric": "tokens/s, OPD loss fwd+bwd with distribution-level loss against a teacher stored as %d tokens "
+                  "per row, V=%d %s" % (k, V, w["dtype"]),
+        "value": w["n_trainable"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload + "+teacher_list", "B": B, "T_rows": T, "V": V, "k": k,
+                   "storage": w["dtype"], "call": "fopd_loss_fwd_bwd_topk_teacher"},
+        "roofline": {"bound": "hbm", "kernel": "fopd_k4_grad", "achieved": k4_bytes / k4_s / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k4_bytes / k4_s / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_launch": k4_bytes, "avg_ms": k4_s * 1e3},
+        "kernels": {"fopd_k1_lse": {"avg_ms": k1_s * 1e3, "GB/s": k1_bytes / k1_s / 1e9,
+                                    "frac": k1_bytes / k1_s / 1e9 / HBM_PEAK_GBS},
+                    "list kernels, scores, coefficients": {"ms_per_step": ms - (k1_s + k4_s) * 1e3}}}))
+
+
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -330,7 +395,10 @@ def main():
                     help="skip the projection-fused log-prob measurement reported beside the headline")
     ap.add_argument("--rows-chunk", type=int, default=16384,
                     help="rows per chunk of the loss pass through the projection (--variant lm_head_loss)")
-    ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "lm_head", "lm_head_loss"),
+    ap.add_argument("--list-k", type=int, default=64,
+                    help="tokens per row of the stored teacher (--variant topk_teacher)")
+    ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "topk_teacher", "lm_head",
+                                          "lm_head_loss"),
                     default="default",
                     help="full_kl: the pass whose rollout drift is the full-vocabulary KL against a second "
                          "(stale-checkpoint) logits tensor; lm_head: token log-probs from hidden states with "
@@ -351,6 +419,8 @@ def main():
     hp = DEFAULT_HPARAMS
     if args.variant in ("full_kl", "full_teacher"):
         return bench_full_kl(args, torch, fb, wl, LossPass, hp)
+    if args.variant == "topk_teacher":
+        return bench_topk_teacher(args, torch, fb, wl, hp)
     if args.variant == "lm_head":
         print(json.dumps(bench_lm_head(args, torch, fb, wl)))
         return

@@ -870,7 +870,7 @@ fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, in
   if ((st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s)) != FOPD_OK)
     return st;
   if (T > 0) {
-    const dim3 grid(static_cast<unsigned>(T)), block(kListThreads);
+    const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
     if (dt == FOPD_BF16)
       fopd_topk_terms<FOPD_BF16><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
                                                        list_logp, k, rest_floor, lse_ws, tl_ws, g_rest, p_list, h_list);
@@ -899,7 +899,7 @@ fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, in
   fopd_topk_row_coef<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(c1, c2, g_rest, T, row_coef);
   if ((st = launched()) != FOPD_OK) return st;
   if ((st = launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_ws, logp_ws, row_coef, s)) != FOPD_OK) return st;
-  const dim3 grid(static_cast<unsigned>(T)), block(kListThreads);
+  const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
   if (dt == FOPD_BF16)
     fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
                                                      logp_ws, c1, c2, g_rest, p_list, h_list);

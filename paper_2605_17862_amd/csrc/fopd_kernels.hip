@@ -1510,33 +1510,48 @@ fopd_loss_final(const double* partials, int64_t nparts, const int32_t* n_train, 
 // coefficient per row, corrected at the k listed tokens and at the sampled one.
 // =========================================================================================
 
-constexpr int kListThreads = 64;      // one wavefront per row
+constexpr int kListThreads = 256;     // four wavefronts, one row each
+constexpr int kListRows = kListThreads / 64;
+constexpr int kListHeld = 4;          // slots per lane kept in registers between the two loops (k <= 256)
 
 // Per row of U^sup: gathers the listed logits, forms l_t, G_rest - l_t and, per slot, p_j and h_j = p_j (G_j - l_t).
 // A slot whose id is outside [0, V) is unused.  Rows outside U^sup (and rows whose sampled token is out of range:
-// lse = 0 there) get zeros.
+// lse = 0 there) get zeros.  One wavefront per row.
 template <int DT>
 __global__ void __launch_bounds__(kListThreads)
 fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const uint8_t* mask,
                 const int32_t* list_ids, const float* list_logp, int k, float rest_floor, const float* lse,
                 float* token_loss, float* g_rest, float* p_list, float* h_list) {
-  const int64_t t = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * kListRows + (threadIdx.x >> 6);
+  if (t >= T) return;                                      // whole wavefronts; no barrier in this kernel
+  const int lane = threadIdx.x & 63;
   const int y = token_ids[t];
   const bool live = in_sup_set(mask, t) && y >= 0 && y < V;
   const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+  const int32_t* ids = list_ids + t * k;
+  const float* lqs = list_logp + t * k;
   const double ls = lse[t];
+  // log P_j - lq_j and P_j of the lane's first kListHeld slots stay in registers for the second loop
+  double held_g[kListHeld], held_p[kListHeld];
   double sp = 0.0, sq = 0.0, sl = 0.0;
   if (live) {
-    for (int j = lane; j < k; j += kListThreads) {
-      const int id = list_ids[t * k + j];
-      if (id < 0 || id >= V) continue;
-      const double lq = list_logp[t * k + j];
-      const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
-      const double pj = exp(lp);
-      sp += pj;
-      sq += exp(lq);
-      if (pj > 0.0) sl += pj * (lp - lq);
+    int h = 0;
+    for (int j = lane; j < k; j += 64, ++h) {
+      const int id = ids[j];
+      double pj = 0.0, gj = 0.0;
+      if (id >= 0 && id < V) {
+        const double lq = lqs[j];
+        const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
+        pj = exp(lp);
+        gj = lp - lq;
+        sp += pj;
+        sq += exp(lq);
+        if (pj > 0.0) sl += pj * gj;
+      }
+      if (h < kListHeld) {
+        held_p[h] = pj;
+        held_g[h] = gj;
+      }
     }
   }
   sp = wave_sum(sp);
@@ -1549,16 +1564,26 @@ fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t*
     gr = log(fmax(p_rest, 1e-30)) - log(q_rest);
     ell = sl + (p_rest > 0.0 ? p_rest * gr : 0.0);
   }
-  for (int j = lane; j < k; j += kListThreads) {
+  int h = 0;
+  for (int j = lane; j < k; j += 64, ++h) {
     float pj = 0.f, hj = 0.f;
     if (live) {
-      const int id = list_ids[t * k + j];
-      if (id >= 0 && id < V) {
-        const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
-        const double p = exp(lp);
-        pj = static_cast<float>(p);
-        hj = (p > 0.0) ? static_cast<float>(p * ((lp - static_cast<double>(list_logp[t * k + j])) - ell)) : 0.f;
+      double p, g;
+      if (h < kListHeld) {
+        p = held_p[h];
+        g = held_g[h];
+      } else {
+        const int id = ids[j];
+        p = 0.0;
+        g = 0.0;
+        if (id >= 0 && id < V) {
+          const double lp = static_cast<double>(load_elem<DT>(row, id)) - ls;
+          p = exp(lp);
+          g = lp - static_cast<double>(lqs[j]);
+        }
       }
+      pj = static_cast<float>(p);
+      hj = (p > 0.0) ? static_cast<float>(p * (g - ell)) : 0.f;
     }
     p_list[t * k + j] = pj;
     h_list[t * k + j] = hj;
@@ -1578,21 +1603,23 @@ fopd_topk_row_coef(const float* c1, const float* c2, const float* g_rest, int64_
 
 // After the gradient stream has written c p_u everywhere (and c expm1(lp) at the sampled token): the k listed
 // entries become c1 (p_j - [j is the sampled token]) + c2 h_j, and the sampled token's entry, if it is not listed,
-// c1 (p_y - 1) + c2 (G_rest - l_t) p_y.  Rows without a token-loss share (c2 = 0) are already right.
+// c1 (p_y - 1) + c2 (G_rest - l_t) p_y.  Rows without a token-loss share (c2 = 0) are already right.  One
+// wavefront per row.
 template <int DT>
 __global__ void __launch_bounds__(kListThreads)
 fopd_topk_fixup(void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const int32_t* list_ids, int k,
                 const float* logp, const float* c1, const float* c2, const float* g_rest, const float* p_list,
                 const float* h_list) {
-  const int64_t t = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int64_t t = static_cast<int64_t>(blockIdx.x) * kListRows + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const int lane = threadIdx.x & 63;
   const float a = c1[t], b = c2[t];
   const int y = token_ids[t];
   if (b == 0.f || y < 0 || y >= V) return;
   char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
   const float py_m1 = expm1f(logp[t]);                     // p_y - 1, accurate as p_y -> 1
   bool mine = false;
-  for (int j = lane; j < k; j += kListThreads) {
+  for (int j = lane; j < k; j += 64) {
     const int id = list_ids[t * k + j];
     if (id < 0 || id >= V) continue;
     const float pj = p_list[t * k + j], hj = h_list[t * k + j];
