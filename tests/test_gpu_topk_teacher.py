@@ -290,3 +290,35 @@ def test_topk_teacher_reasoning_full_size_sampled():
     wts = np64(buf.weights)
     for i in np.nonzero(wts == 0.0)[0][:2]:
         assert not bool(buf.dlogits[int(cu[i]):int(cu[i + 1])].any())
+
+
+def test_topk_teacher_replay_from_a_hip_graph():
+    """The call enqueues kernels only (no fill or copy nodes), so it can be captured; replays with eager work and
+    synchronisations in between reproduce the eager bits."""
+    _say("HIP graph capture and replay")
+    k = 24
+    w = wl.generate("tooluse", DEV, seed=64, B=4, turns=2, obs_lo=1, obs_hi=3, resp_lo=3, resp_hi=8, V=8200, dtype="bf16",
+                    boost=4, lag_lo=0, lag_hi=10, row_block=32, teacher_list=(k, 0.6))
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 1.0
+    eager = _Buffers(w["T"], w["V"], w["B"], k, "bf16", w["ld"])
+    _call(w, eager, k, hp, gs)
+    torch.cuda.synchronize()
+    cap = _Buffers(w["T"], w["V"], w["B"], k, "bf16", w["ld"])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        _call(w, cap, k, hp, gs)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        cap.dlogits.fill_(float(rep))
+        cap.loss.zero_()
+        cap.token_loss.fill_(9.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cap.dlogits, eager.dlogits) and torch.equal(cap.loss, eager.loss)
+        assert torch.equal(cap.token_loss, eager.token_loss) and torch.equal(cap.weights, eager.weights)
+    cap.ok()
