@@ -168,6 +168,8 @@ CASES = {
     "bf16 ragged tail, pitch, k over a wavefront": dict(dtype="bf16", V=5003, ld=5008, k=100, B=6),
     "f32": dict(dtype="f32", V=9001, ld=9004, k=7, B=6),
     "two aligned sets": dict(dtype="bf16", V=20000, k=16, B=6, aligned_split=(0.3, 0.3)),
+    # more slots per lane than the kernel keeps in registers between its two loops (4 x 64)
+    "list of 300 tokens": dict(dtype="bf16", V=9001, ld=9008, k=300, B=4),
 }
 
 
