@@ -178,8 +178,8 @@ def bench_topk_teacher(args, torch, fb, wl, hp):
     def step():
         fb.fopd_loss_fwd_bwd_topk_teacher(w["logits"], dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"],
                                           w["list_ids"], w["list_logp"], k, 1e-4, w["teacher_logp"],
-                                          w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, 1.0, loss, fresh,
-                                          weights, logp, token_loss, dlogits, ws)
+                                          w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, None, None, None,
+                                          0, None, None, 1.0, loss, fresh, weights, logp, token_loss, dlogits, ws)
 
     for _ in range(args.warmup):
         step()

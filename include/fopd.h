@@ -153,7 +153,8 @@ fopd_status fopd_token_logprobs(const void* logits, fopd_dtype dt, int64_t T, in
  *   token_loss                      [T] f32 or NULL: a per-row token loss computed elsewhere (the
  *                                   distribution-level KL against the teacher's logits, the `roll_kl`
  *                                   output of fopd_rollout_kl called with the teacher's tensor); when
- *                                   given, ell averages it instead of lp - lq
+ *                                   given, ell averages it instead of lp - lq, and teacher_logp may be NULL
+ *                                   if teacher_logp_stale is NULL too (nothing reads it then)
  *   teacher_logp_stale              [T] f32 or NULL: teacher log-probability under the context
  *                                   used at grading time; NULL gives D^sup = 0
  *   mask [T] uint8 or NULL; seq_lens [B] int32 (sum must be T); lag [B] int32 >= 0
@@ -379,19 +380,37 @@ fopd_status fopd_loss_fwd_bwd_full_teacher(const void* logits, const void* teach
  *   U^sup): f32 outputs; dlogits [T, ld] in the logits' type, may alias logits
  *   workspace  fopd_topk_workspace_bytes(T, B, k) bytes, 256-byte aligned, initialised once with
  *              fopd_workspace_init; sticky flags as in fopd_loss_fwd_bwd
- * Whole samples only (seq_lens must add up to T).  A row whose listed ids repeat a token has an undefined loss
- * and gradient at that token (not checked).
+ * A row whose listed ids repeat a token has an undefined loss and gradient at that token (not checked).
+ *
+ * Modes, by which of the optional inputs are given (any other combination is FOPD_EINVAL):
+ *   none of them        a whole batch: seq_lens add up to T, everything is computed in the call
+ *   freshness_in given  a chunk of a longer batch, rows [row_begin, row_begin + T): freshness_in [B], n_train_in
+ *                       [B] (required), n_roll_in [B] (NULL = the two sets coincide), and the chunk's slices lse_in,
+ *                       logp_in [T] (required).  The flow: per chunk fopd_token_logprobs (-> logp, lse) and
+ *                       fopd_topk_token_loss (-> token_loss); once fopd_freshness_score(logp, behav_logp, NULL,
+ *                       token_loss, teacher_logp, teacher_logp_stale, ...) over the O(T) arrays; then per chunk this
+ *                       call, which forms the listed terms again from lse_in (O(T k)) and makes coefficients, the
+ *                       chunk's additive share of the loss and the gradient rows.  Chunks may cut samples; seq_lens
+ *                       and lag describe the whole batch; teacher_logp / teacher_logp_stale are not read.
+ *
+ * fopd_topk_token_loss: l_t alone, for the flow above.  lse [T] f32 from fopd_token_logprobs on the same rows;
+ * token_loss [T] f32 out (0 outside U^sup).  Needs no workspace.
  */
 size_t fopd_topk_workspace_bytes(int64_t T, int32_t B, int32_t k);
+fopd_status fopd_topk_token_loss(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                 const int32_t* token_ids, const uint8_t* mask, const int32_t* list_ids,
+                                 const float* list_logp, int32_t k, float rest_floor, const float* lse,
+                                 float* token_loss, void* stream);
 fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                                            const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
                                            const int32_t* list_ids, const float* list_logp, int32_t k,
                                            float rest_floor, const float* teacher_logp,
                                            const float* teacher_logp_stale, const int32_t* seq_lens,
-                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
-                                           float* loss, float* freshness, float* weights, float* logp,
-                                           float* token_loss, void* dlogits, void* workspace, size_t workspace_bytes,
-                                           void* stream);
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                           const int32_t* n_train_in, const int32_t* n_roll_in, int64_t row_begin,
+                                           const float* lse_in, const float* logp_in, float grad_scale, float* loss,
+                                           float* freshness, float* weights, float* logp, float* token_loss,
+                                           void* dlogits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Adaptive refresh test (Sec. 4.2, refresh condition; Algorithm 1, step after the aggregates; App. B:

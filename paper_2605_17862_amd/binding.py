@@ -20,7 +20,7 @@ SYMBOLS = (
     "fopd_token_logprobs", "fopd_freshness_score", "fopd_loss_fwd_bwd", "fopd_loss_fwd_bwd_unit", "fopd_loss_fwd_bwd_static",
     "fopd_profile_enable", "fopd_profile_reset", "fopd_profile_read", "fopd_set_option",
     "fopd_refresh_decide", "fopd_rollout_kl", "fopd_loss_fwd_bwd_full_kl", "fopd_loss_fwd_bwd_full_teacher",
-    "fopd_topk_workspace_bytes", "fopd_loss_fwd_bwd_topk_teacher",
+    "fopd_topk_workspace_bytes", "fopd_topk_token_loss", "fopd_loss_fwd_bwd_topk_teacher",
     "fopd_lm_head_workspace_bytes", "fopd_lm_head_token_logprobs",
     "fopd_lm_head_loss_workspace_bytes", "fopd_lm_head_loss_fwd_bwd",
 )
@@ -103,7 +103,10 @@ def load_library():
     lib.fopd_topk_workspace_bytes.argtypes = [i64, i32, i32]
     lib.fopd_loss_fwd_bwd_topk_teacher.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_topk_teacher.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, vp, i32, f32, vp, vp,
-                                                   vp, vp, i32, Hparams, f32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                                   vp, vp, i32, Hparams, vp, vp, vp, i64, vp, vp, f32, vp, vp, vp, vp,
+                                                   vp, vp, vp, sz, vp]
+    lib.fopd_topk_token_loss.restype = ctypes.c_int
+    lib.fopd_topk_token_loss.argtypes = [vp, ctypes.c_int, i64, i64, i64, vp, vp, vp, vp, i32, f32, vp, vp, vp]
     lib.fopd_loss_fwd_bwd_full_kl.restype = ctypes.c_int
     lib.fopd_loss_fwd_bwd_full_kl.argtypes = [vp, vp, ctypes.c_int, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32,
                                               Hparams, vp, vp, vp, i64, vp, vp, vp, vp, f32,
@@ -414,9 +417,22 @@ def fopd_topk_workspace_bytes(T, B, k):
     return int(load_library().fopd_topk_workspace_bytes(int(T), int(B), int(k)))
 
 
+def fopd_topk_token_loss(logits, dt, T, V, ld, token_ids, mask, list_ids, list_logp, k, rest_floor, lse, token_loss,
+                         stream=None):
+    import torch
+    f32 = torch.float32
+    st = load_library().fopd_topk_token_loss(
+        _ptr(logits, (torch.float32, torch.bfloat16), "logits"), int(dt), int(T), int(V), int(ld),
+        _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(list_ids, torch.int32, "list_ids"), _ptr(list_logp, f32, "list_logp"), int(k), float(rest_floor),
+        _ptr(lse, f32, "lse"), _ptr(token_loss, f32, "token_loss"), _stream(stream))
+    _check(st, "fopd_topk_token_loss")
+
+
 def fopd_loss_fwd_bwd_topk_teacher(logits, dt, T, V, ld, token_ids, mask, behav_logp, list_ids, list_logp, k,
-                                   rest_floor, teacher_logp, teacher_logp_stale, seq_lens, lag, B, hp, grad_scale,
-                                   loss, freshness, weights, logp, token_loss, dlogits, workspace, stream=None):
+                                   rest_floor, teacher_logp, teacher_logp_stale, seq_lens, lag, B, hp, freshness_in,
+                                   n_train_in, n_roll_in, row_begin, lse_in, logp_in, grad_scale, loss, freshness,
+                                   weights, logp, token_loss, dlogits, workspace, stream=None):
     import torch
     f32 = torch.float32
     mat = (torch.float32, torch.bfloat16)
@@ -426,7 +442,9 @@ def fopd_loss_fwd_bwd_topk_teacher(logits, dt, T, V, ld, token_ids, mask, behav_
         _ptr(mask, torch.uint8, "mask"), _ptr(behav_logp, f32, "behav_logp"), _ptr(list_ids, torch.int32, "list_ids"),
         _ptr(list_logp, f32, "list_logp"), int(k), float(rest_floor), _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(seq_lens, torch.int32, "seq_lens"),
-        _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), float(grad_scale), _ptr(loss, f32, "loss"),
+        _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), _ptr(freshness_in, f32, "freshness_in"),
+        _ptr(n_train_in, torch.int32, "n_train_in"), _ptr(n_roll_in, torch.int32, "n_roll_in"), int(row_begin),
+        _ptr(lse_in, f32, "lse_in"), _ptr(logp_in, f32, "logp_in"), float(grad_scale), _ptr(loss, f32, "loss"),
         _ptr(freshness, f32, "freshness"), _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"),
         _ptr(token_loss, f32, "token_loss"), _ptr(dlogits, mat, "dlogits"), p, n, _stream(stream))
     _check(st, "fopd_loss_fwd_bwd_topk_teacher")

@@ -525,9 +525,11 @@ fopd_status fopd_freshness_score(const float* logp, const float* behav_logp, con
                                  float* freshness, float* agg, void* workspace, size_t workspace_bytes,
                                  void* stream) {
   if (T < 0 || B <= 0) return FOPD_ESHAPE;
-  if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || teacher_logp == nullptr ||
-      seq_lens == nullptr || lag == nullptr || freshness == nullptr)
+  if (logp == nullptr || (behav_logp == nullptr && roll_kl == nullptr) || seq_lens == nullptr || lag == nullptr ||
+      freshness == nullptr)
     return FOPD_EINVAL;
+  // the sampled token's teacher log-prob is needed for the sampled-token loss and for D^sup
+  if (teacher_logp == nullptr && (token_loss == nullptr || teacher_logp_stale != nullptr)) return FOPD_EINVAL;
   if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
   fopd_status st = check_workspace(workspace, workspace_bytes, T, B);
   if (st != FOPD_OK) return st;
@@ -824,25 +826,61 @@ size_t fopd_topk_workspace_bytes(int64_t T, int32_t B, int32_t k) {
   return Workspace(T, B).total + 2 * align_up(t * kk * sizeof(float), 256);
 }
 
+static fopd_status launch_topk_terms(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                     const int32_t* token_ids, const uint8_t* mask, const int32_t* list_ids,
+                                     const float* list_logp, int32_t k, float rest_floor, const float* lse,
+                                     float* token_loss, float* g_rest, float* p_list, float* h_list, hipStream_t s) {
+  if (T == 0) return FOPD_OK;
+  const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
+  if (dt == FOPD_BF16)
+    fopd_topk_terms<FOPD_BF16><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
+                                                     list_logp, k, rest_floor, lse, token_loss, g_rest, p_list, h_list);
+  else
+    fopd_topk_terms<FOPD_F32><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
+                                                    list_logp, k, rest_floor, lse, token_loss, g_rest, p_list, h_list);
+  return launched();
+}
+
+fopd_status fopd_topk_token_loss(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
+                                 const int32_t* token_ids, const uint8_t* mask, const int32_t* list_ids,
+                                 const float* list_logp, int32_t k, float rest_floor, const float* lse,
+                                 float* token_loss, void* stream) {
+  fopd_status st = check_matrix(logits, dt, T, V, ld);
+  if (st != FOPD_OK) return st;
+  if (k < 1 || k > 4096) return FOPD_ESHAPE;
+  if (token_ids == nullptr || list_ids == nullptr || list_logp == nullptr || lse == nullptr || token_loss == nullptr)
+    return FOPD_EINVAL;
+  if (!(rest_floor > 0.f) || !(rest_floor <= 1.f)) return FOPD_EINVAL;
+  return launch_topk_terms(logits, dt, T, V, ld, token_ids, mask, list_ids, list_logp, k, rest_floor, lse, token_loss,
+                           nullptr, nullptr, nullptr, static_cast<hipStream_t>(stream));
+}
+
 fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, int64_t T, int64_t V, int64_t ld,
                                            const int32_t* token_ids, const uint8_t* mask, const float* behav_logp,
                                            const int32_t* list_ids, const float* list_logp, int32_t k,
                                            float rest_floor, const float* teacher_logp,
                                            const float* teacher_logp_stale, const int32_t* seq_lens,
-                                           const int32_t* lag, int32_t B, fopd_hparams hp, float grad_scale,
-                                           float* loss, float* freshness, float* weights, float* logp,
-                                           float* token_loss, void* dlogits, void* workspace, size_t workspace_bytes,
-                                           void* stream) {
+                                           const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                           const int32_t* n_train_in, const int32_t* n_roll_in, int64_t row_begin,
+                                           const float* lse_in, const float* logp_in, float grad_scale, float* loss,
+                                           float* freshness, float* weights, float* logp, float* token_loss,
+                                           void* dlogits, void* workspace, size_t workspace_bytes, void* stream) {
   fopd_status st = check_matrix(logits, dt, T, V, ld);
   if (st != FOPD_OK) return st;
   if ((st = check_matrix(dlogits, dt, T, V, ld)) != FOPD_OK) return st;
-  if (B <= 0 || k < 1 || k > 4096) return FOPD_ESHAPE;
+  if (B <= 0 || k < 1 || k > 4096 || row_begin < 0) return FOPD_ESHAPE;
   if (token_ids == nullptr || behav_logp == nullptr || list_ids == nullptr || list_logp == nullptr ||
       seq_lens == nullptr || lag == nullptr || loss == nullptr)
     return FOPD_EINVAL;
   if (teacher_logp_stale != nullptr && teacher_logp == nullptr) return FOPD_EINVAL;
   if (!(rest_floor > 0.f) || !(rest_floor <= 1.f)) return FOPD_EINVAL;
   if (!(hp.alpha >= 0.f) || !(hp.beta >= 0.f)) return FOPD_EINVAL;
+  // a chunk of a longer batch brings the scores, the counts and its slices of lse and logp; a whole batch none
+  const bool chunk = (freshness_in != nullptr);
+  const bool all_in = n_train_in != nullptr && lse_in != nullptr && logp_in != nullptr;
+  const bool none_in = n_train_in == nullptr && n_roll_in == nullptr && lse_in == nullptr && logp_in == nullptr &&
+                       row_begin == 0;
+  if (chunk ? !all_in : !none_in) return FOPD_EINVAL;
   if ((st = check_workspace(workspace, workspace_bytes, T, B)) != FOPD_OK) return st;
   if (workspace_bytes < fopd_topk_workspace_bytes(T, B, k)) return FOPD_EWORKSPACE;
 
@@ -855,8 +893,6 @@ fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, in
   double* f64 = at<double>(workspace, w.fresh64);
   float* c1 = at<float>(workspace, w.coef);
   float* c2 = at<float>(workspace, w.coef2);
-  float* lse_ws = at<float>(workspace, w.lse);
-  float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
   float* tl_ws = (token_loss != nullptr) ? token_loss : at<float>(workspace, w.kl);
   float* g_rest = at<float>(workspace, w.dlse);
   float* row_coef = at<float>(workspace, w.logq);
@@ -865,47 +901,60 @@ fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, in
   float* p_list = at<float>(workspace, w.total);
   float* h_list = at<float>(workspace, w.total + list_bytes);
 
-  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, T, cu, flags);
+  fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, chunk ? -1 : T, row_begin + T, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
-  if ((st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s)) != FOPD_OK)
-    return st;
-  if (T > 0) {
-    const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
-    if (dt == FOPD_BF16)
-      fopd_topk_terms<FOPD_BF16><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
-                                                       list_logp, k, rest_floor, lse_ws, tl_ws, g_rest, p_list, h_list);
-    else
-      fopd_topk_terms<FOPD_F32><<<grid, block, 0, s>>>(logits, T, static_cast<int>(V), ld, token_ids, mask, list_ids,
-                                                      list_logp, k, rest_floor, lse_ws, tl_ws, g_rest, p_list, h_list);
-    if ((st = launched()) != FOPD_OK) return st;
+  const float* lse_use = lse_in;
+  const float* logp_use = logp_in;
+  const int32_t* n_use = n_train_in;
+  const int32_t* nr_use = (n_roll_in != nullptr) ? n_roll_in : n_train_in;
+  const double* f64_use = nullptr;
+  if (!chunk) {
+    float* lse_ws = at<float>(workspace, w.lse);
+    float* logp_ws = (logp != nullptr) ? logp : at<float>(workspace, w.logp);
+    if ((st = launch_k1(logits, dt, T, V, ld, token_ids, mask, logp_ws, lse_ws, nullptr, nullptr, flags, s)) != FOPD_OK)
+      return st;
+    lse_use = lse_ws;
+    logp_use = logp_ws;
+  } else if (logp != nullptr && logp != logp_in && T > 0 &&
+             hipMemcpyAsync(logp, logp_in, static_cast<size_t>(T) * sizeof(float), hipMemcpyDeviceToDevice, s) !=
+                 hipSuccess) {
+    return FOPD_EHIP;
   }
-  // token loss = the distribution-level value per row; rollout drift = the sampled estimator; D^sup from the two
-  // sampled-token arrays when both are there
-  fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_ws, behav_logp, nullptr, tl_ws, teacher_logp, teacher_logp_stale,
-                                               mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr,
-                                               nullptr, nullptr, nullptr, f64, nws, nrws);
-  if ((st = launched()) != FOPD_OK) return st;
+  if ((st = launch_topk_terms(logits, dt, T, V, ld, token_ids, mask, list_ids, list_logp, k, rest_floor, lse_use, tl_ws,
+                              g_rest, p_list, h_list, s)) != FOPD_OK)
+    return st;
+  if (!chunk) {
+    // token loss = the distribution-level value per row; rollout drift = the sampled estimator; D^sup from the two
+    // sampled-token arrays when both are there
+    fopd_segment_stats<<<B, kSegThreads, 0, s>>>(logp_use, behav_logp, nullptr, tl_ws, teacher_logp,
+                                                 teacher_logp_stale, mask, cu, lag, T, hp, nullptr, nullptr, nullptr,
+                                                 nullptr, nullptr, nullptr, nullptr, nullptr, f64, nws, nrws);
+    if ((st = launched()) != FOPD_OK) return st;
+    n_use = nws;
+    nr_use = nrws;
+    f64_use = f64;
+  }
   const int64_t nblk = (T + kStreamThreads - 1) / kStreamThreads;
   if (T > 0) {
     fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp_ws, tl_ws, nullptr, behav_logp, mask, cu, nws, nrws, lag, f64, nullptr, T, B, 0, hp, grad_scale, false, c1,
-        c2, partials);
+        logp_use, tl_ws, nullptr, behav_logp, mask, cu, n_use, nr_use, lag, f64_use, freshness_in, T, B, row_begin, hp,
+        grad_scale, false, c1, c2, partials);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, nws, nrws, lag, f64, nullptr, B, hp.xi, loss, weights,
-                                            freshness);
+  fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
+                                            weights, freshness);
   if ((st = launched()) != FOPD_OK) return st;
   if (T == 0) return FOPD_OK;
   fopd_topk_row_coef<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(c1, c2, g_rest, T, row_coef);
   if ((st = launched()) != FOPD_OK) return st;
-  if ((st = launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_ws, logp_ws, row_coef, s)) != FOPD_OK) return st;
+  if ((st = launch_k4(logits, dlogits, dt, T, V, ld, token_ids, lse_use, logp_use, row_coef, s)) != FOPD_OK) return st;
   const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
   if (dt == FOPD_BF16)
     fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
-                                                     logp_ws, c1, c2, g_rest, p_list, h_list);
+                                                     logp_use, c1, c2, g_rest, p_list, h_list);
   else
     fopd_topk_fixup<FOPD_F32><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
-                                                    logp_ws, c1, c2, g_rest, p_list, h_list);
+                                                    logp_use, c1, c2, g_rest, p_list, h_list);
   return launched();
 }
 

@@ -1516,7 +1516,8 @@ constexpr int kListHeld = 4;          // slots per lane kept in registers betwee
 
 // Per row of U^sup: gathers the listed logits, forms l_t, G_rest - l_t and, per slot, p_j and h_j = p_j (G_j - l_t).
 // A slot whose id is outside [0, V) is unused.  Rows outside U^sup (and rows whose sampled token is out of range:
-// lse = 0 there) get zeros.  One wavefront per row.
+// lse = 0 there) get zeros.  One wavefront per row.  g_rest, and p_list together with h_list, may be NULL (only the
+// token loss is wanted).
 template <int DT>
 __global__ void __launch_bounds__(kListThreads)
 fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const uint8_t* mask,
@@ -1565,7 +1566,7 @@ fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t*
     ell = sl + (p_rest > 0.0 ? p_rest * gr : 0.0);
   }
   int h = 0;
-  for (int j = lane; j < k; j += 64, ++h) {
+  for (int j = lane; p_list != nullptr && j < k; j += 64, ++h) {      // (p_list and h_list come together)
     float pj = 0.f, hj = 0.f;
     if (live) {
       double p, g;
@@ -1590,7 +1591,7 @@ fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t*
   }
   if (lane == 0) {
     token_loss[t] = static_cast<float>(ell);
-    g_rest[t] = static_cast<float>(gr - ell);
+    if (g_rest != nullptr) g_rest[t] = static_cast<float>(gr - ell);
   }
 }
 

@@ -128,14 +128,16 @@ def test_single_read_call_rejects_bad_arguments_before_launch():
 
 def _listed(lib, **kw):
     a = dict(logits=4096, dt=1, T=8, V=64, ld=64, ids=4096, mask=None, lb=4096, lids=4096, llq=4096, k=4, floor=1e-4,
-             lq=None, lqs=None, seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), g=1.0, loss=4096, f=None,
-             w=None, lp=None, tl=None, dl=8192, ws=4096, wsb=1 << 20)
+             lq=None, lqs=None, seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), fin=None, nin=None,
+             nroll=None, rb=0, lsein=None, lpin=None, g=1.0, loss=4096, f=None, w=None, lp=None, tl=None, dl=8192,
+             ws=4096, wsb=1 << 20)
     a.update(kw)
     return lib.fopd_loss_fwd_bwd_topk_teacher(P(a["logits"]), a["dt"], a["T"], a["V"], a["ld"], P(a["ids"]),
                                               P(a["mask"]), P(a["lb"]), P(a["lids"]), P(a["llq"]), a["k"], a["floor"],
                                               P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"], a["hp"],
-                                              a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]), P(a["tl"]),
-                                              P(a["dl"]), P(a["ws"]), a["wsb"], None)
+                                              P(a["fin"]), P(a["nin"]), P(a["nroll"]), a["rb"], P(a["lsein"]),
+                                              P(a["lpin"]), a["g"], P(a["loss"]), P(a["f"]), P(a["w"]), P(a["lp"]),
+                                              P(a["tl"]), P(a["dl"]), P(a["ws"]), a["wsb"], None)
 
 
 def test_listed_teacher_call_rejects_bad_arguments_before_launch():
@@ -161,6 +163,19 @@ def test_listed_teacher_call_rejects_bad_arguments_before_launch():
     need = fb.fopd_topk_workspace_bytes(8, 2, 4)
     assert need == fb.fopd_workspace_bytes(8, 2) + 2 * 256
     assert _listed(lib, wsb=need - 1) == 5
+    # a chunk brings scores, counts and its slices of lse and logp; a whole batch brings none of them
+    assert _listed(lib, fin=4096) == 1
+    assert _listed(lib, fin=4096, nin=4096, lsein=4096) == 1
+    assert _listed(lib, nin=4096) == 1
+    assert _listed(lib, rb=8) == 1
+    assert _listed(lib, rb=-1) == 2
+    tok = lib.fopd_topk_token_loss
+    assert tok(P(4096), 1, 8, 64, 64, P(4096), None, P(4096), P(4096), 4, 1e-4, P(4096), None, None) == 1
+    assert tok(P(4096), 1, 8, 64, 64, P(4096), None, P(4096), P(4096), 4, 1e-4, None, P(4096), None) == 1
+    assert tok(P(4096), 1, 8, 64, 64, P(4096), None, None, P(4096), 4, 1e-4, P(4096), P(4096), None) == 1
+    assert tok(P(4096), 1, 8, 64, 64, P(4096), None, P(4096), P(4096), 0, 1e-4, P(4096), P(4096), None) == 2
+    assert tok(P(4096), 1, 8, 64, 64, P(4096), None, P(4096), P(4096), 4, 0.0, P(4096), P(4096), None) == 1
+    assert tok(P(4096 + 2), 1, 8, 64, 64, P(4096), None, P(4096), P(4096), 4, 1e-4, P(4096), P(4096), None) == 3
     assert fb.fopd_topk_workspace_bytes(163894, 64, 64) == fb.fopd_workspace_bytes(163894, 64) + 2 * 163894 * 64 * 4
 
 

@@ -57,8 +57,9 @@ def _call(w, buf, k, hp, gs, dlogits=None, stale=True, logits=None):
     fb.fopd_loss_fwd_bwd_topk_teacher(
         w["logits"] if logits is None else logits, buf.dt, w["T"], w["V"], w["ld"], w["token_ids"], w["mask"],
         w["behav_logp"], w["list_ids"], w["list_logp"], k, FLOOR, w["teacher_logp"],
-        w["teacher_logp_stale"] if stale else None, w["seq_lens"], w["lag"], w["B"], hp, gs, buf.loss, buf.freshness,
-        buf.weights, buf.logp, buf.token_loss, buf.dlogits if dlogits is None else dlogits, buf.workspace)
+        w["teacher_logp_stale"] if stale else None, w["seq_lens"], w["lag"], w["B"], hp, None, None, None, 0, None, None,
+        gs, buf.loss, buf.freshness, buf.weights, buf.logp, buf.token_loss,
+        buf.dlogits if dlogits is None else dlogits, buf.workspace)
 
 
 def _oracle(w, hp, gs, stale=True, rows=None, n_samples=None):
@@ -236,7 +237,7 @@ def test_topk_teacher_listing_every_token_is_the_full_teacher_call():
     buf = _Buffers(T, V, B, k, "f32", V)
     fb.fopd_loss_fwd_bwd_topk_teacher(w["logits"], buf.dt, T, V, V, w["token_ids"], w["mask"], w["behav_logp"],
                                       w["list_ids"], w["list_logp"], k, 1e-6, None, None, w["seq_lens"], w["lag"], B, hp,
-                                      gs, buf.loss, buf.freshness, buf.weights, buf.logp, buf.token_loss, buf.dlogits,
+                                      None, None, None, 0, None, None, gs, buf.loss, buf.freshness, buf.weights, buf.logp, buf.token_loss, buf.dlogits,
                                       buf.workspace)
     buf.ok()
     other = _Buffers(T, V, B, 1, "f32", V)
@@ -324,3 +325,65 @@ def test_topk_teacher_replay_from_a_hip_graph():
         assert torch.equal(cap.dlogits, eager.dlogits) and torch.equal(cap.loss, eager.loss)
         assert torch.equal(cap.token_loss, eager.token_loss) and torch.equal(cap.weights, eager.weights)
     cap.ok()
+
+
+@pytest.mark.parametrize("split", [None, (0.3, 0.3)])
+def test_topk_teacher_chunked_flow(split):
+    """The long-horizon flow: per chunk log-probs and token loss, scores once over the O(T) arrays, then the gradient
+    per chunk with the scores passed in.  Chunks of 16 rows cut the samples.  Against the oracle (scores, loss as the
+    sum of the chunks' shares, every gradient row) and against the whole-batch call (same kernels: token loss and
+    log-probs bit-identical; the gradient up to the last place, the whole call keeping its scores in fp64)."""
+    _say("chunked flow, aligned_split=%s" % (split,))
+    k, rows = 20, 16
+    extra = {} if split is None else dict(aligned_split=split)
+    w = wl.generate("tooluse", DEV, seed=65, B=5, turns=2, obs_lo=1, obs_hi=4, resp_lo=3, resp_hi=9, V=12000,
+                    dtype="bf16", boost=4, lag_lo=0, lag_hi=20, row_block=32, teacher_list=(k, 0.6), **extra)
+    T, V, B, ld = w["T"], w["V"], w["B"], w["ld"]
+    assert T > 3 * rows
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 0.9
+    ref = _oracle(w, hp, gs)
+    whole = _Buffers(T, V, B, k, "bf16", ld)
+    _call(w, whole, k, hp, gs)
+    whole.ok()
+    f32 = dict(dtype=torch.float32, device=DEV)
+    logp, lse, tl = torch.empty(T, **f32), torch.empty(T, **f32), torch.empty(T, **f32)
+    ch = _Buffers(rows, V, B, k, "bf16", ld)
+    for a in range(0, T, rows):
+        b = min(a + rows, T)
+        fb.fopd_token_logprobs(w["logits"][a:b], ch.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b], logp[a:b],
+                               lse[a:b], None, None, ch.workspace)
+        fb.fopd_topk_token_loss(w["logits"][a:b], ch.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b],
+                                w["list_ids"][a:b], w["list_logp"][a:b], k, FLOOR, lse[a:b], tl[a:b])
+    ch.ok()
+    assert torch.equal(tl, whole.token_loss) and torch.equal(logp, whole.logp)
+    sc = _Buffers(T, V, B, 1, "bf16", ld)
+    fresh = torch.empty(B, **f32)
+    n_train = torch.empty(B, dtype=torch.int32, device=DEV)
+    n_roll = torch.empty(B, dtype=torch.int32, device=DEV)
+    fb.fopd_freshness_score(logp, w["behav_logp"], None, tl, w["teacher_logp"], w["teacher_logp_stale"], w["mask"],
+                            w["seq_lens"], w["lag"], T, B, hp, None, n_train, n_roll, None, None, None, None, None, fresh,
+                            None, sc.workspace)
+    sc.ok()
+    assert_close("freshness", np64(fresh), ref["freshness"], rtol=1e-5)
+    out = torch.full((T, ld), 7.0, dtype=torch.bfloat16, device=DEV)
+    total, weights = 0.0, torch.empty(B, **f32)
+    for a in range(0, T, rows):
+        b = min(a + rows, T)
+        fb.fopd_loss_fwd_bwd_topk_teacher(
+            w["logits"][a:b], ch.dt, b - a, V, ld, w["token_ids"][a:b], w["mask"][a:b], w["behav_logp"][a:b],
+            w["list_ids"][a:b], w["list_logp"][a:b], k, FLOOR, None, None, w["seq_lens"], w["lag"], B, hp, fresh, n_train,
+            n_roll, a, lse[a:b], logp[a:b], gs, ch.loss, None, weights, None, None, out[a:b], ch.workspace)
+        total += float(ch.loss)
+    ch.ok()
+    assert abs(total - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12, (total, ref["loss"])
+    assert_close("weights", np64(weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    sample_of_row = np.repeat(np.arange(B), np64(w["seq_lens"]).astype(np.int64))
+    _check_rows(np64(out)[:, :V], w, ref, list(range(T)), hp, gs, B, sample_of_row)
+    a64, b64 = np64(out)[:, :V], np64(whole.dlogits)[:, :V]
+    assert np.all(np.abs(a64 - b64) <= orc.bf16_ulp(b64) + 1e-30)      # fp32 against fp64 scores: the last place
+    # a chunk call without its slices, or a whole call with one, is refused
+    with pytest.raises(fb.FopdError):
+        fb.fopd_loss_fwd_bwd_topk_teacher(
+            w["logits"][:rows], ch.dt, rows, V, ld, w["token_ids"][:rows], w["mask"][:rows], w["behav_logp"][:rows],
+            w["list_ids"][:rows], w["list_logp"][:rows], k, FLOOR, None, None, w["seq_lens"], w["lag"], B, hp, fresh,
+            n_train, n_roll, 0, None, logp[:rows], gs, ch.loss, None, None, None, None, out[:rows], ch.workspace)
