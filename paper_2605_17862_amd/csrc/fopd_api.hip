@@ -181,6 +181,7 @@ struct ScopedTimer {
 struct Options {
   int k14_threads = 256;          // lanes per row in the two-pass-per-row kernel
   int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
+  int k14_regs_grid = 0;          // workgroups of the row-in-registers kernel; 0 = one per compute unit
   int k14_regs = 1;               // 1: rows that fit (16-byte vectors <= 1024 x 19) are held in registers between the passes
 } g_opt;
 
@@ -317,7 +318,7 @@ fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t
   const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
   if (opt.k14_regs != 0 && nvec <= static_cast<int64_t>(kRegRowThreads) * kRegRowVectors && nvec > 2 * kRegRowThreads) {
     // one resident workgroup per compute unit, each walking rows in steps of the grid
-    const int64_t cus = compute_units();
+    const int64_t cus = (opt.k14_regs_grid > 0) ? opt.k14_regs_grid : compute_units();
     const dim3 grid(static_cast<unsigned>(T < cus ? T : cus)), block(kRegRowThreads);
     if (dt == FOPD_BF16)
       fopd_k14_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(
@@ -1274,6 +1275,11 @@ fopd_status fopd_set_option(const char* name, int value) {
   if (key == "k14_regs") {
     if (value != 0 && value != 1) return FOPD_EINVAL;
     g_opt.k14_regs = value;
+    return FOPD_OK;
+  }
+  if (key == "k14_regs_grid") {
+    if (value < 0 || value > 4096) return FOPD_EINVAL;
+    g_opt.k14_regs_grid = value;
     return FOPD_OK;
   }
   if (key == "k14_rows_per_cu") {

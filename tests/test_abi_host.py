@@ -217,8 +217,15 @@ def test_set_option_checks_names_and_values():
     assert lib.fopd_set_option(b"k14_threads", 300) == 1
     assert lib.fopd_set_option(b"k14_rows_per_cu", 2) == 0
     assert lib.fopd_set_option(b"k14_rows_per_cu", 0) == 1
+    assert lib.fopd_set_option(b"k14_regs_grid", 512) == 0
+    assert lib.fopd_set_option(b"k14_regs_grid", -1) == 1
+    assert lib.fopd_set_option(b"k14_regs_grid", 5000) == 1
     assert lib.fopd_set_option(b"no_such_option", 1) == 1
     assert lib.fopd_set_option(None, 1) == 1
+    # back to the defaults: the options are process-wide
+    assert lib.fopd_set_option(b"k14_threads", 256) == 0
+    assert lib.fopd_set_option(b"k14_rows_per_cu", 6) == 0
+    assert lib.fopd_set_option(b"k14_regs_grid", 0) == 0
 
 
 def test_header_is_plain_c(tmp_path):
