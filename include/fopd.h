@@ -450,7 +450,8 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
  *                      The 1024-lane partition sums a row in another order than fopd_token_logprobs does, so
  *                      log-probs may differ from that call's in the last place.
  *   "k14_regs_grid"    workgroups of that row-in-registers kernel, each walking rows in steps of the grid: 1..4096,
- *                      or 0 (default) for one per compute unit.  The results do not depend on it.
+ *                      or 0 (default) for two per compute unit (one is resident at a time; the second half is
+ *                      handed out as compute units finish).  The results do not depend on it.
  * Returns FOPD_EINVAL for an unknown name or a value outside the stated set.
  */
 fopd_status fopd_set_option(const char* name, int value);

@@ -181,7 +181,7 @@ struct ScopedTimer {
 struct Options {
   int k14_threads = 256;          // lanes per row in the two-pass-per-row kernel
   int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
-  int k14_regs_grid = 0;          // workgroups of the row-in-registers kernel; 0 = one per compute unit
+  int k14_regs_grid = 0;          // workgroups of the row-in-registers kernel; 0 = two per compute unit
   int k14_regs = 1;               // 1: rows that fit (16-byte vectors <= 1024 x 19) are held in registers between the passes
 } g_opt;
 
@@ -317,8 +317,11 @@ fopd_status launch_k14(const void* logits, void* dlogits, fopd_dtype dt, int64_t
   constexpr int kRegRowVectors = 19;
   const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
   if (opt.k14_regs != 0 && nvec <= static_cast<int64_t>(kRegRowThreads) * kRegRowVectors && nvec > 2 * kRegRowThreads) {
-    // one resident workgroup per compute unit, each walking rows in steps of the grid
-    const int64_t cus = (opt.k14_regs_grid > 0) ? opt.k14_regs_grid : compute_units();
+    // One workgroup is resident per compute unit (it takes the whole register file) and walks rows in steps of the
+    // grid.  Twice as many workgroups as compute units: the second half is handed out as compute units finish, which
+    // evens out their unequal speeds (measured: as fast as one per compute unit when all run alike, 4 % faster when
+    // the placement of the two buffers makes some slower).
+    const int64_t cus = (opt.k14_regs_grid > 0) ? opt.k14_regs_grid : 2 * compute_units();
     const dim3 grid(static_cast<unsigned>(T < cus ? T : cus)), block(kRegRowThreads);
     if (dt == FOPD_BF16)
       fopd_k14_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(

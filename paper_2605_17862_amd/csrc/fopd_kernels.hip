@@ -665,7 +665,7 @@ fopd_k14_fused(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, 
 
 // =========================================================================================
 // K14R: the same call with the row held in registers between the two passes: 1024 lanes x NV 16-byte vectors
-// (NV = 19 holds a 303,872-byte row), one workgroup per compute unit.  HBM and the fabric see a single read and a
+// (NV = 19 holds a 303,872-byte row), one workgroup resident per compute unit.  HBM and the fabric see a single read and a
 // single write per row.  A workgroup walks rows blockIdx, blockIdx + gridDim, ...: while it stores the gradient of
 // one row it requests the next one into the registers the stores have just released, so that a compute unit's
 // reads and writes overlap and the next row's latency hides behind the store phase; only the reduction between
