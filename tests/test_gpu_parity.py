@@ -752,6 +752,16 @@ def test_row_in_registers_kernel_walks_many_rows_per_workgroup(dtype, V, seed):
     wrow = np.repeat(np64(regs.weights), np64(w["seq_lens"]).astype(np.int64))
     dead = (np64(w["mask"]) == 0) | (wrow == 0.0)
     assert dead.any() and not np.any(x[dead])
+    # the number of workgroups that share the rows does not change a bit of the result
+    try:
+        for grid in (1, 7, 4096):
+            fb.fopd_set_option("k14_regs_grid", grid)
+            again = _pass_for(w)
+            call(again)
+            assert torch.equal(again.dlogits, regs.dlogits) and torch.equal(again.logp, regs.logp), grid
+            assert torch.equal(again.loss, regs.loss) and torch.equal(again.weights, regs.weights), grid
+    finally:
+        fb.fopd_set_option("k14_regs_grid", 0)
 
 
 def test_replay_of_the_row_in_registers_kernel_from_a_hip_graph():
