@@ -601,6 +601,25 @@ def fopd_loss_fwd_bwd_topk_teacher(logits, token_ids, mask, behav_logp, topk_ids
     return res
 
 
+def lm_head_loss_fwd_bwd_topk_teacher(hidden, weight, token_ids, mask, behav_logp, topk_ids, topk_logp, rest_floor,
+                                      teacher_logp, teacher_logp_stale, seq_lens, lag, alpha, beta, xi, lam,
+                                      grad_scale=1.0):
+    """fopd_loss_fwd_bwd_topk_teacher on logits that are the projection z = hidden . weight^T and are never kept
+    (every step of Algorithm 1, the scores included), with the gradient carried through the projection as in
+    lm_head_loss_fwd_bwd: the rows dL/dz are rounded to bfloat16 before the two contractions ("dhidden",
+    "dweight"); "dhidden_exact", "dweight_exact" contract the unrounded rows."""
+    hidden = np.asarray(hidden, dtype=np.float64)
+    weight = np.asarray(weight, dtype=np.float64)
+    z = lm_head_logits(hidden, weight)
+    res = fopd_loss_fwd_bwd_topk_teacher(z, token_ids, mask, behav_logp, topk_ids, topk_logp, rest_floor,
+                                         teacher_logp, teacher_logp_stale, seq_lens, lag, alpha, beta, xi, lam,
+                                         grad_scale=grad_scale, out_dtype="bf16", want_dlogits=True)
+    g, gb = res["dlogits_exact"], res["dlogits"]
+    res.update(logits=z, dhidden=np.matmul(gb, weight), dweight=np.matmul(gb.T, hidden),
+               dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden))
+    return res
+
+
 def refresh_decision(agg, kappa_f, kappa_roll, kappa_sup, step, last_refresh_step, min_interval):
     """Adaptive refresh test (Sec. 4.2 refresh condition; App. B rate limit).  Returns (refresh, reasons):
     reasons lists which of "f", "roll", "sup" hold; refresh is True when any holds and at least

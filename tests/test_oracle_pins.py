@@ -1220,3 +1220,77 @@ def test_topk_teacher_pass_by_finite_differences_and_per_sample_means():
     w = res["weights"]
     want = sum(w[i] * (res["ell"][i] + lam * res["D_roll"][i]) for i in range(B)) / B
     assert abs(res["loss"] - want) < 1e-15
+
+
+def test_projection_with_listed_teacher_by_finite_differences_and_identity_projection():
+    """The listed-teacher pass on projected logits: dL/dhidden and dL/dweight by central differences of the
+    surrogate through the projection (weights frozen; T, d, V all different; two aligned sets; the token loss
+    re-typed from scipy's softmax and explicit event sums), and the identity projection, under which the hidden
+    states are the logits and dL/dhidden must be the stored-logits call's gradient rows."""
+    c = _projection_case(8)
+    rng = _rng(81)
+    T, d = c["H"].shape
+    V = c["W"].shape[0]
+    k, floor = 3, 1e-3
+    zq = c["H"] @ c["W"].T + rng.normal(0, 0.7, size=(T, V))
+    logq_all = scipy.special.log_softmax(zq, axis=1)
+    ids = np.argsort(-logq_all, axis=1)[:, :k].astype(np.int32)
+    ids[2, 1] = V + 3                                   # an unused slot
+    lq_list = np.take_along_axis(logq_all, np.minimum(ids, V - 1), axis=1)
+    alpha, beta, xi, lam, g = 0.5, 0.0, 0.01, 0.7, 1.3
+    res = orc.lm_head_loss_fwd_bwd_topk_teacher(c["H"], c["W"], c["y"], c["mask"], c["lb"], ids, lq_list, floor, None,
+                                                None, c["seq"], c["lag"], alpha, beta, xi, lam, g)
+    wts, B = res["weights"], len(c["seq"])
+    cu, n, nr = res["cu_seqlens"], res["n_train"], res["n_roll"]
+    assert np.all(wts > 0) and list(n) != list(nr)
+
+    def token_loss(zrow, t):
+        p = scipy.special.softmax(zrow)
+        listed = [int(u) for u in ids[t] if 0 <= u < V]
+        tot, q_in = 0.0, 0.0
+        for j, u in enumerate(ids[t]):
+            if 0 <= u < V:
+                tot += p[u] * (math.log(p[u]) - lq_list[t, j])
+                q_in += math.exp(lq_list[t, j])
+        p_rest = sum(p[u] for u in range(V) if u not in listed)
+        return tot + p_rest * (math.log(p_rest) - math.log(max(1.0 - q_in, floor)))
+
+    def surrogate(H, W):
+        z = H @ W.T
+        lpx = scipy.special.log_softmax(z, axis=1)[np.arange(T), c["y"]]
+        tot = 0.0
+        for i in range(B):
+            for t in range(int(cu[i]), int(cu[i + 1])):
+                m = int(c["mask"][t])
+                if m != 0 and m != 2:
+                    tot += g * wts[i] / (B * int(n[i])) * token_loss(z[t], t)
+                if m != 0 and m != 3:
+                    dlt = lpx[t] - c["lb"][t]
+                    tot += g * wts[i] / (B * int(nr[i])) * lam * (math.exp(dlt) * dlt - math.exp(dlt) + 1.0)
+        return tot
+
+    h = 1e-6
+    for (t, j) in itertools.product(range(T), range(d)):
+        Hp, Hm = c["H"].copy(), c["H"].copy()
+        Hp[t, j] += h
+        Hm[t, j] -= h
+        fd = (surrogate(Hp, c["W"]) - surrogate(Hm, c["W"])) / (2 * h)
+        assert abs(fd - res["dhidden_exact"][t, j]) <= 1e-8 + 1e-6 * abs(fd), (t, j)
+    for (v, j) in itertools.product(range(V), range(d)):
+        Wp, Wm = c["W"].copy(), c["W"].copy()
+        Wp[v, j] += h
+        Wm[v, j] -= h
+        fd = (surrogate(c["H"], Wp) - surrogate(c["H"], Wm)) / (2 * h)
+        assert abs(fd - res["dweight_exact"][v, j]) <= 1e-8 + 1e-6 * abs(fd), (v, j)
+    assert not np.any(res["dhidden_exact"][4])                          # row 4 is in neither set
+    # identity projection: hidden states are the logits
+    z = c["H"] @ c["W"].T
+    eye = np.eye(V)
+    ident = orc.lm_head_loss_fwd_bwd_topk_teacher(z, eye, c["y"], c["mask"], c["lb"], ids, lq_list, floor, None, None,
+                                                  c["seq"], c["lag"], alpha, beta, xi, lam, g)
+    stored = orc.fopd_loss_fwd_bwd_topk_teacher(z, c["y"], c["mask"], c["lb"], ids, lq_list, floor, None, None, c["seq"],
+                                                c["lag"], alpha, beta, xi, lam, grad_scale=g, out_dtype="bf16")
+    np.testing.assert_array_equal(ident["dhidden"], stored["dlogits"])              # rounded once, bit for bit
+    np.testing.assert_allclose(ident["dhidden_exact"], stored["dlogits_exact"], atol=1e-15)
+    np.testing.assert_allclose(ident["dweight_exact"], stored["dlogits_exact"].T @ z, atol=1e-13)
+    assert abs(ident["loss"] - stored["loss"]) < 1e-15

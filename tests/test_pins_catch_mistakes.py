@@ -76,6 +76,11 @@ MISTAKES = {
     "listed-token teacher: supervision drift kept without the stale array": (
         "    if teacher_logp is None or teacher_logp_stale is None:\n        k_sup = np.zeros(T)",
         "    if teacher_logp is None:\n        k_sup = np.zeros(T)\n    elif teacher_logp_stale is None:\n        k_sup = kl_estimator(np.asarray(teacher_logp, dtype=np.float64))"),
+    "listed-token teacher through the projection: rows contracted unrounded": (
+        'g, gb = res["dlogits_exact"], res["dlogits"]', 'g, gb = res["dlogits_exact"], res["dlogits_exact"]'),
+    "listed-token teacher through the projection: weight gradient contracts over the wrong axis": (
+        "               dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden))",
+        "               dhidden_exact=np.matmul(g, weight), dweight_exact=np.matmul(g.T, hidden)[::-1])"),
     "one-hot not subtracted": ("    g[y] -= 1.0\n    return c_t * g", "    return c_t * g"),
     "log-sum-exp forgets the shift": ("return float(mx + np.log(np.sum(np.exp(z - mx))))",
                                       "return float(np.log(np.sum(np.exp(z - mx))))"),
