@@ -275,7 +275,7 @@ def bench_lm_head(args, torch, fb, wl, steps=None):
                      "traffic": None, "flops_per_launch": flops, "avg_ms": k7_s * 1e3}}
 
 
-def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
+def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, with_listed=False):
     """Result record for fopd_lm_head_loss_fwd_bwd: loss, dL/dhidden and dL/dweight from hidden states (d = 4096),
     the [V, d] projection and scores computed beforehand, on the rows, mask and lags of the workload; the
     logits exist only as one chunk of `rows_chunk` rows at a time."""
@@ -285,7 +285,8 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
     seq_lens, mask = wl.structure_only(args.workload, seed=0)
     lag = np.random.RandomState(0).randint(0, 5, size=len(seq_lens)).astype(np.int32)
     T, d, V, B = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"]), len(seq_lens)
-    w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, "cuda:0", seed=0), seq_lens, lag, seed=0)
+    w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, "cuda:0", seed=0), seq_lens, lag, seed=0,
+                              teacher_list=(args.list_k, 0.5) if with_listed else None)
     w["mask"] = torch.from_numpy(mask).to("cuda:0")
 
     def aligned(nbytes):
@@ -348,6 +349,28 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
         st, flags = fb.fopd_workspace_status(ws)
         if st != 0:
             sys.exit("device flags set: %d" % flags)
+    # the same with the teacher stored as k tokens per row (distribution-level loss; scores formed inside)
+    listed = None
+    if with_listed and int(seq_lens.max()) <= rows_chunk:
+        k = args.list_k
+        del ws
+        wsl = aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k))
+
+        def step_listed():
+            fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+                w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"], w["behav_logp"], w["list_ids"],
+                w["list_logp"], k, 1e-4, None, None, w["seq_lens"], w["lag"], B, hp, seq_lens, 1.0, rows_chunk, loss,
+                fresh, weights, logp, lse, None, dh, d, dw, d, 0, wsl)
+        step_listed()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(steps):
+            step_listed()
+        torch.cuda.synchronize()
+        listed = (time.perf_counter() - t2) / steps * 1e3
+        st, flags = fb.fopd_workspace_status(wsl)
+        if st != 0:
+            sys.exit("device flags set: %d" % flags)
     n_chunks = (T + rows_chunk - 1) // rows_chunk
     ldz = (V + 63) // 64 * 64
     rp = sum(((min(rows_chunk, T - a) + 63) // 64) * 64 for a in range(0, T, rows_chunk))
@@ -381,7 +404,11 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None):
         "scores_formed_inside": None if inside is None else {
             "call": "fopd_lm_head_loss_fwd_bwd with freshness_in = NULL (chunks of whole samples; scoring, loss and both "
                     "gradients with one projection per step)",
-            "ms_per_call": inside, "tokens/s": int(((mask != 0) & (mask != 2)).sum()) / (inside * 1e-3)}}
+            "ms_per_call": inside, "tokens/s": int(((mask != 0) & (mask != 2)).sum()) / (inside * 1e-3)},
+        "listed_teacher": None if listed is None else {
+            "call": "fopd_lm_head_loss_fwd_bwd_topk_teacher (teacher stored as %d tokens per row; chunks of whole samples, "
+                    "one projection per step)" % args.list_k,
+            "ms_per_call": listed, "tokens/s": int(((mask != 0) & (mask != 2)).sum()) / (listed * 1e-3)}}
 
 
 def main():
@@ -425,7 +452,7 @@ def main():
         print(json.dumps(bench_lm_head(args, torch, fb, wl)))
         return
     if args.variant == "lm_head_loss":
-        print(json.dumps(bench_lm_head_loss(args, torch, fb, wl, hp)))
+        print(json.dumps(bench_lm_head_loss(args, torch, fb, wl, hp, with_listed=True)))
         return
     w = wl.generate(args.workload, "cuda:0", seed=0)
     T, V, B = w["T"], w["V"], w["B"]

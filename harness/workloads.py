@@ -228,11 +228,14 @@ def generate_lm_head(T, d, V, device="cpu", seed=0, logit_sigma=3.0, masked_ever
     return dict(T=T, d=d, V=V, ldh=ldh, ldw=ldw, hidden=hidden, weight=weight, token_ids=token_ids, mask=mask)
 
 
-def attach_loss_inputs(h, seq_lens, lag, seed=0, behav_sigma=0.05, teacher_mu=-0.2, teacher_sigma=0.4, row_block=2048):
+def attach_loss_inputs(h, seq_lens, lag, seed=0, behav_sigma=0.05, teacher_mu=-0.2, teacher_sigma=0.4, row_block=2048,
+                       teacher_list=None):
     """Adds to a generate_lm_head() dict what the loss pass needs besides hidden states and the projection:
     seq_lens / lag (given, numpy int32; sum(seq_lens) == T) and the stored log-probabilities
     behav_logp = min(lp + behav_sigma * lag_i * N(0,1), 0), teacher_logp = min(lp + N(teacher_mu, teacher_sigma^2), 0),
-    where lp is the tensor library's log_softmax of the projected row at the drawn token (input preparation)."""
+    where lp is the tensor library's log_softmax of the projected row at the drawn token (input preparation).
+    teacher_list=(k, s) also adds `list_ids`, `list_logp` [T, k]: the k most likely tokens of a teacher whose logits
+    are the projected row + s * N(0, 1) per entry, and their log-probabilities."""
     dev = h["hidden"].device
     T, d, V = h["T"], h["d"], h["V"]
     seq_lens = np.asarray(seq_lens, dtype=np.int32)
@@ -241,6 +244,12 @@ def attach_loss_inputs(h, seq_lens, lag, seed=0, behav_sigma=0.05, teacher_mu=-0
     gen = torch.Generator(device=dev)
     gen.manual_seed(seed * 1000003 + 41)
     ref = torch.empty(T, dtype=torch.float32, device=dev)
+    list_ids = list_logp = None
+    if teacher_list is not None:
+        list_ids = torch.empty(T, int(teacher_list[0]), dtype=torch.int32, device=dev)
+        list_logp = torch.empty(T, int(teacher_list[0]), dtype=torch.float32, device=dev)
+        gen_list = torch.Generator(device=dev)
+        gen_list.manual_seed(seed * 1000003 + 43)
     wt = h["weight"][:, :d].float().t().contiguous() if dev.type == "cpu" else None
     for a in range(0, T, row_block):
         b = min(a + row_block, T)
@@ -249,6 +258,12 @@ def attach_loss_inputs(h, seq_lens, lag, seed=0, behav_sigma=0.05, teacher_mu=-0
         else:
             z = (h["hidden"][a:b, :d] @ h["weight"][:, :d].t()).float()
         ref[a:b] = torch.log_softmax(z, dim=1).gather(1, h["token_ids"][a:b].long()[:, None])[:, 0]
+        if teacher_list is not None:
+            zq = z + float(teacher_list[1]) * torch.randn(b - a, V, generator=gen_list, device=dev)
+            top = torch.topk(zq, int(teacher_list[0]), dim=1)
+            list_ids[a:b] = top.indices.to(torch.int32)
+            list_logp[a:b] = top.values - torch.logsumexp(zq, dim=1, keepdim=True)
+            del zq, top
         del z
     per_tok_lag = torch.from_numpy(np.repeat(lag, seq_lens).astype(np.float32)).to(dev)
     n1 = torch.randn(T, generator=gen, device=dev)
@@ -257,5 +272,6 @@ def attach_loss_inputs(h, seq_lens, lag, seed=0, behav_sigma=0.05, teacher_mu=-0
     out.update(B=len(seq_lens), seq_lens=torch.from_numpy(seq_lens).to(dev), lag=torch.from_numpy(lag).to(dev),
                seq_lens_host=seq_lens, lag_host=lag,
                behav_logp=torch.clamp(ref + behav_sigma * per_tok_lag * n1, max=0.0),
-               teacher_logp=torch.clamp(ref + teacher_mu + teacher_sigma * n2, max=0.0))
+               teacher_logp=torch.clamp(ref + teacher_mu + teacher_sigma * n2, max=0.0), list_ids=list_ids,
+               list_logp=list_logp)
     return out

@@ -528,6 +528,32 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
                                       int accumulate_dweight, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same pass through the projection with the distribution-level token loss against a teacher stored as k tokens
+ * per row (the loss, coarsening and gradient of fopd_loss_fwd_bwd_topk_teacher, on logits that exist only chunk by
+ * chunk): per chunk of whole samples the logits are formed in fp32 scratch, the log-sum-exp kernel and the listed
+ * terms run on them, the samples' scores follow at once (the freshness_in == NULL mode of
+ * fopd_lm_head_loss_fwd_bwd: one projection per step), the gradient rows are written as bf16 with one coefficient
+ * per row and corrected at the k listed tokens and the sampled one, and the two contractions fold them into dhidden
+ * and dweight.
+ *   list_ids, list_logp [T, k], k, rest_floor     as in fopd_loss_fwd_bwd_topk_teacher
+ *   teacher_logp, teacher_logp_stale [T] or NULL  the sampled token's teacher log-probabilities, for D^sup only
+ *                                                 (D^sup = 0 unless both are given; the stale one alone is FOPD_EINVAL)
+ *   seq_lens_host [B] int32 (HOST memory, the values of seq_lens); every sample at most rows_chunk rows long
+ *   token_loss [T] f32 out or NULL (l_t; 0 outside U^sup); the other arguments as in fopd_lm_head_loss_fwd_bwd
+ *   workspace  fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k) bytes
+ */
+size_t fopd_lm_head_loss_topk_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk,
+                                              int32_t k);
+fopd_status fopd_lm_head_loss_fwd_bwd_topk_teacher(
+    const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T, int64_t V, int64_t d,
+    const int32_t* token_ids, const uint8_t* mask, const float* behav_logp, const int32_t* list_ids,
+    const float* list_logp, int32_t k, float rest_floor, const float* teacher_logp, const float* teacher_logp_stale,
+    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const int32_t* seq_lens_host,
+    float grad_scale, int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse,
+    float* token_loss, float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels
  * is bracketed by HIP events on the launch stream (process-wide state behind the library's mutex; the
  * events are created on first use, so do not enable it around code that may not allocate).

@@ -23,6 +23,7 @@ SYMBOLS = (
     "fopd_topk_workspace_bytes", "fopd_topk_token_loss", "fopd_loss_fwd_bwd_topk_teacher",
     "fopd_lm_head_workspace_bytes", "fopd_lm_head_token_logprobs",
     "fopd_lm_head_loss_workspace_bytes", "fopd_lm_head_loss_fwd_bwd",
+    "fopd_lm_head_loss_topk_workspace_bytes", "fopd_lm_head_loss_fwd_bwd_topk_teacher",
 )
 
 
@@ -90,6 +91,12 @@ def load_library():
     lib.fopd_lm_head_loss_fwd_bwd.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32, Hparams,
                                               vp, vp, vp, vp, f32, i64, vp, vp, vp, vp, vp, vp, i64, vp, i64,
                                               ctypes.c_int, vp, sz, vp]
+    lib.fopd_lm_head_loss_topk_workspace_bytes.restype = sz
+    lib.fopd_lm_head_loss_topk_workspace_bytes.argtypes = [i64, i64, i64, i32, i64, i32]
+    lib.fopd_lm_head_loss_fwd_bwd_topk_teacher.restype = ctypes.c_int
+    lib.fopd_lm_head_loss_fwd_bwd_topk_teacher.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, i32, f32,
+                                                           vp, vp, vp, vp, i32, Hparams, vp, f32, i64, vp, vp, vp, vp,
+                                                           vp, vp, vp, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -260,6 +267,48 @@ def fopd_lm_head_loss_fwd_bwd(hidden, ldh, weight, ldw, T, V, d, token_ids, mask
         _ptr(dhidden, f32, "dhidden"), int(lddh), _ptr(dweight, f32, "dweight"), int(lddw),
         int(bool(accumulate_dweight)), p, n, _stream(stream))
     _check(st, "fopd_lm_head_loss_fwd_bwd")
+
+
+def _host_lengths(seq_lens_host, B):
+    import numpy as np
+    import torch
+    if isinstance(seq_lens_host, torch.Tensor):
+        if seq_lens_host.is_cuda:
+            raise TypeError("seq_lens_host must be in host memory")
+        seq_lens_host = seq_lens_host.numpy()
+    host = np.ascontiguousarray(np.asarray(seq_lens_host), dtype=np.int32)
+    if host.shape != (int(B),):
+        raise ValueError("seq_lens_host must hold B lengths")
+    return host
+
+
+def fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k):
+    return int(load_library().fopd_lm_head_loss_topk_workspace_bytes(int(T), int(V), int(d), int(B), int(rows_chunk),
+                                                                     int(k)))
+
+
+def fopd_lm_head_loss_fwd_bwd_topk_teacher(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, list_ids,
+                                           list_logp, k, rest_floor, teacher_logp, teacher_logp_stale, seq_lens, lag, B,
+                                           hp, seq_lens_host, grad_scale, rows_chunk, loss, freshness, weights, logp,
+                                           lse, token_loss, dhidden, lddh, dweight, lddw, accumulate_dweight, workspace,
+                                           stream=None):
+    """seq_lens_host: the sample lengths in HOST memory (a CPU int32 tensor, a numpy array or a list)."""
+    import torch
+    f32 = torch.float32
+    p, n = _ws(workspace)
+    host = None if seq_lens_host is None else _host_lengths(seq_lens_host, B)
+    st = load_library().fopd_lm_head_loss_fwd_bwd_topk_teacher(
+        _ptr(hidden, torch.bfloat16, "hidden"), int(ldh), _ptr(weight, torch.bfloat16, "weight"), int(ldw),
+        int(T), int(V), int(d), _ptr(token_ids, torch.int32, "token_ids"), _ptr(mask, torch.uint8, "mask"),
+        _ptr(behav_logp, f32, "behav_logp"), _ptr(list_ids, torch.int32, "list_ids"), _ptr(list_logp, f32, "list_logp"),
+        int(k), float(rest_floor), _ptr(teacher_logp, f32, "teacher_logp"),
+        _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(seq_lens, torch.int32, "seq_lens"),
+        _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), None if host is None else ctypes.c_void_p(host.ctypes.data),
+        float(grad_scale), int(rows_chunk), _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"),
+        _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"),
+        _ptr(token_loss, f32, "token_loss"), _ptr(dhidden, f32, "dhidden"), int(lddh), _ptr(dweight, f32, "dweight"),
+        int(lddw), int(bool(accumulate_dweight)), p, n, _stream(stream))
+    _check(st, "fopd_lm_head_loss_fwd_bwd_topk_teacher")
 
 
 def fopd_flags_status(flags):

@@ -85,8 +85,10 @@ void* g_scratch_ptr[64] = {};
 struct LmLossWorkspace {
   size_t flags = 0, cu = 0, n_train = 0, n_roll = 0, fresh64 = 0, coef = 0, partials = 0, chunk_loss = 0, z = 0, g = 0,
          wt = 0, total = 0;
+  // with a teacher stored as k tokens per row: token loss [T], per-row values and per-slot terms of one chunk
+  size_t token_loss = 0, c2 = 0, g_rest = 0, row_coef = 0, p_list = 0, h_list = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
-  LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk) {
+  LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk, int32_t k = 0) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
     const int64_t t = T < 0 ? 0 : T;
     const int64_t rc = rows_chunk < 64 ? 64 : rows_chunk;
@@ -108,8 +110,27 @@ struct LmLossWorkspace {
     z = Workspace::take(off, r * static_cast<size_t>(ldz) * sizeof(float));
     g = Workspace::take(off, r * static_cast<size_t>(ldz) * 2);
     wt = Workspace::take(off, dd * static_cast<size_t>(ldz) * 2);
+    if (k > 0) {
+      const size_t kk = static_cast<size_t>(k);
+      token_loss = Workspace::take(off, static_cast<size_t>(t) * sizeof(float));
+      c2 = Workspace::take(off, r * sizeof(float));
+      g_rest = Workspace::take(off, r * sizeof(float));
+      row_coef = Workspace::take(off, r * sizeof(float));
+      p_list = Workspace::take(off, r * kk * sizeof(float));
+      h_list = Workspace::take(off, r * kk * sizeof(float));
+    }
     total = off;
   }
+};
+
+// The teacher of the loss pass through the projection when it is stored as k tokens per row.
+struct ListedTeacher {
+  const int32_t* ids = nullptr;
+  const float* logp = nullptr;
+  int32_t k = 0;
+  float rest_floor = 0.f;
+  const float* teacher_logp_stale = nullptr;     // with teacher_logp: the sampled token's, for D^sup
+  float* token_loss = nullptr;                   // [T] out, may be NULL
 };
 
 template <typename P>
@@ -1113,22 +1134,33 @@ static fopd_status launch_transpose(const void* in, int64_t ld_in, int64_t rows,
   return launched();
 }
 
-fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T,
-                                      int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
-                                      const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
-                                      const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
-                                      const int32_t* n_train_in, const int32_t* n_roll_in,
-                                      const int32_t* seq_lens_host, float grad_scale, int64_t rows_chunk, float* loss,
-                                      float* freshness, float* weights, float* logp, float* lse, float* dhidden,
-                                      int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
-                                      void* workspace, size_t workspace_bytes, void* stream) {
+// The loss pass through the projection.  `listed` == nullptr: the sampled-token loss against teacher_logp
+// (fopd_lm_head_loss_fwd_bwd); else the distribution-level loss against a teacher stored as k tokens per row, scores
+// formed inside the call (fopd_lm_head_loss_fwd_bwd_topk_teacher; teacher_logp then only serves D^sup and may be NULL).
+static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T,
+                                     int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
+                                     const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
+                                     const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                     const int32_t* n_train_in, const int32_t* n_roll_in,
+                                     const int32_t* seq_lens_host, float grad_scale, int64_t rows_chunk, float* loss,
+                                     float* freshness, float* weights, float* logp, float* lse, float* dhidden,
+                                     int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
+                                     const ListedTeacher* listed, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
   if (T < 0 || T > 2147483647LL || V <= 0 || V > 2147483647LL - 64 || d <= 0 || d % 64 != 0 || ldh < d || ldw < d ||
       lddh < d || lddw < d || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
     return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
-      teacher_logp == nullptr || seq_lens == nullptr || lag == nullptr || loss == nullptr || logp == nullptr ||
-      lse == nullptr || dhidden == nullptr || dweight == nullptr)
+      (teacher_logp == nullptr && listed == nullptr) || seq_lens == nullptr || lag == nullptr || loss == nullptr ||
+      logp == nullptr || lse == nullptr || dhidden == nullptr || dweight == nullptr)
     return FOPD_EINVAL;
+  if (listed != nullptr) {
+    if (listed->k < 1 || listed->k > 4096) return FOPD_ESHAPE;
+    if (listed->ids == nullptr || listed->logp == nullptr || freshness_in != nullptr) return FOPD_EINVAL;
+    if (listed->teacher_logp_stale != nullptr && teacher_logp == nullptr) return FOPD_EINVAL;
+    if (!(listed->rest_floor > 0.f) || !(listed->rest_floor <= 1.f)) return FOPD_EINVAL;
+  }
+  const int32_t list_k = (listed != nullptr) ? listed->k : 0;
   const bool scored = (freshness_in != nullptr);
   // without scores they are formed inside the call, per chunk: the chunks then follow sample boundaries, which
   // the host must know
@@ -1138,7 +1170,7 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   if (misaligned(hidden, 16) || misaligned(weight, 16) || (ldh * 2) % 16 != 0 || (ldw * 2) % 16 != 0 ||
       misaligned(dhidden, 16) || misaligned(dweight, 16))
     return FOPD_EALIGN;
-  const LmLossWorkspace lay(T, V, d, B, rows_chunk);
+  const LmLossWorkspace lay(T, V, d, B, rows_chunk, list_k);
   if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
 
   // The chunks: [row begin, rows, first sample, one past the last sample].  With scores supplied they are
@@ -1186,6 +1218,16 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   const __bf16* Wm = static_cast<const __bf16*>(weight);
   const int64_t ldz = lay.ldz;
   const double* f64_use = scored ? nullptr : f64;
+  float* tl = nullptr;               // listed teacher: token loss of every row, then this chunk's per-row values
+  float *c2 = nullptr, *g_rest = nullptr, *row_coef = nullptr, *p_list = nullptr, *h_list = nullptr;
+  if (listed != nullptr) {
+    tl = (listed->token_loss != nullptr) ? listed->token_loss : at<float>(workspace, lay.token_loss);
+    c2 = at<float>(workspace, lay.c2);
+    g_rest = at<float>(workspace, lay.g_rest);
+    row_coef = at<float>(workspace, lay.row_coef);
+    p_list = at<float>(workspace, lay.p_list);
+    h_list = at<float>(workspace, lay.h_list);
+  }
 
   fopd_scan_seqlens<<<1, kScanThreads, 0, s>>>(seq_lens, lag, B, T, 0, cu, flags);
   if ((st = launched()) != FOPD_OK) return st;
@@ -1227,17 +1269,35 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     if ((st = launch_k1(Z, FOPD_F32, R, V, ldz, token_ids + a, mask == nullptr ? nullptr : mask + a, logp + a, lse + a,
                         nullptr, nullptr, flags, s)) != FOPD_OK)
       return st;
+    const uint8_t* mask_c = (mask == nullptr) ? nullptr : mask + a;
+    if (listed != nullptr) {
+      // the listed logits of each row are in the chunk's scratch: token loss, G_rest - l_t and the per-slot terms
+      if ((st = launch_topk_terms(Z, FOPD_F32, R, V, ldz, token_ids + a, mask_c, listed->ids + a * list_k,
+                                  listed->logp + a * list_k, list_k, listed->rest_floor, lse + a, tl + a, g_rest, p_list,
+                                  h_list, s)) != FOPD_OK)
+        return st;
+    }
     if (!scored) {
       // the chunk holds whole samples: their scores follow from the log-probs just made
       fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
-          logp, behav_logp, nullptr, nullptr, teacher_logp, nullptr, mask, cu + c.i0, lag + c.i0, T, hp, nullptr, nullptr,
-          nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, f64 + c.i0, nws + c.i0, nrws + c.i0);
+          logp, behav_logp, nullptr, tl, teacher_logp, (listed != nullptr) ? listed->teacher_logp_stale : nullptr, mask,
+          cu + c.i0, lag + c.i0, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+          f64 + c.i0, nws + c.i0, nrws + c.i0);
       if ((st = launched()) != FOPD_OK) return st;
     }
     const int64_t nblk = (R + kStreamThreads - 1) / kStreamThreads;
-    fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-        logp + a, behav_logp + a, teacher_logp + a, mask == nullptr ? nullptr : mask + a, cu, n_use, nr_use, lag, f64_use,
-        freshness_in, R, B, a, hp, grad_scale, coef, partials, flags);
+    if (listed != nullptr) {
+      // c1 (into `coef`), c2 and the chunk's share of the loss; then the stream's coefficient c1 + c2 (G_rest - l_t)
+      fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+          logp + a, tl + a, nullptr, behav_logp + a, mask_c, cu, n_use, nr_use, lag, f64_use, freshness_in, R, B, a, hp,
+          grad_scale, false, coef, c2, partials);
+      if ((st = launched()) != FOPD_OK) return st;
+      fopd_topk_row_coef<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(coef, c2, g_rest, R, row_coef);
+    } else {
+      fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
+          logp + a, behav_logp + a, teacher_logp + a, mask_c, cu, n_use, nr_use, lag, f64_use, freshness_in, R, B, a, hp,
+          grad_scale, coef, partials, flags);
+    }
     if ((st = launched()) != FOPD_OK) return st;
     // (weights and scores of samples whose chunk is still to come are overwritten by the later calls)
     fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi,
@@ -1246,8 +1306,17 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
     {
       ScopedTimer timer(1, s);
       fopd_k4_grad_wide<<<static_cast<unsigned>(R), kGradThreads, 0, s>>>(
-          Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), token_ids + a, lse + a, logp + a, coef);
+          Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), token_ids + a, lse + a, logp + a,
+          (listed != nullptr) ? row_coef : coef);
       if ((st = launched()) != FOPD_OK) return st;
+      if (listed != nullptr) {
+        // the k listed entries of each row and the sampled token's, in the bf16 rows just written
+        const dim3 grid(static_cast<unsigned>((R + kListRows - 1) / kListRows)), block(kListThreads);
+        fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(G, R, static_cast<int>(V), ldz, token_ids + a,
+                                                         listed->ids + a * list_k, list_k, logp + a, coef, c2, g_rest,
+                                                         p_list, h_list);
+        if ((st = launched()) != FOPD_OK) return st;
+      }
     }
     // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
     if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dhidden + a * lddh, lddh, 5, s)) != FOPD_OK) return st;
@@ -1264,6 +1333,47 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
   }
   fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);
   return launched();
+}
+
+fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T,
+                                      int64_t V, int64_t d, const int32_t* token_ids, const uint8_t* mask,
+                                      const float* behav_logp, const float* teacher_logp, const int32_t* seq_lens,
+                                      const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+                                      const int32_t* n_train_in, const int32_t* n_roll_in,
+                                      const int32_t* seq_lens_host, float grad_scale, int64_t rows_chunk, float* loss,
+                                      float* freshness, float* weights, float* logp, float* lse, float* dhidden,
+                                      int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  return lm_head_loss_impl(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, teacher_logp, seq_lens, lag,
+                           B, hp, freshness_in, n_train_in, n_roll_in, seq_lens_host, grad_scale, rows_chunk, loss,
+                           freshness, weights, logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, nullptr,
+                           workspace, workspace_bytes, stream);
+}
+
+size_t fopd_lm_head_loss_topk_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk,
+                                              int32_t k) {
+  return LmLossWorkspace(T, V, d, B, rows_chunk, k < 1 ? 1 : k).total;
+}
+
+fopd_status fopd_lm_head_loss_fwd_bwd_topk_teacher(
+    const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T, int64_t V, int64_t d,
+    const int32_t* token_ids, const uint8_t* mask, const float* behav_logp, const int32_t* list_ids,
+    const float* list_logp, int32_t k, float rest_floor, const float* teacher_logp, const float* teacher_logp_stale,
+    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const int32_t* seq_lens_host,
+    float grad_scale, int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse,
+    float* token_loss, float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
+    void* workspace, size_t workspace_bytes, void* stream) {
+  ListedTeacher listed;
+  listed.ids = list_ids;
+  listed.logp = list_logp;
+  listed.k = k;
+  listed.rest_floor = rest_floor;
+  listed.teacher_logp_stale = teacher_logp_stale;
+  listed.token_loss = token_loss;
+  return lm_head_loss_impl(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, teacher_logp, seq_lens, lag,
+                           B, hp, nullptr, nullptr, nullptr, seq_lens_host, grad_scale, rows_chunk, loss, freshness,
+                           weights, logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, &listed, workspace,
+                           workspace_bytes, stream);
 }
 
 fopd_status fopd_set_option(const char* name, int value) {

@@ -318,3 +318,36 @@ def test_projection_workspace_bytes():
     assert a == b and c > b and a % 256 == 0     # rows are padded to whole 256-token tiles
     assert fb.fopd_lm_head_workspace_bytes(163894) >= 163894 * 32 * 8
     assert fb.fopd_lm_head_workspace_bytes(0) >= 256
+
+
+def _lml_listed(lib, **kw):
+    a = dict(hidden=4096, ldh=64, weight=4096, ldw=64, T=128, V=100, d=64, ids=4096, lb=4096, lids=4096, llq=4096, k=4,
+             floor=1e-4, lq=None, lqs=None, seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), host=[64, 64],
+             chunk=64, loss=4096, lp=4096, lse=4096, dh=8192, dw=8192, ws=4096, wsb=1 << 24)
+    a.update(kw)
+    host = a["host"]
+    keep = (ctypes.c_int32 * len(host))(*host) if host is not None else None
+    return lib.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+        P(a["hidden"]), a["ldh"], P(a["weight"]), a["ldw"], a["T"], a["V"], a["d"], P(a["ids"]), None, P(a["lb"]),
+        P(a["lids"]), P(a["llq"]), a["k"], a["floor"], P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"], a["hp"],
+        None if keep is None else ctypes.cast(keep, ctypes.c_void_p), 1.0, a["chunk"], P(a["loss"]), None, None,
+        P(a["lp"]), P(a["lse"]), None, P(a["dh"]), 64, P(a["dw"]), 64, 0, P(a["ws"]), a["wsb"], None)
+
+
+def test_projection_loss_with_listed_teacher_rejects_bad_arguments_before_launch():
+    lib = fb.load_library()
+    assert _lml_listed(lib, hidden=None) == 1
+    assert _lml_listed(lib, lids=None) == 1
+    assert _lml_listed(lib, llq=None) == 1
+    assert _lml_listed(lib, host=None) == 1                       # whole samples per chunk: the host needs the lengths
+    assert _lml_listed(lib, lqs=4096) == 1                        # the stale array without the current one
+    assert _lml_listed(lib, floor=0.0) == 1
+    assert _lml_listed(lib, k=0) == 2
+    assert _lml_listed(lib, k=4097) == 2
+    assert _lml_listed(lib, chunk=32) == 2
+    assert _lml_listed(lib, host=[100, 28]) == 2                  # a sample longer than a chunk
+    assert _lml_listed(lib, wsb=4096) == 5
+    plain = fb.fopd_lm_head_loss_workspace_bytes(128, 100, 64, 2, 64)
+    listed = fb.fopd_lm_head_loss_topk_workspace_bytes(128, 100, 64, 2, 64, 4)
+    assert listed > plain and listed - plain < 128 * 4 + 64 * 4 * (3 + 2 * 4) + 6 * 256 + 1
+    assert _lml_listed(lib, wsb=listed - 1) == 5

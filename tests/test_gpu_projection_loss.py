@@ -312,3 +312,95 @@ def test_projection_loss_random_shapes_sweep():
         f = _scores_from_the_oracle(w, hp)
         out = _run(w, hp, g, rows_chunk, f, pad_h=pad_h, pad_w=pad_w)
         _compare(w, hp, g, out, f, check_scale=False)
+
+
+# ---------------------------------------------------------------------------------------
+# the same pass with the teacher stored as k tokens per row
+# ---------------------------------------------------------------------------------------
+
+LISTED_CASES = {
+    # T-split, d, V, ldh, ldw, masked_every, rows_chunk, k
+    "ragged": ((90, 130, 80), 128, 1000, 136, 128, 7, 192, 12),
+    "two_samples_per_chunk": ((60, 70, 50, 40), 64, 5003, 64, 72, 0, 128, 5),
+    "full_vocab": ((300, 350, 400), 256, 151936, 256, 256, 9, 512, 64),
+}
+
+
+@pytest.mark.parametrize("name", sorted(LISTED_CASES))
+def test_projection_loss_with_listed_teacher(name):
+    """fopd_lm_head_loss_fwd_bwd_topk_teacher against the oracle's lm_head_loss_fwd_bwd_topk_teacher: log-probs,
+    token loss, scores, weights, loss, and dhidden / dweight within the bound that follows from the tolerance of the
+    gradient rows (each a bf16 value within its limit of the oracle's bf16 row; exact bf16 operands; fp32 sums):
+    |dH - dH_ref| <= (lim + 2^-20 |g|) |W|, likewise for dweight with |H|."""
+    from test_gpu_topk_teacher import coefficient_uncertainties, grad_row_want_and_limit
+    seq, d, V, ldh, ldw, every, rows_chunk, k = LISTED_CASES[name]
+    T, B = sum(seq), len(seq)
+    _say("listed teacher, %s: T=%d d=%d V=%d k=%d chunks of at most %d rows" % (name, T, d, V, k, rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=9, masked_every=every, ldh=ldh, ldw=ldw)
+    lag = [0, 3, 40, 1][:B]                            # the third sample is gated
+    w = wl.attach_loss_inputs(h, seq, lag, seed=9, teacher_list=(k, 0.6))
+    w["list_ids"][1, 0] = -1                            # an unused slot
+    if not bool((w["list_ids"][2] == w["token_ids"][2]).any()):
+        w["list_ids"][2, k // 2] = w["token_ids"][2]    # a listed sampled token
+    hp, g, floor = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.7, 1e-4
+    ws = _aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k))
+    f32 = dict(dtype=torch.float32, device=DEV)
+    out = dict(loss=torch.full((1,), 7.0, **f32), fresh=torch.empty(B, **f32), weights=torch.empty(B, **f32),
+               logp=torch.full((T,), 7.0, **f32), lse=torch.full((T,), 7.0, **f32), tl=torch.full((T,), 7.0, **f32),
+               dh=torch.full((T, d + 8), 7.0, **f32), dw=torch.full((V, d), 7.0, **f32))
+    fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+        w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"], w["behav_logp"], w["list_ids"],
+        w["list_logp"], k, floor, None, None, w["seq_lens"], w["lag"], B, hp, w["seq_lens_host"], g, rows_chunk,
+        out["loss"], out["fresh"], out["weights"], out["logp"], out["lse"], out["tl"], out["dh"], d + 8, out["dw"], d,
+        False, ws)
+    torch.cuda.synchronize()
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    assert bool((out["dh"][:, d:] == 7.0).all())
+    H, W = np64(w["hidden"])[:, :d], np64(w["weight"])[:, :d]
+    mask = np64(w["mask"])
+    ids, lq, y = np64(w["list_ids"]), np64(w["list_logp"]), np64(w["token_ids"])
+    ref = orc.lm_head_loss_fwd_bwd_topk_teacher(H, W, y, mask, np64(w["behav_logp"]), ids, lq, floor, None, None,
+                                                w["seq_lens_host"], w["lag_host"], hp[0], hp[1], hp[2], hp[3], g)
+    assert_close("logp", np64(out["logp"]), ref["logp"], atol=1e-4)
+    assert_close("lse", np64(out["lse"]), ref["lse"], atol=1e-4)
+    assert_close("freshness", np64(out["fresh"]), ref["freshness"], rtol=1e-5)
+    assert_close("weights", np64(out["weights"]), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+    assert abs(float(out["loss"]) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-6 * float(np.mean(ref["weights"])) + 1e-12
+    sample_of_row = np.repeat(np.arange(B), np.asarray(seq))
+    lim = np.zeros((T, V))
+    got_tl = np64(out["tl"])
+    for t in range(T):
+        m, i = int(mask[t]), int(sample_of_row[t])
+        if m == 0:
+            assert got_tl[t] == 0.0
+            continue
+        ell, G = orc.topk_token_loss_row(ref["logits"][t], ids[t], lq[t], floor)
+        listed = np.zeros(V, dtype=bool)
+        listed[[int(u) for u in ids[t] if 0 <= int(u) < V]] = True
+        g_rest = float(G[~listed][0])
+        # (the last term: the projected logits carry the fp32 accumulation of d products, a few 1e-6 on each
+        # listed log-prob)
+        assert abs(got_tl[t] - ell) <= 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0) + 2e-6, (t, got_tl[t], ell)
+        if ref["c1"][t] == 0.0 and ref["c2"][t] == 0.0:
+            continue
+        eps_c1, eps_c2 = coefficient_uncertainties(ref, t, i, m, hp, g, B)
+        # the logits themselves carry the fp32 accumulation of the projection: lse to 1e-4 is what the path states, the
+        # listed probabilities follow it
+        _, lim_row, _ = grad_row_want_and_limit(ref["logits"][t], int(y[t]), ids[t], lq[t], floor, ref["c1"][t],
+                                                ref["c2"][t], eps_c1, eps_c2, ref["lse"][t], "bf16")
+        lim[t] = lim_row + 2.0 ** -20 * np.abs(ref["dlogits"][t])
+    lim_h = lim @ np.abs(W) + 1e-30
+    lim_w = lim.T @ np.abs(H) + 1e-30
+    got_h, got_w = np64(out["dh"])[:, :d], np64(out["dw"])
+    err_h, err_w = np.abs(got_h - ref["dhidden"]), np.abs(got_w - ref["dweight"])
+    rel_h = float(err_h.max() / max(np.abs(ref["dhidden"]).max(), 1e-300))
+    rel_w = float(err_w.max() / max(np.abs(ref["dweight"]).max(), 1e-300))
+    _say("max |err| / max |value|: dhidden %.2e, dweight %.2e; worst err / bound: %.3f, %.3f"
+         % (rel_h, rel_w, float((err_h / lim_h).max()), float((err_w / lim_w).max())))
+    assert np.all(err_h <= lim_h), "dhidden: worst error / bound %.3f" % float((err_h / lim_h).max())
+    assert np.all(err_w <= lim_w), "dweight: worst error / bound %.3f" % float((err_w / lim_w).max())
+    assert rel_h < 2e-3 and rel_w < 2e-3
+    assert np.any(got_h[mask != 0]) and not np.any(got_h[mask == 0])
+    assert ref["weights"][2] == 0.0 and float(out["weights"][2]) == 0.0
+    a2 = sum(seq[:2])
+    assert not bool(out["dh"][a2:a2 + seq[2], :d].any())

@@ -87,38 +87,58 @@ def _token_loss_tolerance(z_row, ids, lq):
     return ell, G, listed, p, p_rest, 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0)
 
 
+def grad_row_want_and_limit(z, y, ids, lq, rest_floor, c1, c2, eps_c1, eps_c2, lse_t, store):
+    """The oracle's gradient row rounded to the storage type, and the per-element limit on |GPU - that|."""
+    exact = orc.dlogits_row_topk(z, y, ids, lq, rest_floor, c1, c2)
+    ell, G = orc.topk_token_loss_row(z, ids, lq, rest_floor)
+    V = z.shape[0]
+    listed = np.zeros(V, dtype=bool)
+    listed[[int(u) for u in ids if 0 <= int(u) < V]] = True
+    p = np.exp(z - orc.row_logsumexp(z))
+    p_rest = float(np.sum(p[~listed]))
+    g_rest = float(G[~listed][0]) if np.any(~listed) and p_rest > 0.0 else 0.0
+    eps_l = 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0)
+    pm = p.copy()
+    pm[y] -= 1.0
+    dG = np.where(listed, 2e-6, 2e-6 + 2e-6 / max(p_rest, 1e-30))
+    floor = np.abs(pm) * eps_c1 + p * (np.abs(G - ell) * eps_c2 + abs(c2) * (dG + eps_l)) + 2.0 ** -126
+    floor[y] += (abs(c1) + eps_c1) * 4.0 * np.spacing(max(abs(lse_t), 1.0))
+    if store == "bf16":
+        want = orc.round_to_bf16(exact)
+        lim = 2.0 * orc.bf16_ulp(want) + floor
+    else:
+        want = orc.round_to_f32(exact)
+        lim = 2e-5 * np.abs(want) + floor
+    return want, lim, listed
+
+
+def coefficient_uncertainties(ref, r, i, m, hp, gs, n_samples):
+    """Absolute uncertainty of c1 and c2 of one row that the tolerances on lp (fp32) and f_i (1e-5) allow."""
+    lam = hp[3]
+    f, wt = ref["freshness"][i], ref["weights"][i]
+    n_sup, n_roll = int(ref["n_train"][i]), int(ref["n_roll"][i])
+    eps_c1 = (abs(gs) / (n_samples * n_roll) * lam * (wt * EPS_A + EPS_F * f * abs(ref["rho"][r] * ref["delta"][r]))
+              if m in (1, 2) and n_roll > 0 else 0.0)
+    eps_c2 = abs(gs) / (n_samples * n_sup) * EPS_F * f if m in (1, 3) and n_sup > 0 else 0.0
+    return eps_c1, eps_c2
+
+
 def _check_rows(got_rows, w, ref, rows, hp, gs, n_samples, sample_of_row, offset=0, z_rows=None):
     """got_rows[k] is the GPU gradient row of global row rows[k]; ref holds oracle arrays indexed by row - offset."""
     V, store = w["V"], w["dtype"]
-    lam = hp[3]
     for k, t in enumerate(rows):
         r = t - offset
         z = np64(w["logits"][t])[:V] if z_rows is None else z_rows[k]
         ids, lq, y = np64(w["list_ids"][t]), np64(w["list_logp"][t]), int(w["token_ids"][t])
         c1, c2 = ref["c1"][r], ref["c2"][r]
         i = sample_of_row[r]
-        f, wt = ref["freshness"][i], ref["weights"][i]
+        f = ref["freshness"][i]
         n_sup, n_roll = int(ref["n_train"][i]), int(ref["n_roll"][i])
         if c1 == 0.0 and c2 == 0.0 and (min(n_sup, n_roll) == 0 or f < hp[2] * (1 - 1e-4) or int(w["mask_host"][t]) == 0):
             assert not np.any(got_rows[k]), "row %d must be exactly zero" % t
             continue
-        exact = orc.dlogits_row_topk(z, y, ids, lq, FLOOR, c1, c2)
-        ell, G, listed, p, p_rest, eps_l = _token_loss_tolerance(z, ids, lq)
-        pm = p.copy()
-        pm[y] -= 1.0
-        m = int(w["mask_host"][t])
-        eps_c1 = (abs(gs) / (n_samples * n_roll) * lam * (wt * EPS_A + EPS_F * f * abs(ref["rho"][r] * ref["delta"][r]))
-                  if m in (1, 2) else 0.0)
-        eps_c2 = abs(gs) / (n_samples * n_sup) * EPS_F * f if m in (1, 3) else 0.0
-        dG = np.where(listed, 2e-6, 2e-6 + 2e-6 / max(p_rest, 1e-30))
-        floor = np.abs(pm) * eps_c1 + p * (np.abs(G - ell) * eps_c2 + abs(c2) * (dG + eps_l)) + 2.0 ** -126
-        floor[y] += (abs(c1) + eps_c1) * 4.0 * np.spacing(max(abs(ref["lse"][r]), 1.0))
-        if store == "bf16":
-            want = orc.round_to_bf16(exact)
-            lim = 2.0 * orc.bf16_ulp(want) + floor
-        else:
-            want = orc.round_to_f32(exact)
-            lim = 2e-5 * np.abs(want) + floor
+        eps_c1, eps_c2 = coefficient_uncertainties(ref, r, i, int(w["mask_host"][t]), hp, gs, n_samples)
+        want, lim, listed = grad_row_want_and_limit(z, y, ids, lq, FLOOR, c1, c2, eps_c1, eps_c2, ref["lse"][r], store)
         err = np.abs(got_rows[k] - want)
         bad = ~((err <= lim) | (got_rows[k] == want))
         assert not np.any(bad), "row %d: %d elements off, worst %.3e vs limit %.3e at u=%d (listed: %s, y=%d)" % (
