@@ -511,7 +511,9 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *   rows_chunk   rows per chunk, a multiple of 64 (scratch at V = 151,936, d = 4096: 8.7 GB for 8192 rows, 16.2 GB for 16384, which is 4 - 10 % faster)
  *   loss [1], freshness [B] (may be NULL; a copy of freshness_in when that is given), weights [B] (may be NULL),
  *   logp [T], lse [T]: f32 outputs
- *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0
+ *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0.
+ *                Both NULL (with freshness_in == NULL): the call only scores - log-probs, scores, weights and the
+ *                loss of the first loop of Algorithm 1 on projected logits, one contraction per chunk instead of three
  *   workspace    fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) bytes, 256-byte aligned, initialised
  *                once with fopd_workspace_init; the same sticky flags as the other entry points
  * The first call in a process sets kernel attributes: make one call before capturing it into a HIP graph.
@@ -539,7 +541,8 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
  *   teacher_logp, teacher_logp_stale [T] or NULL  the sampled token's teacher log-probabilities, for D^sup only
  *                                                 (D^sup = 0 unless both are given; the stale one alone is FOPD_EINVAL)
  *   seq_lens_host [B] int32 (HOST memory, the values of seq_lens); every sample at most rows_chunk rows long
- *   token_loss [T] f32 out or NULL (l_t; 0 outside U^sup); the other arguments as in fopd_lm_head_loss_fwd_bwd
+ *   token_loss [T] f32 out or NULL (l_t; 0 outside U^sup); the other arguments as in fopd_lm_head_loss_fwd_bwd,
+ *   dhidden and dweight both NULL included (scoring only: the buffer's listed-teacher scores without a gradient pass)
  *   workspace  fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k) bytes
  */
 size_t fopd_lm_head_loss_topk_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk,

@@ -1147,13 +1147,17 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
                                      int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
                                      const ListedTeacher* listed, void* workspace, size_t workspace_bytes,
                                      void* stream) {
+  // without the two gradient outputs the call only scores: log-probs, token loss, scores, weights and the loss
+  // (first loop of Algorithm 1 on projected logits)
+  const bool grads = (dhidden != nullptr);
   if (T < 0 || T > 2147483647LL || V <= 0 || V > 2147483647LL - 64 || d <= 0 || d % 64 != 0 || ldh < d || ldw < d ||
-      lddh < d || lddw < d || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
+      (grads && (lddh < d || lddw < d)) || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
     return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
       (teacher_logp == nullptr && listed == nullptr) || seq_lens == nullptr || lag == nullptr || loss == nullptr ||
-      logp == nullptr || lse == nullptr || dhidden == nullptr || dweight == nullptr)
+      logp == nullptr || lse == nullptr || (dhidden == nullptr) != (dweight == nullptr))
     return FOPD_EINVAL;
+  if (!grads && freshness_in != nullptr) return FOPD_EINVAL;       // scoring needs the scores to be formed inside
   if (listed != nullptr) {
     if (listed->k < 1 || listed->k > 4096) return FOPD_ESHAPE;
     if (listed->ids == nullptr || listed->logp == nullptr || freshness_in != nullptr) return FOPD_EINVAL;
@@ -1249,14 +1253,14 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
                                               weights, freshness);
     if ((st = launched()) != FOPD_OK) return st;
-    if (accumulate_dweight == 0) {
+    if (grads && accumulate_dweight == 0) {
       fopd_fill_zero_f32<<<static_cast<unsigned>(V), 256, 0, s>>>(dweight, lddw, static_cast<int>(d));
       return launched();
     }
     return FOPD_OK;
   }
   // the projection matrix with the vocabulary contiguous (zero beyond V), once per call
-  if ((st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
+  if (grads && (st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
 
   int64_t ci = 0;
   for (const Chunk& c : chunks) {
@@ -1303,6 +1307,10 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, nblk, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi,
                                               chunk_loss + ci, weights, freshness);
     if ((st = launched()) != FOPD_OK) return st;
+    if (!grads) {
+      ++ci;
+      continue;
+    }
     {
       ScopedTimer timer(1, s);
       fopd_k4_grad_wide<<<static_cast<unsigned>(R), kGradThreads, 0, s>>>(

@@ -404,3 +404,57 @@ def test_projection_loss_with_listed_teacher(name):
     assert ref["weights"][2] == 0.0 and float(out["weights"][2]) == 0.0
     a2 = sum(seq[:2])
     assert not bool(out["dh"][a2:a2 + seq[2], :d].any())
+
+
+def test_projection_scores_only_calls_give_the_full_calls_scores():
+    """With dhidden and dweight both NULL the two calls only score the buffer (first loop of Algorithm 1 on projected
+    logits): every output they share with the full call is bit-identical to it, and nothing else is written."""
+    _say("scores-only calls (no gradient outputs)")
+    seq, d, V, k, rows_chunk = (90, 130, 80), 128, 3000, 9, 192
+    T, B = sum(seq), len(seq)
+    h = wl.generate_lm_head(T, d, V, DEV, seed=12, masked_every=6)
+    w = wl.attach_loss_inputs(h, seq, [0, 3, 40], seed=12, teacher_list=(k, 0.6))
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
+    f32 = dict(dtype=torch.float32, device=DEV)
+
+    def outs():
+        return dict(loss=torch.full((1,), 7.0, **f32), fresh=torch.full((B,), 7.0, **f32),
+                    weights=torch.full((B,), 7.0, **f32), logp=torch.full((T,), 7.0, **f32),
+                    lse=torch.full((T,), 7.0, **f32), tl=torch.full((T,), 7.0, **f32))
+
+    def listed(o, dh, dw):
+        ws = _aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k))
+        fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+            w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
+            w["list_ids"], w["list_logp"], k, 1e-4, None, None, w["seq_lens"], w["lag"], B, hp, w["seq_lens_host"], g,
+            rows_chunk, o["loss"], o["fresh"], o["weights"], o["logp"], o["lse"], o["tl"], dh, d, dw, d, False, ws)
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+
+    def sampled(o, dh, dw):
+        ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None, None,
+                                     g, rows_chunk, o["loss"], o["weights"], o["logp"], o["lse"], dh, d, dw, d, False, ws,
+                                     seq_lens_host=w["seq_lens_host"], freshness=o["fresh"])
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+
+    for call, keys in ((listed, ("loss", "fresh", "weights", "logp", "lse", "tl")),
+                       (sampled, ("loss", "fresh", "weights", "logp", "lse"))):
+        full, only = outs(), outs()
+        call(full, torch.empty(T, d, **f32), torch.empty(V, d, **f32))
+        call(only, None, None)
+        for key in keys:
+            assert torch.equal(full[key], only[key]), key
+        assert bool((only["fresh"] != 7.0).all()) and bool((only["logp"] != 7.0).all())
+    # one gradient output without the other, or scoring with scores supplied, is refused
+    o = outs()
+    with pytest.raises(fb.FopdError):
+        listed(o, torch.empty(T, d, **f32), None)
+    with pytest.raises(fb.FopdError):
+        ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, o["fresh"], None,
+                                     None, g, rows_chunk, o["loss"], o["weights"], o["logp"], o["lse"], None, d, None, d,
+                                     False, ws)
