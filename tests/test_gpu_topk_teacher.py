@@ -407,3 +407,49 @@ def test_topk_teacher_chunked_flow(split):
             w["logits"][:rows], ch.dt, rows, V, ld, w["token_ids"][:rows], w["mask"][:rows], w["behav_logp"][:rows],
             w["list_ids"][:rows], w["list_logp"][:rows], k, FLOOR, None, None, w["seq_lens"], w["lag"], B, hp, fresh,
             n_train, n_roll, 0, None, logp[:rows], gs, ch.loss, None, None, None, None, out[:rows], ch.workspace)
+
+
+def test_topk_teacher_edge_cases_empty_batch_no_mask_largest_list():
+    """T = 0 (loss 0, weights 0, nothing else touched); no mask (every row in both sets); k = 4096, the largest list."""
+    _say("edge cases: empty batch, no mask, k = 4096")
+    f32 = dict(dtype=torch.float32, device=DEV)
+    # empty batch
+    B, V, k = 3, 512, 4
+    buf = _Buffers(1, V, B, k, "bf16", V)
+    z = torch.full((1, V), 3.0, dtype=torch.bfloat16, device=DEV)       # pointers must not be NULL; nothing is read
+    i32 = dict(dtype=torch.int32, device=DEV)
+    buf.weights.fill_(7.0)
+    buf.loss.fill_(7.0)
+    fb.fopd_loss_fwd_bwd_topk_teacher(z, buf.dt, 0, V, V, torch.zeros(1, **i32), None, torch.zeros(1, **f32),
+                                      torch.zeros(1, k, **i32), torch.zeros(1, k, **f32), k, FLOOR, None, None,
+                                      torch.zeros(B, **i32), torch.zeros(B, **i32), B, (1.0, 1.0, 0.05, 0.1), None, None,
+                                      None, 0, None, None, 1.0, buf.loss, buf.freshness, buf.weights, None, None, z,
+                                      buf.workspace)
+    buf.ok()
+    assert float(buf.loss) == 0.0 and not bool(buf.weights.any()) and not bool(buf.freshness.any())
+    assert bool((z == 3.0).all())
+    # no mask
+    k = 10
+    w = wl.generate("tooluse", DEV, seed=66, B=3, turns=2, obs_lo=0, obs_hi=0, resp_lo=3, resp_hi=7, V=4104, dtype="bf16",
+                    boost=4, lag_lo=0, lag_hi=10, row_block=32, teacher_list=(k, 0.6))
+    hp, gs = (1.0, 1.0, 0.05, 0.3), 1.0
+    ones = dict(w, mask=torch.ones(w["T"], dtype=torch.uint8, device=DEV), mask_host=np.ones(w["T"], dtype=np.uint8))
+    ref = _oracle(ones, hp, gs)
+    buf = _Buffers(w["T"], w["V"], w["B"], k, "bf16", w["ld"])
+    _call(dict(w, mask=None), buf, k, hp, gs)
+    buf.ok()
+    assert abs(float(buf.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    _check_rows(np64(buf.dlogits)[:, :w["V"]], ones, ref, list(range(w["T"])), hp, gs, w["B"],
+                np.repeat(np.arange(w["B"]), np64(w["seq_lens"]).astype(np.int64)))
+    # the largest list: every token of a 4096-token vocabulary listed, in the teacher's order
+    k = 4096
+    w = wl.generate("tooluse", DEV, seed=67, B=2, turns=1, obs_lo=1, obs_hi=2, resp_lo=3, resp_hi=5, V=4096, dtype="f32",
+                    boost=4, lag_lo=0, lag_hi=4, row_block=32, teacher_list=(k, 0.6))
+    ref = _oracle(w, hp, gs)
+    buf = _Buffers(w["T"], w["V"], w["B"], k, "f32", w["ld"])
+    _call(w, buf, k, hp, gs)
+    buf.ok()
+    assert abs(float(buf.loss) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-12
+    sup = (np64(w["mask"]) != 0) & (np64(w["mask"]) != 2)
+    # with nothing left for the rest on either side its term is noise of what fp32 leaves of 1: 1e-6 log(1e-6 / floor)
+    assert_close("token loss", np64(buf.token_loss)[sup], ref["token_loss"][sup], rtol=2e-5, atol=2e-5)
