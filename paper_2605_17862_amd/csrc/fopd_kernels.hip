@@ -1561,8 +1561,10 @@ fopd_topk_terms(const void* logits, int64_t T, int V, int64_t ld, const int32_t*
   double ell = 0.0, gr = 0.0;
   if (live) {
     const double p_rest = 1.0 - sp, q_rest = fmax(1.0 - sq, static_cast<double>(rest_floor));
-    // what fp32 log-probs leave of 1 is noise below 1e-30: the rest then holds no token worth a gradient
-    gr = log(fmax(p_rest, 1e-30)) - log(q_rest);
+    // The listed probabilities come from fp32 log-probs, so what they leave of 1 is known to about 2e-6 and cannot
+    // be told from 0 below 2^-24: the rest's probability is floored there.  An unlisted token then has p_u <= P_rest
+    // of that size, and its gradient entry p_u c2 (G_rest - l_t) stays within 1e-5 |c2| of the exact one.
+    gr = log(fmax(p_rest, 5.9604644775390625e-8)) - log(q_rest);
     ell = sl + (p_rest > 0.0 ? p_rest * gr : 0.0);
   }
   int h = 0;
