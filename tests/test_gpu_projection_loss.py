@@ -326,23 +326,10 @@ LISTED_CASES = {
 }
 
 
-@pytest.mark.parametrize("name", sorted(LISTED_CASES))
-def test_projection_loss_with_listed_teacher(name):
-    """fopd_lm_head_loss_fwd_bwd_topk_teacher against the oracle's lm_head_loss_fwd_bwd_topk_teacher: log-probs,
-    token loss, scores, weights, loss, and dhidden / dweight within the bound that follows from the tolerance of the
-    gradient rows (each a bf16 value within its limit of the oracle's bf16 row; exact bf16 operands; fp32 sums):
-    |dH - dH_ref| <= (lim + 2^-20 |g|) |W|, likewise for dweight with |H|."""
+def _listed_run_and_compare(w, seq, d, V, k, rows_chunk, hp, g, floor, lq_tok=None, lqs_tok=None, gated=None):
+    """fopd_lm_head_loss_fwd_bwd_topk_teacher against the oracle on one workload (see the test below for the bound)."""
     from test_gpu_topk_teacher import coefficient_uncertainties, grad_row_want_and_limit
-    seq, d, V, ldh, ldw, every, rows_chunk, k = LISTED_CASES[name]
     T, B = sum(seq), len(seq)
-    _say("listed teacher, %s: T=%d d=%d V=%d k=%d chunks of at most %d rows" % (name, T, d, V, k, rows_chunk))
-    h = wl.generate_lm_head(T, d, V, DEV, seed=9, masked_every=every, ldh=ldh, ldw=ldw)
-    lag = [0, 3, 40, 1][:B]                            # the third sample is gated
-    w = wl.attach_loss_inputs(h, seq, lag, seed=9, teacher_list=(k, 0.6))
-    w["list_ids"][1, 0] = -1                            # an unused slot
-    if not bool((w["list_ids"][2] == w["token_ids"][2]).any()):
-        w["list_ids"][2, k // 2] = w["token_ids"][2]    # a listed sampled token
-    hp, g, floor = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.7, 1e-4
     ws = _aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k))
     f32 = dict(dtype=torch.float32, device=DEV)
     out = dict(loss=torch.full((1,), 7.0, **f32), fresh=torch.empty(B, **f32), weights=torch.empty(B, **f32),
@@ -350,7 +337,7 @@ def test_projection_loss_with_listed_teacher(name):
                dh=torch.full((T, d + 8), 7.0, **f32), dw=torch.full((V, d), 7.0, **f32))
     fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
         w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"], w["behav_logp"], w["list_ids"],
-        w["list_logp"], k, floor, None, None, w["seq_lens"], w["lag"], B, hp, w["seq_lens_host"], g, rows_chunk,
+        w["list_logp"], k, floor, lq_tok, lqs_tok, w["seq_lens"], w["lag"], B, hp, w["seq_lens_host"], g, rows_chunk,
         out["loss"], out["fresh"], out["weights"], out["logp"], out["lse"], out["tl"], out["dh"], d + 8, out["dw"], d,
         False, ws)
     torch.cuda.synchronize()
@@ -359,36 +346,40 @@ def test_projection_loss_with_listed_teacher(name):
     H, W = np64(w["hidden"])[:, :d], np64(w["weight"])[:, :d]
     mask = np64(w["mask"])
     ids, lq, y = np64(w["list_ids"]), np64(w["list_logp"]), np64(w["token_ids"])
-    ref = orc.lm_head_loss_fwd_bwd_topk_teacher(H, W, y, mask, np64(w["behav_logp"]), ids, lq, floor, None, None,
+    ref = orc.lm_head_loss_fwd_bwd_topk_teacher(H, W, y, mask, np64(w["behav_logp"]), ids, lq, floor,
+                                                None if lq_tok is None else np64(lq_tok),
+                                                None if lqs_tok is None else np64(lqs_tok),
                                                 w["seq_lens_host"], w["lag_host"], hp[0], hp[1], hp[2], hp[3], g)
     assert_close("logp", np64(out["logp"]), ref["logp"], atol=1e-4)
     assert_close("lse", np64(out["lse"]), ref["lse"], atol=1e-4)
     assert_close("freshness", np64(out["fresh"]), ref["freshness"], rtol=1e-5)
     assert_close("weights", np64(out["weights"]), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
-    assert abs(float(out["loss"]) - ref["loss"]) <= 1e-5 * abs(ref["loss"]) + 1e-6 * float(np.mean(ref["weights"])) + 1e-12
     sample_of_row = np.repeat(np.arange(B), np.asarray(seq))
     lim = np.zeros((T, V))
     got_tl = np64(out["tl"])
+    worst_tol = 0.0
     for t in range(T):
         m, i = int(mask[t]), int(sample_of_row[t])
-        if m == 0:
+        if m == 0 or m == 2:
             assert got_tl[t] == 0.0
-            continue
-        ell, G = orc.topk_token_loss_row(ref["logits"][t], ids[t], lq[t], floor)
-        listed = np.zeros(V, dtype=bool)
-        listed[[int(u) for u in ids[t] if 0 <= int(u) < V]] = True
-        g_rest = float(G[~listed][0])
-        # (the last term: the projected logits carry the fp32 accumulation of d products, a few 1e-6 on each
-        # listed log-prob)
-        assert abs(got_tl[t] - ell) <= 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0) + 2e-6, (t, got_tl[t], ell)
-        if ref["c1"][t] == 0.0 and ref["c2"][t] == 0.0:
+        else:
+            ell, G = orc.topk_token_loss_row(ref["logits"][t], ids[t], lq[t], floor)
+            listed = np.zeros(V, dtype=bool)
+            listed[[int(u) for u in ids[t] if 0 <= int(u) < V]] = True
+            g_rest = float(G[~listed][0]) if np.any(~listed) else 0.0
+            # (the last term: the projected logits carry the fp32 accumulation of d products, a few 1e-6 on each
+            # listed log-prob)
+            tol = 2e-5 * abs(ell) + 1e-6 * (abs(g_rest) + 3.0) + 2e-6
+            worst_tol = max(worst_tol, tol)
+            assert abs(got_tl[t] - ell) <= tol, (t, got_tl[t], ell)
+        if m == 0 or (ref["c1"][t] == 0.0 and ref["c2"][t] == 0.0):
             continue
         eps_c1, eps_c2 = coefficient_uncertainties(ref, t, i, m, hp, g, B)
-        # the logits themselves carry the fp32 accumulation of the projection: lse to 1e-4 is what the path states, the
-        # listed probabilities follow it
         _, lim_row, _ = grad_row_want_and_limit(ref["logits"][t], int(y[t]), ids[t], lq[t], floor, ref["c1"][t],
                                                 ref["c2"][t], eps_c1, eps_c2, ref["lse"][t], "bf16")
         lim[t] = lim_row + 2.0 ** -20 * np.abs(ref["dlogits"][t])
+    assert abs(float(out["loss"]) - ref["loss"]) <= (1e-5 * abs(ref["loss"]) + float(np.mean(ref["weights"])) * worst_tol
+                                                     + 1e-12), (float(out["loss"]), ref["loss"])
     lim_h = lim @ np.abs(W) + 1e-30
     lim_w = lim.T @ np.abs(H) + 1e-30
     got_h, got_w = np64(out["dh"])[:, :d], np64(out["dw"])
@@ -399,11 +390,64 @@ def test_projection_loss_with_listed_teacher(name):
          % (rel_h, rel_w, float((err_h / lim_h).max()), float((err_w / lim_w).max())))
     assert np.all(err_h <= lim_h), "dhidden: worst error / bound %.3f" % float((err_h / lim_h).max())
     assert np.all(err_w <= lim_w), "dweight: worst error / bound %.3f" % float((err_w / lim_w).max())
+    assert not np.any(got_h[mask == 0])
+    if gated is not None:
+        assert ref["weights"][gated] == 0.0 and float(out["weights"][gated]) == 0.0
+        a2 = sum(seq[:gated])
+        assert not bool(out["dh"][a2:a2 + seq[gated], :d].any())
+    return ref, rel_h, rel_w
+
+
+@pytest.mark.parametrize("name", sorted(LISTED_CASES))
+def test_projection_loss_with_listed_teacher(name):
+    """fopd_lm_head_loss_fwd_bwd_topk_teacher against the oracle's lm_head_loss_fwd_bwd_topk_teacher: log-probs,
+    token loss, scores, weights, loss, and dhidden / dweight within the bound that follows from the tolerance of the
+    gradient rows (each a bf16 value within its limit of the oracle's bf16 row; exact bf16 operands; fp32 sums):
+    |dH - dH_ref| <= (lim + 2^-20 |g|) |W|, likewise for dweight with |H|."""
+    seq, d, V, ldh, ldw, every, rows_chunk, k = LISTED_CASES[name]
+    T, B = sum(seq), len(seq)
+    _say("listed teacher, %s: T=%d d=%d V=%d k=%d chunks of at most %d rows" % (name, T, d, V, k, rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=9, masked_every=every, ldh=ldh, ldw=ldw)
+    lag = [0, 3, 40, 1][:B]                            # the third sample is gated
+    w = wl.attach_loss_inputs(h, seq, lag, seed=9, teacher_list=(k, 0.6))
+    w["list_ids"][1, 0] = -1                            # an unused slot
+    if not bool((w["list_ids"][2] == w["token_ids"][2]).any()):
+        w["list_ids"][2, k // 2] = w["token_ids"][2]    # a listed sampled token
+    hp, g, floor = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.7, 1e-4
+    ref, rel_h, rel_w = _listed_run_and_compare(w, seq, d, V, k, rows_chunk, hp, g, floor, gated=2)
     assert rel_h < 2e-3 and rel_w < 2e-3
-    assert np.any(got_h[mask != 0]) and not np.any(got_h[mask == 0])
-    assert ref["weights"][2] == 0.0 and float(out["weights"][2]) == 0.0
-    a2 = sum(seq[:2])
-    assert not bool(out["dh"][a2:a2 + seq[2], :d].any())
+
+
+def test_projection_loss_with_listed_teacher_random_sweep():
+    """Ten seeded random problems: sample count and lengths, hidden size, vocabulary, list length, rows per chunk,
+    masks with two aligned sets, lags, hyper-parameters, upstream scale, with and without the two sampled-token
+    teacher arrays that give D^sup."""
+    rs = np.random.RandomState(123)
+    for case in range(10):
+        B = int(rs.randint(1, 5))
+        seq = tuple(int(x) for x in rs.randint(1, 90, size=B))
+        T = sum(seq)
+        d = int(rs.choice([64, 128, 192]))
+        V = int(rs.choice([40, 257, 1000, 4099]))
+        k = int(min(V, rs.choice([1, 3, 16, 70])))
+        rows_chunk = int(rs.choice([64, 128, 256]))
+        rows_chunk = max(rows_chunk, (max(seq) + 63) // 64 * 64)
+        hp = _as_passed((float(rs.choice([0.0, 0.5, 2.0])), float(rs.choice([0.0, 1.0])),
+                         float(rs.choice([0.0, 0.05, 0.2])), float(rs.choice([0.0, 0.1, 1.0]))))
+        g = float(rs.choice([1.0, 0.25, -2.0]))
+        _say("random case %d: seq=%s d=%d V=%d k=%d chunk=%d hp=%s g=%g" % (case, seq, d, V, k, rows_chunk, hp, g))
+        h = wl.generate_lm_head(T, d, V, DEV, seed=300 + case)
+        lag = rs.choice([0, 1, 5, 30], size=B).astype(np.int32)
+        w = wl.attach_loss_inputs(h, seq, lag, seed=300 + case, teacher_list=(k, 0.6))
+        m = rs.choice([0, 1, 1, 1, 2, 3], size=T).astype(np.uint8)
+        w["mask"] = torch.from_numpy(m).to(DEV)
+        drop = torch.from_numpy(rs.rand(T, k) < 0.1).to(DEV)
+        w["list_ids"][drop] = -1
+        lq_tok = lqs_tok = None
+        if case % 2 == 1:
+            lq_tok = w["teacher_logp"]
+            lqs_tok = torch.clamp(lq_tok + 0.2 * torch.from_numpy(rs.randn(T).astype(np.float32)).to(DEV), max=0.0)
+        _listed_run_and_compare(w, seq, d, V, k, rows_chunk, hp, g, 1e-4, lq_tok, lqs_tok)
 
 
 def test_projection_scores_only_calls_give_the_full_calls_scores():
