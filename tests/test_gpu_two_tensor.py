@@ -304,3 +304,66 @@ def test_full_kl_chunked_flow_at_the_coding_workload_size():
             assert not bool(row.any()), "row %d must be zero" % t
         else:
             assert abs(float(row.sum())) <= 2.0 ** -7 * float(row.abs().sum()) + 1e-30
+
+
+def test_two_tensor_variants_random_shapes_sweep():
+    """Twenty-four seeded random problems through both two-tensor calls: vocabulary size and pitch, storage type,
+    sample count and lengths, masks with one or two aligned sets, lags (some gated), the spread between the two
+    tensors, hyper-parameters and upstream scale all vary."""
+    rs = np.random.RandomState(55)
+    for case in range(24):
+        dtype = "bf16" if rs.rand() < 0.7 else "f32"
+        per = 8 if dtype == "bf16" else 4
+        V = int(rs.choice([2, 5, 9, 31, 64, 255, 1000, 2049, 4096, 10007, 32768]))
+        ld = ((V + per - 1) // per) * per + per * int(rs.randint(0, 3))
+        B = int(rs.randint(1, 6))
+        hp = (float(rs.choice([0.0, 0.5, 1.0, 2.0])), float(rs.choice([0.0, 1.0])),
+              float(rs.choice([0.0, 0.05, 0.2])), float(rs.choice([0.0, 0.1, 1.0])))
+        g = float(rs.choice([1.0, 0.125, -2.0]))
+        sigma = float(rs.choice([0.02, 0.1, 0.5]))
+        teacher = bool(case % 2)
+        split = dict(aligned_split=(0.3, 0.3)) if case % 3 == 2 else {}
+        _say("random case %d: %s %s V=%d ld=%d B=%d hp=%s g=%g sigma=%g" % (
+            case, "teacher" if teacher else "stale", dtype, V, ld, B, hp, g, sigma))
+        w = wl.generate("tooluse", DEV, seed=3000 + case, B=B, turns=int(rs.randint(1, 4)), obs_lo=0,
+                        obs_hi=int(rs.randint(0, 5)), resp_lo=0, resp_hi=int(rs.randint(1, 9)), V=V, ld=ld, dtype=dtype,
+                        boost=min(3, V), lag_lo=1 if teacher else 0, lag_hi=int(rs.choice([3, 25])), stale_sigma=0.1,
+                        stale_logit_sigma=sigma, row_block=64, **split)
+        T = w["T"]
+        if T == 0:
+            continue
+        z, z2 = np64(w["logits"])[:, :V], np64(w["logits_stale"])[:, :V]
+        lp = _pass_for(w)
+        kl = torch.empty(T, device=DEV)
+        lp.dlogits.fill_(4.0)
+        if teacher:
+            ref = orc.fopd_loss_fwd_bwd_full_teacher(z, z2, np64(w["token_ids"]), np64(w["mask"]), np64(w["behav_logp"]),
+                                                     np64(w["teacher_logp"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                                     hp[0], hp[1], hp[2], hp[3], g, out_dtype=dtype)
+            fb.fopd_loss_fwd_bwd_full_teacher(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"],
+                                              w["mask"], w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B,
+                                              hp, None, None, None, 0, None, None, None, None, g, lp.loss, lp.freshness,
+                                              lp.weights, lp.logp, kl, lp.dlogits, lp.workspace)
+            want_kl = ref["token_kl"]
+        else:
+            ref = orc.fopd_loss_fwd_bwd_full_kl(z, z2, np64(w["token_ids"]), np64(w["mask"]), np64(w["teacher_logp"]),
+                                                np64(w["teacher_logp_stale"]), np64(w["seq_lens"]), np64(w["lag"]),
+                                                hp[0], hp[1], hp[2], hp[3], g, out_dtype=dtype)
+            fb.fopd_loss_fwd_bwd_full_kl(w["logits"], w["logits_stale"], lp.dt, T, V, ld, ld, w["token_ids"], w["mask"],
+                                         w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, None,
+                                         None, None, 0, None, None, None, None, g, lp.loss, lp.freshness, lp.weights,
+                                         lp.logp, kl, lp.dlogits, lp.workspace)
+            want_kl = ref["roll_kl"]
+        _sync_ok(lp)
+        assert_close("logp", np64(lp.logp), ref["logp"], atol=1e-4)
+        assert_close("per-row KL", np64(kl), want_kl, rtol=2e-5, atol=KL_ROW_ATOL)
+        assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+        assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+        # the loss is a weighted mean of means of per-row values that carry KL_ROW_ATOL each
+        assert abs(float(lp.loss) - ref["loss"]) <= (1e-5 * abs(ref["loss"]) + float(np.mean(ref["weights"])) * KL_ROW_ATOL
+                                                     * (1.0 + hp[3]) + 1e-12), (float(lp.loss), ref["loss"])
+        sample_of = np.repeat(np.arange(B), np64(w["seq_lens"]).astype(np.int64))
+        check_grad_rows_full_kl(np64(lp.dlogits)[:, :V], z, z2, np64(w["token_ids"]), ref, range(T), hp, g, B, sample_of,
+                                dtype, c2_scales_with_weight=teacher)
+        if ld > V:
+            assert bool((lp.dlogits[:, V:] == 4.0).all())
