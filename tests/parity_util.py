@@ -6,7 +6,9 @@ rounding (|lse| < 32) plus a 2e-7 bias from log2(e) held as a float; everything 
 after that is fp64.  Hence:
   integers (cu_seqlens, n_train, gather_idx)      bit-exact
   logp, lse                                       1e-4 absolute
-  freshness, loss                                 1e-5 relative
+  freshness, loss                                 1e-5 relative (the loss, mean_i w_i (l_i + lambda D_i): plus what the
+                                                  absolute tolerances of w_i and l_i below leave when a weight is
+                                                  barely positive or lp - lq nearly cancels)
   weights                                         1e-5 * f_i absolute (w = f - xi cancels near the gate)
   D_roll, D_sup, ell                              2e-5 relative + 1e-9 absolute
   dlogits                                         2 ulp of the storage type (bf16), 2e-5 relative (f32),

@@ -556,6 +556,56 @@ def test_single_read_call_returns_rows_at_unit_weight(dtype, V, ld, workload):
     assert torch.allclose(two.weights, lp.weights, rtol=2e-6, atol=1e-7)
 
 
+def test_single_read_call_random_shapes_sweep():
+    """Twenty seeded random problems through fopd_loss_fwd_bwd_unit: rows short enough for the kernel that re-reads
+    a row and long enough for the one that holds it in registers, both storage types, one or two aligned sets, lags
+    (some gated), hyper-parameters and upstream scale."""
+    rs = np.random.RandomState(88)
+    for case in range(20):
+        dtype = "bf16" if rs.rand() < 0.7 else "f32"
+        per = 8 if dtype == "bf16" else 4
+        V = int(rs.choice([2, 9, 64, 1000, 4096, 10007, 16392, 20000, 40000, 77777]))
+        ld = ((V + per - 1) // per) * per + per * int(rs.randint(0, 3))
+        B = int(rs.randint(1, 6))
+        hp = (float(rs.choice([0.0, 0.5, 1.0, 2.0])), float(rs.choice([0.0, 1.0])),
+              float(rs.choice([0.0, 0.05, 0.2])), float(rs.choice([0.0, 0.1, 1.0])))
+        gs = float(rs.choice([1.0, 0.125, -2.0]))
+        split = dict(aligned_split=(0.3, 0.3)) if case % 3 == 2 else {}
+        _say("single-read random case %d: %s V=%d ld=%d B=%d hp=%s g=%g" % (case, dtype, V, ld, B, hp, gs))
+        w = wl.generate("tooluse", DEV, seed=4000 + case, B=B, turns=int(rs.randint(1, 4)), obs_lo=0,
+                        obs_hi=int(rs.randint(0, 5)), resp_lo=0, resp_hi=int(rs.randint(1, 9)), V=V, ld=ld, dtype=dtype,
+                        boost=min(3, V), lag_lo=0, lag_hi=int(rs.choice([0, 3, 25])),
+                        stale_sigma=float(rs.choice([0.0, 0.1])), row_block=64, **split)
+        T = w["T"]
+        if T == 0:
+            continue
+        ref = oracle_full(w, hp, gs, want_dlogits=True, unit_rows=True)
+        lp = _pass_for(w)
+        lp.dlogits.fill_(7.0)
+        fb.fopd_loss_fwd_bwd_unit(w["logits"], lp.dt, T, V, ld, w["token_ids"], w["mask"], w["behav_logp"],
+                                  w["teacher_logp"], w["teacher_logp_stale"], w["seq_lens"], w["lag"], B, hp, gs, lp.loss,
+                                  lp.freshness, lp.weights, lp.logp, lp.dlogits, lp.workspace)
+        _sync_ok(lp)
+        live = np64(w["mask"]) != 0
+        assert_close("logp", np64(lp.logp)[live], ref["logp"][live], rtol=1e-5, atol=2e-6)
+        assert_close("freshness", np64(lp.freshness), ref["freshness"], rtol=1e-5)
+        assert_close("weights", np64(lp.weights), ref["weights"], atol=1e-5 * ref["freshness"] + 1e-12)
+        # L = mean_i w_i (l_i + lambda D_i): w_i = f_i - xi carries the absolute 1e-5 f_i of its score (case 9 here:
+        # f = 0.0504 against xi = 0.05, so w is known to 1e-3 of itself), and l_i is a mean of differences of fp32
+        # log-probs, good to 1e-6 absolute
+        per_sample = (1e-5 * ref["freshness"] * np.abs(ref["ell"] + hp[3] * ref["D_roll"]) * (ref["weights"] > 0)
+                      + 1e-6 * ref["weights"])
+        loss_tol = 1e-5 * abs(ref["loss"]) + float(np.mean(per_sample)) + 1e-12
+        assert abs(float(lp.loss) - ref["loss"]) <= loss_tol, (float(lp.loss), ref["loss"])
+        valid = np.minimum(ref["n_train"], ref["n_roll"]) > 0
+        unit_ref = dict(ref, weights=valid.astype(np.float64), freshness=np.zeros(B))
+        eps_c = coef_uncertainty(unit_ref, hp, gs, B, np64(w["mask"]))
+        y = ref["gather_idx"] - np.arange(T) * ld
+        check_grad_rows(np64(lp.dlogits)[:, :V], np64(w["logits"])[:, :V], y, ref["lse"], ref["coef_unit"], eps_c, dtype)
+        if ld > V:
+            assert bool((lp.dlogits[:, V:] == 7.0).all())
+
+
 def test_single_read_call_without_a_mask_counts_every_row():
     """A NULL mask means that every row is in both aligned sets, and a NULL stale teacher log-prob means
     D^sup = 0: checked against the oracle given a mask of ones and the fresh teacher log-probs as the stale ones."""
