@@ -519,6 +519,20 @@ def main():
     st, flags = lp.status()
     if st != 0:
         sys.exit("device flags set: %d" % flags)
+    # A yardstick that shares nothing with the kernels: the tensor library's device-to-device copy of the same
+    # logits into the same gradient buffer, in this process.  (Where the driver placed the pair of buffers moves
+    # every copy-shaped kernel by a few per cent; this copy sees the same placement as the gradient kernel did.)
+    copy_ms = None
+    if lp.dlogits.shape == w["logits"].shape:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        lp.dlogits.copy_(w["logits"])
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            lp.dlogits.copy_(w["logits"])
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms = e0.elapsed_time(e1) / 5
     ms_per_step = elapsed / args.steps * 1e3
     n_train = w["n_trainable"]
 
@@ -572,6 +586,12 @@ def main():
         "ms_per_call": unit_elapsed / args.steps * 1e3, "tokens/s": n_train * args.steps / unit_elapsed,
         "GB/s": unit_bytes / (unit_elapsed / args.steps) / 1e9,
         "frac": unit_bytes / (unit_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS}
+    if copy_ms is not None:
+        copy_bytes = 2 * T * w["ld"] * e
+        out["copy_yardstick"] = {
+            "call": "torch Tensor.copy_ of the logits into the gradient buffer (same two buffers, same process)",
+            "ms": copy_ms, "GB/s": copy_bytes / (copy_ms * 1e-3) / 1e9, "frac": copy_bytes / (copy_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "fopd_k4_grad_over_copy": achieved / (copy_bytes / (copy_ms * 1e-3) / 1e9)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, hp)
     if not args.no_projection:
