@@ -96,7 +96,7 @@ struct LmLossWorkspace {
     r_pad = static_cast<int64_t>(r);
     n_chunks = (t + rc - 1) / rc;
     ldz = (V + 63) / 64 * 64;
-    const size_t v = static_cast<size_t>(V < 0 ? 0 : V), dd = static_cast<size_t>(d < 0 ? 0 : d);
+    const size_t dd = static_cast<size_t>(d < 0 ? 0 : d);
     size_t off = 0;
     flags = Workspace::take(off, 4 * sizeof(int32_t));
     cu = Workspace::take(off, (b + 1) * sizeof(int64_t));
