@@ -66,6 +66,8 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 //   7  the wavefront raises its priority while it issues matrix instructions: no gain
 //   8  no result stores
 //   9  (results correct) non-temporal result stores
+//  10  (results correct) no scheduling group barriers: the order inside a slice is the scheduler's (memory instructions
+//      first); 11, 13: two other orders (fragment reads first; one memory instruction per gap)
 //
 // VIA_REGS != 0: the operand stages travel global -> vector registers -> LDS (ordinary loads, then ds_write_b128 to
 // the same swizzled slots) instead of global -> LDS directly.  1: the loads of pair p + 2 are issued at the start
@@ -249,6 +251,41 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
     if (PROBE == 7) __builtin_amdgcn_s_setprio(0);
   };
 
+  // PROBE 10: within a slice, the two LDS writes, the two global loads and the six fragment reads are spread
+  // between the eight matrix instructions instead of being left to the scheduler
+#define FOPD_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+  // Order of the instructions inside a 16-k slice, fixed by scheduling group barriers (masks: 0x008 matrix
+  // instruction, 0x020 global load, 0x100 LDS read, 0x200 LDS write).  Left to itself the scheduler puts a slice's ten
+  // memory instructions ahead of its eight matrix instructions; with one or two of them between consecutive matrix
+  // instructions the matrix pipe keeps issuing while they go out: 4 - 5 % on the whole loop (gemm_probe).  Slices
+  // 0 - 2: the two LDS writes, the two global loads, then the six fragment reads in pairs.  Slice 3 sits behind the
+  // barrier: fragment reads in pairs, then the two global loads, each followed by a matrix instruction.
+  // (the counts are those of the shipped shape: eight wavefronts, a quarter of a pair per slice)
+  constexpr bool kShippedShape = (VIA_REGS == 4 && WAVES == 8 && TJ == 2);
+  constexpr int kSched = (!kShippedShape || PROBE == 10) ? 0 : (PROBE == 11) ? 11 : (PROBE == 13) ? 13 : 12;
+  auto interleave_tail = [&]() {
+    if constexpr (kSched != 0) {
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 4);
+    }
+  };
+  auto interleave = [&]() {
+    if constexpr (kSched == 11) {           // fragment reads first, then the LDS writes, the loads last
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 2);
+    }
+    if constexpr (kSched == 12) {           // shipped
+      FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 2);
+    }
+    if constexpr (kSched == 13) {           // one memory instruction per gap where there is room
+      FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1);
+    }
+  };
   [[maybe_unused]] uint32_t pf_word = 0;
   [[maybe_unused]] const char* pf_base = Ab;
   if constexpr (PROBE == 6) {
@@ -285,17 +322,20 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
       }
       read_frags(1, lo, 1);
       multiply(0);
+      interleave();
       __builtin_amdgcn_sched_barrier(0);
       if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 1);
       if (VIA_REGS >= 3) load_regs_quarter(k_next, 1);
       read_frags(0, hi, 0);
       multiply(1);
+      interleave();
       __builtin_amdgcn_sched_barrier(0);
       if (VIA_REGS == 2) load_regs_b(k_next);
       if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 2);
       if (VIA_REGS >= 3) load_regs_quarter(k_next, 2);
       read_frags(1, hi, 1);
       multiply(0);
+      interleave();
       __builtin_amdgcn_sched_barrier(0);
       if (VIA_REGS == 4) write_lds_quarter(pb ^ 1, 3);
       __syncthreads();
@@ -307,8 +347,10 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
         if (lane < 12) pf_word = *reinterpret_cast<const uint32_t*>(pf_base + static_cast<int64_t>(min(p + 3, n_pairs - 1)) * 128);
       }
       read_frags(0, next, 0);
-      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (kSched == 0) __builtin_amdgcn_sched_barrier(0);
       multiply(1);
+      interleave_tail();
+      if constexpr (kSched != 0) __builtin_amdgcn_sched_barrier(0);
     }
   } else {
     // Same schedule as the projection kernel: two pairs of stages in the LDS; while pair p multiplies, pair p + 1
@@ -426,7 +468,7 @@ __device__ __forceinline__ bf16x8 tn_read_fragment(const unsigned char* p) {
   return __builtin_bit_cast(bf16x8, both);
 }
 
-template <bool ACCUMULATE>
+template <bool ACCUMULATE, int SCHED = 2>
 __global__ void __launch_bounds__(kGemmThreads)
 fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, const __bf16* __restrict__ Bk, int64_t ldb,
              int N, int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
@@ -501,6 +543,23 @@ fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, cons
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
   };
 
+  // the order inside a slice, as in fopd_gemm_nt: the two LDS writes, the two global loads and the twelve transpose
+  // reads (four per gap) go between the eight matrix instructions
+  // SCHED (timing variants of gemm_probe): 0 the scheduler's own order, 1 reads four per gap behind the writes and
+  // loads, 2 two memory instructions in every gap
+  auto tn_interleave = [&]() {
+    if constexpr (SCHED == 1) {
+      FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x200, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 2);
+    }
+    if constexpr (SCHED == 2) {
+      FOPD_SGB(0x200, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+    }
+  };
+
   // pair 0 into the LDS, pair 1 into registers (requested in the order the loop keeps); then per pair p and 16-k
   // slice s: quarter s of pair p + 1 -> LDS, request quarter s of pair p + 2, multiply slice s of pair p
   const int n_pairs = K / 64;
@@ -526,23 +585,37 @@ fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, cons
     load_quarter(k_next, 0);
     read_frags(1, lo, 1);
     multiply(0);
+    tn_interleave();
     __builtin_amdgcn_sched_barrier(0);
     write_quarter(pb ^ 1, 1);
     load_quarter(k_next, 1);
     read_frags(0, hi, 0);
     multiply(1);
+    tn_interleave();
     __builtin_amdgcn_sched_barrier(0);
     write_quarter(pb ^ 1, 2);
     load_quarter(k_next, 2);
     read_frags(1, hi, 1);
     multiply(0);
+    tn_interleave();
     __builtin_amdgcn_sched_barrier(0);
     write_quarter(pb ^ 1, 3);
     __syncthreads();
     load_quarter(k_next, 3);
     read_frags(0, next, 0);
-    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (SCHED == 0) __builtin_amdgcn_sched_barrier(0);
     multiply(1);
+    // behind the barrier: the transpose reads, then the two global loads, between the matrix instructions
+    if constexpr (SCHED == 1) {
+      FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 4); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 1); FOPD_SGB(0x020, 1); FOPD_SGB(0x008, 4);
+    }
+    if constexpr (SCHED == 2) {
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1); FOPD_SGB(0x100, 2); FOPD_SGB(0x008, 1);
+      FOPD_SGB(0x020, 2); FOPD_SGB(0x008, 2);
+    }
+    if constexpr (SCHED != 0) __builtin_amdgcn_sched_barrier(0);
   }
 
   // result stores: as fopd_gemm_nt (register r of block (i, j): n = 32 j + 8 (r / 4) + 4 (lane / 32) + r % 4,

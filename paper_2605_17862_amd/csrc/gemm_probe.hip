@@ -161,38 +161,47 @@ int main(int argc, char** argv) {
   if (run<7, 2, 4, 2, 4>("  ... wave priority raised for MFMAs", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<8, 2, 4, 2, 4>("  ... no result stores", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<9, 2, 4, 2, 4>("  ... non-temporal result stores", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<10, 2, 4, 2, 4>("  ... slice order left to the scheduler", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<11, 2, 4, 2, 4>("  ... fragment reads first in a slice", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<13, 2, 4, 2, 4>("  ... one memory instruction per gap", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run_sustained(A, ld, M, B, ld, N, K, out, groups, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
   FOPD_PROBE_SET(2, 2, 4)
   if (run<0, 2, 2, 4, 1>("whole loop, stages through registers", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<0, 2, 2, 4, 4>("  ... a quarter of a pair per slice", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
 #undef FOPD_PROBE_SET
-  if (N == 8192 && M == 151936 && K == 4096 && pad == 0) {
+  if (N >= 8192 && M == 151936 && K == 4096 && pad == 0) {
     // the weight gradient's shape with both operands k-major, in the same buffers: Out[151936, 4096] =
-    // sum over 4096 rows of Bk[4096, 151936] (all of buffer A) and Ak[4096, 4096] (half of buffer B)
+    // sum over 4096 rows of Bk[4096, 151936] (all of buffer A) and Ak[4096, 4096] (half of the first 8192 rows of
+    // buffer B); three orders of the instructions inside a slice
     using namespace fopd;
-    auto kern = fopd_gemm_tn<false>;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            kTnLdsBytes) != hipSuccess) {
-      printf("gemm_probe: %d bytes of LDS refused\n", kTnLdsBytes);
-      return 1;
-    }
     const int tm = 4096 / kGemmTile, tn = (151936 + kGemmTileN - 1) / kGemmTileN;
     const unsigned grid = static_cast<unsigned>(((tm + 7) / 8) * ((tn + 31) / 32) * 256);
-    float total = 0.f;
-    for (int rep = 0; rep < 4; ++rep) {
-      CHECK(hipEventRecord(e0, 0));
-      kern<<<grid, kGemmThreads, kTnLdsBytes>>>(B, 4096, 4096, 4096, A, 151936, 151936, 4096, out, 4096, tm, tn);
-      CHECK(hipGetLastError());
-      CHECK(hipEventRecord(e1, 0));
-      CHECK(hipEventSynchronize(e1));
-      float ms = 0.f;
-      CHECK(hipEventElapsedTime(&ms, e0, e1));
-      if (rep > 0) total += ms;
-    }
     const double flops = 2.0 * 4096 * 151936.0 * 4096;
-    printf("gemm_probe: both operands k-major, Out[151936, 4096], K = 4096: avg %.3f ms, %.0f TFLOP/s (%.3f of 2500)\n",
-           total / 3, flops / (total / 3) * 1e-9, flops / (total / 3) * 1e-9 / 2500.0);
+    auto time_tn = [&](auto kern, const char* name) -> int {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kTnLdsBytes) != hipSuccess) {
+        printf("gemm_probe: %d bytes of LDS refused\n", kTnLdsBytes);
+        return 1;
+      }
+      float total = 0.f;
+      for (int rep = 0; rep < 4; ++rep) {
+        CHECK(hipEventRecord(e0, 0));
+        kern<<<grid, kGemmThreads, kTnLdsBytes>>>(B, 4096, 4096, 4096, A, 151936, 151936, 4096, out, 4096, tm, tn);
+        CHECK(hipGetLastError());
+        CHECK(hipEventRecord(e1, 0));
+        CHECK(hipEventSynchronize(e1));
+        float ms = 0.f;
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        if (rep > 0) total += ms;
+      }
+      printf("gemm_probe: both operands k-major, Out[151936, 4096], K = 4096, %s: avg %.3f ms, %.0f TFLOP/s (%.3f of 2500)\n",
+             name, total / 3, flops / (total / 3) * 1e-9, flops / (total / 3) * 1e-9 / 2500.0);
+      return 0;
+    };
+    if (time_tn(fopd_gemm_tn<false, 0>, "slice order left to the scheduler")) return 1;
+    if (time_tn(fopd_gemm_tn<false, 1>, "reads four per gap")) return 1;
+    if (time_tn(fopd_gemm_tn<false, 2>, "two memory instructions per gap (shipped)")) return 1;
   }
   CHECK(hipFree(A));
   CHECK(hipFree(B));
