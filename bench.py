@@ -310,6 +310,9 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     ws = aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
     loss, weights = torch.empty(1, **f32), torch.empty(B, **f32)
     dh, dw = torch.empty(T, d, **f32), torch.empty(V, d, **f32)
+    # masked rows are left out of the contractions unless --no-compact asks for every row to be projected
+    fb.fopd_set_option("lm_head_compact", 0 if args.no_compact else 1)
+    live = T if args.no_compact else int((mask != 0).sum())
 
     def step():
         fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
@@ -374,8 +377,12 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     n_chunks = (T + rows_chunk - 1) // rows_chunk
     ldz = (V + 63) // 64 * 64
     rp = sum(((min(rows_chunk, T - a) + 63) // 64) * 64 for a in range(0, T, rows_chunk))
-    # flops actually issued per call, operand padding included: logits, dhidden, dweight contractions
-    flops = {4: 2.0 * T * V * d, 5: 2.0 * T * ldz * d, 6: 2.0 * rp * V * d}
+    # flops per call: logits, dhidden, dweight contractions.  Every row projected: what is issued, operand padding
+    # included; masked rows left out: the live rows' (the tiles' ragged ends are issued on top and not counted)
+    if live == T:
+        flops = {4: 2.0 * T * V * d, 5: 2.0 * T * ldz * d, 6: 2.0 * rp * V * d}
+    else:
+        flops = {4: 2.0 * live * V * d, 5: 2.0 * live * ldz * d, 6: 2.0 * live * V * d}
     names = {4: "logits = hidden . weight^T", 5: "dhidden = dlogits . weight", 6: "dweight += dlogits^T . hidden"}
     kern, tot_ms = {}, 0.0
     for slot in (4, 5, 6):
@@ -392,8 +399,9 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
         "value": int(((mask != 0) & (mask != 2)).sum()) * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
         "steps": steps, "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d, "rows_chunk": rows_chunk,
-                   "chunks": n_chunks, "call": "fopd_lm_head_loss_fwd_bwd",
+        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "rows_with_mask_0": int((mask == 0).sum()),
+                   "masked_rows_left_out_of_the_contractions": not args.no_compact, "V": V, "d": d,
+                   "rows_chunk": rows_chunk, "chunks": n_chunks, "call": "fopd_lm_head_loss_fwd_bwd",
                    "scratch_GB": fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) / 1e9},
         "roofline": {"bound": "mfma", "kernel": "fopd_gemm_nt, fopd_gemm_tn (three contractions per chunk)",
                      "achieved": all_flops / (tot_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -422,6 +430,8 @@ def main():
                     help="skip the projection-fused log-prob measurement reported beside the headline")
     ap.add_argument("--rows-chunk", type=int, default=16384,
                     help="rows per chunk of the loss pass through the projection (--variant lm_head_loss)")
+    ap.add_argument("--no-compact", action="store_true",
+                    help="lm_head_loss: project every row of a chunk, masked ones included (option lm_head_compact = 0)")
     ap.add_argument("--list-k", type=int, default=64,
                     help="tokens per row of the stored teacher (--variant topk_teacher)")
     ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "topk_teacher", "lm_head",

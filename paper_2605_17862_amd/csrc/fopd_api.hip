@@ -87,6 +87,10 @@ struct LmLossWorkspace {
          wt = 0, total = 0;
   // with a teacher stored as k tokens per row: token loss [T], per-row values and per-slot terms of one chunk
   size_t token_loss = 0, c2 = 0, g_rest = 0, row_coef = 0, p_list = 0, h_list = 0;
+  // the chunk's live rows moved to the front: prefix counts, row map, live count, sample offsets, then the dense
+  // copies of the per-row inputs and outputs, of the hidden rows and of their gradient
+  size_t ex = 0, row_map = 0, n_live = 0, cu_c = 0, tok_c = 0, mask_c = 0, behav_c = 0, teach_c = 0, stale_c = 0,
+         logp_c = 0, lse_c = 0, tl_c = 0, ids_c = 0, llp_c = 0, h_c = 0, dh_c = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
   LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk, int32_t k = 0) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
@@ -118,7 +122,23 @@ struct LmLossWorkspace {
       row_coef = Workspace::take(off, r * sizeof(float));
       p_list = Workspace::take(off, r * kk * sizeof(float));
       h_list = Workspace::take(off, r * kk * sizeof(float));
+      ids_c = Workspace::take(off, r * kk * sizeof(int32_t));
+      llp_c = Workspace::take(off, r * kk * sizeof(float));
     }
+    ex = Workspace::take(off, (r + 1) * sizeof(int32_t));
+    row_map = Workspace::take(off, r * sizeof(int32_t));
+    n_live = Workspace::take(off, 64 * sizeof(int32_t));
+    cu_c = Workspace::take(off, (b + 1) * sizeof(int64_t));
+    tok_c = Workspace::take(off, r * sizeof(int32_t));
+    mask_c = Workspace::take(off, r);
+    behav_c = Workspace::take(off, r * sizeof(float));
+    teach_c = Workspace::take(off, r * sizeof(float));
+    stale_c = Workspace::take(off, r * sizeof(float));
+    logp_c = Workspace::take(off, r * sizeof(float));
+    lse_c = Workspace::take(off, r * sizeof(float));
+    tl_c = Workspace::take(off, r * sizeof(float));
+    h_c = Workspace::take(off, r * dd * 2);
+    dh_c = Workspace::take(off, r * dd * sizeof(float));
     total = off;
   }
 };
@@ -204,6 +224,7 @@ struct Options {
   int k14_rows_per_cu = 6;        // rows in flight per compute unit (measured optimum on MI355X)
   int k14_regs_grid = 0;          // workgroups of the row-in-registers kernel; 0 = two per compute unit
   int k14_regs = 1;               // 1: rows that fit (16-byte vectors <= 1024 x 19) are held in registers between the passes
+  int lm_head_compact = 1;        // 1: the loss pass through the projection leaves masked rows out of its contractions
 } g_opt;
 
 inline Options current_options() {
@@ -1057,9 +1078,11 @@ size_t fopd_lm_head_loss_workspace_bytes(int64_t T, int64_t V, int64_t d, int32_
   return LmLossWorkspace(T, V, d, B, rows_chunk).total;
 }
 
-// Out[n, m] (+)= sum_k Bn[n, k] Am[m, k] on `s`; `slot` = timing slot of this contraction.
+// Out[n, m] (+)= sum_k Bn[n, k] Am[m, k] on `s`; `slot` = timing slot of this contraction.  n_live != NULL: a device
+// int, the number of leading rows of Bn that count (the tiles past them are not computed).
 static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, int64_t M, const __bf16* Bn, int64_t ldb,
-                               int64_t N, int64_t K, float* Out, int64_t ldo, int slot, hipStream_t s) {
+                               int64_t N, int64_t K, float* Out, int64_t ldo, int slot, hipStream_t s,
+                               const int* n_live = nullptr) {
   if (M <= 0 || N <= 0) return FOPD_OK;
   if (K <= 0 || K % 64 != 0 || M > 2147483647LL || N > 2147483647LL || K > 2147483647LL) return FOPD_ESHAPE;
   // byte offsets inside one 256-row operand tile are 32-bit
@@ -1076,18 +1099,18 @@ static fopd_status launch_gemm(bool accumulate, const __bf16* Am, int64_t lda, i
   ScopedTimer timer(slot, s);
   if (accumulate)
     fopd_gemm_nt<true, 0><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
-                                                          static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
+                                                          static_cast<int>(K), Out, ldo, tiles_m, tiles_n, n_live);
   else
     fopd_gemm_nt<false, 0><<<grid, block, kGemmLdsBytes, s>>>(Am, lda, static_cast<int>(M), Bn, ldb, static_cast<int>(N),
-                                                           static_cast<int>(K), Out, ldo, tiles_m, tiles_n);
+                                                           static_cast<int>(K), Out, ldo, tiles_m, tiles_n, n_live);
   return launched();
 }
 
 // Out[n, m] (+)= sum_{k < K} Bk[k, n] Ak[k, m] on `s`; Ak has rows_a readable rows, Bk has K and zeros where a row
-// is not to count.
+// is not to count.  k_live != NULL: a device int, the number of leading rows that count (K is cut to it, rounded up to 64).
 static fopd_status launch_gemm_tn(bool accumulate, const __bf16* Ak, int64_t lda, int64_t M, int64_t rows_a,
                                   const __bf16* Bk, int64_t ldb, int64_t N, int64_t K, float* Out, int64_t ldo, int slot,
-                                  hipStream_t s) {
+                                  hipStream_t s, const int* k_live = nullptr) {
   if (M <= 0 || N <= 0) return FOPD_OK;
   if (K <= 0 || K % 64 != 0 || rows_a < 1 || rows_a > K || M > 2147483647LL || N > 2147483647LL || K > 2147483647LL ||
       M % 8 != 0 || lda % 8 != 0 || ldb % 8 != 0 || lda < M || ldb < (N + 7) / 8 * 8)
@@ -1105,11 +1128,11 @@ static fopd_status launch_gemm_tn(bool accumulate, const __bf16* Ak, int64_t lda
   if (accumulate)
     fopd_gemm_tn<true><<<grid, block, kTnLdsBytes, s>>>(Ak, lda, static_cast<int>(M), static_cast<int>(rows_a), Bk, ldb,
                                                        static_cast<int>(N), static_cast<int>(K), Out, ldo, tiles_m,
-                                                       tiles_n);
+                                                       tiles_n, k_live);
   else
     fopd_gemm_tn<false><<<grid, block, kTnLdsBytes, s>>>(Ak, lda, static_cast<int>(M), static_cast<int>(rows_a), Bk, ldb,
                                                         static_cast<int>(N), static_cast<int>(K), Out, ldo, tiles_m,
-                                                        tiles_n);
+                                                        tiles_n, k_live);
   return launched();
 }
 
@@ -1262,45 +1285,111 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   // the projection matrix with the vocabulary contiguous (zero beyond V), once per call
   if (grads && (st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
 
+  // Masked rows have no log-prob and no gradient row: with a mask, each chunk's live rows are moved to the front
+  // (dense copies of the per-row inputs and of the hidden rows), every kernel of the chunk runs on those, the
+  // contractions read the live count on the device and leave out the tiles past it, and the per-row outputs and
+  // dL/dhidden rows are scattered back.
+  const bool compact = (mask != nullptr) && (current_options().lm_head_compact != 0);
+  int32_t* ex = at<int32_t>(workspace, lay.ex);
+  int32_t* row_map = at<int32_t>(workspace, lay.row_map);
+  int32_t* n_live = at<int32_t>(workspace, lay.n_live);
+  int64_t* cu_c = at<int64_t>(workspace, lay.cu_c);
+  const float* stale = (listed != nullptr) ? listed->teacher_logp_stale : nullptr;
+
   int64_t ci = 0;
   for (const Chunk& c : chunks) {
     const int64_t a = c.a, R = c.R;
     if (R == 0) continue;
     const int64_t Rp = (R + 63) / 64 * 64;
+    // what the chunk's kernels see: the caller's rows a .. a + R - 1, or the dense copies of the live ones
     const __bf16* Hc = Hm + a * ldh;
+    int64_t ldhc = ldh;
+    const int32_t* tok = token_ids + a;
+    const uint8_t* msk = (mask == nullptr) ? nullptr : mask + a;
+    const float* bl = behav_logp + a;
+    const float* tq = (teacher_logp == nullptr) ? nullptr : teacher_logp + a;
+    const int32_t* lids = (listed != nullptr) ? listed->ids + a * list_k : nullptr;
+    const float* llp = (listed != nullptr) ? listed->logp + a * list_k : nullptr;
+    float* lp_o = logp + a;
+    float* ls_o = lse + a;
+    float* tl_o = (tl != nullptr) ? tl + a : nullptr;
+    float* dH = grads ? dhidden + a * lddh : nullptr;
+    int64_t lddhc = lddh;
+    const int64_t* cu_k = cu;           // sample offsets and the chunk's first row in the row numbering of the kernels
+    int64_t a_k = a;
+    const int* live = nullptr;
+    if (compact) {
+      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, static_cast<int>(R), cu, B, a, ex, row_map, n_live, cu_c);
+      if ((st = launched()) != FOPD_OK) return st;
+      fopd_live_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(
+          row_map, n_live, tok, msk, bl, tq, (stale != nullptr) ? stale + a : nullptr, lids, llp, list_k,
+          reinterpret_cast<const uint16_t*>(Hc), ldh, static_cast<int>(d), at<int32_t>(workspace, lay.tok_c),
+          at<uint8_t>(workspace, lay.mask_c), at<float>(workspace, lay.behav_c), at<float>(workspace, lay.teach_c),
+          at<float>(workspace, lay.stale_c), at<int32_t>(workspace, lay.ids_c), at<float>(workspace, lay.llp_c),
+          at<uint16_t>(workspace, lay.h_c));
+      if ((st = launched()) != FOPD_OK) return st;
+      Hc = at<__bf16>(workspace, lay.h_c);
+      ldhc = d;
+      tok = at<int32_t>(workspace, lay.tok_c);
+      msk = at<uint8_t>(workspace, lay.mask_c);
+      bl = at<float>(workspace, lay.behav_c);
+      if (tq != nullptr) tq = at<float>(workspace, lay.teach_c);
+      if (listed != nullptr) {
+        lids = at<int32_t>(workspace, lay.ids_c);
+        llp = at<float>(workspace, lay.llp_c);
+        tl_o = at<float>(workspace, lay.tl_c);
+      }
+      lp_o = at<float>(workspace, lay.logp_c);
+      ls_o = at<float>(workspace, lay.lse_c);
+      if (grads) dH = at<float>(workspace, lay.dh_c);
+      lddhc = d;
+      cu_k = cu_c;
+      a_k = 0;
+      live = n_live;
+    }
+    // the per-row outputs and dL/dhidden rows of the live rows go back to the caller's rows, zeros to the others
+    auto scatter = [&]() -> fopd_status {
+      if (!compact) return FOPD_OK;
+      fopd_live_scatter<<<static_cast<unsigned>(R), 256, 0, s>>>(
+          ex, lp_o, ls_o, tl_o, dH, static_cast<int>(d), logp + a, lse + a,
+          (listed != nullptr && listed->token_loss != nullptr) ? listed->token_loss + a : nullptr,
+          grads ? dhidden + a * lddh : nullptr, lddh);
+      return launched();
+    };
     // logits of the chunk, fp32, never rounded to the storage type of stored logits
-    if ((st = launch_gemm(false, Wm, ldw, V, Hc, ldh, R, d, Z, ldz, 4, s)) != FOPD_OK) return st;
-    if ((st = launch_k1(Z, FOPD_F32, R, V, ldz, token_ids + a, mask == nullptr ? nullptr : mask + a, logp + a, lse + a,
-                        nullptr, nullptr, flags, s)) != FOPD_OK)
-      return st;
-    const uint8_t* mask_c = (mask == nullptr) ? nullptr : mask + a;
+    if ((st = launch_gemm(false, Wm, ldw, V, Hc, ldhc, R, d, Z, ldz, 4, s, live)) != FOPD_OK) return st;
+    if ((st = launch_k1(Z, FOPD_F32, R, V, ldz, tok, msk, lp_o, ls_o, nullptr, nullptr, flags, s)) != FOPD_OK) return st;
     if (listed != nullptr) {
       // the listed logits of each row are in the chunk's scratch: token loss, G_rest - l_t and the per-slot terms
-      if ((st = launch_topk_terms(Z, FOPD_F32, R, V, ldz, token_ids + a, mask_c, listed->ids + a * list_k,
-                                  listed->logp + a * list_k, list_k, listed->rest_floor, lse + a, tl + a, g_rest, p_list,
-                                  h_list, s)) != FOPD_OK)
+      if ((st = launch_topk_terms(Z, FOPD_F32, R, V, ldz, tok, msk, lids, llp, list_k, listed->rest_floor, ls_o, tl_o,
+                                  g_rest, p_list, h_list, s)) != FOPD_OK)
         return st;
     }
     if (!scored) {
       // the chunk holds whole samples: their scores follow from the log-probs just made
-      fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
-          logp, behav_logp, nullptr, tl, teacher_logp, (listed != nullptr) ? listed->teacher_logp_stale : nullptr, mask,
-          cu + c.i0, lag + c.i0, T, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
-          f64 + c.i0, nws + c.i0, nrws + c.i0);
+      if (compact)
+        fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
+            lp_o, bl, nullptr, tl_o, tq, (stale != nullptr) ? at<float>(workspace, lay.stale_c) : nullptr, msk,
+            cu_c + c.i0, lag + c.i0, R, hp, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+            f64 + c.i0, nws + c.i0, nrws + c.i0);
+      else
+        fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
+            logp, behav_logp, nullptr, tl, teacher_logp, stale, mask, cu + c.i0, lag + c.i0, T, hp, nullptr, nullptr,
+            nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, f64 + c.i0, nws + c.i0, nrws + c.i0);
       if ((st = launched()) != FOPD_OK) return st;
     }
     const int64_t nblk = (R + kStreamThreads - 1) / kStreamThreads;
     if (listed != nullptr) {
       // c1 (into `coef`), c2 and the chunk's share of the loss; then the stream's coefficient c1 + c2 (G_rest - l_t)
       fopd_coef_loss_kl<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-          logp + a, tl + a, nullptr, behav_logp + a, mask_c, cu, n_use, nr_use, lag, f64_use, freshness_in, R, B, a, hp,
-          grad_scale, false, coef, c2, partials);
+          lp_o, tl_o, nullptr, bl, msk, cu_k, n_use, nr_use, lag, f64_use, freshness_in, R, B, a_k, hp, grad_scale,
+          false, coef, c2, partials);
       if ((st = launched()) != FOPD_OK) return st;
       fopd_topk_row_coef<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(coef, c2, g_rest, R, row_coef);
     } else {
       fopd_coef_loss<<<static_cast<unsigned>(nblk), kStreamThreads, 0, s>>>(
-          logp + a, behav_logp + a, teacher_logp + a, mask_c, cu, n_use, nr_use, lag, f64_use, freshness_in, R, B, a, hp,
-          grad_scale, coef, partials, flags);
+          lp_o, bl, tq, msk, cu_k, n_use, nr_use, lag, f64_use, freshness_in, R, B, a_k, hp, grad_scale, coef, partials,
+          flags);
     }
     if ((st = launched()) != FOPD_OK) return st;
     // (weights and scores of samples whose chunk is still to come are overwritten by the later calls)
@@ -1308,26 +1397,26 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
                                               chunk_loss + ci, weights, freshness);
     if ((st = launched()) != FOPD_OK) return st;
     if (!grads) {
+      if ((st = scatter()) != FOPD_OK) return st;
       ++ci;
       continue;
     }
     {
       ScopedTimer timer(1, s);
       fopd_k4_grad_wide<<<static_cast<unsigned>(R), kGradThreads, 0, s>>>(
-          Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), token_ids + a, lse + a, logp + a,
-          (listed != nullptr) ? row_coef : coef);
+          Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), tok, ls_o, lp_o,
+          (listed != nullptr) ? row_coef : coef, live);
       if ((st = launched()) != FOPD_OK) return st;
       if (listed != nullptr) {
         // the k listed entries of each row and the sampled token's, in the bf16 rows just written
         const dim3 grid(static_cast<unsigned>((R + kListRows - 1) / kListRows)), block(kListThreads);
-        fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(G, R, static_cast<int>(V), ldz, token_ids + a,
-                                                         listed->ids + a * list_k, list_k, logp + a, coef, c2, g_rest,
-                                                         p_list, h_list);
+        fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(G, R, static_cast<int>(V), ldz, tok, lids, list_k, lp_o, coef,
+                                                         c2, g_rest, p_list, h_list);
         if ((st = launched()) != FOPD_OK) return st;
       }
     }
     // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
-    if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dhidden + a * lddh, lddh, 5, s)) != FOPD_OK) return st;
+    if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dH, lddhc, 5, s, live)) != FOPD_OK) return st;
     // dL/dweight: vocabulary x hidden, contraction over the chunk's rows, both operands as they are stored; the
     // gradient rows past the chunk's end, up to a multiple of 64, are zero
     if (Rp > R) {
@@ -1336,7 +1425,8 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
       if ((st = launched()) != FOPD_OK) return st;
     }
     const bool acc = (ci > 0) || (accumulate_dweight != 0);
-    if ((st = launch_gemm_tn(acc, Hc, ldh, d, R, G, ldz, V, Rp, dweight, lddw, 6, s)) != FOPD_OK) return st;
+    if ((st = launch_gemm_tn(acc, Hc, ldhc, d, R, G, ldz, V, Rp, dweight, lddw, 6, s, live)) != FOPD_OK) return st;
+    if ((st = scatter()) != FOPD_OK) return st;
     ++ci;
   }
   fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);
@@ -1401,6 +1491,11 @@ fopd_status fopd_set_option(const char* name, int value) {
   if (key == "k14_regs_grid") {
     if (value < 0 || value > 4096) return FOPD_EINVAL;
     g_opt.k14_regs_grid = value;
+    return FOPD_OK;
+  }
+  if (key == "lm_head_compact") {
+    if (value != 0 && value != 1) return FOPD_EINVAL;
+    g_opt.lm_head_compact = value;
     return FOPD_OK;
   }
   if (key == "k14_rows_per_cu") {

@@ -79,7 +79,8 @@ template <bool ACCUMULATE, int PROBE = 0, int WM = kGemmWavesM, int WN = kGemmWa
           int VIA_REGS = kGemmStaging>
 __global__ void __launch_bounds__(64 * WM * WN)
 fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __restrict__ Bn, int64_t ldb, int N,
-             int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
+             int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n,
+             const int* __restrict__ n_live) {
   extern __shared__ __align__(16) unsigned char gemm_smem[];
   constexpr int WAVES = WM * WN;
   constexpr int TI = 8 / WM;                   // 32-row blocks along m per wavefront
@@ -98,8 +99,20 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int m_blocks = (tiles_m + 7) >> 3;
   const int round = slot >> 5;
-  const int tile_m = ((round % m_blocks) << 3) + ((slot >> 2) & 7);
-  const int tile_n = ((((round / m_blocks) << 3) + xcd) << 2) + (slot & 3);
+  int tile_m = ((round % m_blocks) << 3) + ((slot >> 2) & 7);
+  int tile_n = ((((round / m_blocks) << 3) + xcd) << 2) + (slot & 3);
+  if (n_live != nullptr) {
+    // Only the first *n_live rows of Bn count (a device-side count: the launch covers all N): tiles past them are
+    // left out, and the groups of 4 x 8 tiles are dealt to the XCDs in turn, the groups along n fastest, so that
+    // the XCDs stay evenly loaded whatever the count is.
+    const int live = *n_live;
+    if (live <= 0) return;
+    tiles_n = min(tiles_n, (live + TN - 1) / TN);
+    const int quads = (tiles_n + 3) >> 2;
+    const int unit = (round << 3) + xcd;
+    tile_m = ((unit / quads) << 3) + ((slot >> 2) & 7);
+    tile_n = ((unit % quads) << 2) + (slot & 3);
+  }
   if (tile_m >= tiles_m || tile_n >= tiles_n) return;      // whole workgroup, before any barrier
   const int m0 = tile_m * kGemmTile, n0 = tile_n * TN;
 
@@ -471,9 +484,17 @@ __device__ __forceinline__ bf16x8 tn_read_fragment(const unsigned char* p) {
 template <bool ACCUMULATE, int SCHED = 2>
 __global__ void __launch_bounds__(kGemmThreads)
 fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, const __bf16* __restrict__ Bk, int64_t ldb,
-             int N, int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n) {
+             int N, int K, float* __restrict__ Out, int64_t ldo, int tiles_m, int tiles_n,
+             const int* __restrict__ k_live) {
   extern __shared__ __align__(16) unsigned char gemm_smem[];
   constexpr int WM = kGemmWavesM, WN = kGemmWavesN, TI = 8 / WM, TJ = 8 / WN;
+  if (k_live != nullptr) {
+    // only the first *k_live rows of the operands count (a device-side count; the rows after them, up to the next
+    // multiple of 64, hold zeros in Bk and finite values in Ak)
+    const int live = *k_live;
+    if (ACCUMULATE && live <= 0) return;
+    K = min(K, max(64, (live + 63) & ~63));
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
@@ -664,9 +685,13 @@ fopd_transpose_bf16(const uint16_t* __restrict__ in, int64_t ld_in, int rows, in
 __global__ void __launch_bounds__(kGradThreads)
 fopd_k4_grad_wide(const float* __restrict__ Z, int64_t ldz, uint16_t* __restrict__ G, int64_t ldg, int V,
                   const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
-                  const float* __restrict__ logp, const float* __restrict__ coef) {
+                  const float* __restrict__ logp, const float* __restrict__ coef,
+                  const int* __restrict__ n_live) {
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x;
+  // rows past the live ones, rounded up to the 64-row step of the contraction over rows (which takes at least one
+  // step), are read by nobody
+  if (n_live != nullptr && t >= max(64, (*n_live + 63) & ~63)) return;
   const float c = coef[t];
   const int y = token_ids[t];
   uint16_t* orow = G + t * ldg;
@@ -711,6 +736,109 @@ fopd_k4_grad_wide(const float* __restrict__ Z, int64_t ldz, uint16_t* __restrict
 __global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld, int cols) {
   float* row = out + static_cast<int64_t>(blockIdx.x) * ld;
   for (int c = threadIdx.x; c < cols; c += 256) row[c] = 0.f;
+}
+
+// ---- rows that take part (mask != 0) moved to the front of a chunk, so that the contractions skip the others ----
+// Masked rows (observations, prompts) have no log-prob and no gradient row: the chunk's per-row inputs and hidden
+// states are gathered into dense arrays of the live rows, every kernel of the chunk runs on those, and the per-row
+// outputs and dL/dhidden rows are scattered back (zeros at masked rows).  The live count stays on the device: the
+// launches cover the whole chunk, the contraction kernels read the count and leave out the tiles past it.
+
+constexpr int kLiveScanThreads = 1024;
+
+// One workgroup.  mask = the chunk's first row (NULL: every row is live).  ex[j] = live rows before chunk row j,
+// j = 0 .. R; row_map[c] = chunk row of compact row c; n_live[0] = ex[R]; cu_c[i] = ex[clamp(cu[i] - row_begin, 0, R)],
+// i = 0 .. B: the samples' offsets among the chunk's live rows.
+__global__ void __launch_bounds__(kLiveScanThreads)
+fopd_live_scan(const uint8_t* __restrict__ mask, int R, const int64_t* __restrict__ cu, int B, int64_t row_begin,
+               int* __restrict__ ex, int* __restrict__ row_map, int* __restrict__ n_live, int64_t* __restrict__ cu_c) {
+  __shared__ int sh[kLiveScanThreads];
+  const int tid = threadIdx.x;
+  const int per = (R + kLiveScanThreads - 1) / kLiveScanThreads;
+  const int lo = min(tid * per, R), hi = min(lo + per, R);
+  int local = 0;
+  for (int j = lo; j < hi; ++j) local += (mask == nullptr || mask[j] != 0) ? 1 : 0;
+  sh[tid] = local;
+  __syncthreads();
+  for (int off = 1; off < kLiveScanThreads; off <<= 1) {     // inclusive scan of the per-thread counts
+    const int add = (tid >= off) ? sh[tid - off] : 0;
+    __syncthreads();
+    sh[tid] += add;
+    __syncthreads();
+  }
+  int run = sh[tid] - local;
+  for (int j = lo; j < hi; ++j) {
+    ex[j] = run;
+    if (mask == nullptr || mask[j] != 0) row_map[run++] = j;
+  }
+  if (tid == kLiveScanThreads - 1) {
+    ex[R] = sh[tid];
+    n_live[0] = sh[tid];
+  }
+  __syncthreads();                                           // ex[] of the other lanes is visible from here on
+  for (int i = tid; i <= B; i += kLiveScanThreads) {
+    int64_t j = cu[i] - row_begin;
+    j = j < 0 ? 0 : (j > R ? R : j);
+    cu_c[i] = ex[j];
+  }
+}
+
+// Compact row c = blockIdx.x of the chunk (c < R): the per-row inputs and the hidden row of chunk row row_map[c], or,
+// past the live rows, a masked row of zeros.  Pointers are to the chunk's first row; teacher_logp, teacher_stale and
+// the list may be NULL (then so are their outputs' uses).  d % 8 == 0.
+__global__ void __launch_bounds__(256)
+fopd_live_gather(const int* __restrict__ row_map, const int* __restrict__ n_live, const int32_t* __restrict__ token_ids,
+                 const uint8_t* __restrict__ mask, const float* __restrict__ behav_logp,
+                 const float* __restrict__ teacher_logp, const float* __restrict__ teacher_stale,
+                 const int32_t* __restrict__ list_ids, const float* __restrict__ list_logp, int k,
+                 const uint16_t* __restrict__ hidden, int64_t ldh, int d, int32_t* __restrict__ token_ids_c,
+                 uint8_t* __restrict__ mask_c, float* __restrict__ behav_c, float* __restrict__ teacher_c,
+                 float* __restrict__ stale_c, int32_t* __restrict__ list_ids_c, float* __restrict__ list_logp_c,
+                 uint16_t* __restrict__ hidden_c) {
+  const int64_t c = blockIdx.x;
+  const int tid = threadIdx.x;
+  const bool live = c < n_live[0];
+  const int64_t j = live ? row_map[c] : 0;
+  if (tid == 0) {
+    token_ids_c[c] = live ? token_ids[j] : 0;
+    mask_c[c] = live ? (mask != nullptr ? mask[j] : static_cast<uint8_t>(1)) : static_cast<uint8_t>(0);
+    behav_c[c] = live ? behav_logp[j] : 0.f;
+    if (teacher_logp != nullptr) teacher_c[c] = live ? teacher_logp[j] : 0.f;
+    if (teacher_stale != nullptr) stale_c[c] = live ? teacher_stale[j] : 0.f;
+  }
+  if (list_ids != nullptr) {
+    for (int q = tid; q < k; q += 256) {
+      list_ids_c[c * k + q] = live ? list_ids[j * k + q] : -1;
+      list_logp_c[c * k + q] = live ? list_logp[j * k + q] : 0.f;
+    }
+  }
+  const u32x4* src = reinterpret_cast<const u32x4*>(hidden + j * ldh);
+  u32x4* dst = reinterpret_cast<u32x4*>(hidden_c + c * d);
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  for (int v = tid; v < d / 8; v += 256) dst[v] = live ? src[v] : zero;
+}
+
+// Chunk row j = blockIdx.x (j < R) gets its outputs back: the compact row ex[j] if the row is live, zeros if not.
+// token_loss / token_loss_c and dhidden / dhidden_c may be NULL.
+__global__ void __launch_bounds__(256)
+fopd_live_scatter(const int* __restrict__ ex, const float* __restrict__ logp_c, const float* __restrict__ lse_c,
+                  const float* __restrict__ token_loss_c, const float* __restrict__ dhidden_c, int d,
+                  float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ token_loss,
+                  float* __restrict__ dhidden, int64_t lddh) {
+  const int64_t j = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int c = ex[j];
+  const bool live = ex[j + 1] > c;
+  if (tid == 0) {
+    logp[j] = live ? logp_c[c] : 0.f;
+    lse[j] = live ? lse_c[c] : 0.f;
+    if (token_loss != nullptr) token_loss[j] = live ? token_loss_c[c] : 0.f;
+  }
+  if (dhidden != nullptr) {
+    const float* src = dhidden_c + static_cast<int64_t>(c) * d;
+    float* dst = dhidden + j * lddh;
+    for (int v = tid; v < d; v += 256) dst[v] = live ? src[v] : 0.f;
+  }
 }
 
 // loss = sum of the per-chunk shares, in chunk order.

@@ -75,7 +75,7 @@ static int run(const char* name, const __bf16* A, int64_t lda, int M, const __bf
   float total = 0.f;
   for (int rep = 0; rep < 4; ++rep) {          // first launch is a warm-up
     CHECK(hipEventRecord(e0, 0));
-    kern<<<grid, 64 * WM * WN, lds>>>(A, lda, M, B, ldb, N, K, out, M, tiles_m, tiles_n);
+    kern<<<grid, 64 * WM * WN, lds>>>(A, lda, M, B, ldb, N, K, out, M, tiles_m, tiles_n, nullptr);
     CHECK(hipGetLastError());
     CHECK(hipEventRecord(e1, 0));
     CHECK(hipEventSynchronize(e1));
@@ -103,7 +103,7 @@ static int run_sustained(const __bf16* A, int64_t lda, int M, const __bf16* B, i
   const double flops = 2.0 * M * static_cast<double>(N) * K;
   for (int group = 0; group < groups; ++group) {
     CHECK(hipEventRecord(e0, 0));
-    for (int rep = 0; rep < 20; ++rep) kern<<<grid, 512, lds>>>(A, lda, M, B, ldb, N, K, out, M, tiles_m, tiles_n);
+    for (int rep = 0; rep < 20; ++rep) kern<<<grid, 512, lds>>>(A, lda, M, B, ldb, N, K, out, M, tiles_m, tiles_n, nullptr);
     CHECK(hipGetLastError());
     CHECK(hipEventRecord(e1, 0));
     CHECK(hipEventSynchronize(e1));
@@ -187,7 +187,7 @@ int main(int argc, char** argv) {
       float total = 0.f;
       for (int rep = 0; rep < 4; ++rep) {
         CHECK(hipEventRecord(e0, 0));
-        kern<<<grid, kGemmThreads, kTnLdsBytes>>>(B, 4096, 4096, 4096, A, 151936, 151936, 4096, out, 4096, tm, tn);
+        kern<<<grid, kGemmThreads, kTnLdsBytes>>>(B, 4096, 4096, 4096, A, 151936, 151936, 4096, out, 4096, tm, tn, nullptr);
         CHECK(hipGetLastError());
         CHECK(hipEventRecord(e1, 0));
         CHECK(hipEventSynchronize(e1));

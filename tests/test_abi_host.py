@@ -220,6 +220,9 @@ def test_set_option_checks_names_and_values():
     assert lib.fopd_set_option(b"k14_regs_grid", 512) == 0
     assert lib.fopd_set_option(b"k14_regs_grid", -1) == 1
     assert lib.fopd_set_option(b"k14_regs_grid", 5000) == 1
+    assert lib.fopd_set_option(b"lm_head_compact", 0) == 0
+    assert lib.fopd_set_option(b"lm_head_compact", 2) == 1
+    assert lib.fopd_set_option(b"lm_head_compact", 1) == 0
     assert lib.fopd_set_option(b"no_such_option", 1) == 1
     assert lib.fopd_set_option(None, 1) == 1
     # back to the defaults: the options are process-wide
@@ -349,5 +352,5 @@ def test_projection_loss_with_listed_teacher_rejects_bad_arguments_before_launch
     assert _lml_listed(lib, wsb=4096) == 5
     plain = fb.fopd_lm_head_loss_workspace_bytes(128, 100, 64, 2, 64)
     listed = fb.fopd_lm_head_loss_topk_workspace_bytes(128, 100, 64, 2, 64, 4)
-    assert listed > plain and listed - plain < 128 * 4 + 64 * 4 * (3 + 2 * 4) + 6 * 256 + 1
+    assert listed > plain and listed - plain < 128 * 4 + 64 * 4 * (3 + 4 * 4) + 8 * 256 + 1
     assert _lml_listed(lib, wsb=listed - 1) == 5

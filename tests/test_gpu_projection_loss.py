@@ -502,3 +502,92 @@ def test_projection_scores_only_calls_give_the_full_calls_scores():
                                      w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, o["fresh"], None,
                                      None, g, rows_chunk, o["loss"], o["weights"], o["logp"], o["lse"], None, d, None, d,
                                      False, ws)
+
+
+# ---------------------------------------------------------------------------------------
+# masked spans (observations, prompts): their rows are left out of the contractions
+# ---------------------------------------------------------------------------------------
+
+def _span_mask(T, dead, rs):
+    """All ones, then a few 2s and 3s (two aligned sets), then zeros on the given [start, stop) spans."""
+    m = rs.choice([1, 1, 1, 2, 3], size=T).astype(np.uint8)
+    for a, b in dead:
+        m[a:b] = 0
+    return m
+
+
+def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
+    """Long masked spans, as the observation turns of a tool-use buffer: a first chunk with no live row at all, a
+    chunk in the middle with none, a masked tail, a sample with no live row.  The three forms of the pass (scores
+    supplied, scores formed inside, listed teacher) against the oracle, then each against itself with the
+    compaction of live rows switched off: the same log-probs, scores, loss and dhidden rows bit for bit (each row's
+    contraction does not depend on where the row sits), dweight up to the order of the fp32 sum over rows."""
+    seq, d, V, k, rows_chunk = (300, 90, 260, 250), 128, 3000, 9, 128
+    T, B = sum(seq), len(seq)
+    rs = np.random.RandomState(77)
+    dead = [(0, 150), (200, 230), (300, 390), (512, 640), (700, 701), (880, 900)]
+    _say("masked spans %s of T=%d rows, samples %s, chunks of %d rows" % (dead, T, list(seq), rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=31)
+    h["mask"] = torch.from_numpy(_span_mask(T, dead, rs)).to(DEV)
+    w = wl.attach_loss_inputs(h, seq, [0, 1, 3, 2], seed=31, teacher_list=(k, 0.6))
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
+    f32 = dict(dtype=torch.float32, device=DEV)
+
+    def scored(chunk):
+        f = _scores_from_the_oracle(w, hp)
+        out = _run(w, hp, g, chunk, f, pad_h=4)
+        return out, f
+
+    def unscored(chunk):
+        ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, chunk))
+        out = dict(loss=torch.full((1,), 7.0, **f32), weights=torch.full((B,), 7.0, **f32),
+                   freshness=torch.full((B,), 7.0, **f32), logp=torch.full((T,), 7.0, **f32),
+                   lse=torch.full((T,), 7.0, **f32), dhidden=torch.full((T, d), 7.0, **f32),
+                   dweight=torch.full((V, d), 7.0, **f32))
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None, None,
+                                     g, chunk, out["loss"], out["weights"], out["logp"], out["lse"], out["dhidden"], d,
+                                     out["dweight"], d, False, ws, seq_lens_host=w["seq_lens_host"],
+                                     freshness=out["freshness"])
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+        return out
+
+    def listed(chunk):
+        ws = _aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, chunk, k))
+        out = dict(loss=torch.full((1,), 7.0, **f32), freshness=torch.full((B,), 7.0, **f32),
+                   weights=torch.full((B,), 7.0, **f32), logp=torch.full((T,), 7.0, **f32),
+                   lse=torch.full((T,), 7.0, **f32), tl=torch.full((T,), 7.0, **f32),
+                   dhidden=torch.full((T, d), 7.0, **f32), dweight=torch.full((V, d), 7.0, **f32))
+        fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+            w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
+            w["list_ids"], w["list_logp"], k, 1e-4, None, None, w["seq_lens"], w["lag"], B, hp, w["seq_lens_host"], g,
+            chunk, out["loss"], out["freshness"], out["weights"], out["logp"], out["lse"], out["tl"], out["dhidden"], d,
+            out["dweight"], d, False, ws)
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+        return out
+
+    # against the oracle
+    out_s, f = scored(rows_chunk)
+    ref = _compare(w, hp, g, out_s, f)
+    assert ref["weights"][1] == 0.0 and float(out_s["weights"][1]) == 0.0          # the sample with no live row
+    dead_rows = torch.from_numpy(np64(w["mask"]) == 0).to(DEV)
+    assert not bool(out_s["logp"][dead_rows].any()) and not bool(out_s["lse"][dead_rows].any())
+    out_u = unscored(320)
+    _compare(w, hp, g, out_u, np64(out_u["freshness"]).astype(np.float32))
+    _listed_run_and_compare(w, seq, d, V, k, 320, hp, g, 1e-4)
+    out_l = listed(320)
+    # against the same calls on all rows
+    try:
+        fb.fopd_set_option("lm_head_compact", 0)
+        all_s, _ = scored(rows_chunk)
+        all_u, all_l = unscored(320), listed(320)
+    finally:
+        fb.fopd_set_option("lm_head_compact", 1)
+    for name, got, want in (("scores supplied", out_s, all_s), ("scores formed inside", out_u, all_u),
+                            ("listed teacher", out_l, all_l)):
+        for key in sorted(set(got) & set(want) - {"ws", "dweight"}):
+            assert torch.equal(got[key], want[key]), (name, key)
+        scale = float(want["dweight"].abs().max())
+        assert torch.allclose(got["dweight"], want["dweight"], rtol=1e-4, atol=1e-6 * scale), name
