@@ -283,8 +283,10 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     steps = args.steps if steps is None else steps
     rows_chunk = args.rows_chunk if rows_chunk is None else rows_chunk
     seq_lens, mask = wl.structure_only(args.workload, seed=0)
-    lag = np.random.RandomState(0).randint(0, 5, size=len(seq_lens)).astype(np.int32)
-    T, d, V, B = int(seq_lens.sum()), 4096, int(wl.CONFIGS[args.workload]["V"]), len(seq_lens)
+    cfg = wl.CONFIGS[args.workload]              # lags over the workload's range (0 .. 4 where it states none)
+    lag = np.random.RandomState(0).randint(cfg.get("lag_lo", 0), cfg.get("lag_hi", 4) + 1,
+                                           size=len(seq_lens)).astype(np.int32)
+    T, d, V, B = int(seq_lens.sum()), 4096, int(cfg["V"]), len(seq_lens)
     w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, "cuda:0", seed=0), seq_lens, lag, seed=0,
                               teacher_list=(args.list_k, 0.5) if with_listed else None)
     w["mask"] = torch.from_numpy(mask).to("cuda:0")
@@ -310,9 +312,9 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     ws = aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
     loss, weights = torch.empty(1, **f32), torch.empty(B, **f32)
     dh, dw = torch.empty(T, d, **f32), torch.empty(V, d, **f32)
-    # masked rows are left out of the contractions unless --no-compact asks for every row to be projected
+    # masked rows are left out of the three contractions, and rows without a gradient (gated samples) out of the two
+    # gradient ones, unless --no-compact asks for every row to be projected
     fb.fopd_set_option("lm_head_compact", 0 if args.no_compact else 1)
-    live = T if args.no_compact else int((mask != 0).sum())
 
     def step():
         fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
@@ -378,11 +380,17 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     ldz = (V + 63) // 64 * 64
     rp = sum(((min(rows_chunk, T - a) + 63) // 64) * 64 for a in range(0, T, rows_chunk))
     # flops per call: logits, dhidden, dweight contractions.  Every row projected: what is issued, operand padding
-    # included; masked rows left out: the live rows' (the tiles' ragged ends are issued on top and not counted)
-    if live == T:
+    # included; else the live rows' for the logits and, for the two gradient contractions, those of the rows that
+    # have a gradient row (the tiles' ragged ends are issued on top and not counted)
+    w_host = weights.cpu().numpy()
+    row_w = np.repeat(w_host, seq_lens)
+    live = int((mask != 0).sum())
+    with_grad = int(((mask != 0) & (row_w > 0)).sum())
+    if args.no_compact or (live == T and with_grad == T):
+        live = with_grad = T
         flops = {4: 2.0 * T * V * d, 5: 2.0 * T * ldz * d, 6: 2.0 * rp * V * d}
     else:
-        flops = {4: 2.0 * live * V * d, 5: 2.0 * live * ldz * d, 6: 2.0 * live * V * d}
+        flops = {4: 2.0 * live * V * d, 5: 2.0 * with_grad * ldz * d, 6: 2.0 * with_grad * V * d}
     names = {4: "logits = hidden . weight^T", 5: "dhidden = dlogits . weight", 6: "dweight += dlogits^T . hidden"}
     kern, tot_ms = {}, 0.0
     for slot in (4, 5, 6):
@@ -400,7 +408,8 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
         "steps": steps, "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload + "+lm_head", "T_rows": T, "rows_with_mask_0": int((mask == 0).sum()),
-                   "masked_rows_left_out_of_the_contractions": not args.no_compact, "V": V, "d": d,
+                   "gated_samples": int((w_host == 0).sum()), "rows_of_gated_samples": int((row_w == 0).sum()),
+                   "rows_without_a_share_left_out_of_the_contractions": not args.no_compact, "V": V, "d": d,
                    "rows_chunk": rows_chunk, "chunks": n_chunks, "call": "fopd_lm_head_loss_fwd_bwd",
                    "scratch_GB": fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) / 1e9},
         "roofline": {"bound": "mfma", "kernel": "fopd_gemm_nt, fopd_gemm_tn (three contractions per chunk)",

@@ -452,11 +452,12 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
  *   "k14_regs_grid"    workgroups of that row-in-registers kernel, each walking rows in steps of the grid: 1..4096,
  *                      or 0 (default) for two per compute unit (one is resident at a time; the second half is
  *                      handed out as compute units finish).  The results do not depend on it.
- *   "lm_head_compact"  1 (default): fopd_lm_head_loss_fwd_bwd and fopd_lm_head_loss_fwd_bwd_topk_teacher, when given
- *                      a mask, move each chunk's rows with mask != 0 to the front and leave the others out of the
- *                      three contractions (the count stays on the device: no synchronisation); 0: every row of a
- *                      chunk is projected.  Per-row outputs and dhidden are the same bit for bit, dweight up to the
- *                      order of its fp32 sum over rows.
+ *   "lm_head_compact"  1 (default): fopd_lm_head_loss_fwd_bwd and fopd_lm_head_loss_fwd_bwd_topk_teacher move each
+ *                      chunk's rows with mask != 0 to the front and leave the others out of the three contractions,
+ *                      and the rows without a gradient (c_t = 0: samples of weight 0) out of the two gradient
+ *                      ones (the counts stay on the device: no synchronisation); 0: every row of a chunk goes
+ *                      through all three.  Per-row outputs and dhidden are the same bit for bit, dweight up to
+ *                      the order of its fp32 sum over rows.
  * Returns FOPD_EINVAL for an unknown name or a value outside the stated set.
  */
 fopd_status fopd_set_option(const char* name, int value);
@@ -498,8 +499,9 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  * contractions fold the rows into dhidden and dweight; then the scratch is reused.  All work is bf16 inputs with
  * fp32 accumulation; the result does not depend on rows_chunk except through the order of the fp32 sums over
  * rows in dweight.  Rows with mask == 0 (observations, prompts: no log-prob, no gradient row) cost no matrix work:
- * with a mask, each chunk's other rows are gathered to the front, the kernels run on those, and the per-row outputs
- * and dhidden rows are scattered back, zeros at the masked rows (option "lm_head_compact").
+ * each chunk's other rows are gathered to the front, the kernels run on those, and the per-row outputs and dhidden
+ * rows are scattered back, zeros at the masked rows; likewise the rows of samples of weight 0 are left out of the
+ * two gradient contractions (option "lm_head_compact").
  *
  * Scores, two ways:
  *   freshness_in != NULL  [B] f32 scores formed earlier (Algorithm 1 scores the buffer before its minibatch loop;

@@ -89,8 +89,9 @@ struct LmLossWorkspace {
   size_t token_loss = 0, c2 = 0, g_rest = 0, row_coef = 0, p_list = 0, h_list = 0;
   // the chunk's live rows moved to the front: prefix counts, row map, live count, sample offsets, then the dense
   // copies of the per-row inputs and outputs, of the hidden rows and of their gradient
+  // and, for the gradient side, the same among the live rows for those that have a gradient row
   size_t ex = 0, row_map = 0, n_live = 0, cu_c = 0, tok_c = 0, mask_c = 0, behav_c = 0, teach_c = 0, stale_c = 0,
-         logp_c = 0, lse_c = 0, tl_c = 0, ids_c = 0, llp_c = 0, h_c = 0, dh_c = 0;
+         logp_c = 0, lse_c = 0, tl_c = 0, ids_c = 0, llp_c = 0, h_c = 0, dh_c = 0, grad_ex = 0, h_g = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
   LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk, int32_t k = 0) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
@@ -139,6 +140,8 @@ struct LmLossWorkspace {
     tl_c = Workspace::take(off, r * sizeof(float));
     h_c = Workspace::take(off, r * dd * 2);
     dh_c = Workspace::take(off, r * dd * sizeof(float));
+    grad_ex = Workspace::take(off, (r + 1) * sizeof(int32_t));
+    h_g = Workspace::take(off, r * dd * 2);
     total = off;
   }
 };
@@ -997,10 +1000,10 @@ fopd_status fopd_loss_fwd_bwd_topk_teacher(const void* logits, fopd_dtype dt, in
   const dim3 grid(static_cast<unsigned>((T + kListRows - 1) / kListRows)), block(kListThreads);
   if (dt == FOPD_BF16)
     fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
-                                                     logp_use, c1, c2, g_rest, p_list, h_list);
+                                                     logp_use, c1, c2, g_rest, p_list, h_list, nullptr);
   else
     fopd_topk_fixup<FOPD_F32><<<grid, block, 0, s>>>(dlogits, T, static_cast<int>(V), ld, token_ids, list_ids, k,
-                                                    logp_use, c1, c2, g_rest, p_list, h_list);
+                                                    logp_use, c1, c2, g_rest, p_list, h_list, nullptr);
   return launched();
 }
 
@@ -1285,14 +1288,17 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   // the projection matrix with the vocabulary contiguous (zero beyond V), once per call
   if (grads && (st = launch_transpose(weight, ldw, V, d, Wt, ldz, ldz, s)) != FOPD_OK) return st;
 
-  // Masked rows have no log-prob and no gradient row: with a mask, each chunk's live rows are moved to the front
-  // (dense copies of the per-row inputs and of the hidden rows), every kernel of the chunk runs on those, the
-  // contractions read the live count on the device and leave out the tiles past it, and the per-row outputs and
-  // dL/dhidden rows are scattered back.
-  const bool compact = (mask != nullptr) && (current_options().lm_head_compact != 0);
+  // Masked rows have no log-prob and no gradient row: each chunk's live rows are moved to the front (dense copies
+  // of the per-row inputs and of the hidden rows), every kernel of the chunk runs on those, the contractions read
+  // the live count on the device and leave out the tiles past it, and the per-row outputs are scattered back.  The
+  // gradient side is made dense once more when the coefficients are known: rows with c_t = 0 (samples the freshness
+  // weight gates out, rows outside both aligned sets' reach) get no gradient row and cost no matrix work either.
+  const bool compact = (current_options().lm_head_compact != 0);
   int32_t* ex = at<int32_t>(workspace, lay.ex);
   int32_t* row_map = at<int32_t>(workspace, lay.row_map);
   int32_t* n_live = at<int32_t>(workspace, lay.n_live);
+  int32_t* n_grad = n_live + 1;
+  int32_t* grad_ex = at<int32_t>(workspace, lay.grad_ex);
   int64_t* cu_c = at<int64_t>(workspace, lay.cu_c);
   const float* stale = (listed != nullptr) ? listed->teacher_logp_stale : nullptr;
 
@@ -1319,7 +1325,8 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     int64_t a_k = a;
     const int* live = nullptr;
     if (compact) {
-      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, static_cast<int>(R), cu, B, a, ex, row_map, n_live, cu_c);
+      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, nullptr, nullptr, static_cast<int>(R), cu, B, a, ex, row_map,
+                                                    n_live, cu_c);
       if ((st = launched()) != FOPD_OK) return st;
       fopd_live_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(
           row_map, n_live, tok, msk, bl, tq, (stale != nullptr) ? stale + a : nullptr, lids, llp, list_k,
@@ -1331,7 +1338,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
       Hc = at<__bf16>(workspace, lay.h_c);
       ldhc = d;
       tok = at<int32_t>(workspace, lay.tok_c);
-      msk = at<uint8_t>(workspace, lay.mask_c);
+      msk = at<uint8_t>(workspace, lay.mask_c);      // (never NULL from here on: the rows behind the live ones are masked)
       bl = at<float>(workspace, lay.behav_c);
       if (tq != nullptr) tq = at<float>(workspace, lay.teach_c);
       if (listed != nullptr) {
@@ -1351,7 +1358,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     auto scatter = [&]() -> fopd_status {
       if (!compact) return FOPD_OK;
       fopd_live_scatter<<<static_cast<unsigned>(R), 256, 0, s>>>(
-          ex, lp_o, ls_o, tl_o, dH, static_cast<int>(d), logp + a, lse + a,
+          ex, lp_o, ls_o, tl_o, grad_ex, dH, static_cast<int>(d), logp + a, lse + a,
           (listed != nullptr && listed->token_loss != nullptr) ? listed->token_loss + a : nullptr,
           grads ? dhidden + a * lddh : nullptr, lddh);
       return launched();
@@ -1401,31 +1408,52 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
       ++ci;
       continue;
     }
+    const int32_t* gex = nullptr;        // the rows that have a gradient row, counted among the chunk's (live) rows
+    const __bf16* Hg = Hc;               // their hidden rows
+    int64_t rows_hg = R;
+    if (compact) {
+      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(nullptr, coef, (listed != nullptr) ? c2 : nullptr,
+                                                    static_cast<int>(R), nullptr, -1, 0, grad_ex, nullptr, n_grad,
+                                                    nullptr);
+      if ((st = launched()) != FOPD_OK) return st;
+      fopd_grad_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(grad_ex, reinterpret_cast<const uint16_t*>(Hc), ldhc,
+                                                               static_cast<int>(d), at<uint16_t>(workspace, lay.h_g));
+      if ((st = launched()) != FOPD_OK) return st;
+      gex = grad_ex;
+      Hg = at<__bf16>(workspace, lay.h_g);
+      rows_hg = Rp;
+      live = n_grad;
+    }
     {
       ScopedTimer timer(1, s);
       fopd_k4_grad_wide<<<static_cast<unsigned>(R), kGradThreads, 0, s>>>(
           Z, ldz, reinterpret_cast<uint16_t*>(G), ldz, static_cast<int>(V), tok, ls_o, lp_o,
-          (listed != nullptr) ? row_coef : coef, live);
+          (listed != nullptr) ? row_coef : coef, gex);
       if ((st = launched()) != FOPD_OK) return st;
       if (listed != nullptr) {
         // the k listed entries of each row and the sampled token's, in the bf16 rows just written
         const dim3 grid(static_cast<unsigned>((R + kListRows - 1) / kListRows)), block(kListThreads);
         fopd_topk_fixup<FOPD_BF16><<<grid, block, 0, s>>>(G, R, static_cast<int>(V), ldz, tok, lids, list_k, lp_o, coef,
-                                                         c2, g_rest, p_list, h_list);
+                                                         c2, g_rest, p_list, h_list, gex);
         if ((st = launched()) != FOPD_OK) return st;
       }
     }
-    // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
-    if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dH, lddhc, 5, s, live)) != FOPD_OK) return st;
-    // dL/dweight: vocabulary x hidden, contraction over the chunk's rows, both operands as they are stored; the
-    // gradient rows past the chunk's end, up to a multiple of 64, are zero
-    if (Rp > R) {
+    // the contraction over rows reads whole steps of 64 rows: zeros behind the last gradient row
+    if (compact) {
+      fopd_grad_tail_zero<<<64, 256, 0, s>>>(n_grad, reinterpret_cast<uint16_t*>(G), ldz,
+                                             at<uint16_t>(workspace, lay.h_g), static_cast<int>(d));
+      if ((st = launched()) != FOPD_OK) return st;
+    } else if (Rp > R) {
       fopd_fill_zero_f32<<<static_cast<unsigned>(Rp - R), 256, 0, s>>>(reinterpret_cast<float*>(G + R * ldz), ldz / 2,
                                                                      static_cast<int>(ldz / 2));
       if ((st = launched()) != FOPD_OK) return st;
     }
+    // dL/dhidden of the chunk: rows x hidden, contraction over the vocabulary
+    if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dH, lddhc, 5, s, live)) != FOPD_OK) return st;
+    // dL/dweight: vocabulary x hidden, contraction over the chunk's rows, both operands as they are stored
     const bool acc = (ci > 0) || (accumulate_dweight != 0);
-    if ((st = launch_gemm_tn(acc, Hc, ldhc, d, R, G, ldz, V, Rp, dweight, lddw, 6, s, live)) != FOPD_OK) return st;
+    if ((st = launch_gemm_tn(acc, Hg, compact ? d : ldhc, d, rows_hg, G, ldz, V, Rp, dweight, lddw, 6, s, live)) != FOPD_OK)
+      return st;
     if ((st = scatter()) != FOPD_OK) return st;
     ++ci;
   }

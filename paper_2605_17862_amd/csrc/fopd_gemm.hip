@@ -681,20 +681,24 @@ fopd_transpose_bf16(const uint16_t* __restrict__ in, int64_t ld_in, int rows, in
 // Gradient rows of one chunk from fp32 logits (ldz floats per row) to bf16 (ldg entries per row):
 //   g[t, v] = c_t (exp(z[t, v] - lse_t) - [v == y_t]),  columns V .. ldg - 1 written as zeros
 // (they are the zero padding of the contraction that follows).  One workgroup per row; rows with c_t == 0 or
-// an out-of-range token id are zero-filled without reading the logits.
+// an out-of-range token id are zero-filled without reading the logits.  With grad_ex (grad_ex[t] = rows that have
+// a gradient row before row t, t = 0 .. rows) the rows that have one (grad_ex[t + 1] > grad_ex[t]) are written
+// densely, row t to row grad_ex[t] of G, and the others not at all.
 __global__ void __launch_bounds__(kGradThreads)
 fopd_k4_grad_wide(const float* __restrict__ Z, int64_t ldz, uint16_t* __restrict__ G, int64_t ldg, int V,
                   const int32_t* __restrict__ token_ids, const float* __restrict__ lse,
                   const float* __restrict__ logp, const float* __restrict__ coef,
-                  const int* __restrict__ n_live) {
+                  const int* __restrict__ grad_ex) {
   const int64_t t = blockIdx.x;
   const int tid = threadIdx.x;
-  // rows past the live ones, rounded up to the 64-row step of the contraction over rows (which takes at least one
-  // step), are read by nobody
-  if (n_live != nullptr && t >= max(64, (*n_live + 63) & ~63)) return;
   const float c = coef[t];
   const int y = token_ids[t];
-  uint16_t* orow = G + t * ldg;
+  int64_t out = t;
+  if (grad_ex != nullptr) {
+    out = grad_ex[t];
+    if (grad_ex[t + 1] == out) return;
+  }
+  uint16_t* orow = G + out * ldg;
   u32x4* ov = reinterpret_cast<u32x4*>(orow);
   const int nvec_out = static_cast<int>(ldg / 8);
   if (c == 0.f || y < 0 || y >= V) {
@@ -738,26 +742,35 @@ __global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld
   for (int c = threadIdx.x; c < cols; c += 256) row[c] = 0.f;
 }
 
-// ---- rows that take part (mask != 0) moved to the front of a chunk, so that the contractions skip the others ----
+// ---- rows that take part moved to the front of a chunk, so that the contractions skip the others ----
 // Masked rows (observations, prompts) have no log-prob and no gradient row: the chunk's per-row inputs and hidden
-// states are gathered into dense arrays of the live rows, every kernel of the chunk runs on those, and the per-row
-// outputs and dL/dhidden rows are scattered back (zeros at masked rows).  The live count stays on the device: the
-// launches cover the whole chunk, the contraction kernels read the count and leave out the tiles past it.
+// states are gathered into dense arrays of the live rows (mask != 0), every kernel of the chunk runs on those, and
+// the per-row outputs are scattered back (zeros at masked rows).  Once the coefficients are known the same is done
+// again for the gradient side: only the rows with c_t != 0 (not those of samples the freshness weight gates out)
+// get a gradient row, written densely, and the two gradient contractions run on those.  The counts stay on the
+// device: the launches cover the whole chunk, the contraction kernels read the count and leave out the rest.
 
 constexpr int kLiveScanThreads = 1024;
 
-// One workgroup.  mask = the chunk's first row (NULL: every row is live).  ex[j] = live rows before chunk row j,
-// j = 0 .. R; row_map[c] = chunk row of compact row c; n_live[0] = ex[R]; cu_c[i] = ex[clamp(cu[i] - row_begin, 0, R)],
-// i = 0 .. B: the samples' offsets among the chunk's live rows.
+// One workgroup.  A row is live if coef != NULL ? (coef[j] != 0 or, with coef2, coef2[j] != 0) : (mask == NULL ||
+// mask[j] != 0); mask / coef / coef2 point at the chunk's first row.  ex[j] = live rows before chunk row j, j = 0 .. R; row_map[c] = chunk row of compact row c
+// (row_map may be NULL); n_live[0] = ex[R]; cu_c[i] = ex[clamp(cu[i] - row_begin, 0, R)], i = 0 .. B: the samples'
+// offsets among the chunk's live rows (B < 0: none wanted).
 __global__ void __launch_bounds__(kLiveScanThreads)
-fopd_live_scan(const uint8_t* __restrict__ mask, int R, const int64_t* __restrict__ cu, int B, int64_t row_begin,
-               int* __restrict__ ex, int* __restrict__ row_map, int* __restrict__ n_live, int64_t* __restrict__ cu_c) {
+fopd_live_scan(const uint8_t* __restrict__ mask, const float* __restrict__ coef, const float* __restrict__ coef2, int R,
+               const int64_t* __restrict__ cu,
+               int B, int64_t row_begin, int* __restrict__ ex, int* __restrict__ row_map, int* __restrict__ n_live,
+               int64_t* __restrict__ cu_c) {
   __shared__ int sh[kLiveScanThreads];
   const int tid = threadIdx.x;
   const int per = (R + kLiveScanThreads - 1) / kLiveScanThreads;
   const int lo = min(tid * per, R), hi = min(lo + per, R);
+  auto is_live = [&](int j) {
+    if (coef != nullptr) return coef[j] != 0.f || (coef2 != nullptr && coef2[j] != 0.f);
+    return mask == nullptr || mask[j] != 0;
+  };
   int local = 0;
-  for (int j = lo; j < hi; ++j) local += (mask == nullptr || mask[j] != 0) ? 1 : 0;
+  for (int j = lo; j < hi; ++j) local += is_live(j) ? 1 : 0;
   sh[tid] = local;
   __syncthreads();
   for (int off = 1; off < kLiveScanThreads; off <<= 1) {     // inclusive scan of the per-thread counts
@@ -769,7 +782,10 @@ fopd_live_scan(const uint8_t* __restrict__ mask, int R, const int64_t* __restric
   int run = sh[tid] - local;
   for (int j = lo; j < hi; ++j) {
     ex[j] = run;
-    if (mask == nullptr || mask[j] != 0) row_map[run++] = j;
+    if (is_live(j)) {
+      if (row_map != nullptr) row_map[run] = j;
+      ++run;
+    }
   }
   if (tid == kLiveScanThreads - 1) {
     ex[R] = sh[tid];
@@ -818,13 +834,43 @@ fopd_live_gather(const int* __restrict__ row_map, const int* __restrict__ n_live
   for (int v = tid; v < d / 8; v += 256) dst[v] = live ? src[v] : zero;
 }
 
-// Chunk row j = blockIdx.x (j < R) gets its outputs back: the compact row ex[j] if the row is live, zeros if not.
-// token_loss / token_loss_c and dhidden / dhidden_c may be NULL.
+// The hidden rows of the compact rows that have a gradient (grad_ex[c + 1] > grad_ex[c]), densely: row c of hidden_c
+// to row grad_ex[c] of hidden_g (d entries per row, d % 8 == 0).  Grid: one workgroup per compact row.
+__global__ void __launch_bounds__(256)
+fopd_grad_gather(const int* __restrict__ grad_ex, const uint16_t* __restrict__ hidden_c, int64_t ldh, int d,
+                 uint16_t* __restrict__ hidden_g) {
+  const int64_t c = blockIdx.x;
+  const int g = grad_ex[c];
+  if (grad_ex[c + 1] == g) return;
+  const u32x4* src = reinterpret_cast<const u32x4*>(hidden_c + c * ldh);
+  u32x4* dst = reinterpret_cast<u32x4*>(hidden_g + static_cast<int64_t>(g) * d);
+  for (int v = threadIdx.x; v < d / 8; v += 256) dst[v] = src[v];
+}
+
+// Zeros behind the rows that have a gradient, up to the next multiple of 64 (at least 64 rows in all): the
+// contraction over rows reads that far.  Row n_grad[0] + blockIdx.x of G (ldg entries, ldg % 8 == 0) and of hidden_g
+// (d entries); grid: 64 workgroups.
+__global__ void __launch_bounds__(256)
+fopd_grad_tail_zero(const int* __restrict__ n_grad, uint16_t* __restrict__ G, int64_t ldg,
+                    uint16_t* __restrict__ hidden_g, int d) {
+  const int n = n_grad[0];
+  const int64_t row = static_cast<int64_t>(n) + blockIdx.x;
+  if (row >= max(64, (n + 63) & ~63)) return;
+  const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+  u32x4* g = reinterpret_cast<u32x4*>(G + row * ldg);
+  for (int v = threadIdx.x; v < static_cast<int>(ldg / 8); v += 256) g[v] = zero;
+  u32x4* h = reinterpret_cast<u32x4*>(hidden_g + row * d);
+  for (int v = threadIdx.x; v < d / 8; v += 256) h[v] = zero;
+}
+
+// Chunk row j = blockIdx.x (j < R) gets its outputs back: those of compact row ex[j] if the row is live, zeros if
+// not; its dL/dhidden row is row grad_ex[ex[j]] of dhidden_g if the row has a gradient, zeros if not.
+// token_loss / token_loss_c and dhidden / dhidden_g / grad_ex may be NULL.
 __global__ void __launch_bounds__(256)
 fopd_live_scatter(const int* __restrict__ ex, const float* __restrict__ logp_c, const float* __restrict__ lse_c,
-                  const float* __restrict__ token_loss_c, const float* __restrict__ dhidden_c, int d,
-                  float* __restrict__ logp, float* __restrict__ lse, float* __restrict__ token_loss,
-                  float* __restrict__ dhidden, int64_t lddh) {
+                  const float* __restrict__ token_loss_c, const int* __restrict__ grad_ex,
+                  const float* __restrict__ dhidden_g, int d, float* __restrict__ logp, float* __restrict__ lse,
+                  float* __restrict__ token_loss, float* __restrict__ dhidden, int64_t lddh) {
   const int64_t j = blockIdx.x;
   const int tid = threadIdx.x;
   const int c = ex[j];
@@ -835,9 +881,11 @@ fopd_live_scatter(const int* __restrict__ ex, const float* __restrict__ logp_c, 
     if (token_loss != nullptr) token_loss[j] = live ? token_loss_c[c] : 0.f;
   }
   if (dhidden != nullptr) {
-    const float* src = dhidden_c + static_cast<int64_t>(c) * d;
+    const int g = live ? grad_ex[c] : 0;
+    const bool has = live && grad_ex[c + 1] > g;
+    const float* src = dhidden_g + static_cast<int64_t>(g) * d;
     float* dst = dhidden + j * lddh;
-    for (int v = tid; v < d; v += 256) dst[v] = live ? src[v] : 0.f;
+    for (int v = tid; v < d; v += 256) dst[v] = has ? src[v] : 0.f;
   }
 }
 

@@ -1607,19 +1607,19 @@ fopd_topk_row_coef(const float* c1, const float* c2, const float* g_rest, int64_
 // After the gradient stream has written c p_u everywhere (and c expm1(lp) at the sampled token): the k listed
 // entries become c1 (p_j - [j is the sampled token]) + c2 h_j, and the sampled token's entry, if it is not listed,
 // c1 (p_y - 1) + c2 (G_rest - l_t) p_y.  Rows without a token-loss share (c2 = 0) are already right.  One
-// wavefront per row.
+// wavefront per row.  out_row != NULL: row t of the inputs is row out_row[t] of dlogits (gradient rows stored densely).
 template <int DT>
 __global__ void __launch_bounds__(kListThreads)
 fopd_topk_fixup(void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids, const int32_t* list_ids, int k,
                 const float* logp, const float* c1, const float* c2, const float* g_rest, const float* p_list,
-                const float* h_list) {
+                const float* h_list, const int* out_row) {
   const int64_t t = static_cast<int64_t>(blockIdx.x) * kListRows + (threadIdx.x >> 6);
   if (t >= T) return;
   const int lane = threadIdx.x & 63;
   const float a = c1[t], b = c2[t];
   const int y = token_ids[t];
   if (b == 0.f || y < 0 || y >= V) return;
-  char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+  char* orow = static_cast<char*>(dlogits) + (out_row != nullptr ? static_cast<int64_t>(out_row[t]) : t) * ld * Elem<DT>::kBytes;
   const float py_m1 = expm1f(logp[t]);                     // p_y - 1, accurate as p_y -> 1
   bool mine = false;
   for (int j = lane; j < k; j += 64) {

@@ -518,9 +518,10 @@ def _span_mask(T, dead, rs):
 
 def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
     """Long masked spans, as the observation turns of a tool-use buffer: a first chunk with no live row at all, a
-    chunk in the middle with none, a masked tail, a sample with no live row.  The three forms of the pass (scores
-    supplied, scores formed inside, listed teacher) against the oracle, then each against itself with the
-    compaction of live rows switched off: the same log-probs, scores, loss and dhidden rows bit for bit (each row's
+    chunk in the middle with none, a masked tail, a sample with no live row, and a sample that the freshness weight
+    gates out (log-probs but no gradient rows).  The three forms of the pass (scores supplied, scores formed inside,
+    listed teacher) against the oracle, then each against itself with the compaction of live rows and of gradient
+    rows switched off: the same log-probs, scores, loss and dhidden rows bit for bit (each row's
     contraction does not depend on where the row sits), dweight up to the order of the fp32 sum over rows."""
     seq, d, V, k, rows_chunk = (300, 90, 260, 250), 128, 3000, 9, 128
     T, B = sum(seq), len(seq)
@@ -529,7 +530,7 @@ def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
     _say("masked spans %s of T=%d rows, samples %s, chunks of %d rows" % (dead, T, list(seq), rows_chunk))
     h = wl.generate_lm_head(T, d, V, DEV, seed=31)
     h["mask"] = torch.from_numpy(_span_mask(T, dead, rs)).to(DEV)
-    w = wl.attach_loss_inputs(h, seq, [0, 1, 3, 2], seed=31, teacher_list=(k, 0.6))
+    w = wl.attach_loss_inputs(h, seq, [0, 1, 40, 2], seed=31, teacher_list=(k, 0.6))     # the third sample is gated
     hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
     f32 = dict(dtype=torch.float32, device=DEV)
 
@@ -572,6 +573,8 @@ def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
     out_s, f = scored(rows_chunk)
     ref = _compare(w, hp, g, out_s, f)
     assert ref["weights"][1] == 0.0 and float(out_s["weights"][1]) == 0.0          # the sample with no live row
+    assert ref["weights"][2] == 0.0 and float(out_s["weights"][2]) == 0.0          # the gated one: log-probs, no gradient
+    assert bool(out_s["logp"][400:500].any()) and not bool(out_s["dhidden"][390:650].any())
     dead_rows = torch.from_numpy(np64(w["mask"]) == 0).to(DEV)
     assert not bool(out_s["logp"][dead_rows].any()) and not bool(out_s["lse"][dead_rows].any())
     out_u = unscored(320)
