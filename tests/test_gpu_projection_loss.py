@@ -594,3 +594,68 @@ def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
             assert torch.equal(got[key], want[key]), (name, key)
         scale = float(want["dweight"].abs().max())
         assert torch.allclose(got["dweight"], want["dweight"], rtol=1e-4, atol=1e-6 * scale), name
+
+
+def test_projection_loss_replays_from_a_hip_graph_with_other_masks():
+    """The pass enqueues kernels only and keeps the counts of live rows and of gradient rows on the device, so a
+    captured call stays right when the mask behind it changes: three replays, each after the mask tensor was
+    overwritten (other masked spans; no row masked; every row masked), against eager calls on the same inputs."""
+    seq, d, V, rows_chunk = (150, 90, 200), 64, 2000, 128
+    T, B = sum(seq), len(seq)
+    rs = np.random.RandomState(5)
+    _say("HIP graph replay of the pass through the projection with the mask changed between replays")
+    h = wl.generate_lm_head(T, d, V, DEV, seed=41)
+    h["mask"] = torch.from_numpy(_span_mask(T, [(0, 130), (300, 340)], rs)).to(DEV)
+    w = wl.attach_loss_inputs(h, seq, [0, 40, 2], seed=41)
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 0.7
+    f32 = dict(dtype=torch.float32, device=DEV)
+    f_in = torch.tensor([0.9, 0.01, 0.3], **f32)                  # the second sample is gated
+
+    def outs():
+        return dict(loss=torch.full((1,), 7.0, **f32), weights=torch.full((B,), 7.0, **f32),
+                    freshness=torch.full((B,), 7.0, **f32), logp=torch.full((T,), 7.0, **f32),
+                    lse=torch.full((T,), 7.0, **f32), dhidden=torch.full((T, d), 7.0, **f32),
+                    dweight=torch.full((V, d), 7.0, **f32),
+                    ws=_aligned(max(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk),
+                                    fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, 256))))
+
+    def call(o, scores):
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, scores, None,
+                                     None, g, rows_chunk if scores is not None else 256, o["loss"], o["weights"],
+                                     o["logp"], o["lse"], o["dhidden"], d, o["dweight"], d, False, o["ws"],
+                                     seq_lens_host=None if scores is not None else w["seq_lens_host"],
+                                     freshness=o["freshness"])
+
+    e1, e2, g1, g2 = outs(), outs(), outs(), outs()
+    call(e1, f_in)                                                # (also sets the kernel attributes before the capture)
+    call(e2, None)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        call(g1, f_in)
+        call(g2, None)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    masks = [_span_mask(T, [(10, 20), (140, 260), (430, 440)], rs), np.ones(T, dtype=np.uint8),
+             np.zeros(T, dtype=np.uint8)]
+    for rep, m in enumerate(masks):
+        w["mask"].copy_(torch.from_numpy(m).to(DEV))              # the same tensor the graph reads
+        for o in (e1, e2, g1, g2):
+            o["dhidden"].fill_(float(rep))
+            o["loss"].fill_(9.0)
+        call(e1, f_in)
+        call(e2, None)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in (("scores supplied", g1, e1), ("scores formed inside", g2, e2)):
+            for key in sorted(set(got) - {"ws"}):
+                assert torch.equal(got[key], want[key]), (rep, name, key)
+            assert fb.fopd_workspace_status(got["ws"]) == (0, 0)
+        live = int((m != 0).sum())
+        assert bool(g1["dhidden"].any()) == (live > 0)
+        assert int((g1["logp"] != 0).sum()) <= live and not bool(g1["dhidden"][torch.from_numpy(m == 0).to(DEV)].any())
