@@ -66,6 +66,8 @@ constexpr int kGemmLdsBytes = gemm_lds_bytes(kGemmWavesN, 8 / kGemmWavesN);
 //   7  the wavefront raises its priority while it issues matrix instructions: no gain
 //   8  no result stores
 //   9  (results correct) non-temporal result stores
+//  14  (results correct) the first round of workgroups starts skewed in time (steps of 512 cycles inside an XCD), to
+//      spread the bursts of result stores: no gain (steps of 128 and 2048 cycles neither)
 //  10  (results correct) no scheduling group barriers: the order inside a slice is the scheduler's (memory instructions
 //      first); 11, 13: two other orders (fragment reads first; one memory instruction per gap)
 //
@@ -115,6 +117,14 @@ fopd_gemm_nt(const __bf16* __restrict__ Am, int64_t lda, int M, const __bf16* __
   }
   if (tile_m >= tiles_m || tile_n >= tiles_n) return;      // whole workgroup, before any barrier
   const int m0 = tile_m * kGemmTile, n0 = tile_n * TN;
+  if constexpr (PROBE == 14) {
+    // the workgroups of the first round start a little apart (those of one XCD 0 .. 31 steps of 512 cycles), so that
+    // the result stores of the compute units do not all fall into the same few microseconds
+    if (blockIdx.x < 256) {
+      const int steps = (blockIdx.x >> 3) & 31;
+      for (int i = 0; i < steps; ++i) __builtin_amdgcn_s_sleep(8);
+    }
+  }
 
   // global -> LDS copy: see the projection kernel.  An operand tile of a stage is 16 wave instructions of 1 KB;
   // wavefront w issues instructions CPQ w .. CPQ w + CPQ - 1; instruction q fills rows 16 q .. 16 q + 15; lane i

@@ -164,6 +164,7 @@ int main(int argc, char** argv) {
   if (run<10, 2, 4, 2, 4>("  ... slice order left to the scheduler", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<11, 2, 4, 2, 4>("  ... fragment reads first in a slice", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run<13, 2, 4, 2, 4>("  ... one memory instruction per gap", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
+  if (run<14, 2, 4, 2, 4>("  ... first round skewed by 512 cycles", A, ld, M, B, ld, N, K, out, e0, e1)) return 1;
   if (run_sustained(A, ld, M, B, ld, N, K, out, groups, e0, e1)) return 1;
   printf("gemm_probe: tile 256 x 256, four wavefronts of 128 x 128\n");
   FOPD_PROBE_SET(2, 2, 4)
