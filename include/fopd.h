@@ -517,7 +517,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *
  *   hidden [T, ldh] bf16, weight [V, ldw] bf16, d a multiple of 64; token_ids, mask, behav_logp, teacher_logp,
  *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
- *   rows_chunk   rows per chunk, a multiple of 64 (scratch at V = 151,936, d = 4096: 8.7 GB for 8192 rows, 16.2 GB for 16384, which is 4 - 10 % faster)
+ *   rows_chunk   rows per chunk, a multiple of 64 (scratch at V = 151,936, d = 4096: 9.0 GB for 8192 rows, 16.7 GB for 16384, which is 4 - 10 % faster)
  *   loss [1], freshness [B] (may be NULL; a copy of freshness_in when that is given), weights [B] (may be NULL),
  *   logp [T], lse [T]: f32 outputs
  *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0.
