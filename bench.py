@@ -240,6 +240,9 @@ def bench_lm_head(args, torch, fb, wl, steps=None):
     fb.fopd_workspace_init(ws)
     logp = torch.empty(T, dtype=torch.float32, device="cuda:0")
     lse = torch.empty(T, dtype=torch.float32, device="cuda:0")
+    # masked rows are not projected unless --no-compact asks for every row
+    fb.fopd_set_option("lm_head_compact", 0 if args.no_compact else 1)
+    rows = T if args.no_compact else int((mask != 0).sum())
 
     def step():
         fb.fopd_lm_head_token_logprobs(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"],
@@ -261,14 +264,15 @@ def bench_lm_head(args, torch, fb, wl, steps=None):
         sys.exit("device flags set: %d" % flags)
     k7_ms, n7 = fb.fopd_profile_read(3)
     k7_s = k7_ms / max(n7, 1) * 1e-3
-    flops = 2.0 * T * V * d                             # every row is multiplied, masked or not
+    flops = 2.0 * rows * V * d                          # the rows that are projected
     return {
         "metric": "tokens/s, token log-probs from hidden states (projection fused, logits never stored), "
                   "V=%d d=%d bf16" % (V, d),
         "value": int((mask != 0).sum()) * steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
         "steps": steps, "warmup": args.warmup, "ms_per_step": elapsed / steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "V": V, "d": d,
+        "config": {"workload": args.workload + "+lm_head", "T_rows": T, "rows_with_mask_0": int((mask == 0).sum()),
+                   "masked_rows_projected": bool(args.no_compact), "V": V, "d": d,
                    "call": "fopd_lm_head_token_logprobs"},
         "roofline": {"bound": "mfma", "kernel": "fopd_k7_lm_head_lse", "achieved": flops / k7_s / 1e12,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": flops / k7_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
@@ -440,7 +444,7 @@ def main():
     ap.add_argument("--rows-chunk", type=int, default=16384,
                     help="rows per chunk of the loss pass through the projection (--variant lm_head_loss)")
     ap.add_argument("--no-compact", action="store_true",
-                    help="lm_head_loss: project every row of a chunk, masked ones included (option lm_head_compact = 0)")
+                    help="lm_head, lm_head_loss: project every row, masked ones included (option lm_head_compact = 0)")
     ap.add_argument("--list-k", type=int, default=64,
                     help="tokens per row of the stored teacher (--variant topk_teacher)")
     ap.add_argument("--variant", choices=("default", "full_kl", "full_teacher", "topk_teacher", "lm_head",

@@ -452,7 +452,8 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
  *   "k14_regs_grid"    workgroups of that row-in-registers kernel, each walking rows in steps of the grid: 1..4096,
  *                      or 0 (default) for two per compute unit (one is resident at a time; the second half is
  *                      handed out as compute units finish).  The results do not depend on it.
- *   "lm_head_compact"  1 (default): fopd_lm_head_loss_fwd_bwd and fopd_lm_head_loss_fwd_bwd_topk_teacher move each
+ *   "lm_head_compact"  1 (default): fopd_lm_head_token_logprobs projects only the rows with mask != 0;
+ *                      fopd_lm_head_loss_fwd_bwd and fopd_lm_head_loss_fwd_bwd_topk_teacher move each
  *                      chunk's rows with mask != 0 to the front and leave the others out of the three contractions,
  *                      and the rows without a gradient (c_t = 0: samples of weight 0) out of the two gradient
  *                      ones (the counts stay on the device: no synchronisation); 0: every row of a chunk goes
@@ -471,7 +472,9 @@ fopd_status fopd_set_option(const char* name, int value);
  *
  *   hidden      [T, ldh] bf16, ldh >= d           weight      [V, ldw] bf16, ldw >= d
  *   d           hidden size, a multiple of 64; T * ldh and V * ldw must each be below 2^31
- *   token_ids, mask, logp, lse: as in fopd_token_logprobs (masked rows give 0, 0)
+ *   token_ids, mask, logp, lse: as in fopd_token_logprobs (masked rows give 0, 0; they are not projected: the
+ *               kernel gathers the other rows through a row map and reads their count on the device, option
+ *               "lm_head_compact")
  *   workspace   fopd_lm_head_workspace_bytes(T) bytes, 256-byte aligned, initialised once with
  *               fopd_workspace_init; token ids outside [0, V) raise the same sticky flag
  *

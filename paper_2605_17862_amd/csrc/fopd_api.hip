@@ -52,13 +52,16 @@ struct Workspace {
 // Workspace of the projection-fused log-prob call: the same flag words, then one (reference, sum) pair per
 // strip and token, the tokens padded to whole tiles.
 struct LmWorkspace {
-  size_t flags, partial, t_pad, total;
+  size_t flags, n_live, partial, ex, row_map, t_pad, total;
   explicit LmWorkspace(int64_t T) {
     const size_t t = static_cast<size_t>(T < 0 ? 0 : T);
     t_pad = (t + kLmTile - 1) / kLmTile * kLmTile;
     flags = 0;
+    n_live = 128;                                        // the count of unmasked rows, on the device
     partial = 256;
-    total = align_up(partial + static_cast<size_t>(kLmStripsMax) * t_pad * sizeof(float2), 256);
+    ex = align_up(partial + static_cast<size_t>(kLmStripsMax) * t_pad * sizeof(float2), 256);
+    row_map = align_up(ex + (t + 1) * sizeof(int32_t), 256);
+    total = align_up(row_map + t * sizeof(int32_t), 256);
   }
 };
 
@@ -1064,16 +1067,27 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
   float2* partial = at<float2>(workspace, lay.partial);
   const __bf16* Wp = static_cast<const __bf16*>(weight);
   const __bf16* Hp = static_cast<const __bf16*>(hidden);
+  // Masked rows have no log-prob: with a mask only the other rows are projected.  Their count stays on the device;
+  // the kernel gathers them through a row map as it loads and leaves out the token tiles past the count.
+  int32_t *ex = nullptr, *row_map = nullptr, *n_live = nullptr;
+  if (mask != nullptr && current_options().lm_head_compact != 0) {
+    ex = at<int32_t>(workspace, lay.ex);
+    row_map = at<int32_t>(workspace, lay.row_map);
+    n_live = at<int32_t>(workspace, lay.n_live);
+    fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), nullptr, -1, 0, ex, row_map,
+                                                  n_live, nullptr);
+    if (launched() != FOPD_OK) return FOPD_EHIP;
+  }
   {
     ScopedTimer timer(3, s);
     kern<<<dim3(grid), dim3(kLmThreads), kLmLdsBytes, s>>>(Wp, ldw, Hp, ldh, static_cast<int>(T), static_cast<int>(V),
                                                     static_cast<int>(d), partial, n_token_tiles, n_vocab_tiles,
-                                                    n_strips, static_cast<int64_t>(lay.t_pad));
+                                                    n_strips, static_cast<int64_t>(lay.t_pad), row_map, n_live);
   }
   if (launched() != FOPD_OK) return FOPD_EHIP;
   fopd_k7_finish<<<dim3(static_cast<unsigned>((T + 3) / 4)), dim3(256), 0, s>>>(
       Wp, ldw, Hp, ldh, partial, n_strips, static_cast<int>(T), static_cast<int>(V), static_cast<int>(d),
-      static_cast<int64_t>(lay.t_pad), token_ids, mask, logp, lse, at<int32_t>(workspace, lay.flags));
+      static_cast<int64_t>(lay.t_pad), token_ids, mask, logp, lse, at<int32_t>(workspace, lay.flags), ex);
   return launched();
 }
 

@@ -83,7 +83,7 @@ __device__ __forceinline__ void lm_load_to_lds(const char* base, uint32_t voff, 
 __global__ void __launch_bounds__(kLmThreads)
 fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restrict__ H, int64_t ldh,
                     int T, int V, int d, float2* __restrict__ partial, int n_token_tiles, int n_vocab_tiles,
-                    int n_strips, int64_t t_pad) {
+                    int n_strips, int64_t t_pad, const int* __restrict__ row_map, const int* __restrict__ n_live) {
   extern __shared__ __align__(16) unsigned char lm_smem[];
   constexpr int WN = 4;                                // wavefronts along the tokens
   constexpr int NJ = 8 / WN;                           // 32-token blocks per wavefront
@@ -97,8 +97,21 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int strip_groups = n_strips >> 3;
   const int chunk_id = slot >> 5;
-  const int strip = ((chunk_id % strip_groups) << 3) + ((slot >> 2) & 7);
-  const int token_tile = ((((chunk_id / strip_groups) << 3) + xcd) << 2) + (slot & 3);
+  int strip = ((chunk_id % strip_groups) << 3) + ((slot >> 2) & 7);
+  int token_tile = ((((chunk_id / strip_groups) << 3) + xcd) << 2) + (slot & 3);
+  if (n_live != nullptr) {
+    // Only the rows row_map[0 .. *n_live - 1] of H take part (masked rows left out; the count stays on the device
+    // and the launch covers all T): token tile c holds compact rows 256 c .. 256 c + 255, gathered by the loads, and
+    // the groups of 4 token tiles x 8 strips are dealt to the XCDs in turn so that they stay evenly loaded.
+    T = *n_live;
+    if (T <= 0) return;
+    n_token_tiles = min(n_token_tiles, (T + kLmTile - 1) / kLmTile);
+    const int quads = (n_token_tiles + 3) >> 2;
+    const int unit = (chunk_id << 3) + xcd;
+    if (unit / quads >= strip_groups) return;
+    strip = ((unit / quads) << 3) + ((slot >> 2) & 7);
+    token_tile = ((unit % quads) << 2) + (slot & 3);
+  }
   if (token_tile >= n_token_tiles) return;             // whole workgroup, before any barrier
   const int vt_begin = static_cast<int>(static_cast<int64_t>(strip) * n_vocab_tiles / n_strips);
   const int vt_end = static_cast<int>(static_cast<int64_t>(strip + 1) * n_vocab_tiles / n_strips);
@@ -116,12 +129,15 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
   const int cp_chunk = (lane & 3) ^ ((lane >> 4) & 3);
   const int cp_lds = wave * 2048;                      // LDS offset of instruction 2 w inside the operand
   const char* Wb = reinterpret_cast<const char*>(W);
-  const char* Hb = reinterpret_cast<const char*>(H) + static_cast<int64_t>(t0) * ldh * 2;
+  const char* Hb = reinterpret_cast<const char*>(H) + (row_map != nullptr ? 0 : static_cast<int64_t>(t0) * ldh * 2);
   const uint32_t ldw2 = static_cast<uint32_t>(ldw) * 2u;
   uint32_t h_off[2];
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
-    h_off[q] = static_cast<uint32_t>(min(cp_row + 16 * q, T - 1 - t0)) * static_cast<uint32_t>(ldh) * 2u + cp_chunk * 16;
+  for (int q = 0; q < 2; ++q) {
+    const int r = min(cp_row + 16 * q, T - 1 - t0);
+    const uint32_t row = (row_map != nullptr) ? static_cast<uint32_t>(row_map[t0 + r]) : static_cast<uint32_t>(r);
+    h_off[q] = row * static_cast<uint32_t>(ldh) * 2u + cp_chunk * 16;
+  }
 
   // The two stages that hold vocabulary tile `vtile`, hidden elements ko .. ko + 63, travel through vector
   // registers in four quarters (ordinary 16-byte loads, then ds_write_b128 to LDS offset 1024 q + 16 lane of
@@ -340,12 +356,13 @@ fopd_k7_lm_head_lse(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __r
 
 // One wavefront per token: the sampled token's logit as a dot product of two rows (fp32 products of
 // bf16 are exact, the sum is fp32), then the merge of the strip pairs.  lp is clamped at 0 because
-// this dot product and the matrix cores sum the same products in different orders.
+// this dot product and the matrix cores sum the same products in different orders.  ex != NULL: only the unmasked
+// rows were projected, row t as compact row ex[t] (ex[t] = unmasked rows before row t).
 __global__ void __launch_bounds__(256)
 fopd_k7_finish(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restrict__ H, int64_t ldh,
                const float2* __restrict__ partial, int n_strips, int T, int V, int d, int64_t t_pad,
                const int32_t* __restrict__ token_ids, const uint8_t* __restrict__ mask,
-               float* __restrict__ logp, float* __restrict__ lse, int32_t* flags) {
+               float* __restrict__ logp, float* __restrict__ lse, int32_t* flags, const int* __restrict__ ex) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (t >= T) return;
@@ -376,10 +393,11 @@ fopd_k7_finish(const __bf16* __restrict__ W, int64_t ldw, const __bf16* __restri
   }
   dot = wave_sum(dot);
   if (lane == 0) {
-    float2 e = partial[t];
+    const int c = (ex != nullptr) ? ex[t] : t;           // the token's place among the rows that were projected
+    float2 e = partial[c];
     float m = e.x, s = e.y;
     for (int k = 1; k < n_strips; ++k) {
-      e = partial[static_cast<int64_t>(k) * t_pad + t];
+      e = partial[static_cast<int64_t>(k) * t_pad + c];
       lm_merge(m, s, e.x, e.y);
     }
     const double l = static_cast<double>(m) + log(static_cast<double>(s));

@@ -1484,6 +1484,36 @@ def test_projection_fused_logprobs(name):
 
 
 @pytest.mark.gpu
+def test_projection_fused_leaves_masked_spans_out():
+    """Long masked spans (observation turns): only the other rows are projected, gathered through a row map, with
+    their count kept on the device.  Against the oracle, and bit for bit against the call that projects every row
+    (a token's sums do not depend on where its row sits in a tile); then with every row masked."""
+    T, d, V = 2600, 64, 3000
+    _say("lm_head with masked spans: T=%d d=%d V=%d" % (T, d, V))
+    w = wl.generate_lm_head(T, d, V, DEV, seed=15)
+    m = np.ones(T, dtype=np.uint8)
+    for a, b in ((0, 300), (700, 1500), (1501, 1800), (2590, 2600)):
+        m[a:b] = 0
+    w["mask"] = torch.from_numpy(m).to(DEV)
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(w["hidden"]), np64(w["weight"]), np64(w["token_ids"]), np64(w["mask"]))
+    assert_close("lse (masked spans)", np64(lse), ref_lse, rtol=0, atol=1e-4)
+    assert_close("logp (masked spans)", np64(logp), ref_lp, rtol=0, atol=1e-4)
+    assert not bool(logp[torch.from_numpy(m == 0).to(DEV)].any()) and bool((lse[torch.from_numpy(m != 0).to(DEV)] != 0).all())
+    try:
+        fb.fopd_set_option("lm_head_compact", 0)
+        logp_all, lse_all, _ = _lm_head_call(w)
+    finally:
+        fb.fopd_set_option("lm_head_compact", 1)
+    assert torch.equal(logp, logp_all) and torch.equal(lse, lse_all)
+    w["mask"].zero_()
+    logp0, lse0, ws0 = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws0) == (0, 0)
+    assert not bool(logp0.any()) and not bool(lse0.any())
+
+
+@pytest.mark.gpu
 def test_projection_fused_token_range_flag_and_empty_call():
     w = wl.generate_lm_head(40, 64, 300, DEV, seed=6)
     w["token_ids"][3] = 300
