@@ -524,6 +524,8 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *   loss [1], freshness [B] (may be NULL; a copy of freshness_in when that is given), weights [B] (may be NULL),
  *   logp [T], lse [T]: f32 outputs
  *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0.
+ *                dweight NULL, dhidden given: the projection is not trained (a frozen or tied head whose gradient
+ *                is formed elsewhere): two contractions per chunk instead of three.
  *                Both NULL (with freshness_in == NULL): the call only scores - log-probs, scores, weights and the
  *                loss of the first loop of Algorithm 1 on projected logits, one contraction per chunk instead of three
  *   workspace    fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk) bytes, 256-byte aligned, initialised

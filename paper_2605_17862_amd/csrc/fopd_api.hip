@@ -1190,12 +1190,13 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   // without the two gradient outputs the call only scores: log-probs, token loss, scores, weights and the loss
   // (first loop of Algorithm 1 on projected logits)
   const bool grads = (dhidden != nullptr);
+  const bool head_grad = (dweight != nullptr);         // NULL with dhidden given: the projection is not trained
   if (T < 0 || T > 2147483647LL || V <= 0 || V > 2147483647LL - 64 || d <= 0 || d % 64 != 0 || ldh < d || ldw < d ||
-      (grads && (lddh < d || lddw < d)) || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
+      (grads && lddh < d) || (head_grad && lddw < d) || B <= 0 || rows_chunk < 64 || rows_chunk % 64 != 0 || rows_chunk > 1048576)
     return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
       (teacher_logp == nullptr && listed == nullptr) || seq_lens == nullptr || lag == nullptr || loss == nullptr ||
-      logp == nullptr || lse == nullptr || (dhidden == nullptr) != (dweight == nullptr))
+      logp == nullptr || lse == nullptr || (dhidden == nullptr && dweight != nullptr))
     return FOPD_EINVAL;
   if (!grads && freshness_in != nullptr) return FOPD_EINVAL;       // scoring needs the scores to be formed inside
   if (listed != nullptr) {
@@ -1293,7 +1294,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     fopd_loss_final<<<1, kSegThreads, 0, s>>>(partials, 0, n_use, nr_use, lag, f64_use, freshness_in, B, hp.xi, loss,
                                               weights, freshness);
     if ((st = launched()) != FOPD_OK) return st;
-    if (grads && accumulate_dweight == 0) {
+    if (head_grad && accumulate_dweight == 0) {
       fopd_fill_zero_f32<<<static_cast<unsigned>(V), 256, 0, s>>>(dweight, lddw, static_cast<int>(d));
       return launched();
     }
@@ -1466,7 +1467,8 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     if ((st = launch_gemm(false, Wt, ldz, d, G, ldz, R, ldz, dH, lddhc, 5, s, live)) != FOPD_OK) return st;
     // dL/dweight: vocabulary x hidden, contraction over the chunk's rows, both operands as they are stored
     const bool acc = (ci > 0) || (accumulate_dweight != 0);
-    if ((st = launch_gemm_tn(acc, Hg, compact ? d : ldhc, d, rows_hg, G, ldz, V, Rp, dweight, lddw, 6, s, live)) != FOPD_OK)
+    if (head_grad &&
+        (st = launch_gemm_tn(acc, Hg, compact ? d : ldhc, d, rows_hg, G, ldz, V, Rp, dweight, lddw, 6, s, live)) != FOPD_OK)
       return st;
     if ((st = scatter()) != FOPD_OK) return st;
     ++ci;

@@ -300,7 +300,7 @@ def _lml(lib, **kw):
 def test_projection_loss_rejects_bad_arguments_before_launch():
     lib = fb.load_library()
     assert _lml(lib, hidden=None) == 1
-    assert _lml(lib, dw=None) == 1
+    assert _lml(lib, dh=None) == 1                                # a weight gradient without the hidden one
     assert _lml(lib, chunk=32) == 2                               # rows per chunk: a multiple of 64
     assert _lml(lib, d=96, ldh=96, ldw=96) == 2
     assert _lml(lib, nroll=4096) == 1                             # roll counts only together with the sup counts

@@ -596,6 +596,30 @@ def test_projection_loss_leaves_masked_spans_out_of_the_contractions():
         assert torch.allclose(got["dweight"], want["dweight"], rtol=1e-4, atol=1e-6 * scale), name
 
 
+def test_projection_loss_without_the_weight_gradient():
+    """dweight = NULL (a head that is not trained): everything else bit for bit as in the full call."""
+    seq, d, V, rows_chunk = (90, 130, 80), 128, 3000, 128
+    T, B = sum(seq), len(seq)
+    _say("pass through the projection without dL/dweight")
+    h = wl.generate_lm_head(T, d, V, DEV, seed=17, masked_every=6)
+    w = wl.attach_loss_inputs(h, seq, [0, 3, 40], seed=17)
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
+    f = _scores_from_the_oracle(w, hp)
+    full = _run(w, hp, g, rows_chunk, f)
+    ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+    f32 = dict(dtype=torch.float32, device=DEV)
+    out = dict(loss=torch.full((1,), 7.0, **f32), weights=torch.empty(B, **f32), logp=torch.full((T,), 7.0, **f32),
+               lse=torch.full((T,), 7.0, **f32), dhidden=torch.full((T, d), 7.0, **f32))
+    fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                 w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp,
+                                 torch.from_numpy(f).to(DEV), None, None, g, rows_chunk, out["loss"], out["weights"],
+                                 out["logp"], out["lse"], out["dhidden"], d, None, 0, False, ws)
+    torch.cuda.synchronize()
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    for key in sorted(out):
+        assert torch.equal(out[key], full[key]), key
+
+
 def test_projection_loss_replays_from_a_hip_graph_with_other_masks():
     """The pass enqueues kernels only and keeps the counts of live rows and of gradient rows on the device, so a
     captured call stays right when the mask behind it changes: three replays, each after the mask tensor was
