@@ -492,10 +492,10 @@ def test_projection_scores_only_calls_give_the_full_calls_scores():
         for key in keys:
             assert torch.equal(full[key], only[key]), key
         assert bool((only["fresh"] != 7.0).all()) and bool((only["logp"] != 7.0).all())
-    # one gradient output without the other, or scoring with scores supplied, is refused
+    # the weight gradient without the hidden one, or scoring with scores supplied, is refused
     o = outs()
     with pytest.raises(fb.FopdError):
-        listed(o, torch.empty(T, d, **f32), None)
+        listed(o, None, torch.empty(V, d, **f32))
     with pytest.raises(fb.FopdError):
         ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
         fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
