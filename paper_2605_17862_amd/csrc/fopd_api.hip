@@ -129,8 +129,8 @@ struct LmLossWorkspace {
       ids_c = Workspace::take(off, r * kk * sizeof(int32_t));
       llp_c = Workspace::take(off, r * kk * sizeof(float));
     }
-    ex = Workspace::take(off, (r + 1) * sizeof(int32_t));
-    row_map = Workspace::take(off, r * sizeof(int32_t));
+    ex = Workspace::take(off, (static_cast<size_t>(t) + 1) * sizeof(int32_t));     // (a whole call's rows when the
+    row_map = Workspace::take(off, static_cast<size_t>(t) * sizeof(int32_t));       //  scores are supplied)
     n_live = Workspace::take(off, 64 * sizeof(int32_t));
     cu_c = Workspace::take(off, (b + 1) * sizeof(int64_t));
     tok_c = Workspace::take(off, r * sizeof(int32_t));
@@ -1313,9 +1313,25 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   int32_t* row_map = at<int32_t>(workspace, lay.row_map);
   int32_t* n_live = at<int32_t>(workspace, lay.n_live);
   int32_t* n_grad = n_live + 1;
+  int32_t* n_chunk = n_live + 2;
   int32_t* grad_ex = at<int32_t>(workspace, lay.grad_ex);
   int64_t* cu_c = at<int64_t>(workspace, lay.cu_c);
   const float* stale = (listed != nullptr) ? listed->teacher_logp_stale : nullptr;
+  // With scores supplied a chunk may cut samples anywhere, so the live rows of the whole call are numbered once and
+  // chunk c is live rows c rows_chunk .. (c + 1) rows_chunk - 1: every chunk but the last is full, whatever the mask.
+  // The host does not know how many there are: it walks ceil(T / rows_chunk) chunks and the last ones may be empty.
+  const bool global_rows = compact && scored;
+  if (global_rows) {
+    fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), cu, B, 0, ex, row_map,
+                                                  n_live, cu_c);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  if (compact && mask != nullptr) {
+    fopd_masked_rows_zero<<<static_cast<unsigned>(T), 256, 0, s>>>(
+        mask, logp, lse, (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr, lddh,
+        static_cast<int>(d));
+    if ((st = launched()) != FOPD_OK) return st;
+  }
 
   int64_t ci = 0;
   for (const Chunk& c : chunks) {
@@ -1339,13 +1355,18 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     const int64_t* cu_k = cu;           // sample offsets and the chunk's first row in the row numbering of the kernels
     int64_t a_k = a;
     const int* live = nullptr;
+    // where the chunk's dense rows come from: live rows map_off .. of the numbering, as offsets from row row_base
+    const int64_t map_off = global_rows ? a : 0, row_base = global_rows ? 0 : a;
     if (compact) {
-      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, nullptr, nullptr, static_cast<int>(R), cu, B, a, ex, row_map,
-                                                    n_live, cu_c);
-      if ((st = launched()) != FOPD_OK) return st;
+      if (!global_rows) {
+        fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, nullptr, nullptr, static_cast<int>(R), cu, B, a, ex, row_map,
+                                                      n_live, cu_c);
+        if ((st = launched()) != FOPD_OK) return st;
+      }
       fopd_live_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(
-          row_map, n_live, tok, msk, bl, tq, (stale != nullptr) ? stale + a : nullptr, lids, llp, list_k,
-          reinterpret_cast<const uint16_t*>(Hc), ldh, static_cast<int>(d), at<int32_t>(workspace, lay.tok_c),
+          row_map, n_live, map_off, row_base, n_chunk, token_ids, mask, behav_logp, teacher_logp, stale,
+          (listed != nullptr) ? listed->ids : nullptr, (listed != nullptr) ? listed->logp : nullptr, list_k,
+          reinterpret_cast<const uint16_t*>(Hm), ldh, static_cast<int>(d), at<int32_t>(workspace, lay.tok_c),
           at<uint8_t>(workspace, lay.mask_c), at<float>(workspace, lay.behav_c), at<float>(workspace, lay.teach_c),
           at<float>(workspace, lay.stale_c), at<int32_t>(workspace, lay.ids_c), at<float>(workspace, lay.llp_c),
           at<uint16_t>(workspace, lay.h_c));
@@ -1365,17 +1386,17 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
       ls_o = at<float>(workspace, lay.lse_c);
       if (grads) dH = at<float>(workspace, lay.dh_c);
       lddhc = d;
-      cu_k = cu_c;
-      a_k = 0;
-      live = n_live;
+      cu_k = cu_c;                     // the samples' offsets in the numbering of the live rows
+      a_k = map_off;
+      live = n_chunk;
     }
-    // the per-row outputs and dL/dhidden rows of the live rows go back to the caller's rows, zeros to the others
+    // the per-row outputs and dL/dhidden rows of the live rows go back to the caller's rows (the masked rows' were
+    // cleared at the start)
     auto scatter = [&]() -> fopd_status {
       if (!compact) return FOPD_OK;
       fopd_live_scatter<<<static_cast<unsigned>(R), 256, 0, s>>>(
-          ex, lp_o, ls_o, tl_o, grad_ex, dH, static_cast<int>(d), logp + a, lse + a,
-          (listed != nullptr && listed->token_loss != nullptr) ? listed->token_loss + a : nullptr,
-          grads ? dhidden + a * lddh : nullptr, lddh);
+          row_map, n_live, map_off, row_base, lp_o, ls_o, tl_o, grad_ex, dH, static_cast<int>(d), logp, lse,
+          (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr, lddh);
       return launched();
     };
     // logits of the chunk, fp32, never rounded to the storage type of stored logits

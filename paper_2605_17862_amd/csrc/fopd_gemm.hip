@@ -755,7 +755,9 @@ __global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld
 // ---- rows that take part moved to the front of a chunk, so that the contractions skip the others ----
 // Masked rows (observations, prompts) have no log-prob and no gradient row: the chunk's per-row inputs and hidden
 // states are gathered into dense arrays of the live rows (mask != 0), every kernel of the chunk runs on those, and
-// the per-row outputs are scattered back (zeros at masked rows).  Once the coefficients are known the same is done
+// the per-row outputs are scattered back (zeros at masked rows).  With scores supplied the live rows of the whole
+// call are numbered once and the chunks are runs of that numbering, so that every chunk but the last is full; with
+// the scores formed inside, the chunks are whole samples and each is numbered by itself.  Once the coefficients are known the same is done
 // again for the gradient side: only the rows with c_t != 0 (not those of samples the freshness weight gates out)
 // get a gradient row, written densely, and the two gradient contractions run on those.  The counts stay on the
 // device: the launches cover the whole chunk, the contraction kernels read the count and leave out the rest.
@@ -809,23 +811,30 @@ fopd_live_scan(const uint8_t* __restrict__ mask, const float* __restrict__ coef,
   }
 }
 
-// Compact row c = blockIdx.x of the chunk (c < R): the per-row inputs and the hidden row of chunk row row_map[c], or,
-// past the live rows, a masked row of zeros.  Pointers are to the chunk's first row; teacher_logp, teacher_stale and
-// the list may be NULL (then so are their outputs' uses).  d % 8 == 0.
+// Dense row c = blockIdx.x of a chunk (c < gridDim.x) is live row map_off + c of the scan: row row_base +
+// row_map[map_off + c] of the caller's arrays if map_off + c < n_live[0], else a masked row of zeros.  Gathers the
+// per-row inputs, the listed teacher and the hidden row; the arrays are the caller's (first row), not the chunk's;
+// teacher_logp, teacher_stale and the list may be NULL.  n_chunk[0] = the chunk's live rows (what the contraction
+// kernels read).  d % 8 == 0.
 __global__ void __launch_bounds__(256)
-fopd_live_gather(const int* __restrict__ row_map, const int* __restrict__ n_live, const int32_t* __restrict__ token_ids,
-                 const uint8_t* __restrict__ mask, const float* __restrict__ behav_logp,
-                 const float* __restrict__ teacher_logp, const float* __restrict__ teacher_stale,
-                 const int32_t* __restrict__ list_ids, const float* __restrict__ list_logp, int k,
-                 const uint16_t* __restrict__ hidden, int64_t ldh, int d, int32_t* __restrict__ token_ids_c,
-                 uint8_t* __restrict__ mask_c, float* __restrict__ behav_c, float* __restrict__ teacher_c,
-                 float* __restrict__ stale_c, int32_t* __restrict__ list_ids_c, float* __restrict__ list_logp_c,
-                 uint16_t* __restrict__ hidden_c) {
+fopd_live_gather(const int* __restrict__ row_map, const int* __restrict__ n_live, int64_t map_off, int64_t row_base,
+                 int* __restrict__ n_chunk, const int32_t* __restrict__ token_ids, const uint8_t* __restrict__ mask,
+                 const float* __restrict__ behav_logp, const float* __restrict__ teacher_logp,
+                 const float* __restrict__ teacher_stale, const int32_t* __restrict__ list_ids,
+                 const float* __restrict__ list_logp, int k, const uint16_t* __restrict__ hidden, int64_t ldh, int d,
+                 int32_t* __restrict__ token_ids_c, uint8_t* __restrict__ mask_c, float* __restrict__ behav_c,
+                 float* __restrict__ teacher_c, float* __restrict__ stale_c, int32_t* __restrict__ list_ids_c,
+                 float* __restrict__ list_logp_c, uint16_t* __restrict__ hidden_c) {
   const int64_t c = blockIdx.x;
   const int tid = threadIdx.x;
-  const bool live = c < n_live[0];
-  const int64_t j = live ? row_map[c] : 0;
+  const int64_t total = n_live[0];
+  const bool live = map_off + c < total;
+  const int64_t j = live ? row_base + row_map[map_off + c] : 0;
   if (tid == 0) {
+    if (c == 0) {
+      const int64_t here = total - map_off;
+      n_chunk[0] = static_cast<int>(here < 0 ? 0 : (here > gridDim.x ? gridDim.x : here));
+    }
     token_ids_c[c] = live ? token_ids[j] : 0;
     mask_c[c] = live ? (mask != nullptr ? mask[j] : static_cast<uint8_t>(1)) : static_cast<uint8_t>(0);
     behav_c[c] = live ? behav_logp[j] : 0.f;
@@ -873,29 +882,49 @@ fopd_grad_tail_zero(const int* __restrict__ n_grad, uint16_t* __restrict__ G, in
   for (int v = threadIdx.x; v < d / 8; v += 256) h[v] = zero;
 }
 
-// Chunk row j = blockIdx.x (j < R) gets its outputs back: those of compact row ex[j] if the row is live, zeros if
-// not; its dL/dhidden row is row grad_ex[ex[j]] of dhidden_g if the row has a gradient, zeros if not.
-// token_loss / token_loss_c and dhidden / dhidden_g / grad_ex may be NULL.
+// Dense row c = blockIdx.x of a chunk hands its outputs to the caller's row row_base + row_map[map_off + c] (nothing
+// if map_off + c >= n_live[0]): log-prob, log-sum-exp, token loss, and as dL/dhidden row the dense gradient row
+// grad_ex[c] of dhidden_g if the row has one (grad_ex[c + 1] > grad_ex[c]), zeros if not.  token_loss / token_loss_c
+// and dhidden / dhidden_g / grad_ex may be NULL.
 __global__ void __launch_bounds__(256)
-fopd_live_scatter(const int* __restrict__ ex, const float* __restrict__ logp_c, const float* __restrict__ lse_c,
+fopd_live_scatter(const int* __restrict__ row_map, const int* __restrict__ n_live, int64_t map_off, int64_t row_base,
+                  const float* __restrict__ logp_c, const float* __restrict__ lse_c,
                   const float* __restrict__ token_loss_c, const int* __restrict__ grad_ex,
                   const float* __restrict__ dhidden_g, int d, float* __restrict__ logp, float* __restrict__ lse,
                   float* __restrict__ token_loss, float* __restrict__ dhidden, int64_t lddh) {
-  const int64_t j = blockIdx.x;
+  const int64_t c = blockIdx.x;
   const int tid = threadIdx.x;
-  const int c = ex[j];
-  const bool live = ex[j + 1] > c;
+  if (map_off + c >= n_live[0]) return;
+  const int64_t t = row_base + row_map[map_off + c];
   if (tid == 0) {
-    logp[j] = live ? logp_c[c] : 0.f;
-    lse[j] = live ? lse_c[c] : 0.f;
-    if (token_loss != nullptr) token_loss[j] = live ? token_loss_c[c] : 0.f;
+    logp[t] = logp_c[c];
+    lse[t] = lse_c[c];
+    if (token_loss != nullptr) token_loss[t] = token_loss_c[c];
   }
   if (dhidden != nullptr) {
-    const int g = live ? grad_ex[c] : 0;
-    const bool has = live && grad_ex[c + 1] > g;
+    const int g = grad_ex[c];
+    const bool has = grad_ex[c + 1] > g;
     const float* src = dhidden_g + static_cast<int64_t>(g) * d;
-    float* dst = dhidden + j * lddh;
+    float* dst = dhidden + t * lddh;
     for (int v = tid; v < d; v += 256) dst[v] = has ? src[v] : 0.f;
+  }
+}
+
+// Zeros in the outputs of the masked rows (mask[r] == 0) among rows 0 .. gridDim.x - 1 of the arrays given (their
+// first row is the range's): log-prob, log-sum-exp, token loss (may be NULL), dL/dhidden row (may be NULL).
+__global__ void __launch_bounds__(256)
+fopd_masked_rows_zero(const uint8_t* __restrict__ mask, float* __restrict__ logp, float* __restrict__ lse,
+                      float* __restrict__ token_loss, float* __restrict__ dhidden, int64_t lddh, int d) {
+  const int64_t r = blockIdx.x;
+  if (mask[r] != 0) return;
+  if (threadIdx.x == 0) {
+    logp[r] = 0.f;
+    lse[r] = 0.f;
+    if (token_loss != nullptr) token_loss[r] = 0.f;
+  }
+  if (dhidden != nullptr) {
+    float* dst = dhidden + r * lddh;
+    for (int v = threadIdx.x; v < d; v += 256) dst[v] = 0.f;
   }
 }
 
