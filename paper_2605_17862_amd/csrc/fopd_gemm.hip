@@ -662,7 +662,9 @@ fopd_gemm_tn(const __bf16* __restrict__ Ak, int64_t lda, int M, int rows_a, cons
 #pragma unroll
       for (int i = 0; i < TI; ++i) {
         if (m + 32 * i < M) {
-          if (ACCUMULATE) orow[m + 32 * i] += acc[i][j][r];
+          // (every entry of Out belongs to one lane of one workgroup, so the hardware add below, which does not
+          // wait for the old value to come back, gives the same sums as load - add - store, in the same order)
+          if (ACCUMULATE) unsafeAtomicAdd(orow + m + 32 * i, acc[i][j][r]);
           else orow[m + 32 * i] = acc[i][j][r];
         }
       }
