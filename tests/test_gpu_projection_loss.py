@@ -223,17 +223,20 @@ def test_projection_loss_rejects_bad_arguments():
     assert e.value.status == 5                                     # workspace too small
 
 
-def test_projection_loss_at_benchmark_size_sampled_rows():
-    """The benchmark's shape (rows, mask and lags of the reasoning workload, d = 4096, V = 151,936, chunks of 8192
-    rows).  The scores are an input of this call (Algorithm 1 computes them in its first loop), so seeded values
+@pytest.mark.parametrize("workload", ["reasoning", "tooluse"])
+def test_projection_loss_at_benchmark_size_sampled_rows(workload):
+    """The benchmark's shape (rows, mask and lags of the reasoning workload, and of the tool-use one, a third of whose
+    rows are masked observation spans; d = 4096, V = 151,936, chunks of 8192 rows).  The scores are an input of this call (Algorithm 1 computes them in its first loop), so seeded values
     are supplied; the oracle then gives, row by row, the log-prob, the coefficient, the bf16 gradient row and its
     contraction with the projection matrix for sampled rows.  dweight is tied to dhidden by the identity
     <dhidden, hidden> = sum_{t,v} dz[t,v] z[t,v] = <dweight, weight>, which holds at any size."""
-    seq, mask = wl.structure_only("reasoning", seed=0)
+    seq, mask = wl.structure_only(workload, seed=0)
     T, d, V, B, rows_chunk = int(seq.sum()), 4096, 151936, len(seq), 8192
-    _say("benchmark size: T=%d d=%d V=%d, %d chunks: generating ..." % (T, d, V, (T + rows_chunk - 1) // rows_chunk))
+    _say("benchmark size (%s): T=%d (%d masked) d=%d V=%d, %d chunks: generating ..."
+         % (workload, T, int((mask == 0).sum()), d, V, (T + rows_chunk - 1) // rows_chunk))
     lag = np.random.RandomState(0).randint(0, 5, size=B).astype(np.int32)
     w = wl.attach_loss_inputs(wl.generate_lm_head(T, d, V, DEV, seed=0), seq, lag, seed=0)
+    w["mask"] = torch.from_numpy(mask).to(DEV)
     hp, g = (1.0, 1.0, 0.05, 0.1), 1.0
     f = np.random.RandomState(5).uniform(0.0, 1.0, size=B).astype(np.float32)
     f[3] = 0.01                                                   # one sample gated by the threshold
@@ -246,9 +249,14 @@ def test_projection_loss_at_benchmark_size_sampled_rows():
     W64 = np64(w["weight"])
     rs = np.random.RandomState(11)
     rows = sorted(set(rs.randint(0, T, size=10).tolist() + [0, T - 1, int(cu[3]) + 1, rows_chunk - 1, rows_chunk]))
+    live_rows = np.flatnonzero(mask != 0)
+    rows = sorted(set(rows + [int(live_rows[0]), int(live_rows[-1]), int(live_rows[len(live_rows) // 2])]))
     lb, lq, y = np64(w["behav_logp"]), np64(w["teacher_logp"]), np64(w["token_ids"])
     worst = 0.0
     for t in rows:
+        if mask[t] == 0:                                          # a masked row: no log-prob, no gradient row
+            assert float(out["logp"][t]) == 0.0 and float(out["lse"][t]) == 0.0 and not bool(out["dhidden"][t].any())
+            continue
         i = int(np.searchsorted(cu, t, side="right") - 1)
         h = np64(w["hidden"][t])
         z = orc.lm_head_logits(h[None, :], W64)
