@@ -339,6 +339,23 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
     st, flags = fb.fopd_workspace_status(ws)
     if st != 0:
         sys.exit("device flags set: %d" % flags)
+    # scores supplied and no per-row outputs wanted: the samples of weight 0 are left out of the call altogether
+    lean = None
+    if not args.no_compact:
+        def step_lean():
+            fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"],
+                                         w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, fresh,
+                                         n_train, n_roll, 1.0, rows_chunk, loss, weights, None, None, dh, d, dw, d, 0, ws)
+        step_lean()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(steps):
+            step_lean()
+        torch.cuda.synchronize()
+        lean = (time.perf_counter() - t3) / steps * 1e3
+        st, flags = fb.fopd_workspace_status(ws)
+        if st != 0:
+            sys.exit("device flags set: %d" % flags)
     # the same call with no scores supplied: they are formed inside, per chunk of whole samples, so that a step
     # from hidden states projects once instead of twice (possible when every sample fits into a chunk)
     inside = None
@@ -422,6 +439,9 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
                      "flops_per_launch": all_flops / (3 * n_chunks), "avg_ms": tot_ms / (3 * n_chunks)},
         "kernels": kern,
         "outside_the_contractions_ms": elapsed / steps * 1e3 - tot_ms,
+        "scores_supplied_no_row_outputs": None if lean is None else {
+            "call": "fopd_lm_head_loss_fwd_bwd with logp = lse = NULL (samples of weight 0 are not projected at all)",
+            "ms_per_call": lean, "tokens/s": int(((mask != 0) & (mask != 2)).sum()) / (lean * 1e-3)},
         "scores_formed_inside": None if inside is None else {
             "call": "fopd_lm_head_loss_fwd_bwd with freshness_in = NULL (chunks of whole samples; scoring, loss and both "
                     "gradients with one projection per step)",

@@ -522,7 +522,9 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
  *   rows_chunk   rows per chunk, a multiple of 64 (scratch at V = 151,936, d = 4096: 9.0 GB for 8192 rows, 16.7 GB for 16384, which is 4 - 10 % faster)
  *   loss [1], freshness [B] (may be NULL; a copy of freshness_in when that is given), weights [B] (may be NULL),
- *   logp [T], lse [T]: f32 outputs
+ *   logp [T], lse [T]: f32 outputs.  With freshness_in given (and both gradient outputs) the two may be NULL together
+ *                (the caller has them from the scoring call): the samples of weight 0 are then left out of the call
+ *                altogether, none of their rows is projected (needs option "lm_head_compact" = 1, the default)
  *   dhidden [T, lddh] f32 out; dweight [V, lddw] f32: overwritten, or added to when accumulate_dweight != 0.
  *                dweight NULL, dhidden given: the projection is not trained (a frozen or tied head whose gradient
  *                is formed elsewhere): two contractions per chunk instead of three.

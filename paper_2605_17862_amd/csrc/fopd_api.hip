@@ -94,7 +94,7 @@ struct LmLossWorkspace {
   // copies of the per-row inputs and outputs, of the hidden rows and of their gradient
   // and, for the gradient side, the same among the live rows for those that have a gradient row
   size_t ex = 0, row_map = 0, n_live = 0, cu_c = 0, tok_c = 0, mask_c = 0, behav_c = 0, teach_c = 0, stale_c = 0,
-         logp_c = 0, lse_c = 0, tl_c = 0, ids_c = 0, llp_c = 0, h_c = 0, dh_c = 0, grad_ex = 0, h_g = 0;
+         logp_c = 0, lse_c = 0, tl_c = 0, ids_c = 0, llp_c = 0, h_c = 0, dh_c = 0, grad_ex = 0, h_g = 0, keep = 0;
   int64_t ldz = 0, r_pad = 0, n_chunks = 0;
   LmLossWorkspace(int64_t T, int64_t V, int64_t d, int32_t B, int64_t rows_chunk, int32_t k = 0) {
     const size_t b = static_cast<size_t>(B < 0 ? 0 : B);
@@ -145,6 +145,7 @@ struct LmLossWorkspace {
     dh_c = Workspace::take(off, r * dd * sizeof(float));
     grad_ex = Workspace::take(off, (r + 1) * sizeof(int32_t));
     h_g = Workspace::take(off, r * dd * 2);
+    keep = Workspace::take(off, b * sizeof(int32_t));
     total = off;
   }
 };
@@ -1075,7 +1076,7 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
     row_map = at<int32_t>(workspace, lay.row_map);
     n_live = at<int32_t>(workspace, lay.n_live);
     fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), nullptr, -1, 0, ex, row_map,
-                                                  n_live, nullptr);
+                                                  n_live, nullptr, nullptr);
     if (launched() != FOPD_OK) return FOPD_EHIP;
   }
   {
@@ -1196,7 +1197,13 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || behav_logp == nullptr ||
       (teacher_logp == nullptr && listed == nullptr) || seq_lens == nullptr || lag == nullptr || loss == nullptr ||
-      logp == nullptr || lse == nullptr || (dhidden == nullptr && dweight != nullptr))
+      (logp == nullptr) != (lse == nullptr) || (dhidden == nullptr && dweight != nullptr))
+    return FOPD_EINVAL;
+  // Without the two per-row outputs (a caller that supplies scores has them from the scoring call) the samples of
+  // weight 0 are left out of the call altogether; this needs the scores and the numbering of the live rows.
+  const bool drop_gated = (logp == nullptr);
+  if (drop_gated && (freshness_in == nullptr || listed != nullptr || dhidden == nullptr ||
+                     current_options().lm_head_compact == 0))
     return FOPD_EINVAL;
   if (!grads && freshness_in != nullptr) return FOPD_EINVAL;       // scoring needs the scores to be formed inside
   if (listed != nullptr) {
@@ -1321,15 +1328,22 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   // chunk c is live rows c rows_chunk .. (c + 1) rows_chunk - 1: every chunk but the last is full, whatever the mask.
   // The host does not know how many there are: it walks ceil(T / rows_chunk) chunks and the last ones may be empty.
   const bool global_rows = compact && scored;
-  if (global_rows) {
-    fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), cu, B, 0, ex, row_map,
-                                                  n_live, cu_c);
+  int32_t* keep = nullptr;             // with drop_gated: 1 for the samples of positive weight
+  if (drop_gated) {
+    keep = at<int32_t>(workspace, lay.keep);
+    fopd_sample_keep<<<static_cast<unsigned>((B + 255) / 256), 256, 0, s>>>(freshness_in, n_use, nr_use, lag, B, hp.xi,
+                                                                          keep);
     if ((st = launched()) != FOPD_OK) return st;
   }
-  if (compact && mask != nullptr) {
+  if (global_rows) {
+    fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), cu, B, 0, ex, row_map,
+                                                  n_live, cu_c, keep);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
+  if (compact && (mask != nullptr || keep != nullptr)) {
     fopd_masked_rows_zero<<<static_cast<unsigned>(T), 256, 0, s>>>(
-        mask, logp, lse, (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr, lddh,
-        static_cast<int>(d));
+        mask, cu, B, keep, logp, lse, (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr,
+        lddh, static_cast<int>(d));
     if ((st = launched()) != FOPD_OK) return st;
   }
 
@@ -1360,7 +1374,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     if (compact) {
       if (!global_rows) {
         fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(msk, nullptr, nullptr, static_cast<int>(R), cu, B, a, ex, row_map,
-                                                      n_live, cu_c);
+                                                      n_live, cu_c, nullptr);
         if ((st = launched()) != FOPD_OK) return st;
       }
       fopd_live_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(
@@ -1450,7 +1464,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     if (compact) {
       fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(nullptr, coef, (listed != nullptr) ? c2 : nullptr,
                                                     static_cast<int>(R), nullptr, -1, 0, grad_ex, nullptr, n_grad,
-                                                    nullptr);
+                                                    nullptr, nullptr);
       if ((st = launched()) != FOPD_OK) return st;
       fopd_grad_gather<<<static_cast<unsigned>(R), 256, 0, s>>>(grad_ex, reinterpret_cast<const uint16_t*>(Hc), ldhc,
                                                                static_cast<int>(d), at<uint16_t>(workspace, lay.h_g));

@@ -766,22 +766,35 @@ __global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld
 
 constexpr int kLiveScanThreads = 1024;
 
+// keep[i] = 1 if sample i has a positive weight under the supplied scores, else 0.
+__global__ void __launch_bounds__(256)
+fopd_sample_keep(const float* __restrict__ fresh32, const int32_t* __restrict__ n_train,
+                 const int32_t* __restrict__ n_roll, const int32_t* __restrict__ lag, int B, float xi,
+                 int* __restrict__ keep) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B) return;
+  const int32_t n = n_train[i];
+  keep[i] = weight_of(static_cast<double>(fresh32[i]), n, (n_roll != nullptr) ? n_roll[i] : n, lag[i], xi) > 0.0 ? 1 : 0;
+}
+
 // One workgroup.  A row is live if coef != NULL ? (coef[j] != 0 or, with coef2, coef2[j] != 0) : (mask == NULL ||
-// mask[j] != 0); mask / coef / coef2 point at the chunk's first row.  ex[j] = live rows before chunk row j, j = 0 .. R; row_map[c] = chunk row of compact row c
+// mask[j] != 0) and, with keep, keep[sample of row row_begin + j] != 0; mask / coef / coef2 point at the chunk's
+// first row.  ex[j] = live rows before chunk row j, j = 0 .. R; row_map[c] = chunk row of compact row c
 // (row_map may be NULL); n_live[0] = ex[R]; cu_c[i] = ex[clamp(cu[i] - row_begin, 0, R)], i = 0 .. B: the samples'
 // offsets among the chunk's live rows (B < 0: none wanted).
 __global__ void __launch_bounds__(kLiveScanThreads)
 fopd_live_scan(const uint8_t* __restrict__ mask, const float* __restrict__ coef, const float* __restrict__ coef2, int R,
                const int64_t* __restrict__ cu,
                int B, int64_t row_begin, int* __restrict__ ex, int* __restrict__ row_map, int* __restrict__ n_live,
-               int64_t* __restrict__ cu_c) {
+               int64_t* __restrict__ cu_c, const int* __restrict__ keep) {
   __shared__ int sh[kLiveScanThreads];
   const int tid = threadIdx.x;
   const int per = (R + kLiveScanThreads - 1) / kLiveScanThreads;
   const int lo = min(tid * per, R), hi = min(lo + per, R);
   auto is_live = [&](int j) {
     if (coef != nullptr) return coef[j] != 0.f || (coef2 != nullptr && coef2[j] != 0.f);
-    return mask == nullptr || mask[j] != 0;
+    if (mask != nullptr && mask[j] == 0) return false;
+    return keep == nullptr || keep[sample_of_row(cu, B, row_begin + j)] != 0;
   };
   int local = 0;
   for (int j = lo; j < hi; ++j) local += is_live(j) ? 1 : 0;
@@ -885,7 +898,7 @@ fopd_grad_tail_zero(const int* __restrict__ n_grad, uint16_t* __restrict__ G, in
 }
 
 // Dense row c = blockIdx.x of a chunk hands its outputs to the caller's row row_base + row_map[map_off + c] (nothing
-// if map_off + c >= n_live[0]): log-prob, log-sum-exp, token loss, and as dL/dhidden row the dense gradient row
+// if map_off + c >= n_live[0]): log-prob and log-sum-exp (logp, lse: NULL together), token loss, and as dL/dhidden row the dense gradient row
 // grad_ex[c] of dhidden_g if the row has one (grad_ex[c + 1] > grad_ex[c]), zeros if not.  token_loss / token_loss_c
 // and dhidden / dhidden_g / grad_ex may be NULL.
 __global__ void __launch_bounds__(256)
@@ -899,8 +912,10 @@ fopd_live_scatter(const int* __restrict__ row_map, const int* __restrict__ n_liv
   if (map_off + c >= n_live[0]) return;
   const int64_t t = row_base + row_map[map_off + c];
   if (tid == 0) {
-    logp[t] = logp_c[c];
-    lse[t] = lse_c[c];
+    if (logp != nullptr) {
+      logp[t] = logp_c[c];
+      lse[t] = lse_c[c];
+    }
     if (token_loss != nullptr) token_loss[t] = token_loss_c[c];
   }
   if (dhidden != nullptr) {
@@ -912,16 +927,21 @@ fopd_live_scatter(const int* __restrict__ row_map, const int* __restrict__ n_liv
   }
 }
 
-// Zeros in the outputs of the masked rows (mask[r] == 0) among rows 0 .. gridDim.x - 1 of the arrays given (their
-// first row is the range's): log-prob, log-sum-exp, token loss (may be NULL), dL/dhidden row (may be NULL).
+// Zeros in the outputs of the rows 0 .. gridDim.x - 1 that take no part: masked ones (mask != NULL and mask[r] == 0)
+// and, with keep, those of samples with keep[i] == 0 (cu: the samples' offsets).  Log-prob and log-sum-exp (NULL
+// together), token loss (may be NULL), dL/dhidden row (may be NULL).
 __global__ void __launch_bounds__(256)
-fopd_masked_rows_zero(const uint8_t* __restrict__ mask, float* __restrict__ logp, float* __restrict__ lse,
+fopd_masked_rows_zero(const uint8_t* __restrict__ mask, const int64_t* __restrict__ cu, int B,
+                      const int* __restrict__ keep, float* __restrict__ logp, float* __restrict__ lse,
                       float* __restrict__ token_loss, float* __restrict__ dhidden, int64_t lddh, int d) {
   const int64_t r = blockIdx.x;
-  if (mask[r] != 0) return;
+  const bool masked = (mask != nullptr && mask[r] == 0);
+  if (!masked && (keep == nullptr || keep[sample_of_row(cu, B, r)] != 0)) return;
   if (threadIdx.x == 0) {
-    logp[r] = 0.f;
-    lse[r] = 0.f;
+    if (logp != nullptr) {
+      logp[r] = 0.f;
+      lse[r] = 0.f;
+    }
     if (token_loss != nullptr) token_loss[r] = 0.f;
   }
   if (dhidden != nullptr) {

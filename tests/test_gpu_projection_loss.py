@@ -628,6 +628,46 @@ def test_projection_loss_without_the_weight_gradient():
         assert torch.equal(out[key], full[key]), key
 
 
+def test_projection_loss_without_per_row_outputs_leaves_gated_samples_out():
+    """Scores supplied and logp = lse = NULL (the caller has them from the scoring call): the samples of weight 0 are
+    not projected at all.  Loss, weights and both gradients as in the call that returns the log-probs."""
+    seq, d, V, rows_chunk = (150, 90, 200, 60), 128, 3000, 128
+    T, B = sum(seq), len(seq)
+    rs = np.random.RandomState(3)
+    _say("scores supplied, no per-row outputs: gated samples left out")
+    h = wl.generate_lm_head(T, d, V, DEV, seed=51)
+    h["mask"] = torch.from_numpy(_span_mask(T, [(0, 40), (300, 330)], rs)).to(DEV)
+    w = wl.attach_loss_inputs(h, seq, [0, 3, 1, 2], seed=51)
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
+    f = np.array([0.8, 0.04, 0.5, 0.05], dtype=np.float32)         # the second sample gated, the fourth on the threshold
+    full = _run(w, hp, g, rows_chunk, f)
+    assert float(full["weights"][1]) == 0.0 and float(full["weights"][3]) == 0.0 and float(full["weights"][2]) > 0.0
+    ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+    f32 = dict(dtype=torch.float32, device=DEV)
+    out = dict(loss=torch.full((1,), 7.0, **f32), weights=torch.empty(B, **f32), dhidden=torch.full((T, d), 7.0, **f32),
+               dweight=torch.full((V, d), 7.0, **f32))
+
+    def call(lp, ls, fin):
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, fin, None, None, g,
+                                     rows_chunk, out["loss"], out["weights"], lp, ls, out["dhidden"], d, out["dweight"], d,
+                                     False, ws, seq_lens_host=w["seq_lens_host"])
+
+    call(None, None, torch.from_numpy(f).to(DEV))
+    torch.cuda.synchronize()
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    assert torch.equal(out["weights"], full["weights"]) and torch.equal(out["dhidden"], full["dhidden"])
+    assert not bool(out["dhidden"][150:240].any()) and not bool(out["dhidden"][440:].any())
+    assert abs(float(out["loss"]) - float(full["loss"])) <= 2e-6 * abs(float(full["loss"]))
+    scale = float(full["dweight"].abs().max())
+    assert torch.allclose(out["dweight"], full["dweight"], rtol=1e-4, atol=1e-6 * scale)
+    # one of the two without the other, or neither without scores, is refused
+    lp = torch.empty(T, **f32)
+    for args in ((lp, None, torch.from_numpy(f).to(DEV)), (None, None, None)):
+        with pytest.raises(fb.FopdError):
+            call(*args)
+
+
 def test_projection_loss_replays_from_a_hip_graph_with_other_masks():
     """The pass enqueues kernels only and keeps the counts of live rows and of gradient rows on the device, so a
     captured call stays right when the mask behind it changes: three replays, each after the mask tensor was
