@@ -69,10 +69,14 @@ typedef enum {
   FOPD_ELAG = 8,         /* device flag: some lag < 0 */
   FOPD_EHIP = 9,         /* a HIP runtime call or kernel launch failed */
   FOPD_ESETS = 10,       /* device flag: mask bytes 2 / 3 (the two aligned sets differ) in a chunk call made without n_roll_in */
-  FOPD_ELIMIT = 11       /* T or B beyond the fixed limits of an entry point that owns its scratch memory */
+  FOPD_ELIMIT = 11,      /* T or B beyond the fixed limits of an entry point that owns its scratch memory */
+  FOPD_STATUS_ANY_INT = 0x7fffffff   /* not a status: makes every int a value of the type, so that a caller's
+                                        out-of-range code reaches fopd_status_string's default branch defined */
 } fopd_status;
 
-typedef enum { FOPD_F32 = 0, FOPD_BF16 = 1 } fopd_dtype;
+/* (FOPD_DTYPE_ANY_INT is not an element type: with it a caller's unknown code is a value of the type, which the
+ * entry points answer with FOPD_EDTYPE) */
+typedef enum { FOPD_F32 = 0, FOPD_BF16 = 1, FOPD_DTYPE_ANY_INT = 0x7fffffff } fopd_dtype;
 
 /* Hyper-parameters of Algorithm 1: score coefficients alpha, beta >= 0 (Eq. "freshness"),
  * gate threshold xi (freshness weighting) and anchor strength lambda (full objective). */
