@@ -1445,6 +1445,17 @@ def test_projection_fused_replay_from_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(logp, logp_e) and torch.equal(lse, lse_e)
     assert fb.fopd_workspace_status(ws) == (0, 0)
+    # the number of unmasked rows is read on the device: the captured call follows a mask that changes behind it
+    rs = np.random.RandomState(2)
+    for m in (rs.choice([0, 1], size=w["T"]).astype(np.uint8), np.ones(w["T"], dtype=np.uint8),
+              np.zeros(w["T"], dtype=np.uint8)):
+        w["mask"].copy_(torch.from_numpy(m).to(DEV))
+        logp_m, lse_m, ws_m = _lm_head_call(w)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(logp, logp_m) and torch.equal(lse, lse_m)
+        assert int((lse != 0).sum()) == int(m.sum()) and fb.fopd_workspace_status(ws_m) == (0, 0)
 
 
 @pytest.mark.gpu
