@@ -787,36 +787,41 @@ fopd_live_scan(const uint8_t* __restrict__ mask, const float* __restrict__ coef,
                const int64_t* __restrict__ cu,
                int B, int64_t row_begin, int* __restrict__ ex, int* __restrict__ row_map, int* __restrict__ n_live,
                int64_t* __restrict__ cu_c, const int* __restrict__ keep) {
-  __shared__ int sh[kLiveScanThreads];
-  const int tid = threadIdx.x;
-  const int per = (R + kLiveScanThreads - 1) / kLiveScanThreads;
-  const int lo = min(tid * per, R), hi = min(lo + per, R);
+  __shared__ int wave_total[kLiveScanThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   auto is_live = [&](int j) {
     if (coef != nullptr) return coef[j] != 0.f || (coef2 != nullptr && coef2[j] != 0.f);
     if (mask != nullptr && mask[j] == 0) return false;
     return keep == nullptr || keep[sample_of_row(cu, B, row_begin + j)] != 0;
   };
-  int local = 0;
-  for (int j = lo; j < hi; ++j) local += is_live(j) ? 1 : 0;
-  sh[tid] = local;
-  __syncthreads();
-  for (int off = 1; off < kLiveScanThreads; off <<= 1) {     // inclusive scan of the per-thread counts
-    const int add = (tid >= off) ? sh[tid - off] : 0;
+  // 1024 rows at a time, row base + tid to lane tid (reads and writes of consecutive lanes are consecutive): a
+  // wavefront's ballot gives each lane its place among the wavefront's live rows, the sixteen totals give the rest
+  int run = 0;
+  for (int64_t base = 0; base < R; base += kLiveScanThreads) {
+    const int64_t j = base + tid;
+    const bool live = j < R && is_live(static_cast<int>(j));
+    const unsigned long long votes = __ballot(live);
+    const int before_lane = __popcll(votes & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_total[wave] = __popcll(votes);
     __syncthreads();
-    sh[tid] += add;
-    __syncthreads();
-  }
-  int run = sh[tid] - local;
-  for (int j = lo; j < hi; ++j) {
-    ex[j] = run;
-    if (is_live(j)) {
-      if (row_map != nullptr) row_map[run] = j;
-      ++run;
+    int before_wave = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kLiveScanThreads / 64; ++w) {
+      const int n = wave_total[w];
+      before_wave += (w < wave) ? n : 0;
+      all += n;
     }
+    if (j < R) {
+      const int at = run + before_wave + before_lane;
+      ex[j] = at;
+      if (live && row_map != nullptr) row_map[at] = static_cast<int>(j);
+    }
+    run += all;
+    __syncthreads();                                         // before the totals are overwritten
   }
-  if (tid == kLiveScanThreads - 1) {
-    ex[R] = sh[tid];
-    n_live[0] = sh[tid];
+  if (tid == 0) {
+    ex[R] = run;
+    n_live[0] = run;
   }
   __syncthreads();                                           // ex[] of the other lanes is visible from here on
   for (int i = tid; i <= B; i += kLiveScanThreads) {
