@@ -560,6 +560,11 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
  *   list_ids, list_logp [T, k], k, rest_floor     as in fopd_loss_fwd_bwd_topk_teacher
  *   teacher_logp, teacher_logp_stale [T] or NULL  the sampled token's teacher log-probabilities, for D^sup only
  *                                                 (D^sup = 0 unless both are given; the stale one alone is FOPD_EINVAL)
+ *   freshness_in, n_train_in, n_roll_in           NULL: the scores are formed inside the call, as described above
+ *                                                 (seq_lens_host is then needed).  Given: scores formed earlier
+ *                                                 (the scoring-only form of this call over the buffer gives them),
+ *                                                 exactly as in fopd_lm_head_loss_fwd_bwd: chunks may cut samples,
+ *                                                 seq_lens_host is not read, both gradient outputs are required
  *   seq_lens_host [B] int32 (HOST memory, the values of seq_lens); every sample at most rows_chunk rows long
  *   token_loss [T] f32 out or NULL (l_t; 0 outside U^sup); the other arguments as in fopd_lm_head_loss_fwd_bwd,
  *   dhidden and dweight both NULL included (scoring only: the buffer's listed-teacher scores without a gradient pass)
@@ -571,10 +576,11 @@ fopd_status fopd_lm_head_loss_fwd_bwd_topk_teacher(
     const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T, int64_t V, int64_t d,
     const int32_t* token_ids, const uint8_t* mask, const float* behav_logp, const int32_t* list_ids,
     const float* list_logp, int32_t k, float rest_floor, const float* teacher_logp, const float* teacher_logp_stale,
-    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const int32_t* seq_lens_host,
-    float grad_scale, int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse,
-    float* token_loss, float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
-    void* workspace, size_t workspace_bytes, void* stream);
+    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+    const int32_t* n_train_in, const int32_t* n_roll_in, const int32_t* seq_lens_host, float grad_scale,
+    int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse, float* token_loss,
+    float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight, void* workspace,
+    size_t workspace_bytes, void* stream);
 
 /*
  * Per-kernel timing for benchmarks.  While enabled, every launch of the two streaming kernels

@@ -95,8 +95,8 @@ def load_library():
     lib.fopd_lm_head_loss_topk_workspace_bytes.argtypes = [i64, i64, i64, i32, i64, i32]
     lib.fopd_lm_head_loss_fwd_bwd_topk_teacher.restype = ctypes.c_int
     lib.fopd_lm_head_loss_fwd_bwd_topk_teacher.argtypes = [vp, i64, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp, i32, f32,
-                                                           vp, vp, vp, vp, i32, Hparams, vp, f32, i64, vp, vp, vp, vp,
-                                                           vp, vp, vp, i64, vp, i64, ctypes.c_int, vp, sz, vp]
+                                                           vp, vp, vp, vp, i32, Hparams, vp, vp, vp, vp, f32, i64, vp, vp,
+                                                           vp, vp, vp, vp, vp, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     lib.fopd_freshness_score.restype = ctypes.c_int
     lib.fopd_freshness_score.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, Hparams,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -291,8 +291,9 @@ def fopd_lm_head_loss_fwd_bwd_topk_teacher(hidden, ldh, weight, ldw, T, V, d, to
                                            list_logp, k, rest_floor, teacher_logp, teacher_logp_stale, seq_lens, lag, B,
                                            hp, seq_lens_host, grad_scale, rows_chunk, loss, freshness, weights, logp,
                                            lse, token_loss, dhidden, lddh, dweight, lddw, accumulate_dweight, workspace,
-                                           stream=None):
-    """seq_lens_host: the sample lengths in HOST memory (a CPU int32 tensor, a numpy array or a list)."""
+                                           stream=None, freshness_in=None, n_train_in=None, n_roll_in=None):
+    """seq_lens_host: the sample lengths in HOST memory (a CPU int32 tensor, a numpy array or a list); not needed
+    when freshness_in (scores formed earlier, with n_train_in / n_roll_in from fopd_freshness_score or None) is given."""
     import torch
     f32 = torch.float32
     p, n = _ws(workspace)
@@ -303,7 +304,9 @@ def fopd_lm_head_loss_fwd_bwd_topk_teacher(hidden, ldh, weight, ldw, T, V, d, to
         _ptr(behav_logp, f32, "behav_logp"), _ptr(list_ids, torch.int32, "list_ids"), _ptr(list_logp, f32, "list_logp"),
         int(k), float(rest_floor), _ptr(teacher_logp, f32, "teacher_logp"),
         _ptr(teacher_logp_stale, f32, "teacher_logp_stale"), _ptr(seq_lens, torch.int32, "seq_lens"),
-        _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), None if host is None else ctypes.c_void_p(host.ctypes.data),
+        _ptr(lag, torch.int32, "lag"), int(B), _hp(hp), _ptr(freshness_in, f32, "freshness_in"),
+        _ptr(n_train_in, torch.int32, "n_train_in"), _ptr(n_roll_in, torch.int32, "n_roll_in"),
+        None if host is None else ctypes.c_void_p(host.ctypes.data),
         float(grad_scale), int(rows_chunk), _ptr(loss, f32, "loss"), _ptr(freshness, f32, "freshness"),
         _ptr(weights, f32, "weights"), _ptr(logp, f32, "logp"), _ptr(lse, f32, "lse"),
         _ptr(token_loss, f32, "token_loss"), _ptr(dhidden, f32, "dhidden"), int(lddh), _ptr(dweight, f32, "dweight"),

@@ -1208,7 +1208,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   if (!grads && freshness_in != nullptr) return FOPD_EINVAL;       // scoring needs the scores to be formed inside
   if (listed != nullptr) {
     if (listed->k < 1 || listed->k > 4096) return FOPD_ESHAPE;
-    if (listed->ids == nullptr || listed->logp == nullptr || freshness_in != nullptr) return FOPD_EINVAL;
+    if (listed->ids == nullptr || listed->logp == nullptr) return FOPD_EINVAL;
     if (listed->teacher_logp_stale != nullptr && teacher_logp == nullptr) return FOPD_EINVAL;
     if (!(listed->rest_floor > 0.f) || !(listed->rest_floor <= 1.f)) return FOPD_EINVAL;
   }
@@ -1536,10 +1536,11 @@ fopd_status fopd_lm_head_loss_fwd_bwd_topk_teacher(
     const void* hidden, int64_t ldh, const void* weight, int64_t ldw, int64_t T, int64_t V, int64_t d,
     const int32_t* token_ids, const uint8_t* mask, const float* behav_logp, const int32_t* list_ids,
     const float* list_logp, int32_t k, float rest_floor, const float* teacher_logp, const float* teacher_logp_stale,
-    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const int32_t* seq_lens_host,
-    float grad_scale, int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse,
-    float* token_loss, float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight,
-    void* workspace, size_t workspace_bytes, void* stream) {
+    const int32_t* seq_lens, const int32_t* lag, int32_t B, fopd_hparams hp, const float* freshness_in,
+    const int32_t* n_train_in, const int32_t* n_roll_in, const int32_t* seq_lens_host, float grad_scale,
+    int64_t rows_chunk, float* loss, float* freshness, float* weights, float* logp, float* lse, float* token_loss,
+    float* dhidden, int64_t lddh, float* dweight, int64_t lddw, int accumulate_dweight, void* workspace,
+    size_t workspace_bytes, void* stream) {
   ListedTeacher listed;
   listed.ids = list_ids;
   listed.logp = list_logp;
@@ -1548,7 +1549,7 @@ fopd_status fopd_lm_head_loss_fwd_bwd_topk_teacher(
   listed.teacher_logp_stale = teacher_logp_stale;
   listed.token_loss = token_loss;
   return lm_head_loss_impl(hidden, ldh, weight, ldw, T, V, d, token_ids, mask, behav_logp, teacher_logp, seq_lens, lag,
-                           B, hp, nullptr, nullptr, nullptr, seq_lens_host, grad_scale, rows_chunk, loss, freshness,
+                           B, hp, freshness_in, n_train_in, n_roll_in, seq_lens_host, grad_scale, rows_chunk, loss, freshness,
                            weights, logp, lse, dhidden, lddh, dweight, lddw, accumulate_dweight, &listed, workspace,
                            workspace_bytes, stream);
 }

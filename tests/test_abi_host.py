@@ -327,13 +327,15 @@ def test_projection_workspace_bytes():
 def _lml_listed(lib, **kw):
     a = dict(hidden=4096, ldh=64, weight=4096, ldw=64, T=128, V=100, d=64, ids=4096, lb=4096, lids=4096, llq=4096, k=4,
              floor=1e-4, lq=None, lqs=None, seq=4096, lag=4096, B=2, hp=fb.Hparams(1, 1, 0.05, 0.1), host=[64, 64],
-             chunk=64, loss=4096, lp=4096, lse=4096, dh=8192, dw=8192, ws=4096, wsb=1 << 24)
+             chunk=64, loss=4096, lp=4096, lse=4096, dh=8192, dw=8192, ws=4096, wsb=1 << 24, fin=None, nin=None,
+             nroll=None)
     a.update(kw)
     host = a["host"]
     keep = (ctypes.c_int32 * len(host))(*host) if host is not None else None
     return lib.fopd_lm_head_loss_fwd_bwd_topk_teacher(
         P(a["hidden"]), a["ldh"], P(a["weight"]), a["ldw"], a["T"], a["V"], a["d"], P(a["ids"]), None, P(a["lb"]),
         P(a["lids"]), P(a["llq"]), a["k"], a["floor"], P(a["lq"]), P(a["lqs"]), P(a["seq"]), P(a["lag"]), a["B"], a["hp"],
+        P(a["fin"]), P(a["nin"]), P(a["nroll"]),
         None if keep is None else ctypes.cast(keep, ctypes.c_void_p), 1.0, a["chunk"], P(a["loss"]), None, None,
         P(a["lp"]), P(a["lse"]), None, P(a["dh"]), 64, P(a["dw"]), 64, 0, P(a["ws"]), a["wsb"], None)
 
@@ -344,6 +346,9 @@ def test_projection_loss_with_listed_teacher_rejects_bad_arguments_before_launch
     assert _lml_listed(lib, lids=None) == 1
     assert _lml_listed(lib, llq=None) == 1
     assert _lml_listed(lib, host=None) == 1                       # whole samples per chunk: the host needs the lengths
+    assert _lml_listed(lib, nin=4096) == 1                        # counts without scores
+    assert _lml_listed(lib, fin=4096, nroll=4096) == 1            # roll counts only together with the sup counts
+    assert _lml_listed(lib, fin=4096, dh=None, dw=None) == 1      # scoring with scores supplied
     assert _lml_listed(lib, lqs=4096) == 1                        # the stale array without the current one
     assert _lml_listed(lib, floor=0.0) == 1
     assert _lml_listed(lib, k=0) == 2

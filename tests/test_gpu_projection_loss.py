@@ -426,6 +426,47 @@ def test_projection_loss_with_listed_teacher(name):
     assert rel_h < 2e-3 and rel_w < 2e-3
 
 
+def test_projection_loss_with_listed_teacher_and_supplied_scores():
+    """The listed-teacher pass with scores formed earlier (Algorithm 1 scores the buffer before its minibatch loop):
+    given the scores its own scoring-only form reports, the call with freshness_in, whose chunks cut samples, returns
+    the loss, token losses, log-probs and gradients of the call that forms the scores itself (the weights differ
+    in the last place: float32 scores against the float64 ones used inside)."""
+    seq, d, V, k, rows_chunk = (90, 130, 80, 70), 128, 3000, 9, 192
+    T, B = sum(seq), len(seq)
+    _say("listed teacher with supplied scores: T=%d, chunks of %d rows" % (T, rows_chunk))
+    h = wl.generate_lm_head(T, d, V, DEV, seed=23, masked_every=6)
+    w = wl.attach_loss_inputs(h, seq, [0, 3, 40, 1], seed=23, teacher_list=(k, 0.6))
+    hp, g = _as_passed((1.0, 1.0, 0.05, 0.3)), 1.3
+    f32 = dict(dtype=torch.float32, device=DEV)
+
+    def run(fin, chunk, grads=True):
+        ws = _aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, chunk, k))
+        o = dict(loss=torch.full((1,), 7.0, **f32), fresh=torch.full((B,), 7.0, **f32),
+                 weights=torch.full((B,), 7.0, **f32), logp=torch.full((T,), 7.0, **f32),
+                 lse=torch.full((T,), 7.0, **f32), tl=torch.full((T,), 7.0, **f32),
+                 dh=torch.full((T, d), 7.0, **f32) if grads else None, dw=torch.full((V, d), 7.0, **f32) if grads else None)
+        fb.fopd_lm_head_loss_fwd_bwd_topk_teacher(
+            w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"], w["behav_logp"],
+            w["list_ids"], w["list_logp"], k, 1e-4, None, None, w["seq_lens"], w["lag"], B, hp,
+            None if fin is not None else w["seq_lens_host"], g, chunk, o["loss"], o["fresh"], o["weights"], o["logp"],
+            o["lse"], o["tl"], o["dh"], d, o["dw"], d, False, ws, freshness_in=fin)
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+        return o
+
+    scores = run(None, rows_chunk, grads=False)                   # the scoring loop
+    inside = run(None, rows_chunk)                                # one call that does both
+    given = run(scores["fresh"].clone(), 64)                      # the minibatch call, chunks that cut samples
+    assert float(given["weights"][2]) == 0.0 and not bool(given["dh"][220:300].any())
+    for key in ("logp", "lse", "tl", "fresh"):
+        assert torch.equal(given[key], inside[key]), key
+    assert torch.allclose(given["weights"], inside["weights"], rtol=1e-6, atol=1e-9)
+    assert abs(float(given["loss"]) - float(inside["loss"])) <= 1e-5 * abs(float(inside["loss"]))
+    for key in ("dh", "dw"):
+        scale = float(inside[key].abs().max())
+        assert torch.allclose(given[key], inside[key], rtol=2e-2, atol=1e-5 * scale), key
+
+
 def test_projection_loss_with_listed_teacher_random_sweep():
     """Ten seeded random problems: sample count and lengths, hidden size, vocabulary, list length, rows per chunk,
     masks with two aligned sets, lags, hyper-parameters, upstream scale, with and without the two sampled-token
