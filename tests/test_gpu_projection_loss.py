@@ -772,3 +772,56 @@ def test_projection_loss_replays_from_a_hip_graph_with_other_masks():
         live = int((m != 0).sum())
         assert bool(g1["dhidden"].any()) == (live > 0)
         assert int((g1["logp"] != 0).sum()) <= live and not bool(g1["dhidden"][torch.from_numpy(m == 0).to(DEV)].any())
+
+
+def test_projection_loss_row_numbering_random_sweep():
+    """Sixteen seeded random problems for the numbering of live rows and of gradient rows: masks made of random
+    spans (some samples fully masked, some chunks without a live row), random supplied scores around the threshold
+    (gated samples), chunk sizes that cut samples, ragged row counts.  The call with scores supplied against the
+    same call with the numbering switched off (every row through all three contractions): per-row outputs and dhidden
+    bit for bit, dweight up to the order of its fp32 sum, the loss to 2e-6; and the call without per-row outputs
+    against both."""
+    rs = np.random.RandomState(2024)
+    f32 = dict(dtype=torch.float32, device=DEV)
+    for case in range(16):
+        B = int(rs.randint(1, 6))
+        seq = tuple(int(x) for x in rs.randint(1, 200, size=B))
+        T, d, V = sum(seq), int(rs.choice([64, 128])), int(rs.choice([300, 1000, 2049]))
+        rows_chunk = int(rs.choice([64, 128, 256]))
+        m = rs.choice([1, 1, 1, 2, 3], size=T).astype(np.uint8)
+        for _ in range(int(rs.randint(0, 6))):                    # masked spans
+            a = int(rs.randint(0, T))
+            m[a:a + int(rs.randint(1, 150))] = 0
+        if case % 5 == 4:
+            m[:] = 0 if case % 2 == 0 else 1                      # nothing live / nothing masked
+        f = rs.choice([0.0, 0.04, 0.05, 0.3, 0.9], size=B).astype(np.float32)
+        hp, g = _as_passed((1.0, 1.0, 0.05, float(rs.choice([0.0, 0.3])))), float(rs.choice([1.0, -0.5]))
+        _say("numbering case %d: seq=%s d=%d V=%d chunk=%d, %d of %d rows masked, scores %s"
+             % (case, seq, d, V, rows_chunk, int((m == 0).sum()), T, f.tolist()))
+        h = wl.generate_lm_head(T, d, V, DEV, seed=400 + case)
+        h["mask"] = torch.from_numpy(m).to(DEV)
+        w = wl.attach_loss_inputs(h, seq, [int(x) for x in rs.randint(0, 5, size=B)], seed=400 + case)
+        on = _run(w, hp, g, rows_chunk, f, pad_h=int(rs.choice([0, 3])))
+        try:
+            fb.fopd_set_option("lm_head_compact", 0)
+            off = _run(w, hp, g, rows_chunk, f)
+        finally:
+            fb.fopd_set_option("lm_head_compact", 1)
+        for key in ("logp", "lse", "weights", "dhidden"):
+            assert torch.equal(on[key], off[key]), (case, key)
+        scale = max(float(off["dweight"].abs().max()), 1e-30)
+        assert torch.allclose(on["dweight"], off["dweight"], rtol=1e-4, atol=1e-6 * scale), case
+        assert abs(float(on["loss"]) - float(off["loss"])) <= 2e-6 * abs(float(off["loss"])) + 1e-12, case
+        # without per-row outputs
+        ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
+        lean = dict(loss=torch.full((1,), 7.0, **f32), weights=torch.empty(B, **f32),
+                    dhidden=torch.full((T, d), 7.0, **f32), dweight=torch.full((V, d), 7.0, **f32))
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp,
+                                     torch.from_numpy(f).to(DEV), None, None, g, rows_chunk, lean["loss"], lean["weights"],
+                                     None, None, lean["dhidden"], d, lean["dweight"], d, False, ws)
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+        assert torch.equal(lean["weights"], off["weights"]) and torch.equal(lean["dhidden"], off["dhidden"]), case
+        assert torch.allclose(lean["dweight"], off["dweight"], rtol=1e-4, atol=1e-6 * scale), case
+        assert abs(float(lean["loss"]) - float(off["loss"])) <= 2e-6 * abs(float(off["loss"])) + 1e-12, case
