@@ -812,6 +812,10 @@ def test_projection_loss_row_numbering_random_sweep():
         scale = max(float(off["dweight"].abs().max()), 1e-30)
         assert torch.allclose(on["dweight"], off["dweight"], rtol=1e-4, atol=1e-6 * scale), case
         assert abs(float(on["loss"]) - float(off["loss"])) <= 2e-6 * abs(float(off["loss"])) + 1e-12, case
+        if case % 4 == 0:                                         # added to a running sum (kept as it is if nothing is live)
+            base = torch.full((V, d), 0.5, device=DEV)
+            acc = _run(w, hp, g, rows_chunk, f, accumulate=True, dweight=base.clone())
+            assert torch.allclose(acc["dweight"], off["dweight"] + 0.5, rtol=1e-4, atol=1e-6 * scale + 1e-7), case
         # without per-row outputs
         ws = _aligned(fb.fopd_lm_head_loss_workspace_bytes(T, V, d, B, rows_chunk))
         lean = dict(loss=torch.full((1,), 7.0, **f32), weights=torch.empty(B, **f32),
