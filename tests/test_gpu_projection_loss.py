@@ -195,15 +195,24 @@ def test_projection_loss_forms_the_scores_itself_when_given_none(seq, rows_chunk
     assert torch.equal(again["logp"], out["logp"])
     assert torch.allclose(again["dhidden"], out["dhidden"], rtol=2e-2, atol=1e-6 * float(out["dhidden"].abs().max()))
     assert torch.allclose(again["dweight"], out["dweight"], rtol=2e-2, atol=1e-5 * float(out["dweight"].abs().max()))
-    # a sample longer than a chunk cannot be scored inside the call
+    # a sample longer than a chunk: the call sweeps the rows twice (log-probs of every chunk first, then the scores
+    # of all samples, then the pass as if they had been supplied) and gives what the one-chunk-per-sample call gave
     if max(seq) > 64:
-        with pytest.raises(fb.FopdError) as e:
-            fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
-                                         w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None,
-                                         None, g, 64, out["loss"], out["weights"], out["logp"], out["lse"],
-                                         out["dhidden"], d, out["dweight"], d, False, ws,
-                                         seq_lens_host=w["seq_lens_host"])
-        assert e.value.status == 2
+        two = dict(loss=torch.full((1,), 7.0, device=DEV), weights=torch.full((B,), 7.0, device=DEV),
+                   freshness=torch.full((B,), 7.0, device=DEV), logp=torch.full((T,), 7.0, device=DEV),
+                   lse=torch.full((T,), 7.0, device=DEV), dhidden=torch.full((T, d), 7.0, device=DEV),
+                   dweight=torch.full((V, d), 7.0, device=DEV))
+        fb.fopd_lm_head_loss_fwd_bwd(w["hidden"], w["ldh"], w["weight"], w["ldw"], T, V, d, w["token_ids"], w["mask"],
+                                     w["behav_logp"], w["teacher_logp"], w["seq_lens"], w["lag"], B, hp, None, None,
+                                     None, g, 64, two["loss"], two["weights"], two["logp"], two["lse"],
+                                     two["dhidden"], d, two["dweight"], d, False, ws,
+                                     seq_lens_host=w["seq_lens_host"], freshness=two["freshness"])
+        torch.cuda.synchronize()
+        assert fb.fopd_workspace_status(ws) == (0, 0)
+        for key in ("logp", "lse", "freshness", "weights", "dhidden"):
+            assert torch.equal(two[key], out[key]), key
+        assert abs(float(two["loss"]) - float(out["loss"])) <= 2e-6 * abs(float(out["loss"]))
+        assert torch.allclose(two["dweight"], out["dweight"], rtol=1e-4, atol=1e-6 * float(out["dweight"].abs().max()))
 
 
 def test_projection_loss_rejects_bad_arguments():
@@ -465,6 +474,12 @@ def test_projection_loss_with_listed_teacher_and_supplied_scores():
     for key in ("dh", "dw"):
         scale = float(inside[key].abs().max())
         assert torch.allclose(given[key], inside[key], rtol=2e-2, atol=1e-5 * scale), key
+    # no scores and chunks shorter than the samples: two sweeps inside the call, the same float64 scores
+    swept = run(None, 64)
+    for key in ("logp", "lse", "tl", "fresh", "weights", "dh"):
+        assert torch.equal(swept[key], inside[key]), key
+    assert abs(float(swept["loss"]) - float(inside["loss"])) <= 2e-6 * abs(float(inside["loss"]))
+    assert torch.allclose(swept["dw"], inside["dw"], rtol=1e-4, atol=1e-6 * float(inside["dw"].abs().max()))
 
 
 def test_projection_loss_with_listed_teacher_random_sweep():
