@@ -1345,8 +1345,8 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
   int32_t* keep = nullptr;             // with drop_gated: 1 for the samples of positive weight
   if (drop_gated) {
     keep = at<int32_t>(workspace, lay.keep);
-    fopd_sample_keep<<<static_cast<unsigned>((B + 255) / 256), 256, 0, s>>>(freshness_in, n_use, nr_use, lag, B, hp.xi,
-                                                                          keep);
+    fopd_sample_keep<<<static_cast<unsigned>((B + 255) / 256), 256, 0, s>>>(nullptr, freshness_in, n_use, nr_use, lag,
+                                                                          B, hp.xi, keep);
     if ((st = launched()) != FOPD_OK) return st;
   }
   if (global_rows) {
@@ -1535,6 +1535,21 @@ static fopd_status lm_head_loss_impl(const void* hidden, int64_t ldh, const void
         logp, behav_logp, nullptr, tl, teacher_logp, stale, mask, cu, lag, T, hp, nullptr, nullptr, nullptr, nullptr,
         nullptr, nullptr, nullptr, nullptr, f64, nws, nrws);
     if ((st = launched()) != FOPD_OK) return st;
+    if (global_rows) {
+      // the log-probs of every live row are in place: the second sweep leaves the samples of weight 0 out altogether
+      keep = at<int32_t>(workspace, lay.keep);
+      fopd_sample_keep<<<static_cast<unsigned>((B + 255) / 256), 256, 0, s>>>(f64, nullptr, n_use, nr_use, lag, B, hp.xi,
+                                                                            keep);
+      if ((st = launched()) != FOPD_OK) return st;
+      fopd_live_scan<<<1, kLiveScanThreads, 0, s>>>(mask, nullptr, nullptr, static_cast<int>(T), cu, B, 0, ex, row_map,
+                                                    n_live, cu_c, keep);
+      if ((st = launched()) != FOPD_OK) return st;
+      if (grads) {
+        fopd_masked_rows_zero<<<static_cast<unsigned>(T), 256, 0, s>>>(mask, cu, B, keep, nullptr, nullptr, nullptr,
+                                                                       dhidden, lddh, static_cast<int>(d));
+        if ((st = launched()) != FOPD_OK) return st;
+      }
+    }
   }
   }
   fopd_sum_chunks<<<1, 64, 0, s>>>(chunk_loss, static_cast<int>(ci), loss);

@@ -766,15 +766,17 @@ __global__ void __launch_bounds__(256) fopd_fill_zero_f32(float* out, int64_t ld
 
 constexpr int kLiveScanThreads = 1024;
 
-// keep[i] = 1 if sample i has a positive weight under the supplied scores, else 0.
+// keep[i] = 1 if sample i has a positive weight under the scores given (float64 ones if fresh64 != NULL, else the
+// float32 ones), else 0.
 __global__ void __launch_bounds__(256)
-fopd_sample_keep(const float* __restrict__ fresh32, const int32_t* __restrict__ n_train,
-                 const int32_t* __restrict__ n_roll, const int32_t* __restrict__ lag, int B, float xi,
-                 int* __restrict__ keep) {
+fopd_sample_keep(const double* __restrict__ fresh64, const float* __restrict__ fresh32,
+                 const int32_t* __restrict__ n_train, const int32_t* __restrict__ n_roll,
+                 const int32_t* __restrict__ lag, int B, float xi, int* __restrict__ keep) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= B) return;
   const int32_t n = n_train[i];
-  keep[i] = weight_of(static_cast<double>(fresh32[i]), n, (n_roll != nullptr) ? n_roll[i] : n, lag[i], xi) > 0.0 ? 1 : 0;
+  const double f = (fresh64 != nullptr) ? fresh64[i] : static_cast<double>(fresh32[i]);
+  keep[i] = weight_of(f, n, (n_roll != nullptr) ? n_roll[i] : n, lag[i], xi) > 0.0 ? 1 : 0;
 }
 
 // One workgroup.  A row is live if coef != NULL ? (coef[j] != 0 or, with coef2, coef2[j] != 0) : (mask == NULL ||
