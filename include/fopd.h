@@ -475,7 +475,8 @@ fopd_status fopd_set_option(const char* name, int value);
  * students are Qwen models, App. B, whose projection is [V, d] = [151,936, 4096].)
  *
  *   hidden      [T, ldh] bf16, ldh >= d           weight      [V, ldw] bf16, ldw >= d
- *   d           hidden size, a multiple of 64; T * ldh and V * ldw must each be below 2^31
+ *   d           hidden size, a multiple of 64; V * ldw must be below 2^31 (32-bit offsets inside the matrix); rows
+ *               beyond 2^31 / ldh go through in blocks of that many, launch after launch
  *   token_ids, mask, logp, lse: as in fopd_token_logprobs (masked rows give 0, 0; they are not projected: the
  *               kernel gathers the other rows through a row map and reads their count on the device, option
  *               "lm_head_compact")

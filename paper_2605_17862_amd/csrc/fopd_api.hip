@@ -1037,10 +1037,26 @@ fopd_status fopd_lm_head_token_logprobs(const void* hidden, int64_t ldh, const v
                                         const uint8_t* mask, float* logp, float* lse, void* workspace,
                                         size_t workspace_bytes, void* stream) {
   if (T < 0 || V <= 0 || d <= 0 || d % (2 * kLmK) != 0 || ldh < d || ldw < d) return FOPD_ESHAPE;
-  // every byte offset inside either matrix must fit 32 bits
-  if (T * ldh >= 2147483648LL || V * ldw >= 2147483648LL) return FOPD_ESHAPE;
+  // every byte offset inside the projection matrix must fit 32 bits
+  if (V * ldw >= 2147483648LL || ldh >= 2147483648LL) return FOPD_ESHAPE;
   if (hidden == nullptr || weight == nullptr || token_ids == nullptr || logp == nullptr || lse == nullptr)
     return FOPD_EINVAL;
+  // ... and inside the hidden states of one launch: more rows than that go through in blocks (rows are independent)
+  if (T * ldh >= 2147483648LL) {
+    if (misaligned(hidden, 16) || (ldh * 2) % 16 != 0) return FOPD_EALIGN;
+    if (workspace == nullptr || misaligned(workspace, 256) || workspace_bytes < LmWorkspace(T).total)
+      return FOPD_EWORKSPACE;
+    const int64_t block = (2147483647LL / ldh) / kLmTile * kLmTile;
+    if (block <= 0) return FOPD_ESHAPE;
+    for (int64_t a = 0; a < T; a += block) {
+      const int64_t rows = (T - a < block) ? T - a : block;
+      const fopd_status st = fopd_lm_head_token_logprobs(
+          static_cast<const __bf16*>(hidden) + a * ldh, ldh, weight, ldw, rows, V, d, token_ids + a,
+          mask == nullptr ? nullptr : mask + a, logp + a, lse + a, workspace, workspace_bytes, stream);
+      if (st != FOPD_OK) return st;
+    }
+    return FOPD_OK;
+  }
   if (misaligned(hidden, 16) || misaligned(weight, 16) || (ldh * 2) % 16 != 0 || (ldw * 2) % 16 != 0)
     return FOPD_EALIGN;
   const LmWorkspace lay(T);

@@ -272,7 +272,8 @@ def test_projection_entry_point_rejects_bad_arguments_before_launch():
     assert _lmh(lib, ldw=56) == 2
     assert _lmh(lib, T=-1) == 2
     assert _lmh(lib, V=0) == 2
-    assert _lmh(lib, T=1 << 20, ldh=1 << 11) == 2           # T * ldh reaches 2^31
+    assert _lmh(lib, T=1 << 20, ldh=1 << 11) == 5           # T * ldh reaches 2^31: row blocks; the workspace is too small
+    assert _lmh(lib, T=1 << 20, ldh=1 << 11, hidden=4104, wsb=1 << 30) == 3
     assert _lmh(lib, V=1 << 19, ldw=1 << 12) == 2           # V * ldw reaches 2^31
     assert _lmh(lib, hidden=4104) == 3           # EALIGN: base not on 16 bytes
     assert _lmh(lib, ldh=68) == 3                # row pitch not a multiple of 16 bytes

@@ -1525,6 +1525,35 @@ def test_projection_fused_leaves_masked_spans_out():
 
 
 @pytest.mark.gpu
+def test_projection_fused_more_rows_than_32_bit_offsets_reach():
+    """T * ldh beyond 2^31 (a wide row pitch stands in for a long buffer): the call goes through the rows in blocks.
+    Rows on both sides of the block boundary, the first and the last against the oracle; masked rows give zeros."""
+    d, V, ldh = 64, 500, 8192
+    T = (2 ** 31 - 1) // ldh // 256 * 256 + 777                  # one full block of 261,888 rows and a ragged second one
+    _say("lm_head in row blocks: T=%d ldh=%d (T * ldh = %.3f * 2^31)" % (T, ldh, T * ldh / 2.0 ** 31))
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    hidden = torch.zeros(T, ldh, dtype=torch.bfloat16, device=DEV)
+    hidden[:, :d] = torch.randn(T, d, generator=gen, device=DEV).to(torch.bfloat16)
+    weight = (torch.randn(V, d, generator=gen, device=DEV) * 0.4).to(torch.bfloat16)
+    token_ids = torch.randint(0, V, (T,), generator=gen, device=DEV, dtype=torch.int32)
+    mask = torch.ones(T, dtype=torch.uint8, device=DEV)
+    mask[5::7] = 0
+    w = dict(T=T, d=d, V=V, ldh=ldh, ldw=d, hidden=hidden, weight=weight, token_ids=token_ids, mask=mask)
+    logp, lse, ws = _lm_head_call(w)
+    assert fb.fopd_workspace_status(ws) == (0, 0)
+    edge = T - 777
+    rows = [0, 1, 5, edge - 2, edge - 1, edge, edge + 1, T - 2, T - 1] + [int(x) for x in
+                                                                        np.random.RandomState(1).randint(0, T, size=12)]
+    idx = torch.tensor(rows, device=DEV)
+    ref_lse, ref_lp = orc.lm_head_token_logprobs(np64(hidden[idx, :d]), np64(weight), np64(token_ids[idx]), np64(mask[idx]))
+    assert_close("lse (row blocks)", np64(lse[idx]), ref_lse, rtol=0, atol=1e-4)
+    assert_close("logp (row blocks)", np64(logp[idx]), ref_lp, rtol=0, atol=1e-4)
+    assert not bool(logp[5::7].any()) and not bool(lse[5::7].any())
+    assert int((lse != 0).sum()) == int(mask.sum())
+
+
+@pytest.mark.gpu
 def test_projection_fused_token_range_flag_and_empty_call():
     w = wl.generate_lm_head(40, 64, 300, DEV, seed=6)
     w["token_ids"][3] = 300
