@@ -232,6 +232,7 @@ struct Options {
   int k14_regs_grid = 0;          // workgroups of the row-in-registers kernel; 0 = two per compute unit
   int k14_regs = 1;               // 1: rows that fit (16-byte vectors <= 1024 x 19) are held in registers between the passes
   int lm_head_compact = 1;        // 1: the loss pass through the projection leaves masked rows out of its contractions
+  int k4_regs = 1;                // 1: the gradient kernel holds a row in registers between its loads and stores
 } g_opt;
 
 inline Options current_options() {
@@ -310,7 +311,22 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
                       const int32_t* token_ids, const float* lse, const float* logp, const float* coef,
                       hipStream_t s, bool timed = true) {
   if (T == 0) return FOPD_OK;
+  const Options opt = current_options();
   ScopedTimer timer(1, s, timed);
+  constexpr int kRegRowVectors = 19;
+  const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
+  if (opt.k4_regs != 0 && nvec <= 1024LL * kRegRowVectors && nvec > 2 * 1024) {
+    // the row-in-registers shape: two workgroups of 1024 lanes per compute unit (one resident at a time)
+    const int64_t wgs = 2 * compute_units();
+    const dim3 grid(static_cast<unsigned>(T < wgs ? T : wgs)), block(1024);
+    if (dt == FOPD_BF16)
+      fopd_k4_grad_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+                                                                          token_ids, lse, logp, coef);
+    else
+      fopd_k4_grad_regs<FOPD_F32, kRegRowVectors><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
+                                                                         token_ids, lse, logp, coef);
+    return launched();
+  }
   const dim3 grid(static_cast<unsigned>(T)), block(kGradThreads);
   if (dt == FOPD_BF16)
     fopd_k4_grad<FOPD_BF16, kGradUnroll><<<grid, block, 0, s>>>(logits, dlogits, T, static_cast<int>(V), ld,
@@ -1631,6 +1647,11 @@ fopd_status fopd_set_option(const char* name, int value) {
   if (key == "k14_regs_grid") {
     if (value < 0 || value > 4096) return FOPD_EINVAL;
     g_opt.k14_regs_grid = value;
+    return FOPD_OK;
+  }
+  if (key == "k4_regs") {
+    if (value != 0 && value != 1) return FOPD_EINVAL;
+    g_opt.k4_regs = value;
     return FOPD_OK;
   }
   if (key == "lm_head_compact") {

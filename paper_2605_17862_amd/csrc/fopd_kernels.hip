@@ -897,6 +897,83 @@ struct LaneStateKl {
   bool far = false;                                             // the references were more than 2^100 apart
 };
 
+// =========================================================================================
+// K4R: the gradient kernel with the row held in registers between its loads and its stores, in the launch shape of
+// fopd_k14_regs (1024 lanes x NV 16-byte vectors, one workgroup resident per compute unit, walking rows in steps of
+// the grid).  A compute unit then reads a whole row, then writes a whole row, instead of mixing 16-byte reads and
+// writes: measured with a plain copy of this shape (hbm_probe, "regs-copy": 5.63 TB/s where 2048 workgroups striding
+// over the buffers reach 5.33 in the same process).  Every entry is computed exactly as in fopd_k4_grad: same bits.
+// Rows of more than 1024 NV vectors do not fit and take fopd_k4_grad.
+// =========================================================================================
+// (Requesting a vector of the next row as soon as its register's entry is stored, so that loads and stores of a compute
+// unit overlap, is much slower: 28.1 ms against 18.6 ms on the benchmark's rows.)
+template <int DT, int NV>
+__global__ void __launch_bounds__(1024)
+fopd_k4_grad_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
+                  const float* lse, const float* logp, const float* coef) {
+  constexpr int E = Elem<DT>::kPerVec;
+  constexpr int NT = 1024;
+  const int tid = threadIdx.x;
+  const int nvec = V / E;
+  const int idx = nvec * E + tid;                          // ragged end of a row: one entry per lane
+  auto row_of = [&](int64_t t) { return static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes; };
+  auto has_row = [&](int64_t t, float& c, int& y) {
+    if (t >= T) return false;
+    c = coef[t];
+    y = token_ids[t];
+    return c != 0.f && y >= 0 && y < V;
+  };
+  u32x4 q[NV];
+  float tail = 0.f;
+  auto load_row = [&](int64_t t) {
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row_of(t));
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int j = tid + k * NT;
+      if (j < nvec) q[k] = __builtin_nontemporal_load(rv + j);
+    }
+    if (idx < V) tail = load_elem<DT>(row_of(t), idx);
+  };
+  int64_t t = blockIdx.x;
+  float c = 0.f;
+  int y = 0;
+  bool live = has_row(t, c, y);
+  for (; t < T; t += gridDim.x) {
+    char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+    if (!live) {
+      row_zero<DT, NT>(orow, V);
+    } else {
+      load_row(t);
+      u32x4* ov = reinterpret_cast<u32x4*>(orow);
+      const float lseL = lse[t] * kLog2e;
+      const float gy = c * expm1f(logp[t]);                // the sampled token's entry, accurate as p_y -> 1
+      const int jy = y / E, ey = y % E;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int j = tid + k * NT;
+        if (j < nvec) {
+          float x[E];
+          unpack<DT>(q[k], x);
+#pragma unroll
+          for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+          if (j == jy) {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+              if (e == ey) x[e] = gy;
+          }
+          __builtin_nontemporal_store(pack<DT>(x), ov + j);
+        }
+      }
+      if (idx < V) {
+        float g = c * fast_exp2(fmaf(tail, kLog2e, -lseL));
+        if (idx == y) g = gy;
+        store_elem<DT>(orow, idx, g);
+      }
+    }
+    live = has_row(t + gridDim.x, c, y);
+  }
+}
+
 constexpr float kKlRefGap = 100.f;
 
 template <int N>

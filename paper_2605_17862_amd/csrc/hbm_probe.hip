@@ -9,6 +9,10 @@
 //     runtime copy      hipMemcpyAsync device-to-device (the runtime's own copy path)
 //     flat copy         a fixed grid of 2048 workgroups striding over the buffer in 16 KB blocks
 //     burst copy        each workgroup loads a 64 KB contiguous chunk into registers, then stores it
+//     regs copy         one 1024-lane workgroup per compute unit walks rows, holding a whole row in registers
+//                       between its loads and its stores (the shape of the row-in-registers loss kernel)
+//     phased copy       the same, with every compute unit loading only in even and storing only in odd time slots of
+//                       13 us of the chip's constant clock, so that the memory sees reads and writes in turn
 //   read:write mixes, row shape
 //     2r1w              two buffers read, one written (the mix of the two-tensor gradient kernel)
 //     1r2w              one buffer read, two written
@@ -136,6 +140,39 @@ __global__ void __launch_bounds__(kThreads) hbm_probe_1r2w(const u32x4* in, u32x
     }                                                                               \
   } while (0)
 
+constexpr int kRegsThreads = 1024, kRegsVecs = (kRowVecs + kRegsThreads - 1) / kRegsThreads;
+
+// Leaves as soon as the constant 100 MHz clock is in a slot of the wanted kind (slots of `slot` ticks; even ones are
+// for loads, odd ones for stores).  The clock advances, so every wavefront leaves.
+__device__ __forceinline__ void hbm_probe_wait_slot(unsigned want_odd, unsigned slot) {
+  for (;;) {
+    const unsigned long long t = __builtin_amdgcn_s_memrealtime();
+    if (static_cast<unsigned>((t / slot) & 1ull) == want_odd) break;
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
+
+// slot = 0: loads and stores of the compute units fall as they come; else: see above.
+__global__ void __launch_bounds__(kRegsThreads) hbm_probe_copy_regs(const u32x4* in, u32x4* out, int rows, unsigned slot) {
+  u32x4 v[kRegsVecs];
+  for (int row = blockIdx.x; row < rows; row += gridDim.x) {
+    const u32x4* r = in + static_cast<size_t>(row) * kRowVecs;
+    u32x4* o = out + static_cast<size_t>(row) * kRowVecs;
+    if (slot != 0) hbm_probe_wait_slot(0, slot);
+#pragma unroll
+    for (int k = 0; k < kRegsVecs; ++k) {
+      const int j = threadIdx.x + k * kRegsThreads;
+      if (j < kRowVecs) v[k] = __builtin_nontemporal_load(r + j);
+    }
+    if (slot != 0) hbm_probe_wait_slot(1, slot);
+#pragma unroll
+    for (int k = 0; k < kRegsVecs; ++k) {
+      const int j = threadIdx.x + k * kRegsThreads;
+      if (j < kRowVecs) __builtin_nontemporal_store(v[k], o + j);
+    }
+  }
+}
+
 int main(int argc, char** argv) {
   const double gib = (argc > 1) ? atof(argv[1]) : 8.0;
   if (!(gib > 0.0) || gib > 64.0) {
@@ -159,9 +196,15 @@ int main(int argc, char** argv) {
   CHECK(hipEventCreate(&e0));
   CHECK(hipEventCreate(&e1));
   printf("hbm_probe: %u rows of %zu bytes = %.3f GB per buffer\n", rows, row_bytes, bytes * 1e-9);
-  const char* names[9] = {"read", "write", "copy", "runtime-copy", "flat-copy", "burst-copy", "2r1w", "1r2w", "2r"};
-  const double factor[9] = {1.0, 1.0, 2.0, 2.0, 2.0, 2.0, 3.0, 3.0, 2.0};
-  for (int which = 0; which < 9; ++which) {
+  const char* names[11] = {"read", "write", "copy", "runtime-copy", "flat-copy", "burst-copy", "2r1w", "1r2w", "2r",
+                           "regs-copy", "phased-copy"};
+  const double factor[11] = {1.0, 1.0, 2.0, 2.0, 2.0, 2.0, 3.0, 3.0, 2.0, 2.0, 2.0};
+  int cus = 256;
+  {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, 0) == hipSuccess && prop.multiProcessorCount > 0) cus = prop.multiProcessorCount;
+  }
+  for (int which = 0; which < 11; ++which) {
     const double moved = factor[which] * bytes;
     float total = 0.f;
     for (int rep = 0; rep < 6; ++rep) {        // first launch is a warm-up
@@ -175,7 +218,9 @@ int main(int argc, char** argv) {
         case 5: hbm_probe_copy_burst<<<kFlatGrid, kThreads>>>(a, b, nvec); break;
         case 6: hbm_probe_2r1w<<<rows, kThreads>>>(a, c, b); break;
         case 7: hbm_probe_1r2w<<<rows, kThreads>>>(a, b, c); break;
-        default: hbm_probe_2r<<<rows, kThreads>>>(a, c, sink); break;
+        case 8: hbm_probe_2r<<<rows, kThreads>>>(a, c, sink); break;
+        case 9: hbm_probe_copy_regs<<<cus, kRegsThreads>>>(a, b, static_cast<int>(rows), 0u); break;
+        default: hbm_probe_copy_regs<<<cus, kRegsThreads>>>(a, b, static_cast<int>(rows), 1300u); break;
       }
       CHECK(hipGetLastError());
       CHECK(hipEventRecord(e1, 0));

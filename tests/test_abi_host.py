@@ -220,6 +220,9 @@ def test_set_option_checks_names_and_values():
     assert lib.fopd_set_option(b"k14_regs_grid", 512) == 0
     assert lib.fopd_set_option(b"k14_regs_grid", -1) == 1
     assert lib.fopd_set_option(b"k14_regs_grid", 5000) == 1
+    assert lib.fopd_set_option(b"k4_regs", 0) == 0
+    assert lib.fopd_set_option(b"k4_regs", 2) == 1
+    assert lib.fopd_set_option(b"k4_regs", 1) == 0
     assert lib.fopd_set_option(b"lm_head_compact", 0) == 0
     assert lib.fopd_set_option(b"lm_head_compact", 2) == 1
     assert lib.fopd_set_option(b"lm_head_compact", 1) == 0

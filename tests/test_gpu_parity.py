@@ -744,6 +744,43 @@ def test_replay_from_a_hip_graph():
     _sync_ok(g2)
 
 
+@pytest.mark.parametrize("dtype,V,seed", [("bf16", 20011, 3), ("f32", 9006, 4), ("bf16", 155648, 5), ("bf16", 16392, 6)])
+def test_gradient_kernel_in_the_row_in_registers_shape_gives_the_same_bits(dtype, V, seed):
+    """The fused step (log-sum-exp pass, scores, gradient pass) with the gradient kernel in its two launch shapes:
+    one 256-lane workgroup per row, and 1024-lane workgroups that walk rows holding each in registers between its
+    loads and its stores (masked, gated, live and invalid rows in any order; more rows than workgroups; a ragged row
+    end; the gradient written over the logits)."""
+    _say("gradient kernel, row-in-registers shape against one workgroup per row: %s V=%d" % (dtype, V))
+    w = wl.generate("tooluse", DEV, seed=seed, B=40, turns=3, obs_lo=0, obs_hi=9, resp_lo=1, resp_hi=24, V=V,
+                    ld=(V + 7) // 8 * 8 + 8, dtype=dtype, boost=4, lag_lo=0, lag_hi=40, row_block=64,
+                    aligned_split=(0.2, 0.2))
+    assert w["T"] > 600
+    hp = (1.0, 1.0, 0.05, 0.3)
+    out = {}
+    try:
+        for shape in (0, 1):
+            fb.fopd_set_option("k4_regs", shape)
+            lp = _pass_for(w)
+            lp.dlogits.fill_(3.0)
+            lp.loss_fwd_bwd(w, hp)
+            _sync_ok(lp)
+            out[shape] = lp
+    finally:
+        fb.fopd_set_option("k4_regs", 1)
+    assert torch.equal(out[0].dlogits, out[1].dlogits) and torch.equal(out[0].loss, out[1].loss)
+    assert bool((out[1].dlogits[:, V:] == 3.0).all())                 # the row padding is not touched
+    live = (out[1].weights > 0)
+    assert bool(live.any()) and bool((~live).any()) and bool(out[1].dlogits[:, :V].any())
+    # in place
+    inplace = _pass_for(w, alloc_dlogits=False)
+    logits = w["logits"].clone()
+    fb.fopd_loss_fwd_bwd(logits, inplace.dt, w["T"], V, w["ld"], w["token_ids"], w["mask"], w["behav_logp"],
+                         w["teacher_logp"], None, w["seq_lens"], w["lag"], w["B"], hp, None, None, None, 0, None, None,
+                         1.0, inplace.loss, inplace.freshness, inplace.weights, inplace.logp, logits, inplace.workspace)
+    _sync_ok(inplace)
+    assert torch.equal(logits[:, :V], out[1].dlogits[:, :V])
+
+
 @pytest.mark.parametrize("dtype,V,seed", [("bf16", 20008, 3), ("f32", 9004, 4), ("bf16", 155648, 5)])
 def test_row_in_registers_kernel_walks_many_rows_per_workgroup(dtype, V, seed):
     """More rows than compute units, so that every workgroup of the row-in-registers kernel walks several rows
