@@ -457,9 +457,9 @@ int fopd_refresh_decide(const float* agg_host, const fopd_refresh_config* cfg_ho
  *                      or 0 (default) for two per compute unit (one is resident at a time; the second half is
  *                      handed out as compute units finish).  The results do not depend on it.
  *   "k4_regs"          1 (default): the gradient kernel of the calls that read the logits twice takes the launch
- *                      shape of the row-in-registers kernel for rows of 2049 .. 19456 16-byte vectors (a compute
- *                      unit reads a whole row, then writes a whole row: 1 - 5 % faster); 0: one 256-lane workgroup
- *                      per row.  The same bits either way.
+ *                      shape of the row-in-registers kernel for rows of more than 2048 16-byte vectors (a compute
+ *                      unit reads a whole row, or a run of at most 19456 vectors of it, then writes it: 1 - 5 %
+ *                      faster); 0: one 256-lane workgroup per row.  The same bits either way.
  *   "lm_head_compact"  1 (default): fopd_lm_head_token_logprobs projects only the rows with mask != 0;
  *                      fopd_lm_head_loss_fwd_bwd and fopd_lm_head_loss_fwd_bwd_topk_teacher move each
  *                      chunk's rows with mask != 0 to the front and leave the others out of the three contractions,

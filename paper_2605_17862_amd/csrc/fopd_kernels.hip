@@ -907,74 +907,71 @@ struct LaneStateKl {
 // the grid).  A compute unit then reads a whole row, then writes a whole row, instead of mixing 16-byte reads and
 // writes: measured with a plain copy of this shape (hbm_probe, "regs-copy": 5.63 TB/s where 2048 workgroups striding
 // over the buffers reach 5.33 in the same process).  Every entry is computed exactly as in fopd_k4_grad: same bits.
-// Rows of more than 1024 NV vectors do not fit and take fopd_k4_grad.
 // =========================================================================================
 // (Requesting a vector of the next row as soon as its register's entry is stored, so that loads and stores of a compute
 // unit overlap, is much slower: 28.1 ms against 18.6 ms on the benchmark's rows.)
 template <int DT, int NV>
 __global__ void __launch_bounds__(1024)
 fopd_k4_grad_regs(const void* logits, void* dlogits, int64_t T, int V, int64_t ld, const int32_t* token_ids,
-                  const float* lse, const float* logp, const float* coef) {
+                  const float* lse, const float* logp, const float* coef, int segments, int seg_vecs) {
+  // A row longer than 1024 NV vectors is cut into `segments` runs of seg_vecs vectors (<= 1024 NV; the last one may be
+  // shorter and also takes the row's ragged end): with lse_t and c_t known, the runs of a row are independent.
   constexpr int E = Elem<DT>::kPerVec;
   constexpr int NT = 1024;
   const int tid = threadIdx.x;
   const int nvec = V / E;
-  const int idx = nvec * E + tid;                          // ragged end of a row: one entry per lane
-  auto row_of = [&](int64_t t) { return static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes; };
-  auto has_row = [&](int64_t t, float& c, int& y) {
-    if (t >= T) return false;
-    c = coef[t];
-    y = token_ids[t];
-    return c != 0.f && y >= 0 && y < V;
-  };
-  u32x4 q[NV];
-  float tail = 0.f;
-  auto load_row = [&](int64_t t) {
-    const u32x4* rv = reinterpret_cast<const u32x4*>(row_of(t));
+  const int64_t items = T * segments;
+  for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
+    const int64_t t = item / segments;
+    const int seg = static_cast<int>(item - t * segments);
+    const int v0 = seg * seg_vecs;
+    const int v1 = min(nvec, v0 + seg_vecs);               // this run: vectors v0 .. v1 - 1
+    const bool last = (seg == segments - 1);
+    const int idx = nvec * E + tid;                        // ragged end of the row: one entry per lane
+    const float c = coef[t];
+    const int y = token_ids[t];
+    char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
+    u32x4* ov = reinterpret_cast<u32x4*>(orow);
+    if (c == 0.f || y < 0 || y >= V) {                     // no gradient: zeros, the logits are not read
+      const u32x4 zero = u32x4{0u, 0u, 0u, 0u};
+      for (int j = v0 + tid; j < v1; j += NT) __builtin_nontemporal_store(zero, ov + j);
+      if (last && idx < V) store_elem<DT>(orow, idx, 0.f);
+      continue;
+    }
+    const char* row = static_cast<const char*>(logits) + t * ld * Elem<DT>::kBytes;
+    const u32x4* rv = reinterpret_cast<const u32x4*>(row);
+    u32x4 q[NV];
 #pragma unroll
     for (int k = 0; k < NV; ++k) {
-      const int j = tid + k * NT;
-      if (j < nvec) q[k] = __builtin_nontemporal_load(rv + j);
+      const int j = v0 + tid + k * NT;
+      if (j < v1) q[k] = __builtin_nontemporal_load(rv + j);
     }
-    if (idx < V) tail = load_elem<DT>(row_of(t), idx);
-  };
-  int64_t t = blockIdx.x;
-  float c = 0.f;
-  int y = 0;
-  bool live = has_row(t, c, y);
-  for (; t < T; t += gridDim.x) {
-    char* orow = static_cast<char*>(dlogits) + t * ld * Elem<DT>::kBytes;
-    if (!live) {
-      row_zero<DT, NT>(orow, V);
-    } else {
-      load_row(t);
-      u32x4* ov = reinterpret_cast<u32x4*>(orow);
-      const float lseL = lse[t] * kLog2e;
-      const float gy = c * expm1f(logp[t]);                // the sampled token's entry, accurate as p_y -> 1
-      const int jy = y / E, ey = y % E;
+    float tail = 0.f;
+    if (last && idx < V) tail = load_elem<DT>(row, idx);
+    const float lseL = lse[t] * kLog2e;
+    const float gy = c * expm1f(logp[t]);                  // the sampled token's entry, accurate as p_y -> 1
+    const int jy = y / E, ey = y % E;
 #pragma unroll
-      for (int k = 0; k < NV; ++k) {
-        const int j = tid + k * NT;
-        if (j < nvec) {
-          float x[E];
-          unpack<DT>(q[k], x);
+    for (int k = 0; k < NV; ++k) {
+      const int j = v0 + tid + k * NT;
+      if (j < v1) {
+        float x[E];
+        unpack<DT>(q[k], x);
 #pragma unroll
-          for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
-          if (j == jy) {
+        for (int e = 0; e < E; ++e) x[e] = c * fast_exp2(fmaf(x[e], kLog2e, -lseL));
+        if (j == jy) {
 #pragma unroll
-            for (int e = 0; e < E; ++e)
-              if (e == ey) x[e] = gy;
-          }
-          __builtin_nontemporal_store(pack<DT>(x), ov + j);
+          for (int e = 0; e < E; ++e)
+            if (e == ey) x[e] = gy;
         }
-      }
-      if (idx < V) {
-        float g = c * fast_exp2(fmaf(tail, kLog2e, -lseL));
-        if (idx == y) g = gy;
-        store_elem<DT>(orow, idx, g);
+        __builtin_nontemporal_store(pack<DT>(x), ov + j);
       }
     }
-    live = has_row(t + gridDim.x, c, y);
+    if (last && idx < V) {
+      float g = c * fast_exp2(fmaf(tail, kLog2e, -lseL));
+      if (idx == y) g = gy;
+      store_elem<DT>(orow, idx, g);
+    }
   }
 }
 

@@ -744,12 +744,13 @@ def test_replay_from_a_hip_graph():
     _sync_ok(g2)
 
 
-@pytest.mark.parametrize("dtype,V,seed", [("bf16", 20011, 3), ("f32", 9006, 4), ("bf16", 155648, 5), ("bf16", 16392, 6)])
+@pytest.mark.parametrize("dtype,V,seed", [("bf16", 20011, 3), ("f32", 9006, 4), ("bf16", 155648, 5), ("bf16", 16392, 6),
+                                          ("bf16", 155659, 7), ("f32", 160003, 8), ("bf16", 262144, 9)])
 def test_gradient_kernel_in_the_row_in_registers_shape_gives_the_same_bits(dtype, V, seed):
     """The fused step (log-sum-exp pass, scores, gradient pass) with the gradient kernel in its two launch shapes:
     one 256-lane workgroup per row, and 1024-lane workgroups that walk rows holding each in registers between its
     loads and its stores (masked, gated, live and invalid rows in any order; more rows than workgroups; a ragged row
-    end; the gradient written over the logits)."""
+    end; rows longer than the registers hold, which go in two or three runs; the gradient written over the logits)."""
     _say("gradient kernel, row-in-registers shape against one workgroup per row: %s V=%d" % (dtype, V))
     w = wl.generate("tooluse", DEV, seed=seed, B=40, turns=3, obs_lo=0, obs_hi=9, resp_lo=1, resp_hi=24, V=V,
                     ld=(V + 7) // 8 * 8 + 8, dtype=dtype, boost=4, lag_lo=0, lag_hi=40, row_block=64,
