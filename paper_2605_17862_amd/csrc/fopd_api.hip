@@ -316,12 +316,14 @@ fopd_status launch_k4(const void* logits, void* dlogits, fopd_dtype dt, int64_t 
   constexpr int kRegRowVectors = 19;
   const int64_t nvec = V / (dt == FOPD_BF16 ? 8 : 4);
   if (opt.k4_regs != 0 && nvec > 2 * 1024) {
-    // the row-in-registers shape: two workgroups of 1024 lanes per compute unit (one resident at a time); a row
-    // longer than 1024 x 19 vectors goes in equal runs of at most that many
+    // the row-in-registers shape: workgroups of 1024 lanes, one resident per compute unit at a time; a row longer
+    // than 1024 x 19 vectors goes in equal runs of at most that many
     const int64_t per = 1024LL * kRegRowVectors;
     const int segments = static_cast<int>((nvec + per - 1) / per);
     const int seg_vecs = static_cast<int>((nvec + segments - 1) / segments);
-    const int64_t wgs = 2 * compute_units(), items = T * segments;
+    // (sixteen workgroups per compute unit, handed out as the units finish: 1 % faster than two where the placement
+    // of the buffers makes some units slower than others, the same elsewhere)
+    const int64_t wgs = 16 * compute_units(), items = T * segments;
     const dim3 grid(static_cast<unsigned>(items < wgs ? items : wgs)), block(1024);
     if (dt == FOPD_BF16)
       fopd_k4_grad_regs<FOPD_BF16, kRegRowVectors><<<grid, block, 0, s>>>(
