@@ -214,7 +214,9 @@ def bench_topk_teacher(args, torch, fb, wl, hp):
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload + "+teacher_list", "B": B, "T_rows": T, "V": V, "k": k,
                    "storage": w["dtype"], "call": "fopd_loss_fwd_bwd_topk_teacher"},
-        "roofline": {"bound": "hbm", "kernel": "fopd_k4_grad", "achieved": k4_bytes / k4_s / 1e9,
+        "roofline": {"bound": "hbm",
+                     "kernel": "fopd_k4_grad_regs" if V // (8 if w["dtype"] == "bf16" else 4) > 2048 else "fopd_k4_grad",
+                     "achieved": k4_bytes / k4_s / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": k4_bytes / k4_s / 1e9 / HBM_PEAK_GBS,
                      "traffic": None, "bytes_per_launch": k4_bytes, "avg_ms": k4_s * 1e3},
         "kernels": {"fopd_k1_lse": {"avg_ms": k1_s * 1e3, "GB/s": k1_bytes / k1_s / 1e9,
